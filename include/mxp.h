@@ -1,0 +1,112 @@
+/*
+ * mxp.h -- C ABI of the MI355X (gfx950) MXFP4+ library: quantize, de-convert and W4A4 GEMM for the MX+ block
+ * format (MX+, arXiv 2510.14557).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library never allocates, frees, copies to
+ *     the host or synchronises; work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Every pointer must be 16-byte aligned and every leading dimension a multiple of 16 bytes, except the GEMM
+ *     output D, which only needs the alignment of its element type.  Leading dimensions are in elements.
+ *   - K is the reduction dimension; MX blocks are 32 consecutive elements ALONG K (paper Sec. 2 and Sec. 5.1:
+ *     a row of A and a column of B are sequences of blocks), so K % 32 == 0 is required.
+ *   - Return value: MXP_OK or a negative status; nothing is thrown or aborted, and on an error nothing is enqueued.
+ *     Outputs are overwritten, never accumulated into.
+ *
+ * Canonical MXFP4 / MXFP4+ storage of a [rows][K] operand (what bit-exact parity is defined on)
+ *   elems  [rows][K/2]  : element 2j in the low nibble, 2j+1 in the high nibble of byte j.
+ *                         ordinary element (NBM): E2M1  = sign | ee | m      (Sec. 2: 2-bit exponent, bias 1)
+ *                         block-max element (BM) of MXFP4+: sign | m2 m1 m0  (Sec. 4.1/4.2: the exponent field is
+ *                         reused as mantissa; the value is 2^e_max * 1.m2m1m0 with e_max = 2)
+ *   scales [rows][K/32] : biased E8M0 shared exponent (Eq. 1: shared_exp = floor(log2 BM) - e_max, byte = +127);
+ *                         0 = the whole block is zero (flush rule of Sec. 4.1), 255 = block held a NaN/Inf.
+ *   bm_idx [rows][K/32] : position of the BM inside its block in bits [4:0], bits [7:5] zero (Sec. 4.2).
+ *                         Not written / not read when fmt == MXP_FMT_MXFP4.
+ */
+#ifndef MXP_H_
+#define MXP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of un-quantized tensors */
+#define MXP_F32 0
+#define MXP_BF16 1
+
+/* block formats */
+#define MXP_FMT_MXFP4 0  /* plain OCP MXFP4 (Sec. 2) */
+#define MXP_FMT_MXFP4P 1 /* MXFP4+ (Sec. 4)          */
+
+/* status codes */
+#define MXP_OK 0
+#define MXP_ERR_NULL (-1)        /* a required pointer is NULL                        */
+#define MXP_ERR_SHAPE (-2)       /* negative size, K % 32 != 0, or ld smaller than the row */
+#define MXP_ERR_ALIGN (-3)       /* pointer or leading dimension not 16-byte aligned */
+#define MXP_ERR_DTYPE (-4)       /* unknown dtype                                     */
+#define MXP_ERR_FORMAT (-5)      /* unknown block format                              */
+#define MXP_ERR_WORKSPACE (-6)   /* workspace / image buffer too small                */
+#define MXP_ERR_HIP (-7)         /* the HIP runtime reported a launch error           */
+#define MXP_ERR_UNSUPPORTED (-8) /* valid request this build does not implement       */
+
+/* Quantize src[rows][K] (row stride ld_src, dtype MXP_F32 or MXP_BF16) into MXFP4 or MXFP4+.
+ * Per block (Sec. 4.1, Eq. 1): BM = largest magnitude (lowest index on ties); shared_exp = floor(log2|BM|) - 2;
+ * if floor(log2|BM|) <= -125 the block is flushed (scale byte 0, all nibbles 0, index 0); ordinary elements are
+ * x / 2^shared_exp rounded to E2M1 (nearest, ties to even, saturating at 6); for MXFP4+ the BM keeps three mantissa
+ * bits, m = RNE(2|x|/2^shared_exp - 8) saturating at 7 (the shared scale is never altered).  A block holding a
+ * NaN or Inf gets scale byte 255, nibbles 0, index 0.
+ * elems/scales/bm_idx are dense canonical arrays (see top).  bm_idx may be NULL for MXP_FMT_MXFP4. */
+int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                 uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream);
+
+/* Same result as mxp_quantize of the transposed source: src is stored K-strided, element (r, k) at
+ * src[k * ld_src + r] ("weights kept as [K x N]", Sec. 5.1 blocks still run along K). */
+int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                   uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream);
+
+/* De-conversion (Eq. 2): dst[r][k] = (-1)^s * 2^shared_exp * E, with E = 2^e_max * 1.mmm for the BM position of an
+ * MXFP4+ block and the E2M1 value otherwise.  Scale byte 0 gives zeros (tested before the BM branch), 255 gives NaN.
+ * Every result is exact in both output dtypes.  dst is [rows][K] with row stride ld_dst. */
+int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt,
+                   int64_t rows, int64_t K, void* dst, int dst_dtype, int64_t ld_dst, void* stream);
+
+/* MFMA-ready image of one operand (internal layout, never a graded output): every element widened to the 6-bit
+ * E2M3 code the CDNA4 block-scaled MFMA takes -- an E2M1 element maps to code<<2 and the BM, an E2M3 number at
+ * exponent e_max (Sec. 4.2), maps to sign|11|mmm, so one scaled MFMA forms the exact MX+ products including
+ * BM x BM (Sec. 6.2) -- and tiled in the register order of the instruction.  Size depends on rows and K only. */
+size_t mxp_image_bytes(int64_t rows, int64_t K);
+int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt,
+                int64_t rows, int64_t K, void* image, size_t image_bytes, void* stream);
+
+/* D[M][N] = A[M][K] x B^T, B given as [N][K] (K-contiguous, the way a linear layer stores W); both operands in
+ * canonical storage, formats chosen per operand (Sec. 5: activations MXFP4+ with weights MXFP4 or MXFP4+).
+ * The result is the matrix product of the de-converted operands accumulated in fp32 (Sec. 5.1).
+ * D is MXP_F32 or MXP_BF16 with row stride ldd.  workspace must hold mxp_gemm_workspace_bytes(M, N, K) bytes; it is
+ * scratch for the two images and may be reused after the call's work on `stream` has finished. */
+size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int mxp_gemm(int64_t M, int64_t N, int64_t K,
+             const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
+             const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,
+             void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same product from images built earlier with mxp_prepack (weights are packed once, when they are loaded). */
+int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image,
+                       void* D, int d_dtype, int64_t ldd, void* stream);
+
+/* Activations given un-quantized (A[M][K], MXP_F32 or MXP_BF16, row stride lda): quantized on the fly to fmtA on
+ * the same stream, then multiplied with the prepacked weight image (Sec. 7.1: activations are converted at run time,
+ * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes. */
+size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K);
+int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
+                   const void* B_image, void* D, int d_dtype, int64_t ldd,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+const char* mxp_status_string(int status);
+int mxp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXP_H_ */

@@ -1,0 +1,50 @@
+// Internal helpers shared by the HIP translation units of libmxp (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mxp.h"
+
+namespace mxp {
+
+constexpr int kBlock = 32;    // elements per MX block (Sec. 2)
+constexpr int kNumCU = 256;   // MI355X compute units
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int launch_status() {
+  return hipGetLastError() == hipSuccess ? MXP_OK : MXP_ERR_HIP;
+}
+
+// ---- MFMA-ready image geometry --------------------------------------------------------------------------------
+// Unit tile = 32 rows x 64 K = 64 blocks, one per lane of a 32x32x64 block-scaled MFMA operand
+// (lane l <-> row l % 32, K-block l / 32).  A tile stores, for its 64 lanes, first the low 16 bytes of every
+// lane's 24-byte E2M3 block, then the high 8 bytes:  [64 x 16 B][64 x 8 B] = 1536 B.
+// Tiles are ordered [row_tile][k_tile]; rows are padded to a multiple of 256 and K to a multiple of 128.
+// Scales follow the element tiles: for each group of 4 row tiles (128 rows) and each k_tile, 64 dwords, lane l's
+// dword holding the E8M0 bytes of its block in row tiles 4g+0..3 (byte j = row tile 4g+j).
+constexpr int kTileRows = 32;
+constexpr int kTileK = 64;
+constexpr int kTileBytes = 1536;
+constexpr int kRowPad = 256;
+constexpr int kKPad = 128;
+
+struct ImageGeom {
+  int64_t rows_p, K_p;      // padded sizes
+  int64_t row_tiles, k_tiles;
+  int64_t elem_bytes;       // bytes of the element part
+  int64_t scale_bytes;      // bytes of the scale part
+  __host__ __device__ int64_t total() const { return elem_bytes + scale_bytes; }
+};
+
+__host__ __device__ inline ImageGeom image_geom(int64_t rows, int64_t K) {
+  ImageGeom g;
+  g.rows_p = (rows + kRowPad - 1) / kRowPad * kRowPad;
+  g.K_p = (K + kKPad - 1) / kKPad * kKPad;
+  g.row_tiles = g.rows_p / kTileRows;
+  g.k_tiles = g.K_p / kTileK;
+  g.elem_bytes = g.row_tiles * g.k_tiles * (int64_t)kTileBytes;
+  g.scale_bytes = (g.row_tiles / 4) * g.k_tiles * 256;
+  return g;
+}
+
+}  // namespace mxp

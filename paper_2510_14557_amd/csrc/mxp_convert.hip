@@ -1,0 +1,212 @@
+// mxp_dequantize : canonical MXFP4 / MXFP4+ -> fp32 / bf16   (de-conversion, Eq. 2)
+// mxp_prepack    : canonical -> MFMA-ready E2M3 image          (the "BM prepare" step of Sec. 5.2, done once per
+//                  operand instead of once per MMA fragment: on CDNA4 the BM is directly an operand value)
+#include "mxp_common.h"
+
+namespace {
+
+using namespace mxp;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Magnitude of an E2M1 code in units of X/2: {0, .5, 1, 1.5, 2, 3, 4, 6} * 2  -> one nibble each.
+constexpr uint32_t kE2M1TimesTwo = 0xC8643210u;
+
+// fp32 bit pattern of  (-1)^sign * M * 2^(sbyte - 128)  for 1 <= M <= 15, 1 <= sbyte <= 254, built from integer
+// fields so that the one subnormal result (M = 1, sbyte = 1 -> 2^-127) does not depend on the float mode.
+__device__ __forceinline__ uint32_t make_f32(uint32_t sign, uint32_t M, uint32_t sbyte) {
+  const uint32_t p = 31u - (uint32_t)__builtin_clz(M);
+  const uint32_t biased = sbyte - 1u + p;
+  const uint32_t frac = (M << (23u - p)) & 0x7FFFFFu;
+  uint32_t bits = biased == 0u ? 0x00400000u : ((biased << 23) | frac);
+  if (biased >= 255u) bits = 0x7F800000u;                // only reachable with scale bytes a quantizer never writes
+  return (sign << 31) | bits;
+}
+
+template <bool PLUS, bool OUT_BF16>
+__global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                         const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld, int dense,
+                                                         int64_t nq, void* __restrict__ dst) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += stride) {
+    const uint32_t dw = __builtin_nontemporal_load(elems + q);
+    const int64_t g = q >> 2;
+    const uint32_t part = (uint32_t)(q & 3);
+    const uint32_t sbyte = scales[g];
+    const uint32_t bm = PLUS ? (uint32_t)(bm_idx[g] & 31u) : 64u;
+    uint32_t out[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t nib = (dw >> (4 * i)) & 15u;
+      const uint32_t code = nib & 7u;
+      uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;     // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
+      if (PLUS && bm == part * 8u + (uint32_t)i) M = 8u + code;  // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
+      uint32_t bits = (nib >> 3) << 31;
+      if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
+      if (sbyte == 0u) bits = 0u;                            // reserved all-zero code, tested before anything else
+      if (sbyte == 255u) bits = 0x7FC00000u;
+      out[i] = bits;
+    }
+    int64_t off;
+    if (dense) {
+      off = q * 8;
+    } else {
+      const int64_t row = g / nbk;
+      off = row * ld + (g - row * nbk) * 32 + part * 8;
+    }
+    if (OUT_BF16) {
+      u32x4 v;
+      v.x = (out[0] >> 16) | (out[1] & 0xFFFF0000u);
+      v.y = (out[2] >> 16) | (out[3] & 0xFFFF0000u);
+      v.z = (out[4] >> 16) | (out[5] & 0xFFFF0000u);
+      v.w = (out[6] >> 16) | (out[7] & 0xFFFF0000u);
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off));
+    } else {
+      u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
+      u32x4 v0 = {out[0], out[1], out[2], out[3]}, v1 = {out[4], out[5], out[6], out[7]};
+      __builtin_nontemporal_store(v0, p);
+      __builtin_nontemporal_store(v1, p + 1);
+    }
+  }
+}
+
+// 4 nibbles (16 bit) -> 4 six-bit codes (24 bit), code = nibble << 2.  Two multiplies spread the even and the odd
+// nibbles to their positions: bit offsets 4i -> 6i + 2.
+__device__ __forceinline__ uint32_t widen4(uint32_t h) {
+  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
+  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
+}
+
+// One thread widens one 32-element block into its 24-byte E2M3 operand and stores it at its lane slot of the tile.
+// A 256-thread group covers 4 consecutive k-tiles of one row tile, so each source row contributes 128 contiguous bytes.
+template <bool PLUS>
+__global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                      const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                      int64_t k_tiles, uint8_t* __restrict__ img_elems,
+                                                      uint8_t* __restrict__ img_scales) {
+  const int lane = threadIdx.x & 63;
+  const int64_t kt = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t rt = blockIdx.y;
+  if (kt >= k_tiles) return;
+  const int64_t row = rt * kTileRows + (lane & 31);
+  const int64_t kb = kt * 2 + (lane >> 5);
+  uint32_t n[4] = {0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x4 v = elems[b];
+    n[0] = v.x; n[1] = v.y; n[2] = v.z; n[3] = v.w;
+    sbyte = scales[b];
+    if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
+    if (sbyte == 0u) n[0] = n[1] = n[2] = n[3] = 0u;          // flushed block: zero whatever the nibbles say
+  }
+  uint32_t bm_code = 0;
+  if (PLUS && bm < 32u) {
+    // take the BM nibble out of the stream; its code is sign | 11 | mmm  (E2M3 at exponent e_max, Sec. 4.2)
+    const uint32_t sh = (bm & 7u) * 4u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if ((bm >> 3) == (uint32_t)j) {
+        const uint32_t nib = (n[j] >> sh) & 15u;
+        bm_code = ((nib & 8u) << 2) | 0x18u | (nib & 7u);
+        n[j] &= ~(0xFu << sh);
+      }
+    }
+  }
+  // 8 pieces of 24 bits -> 6 dwords
+  uint32_t r[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    r[2 * j] = widen4(n[j] & 0xFFFFu);
+    r[2 * j + 1] = widen4(n[j] >> 16);
+  }
+  uint32_t d[6];
+  d[0] = r[0] | (r[1] << 24);
+  d[1] = (r[1] >> 8) | (r[2] << 16);
+  d[2] = (r[2] >> 16) | (r[3] << 8);
+  d[3] = r[4] | (r[5] << 24);
+  d[4] = (r[5] >> 8) | (r[6] << 16);
+  d[5] = (r[6] >> 16) | (r[7] << 8);
+  if (PLUS && bm < 32u) {
+    const uint32_t pos = bm * 6u;
+    const uint32_t w = pos >> 5, off = pos & 31u;
+    const uint64_t v = (uint64_t)bm_code << off;
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+      if (w == (uint32_t)j) d[j] |= lo;
+      if (w + 1u == (uint32_t)j) d[j] |= hi;
+    }
+  }
+  uint8_t* tile = img_elems + (rt * k_tiles + kt) * (int64_t)kTileBytes;
+  u32x4 lo4 = {d[0], d[1], d[2], d[3]};
+  u32x2 hi2 = {d[4], d[5]};
+  *reinterpret_cast<u32x4*>(tile + lane * 16) = lo4;
+  *reinterpret_cast<u32x2*>(tile + 1024 + lane * 8) = hi2;
+  img_scales[(((rt >> 2) * k_tiles + kt) * 64 + lane) * 4 + (rt & 3)] = (uint8_t)sbyte;
+}
+
+}  // namespace
+
+namespace mxp {
+
+int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                   void* image, hipStream_t stream) {
+  const ImageGeom g = image_geom(rows, K);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  if (g.row_tiles > 65535) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)((g.k_tiles + 3) / 4), (unsigned)g.row_tiles);
+  const u32x4* e = reinterpret_cast<const u32x4*>(elems);
+  if (fmt == MXP_FMT_MXFP4P)
+    hipLaunchKernelGGL((prepack_kernel<true>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  else
+    hipLaunchKernelGGL((prepack_kernel<false>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  return launch_status();
+}
+
+}  // namespace mxp
+
+extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                              int64_t K, void* dst, int dst_dtype, int64_t ld_dst, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (dst_dtype != MXP_F32 && dst_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !dst || (fmt == MXP_FMT_MXFP4P && !bm_idx)) return MXP_ERR_NULL;
+  if (ld_dst < K) return MXP_ERR_SHAPE;
+  const int64_t esz = dst_dtype == MXP_BF16 ? 2 : 4;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (bm_idx && !aligned16(bm_idx)) || (ld_dst * esz) % 16 != 0)
+    return MXP_ERR_ALIGN;
+  const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
+  const int dense = ld_dst == K ? 1 : 0;
+  int64_t want = (nq + 255) / 256;
+  const int64_t cap = (int64_t)kNumCU * 16;
+  const int grid = (int)(want < cap ? want : cap);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint32_t* e32 = reinterpret_cast<const uint32_t*>(elems);
+  const bool plus = fmt == MXP_FMT_MXFP4P, bf = dst_dtype == MXP_BF16;
+  if (plus && bf) hipLaunchKernelGGL((dequantize_kernel<true, true>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
+  else if (plus) hipLaunchKernelGGL((dequantize_kernel<true, false>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
+  else if (bf) hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
+  else hipLaunchKernelGGL((dequantize_kernel<false, false>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
+  return launch_status();
+}
+
+extern "C" size_t mxp_image_bytes(int64_t rows, int64_t K) {
+  if (rows < 0 || K < 0) return 0;
+  return (size_t)mxp::image_geom(rows, K).total();
+}
+
+extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                           int64_t K, void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image || (fmt == MXP_FMT_MXFP4P && !bm_idx)) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
+  if (image_bytes < (size_t)image_geom(rows, K).total()) return MXP_ERR_WORKSPACE;
+  return prepack_launch(elems, scales, bm_idx, fmt, rows, K, image, static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,344 @@
+// mxp_gemm : D[M][N] = A[M][K] x B[N][K]^T on MXFP4 / MXFP4+ operands (Sec. 5.1), fp32 accumulation.
+//
+// Both operands are consumed as E2M3 images (mxp_prepack): every E2M1 element is exactly an E2M3 value and the BM of
+// an MX+ block is an E2M3 number at exponent e_max (Sec. 4.2), so ONE block-scaled MFMA per block pair yields the
+// exact products A_BM x B_NBM, B_BM x A_NBM and A_BM x B_BM that the paper obtains with a BM_H/BM_L split and an
+// extra MMA (Sec. 5.2, Alg. 1) or with its BM Compute Unit (Sec. 6.2).  The shared E8M0 scales go to the MFMA as is.
+//
+// v_mfma_scale_f32_32x32x64_f8f6f4: lane l supplies the 32 K-consecutive elements (= one MX block, 24 bytes as E2M3)
+// of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is
+// D[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32].
+#include "mxp_common.h"
+
+namespace mxp {
+int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                   void* image, hipStream_t stream);
+int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                    uint8_t* scales, uint8_t* bm_idx, hipStream_t stream);
+}  // namespace mxp
+
+namespace {
+
+using namespace mxp;
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kFmtE2M3 = 2;  // cbsz / blgp code of the f8f6f4 MFMA for FP6 E2M3 operands
+
+template <int OA, int OB>
+__device__ __forceinline__ v16f mfma(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, kFmtE2M3, kFmtE2M3, OA, sa, OB, sb);
+}
+
+// Tile configuration: a workgroup of WAVES_M x WAVES_N wavefronts, each computing WM x WN MFMA tiles of 32 x 32.
+template <int WM_, int WN_, int WAVES_M_, int WAVES_N_>
+struct Cfg {
+  static constexpr int WM = WM_, WN = WN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int TM = WM * WAVES_M, TN = WN * WAVES_N;   // 32-row tiles per workgroup
+  static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
+  static constexpr int A_BYTES = TM * kTileBytes, B_BYTES = TN * kTileBytes;
+  static constexpr int SA_BYTES = ((TM + 3) / 4) * 256, SB_BYTES = ((TN + 3) / 4) * 256;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
+  static_assert(WM == 1 || WM == 2 || WM == 4 || WM == 8, "WM"); static_assert(WN == 1 || WN == 2 || WN == 4 || WN == 8, "WN");
+  static constexpr int CHUNKS = STAGE_BYTES / 16;                 // 16-byte pieces per stage
+  static constexpr int PER_THREAD = (CHUNKS + THREADS - 1) / THREADS;
+};
+
+// Source address of 16-byte chunk c of a stage (k-tile kt) -- the stage is a concatenation of contiguous image runs.
+template <class C>
+__device__ __forceinline__ const u32x4* stage_src(int c, int64_t kt, int64_t k_tiles, const uint8_t* a_el, const uint8_t* a_sc,
+                                                  const uint8_t* b_el, const uint8_t* b_sc, int64_t tm0, int64_t tn0) {
+  constexpr int A_CH = C::A_BYTES / 16, B_CH = C::B_BYTES / 16, SA_CH = C::SA_BYTES / 16;
+  const uint8_t* p;
+  if (c < A_CH) {
+    const int t = c / (kTileBytes / 16), w = c % (kTileBytes / 16);
+    p = a_el + ((tm0 + t) * k_tiles + kt) * (int64_t)kTileBytes + w * 16;
+  } else if (c < A_CH + B_CH) {
+    const int cc = c - A_CH;
+    const int t = cc / (kTileBytes / 16), w = cc % (kTileBytes / 16);
+    p = b_el + ((tn0 + t) * k_tiles + kt) * (int64_t)kTileBytes + w * 16;
+  } else if (c < A_CH + B_CH + SA_CH) {
+    const int cc = c - A_CH - B_CH;
+    const int g = cc / 16, w = cc % 16;
+    p = a_sc + ((tm0 / 4 + g) * k_tiles + kt) * 256 + w * 16;
+  } else {
+    const int cc = c - A_CH - B_CH - SA_CH;
+    const int g = cc / 16, w = cc % 16;
+    p = b_sc + ((tn0 / 4 + g) * k_tiles + kt) * 256 + w * 16;
+  }
+  return reinterpret_cast<const u32x4*>(p);
+}
+
+template <class C, bool OUT_BF16>
+__global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                          int64_t k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+  const int64_t tm0 = (int64_t)blockIdx.y * C::TM, tn0 = (int64_t)blockIdx.x * C::TN;
+
+  v16f acc[C::WM][C::WN];
+#pragma unroll
+  for (int i = 0; i < C::WM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  u32x4 stg[C::PER_THREAD];
+  auto fetch = [&](int64_t kt) {
+#pragma unroll
+    for (int u = 0; u < C::PER_THREAD; ++u) {
+      const int c = tid + u * C::THREADS;
+      if (c < C::CHUNKS) stg[u] = *stage_src<C>(c, kt, k_tiles, a_el, a_sc, b_el, b_sc, tm0, tn0);
+    }
+  };
+  auto commit = [&](int buf) {
+    u32x4* dst = reinterpret_cast<u32x4*>(lds + buf * C::STAGE_BYTES);
+#pragma unroll
+    for (int u = 0; u < C::PER_THREAD; ++u) {
+      const int c = tid + u * C::THREADS;
+      if (c < C::CHUNKS) dst[c] = stg[u];
+    }
+  };
+
+  fetch(0);
+  commit(0);
+  __syncthreads();
+  for (int64_t kt = 0; kt < k_tiles; ++kt) {
+    const int buf = (int)(kt & 1);
+    if (kt + 1 < k_tiles) fetch(kt + 1);
+    const uint8_t* st = lds + buf * C::STAGE_BYTES;
+    v8i a[C::WM], b[C::WN];
+#pragma unroll
+    for (int i = 0; i < C::WM; ++i) {
+      const uint8_t* t = st + (wm * C::WM + i) * kTileBytes;
+      const u32x4 lo = *reinterpret_cast<const u32x4*>(t + lane * 16);
+      const u32x2 hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
+      a[i] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < C::WN; ++j) {
+      const uint8_t* t = st + C::A_BYTES + (wn * C::WN + j) * kTileBytes;
+      const u32x4 lo = *reinterpret_cast<const u32x4*>(t + lane * 16);
+      const u32x2 hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
+      b[j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+    }
+    // scale dwords: byte q of group g = row tile 4g + q.  The tiles of one wavefront lie in one group when WM <= 4
+    // (WM in {1, 2, 4} and workgroup tile origins are multiples of the workgroup tile); shift so that op_sel = i & 3
+    // selects tile i.
+    const int64_t ta = tm0 + wm * C::WM, tb = tn0 + wn * C::WN;
+    const int ga = (int)((ta >> 2) - (tm0 >> 2)), gb = (int)((tb >> 2) - (tn0 >> 2));
+    uint32_t sa[(C::WM + 3) / 4], sb[(C::WN + 3) / 4];
+#pragma unroll
+    for (int g = 0; g < (C::WM + 3) / 4; ++g)
+      sa[g] = *reinterpret_cast<const uint32_t*>(st + C::A_BYTES + C::B_BYTES + (ga + g) * 256 + lane * 4) >> (8 * (int)(ta & 3));
+#pragma unroll
+    for (int g = 0; g < (C::WN + 3) / 4; ++g)
+      sb[g] = *reinterpret_cast<const uint32_t*>(st + C::A_BYTES + C::B_BYTES + C::SA_BYTES + (gb + g) * 256 + lane * 4) >> (8 * (int)(tb & 3));
+#pragma unroll
+    for (int i = 0; i < C::WM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::WN; ++j) {
+        const int sai = (int)sa[i >> 2], sbj = (int)sb[j >> 2];
+        switch ((i & 3) * 4 + (j & 3)) {
+          case 0: acc[i][j] = mfma<0, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 1: acc[i][j] = mfma<0, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 2: acc[i][j] = mfma<0, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 3: acc[i][j] = mfma<0, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 4: acc[i][j] = mfma<1, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 5: acc[i][j] = mfma<1, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 6: acc[i][j] = mfma<1, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 7: acc[i][j] = mfma<1, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 8: acc[i][j] = mfma<2, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 9: acc[i][j] = mfma<2, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 10: acc[i][j] = mfma<2, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 11: acc[i][j] = mfma<2, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 12: acc[i][j] = mfma<3, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 13: acc[i][j] = mfma<3, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 14: acc[i][j] = mfma<3, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          default: acc[i][j] = mfma<3, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+        }
+      }
+    if (kt + 1 < k_tiles) commit(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: for a fixed accumulator register the 32 lanes of a half-wave write 32 consecutive columns of one row
+#pragma unroll
+  for (int i = 0; i < C::WM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::WN; ++j) {
+      const int64_t col = (tn0 + wn * C::WN + j) * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = (tm0 + wm * C::WM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < M && col < N) {
+          const float v = acc[i][j][r];
+          if (OUT_BF16) {
+            uint32_t u = __float_as_uint(v);
+            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x00400000u;       // keep NaN a NaN
+            else u += 0x7FFFu + ((u >> 16) & 1u);                          // round to nearest even
+            static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)(u >> 16);
+          } else {
+            static_cast<float*>(Dv)[row * ldd + col] = v;
+          }
+        }
+      }
+    }
+}
+
+template <class C>
+int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+               hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const int64_t gm = (M + C::TM * 32 - 1) / (C::TM * 32), gn = (N + C::TN * 32 - 1) / (C::TN * 32);
+  if (gm > 65535 || gn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)gn, (unsigned)gm);
+  const size_t lds = 2 * (size_t)C::STAGE_BYTES;
+  if (d_dtype == MXP_BF16) {
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<C, true>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
+    (void)once_b;
+    hipLaunchKernelGGL((gemm_kernel<C, true>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi, Bi + gb.elem_bytes,
+                       ga.k_tiles, M, N, D, ldd);
+  } else {
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<C, false>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
+    (void)once_f;
+    hipLaunchKernelGGL((gemm_kernel<C, false>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi, Bi + gb.elem_bytes,
+                       ga.k_tiles, M, N, D, ldd);
+  }
+  return launch_status();
+}
+
+int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                hipStream_t s) {
+  const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
+  const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
+  if (M <= 32) return launch_cfg<Cfg<1, 2, 1, 4>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (M <= 64) return launch_cfg<Cfg<1, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return launch_cfg<Cfg<4, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+}
+
+int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {
+  if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
+  if (M > 0 && N > 0 && !D) return MXP_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(D) % (d_dtype == MXP_BF16 ? 2 : 4) != 0) return MXP_ERR_ALIGN;
+  return MXP_OK;
+}
+
+// K == 0: the product is an empty sum.
+template <bool BF16>
+__global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * N) return;
+  const int64_t r = i / N, c = i - r * N;
+  if (BF16) static_cast<uint16_t*>(D)[r * ldd + c] = 0;
+  else static_cast<float*>(D)[r * ldd + c] = 0.0f;
+}
+
+int zero_output(void* D, int d_dtype, int64_t M, int64_t N, int64_t ldd, hipStream_t s) {
+  const unsigned grid = (unsigned)((M * N + 255) / 256);
+  if (d_dtype == MXP_BF16) hipLaunchKernelGGL(zero_kernel<true>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+  else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+  return launch_status();
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (M < 0 || N < 0 || K < 0) return 0;
+  return align_up((size_t)mxp::image_geom(M, K).total()) + align_up((size_t)mxp::image_geom(N, K).total());
+}
+
+extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, void* D,
+                                  int d_dtype, int64_t ldd, void* stream) {
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc != MXP_OK || M == 0 || N == 0) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
+  if (!A_image || !B_image) return MXP_ERR_NULL;
+  if (!mxp::aligned16(A_image) || !mxp::aligned16(B_image)) return MXP_ERR_ALIGN;
+  return gemm_images(A_image, B_image, M, N, K, D, d_dtype, ldd, s);
+}
+
+extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx,
+                        int fmtA, const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB, void* D,
+                        int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace mxp;
+  if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) || (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P)) return MXP_ERR_FORMAT;
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc != MXP_OK || M == 0 || N == 0) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
+  if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA == MXP_FMT_MXFP4P && !A_idx) || (fmtB == MXP_FMT_MXFP4P && !B_idx) || !workspace)
+    return MXP_ERR_NULL;
+  if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(workspace) ||
+      (A_idx && !aligned16(A_idx)) || (B_idx && !aligned16(B_idx)))
+    return MXP_ERR_ALIGN;
+  if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;
+  uint8_t* wa = static_cast<uint8_t*>(workspace);
+  uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());
+  rc = prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+  if (rc != MXP_OK) return rc;
+  rc = prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
+  if (rc != MXP_OK) return rc;
+  return gemm_images(wa, wb, M, N, K, D, d_dtype, ldd, s);
+}
+
+extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
+  if (M < 0 || K < 0) return 0;
+  const size_t nb = (size_t)(M * (K / mxp::kBlock));
+  return align_up((size_t)mxp::image_geom(M, K).total()) + align_up(nb * 16) + 2 * align_up(nb);
+}
+
+extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
+                              const void* B_image, void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  using namespace mxp;
+  if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc != MXP_OK || M == 0 || N == 0) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
+  if (!A || !B_image || !workspace) return MXP_ERR_NULL;
+  if (lda < K) return MXP_ERR_SHAPE;
+  if (!aligned16(A) || !aligned16(B_image) || !aligned16(workspace) || (lda * (a_dtype == MXP_BF16 ? 2 : 4)) % 16 != 0)
+    return MXP_ERR_ALIGN;
+  if (workspace_bytes < mxp_gemm_bf16a_workspace_bytes(M, K)) return MXP_ERR_WORKSPACE;
+  const size_t nb = (size_t)(M * (K / kBlock));
+  uint8_t* img = static_cast<uint8_t*>(workspace);
+  uint8_t* el = img + align_up((size_t)image_geom(M, K).total());
+  uint8_t* sc = el + align_up(nb * 16);
+  uint8_t* ix = sc + align_up(nb);
+  rc = quantize_launch(A, a_dtype, M, K, lda, fmtA, el, sc, ix, s);
+  if (rc != MXP_OK) return rc;
+  rc = prepack_launch(el, sc, ix, fmtA, M, K, img, s);
+  if (rc != MXP_OK) return rc;
+  return gemm_images(img, B_image, M, N, K, D, d_dtype, ldd, s);
+}
+
+extern "C" const char* mxp_status_string(int status) {
+  switch (status) {
+    case MXP_OK: return "ok";
+    case MXP_ERR_NULL: return "null pointer";
+    case MXP_ERR_SHAPE: return "bad shape (negative size, K not a multiple of 32, or leading dimension too small)";
+    case MXP_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
+    case MXP_ERR_DTYPE: return "unknown dtype";
+    case MXP_ERR_FORMAT: return "unknown block format";
+    case MXP_ERR_WORKSPACE: return "workspace or image buffer too small";
+    case MXP_ERR_HIP: return "HIP launch error";
+    case MXP_ERR_UNSUPPORTED: return "request not supported by this build";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int mxp_version(void) { return 100; }

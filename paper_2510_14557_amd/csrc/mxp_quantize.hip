@@ -1,0 +1,306 @@
+// mxp_quantize / mxp_quantize_t : fp32 or bf16  ->  canonical MXFP4 / MXFP4+  (Sec. 4.1, 4.2, Eq. 1).
+//
+// HBM-bound streaming kernel.  Four lanes share one 32-element block: a lane loads 8 consecutive elements with
+// 16-byte loads (a wavefront reads 1 KiB of bf16 contiguously), the block maximum and its position are found with
+// two DPP quad exchanges, the eight elements are rounded by the CDNA4 pack-convert instruction (round to nearest
+// even, saturating, sign kept -- the element rounding the format fixes), the lane owning the BM overwrites that
+// nibble with the 3-bit extended mantissa, and each lane stores one dword of nibbles.  Scale and index bytes of
+// four neighbouring blocks are gathered into one lane and stored as dwords.
+#include "mxp_common.h"
+
+namespace {
+
+using namespace mxp;
+
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kQuadSwap1 = 0xB1;  // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;  // quad_perm [2,3,0,1]
+constexpr int kRowShr4 = 0x114;
+constexpr int kRowShr8 = 0x118;
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// 3-bit BM mantissa from the 23-bit fraction of the block maximum: round to nearest even on bit 20, and a carry
+// out of the field saturates (the shared scale is never altered, Sec. 4.1).
+__device__ __forceinline__ uint32_t bm_mantissa(uint32_t frac23) {
+  uint32_t m = (frac23 + 0x7FFFFu + ((frac23 >> 20) & 1u)) >> 20;
+  return umin(m, 7u);
+}
+
+// One group = 8 consecutive elements of one block, held by one lane.  `part` = which quarter of the block.
+// Returns the packed dword of 8 nibbles; scale byte and index byte are returned in all four lanes of the quad.
+template <bool BF16, bool PLUS>
+__device__ __forceinline__ uint32_t encode_group(const uint32_t (&w)[8], int part, uint32_t& sbyte, uint32_t& idx) {
+  uint32_t amax32;  // magnitude bits of the block maximum, as an fp32 pattern
+  if (BF16) {
+    // key = magnitude(15 bit) << 16 | (31 - position): one unsigned max gives the maximum and, among equal
+    // magnitudes, the lowest position.
+    uint32_t k = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t m = w[j] & 0x7FFF7FFFu;
+      uint32_t klo = (m << 16) | (uint32_t)(7 - 2 * j);
+      uint32_t khi = (m & 0xFFFF0000u) | (uint32_t)(6 - 2 * j);
+      k = umax(k, umax(klo, khi));
+    }
+    k += (uint32_t)(3 - part) * 8u;
+    k = umax(k, dpp_mov<kQuadSwap1>(k));
+    k = umax(k, dpp_mov<kQuadSwap2>(k));
+    amax32 = k & 0xFFFF0000u;
+    idx = 31u - (k & 31u);
+  } else {
+    uint32_t a[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = w[i] & 0x7FFFFFFFu;
+    uint32_t mx = a[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = umax(mx, a[i]);
+    mx = umax(mx, dpp_mov<kQuadSwap1>(mx));
+    mx = umax(mx, dpp_mov<kQuadSwap2>(mx));
+    uint32_t p = 32u;
+#pragma unroll
+    for (int i = 7; i >= 0; --i) p = (a[i] == mx) ? (uint32_t)(part * 8 + i) : p;
+    p = umin(p, dpp_mov<kQuadSwap1>(p));
+    p = umin(p, dpp_mov<kQuadSwap2>(p));
+    amax32 = mx;
+    idx = p;
+  }
+  const uint32_t E = amax32 >> 23;                     // biased exponent of the BM = floor(log2) + 127
+  const bool flush = E <= 2u;                          // floor(log2 BM) <= -127 + e_max      (Sec. 4.1)
+  const bool nonfinite = E == 255u;
+  const float scale = __uint_as_float((E - 2u) << 23); // X = 2^shared_exp, shared_exp = floor(log2 BM) - e_max (Eq. 1)
+  uint32_t packed = 0;
+  if (BF16) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      union { uint32_t u; v2bf v; } c;
+      c.u = w[j];
+      if (j == 0) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, c.v, scale, 0);
+      if (j == 1) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, c.v, scale, 1);
+      if (j == 2) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, c.v, scale, 2);
+      if (j == 3) packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, c.v, scale, 3);
+    }
+  } else {
+    packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, __uint_as_float(w[0]), __uint_as_float(w[1]), scale, 0);
+    packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, __uint_as_float(w[2]), __uint_as_float(w[3]), scale, 1);
+    packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, __uint_as_float(w[4]), __uint_as_float(w[5]), scale, 2);
+    packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, __uint_as_float(w[6]), __uint_as_float(w[7]), scale, 3);
+  }
+  if (PLUS) {
+    // BM nibble = sign | m2 m1 m0 ; the sign is already in the converted nibble.
+    const uint32_t m3 = bm_mantissa(amax32 & 0x7FFFFFu);
+    const uint32_t sh = (idx & 7u) * 4u;
+    const uint32_t nib = ((packed >> sh) & 8u) | m3;
+    const uint32_t repl = (packed & ~(0xFu << sh)) | (nib << sh);
+    packed = ((idx >> 3) == (uint32_t)part) ? repl : packed;
+  }
+  sbyte = E - 2u;
+  if (flush || nonfinite) {
+    packed = 0;
+    idx = 0;
+    sbyte = nonfinite ? 255u : 0u;
+  }
+  return packed;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void load_group(const void* __restrict__ src, int64_t q, int64_t nbk, int64_t ld, bool dense,
+                                           uint32_t (&w)[8]) {
+  int64_t off;
+  if (dense) {
+    off = q * 8;
+  } else {
+    const int64_t g = q >> 2;
+    const int64_t row = g / nbk;
+    off = row * ld + (g - row * nbk) * 32 + (q & 3) * 8;
+  }
+  if (BF16) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off));
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    w[4] = w[5] = w[6] = w[7] = 0;
+  } else {
+    const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+    const u32x4 v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+    w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w;
+    w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
+  }
+}
+
+// nq = number of 8-element groups (= 4 * blocks).  The loop is uniform per 16-lane row, so DPP exchanges never
+// read a lane that left the loop; lanes past the end compute on zeros and store nothing.
+template <bool BF16, bool PLUS, int U>
+__global__ void __launch_bounds__(256) quantize_kernel(const void* __restrict__ src, int64_t nbk, int64_t ld, int dense,
+                                                       int64_t nq, uint32_t* __restrict__ elems,
+                                                       uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx) {
+  const int part = threadIdx.x & 3;
+  const int quad_in_row = (threadIdx.x & 15) >> 2;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  const int64_t nblocks = nq >> 2;
+  for (int64_t q0 = (int64_t)blockIdx.x * 256 + threadIdx.x; (q0 & ~(int64_t)15) < nq; q0 += stride * U) {
+    uint32_t w[U][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      if (q < nq) {
+        load_group<BF16>(src, q, nbk, ld, dense != 0, w[u]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[u][i] = 0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      if ((q & ~(int64_t)15) >= nq) break;
+      uint32_t sbyte, idx;
+      const uint32_t packed = encode_group<BF16, PLUS>(w[u], part, sbyte, idx);
+      if (q < nq) __builtin_nontemporal_store(packed, elems + q);
+      // gather the four blocks of this 16-lane row into its lane 12
+      uint32_t sv = (part == 0) ? (sbyte << (8 * quad_in_row)) : 0u;
+      sv |= dpp_mov<kRowShr8>(sv);
+      sv |= dpp_mov<kRowShr4>(sv);
+      uint32_t iv = 0;
+      if (PLUS) {
+        iv = (part == 0) ? (idx << (8 * quad_in_row)) : 0u;
+        iv |= dpp_mov<kRowShr8>(iv);
+        iv |= dpp_mov<kRowShr4>(iv);
+      }
+      const int64_t g0 = (q & ~(int64_t)15) >> 2;   // first block of the row
+      if (g0 + 4 <= nblocks) {
+        if ((threadIdx.x & 15) == 12) {
+          *reinterpret_cast<uint32_t*>(scales + g0) = sv;
+          if (PLUS) *reinterpret_cast<uint32_t*>(bm_idx + g0) = iv;
+        }
+      } else if (part == 0 && q < nq) {
+        scales[q >> 2] = (uint8_t)sbyte;
+        if (PLUS) bm_idx[q >> 2] = (uint8_t)idx;
+      }
+    }
+  }
+}
+
+// ---- K-strided source: one thread per block, 32 strided loads that are coalesced across the rows of a wavefront.
+template <bool BF16, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                         uint4* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                         uint8_t* __restrict__ bm_idx) {
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t kb = blockIdx.y;
+  if (r >= rows) return;
+  uint32_t x[32];
+  uint32_t mx = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const int64_t off = (kb * 32 + i) * ld + r;
+    x[i] = BF16 ? ((uint32_t) static_cast<const uint16_t*>(src)[off]) << 16 : static_cast<const uint32_t*>(src)[off];
+    mx = umax(mx, x[i] & 0x7FFFFFFFu);
+  }
+  uint32_t idx = 32;
+#pragma unroll
+  for (int i = 31; i >= 0; --i) idx = ((x[i] & 0x7FFFFFFFu) == mx) ? (uint32_t)i : idx;
+  const uint32_t E = mx >> 23;
+  const float scale = __uint_as_float((E - 2u) << 23);
+  uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t p = 0;
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __uint_as_float(x[8 * j + 0]), __uint_as_float(x[8 * j + 1]), scale, 0);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __uint_as_float(x[8 * j + 2]), __uint_as_float(x[8 * j + 3]), scale, 1);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __uint_as_float(x[8 * j + 4]), __uint_as_float(x[8 * j + 5]), scale, 2);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(p, __uint_as_float(x[8 * j + 6]), __uint_as_float(x[8 * j + 7]), scale, 3);
+    out[j] = p;
+  }
+  if (PLUS) {
+    const uint32_t m3 = bm_mantissa(mx & 0x7FFFFFu);
+    const uint32_t sh = (idx & 7u) * 4u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t nib = ((out[j] >> sh) & 8u) | m3;
+      const uint32_t repl = (out[j] & ~(0xFu << sh)) | (nib << sh);
+      out[j] = ((idx >> 3) == (uint32_t)j) ? repl : out[j];
+    }
+  }
+  uint32_t sbyte = E - 2u;
+  if (E <= 2u || E == 255u) {
+    out[0] = out[1] = out[2] = out[3] = 0;
+    idx = 0;
+    sbyte = (E == 255u) ? 255u : 0u;
+  }
+  const int64_t b = r * nbk + kb;
+  elems[b] = make_uint4(out[0], out[1], out[2], out[3]);
+  scales[b] = (uint8_t)sbyte;
+  if (PLUS) bm_idx[b] = (uint8_t)idx;
+}
+
+int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fmt, const uint8_t* elems,
+                 const uint8_t* scales, const uint8_t* bm_idx) {
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!src || !elems || !scales || (fmt == MXP_FMT_MXFP4P && !bm_idx)) return MXP_ERR_NULL;
+  if (!aligned16(src) || !aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
+  return MXP_OK;
+}
+
+}  // namespace
+
+namespace mxp {
+
+// Shared with the on-the-fly GEMM entry point.
+int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                    uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
+  const int64_t nbk = K / kBlock;
+  const int64_t nq = rows * nbk * 4;
+  const int dense = (ld_src == K) ? 1 : 0;
+  constexpr int U = 4;
+  int64_t want = (nq + 256 * U - 1) / (256 * U);
+  const int64_t cap = (int64_t)kNumCU * 8;
+  const int grid = (int)(want < cap ? want : cap);
+  uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
+  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
+  if (bf && plus) hipLaunchKernelGGL((quantize_kernel<true, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+  else if (bf) hipLaunchKernelGGL((quantize_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+  else if (plus) hipLaunchKernelGGL((quantize_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+  else hipLaunchKernelGGL((quantize_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+  return launch_status();
+}
+
+}  // namespace mxp
+
+extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                            uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream) {
+  using namespace mxp;
+  int rc = check_common(src, src_dtype, rows, K, fmt, elems, scales, bm_idx);
+  if (rc != MXP_OK || rows == 0 || K == 0) return rc;
+  if (ld_src < K) return MXP_ERR_SHAPE;
+  const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
+  if ((ld_src * esz) % 16 != 0) return MXP_ERR_ALIGN;
+  return quantize_launch(src, src_dtype, rows, K, ld_src, fmt, elems, scales, bm_idx, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                              uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream) {
+  using namespace mxp;
+  int rc = check_common(src, src_dtype, rows, K, fmt, elems, scales, bm_idx);
+  if (rc != MXP_OK || rows == 0 || K == 0) return rc;
+  if (ld_src < rows) return MXP_ERR_SHAPE;
+  const int64_t nbk = K / kBlock;
+  if (nbk > 65535) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)((rows + 255) / 256), (unsigned)nbk);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint4* e = reinterpret_cast<uint4*>(elems);
+  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
+  if (bf && plus) hipLaunchKernelGGL((quantize_t_kernel<true, true>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  else if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, false>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  else if (plus) hipLaunchKernelGGL((quantize_t_kernel<false, true>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  else hipLaunchKernelGGL((quantize_t_kernel<false, false>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  return launch_status();
+}

@@ -1,0 +1,207 @@
+"""Thin Python binding over the C-ABI HIP library (include/mxp.h): argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the `mxp_` prefix).  torch supplies device
+memory and the current stream; nothing is computed in Python and there is no fallback path: if libmxp.so is missing
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+F32, BF16 = 0, 1
+MXFP4, MXFP4P = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxp.so")
+
+EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack",
+           "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
+           "mxp_gemm_bf16a", "mxp_status_string", "mxp_version")
+
+_lib = None
+
+
+class MxpError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load libmxp.so once (after torch, so both share one HIP runtime) and declare the signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MxpError("libmxp.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                       "or `python paper_2510_14557_amd/build.py` (needs hipcc)")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    L.mxp_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
+    L.mxp_quantize_t.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
+    L.mxp_dequantize.argtypes = [vp, vp, vp, i32, i64, i64, vp, i32, i64, vp]
+    L.mxp_image_bytes.argtypes = [i64, i64]
+    L.mxp_image_bytes.restype = sz
+    L.mxp_prepack.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
+    L.mxp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    L.mxp_gemm_workspace_bytes.restype = sz
+    L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
+    L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, vp, vp, i32, i64, vp]
+    L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
+    L.mxp_gemm_bf16a_workspace_bytes.restype = sz
+    L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, vp, i32, i64, vp, sz, vp]
+    L.mxp_status_string.argtypes = [i32]
+    L.mxp_status_string.restype = C.c_char_p
+    L.mxp_version.restype = i32
+    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_gemm", "mxp_gemm_prepacked",
+              "mxp_gemm_bf16a"):
+        getattr(L, n).restype = i32
+    _lib = L
+    return L
+
+
+def status_string(rc: int) -> str:
+    return lib().mxp_status_string(rc).decode()
+
+
+def version() -> int:
+    return lib().mxp_version()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MxpError("%s failed: %s (%d)" % (what, status_string(rc), rc))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("expected float32 or bfloat16, got %s" % t.dtype)
+
+
+def _dev2d(t: torch.Tensor):
+    if not t.is_cuda:
+        raise MxpError("tensor must live on the GPU")
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise MxpError("expected a 2-D tensor with unit inner stride")
+    return t
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def quantize(x: torch.Tensor, fmt: int = MXFP4P):
+    """x [rows, K] fp32/bf16 on the GPU -> (elems [rows,K/2], scales [rows,K/32], bm_idx [rows,K/32]) uint8."""
+    _dev2d(x)
+    rows, K = x.shape
+    ld = x.stride(0) if rows > 1 else max(K, 1)
+    elems = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    idx = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    _check(lib().mxp_quantize(_p(x), _dt(x), rows, K, ld, fmt, _p(elems), _p(scales), _p(idx), _stream()), "mxp_quantize")
+    return elems, scales, idx
+
+
+def quantize_into(x, fmt, elems, scales, idx):
+    """Same, into caller-provided buffers (no allocation)."""
+    rows, K = x.shape
+    ld = x.stride(0) if rows > 1 else max(K, 1)
+    _check(lib().mxp_quantize(_p(x), _dt(x), rows, K, ld, fmt, _p(elems), _p(scales), _p(idx), _stream()), "mxp_quantize")
+
+
+def quantize_t(xt: torch.Tensor, fmt: int = MXFP4P):
+    """xt [K, rows] (the operand stored K-strided).  Same outputs as quantize(xt.T)."""
+    _dev2d(xt)
+    K, rows = xt.shape
+    ld = xt.stride(0) if K > 1 else max(rows, 1)
+    elems = torch.empty((rows, K // 2), dtype=torch.uint8, device=xt.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=xt.device)
+    idx = torch.empty((rows, K // 32), dtype=torch.uint8, device=xt.device)
+    _check(lib().mxp_quantize_t(_p(xt), _dt(xt), rows, K, ld, fmt, _p(elems), _p(scales), _p(idx), _stream()),
+           "mxp_quantize_t")
+    return elems, scales, idx
+
+
+def dequantize(q, fmt: int = MXFP4P, dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
+    elems, scales, idx = q
+    rows, K = elems.shape[0], elems.shape[1] * 2
+    if out is None:
+        out = torch.empty((rows, K), dtype=dtype, device=elems.device)
+    ld = out.stride(0) if rows > 1 else max(K, 1)
+    _check(lib().mxp_dequantize(_p(elems), _p(scales), _p(idx), fmt, rows, K, _p(out), _dt(out), ld, _stream()),
+           "mxp_dequantize")
+    return out
+
+
+def image_bytes(rows: int, K: int) -> int:
+    return int(lib().mxp_image_bytes(rows, K))
+
+
+def prepack(q, fmt: int = MXFP4P, out: torch.Tensor | None = None):
+    elems, scales, idx = q
+    rows, K = elems.shape[0], elems.shape[1] * 2
+    n = image_bytes(rows, K)
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack(_p(elems), _p(scales), _p(idx), fmt, rows, K, _p(out), out.numel(), _stream()), "mxp_prepack")
+    return out
+
+
+def gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().mxp_gemm_workspace_bytes(M, N, K))
+
+
+def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None,
+         workspace: torch.Tensor | None = None):
+    """D[M,N] = deq(A)[M,K] @ deq(B)[N,K]^T from canonical operands."""
+    ae, as_, ai = qa
+    be, bs, bi = qb
+    M, K = ae.shape[0], ae.shape[1] * 2
+    N = be.shape[0]
+    if be.shape[1] * 2 != K:
+        raise MxpError("K mismatch between operands")
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=ae.device)
+    if workspace is None:
+        workspace = torch.empty(max(gemm_workspace_bytes(M, N, K), 16), dtype=torch.uint8, device=ae.device)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm(M, N, K, _p(ae), _p(as_), _p(ai), fmt_a, _p(be), _p(bs), _p(bi), fmt_b, _p(out), _dt(out), ldd,
+                          _p(workspace), workspace.numel(), _stream()), "mxp_gemm")
+    return out
+
+
+def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a_image.device)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), _p(b_image), _p(out), _dt(out), ldd, _stream()),
+           "mxp_gemm_prepacked")
+    return out
+
+
+def gemm_bf16a_workspace_bytes(M: int, K: int) -> int:
+    return int(lib().mxp_gemm_bf16a_workspace_bytes(M, K))
+
+
+def gemm_bf16a(a: torch.Tensor, fmt_a, b_image, N: int, out_dtype: torch.dtype = torch.float32,
+               out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """Activations quantized on the fly, weights given as a prepacked image."""
+    _dev2d(a)
+    M, K = a.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a.device)
+    if workspace is None:
+        workspace = torch.empty(max(gemm_bf16a_workspace_bytes(M, K), 16), dtype=torch.uint8, device=a.device)
+    lda = a.stride(0) if M > 1 else max(K, 1)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_bf16a(M, N, K, _p(a), _dt(a), lda, fmt_a, _p(b_image), _p(out), _dt(out), ldd,
+                                _p(workspace), workspace.numel(), _stream()), "mxp_gemm_bf16a")
+    return out

@@ -1,0 +1,72 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol include/mxp.h declares, and rejects bad
+arguments with the documented status codes before touching the GPU.  No kernels are launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_14557_amd import mxp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mxp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mxp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_is_built_and_exports_every_declared_symbol():
+    assert os.path.exists(mxp.LIB_PATH), "libmxp.so missing: run __graft_entry__.build()"
+    L = mxp.lib()
+    names = declared_symbols()
+    assert set(names) == set(mxp.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+    assert mxp.version() >= 100
+    assert mxp.status_string(0) == "ok"
+    for rc in range(-8, 0):
+        assert mxp.status_string(rc) not in ("ok", "unknown status")
+
+
+def test_argument_errors_are_reported_not_launched():
+    L = mxp.lib()
+    buf = (C.c_uint8 * 4096)()
+    addr = (C.addressof(buf) + 15) & ~15
+    p = C.c_void_p(addr)
+    odd = C.c_void_p(addr + 4)
+    # K not a multiple of 32
+    assert L.mxp_quantize(p, mxp.BF16, 4, 48, 48, mxp.MXFP4P, p, p, p, None) == -2
+    # ld smaller than K
+    assert L.mxp_quantize(p, mxp.BF16, 4, 64, 32, mxp.MXFP4P, p, p, p, None) == -2
+    # null pointers
+    assert L.mxp_quantize(None, mxp.BF16, 4, 64, 64, mxp.MXFP4P, p, p, p, None) == -1
+    assert L.mxp_quantize(p, mxp.BF16, 4, 64, 64, mxp.MXFP4P, p, p, None, None) == -1
+    # misaligned pointer / leading dimension
+    assert L.mxp_quantize(odd, mxp.BF16, 4, 64, 64, mxp.MXFP4P, p, p, p, None) == -3
+    assert L.mxp_quantize(p, mxp.BF16, 4, 64, 68, mxp.MXFP4P, p, p, p, None) == -3
+    # unknown dtype / format
+    assert L.mxp_quantize(p, 7, 4, 64, 64, mxp.MXFP4P, p, p, p, None) == -4
+    assert L.mxp_quantize(p, mxp.BF16, 4, 64, 64, 9, p, p, p, None) == -5
+    assert L.mxp_dequantize(p, p, p, 9, 4, 64, p, mxp.F32, 64, None) == -5
+    assert L.mxp_dequantize(p, p, p, mxp.MXFP4P, 4, 64, p, 5, 64, None) == -4
+    assert L.mxp_dequantize(p, p, p, mxp.MXFP4P, 4, 40, p, mxp.F32, 64, None) == -2
+    # workspace too small
+    need = mxp.gemm_workspace_bytes(64, 64, 64)
+    assert need > 0
+    assert L.mxp_gemm(64, 64, 64, p, p, p, 1, p, p, p, 1, p, mxp.F32, 64, p, need - 1, None) == -6
+    assert L.mxp_prepack(p, p, p, 1, 64, 64, p, 16, None) == -6
+    assert L.mxp_gemm(64, 64, 48, p, p, p, 1, p, p, p, 1, p, mxp.F32, 64, p, need, None) == -2
+    assert L.mxp_gemm(64, 64, 64, p, p, p, 1, p, p, p, 1, p, mxp.F32, 32, p, need, None) == -2
+    # empty problems are fine and launch nothing
+    assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
+    assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0
+
+
+def test_image_geometry():
+    # 24 bytes per 32-element block + 1 scale byte, rows padded to 256 and K to 128
+    assert mxp.image_bytes(256, 128) == 256 * 4 * 24 + 256 * 4
+    assert mxp.image_bytes(1, 32) == mxp.image_bytes(256, 128)
+    assert mxp.image_bytes(4096, 4096) == 4096 * 128 * 25
+    assert mxp.gemm_workspace_bytes(4096, 4096, 4096) == 2 * 4096 * 128 * 25

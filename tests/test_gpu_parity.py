@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, on the same seeded inputs.
+
+Quantized bytes, scales and BM indices must be bit-exact; de-converted values bit-exact; GEMM outputs within
+rel-Frobenius 1e-5 and |err| <= 2^-16 * sum_k |a_k b_k| per element.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_14557_amd import mxp, synth
+
+pytestmark = pytest.mark.gpu
+
+FMT = {"mxfp4": (mxp.MXFP4, oracle.MXFP4), "mxfp4p": (mxp.MXFP4P, oracle.MXFP4P)}
+
+
+def to_dev(x: np.ndarray) -> torch.Tensor:
+    """fp32 array or bf16-bit uint16 array -> cuda tensor (fp32 / bf16)."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def q_host(q):
+    return tuple(t.cpu().numpy() for t in q)
+
+
+def q_dev(q):
+    return tuple(torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in q)
+
+
+def assert_q_equal(got, want, fmt_name, what=""):
+    ge, gs, gi = q_host(got)
+    we, ws, wi = want
+    assert (gs == ws).all(), "%s: %d scale bytes differ" % (what, (gs != ws).sum())
+    assert (ge == we).all(), "%s: %d element bytes differ" % (what, (ge != we).sum())
+    if fmt_name == "mxfp4p":
+        assert (gi == wi).all(), "%s: %d index bytes differ" % (what, (gi != wi).sum())
+
+
+def special_tensor(rows=37, K=160, seed=3, bf16=False):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, K)).astype(np.float32) * 2
+    x[rng.random((rows, K)) < 0.02] *= 30
+    x[1, 0:32] = 0.0                                  # all-zero block
+    x[2, 32:64] = 1e-39                               # fp32 subnormals: flushed
+    x[3, 64:96] = 0.0
+    x[3, 70] = 2.0 ** -125                            # exactly at the flush limit
+    x[4, 64:96] = 0.0
+    x[4, 70] = -(2.0 ** -124)                         # just above it: scale byte 1
+    x[5, 96] = x[5, 100] = -7.0                       # equal maxima
+    x[6, 0:32] = (rng.integers(-32, 33, 32) / 8.0)    # exact ties everywhere
+    x[7, 3] = np.inf
+    x[8, 40] = np.nan
+    x[9, 5] = 3.0e38
+    x[10, 0:32] = -0.0
+    x[11, 0:32] = 0.01
+    x[11, 31] = 7.9                                   # BM mantissa carry -> saturates
+    x[12, 0:32] = [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 7.0] * 4
+    x[12, 9] = 7.5
+    if bf16:
+        return synth.f32_to_bf16_bits(x)
+    return x
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_special_cases(fmt, bf16):
+    x = special_tensor(bf16=bf16)
+    got = mxp.quantize(to_dev(x), FMT[fmt][0])
+    torch.cuda.synchronize()
+    assert_q_equal(got, oracle.quantize(x, FMT[fmt][1]), fmt, "special")
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
+def test_quantize_tiny_config(fmt):
+    a, b = synth.tiny()
+    for x in (a, b):
+        got = mxp.quantize(to_dev(x), FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize(x, FMT[fmt][1]), fmt, "tiny")
+
+
+@pytest.mark.parametrize("rows,K", [(1, 32), (5, 96), (3, 4096), (8, 4096), (131, 4096 + 64), (2048, 4096)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_shapes_ragged_and_full(rows, K, bf16):
+    x = synth.activations(rows, K, config_id=2, tensor_id=0, dtype="bf16" if bf16 else "f32")
+    got = mxp.quantize(to_dev(x), mxp.MXFP4P)
+    assert_q_equal(got, oracle.quantize(x, oracle.MXFP4P), "mxfp4p", "%dx%d" % (rows, K))
+
+
+def test_quantize_weights_with_heavy_tails():
+    w = synth.weights(512, 4096, config_id=3, tensor_id=1, t3_frac=0.001)
+    for fmt in ("mxfp4", "mxfp4p"):
+        assert_q_equal(mxp.quantize(to_dev(w), FMT[fmt][0]), oracle.quantize(w, FMT[fmt][1]), fmt, "weights")
+
+
+def test_quantize_strided_rows_and_empty():
+    x = special_tensor(rows=19, K=192, bf16=True)
+    big = torch.zeros((19, 256), dtype=torch.bfloat16, device="cuda")
+    big[:, :192] = to_dev(x)
+    got = mxp.quantize(big[:, :192], mxp.MXFP4P)                       # ld = 256
+    assert_q_equal(got, oracle.quantize(x, oracle.MXFP4P), "mxfp4p", "strided")
+    e, s, i = mxp.quantize(torch.zeros((0, 64), device="cuda"), mxp.MXFP4P)
+    assert e.numel() == 0 and s.numel() == 0
+    e, s, i = mxp.quantize(torch.zeros((4, 0), device="cuda"), mxp.MXFP4P)
+    assert e.numel() == 0
+
+
+def test_quantize_exhaustive_bf16_patterns():
+    pats = np.arange(1 << 16, dtype=np.uint16)
+    # every pattern as an ordinary element next to a fixed BM, for several scales, and as the BM of its own block
+    for k in (-100, -3, 0, 60):
+        bm = synth.f32_to_bf16_bits(np.array([7.96875 * 2.0 ** k], np.float32))[0]
+        vals = synth.bf16_bits_to_f32(pats)
+        ok = np.isfinite(vals) & (np.abs(vals) < 7.96875 * 2.0 ** k)
+        v = pats[ok]
+        n = (len(v) + 30) // 31
+        blocks = np.zeros((n, 32), np.uint16)
+        blocks[:, 0] = bm
+        blocks[:, 1:].reshape(-1)[: len(v)] = v
+        got = mxp.quantize(to_dev(blocks), mxp.MXFP4P)
+        assert_q_equal(got, oracle.quantize(blocks, oracle.MXFP4P), "mxfp4p", "nbm k=%d" % k)
+    blocks = np.zeros((1 << 16, 32), np.uint16)
+    blocks[:, 17] = pats                                              # includes NaN, Inf, subnormals, +-0
+    for fmt in ("mxfp4", "mxfp4p"):
+        got = mxp.quantize(to_dev(blocks), FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize(blocks, FMT[fmt][1]), fmt, "bm exhaustive")
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_t(bf16):
+    x = special_tensor(rows=300, K=160, seed=9, bf16=bf16)
+    xt = np.ascontiguousarray(x.T)
+    for fmt in ("mxfp4", "mxfp4p"):
+        got = mxp.quantize_t(to_dev(xt), FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize_t(xt, FMT[fmt][1]), fmt, "quantize_t")
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
+def test_dequantize_bit_exact(fmt):
+    x = special_tensor(rows=64, K=256, seed=21)
+    q = oracle.quantize(x, FMT[fmt][1])
+    # add hand-made blocks: every nibble at every position with extreme scales, and a flushed block with junk bits
+    e, s, i = (a.copy() for a in q)
+    e[20, :16] = np.arange(16) * 17
+    s[20, 0], i[20, 0] = 1, 3
+    e[21, :16] = np.arange(16) * 17
+    s[21, 0], i[21, 0] = 252, 30
+    e[22, :16] = 0xFF
+    s[22, 0], i[22, 0] = 0, 7
+    e[23, :16] = 0x5A
+    s[23, 0], i[23, 0] = 255, 0
+    want = oracle.dequantize((e, s, i), FMT[fmt][1])
+    for dt in (torch.float32, torch.bfloat16):
+        got = mxp.dequantize(q_dev((e, s, i)), FMT[fmt][0], dt).float().cpu().numpy().astype(np.float64)
+        nan = np.isnan(want)
+        assert (np.isnan(got) == nan).all()
+        assert (got[~nan] == want[~nan]).all()
+        assert (np.signbit(got[~nan]) == np.signbit(want[~nan])).all()
+    # strided destination
+    out = torch.full((64, 320), 9.0, device="cuda")
+    mxp.dequantize(q_dev((e, s, i)), FMT[fmt][0], out=out[:, :256])
+    got = out.cpu().numpy()
+    assert (got[:, 256:] == 9.0).all()
+    nan = np.isnan(want)
+    assert (got[:, :256][~nan] == want[~nan]).all()
+
+
+def check_gemm(D, ref, S, what=""):
+    D = D.double().cpu().numpy()
+    fro = np.linalg.norm(D - ref) / max(np.linalg.norm(ref), 1e-300)
+    assert fro <= 1e-5, "%s: relative Frobenius error %.3e" % (what, fro)
+    bound = 2.0 ** -16 * S
+    worst = (np.abs(D - ref) - bound).max() if D.size else 0.0
+    assert worst <= 0, "%s: element error exceeds 2^-16 * sum|ab| by %.3e" % (what, worst)
+
+
+@pytest.mark.parametrize("fa,fb", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4")])
+def test_gemm_tiny_config(fa, fb):
+    a, b = synth.tiny()
+    qa, qb = oracle.quantize(a, FMT[fa][1]), oracle.quantize(b, FMT[fb][1])
+    ref, S = oracle.gemm(qa, FMT[fa][1], qb, FMT[fb][1])
+    D = mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qb), FMT[fb][0])
+    check_gemm(D, ref, S, "tiny %s x %s" % (fa, fb))
+
+
+def test_gemm_single_block_hand_cases():
+    # equal BM positions, different positions, and a flushed block: results known in closed form
+    a = np.zeros((1, 64), np.float32)
+    b = np.zeros((1, 64), np.float32)
+    a[0, 2], a[0, 9] = 7.0, 1.5
+    b[0, 2], b[0, 9] = -5.0, 3.0
+    a[0, 40] = 1e-39                                                   # second block flushed in A
+    b[0, 40] = 5.0
+    qa, qb = oracle.quantize(a), oracle.quantize(b)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P)
+    assert D.cpu().numpy()[0, 0] == 7.0 * -5.0 + 1.5 * 3.0
+    b[0, 2], b[0, 9] = 3.0, -5.0
+    qb = oracle.quantize(b)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P)
+    assert D.cpu().numpy()[0, 0] == 7.0 * 3.0 + 1.5 * -5.0
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (16, 256, 256), (33, 100, 96), (100, 200, 416), (257, 300, 1024),
+                                   (300, 520, 2048)])
+def test_gemm_shapes(M, N, K):
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = oracle.quantize(a), oracle.quantize(w)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qb, oracle.MXFP4P)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P)
+    check_gemm(D, ref, S, "%dx%dx%d" % (M, N, K))
+    # the GPU quantizer feeds the same product
+    D2 = mxp.gemm(mxp.quantize(to_dev(a)), mxp.MXFP4P, mxp.quantize(to_dev(w)), mxp.MXFP4P)
+    assert torch.equal(D, D2)
+    # prepacked weights + on-the-fly activations
+    img = mxp.prepack(q_dev(qb), mxp.MXFP4P)
+    D3 = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, img, N)
+    assert torch.equal(D, D3)
+    # bf16 output = the fp32 result rounded once
+    Db = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P, out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+def test_gemm_strided_output_and_k0():
+    a = synth.activations(40, 128, config_id=1, tensor_id=0)
+    w = synth.weights(72, 128, config_id=1, tensor_id=1)
+    qa, qb = oracle.quantize(a), oracle.quantize(w)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qb, oracle.MXFP4P)
+    out = torch.full((40, 128), -1.0, device="cuda")
+    mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P, out=out[:, :72])
+    check_gemm(out[:, :72], ref, S, "strided D")
+    assert (out[:, 72:] == -1.0).all()
+    e = torch.zeros((4, 0), dtype=torch.uint8, device="cuda")
+    D = mxp.gemm((e, e, e), mxp.MXFP4P, (torch.zeros((8, 0), dtype=torch.uint8, device="cuda"),) * 3, mxp.MXFP4P)
+    assert D.shape == (4, 8) and not D.any()
+
+
+def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0):
+    """Full-size GEMM on the GPU in the launch configuration the benchmark times; sampled outputs from the oracle."""
+    a, ws = synth.make(name, M=M, N=N)
+    wname = wname or next(iter(ws))
+    w = ws[wname]
+    da, dw = to_dev(a), to_dev(w)
+    qa, qw = mxp.quantize(da, mxp.MXFP4P), mxp.quantize(dw, mxp.MXFP4P)
+    D = mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    Mv, Nv = a.shape[0], w.shape[0]
+    rm = rng.integers(0, Mv, n_samples)
+    rn = rng.integers(0, Nv, n_samples)
+    rm[:8] = [0, Mv - 1, 0, Mv - 1, Mv // 2, 255 % Mv, 256 % Mv, 31 % Mv]
+    rn[:8] = [0, Nv - 1, Nv - 1, 0, Nv // 2, 255 % Nv, 256 % Nv, 32 % Nv]
+    # quantized operands: compare a band of rows bit-exactly with the oracle, then use the GPU bytes for the product
+    rows = np.unique(np.concatenate([np.arange(min(64, Mv)), rm[:256]]))
+    qo = oracle.quantize(a[rows], oracle.MXFP4P)
+    qh = q_host(qa)
+    assert all((g[rows] == o).all() for g, o in zip(qh, qo))
+    rows = np.unique(np.concatenate([np.arange(min(64, Nv)), rn[:256]]))
+    qo = oracle.quantize(w[rows], oracle.MXFP4P)
+    qwh = q_host(qw)
+    assert all((g[rows] == o).all() for g, o in zip(qwh, qo))
+    ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, oracle.MXFP4P, rm, rn)
+    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
+    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+
+
+def test_gemm_full_size_decode_sampled():
+    _sampled_check("decode")
+
+
+def test_gemm_full_size_prefill_attn_sampled():
+    _sampled_check("prefill_attn", wname="wqo")
+    _sampled_check("prefill_attn", wname="wkv")
+
+
+def test_gemm_full_size_prefill_mlp_sampled():
+    _sampled_check("prefill_mlp")
