@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the MXFP4+ hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic Llama-3.1-8B MLP-shaped data (gate/up projection,
+4096 tokens):  quantize the bf16 activations to MXFP4+  ->  W4A4 GEMM against the MXFP4+ weights (E2M3 image build of
+both operands + block-scaled MFMA kernel, fp32 output)  ->  de-convert the activations back to bf16.  Weights are
+quantized once before the timed region (they are static); everything else, including the image build of the weights,
+is inside it.  Inputs are resident in HBM when timing starts.
+
+Prints ONE JSON line.  `value` = 2*M*N*K / (time of the whole step): every stage is in the denominator, only the
+useful GEMM flops are in the numerator.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP4_TFLOPS = 10100.0     # MI355X dense MXFP4 MFMA, published
+PEAK_HBM_GBPS = 8000.0
+
+WORKLOADS = {
+    # name: (synth config, weight name)
+    "prefill_mlp": ("prefill_mlp", "wgate"),
+    "prefill_attn": ("prefill_attn", "wqo"),
+    "decode": ("decode", "w"),
+}
+
+
+def cpu_baseline(a_bits, w_bits, budget_s=15.0):
+    """The CPU oracle on a bounded sample of the same workload: quantize + fp64 GEMM of a row subset."""
+    import numpy as np
+    import oracle
+
+    K = a_bits.shape[1]
+    threads = oracle.num_threads()
+    # calibrate on a small piece, then size the sample for about budget_s of CPU work
+    m0, n0 = min(8, a_bits.shape[0]), min(512, w_bits.shape[0])
+    t = time.perf_counter()
+    qa = oracle.quantize(a_bits[:m0], oracle.MXFP4P)
+    qw = oracle.quantize(w_bits[:n0], oracle.MXFP4P)
+    oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
+    dt = max(time.perf_counter() - t, 1e-4)
+    rate = m0 * n0 * K / dt
+    n = min(w_bits.shape[0], 2048)
+    m = int(max(8, min(a_bits.shape[0], budget_s * rate / (n * K))))
+    t = time.perf_counter()
+    qa = oracle.quantize(a_bits[:m], oracle.MXFP4P)
+    qw = oracle.quantize(w_bits[:n], oracle.MXFP4P)
+    oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
+    oracle.dequantize(qa, oracle.MXFP4P)
+    dt = time.perf_counter() - t
+    return {"value": 2.0 * m * n * K / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "oracle quantize+gemm+dequantize on A[%d x %d] x W[%d x %d]^T (first rows of the same tensors), %.1f s"
+                      % (m, K, n, K, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "prepack", "gemm", "dequantize"],
+                    help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives exist in the method's hot path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_14557_amd import mxp, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    mxp.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    cfg, wname = WORKLOADS[args.workload]
+    a_bits, ws = synth.make(cfg)
+    w_bits = ws[wname]
+    M, K = a_bits.shape
+    N = w_bits.shape[0]
+
+    def to_dev(x):
+        return torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    A, W = to_dev(a_bits), to_dev(w_bits)
+    out_dt = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
+    # static weights: quantized once, outside the timed region
+    qw = mxp.quantize(W, mxp.MXFP4P)
+    del W
+    # every buffer the step touches is allocated once
+    qa = (torch.empty((M, K // 2), dtype=torch.uint8, device=dev), torch.empty((M, K // 32), dtype=torch.uint8, device=dev),
+          torch.empty((M, K // 32), dtype=torch.uint8, device=dev))
+    img_a = torch.empty(mxp.image_bytes(M, K), dtype=torch.uint8, device=dev)
+    img_w = torch.empty(mxp.image_bytes(N, K), dtype=torch.uint8, device=dev)
+    D = torch.empty((M, N), dtype=out_dt, device=dev)
+    back = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+
+    stages = ("quantize", "prepack_a", "prepack_w", "gemm", "dequantize")
+
+    def step_only():
+        if args.only == "quantize":
+            mxp.quantize_into(A, mxp.MXFP4P, *qa)
+        elif args.only == "prepack":
+            mxp.prepack(qw, mxp.MXFP4P, out=img_w)
+        elif args.only == "gemm":
+            mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D)
+        else:
+            mxp.dequantize(qa, mxp.MXFP4P, out=back)
+
+    def step(ev=None):
+        # the same kernels, in the same order, that mxp_quantize + mxp_gemm + mxp_dequantize enqueue
+        if ev is not None:
+            ev[0].record()
+        mxp.quantize_into(A, mxp.MXFP4P, *qa)
+        if ev is not None:
+            ev[1].record()
+        mxp.prepack(qa, mxp.MXFP4P, out=img_a)
+        if ev is not None:
+            ev[2].record()
+        mxp.prepack(qw, mxp.MXFP4P, out=img_w)
+        if ev is not None:
+            ev[3].record()
+        mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D)
+        if ev is not None:
+            ev[4].record()
+        mxp.dequantize(qa, mxp.MXFP4P, out=back)
+        if ev is not None:
+            ev[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if args.only != "all":
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_only()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "ms_per_call": (time.perf_counter() - t0) * 1e3 / args.steps,
+                          "note": "profiling aid, not a benchmark line"}))
+        return
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    stage_ms = {n: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
+                for i, n in enumerate(stages)}
+
+    flops = 2.0 * M * N * K
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    gemm_tflops = flops / (stage_ms["gemm"] * 1e-3) / 1e12
+    q_bytes = M * K * 2.5625                                  # bf16 in + nibbles + scale + index
+    dq_bytes = M * K * (0.5625 + 2.0)
+    pp_bytes = lambda r: r * K * (0.5625 + 0.78125)
+    out_line = {
+        "metric": "MXFP4+ GEMM TFLOP/s (Llama-8B linear shapes); quantize GB/s; % roofline",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "mxfp4+ (E2M1 elements, E2M3 block max, E8M0 scales), fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "A": "bf16 N(0,1) + outlier channels x50",
+                   "W": "bf16 N(0,0.02) + 0.1% Student-t(3)" if args.workload == "prefill_mlp" else "bf16 N(0,0.02)",
+                   "out_dtype": args.out_dtype,
+                   "step": "quantize(A) -> image(A), image(W) -> scaled-MFMA GEMM -> dequantize(A)"},
+        "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / PEAK_FP4_TFLOPS, "traffic": None, "kernel": "gemm_kernel",
+                     "kernel_ms": stage_ms["gemm"]},
+        "stages_ms": stage_ms,
+        "quantize_GBps": q_bytes / (stage_ms["quantize"] * 1e-3) / 1e9,
+        "quantize_frac_hbm": q_bytes / (stage_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "dequantize_GBps": dq_bytes / (stage_ms["dequantize"] * 1e-3) / 1e9,
+        "prepack_w_GBps": pp_bytes(N) / (stage_ms["prepack_w"] * 1e-3) / 1e9,
+        "gemm_only_TFLOPs": gemm_tflops,
+        "gemm_with_prepacked_weights_TFLOPs": flops / ((stage_ms["gemm"] + stage_ms["prepack_a"] + stage_ms["quantize"]) * 1e-3) / 1e12,
+    }
+    if not args.no_cpu_baseline:
+        out_line["cpu_baseline"] = cpu_baseline(a_bits, w_bits)
+    print(json.dumps(out_line))
+
+
+if __name__ == "__main__":
+    main()

@@ -32,6 +32,11 @@ __device__ __forceinline__ v16f mfma(const v8i& a, const v8i& b, const v16f& c, 
   return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, kFmtE2M3, kFmtE2M3, OA, sa, OB, sb);
 }
 
+template <int I, int J>
+__device__ __forceinline__ v16f mfma_sel(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
+  return mfma<(I & 3), (J & 3)>(a, b, c, sa, sb);
+}
+
 // Tile configuration: a workgroup of WAVES_M x WAVES_N wavefronts, each computing WM x WN MFMA tiles of 32 x 32.
 template <int WM_, int WN_, int WAVES_M_, int WAVES_N_>
 struct Cfg {
@@ -45,6 +50,63 @@ struct Cfg {
   static constexpr int CHUNKS = STAGE_BYTES / 16;                 // 16-byte pieces per stage
   static constexpr int PER_THREAD = (CHUNKS + THREADS - 1) / THREADS;
 };
+
+// All WM x WN MFMAs of one k-tile.  op_sel picks, from the lane's scale dword, the byte of row tile i / column tile j.
+template <class C>
+__device__ __forceinline__ void mma_all(v16f (&acc)[C::WM][C::WN], const v8i (&a)[C::WM], const v8i (&b)[C::WN],
+                                        const uint32_t (&sa)[(C::WM + 3) / 4], const uint32_t (&sb)[(C::WN + 3) / 4]) {
+#pragma unroll
+  for (int i = 0; i < C::WM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::WN; ++j) {
+        const int sai = (int)sa[i >> 2], sbj = (int)sb[j >> 2];
+        switch ((i & 3) * 4 + (j & 3)) {
+          case 0: acc[i][j] = mfma<0, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 1: acc[i][j] = mfma<0, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 2: acc[i][j] = mfma<0, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 3: acc[i][j] = mfma<0, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 4: acc[i][j] = mfma<1, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 5: acc[i][j] = mfma<1, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 6: acc[i][j] = mfma<1, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 7: acc[i][j] = mfma<1, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 8: acc[i][j] = mfma<2, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 9: acc[i][j] = mfma<2, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 10: acc[i][j] = mfma<2, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 11: acc[i][j] = mfma<2, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 12: acc[i][j] = mfma<3, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 13: acc[i][j] = mfma<3, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 14: acc[i][j] = mfma<3, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
+          default: acc[i][j] = mfma<3, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+        }
+      }
+}
+
+// Epilogue: for a fixed accumulator register the 32 lanes of a half-wave write 32 consecutive columns of one row.
+template <class C, bool OUT_BF16>
+__device__ __forceinline__ void store_tile(const v16f (&acc)[C::WM][C::WN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
+                                           int64_t N, void* __restrict__ Dv, int64_t ldd) {
+#pragma unroll
+  for (int i = 0; i < C::WM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::WN; ++j) {
+      const int64_t col = (tile_n + j) * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = (tile_m + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < M && col < N) {
+          const float v = acc[i][j][r];
+          if (OUT_BF16) {
+            uint32_t u = __float_as_uint(v);
+            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x00400000u;       // keep NaN a NaN
+            else u += 0x7FFFu + ((u >> 16) & 1u);                          // round to nearest even
+            static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)(u >> 16);
+          } else {
+            static_cast<float*>(Dv)[row * ldd + col] = v;
+          }
+        }
+      }
+    }
+}
 
 // Source address of 16-byte chunk c of a stage (k-tile kt) -- the stage is a concatenation of contiguous image runs.
 template <class C>
@@ -139,56 +201,219 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
 #pragma unroll
     for (int g = 0; g < (C::WN + 3) / 4; ++g)
       sb[g] = *reinterpret_cast<const uint32_t*>(st + C::A_BYTES + C::B_BYTES + C::SA_BYTES + (gb + g) * 256 + lane * 4) >> (8 * (int)(tb & 3));
-#pragma unroll
-    for (int i = 0; i < C::WM; ++i)
-#pragma unroll
-      for (int j = 0; j < C::WN; ++j) {
-        const int sai = (int)sa[i >> 2], sbj = (int)sb[j >> 2];
-        switch ((i & 3) * 4 + (j & 3)) {
-          case 0: acc[i][j] = mfma<0, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 1: acc[i][j] = mfma<0, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 2: acc[i][j] = mfma<0, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 3: acc[i][j] = mfma<0, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 4: acc[i][j] = mfma<1, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 5: acc[i][j] = mfma<1, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 6: acc[i][j] = mfma<1, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 7: acc[i][j] = mfma<1, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 8: acc[i][j] = mfma<2, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 9: acc[i][j] = mfma<2, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 10: acc[i][j] = mfma<2, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 11: acc[i][j] = mfma<2, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 12: acc[i][j] = mfma<3, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 13: acc[i][j] = mfma<3, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 14: acc[i][j] = mfma<3, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          default: acc[i][j] = mfma<3, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-        }
-      }
+    mma_all<C>(acc, a, b, sa, sb);
     if (kt + 1 < k_tiles) commit(buf ^ 1);
     __syncthreads();
   }
 
-  // epilogue: for a fixed accumulator register the 32 lanes of a half-wave write 32 consecutive columns of one row
+  store_tile<C, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
+}
+
+// ---- pipelined kernel: S-stage LDS ring filled by direct global->LDS loads ------------------------------------
+// A stage (one k-tile of the workgroup's A and B tiles plus their scale dwords) is a concatenation of contiguous image
+// runs, so it is copied with global_load_lds_dwordx4: every lane fetches 16 bytes and the wavefront's 1 KiB lands
+// contiguously in LDS at the address held in M0.  The copies bypass the VGPRs, are issued S-3 k-tiles before their use and are
+// tracked by hand: the compiler does not see them, so each k-tile waits with an explicit vmcnt for the stage it is
+// about to read, then meets the other wavefronts at a barrier.  Operand fragments are double-buffered in registers,
+// and the LDS reads and copy issues of the following k-tiles are placed between the MFMAs of the current one, so
+// that they issue in the shadow of the 8-pass MFMAs instead of ahead of them.
+__device__ __forceinline__ void dma16_sv(uint32_t voff, const uint8_t* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma4_sv(uint32_t voff, const uint8_t* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_dma_and_barrier() {
+  // all but the newest N copies of this wavefront have landed; its own LDS reads are done; then meet the others
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 2)
+  return (v8i){lane, 1, 2, 3, 4, 5, 0, 0};   // timing experiment: no LDS operand reads
+#endif
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+}
+
+template <class C, int S, bool OUT_BF16>
+__global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                              const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                              int64_t k_tiles, int64_t M, int64_t N, void* __restrict__ Dv,
+                                                              int64_t ldd) {
+  static_assert(C::WM == 4 && C::WN == 4, "the MFMA / copy interleave below is written for 4 x 4 tiles per wavefront");
+  constexpr int A_CH = C::A_BYTES / 16, B_CH = C::B_BYTES / 16, SA_CH = C::SA_BYTES / 16, SB_CH = C::SB_BYTES / 16;
+  static_assert(A_CH % C::THREADS == 0 && B_CH % C::THREADS == 0, "element runs split into whole workgroup rounds");
+  static_assert(C::SA_BYTES + C::SB_BYTES == 256 * C::WAVES_M * C::WAVES_N, "each wavefront copies 256 scale bytes per stage");
+  static_assert(C::SA_BYTES % 256 == 0, "scale groups");
+  constexpr int UA = A_CH / C::THREADS, UB = B_CH / C::THREADS;
+  static_assert(UA + UB == 6, "copy slots in the interleave");
+  static_assert(S >= 4, "ring depth");
+  constexpr int TILE_CH = kTileBytes / 16;
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+  const int64_t tm0 = (int64_t)blockIdx.y * C::TM, tn0 = (int64_t)blockIdx.x * C::TN;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+
+  // Copy sources.  Element runs: scalar base (advanced by one tile per k-tile) + a per-lane 32-bit offset.
+  uint32_t offA[UA], offB[UB];
+#pragma unroll
+  for (int u = 0; u < UA; ++u) {
+    const int c = tid + u * C::THREADS;
+    offA[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+  }
+#pragma unroll
+  for (int u = 0; u < UB; ++u) {
+    const int c = tid + u * C::THREADS;
+    offB[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+  }
+  const uint8_t* const baseA = a_el + tm0 * k_tiles * kTileBytes;
+  const uint8_t* const baseB = b_el + tn0 * k_tiles * kTileBytes;
+  // Scale dwords: the stage holds SA_BYTES/256 groups of A then the groups of B, 256 bytes (64 lanes x 1 dword) each;
+  // wavefront w copies group w with one dword-wide copy.  256 bytes further per k-tile.
+  constexpr int GA = C::SA_BYTES / 256;
+  const uint8_t* const baseS = wave < GA ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256 : b_sc + ((tn0 / 4 + (wave - GA)) * k_tiles) * 256;
+  const uint32_t offS = (uint32_t)lane * 4u;
+
+  int issue_kt = 0;     // next stage to copy
+  int issue_slot = 0;   // its ring slot
+  const int last_kt = (int)k_tiles - 1;
+  // Copy number u (0..6) of the stage `issue_kt`.  Past the end the last stage is fetched again into a slot that is
+  // never read, which keeps the number of copies in flight the same in every iteration.
+  auto copy = [&](int u) {
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 1)
+    if (issue_kt >= S - 2) return;      // timing experiment: no copies inside the main loop
+#endif
+    const int k = issue_kt < last_kt ? issue_kt : last_kt;
+    const uint32_t slot = lds_base + (uint32_t)issue_slot * C::STAGE_BYTES;
+    if (u < UA) {
+      dma16_sv(offA[u], baseA + (int64_t)k * kTileBytes, slot + (uint32_t)(u * C::THREADS + wave * 64) * 16u);
+    } else if (u < UA + UB) {
+      dma16_sv(offB[u - UA], baseB + (int64_t)k * kTileBytes, slot + C::A_BYTES + (uint32_t)((u - UA) * C::THREADS + wave * 64) * 16u);
+    } else {
+      dma4_sv(offS, baseS + (int64_t)k * 256, slot + C::A_BYTES + C::B_BYTES + (uint32_t)wave * 256u);
+    }
+  };
+  auto next_stage = [&]() {
+    ++issue_kt;
+    issue_slot = issue_slot + 1 == S ? 0 : issue_slot + 1;
+  };
+
+  v16f acc[C::WM][C::WN];
 #pragma unroll
   for (int i = 0; i < C::WM; ++i)
 #pragma unroll
-    for (int j = 0; j < C::WN; ++j) {
-      const int64_t col = (tn0 + wn * C::WN + j) * 32 + (lane & 31);
+    for (int j = 0; j < C::WN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = (tm0 + wm * C::WM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < M && col < N) {
-          const float v = acc[i][j][r];
-          if (OUT_BF16) {
-            uint32_t u = __float_as_uint(v);
-            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x00400000u;       // keep NaN a NaN
-            else u += 0x7FFFu + ((u >> 16) & 1u);                          // round to nearest even
-            static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)(u >> 16);
-          } else {
-            static_cast<float*>(Dv)[row * ldd + col] = v;
-          }
-        }
-      }
-    }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int64_t ta = tm0 + wm * C::WM, tb = tn0 + wn * C::WN;   // multiples of 4: one scale dword covers the 4 tiles
+  const int a_tiles_off = wm * C::WM * kTileBytes;
+  const int b_tiles_off = C::A_BYTES + wn * C::WN * kTileBytes;
+  const int sa_off = C::A_BYTES + C::B_BYTES + wm * 256 + lane * 4;
+  const int sb_off = C::A_BYTES + C::B_BYTES + C::SA_BYTES + wn * 256 + lane * 4;
+
+  v8i a0[4], b0[4], a1[4], b1[4];
+  uint32_t sa0[1], sb0[1], sa1[1], sb1[1];
+
+  // Copy accounting (the copies of one wavefront complete in order, PER_STAGE of them per stage).  The prologue issues
+  // stages 0 .. S-3 and needs stage 0: S-3 newer stages may stay in flight.  Iteration kt waits BEFORE it issues stage
+  // kt+S-2, so stages up to kt+S-3 are issued and it needs stage kt+1: S-4 newer stages may stay in flight.
+  constexpr int PER_STAGE = UA + UB + 1;
+  constexpr int KEEP_PROLOGUE = (S - 3) * PER_STAGE;
+  constexpr int KEEP = (S - 4) * PER_STAGE;
+  static_assert(KEEP_PROLOGUE <= 63, "vmcnt is a 6-bit counter");
+
+  // prologue: stages 0 .. S-3 in flight, stage 0 landed, fragments of k-tile 0 in registers
+#pragma unroll
+  for (int s = 0; s < S - 2; ++s) {
+#pragma unroll
+    for (int u = 0; u < UA + UB + 1; ++u) copy(u);
+    next_stage();
+  }
+  wait_dma_and_barrier<KEEP_PROLOGUE>();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a0[i] = read_operand(lds + a_tiles_off + i * kTileBytes, lane);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) b0[j] = read_operand(lds + b_tiles_off + j * kTileBytes, lane);
+  sa0[0] = *reinterpret_cast<const uint32_t*>(lds + sa_off);
+  sb0[0] = *reinterpret_cast<const uint32_t*>(lds + sb_off);
+
+  int read_slot = 1;    // ring slot of k-tile kt + 1
+
+  // One k-tile: 16 MFMAs on (ca, cb); between them the reads of the next k-tile into (na, nb) and the copies of a
+  // later stage.
+#define MXP_MFMA(m) \
+  acc[(m) / 4][(m) % 4] = mfma_sel<(m) / 4, (m) % 4>(ca[(m) / 4], cb[(m) % 4], acc[(m) / 4][(m) % 4], (int)csa[0], (int)csb[0]); \
+  __builtin_amdgcn_sched_barrier(0)
+  auto ktile = [&](const v8i (&ca)[4], const v8i (&cb)[4], const uint32_t (&csa)[1], const uint32_t (&csb)[1], v8i (&na)[4],
+                   v8i (&nb)[4], uint32_t (&nsa)[1], uint32_t (&nsb)[1]) {
+    MXP_MFMA(0);
+    MXP_MFMA(1);
+    wait_dma_and_barrier<KEEP>();                     // stage kt + 1 is complete in LDS for every wavefront
+    const uint8_t* st = lds + read_slot * C::STAGE_BYTES;
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(2);
+    na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(3);
+    na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(4);
+    na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(5);
+    na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(6);
+    nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(7);
+    nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(8);
+    nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(9);
+    nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane);
+    nsa[0] = *reinterpret_cast<const uint32_t*>(st + sa_off);
+    nsb[0] = *reinterpret_cast<const uint32_t*>(st + sb_off);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(10);
+    copy(0);
+    copy(1);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(11);
+    copy(2);
+    copy(3);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(12);
+    copy(4);
+    copy(5);
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(13);
+    copy(6);
+    next_stage();
+    read_slot = read_slot + 1 == S ? 0 : read_slot + 1;
+    __builtin_amdgcn_sched_barrier(0);
+    MXP_MFMA(14);
+    MXP_MFMA(15);
+  };
+
+  for (int64_t kt = 0; kt < k_tiles; kt += 2) {   // k_tiles is even (K is padded to 128)
+    ktile(a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+    ktile(a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+  }
+#undef MXP_MFMA
+  // drain the copies that were issued past the end before the workgroup's LDS is released
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  store_tile<C, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd);
 }
 
 template <class C>
@@ -215,13 +440,38 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   return launch_status();
 }
 
+template <class C, int S>
+int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+               hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const int64_t gm = (M + C::TM * 32 - 1) / (C::TM * 32), gn = (N + C::TN * 32 - 1) / (C::TN * 32);
+  if (gm > 65535 || gn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)gn, (unsigned)gm);
+  constexpr size_t lds = (size_t)S * C::STAGE_BYTES;
+  static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KiB of a CDNA4 compute unit");
+  if (d_dtype == MXP_BF16) {
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, true>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
+    (void)once_b;
+    hipLaunchKernelGGL((gemm_kernel_dma<C, S, true>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
+                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd);
+  } else {
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, false>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
+    (void)once_f;
+    hipLaunchKernelGGL((gemm_kernel_dma<C, S, false>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
+                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd);
+  }
+  return launch_status();
+}
+
 int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                 hipStream_t s) {
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
   if (M <= 32) return launch_cfg<Cfg<1, 2, 1, 4>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (M <= 64) return launch_cfg<Cfg<1, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  return launch_cfg<Cfg<4, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return launch_dma<Cfg<4, 4, 2, 2>, 6>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
 int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {
