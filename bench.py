@@ -39,14 +39,14 @@ def cpu_baseline(a_bits, w_bits, budget_s=15.0):
     K = a_bits.shape[1]
     threads = oracle.num_threads()
     # calibrate on a small piece, then size the sample for about budget_s of CPU work
-    m0, n0 = min(8, a_bits.shape[0]), min(512, w_bits.shape[0])
+    m0, n0 = min(64, a_bits.shape[0]), min(2048, w_bits.shape[0])
     t = time.perf_counter()
     qa = oracle.quantize(a_bits[:m0], oracle.MXFP4P)
     qw = oracle.quantize(w_bits[:n0], oracle.MXFP4P)
     oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
     dt = max(time.perf_counter() - t, 1e-4)
     rate = m0 * n0 * K / dt
-    n = min(w_bits.shape[0], 2048)
+    n = min(w_bits.shape[0], 4096)
     m = int(max(8, min(a_bits.shape[0], budget_s * rate / (n * K))))
     t = time.perf_counter()
     qa = oracle.quantize(a_bits[:m], oracle.MXFP4P)
@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "prepack", "gemm", "dequantize"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "prepack", "gemm", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -107,6 +107,9 @@ def main():
     back = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
 
     stages = ("quantize", "prepack_a", "prepack_w", "gemm", "dequantize")
+    if args.only == "copy":
+        copy_src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        copy_dst = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
 
     def step_only():
         if args.only == "quantize":
@@ -115,6 +118,9 @@ def main():
             mxp.prepack(qw, mxp.MXFP4P, out=img_w)
         elif args.only == "gemm":
             mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D)
+        elif args.only == "copy":
+            # plain device copy of a known size (256 MiB): the reference that scales the FETCH_SIZE / WRITE_SIZE counters
+            copy_dst.copy_(copy_src)
         else:
             mxp.dequantize(qa, mxp.MXFP4P, out=back)
 
