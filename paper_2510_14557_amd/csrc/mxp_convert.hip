@@ -23,6 +23,13 @@ __device__ __forceinline__ uint32_t make_f32(uint32_t sign, uint32_t M, uint32_t
   return (sign << 31) | bits;
 }
 
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// Eight elements (one dword of nibbles) per lane.  Common case: the E2M1 elements go through the CDNA4 unpack-convert
+// instruction with X = 2^shared_exp as the scale (exact: at most 2 significant bits times a power of two), and the lane
+// that holds the BM overwrites that one element with 2^e_max * 1.mmm * X (Eq. 2, first case).  Blocks whose results
+// can be subnormal or special (scale byte 0, 1, 255) take the integer path, which does not depend on the float mode.
 template <bool PLUS, bool OUT_BF16>
 __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                          const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld, int dense,
@@ -34,18 +41,59 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restr
     const uint32_t part = (uint32_t)(q & 3);
     const uint32_t sbyte = scales[g];
     const uint32_t bm = PLUS ? (uint32_t)(bm_idx[g] & 31u) : 64u;
-    uint32_t out[8];
+    const bool mine = PLUS && (bm >> 3) == part;       // this lane holds the BM
+    const uint32_t pos = bm & 7u;
+    uint32_t out[8];                                   // fp32 patterns, or (OUT_BF16) 4 packed pairs in out[0..3]
+    if (sbyte >= 2u && sbyte != 255u) {
+      const float X = __uint_as_float(sbyte << 23);
+      const uint32_t nib = (dw >> (4u * pos)) & 15u;
+      const float bmv = __uint_as_float(((nib & 8u) << 28) | __float_as_uint((float)(8u + (nib & 7u)) * (X * 0.5f)));
+      if (OUT_BF16) {
+        union { v2bf v; uint32_t u; } c0, c1, c2, c3;
+        c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 0);
+        c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 1);
+        c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 2);
+        c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 3);
+        out[0] = c0.u; out[1] = c1.u; out[2] = c2.u; out[3] = c3.u;
+        if (mine) {
+          const uint32_t h = __float_as_uint(bmv) >> 16;               // exact: 4 significant bits
+          const uint32_t sh = (pos & 1u) * 16u;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t nib = (dw >> (4 * i)) & 15u;
-      const uint32_t code = nib & 7u;
-      uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;     // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
-      if (PLUS && bm == part * 8u + (uint32_t)i) M = 8u + code;  // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
-      uint32_t bits = (nib >> 3) << 31;
-      if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
-      if (sbyte == 0u) bits = 0u;                            // reserved all-zero code, tested before anything else
-      if (sbyte == 255u) bits = 0x7FC00000u;
-      out[i] = bits;
+          for (int j = 0; j < 4; ++j)
+            if ((pos >> 1) == (uint32_t)j) out[j] = (out[j] & ~(0xFFFFu << sh)) | (h << sh);
+        }
+      } else {
+        const v2f f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 0), f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 1);
+        const v2f f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 2), f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 3);
+        out[0] = __float_as_uint(f0[0]); out[1] = __float_as_uint(f0[1]); out[2] = __float_as_uint(f1[0]); out[3] = __float_as_uint(f1[1]);
+        out[4] = __float_as_uint(f2[0]); out[5] = __float_as_uint(f2[1]); out[6] = __float_as_uint(f3[0]); out[7] = __float_as_uint(f3[1]);
+        if (mine) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (pos == (uint32_t)i) out[i] = __float_as_uint(bmv);
+        }
+      }
+    } else {
+      uint32_t f[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t nib = (dw >> (4 * i)) & 15u;
+        const uint32_t code = nib & 7u;
+        uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;           // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
+        if (mine && pos == (uint32_t)i) M = 8u + code;               // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
+        uint32_t bits = (nib >> 3) << 31;
+        if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
+        if (sbyte == 0u) bits = 0u;                                  // reserved all-zero code, tested before anything else
+        if (sbyte == 255u) bits = 0x7FC00000u;
+        f[i] = bits;
+      }
+      if (OUT_BF16) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = (f[2 * j] >> 16) | (f[2 * j + 1] & 0xFFFF0000u);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = f[i];
+      }
     }
     int64_t off;
     if (dense) {
@@ -55,11 +103,7 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restr
       off = row * ld + (g - row * nbk) * 32 + part * 8;
     }
     if (OUT_BF16) {
-      u32x4 v;
-      v.x = (out[0] >> 16) | (out[1] & 0xFFFF0000u);
-      v.y = (out[2] >> 16) | (out[3] & 0xFFFF0000u);
-      v.z = (out[4] >> 16) | (out[5] & 0xFFFF0000u);
-      v.w = (out[6] >> 16) | (out[7] & 0xFFFF0000u);
+      u32x4 v = {out[0], out[1], out[2], out[3]};
       __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off));
     } else {
       u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
@@ -78,23 +122,26 @@ __device__ __forceinline__ uint32_t widen4(uint32_t h) {
 }
 
 // One thread widens one 32-element block into its 24-byte E2M3 operand and stores it at its lane slot of the tile.
-// A 256-thread group covers 4 consecutive k-tiles of one row tile, so each source row contributes 128 contiguous bytes.
+// A 256-thread group covers 32 rows x 8 consecutive K-blocks (4 k-tiles): thread t takes row t / 8, block t % 8, so the
+// eight lanes of a row read 128 contiguous bytes, and the eight rows of a wavefront that share a tile slot range write
+// 128-byte (low part) and 64-byte (high part) runs.
 template <bool PLUS>
 __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                       const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
                                                       int64_t k_tiles, uint8_t* __restrict__ img_elems,
                                                       uint8_t* __restrict__ img_scales) {
-  const int lane = threadIdx.x & 63;
-  const int64_t kt = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int r_in = threadIdx.x >> 3, kb_in = threadIdx.x & 7;
+  const int64_t kt = (int64_t)blockIdx.x * 4 + (kb_in >> 1);
   const int64_t rt = blockIdx.y;
   if (kt >= k_tiles) return;
-  const int64_t row = rt * kTileRows + (lane & 31);
-  const int64_t kb = kt * 2 + (lane >> 5);
+  const int lane = (kb_in & 1) * 32 + r_in;            // slot of this block in its tile: row % 32, K-block % 2
+  const int64_t row = rt * kTileRows + r_in;
+  const int64_t kb = (int64_t)blockIdx.x * 8 + kb_in;
   uint32_t n[4] = {0, 0, 0, 0};
   uint32_t sbyte = 127u, bm = 64u;
   if (row < rows && kb < nbk) {
     const int64_t b = row * nbk + kb;
-    const u32x4 v = elems[b];
+    const u32x4 v = __builtin_nontemporal_load(elems + b);
     n[0] = v.x; n[1] = v.y; n[2] = v.z; n[3] = v.w;
     sbyte = scales[b];
     if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;

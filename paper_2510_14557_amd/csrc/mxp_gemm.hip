@@ -6,8 +6,8 @@
 // extra MMA (Sec. 5.2, Alg. 1) or with its BM Compute Unit (Sec. 6.2).  The shared E8M0 scales go to the MFMA as is.
 //
 // v_mfma_scale_f32_32x32x64_f8f6f4: lane l supplies the 32 K-consecutive elements (= one MX block, 24 bytes as E2M3)
-// of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is
-// D[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32].
+// of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is element
+// [8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of (first operand) x (second operand)^T.
 #include "mxp_common.h"
 
 namespace mxp {
@@ -27,9 +27,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kFmtE2M3 = 2;  // cbsz / blgp code of the f8f6f4 MFMA for FP6 E2M3 operands
 
+// The B tile goes in as the MFMA's first operand and the A tile as its second, i.e. the instruction forms the
+// transposed 32x32 tile: accumulator register r of lane l is then D[m = l % 32][n = 8 * (r / 4) + 4 * (l / 32) + r % 4],
+// four consecutive columns per register quad, which the epilogue stores as one 16-byte piece.
 template <int OA, int OB>
 __device__ __forceinline__ v16f mfma(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, kFmtE2M3, kFmtE2M3, OA, sa, OB, sb);
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, c, kFmtE2M3, kFmtE2M3, OB, sb, OA, sa);
 }
 
 template <int I, int J>
@@ -81,31 +84,59 @@ __device__ __forceinline__ void mma_all(v16f (&acc)[C::WM][C::WN], const v8i (&a
       }
 }
 
-// Epilogue: for a fixed accumulator register the 32 lanes of a half-wave write 32 consecutive columns of one row.
+// Epilogue.  Lane l holds row m = l % 32 of the tile; register quad g holds columns 8g + 4(l / 32) .. +3.  With an
+// aligned D each quad is one 16-byte (fp32) or 8-byte (bf16) store: 64 stores per wavefront tile instead of 256, which
+// keeps the whole epilogue inside one window of the 6-bit vmcnt counter.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;       // keep NaN a NaN
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;                          // round to nearest even
+}
+
 template <class C, bool OUT_BF16>
 __device__ __forceinline__ void store_tile(const v16f (&acc)[C::WM][C::WN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
                                            int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 4)
+  {  // timing experiment: no output stores (one data-dependent store keeps the accumulators alive)
+    float t = 0.f;
+    for (int i = 0; i < C::WM; ++i) for (int j = 0; j < C::WN; ++j) for (int r = 0; r < 16; ++r) t += acc[i][j][r];
+    if (t == 1.2345e-30f) static_cast<float*>(Dv)[0] = t;
+    return;
+  }
+#endif
 #pragma unroll
-  for (int i = 0; i < C::WM; ++i)
+  for (int i = 0; i < C::WM; ++i) {
+    const int64_t row = (tile_m + i) * 32 + (lane & 31);
 #pragma unroll
     for (int j = 0; j < C::WN; ++j) {
-      const int64_t col = (tile_n + j) * 32 + (lane & 31);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = (tile_m + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < M && col < N) {
-          const float v = acc[i][j][r];
+      for (int g = 0; g < 4; ++g) {
+        const int64_t col = (tile_n + j) * 32 + 8 * g + 4 * (lane >> 5);
+        if (row >= M || col >= N) continue;
+        const float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1], v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
+        if (vec_ok && col + 3 < N) {
           if (OUT_BF16) {
-            uint32_t u = __float_as_uint(v);
-            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x00400000u;       // keep NaN a NaN
-            else u += 0x7FFFu + ((u >> 16) & 1u);                          // round to nearest even
-            static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)(u >> 16);
+            u32x2 o = {f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16), f32_to_bf16_rne(v2) | (f32_to_bf16_rne(v3) << 16)};
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col) = o;
           } else {
-            static_cast<float*>(Dv)[row * ldd + col] = v;
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            f32x4 o = {v0, v1, v2, v3};
+            *reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col) = o;
+          }
+        } else {
+          const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (col + q < N) {
+              if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col + q] = (uint16_t)f32_to_bf16_rne(v[q]);
+              else static_cast<float*>(Dv)[row * ldd + col + q] = v[q];
+            }
           }
         }
       }
     }
+  }
 }
 
 // Source address of 16-byte chunk c of a stage (k-tile kt) -- the stage is a concatenation of contiguous image runs.
@@ -209,6 +240,11 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
   store_tile<C, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
 }
 
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
+__device__ long long mxp_dbg[4 * 4096];
+extern "C" int mxp_debug_read(void* dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(mxp_dbg), sizeof(long long) * 4 * 4096); }
+#endif
+
 // ---- pipelined kernel: S-stage LDS ring filled by direct global->LDS loads ------------------------------------
 // A stage (one k-tile of the workgroup's A and B tiles plus their scale dwords) is a concatenation of contiguous image
 // runs, so it is copied with global_load_lds_dwordx4: every lane fetches 16 bytes and the wavefront's 1 KiB lands
@@ -273,36 +309,58 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
     const int c = tid + u * C::THREADS;
     offB[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
   }
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 8)
+  const uint8_t* const baseA = a_el;   // timing experiment: every workgroup copies the same tiles (all L2 hits)
+  const uint8_t* const baseB = b_el;
+#else
   const uint8_t* const baseA = a_el + tm0 * k_tiles * kTileBytes;
   const uint8_t* const baseB = b_el + tn0 * k_tiles * kTileBytes;
+#endif
   // Scale dwords: the stage holds SA_BYTES/256 groups of A then the groups of B, 256 bytes (64 lanes x 1 dword) each;
   // wavefront w copies group w with one dword-wide copy.  256 bytes further per k-tile.
   constexpr int GA = C::SA_BYTES / 256;
   const uint8_t* const baseS = wave < GA ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256 : b_sc + ((tn0 / 4 + (wave - GA)) * k_tiles) * 256;
   const uint32_t offS = (uint32_t)lane * 4u;
 
-  int issue_kt = 0;     // next stage to copy
-  int issue_slot = 0;   // its ring slot
-  const int last_kt = (int)k_tiles - 1;
-  // Copy number u (0..6) of the stage `issue_kt`.  Past the end the last stage is fetched again into a slot that is
-  // never read, which keeps the number of copies in flight the same in every iteration.
+  // Running copy state; everything here is wavefront-uniform and lives in SGPRs.  pA/pB/pS point at the runs of the
+  // next stage to copy and advance by one tile (one scale group) per k-tile until the last k-tile is reached; past
+  // the end the last stage is fetched again into a slot that is never read, which keeps the number of copies in
+  // flight the same in every iteration.  wslot is the LDS address of this wavefront's first copy in the next slot:
+  // copy u of a stage lands at wslot + 4096 u (element runs, 256 lanes x 16 B per round) and the scale dwords at
+  // wslot + sdelta.
+  static_assert(C::A_BYTES == UA * C::THREADS * 16, "A and B runs are consecutive whole rounds");
+  const uint8_t* pA = baseA;
+  const uint8_t* pB = baseB;
+  const uint8_t* pS = baseS;
+  int left = (int)k_tiles - 1;
+  uint32_t wslot = lds_base + (uint32_t)wave * 1024u;
+  const uint32_t wslot_end = wslot + (uint32_t)S * C::STAGE_BYTES;
+  const uint32_t sdelta = (uint32_t)(C::A_BYTES + C::B_BYTES) + (uint32_t)wave * 256u - (uint32_t)wave * 1024u;
+#define MXP_COPY16(voff, sptr, imm) \
+  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "n"(imm), "v"(voff), "s"(sptr) : "memory", "scc")
   auto copy = [&](int u) {
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 1)
-    if (issue_kt >= S - 2) return;      // timing experiment: no copies inside the main loop
-#endif
-    const int k = issue_kt < last_kt ? issue_kt : last_kt;
-    const uint32_t slot = lds_base + (uint32_t)issue_slot * C::STAGE_BYTES;
-    if (u < UA) {
-      dma16_sv(offA[u], baseA + (int64_t)k * kTileBytes, slot + (uint32_t)(u * C::THREADS + wave * 64) * 16u);
-    } else if (u < UA + UB) {
-      dma16_sv(offB[u - UA], baseB + (int64_t)k * kTileBytes, slot + C::A_BYTES + (uint32_t)((u - UA) * C::THREADS + wave * 64) * 16u);
-    } else {
-      dma4_sv(offS, baseS + (int64_t)k * 256, slot + C::A_BYTES + C::B_BYTES + (uint32_t)wave * 256u);
+    switch (u) {
+      case 0: MXP_COPY16(offA[0], pA, 0); break;
+      case 1: MXP_COPY16(offA[UA > 1 ? 1 : 0], pA, 4096); break;
+      case 2: MXP_COPY16(offA[UA > 2 ? 2 : 0], pA, 8192); break;
+      case 3: MXP_COPY16(offB[0], pB, 12288); break;
+      case 4: MXP_COPY16(offB[UB > 1 ? 1 : 0], pB, 16384); break;
+      case 5: MXP_COPY16(offB[UB > 2 ? 2 : 0], pB, 20480); break;
+      default:
+        asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(wslot), "s"(sdelta), "v"(offS), "s"(pS)
+                     : "memory", "scc");
+        break;
     }
   };
+  static_assert(UA == 3 && UB == 3, "copy slots above");
   auto next_stage = [&]() {
-    ++issue_kt;
-    issue_slot = issue_slot + 1 == S ? 0 : issue_slot + 1;
+    const bool more = left > 0;
+    pA += more ? kTileBytes : 0;
+    pB += more ? kTileBytes : 0;
+    pS += more ? 256 : 0;
+    --left;
+    wslot += C::STAGE_BYTES;
+    if (wslot == wslot_end) wslot -= (uint32_t)S * C::STAGE_BYTES;
   };
 
   v16f acc[C::WM][C::WN];
@@ -323,18 +381,20 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   uint32_t sa0[1], sb0[1], sa1[1], sb1[1];
 
   // Copy accounting (the copies of one wavefront complete in order, PER_STAGE of them per stage).  The prologue issues
-  // stages 0 .. S-3 and needs stage 0: S-3 newer stages may stay in flight.  Iteration kt waits BEFORE it issues stage
-  // kt+S-2, so stages up to kt+S-3 are issued and it needs stage kt+1: S-4 newer stages may stay in flight.
+  // stages 0 .. S-2 and needs stage 0: S-2 newer stages may stay in flight.  Iteration kt waits BEFORE it issues stage
+  // kt+S-1, so stages up to kt+S-2 are issued and it needs stage kt+1: S-3 newer stages may stay in flight.  Stage
+  // kt+S-1 goes to the slot of stage kt-1, whose LDS reads (issued in iteration kt-2) every wavefront has completed
+  // before the barrier of iteration kt-1.
   constexpr int PER_STAGE = UA + UB + 1;
-  constexpr int KEEP_PROLOGUE = (S - 3) * PER_STAGE;
-  constexpr int KEEP = (S - 4) * PER_STAGE;
+  constexpr int KEEP_PROLOGUE = (S - 2) * PER_STAGE;
+  constexpr int KEEP = (S - 3) * PER_STAGE;
   static_assert(KEEP_PROLOGUE <= 63, "vmcnt is a 6-bit counter");
 
-  // prologue: stages 0 .. S-3 in flight, stage 0 landed, fragments of k-tile 0 in registers
+  // prologue: stages 0 .. S-2 in flight, stage 0 landed, fragments of k-tile 0 in registers
 #pragma unroll
-  for (int s = 0; s < S - 2; ++s) {
+  for (int s = 0; s < S - 1; ++s) {
 #pragma unroll
-    for (int u = 0; u < UA + UB + 1; ++u) copy(u);
+    for (int u = 0; u < PER_STAGE; ++u) copy(u);
     next_stage();
   }
   wait_dma_and_barrier<KEEP_PROLOGUE>();
@@ -345,72 +405,100 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   sa0[0] = *reinterpret_cast<const uint32_t*>(lds + sa_off);
   sb0[0] = *reinterpret_cast<const uint32_t*>(lds + sb_off);
 
-  int read_slot = 1;    // ring slot of k-tile kt + 1
+  int read_off = C::STAGE_BYTES;    // byte offset of the ring slot of k-tile kt + 1
 
-  // One k-tile: 16 MFMAs on (ca, cb); between them the reads of the next k-tile into (na, nb) and the copies of a
-  // later stage.
+  // One k-tile: 16 MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can issue
+  // one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap: the
+  // barrier after MFMA 1, the LDS reads of the next k-tile after MFMAs 2..8, one copy after each of MFMAs 9..15.
 #define MXP_MFMA(m) \
   acc[(m) / 4][(m) % 4] = mfma_sel<(m) / 4, (m) % 4>(ca[(m) / 4], cb[(m) % 4], acc[(m) / 4][(m) % 4], (int)csa[0], (int)csb[0]); \
   __builtin_amdgcn_sched_barrier(0)
+#define MXP_GAP() __builtin_amdgcn_sched_barrier(0)
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 1)
+#define MXP_LOOP_COPY(u)            // timing experiment: no copies inside the main loop
+#else
+#define MXP_LOOP_COPY(u) copy(u)
+#endif
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 32)
+#define MXP_LOOP_SYNC() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")   // timing experiment: no copy wait, no barrier
+#else
+#define MXP_LOOP_SYNC() wait_dma_and_barrier<KEEP>()
+#endif
   auto ktile = [&](const v8i (&ca)[4], const v8i (&cb)[4], const uint32_t (&csa)[1], const uint32_t (&csb)[1], v8i (&na)[4],
                    v8i (&nb)[4], uint32_t (&nsa)[1], uint32_t (&nsb)[1]) {
     MXP_MFMA(0);
     MXP_MFMA(1);
-    wait_dma_and_barrier<KEEP>();                     // stage kt + 1 is complete in LDS for every wavefront
-    const uint8_t* st = lds + read_slot * C::STAGE_BYTES;
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_LOOP_SYNC();                                  // stage kt + 1 is complete in LDS for every wavefront
+    const uint8_t* st = lds + read_off;
+    MXP_GAP();
     MXP_MFMA(2);
     na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(3);
     na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(4);
     na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(5);
     na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(6);
     nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(7);
     nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
     MXP_MFMA(8);
     nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    MXP_MFMA(9);
     nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane);
     nsa[0] = *reinterpret_cast<const uint32_t*>(st + sa_off);
     nsb[0] = *reinterpret_cast<const uint32_t*>(st + sb_off);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_GAP();
+    MXP_MFMA(9);
+    MXP_LOOP_COPY(0);
+    MXP_GAP();
     MXP_MFMA(10);
-    copy(0);
-    copy(1);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_LOOP_COPY(1);
+    MXP_GAP();
     MXP_MFMA(11);
-    copy(2);
-    copy(3);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_LOOP_COPY(2);
+    MXP_GAP();
     MXP_MFMA(12);
-    copy(4);
-    copy(5);
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_LOOP_COPY(3);
+    MXP_GAP();
     MXP_MFMA(13);
-    copy(6);
-    next_stage();
-    read_slot = read_slot + 1 == S ? 0 : read_slot + 1;
-    __builtin_amdgcn_sched_barrier(0);
+    MXP_LOOP_COPY(4);
+    MXP_GAP();
     MXP_MFMA(14);
+    MXP_LOOP_COPY(5);
+    MXP_GAP();
     MXP_MFMA(15);
+    MXP_LOOP_COPY(6);
+    next_stage();
+    read_off = read_off + C::STAGE_BYTES == S * C::STAGE_BYTES ? 0 : read_off + C::STAGE_BYTES;
+    MXP_GAP();
   };
 
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
+  const long long dbg_c0 = clock64(), dbg_r0 = wall_clock64();   // timing experiment: shader clock during the main loop
+#endif
   for (int64_t kt = 0; kt < k_tiles; kt += 2) {   // k_tiles is even (K is padded to 128)
     ktile(a0, b0, sa0, sb0, a1, b1, sa1, sb1);
     ktile(a1, b1, sa1, sb1, a0, b0, sa0, sb0);
   }
+#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
+  if (tid == 0) {
+    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
+    mxp_dbg[wg * 4 + 0] = clock64() - dbg_c0;
+    mxp_dbg[wg * 4 + 1] = wall_clock64() - dbg_r0;
+    mxp_dbg[wg * 4 + 2] = dbg_r0;
+    mxp_dbg[wg * 4 + 3] = __builtin_amdgcn_s_getreg((6 << 11) | (0 << 6) | 4) /*HW_ID?*/;
+  }
+#endif
 #undef MXP_MFMA
+#undef MXP_GAP
+#undef MXP_COPY16
   // drain the copies that were issued past the end before the workgroup's LDS is released
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   store_tile<C, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd);

@@ -254,15 +254,10 @@ int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fm
 
 namespace mxp {
 
-// Shared with the on-the-fly GEMM entry point.
-int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
-                    uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
-  const int64_t nbk = K / kBlock;
-  const int64_t nq = rows * nbk * 4;
-  const int dense = (ld_src == K) ? 1 : 0;
-  constexpr int U = 4;
-  int64_t want = (nq + 256 * U - 1) / (256 * U);
-  const int64_t cap = (int64_t)kNumCU * 8;
+template <int U>
+static void quantize_dispatch(const void* src, int src_dtype, int64_t nbk, int64_t ld_src, int dense, int64_t nq, int fmt,
+                              int64_t cap, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
+  const int64_t want = (nq + 256 * U - 1) / (256 * U);
   const int grid = (int)(want < cap ? want : cap);
   uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
   const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
@@ -270,6 +265,20 @@ int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int
   else if (bf) hipLaunchKernelGGL((quantize_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
   else if (plus) hipLaunchKernelGGL((quantize_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
   else hipLaunchKernelGGL((quantize_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+}
+
+// Shared with the on-the-fly GEMM entry point.  Launch shape from measurement: tensors of a few tens of MB finish
+// fastest with 4 independent loads per lane on 8 workgroups per CU; large tensors stream best with 2 loads per lane
+// on 32 workgroups per CU (5.6 TB/s on 470 MB of bf16).
+int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                    uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
+  const int64_t nbk = K / kBlock;
+  const int64_t nq = rows * nbk * 4;
+  const int dense = (ld_src == K) ? 1 : 0;
+  if (nq >= (int64_t)4 << 20)
+    quantize_dispatch<2>(src, src_dtype, nbk, ld_src, dense, nq, fmt, (int64_t)kNumCU * 32, elems, scales, bm_idx, stream);
+  else
+    quantize_dispatch<4>(src, src_dtype, nbk, ld_src, dense, nq, fmt, (int64_t)kNumCU * 8, elems, scales, bm_idx, stream);
   return launch_status();
 }
 
