@@ -93,23 +93,15 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;                          // round to nearest even
 }
 
-template <class C, bool OUT_BF16>
-__device__ __forceinline__ void store_tile(const v16f (&acc)[C::WM][C::WN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
+template <int TWM, int TWN, bool OUT_BF16>
+__device__ __forceinline__ void store_tile(const v16f (&acc)[TWM][TWN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
                                            int64_t N, void* __restrict__ Dv, int64_t ldd) {
   const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 4)
-  {  // timing experiment: no output stores (one data-dependent store keeps the accumulators alive)
-    float t = 0.f;
-    for (int i = 0; i < C::WM; ++i) for (int j = 0; j < C::WN; ++j) for (int r = 0; r < 16; ++r) t += acc[i][j][r];
-    if (t == 1.2345e-30f) static_cast<float*>(Dv)[0] = t;
-    return;
-  }
-#endif
 #pragma unroll
-  for (int i = 0; i < C::WM; ++i) {
+  for (int i = 0; i < TWM; ++i) {
     const int64_t row = (tile_m + i) * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < C::WN; ++j) {
+    for (int j = 0; j < TWN; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int64_t col = (tile_n + j) * 32 + 8 * g + 4 * (lane >> 5);
@@ -237,29 +229,22 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
     __syncthreads();
   }
 
-  store_tile<C, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
+  store_tile<C::WM, C::WN, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
 }
 
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
-__device__ long long mxp_dbg[4 * 4096];
-extern "C" int mxp_debug_read(void* dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(mxp_dbg), sizeof(long long) * 4 * 4096); }
-#endif
-
-// ---- pipelined kernel: S-stage LDS ring filled by direct global->LDS loads ------------------------------------
+// ---- pipelined persistent kernel: S-stage LDS ring filled by direct global->LDS loads ---------------------------
 // A stage (one k-tile of the workgroup's A and B tiles plus their scale dwords) is a concatenation of contiguous image
 // runs, so it is copied with global_load_lds_dwordx4: every lane fetches 16 bytes and the wavefront's 1 KiB lands
-// contiguously in LDS at the address held in M0.  The copies bypass the VGPRs, are issued S-3 k-tiles before their use and are
-// tracked by hand: the compiler does not see them, so each k-tile waits with an explicit vmcnt for the stage it is
-// about to read, then meets the other wavefronts at a barrier.  Operand fragments are double-buffered in registers,
-// and the LDS reads and copy issues of the following k-tiles are placed between the MFMAs of the current one, so
-// that they issue in the shadow of the 8-pass MFMAs instead of ahead of them.
-__device__ __forceinline__ void dma16_sv(uint32_t voff, const uint8_t* sbase, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
-}
-__device__ __forceinline__ void dma4_sv(uint32_t voff, const uint8_t* sbase, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
-}
-
+// contiguously in LDS at the address held in M0.  The copies bypass the VGPRs, are issued S-1 k-tiles before their use
+// and are tracked by hand: the compiler does not see them, so each k-tile waits with an explicit vmcnt for the stage
+// it is about to read, then meets the other wavefronts at a barrier.  Operand fragments are double-buffered in
+// registers, and the LDS reads and copy issues of the following k-tiles are placed between the MFMAs of the current
+// one, so that they issue in the shadow of the 8-pass MFMAs instead of ahead of them.
+//
+// One workgroup per compute unit walks a list of output tiles.  Full tiles are 256 x 256; some tile columns are cut
+// into 256 x 128 half tiles so that (a) every workgroup gets the same amount of work and (b) half of the workgroups
+// start with a half tile and the other half end with one: the two groups then run half a tile out of phase, and the
+// output bursts of one group (64 MiB of fp32 per 256 tiles, HBM-write bound) overlap the MFMA phase of the other.
 template <int N>
 __device__ __forceinline__ void wait_dma_and_barrier() {
   // all but the newest N copies of this wavefront have landed; its own LDS reads are done; then meet the others
@@ -267,59 +252,49 @@ __device__ __forceinline__ void wait_dma_and_barrier() {
 }
 
 __device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 2)
-  return (v8i){lane, 1, 2, 3, 4, 5, 0, 0};   // timing experiment: no LDS operand reads
-#endif
   const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
   const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
   return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
 }
 
-template <class C, int S, bool OUT_BF16>
-__global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
-                                                              const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
-                                                              int64_t k_tiles, int64_t M, int64_t N, void* __restrict__ Dv,
-                                                              int64_t ldd) {
-  static_assert(C::WM == 4 && C::WN == 4, "the MFMA / copy interleave below is written for 4 x 4 tiles per wavefront");
-  constexpr int A_CH = C::A_BYTES / 16, B_CH = C::B_BYTES / 16, SA_CH = C::SA_BYTES / 16, SB_CH = C::SB_BYTES / 16;
-  static_assert(A_CH % C::THREADS == 0 && B_CH % C::THREADS == 0, "element runs split into whole workgroup rounds");
-  static_assert(C::SA_BYTES + C::SB_BYTES == 256 * C::WAVES_M * C::WAVES_N, "each wavefront copies 256 scale bytes per stage");
-  static_assert(C::SA_BYTES % 256 == 0, "scale groups");
-  constexpr int UA = A_CH / C::THREADS, UB = B_CH / C::THREADS;
-  static_assert(UA + UB == 6, "copy slots in the interleave");
-  static_assert(S >= 4, "ring depth");
+// One output tile: rows [32 tm0, 32 tm0 + 256), columns [32 tn0, 32 tn0 + 64 WN).  WN = 4: full tile (each wavefront
+// 4 x 4 MFMA tiles); WN = 2: half tile (4 x 2).  The ring slot layout is the same for both: A tiles at 0, B tiles at
+// A_BYTES (8 or 4 of them), scale groups of A then of B behind.
+template <class C, int S, int WN, bool OUT_BF16>
+__device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                         const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
+                                         int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0) {
+  static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
+  static_assert(WN == 4 || WN == 2, "full or half tile");
   constexpr int TILE_CH = kTileBytes / 16;
+  constexpr int UA = C::A_BYTES / 16 / C::THREADS;                  // 3 whole rounds of 256 lanes x 16 B
+  static_assert(UA == 3 && C::A_BYTES == C::B_BYTES && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
+  constexpr int PER_STAGE = WN == 4 ? 7 : 6;                        // copies per wavefront and stage
+  constexpr int NMFMA = 4 * WN;
 
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
-  const int64_t tm0 = (int64_t)blockIdx.y * C::TM, tn0 = (int64_t)blockIdx.x * C::TN;
+  const int wm = wave >> 1, wn = wave & 1;
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
 
   // Copy sources.  Element runs: scalar base (advanced by one tile per k-tile) + a per-lane 32-bit offset.
-  uint32_t offA[UA], offB[UB];
+  uint32_t offE[UA];   // chunk tid + 256 u of an 8-tile run (the same for A and B)
 #pragma unroll
   for (int u = 0; u < UA; ++u) {
     const int c = tid + u * C::THREADS;
-    offA[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+    offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
   }
-#pragma unroll
-  for (int u = 0; u < UB; ++u) {
-    const int c = tid + u * C::THREADS;
-    offB[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
-  }
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 8)
-  const uint8_t* const baseA = a_el;   // timing experiment: every workgroup copies the same tiles (all L2 hits)
-  const uint8_t* const baseB = b_el;
-#else
-  const uint8_t* const baseA = a_el + tm0 * k_tiles * kTileBytes;
-  const uint8_t* const baseB = b_el + tn0 * k_tiles * kTileBytes;
-#endif
-  // Scale dwords: the stage holds SA_BYTES/256 groups of A then the groups of B, 256 bytes (64 lanes x 1 dword) each;
-  // wavefront w copies group w with one dword-wide copy.  256 bytes further per k-tile.
-  constexpr int GA = C::SA_BYTES / 256;
-  const uint8_t* const baseS = wave < GA ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256 : b_sc + ((tn0 / 4 + (wave - GA)) * k_tiles) * 256;
+  // half tile: the B run has 4 tiles = 384 chunks; its second round is chunks 256..383, fetched by wavefronts 0-1 and
+  // fetched again (same source, same destination) by wavefronts 2-3 so that every wavefront issues the same number of
+  // copies per stage.
+  const int ch = 256 + (tid & 127);
+  const uint32_t offH = (uint32_t)((ch / TILE_CH) * k_tiles * kTileBytes + (ch % TILE_CH) * 16);
+  const uint8_t* pA = a_el + tm0 * k_tiles * kTileBytes;
+  const uint8_t* pB = b_el + tn0 * k_tiles * kTileBytes;
+  // Scale dwords: 256 bytes (64 lanes x 1 dword) per group of 4 row tiles and k-tile.  Wavefronts 0,1 copy A's two
+  // groups, wavefronts 2,3 B's two groups (half tile: both copy B's only group; the second copy lands in an unused place).
+  const uint8_t* pS = wave < 2 ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256
+                               : b_sc + ((tn0 / 4 + (WN == 4 ? wave - 2 : 0)) * k_tiles) * 256;
   const uint32_t offS = (uint32_t)lane * 4u;
 
   // Running copy state; everything here is wavefront-uniform and lives in SGPRs.  pA/pB/pS point at the runs of the
@@ -328,31 +303,25 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   // flight the same in every iteration.  wslot is the LDS address of this wavefront's first copy in the next slot:
   // copy u of a stage lands at wslot + 4096 u (element runs, 256 lanes x 16 B per round) and the scale dwords at
   // wslot + sdelta.
-  static_assert(C::A_BYTES == UA * C::THREADS * 16, "A and B runs are consecutive whole rounds");
-  const uint8_t* pA = baseA;
-  const uint8_t* pB = baseB;
-  const uint8_t* pS = baseS;
   int left = (int)k_tiles - 1;
   uint32_t wslot = lds_base + (uint32_t)wave * 1024u;
   const uint32_t wslot_end = wslot + (uint32_t)S * C::STAGE_BYTES;
   const uint32_t sdelta = (uint32_t)(C::A_BYTES + C::B_BYTES) + (uint32_t)wave * 256u - (uint32_t)wave * 1024u;
+  const uint32_t hdelta = (uint32_t)C::A_BYTES + 4096u - (uint32_t)(wave >> 1) * 2048u;
 #define MXP_COPY16(voff, sptr, imm) \
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "n"(imm), "v"(voff), "s"(sptr) : "memory", "scc")
   auto copy = [&](int u) {
-    switch (u) {
-      case 0: MXP_COPY16(offA[0], pA, 0); break;
-      case 1: MXP_COPY16(offA[UA > 1 ? 1 : 0], pA, 4096); break;
-      case 2: MXP_COPY16(offA[UA > 2 ? 2 : 0], pA, 8192); break;
-      case 3: MXP_COPY16(offB[0], pB, 12288); break;
-      case 4: MXP_COPY16(offB[UB > 1 ? 1 : 0], pB, 16384); break;
-      case 5: MXP_COPY16(offB[UB > 2 ? 2 : 0], pB, 20480); break;
-      default:
-        asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(wslot), "s"(sdelta), "v"(offS), "s"(pS)
-                     : "memory", "scc");
-        break;
-    }
+    if (u == 0) MXP_COPY16(offE[0], pA, 0);
+    else if (u == 1) MXP_COPY16(offE[1], pA, 4096);
+    else if (u == 2) MXP_COPY16(offE[2], pA, 8192);
+    else if (u == 3) MXP_COPY16(offE[0], pB, 12288);
+    else if (u == 4 && WN == 4) MXP_COPY16(offE[1], pB, 16384);
+    else if (u == 5 && WN == 4) MXP_COPY16(offE[2], pB, 20480);
+    else if (u == 4 && WN == 2)
+      asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "s"(hdelta), "v"(offH), "s"(pB) : "memory", "scc");
+    else
+      asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(wslot), "s"(sdelta), "v"(offS), "s"(pS) : "memory", "scc");
   };
-  static_assert(UA == 3 && UB == 3, "copy slots above");
   auto next_stage = [&]() {
     const bool more = left > 0;
     pA += more ? kTileBytes : 0;
@@ -363,145 +332,189 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
     if (wslot == wslot_end) wslot -= (uint32_t)S * C::STAGE_BYTES;
   };
 
-  v16f acc[C::WM][C::WN];
+  v16f acc[4][WN];
 #pragma unroll
-  for (int i = 0; i < C::WM; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < C::WN; ++j)
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const int64_t ta = tm0 + wm * C::WM, tb = tn0 + wn * C::WN;   // multiples of 4: one scale dword covers the 4 tiles
-  const int a_tiles_off = wm * C::WM * kTileBytes;
-  const int b_tiles_off = C::A_BYTES + wn * C::WN * kTileBytes;
+  const int64_t ta = tm0 + wm * 4, tb = tn0 + wn * WN;
+  const int a_tiles_off = wm * 4 * kTileBytes;
+  const int b_tiles_off = C::A_BYTES + wn * WN * kTileBytes;
   const int sa_off = C::A_BYTES + C::B_BYTES + wm * 256 + lane * 4;
-  const int sb_off = C::A_BYTES + C::B_BYTES + C::SA_BYTES + wn * 256 + lane * 4;
+  // full tile: group wn of B, bytes 0..3 = the wavefront's 4 column tiles; half tile: group 0, bytes 2 wn, 2 wn + 1
+  const int sb_off = C::A_BYTES + C::B_BYTES + C::SA_BYTES + (WN == 4 ? wn * 256 : 0) + lane * 4;
+  const int sb_shift = WN == 4 ? 0 : 16 * wn;
 
-  v8i a0[4], b0[4], a1[4], b1[4];
-  uint32_t sa0[1], sb0[1], sa1[1], sb1[1];
+  v8i a0[4], b0[WN], a1[4], b1[WN];
+  uint32_t sa0, sb0, sa1, sb1;
 
   // Copy accounting (the copies of one wavefront complete in order, PER_STAGE of them per stage).  The prologue issues
   // stages 0 .. S-2 and needs stage 0: S-2 newer stages may stay in flight.  Iteration kt waits BEFORE it issues stage
   // kt+S-1, so stages up to kt+S-2 are issued and it needs stage kt+1: S-3 newer stages may stay in flight.  Stage
   // kt+S-1 goes to the slot of stage kt-1, whose LDS reads (issued in iteration kt-2) every wavefront has completed
-  // before the barrier of iteration kt-1.
-  constexpr int PER_STAGE = UA + UB + 1;
+  // before the barrier of iteration kt-1.  Stores of an earlier tile that are still in flight also count in vmcnt;
+  // they can only make a wait longer, never shorter than needed.
   constexpr int KEEP_PROLOGUE = (S - 2) * PER_STAGE;
   constexpr int KEEP = (S - 3) * PER_STAGE;
   static_assert(KEEP_PROLOGUE <= 63, "vmcnt is a 6-bit counter");
 
+  // every wavefront is done with the ring contents of the previous tile
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   // prologue: stages 0 .. S-2 in flight, stage 0 landed, fragments of k-tile 0 in registers
 #pragma unroll
   for (int s = 0; s < S - 1; ++s) {
 #pragma unroll
-    for (int u = 0; u < PER_STAGE; ++u) copy(u);
+    for (int u = 0; u < PER_STAGE; ++u) copy(u == PER_STAGE - 1 ? 6 : u);
     next_stage();
   }
   wait_dma_and_barrier<KEEP_PROLOGUE>();
 #pragma unroll
   for (int i = 0; i < 4; ++i) a0[i] = read_operand(lds + a_tiles_off + i * kTileBytes, lane);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) b0[j] = read_operand(lds + b_tiles_off + j * kTileBytes, lane);
-  sa0[0] = *reinterpret_cast<const uint32_t*>(lds + sa_off);
-  sb0[0] = *reinterpret_cast<const uint32_t*>(lds + sb_off);
+  for (int j = 0; j < WN; ++j) b0[j] = read_operand(lds + b_tiles_off + j * kTileBytes, lane);
+  sa0 = *reinterpret_cast<const uint32_t*>(lds + sa_off);
+  sb0 = *reinterpret_cast<const uint32_t*>(lds + sb_off) >> sb_shift;
 
   int read_off = C::STAGE_BYTES;    // byte offset of the ring slot of k-tile kt + 1
 
-  // One k-tile: 16 MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can issue
-  // one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap: the
-  // barrier after MFMA 1, the LDS reads of the next k-tile after MFMAs 2..8, one copy after each of MFMAs 9..15.
-#define MXP_MFMA(m) \
-  acc[(m) / 4][(m) % 4] = mfma_sel<(m) / 4, (m) % 4>(ca[(m) / 4], cb[(m) % 4], acc[(m) / 4][(m) % 4], (int)csa[0], (int)csb[0]); \
+  // One k-tile: 4 WN MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can
+  // issue one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap:
+  // the barrier after MFMA 1, then the LDS reads of the next k-tile, then the copies of stage kt + S - 1.
+#define MXP_MFMA(m)                                                                                                          \
+  acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
   __builtin_amdgcn_sched_barrier(0)
 #define MXP_GAP() __builtin_amdgcn_sched_barrier(0)
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 1)
-#define MXP_LOOP_COPY(u)            // timing experiment: no copies inside the main loop
-#else
-#define MXP_LOOP_COPY(u) copy(u)
-#endif
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 32)
-#define MXP_LOOP_SYNC() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")   // timing experiment: no copy wait, no barrier
-#else
-#define MXP_LOOP_SYNC() wait_dma_and_barrier<KEEP>()
-#endif
-  auto ktile = [&](const v8i (&ca)[4], const v8i (&cb)[4], const uint32_t (&csa)[1], const uint32_t (&csb)[1], v8i (&na)[4],
-                   v8i (&nb)[4], uint32_t (&nsa)[1], uint32_t (&nsb)[1]) {
+  auto ktile = [&](const v8i (&ca)[4], const v8i (&cb)[WN], const uint32_t csa, const uint32_t csb, v8i (&na)[4],
+                   v8i (&nb)[WN], uint32_t& nsa, uint32_t& nsb) {
     MXP_MFMA(0);
     MXP_MFMA(1);
-    MXP_LOOP_SYNC();                                  // stage kt + 1 is complete in LDS for every wavefront
+    wait_dma_and_barrier<KEEP>();                     // stage kt + 1 is complete in LDS for every wavefront
     const uint8_t* st = lds + read_off;
     MXP_GAP();
-    MXP_MFMA(2);
-    na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(3);
-    na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(4);
-    na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(5);
-    na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(6);
-    nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(7);
-    nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
-    MXP_GAP();
-    MXP_MFMA(8);
-    nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane);
-    nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane);
-    nsa[0] = *reinterpret_cast<const uint32_t*>(st + sa_off);
-    nsb[0] = *reinterpret_cast<const uint32_t*>(st + sb_off);
-    MXP_GAP();
-    MXP_MFMA(9);
-    MXP_LOOP_COPY(0);
-    MXP_GAP();
-    MXP_MFMA(10);
-    MXP_LOOP_COPY(1);
-    MXP_GAP();
-    MXP_MFMA(11);
-    MXP_LOOP_COPY(2);
-    MXP_GAP();
-    MXP_MFMA(12);
-    MXP_LOOP_COPY(3);
-    MXP_GAP();
-    MXP_MFMA(13);
-    MXP_LOOP_COPY(4);
-    MXP_GAP();
-    MXP_MFMA(14);
-    MXP_LOOP_COPY(5);
-    MXP_GAP();
-    MXP_MFMA(15);
-    MXP_LOOP_COPY(6);
+    if constexpr (WN == 4) {
+      MXP_MFMA(2);
+      na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(3);
+      na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(4);
+      na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(5);
+      na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(6);
+      nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(7);
+      nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(8);
+      nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane);
+      nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane);
+      nsa = *reinterpret_cast<const uint32_t*>(st + sa_off);
+      nsb = *reinterpret_cast<const uint32_t*>(st + sb_off);
+      MXP_GAP();
+      MXP_MFMA(9);
+      copy(0);
+      MXP_GAP();
+      MXP_MFMA(10);
+      copy(1);
+      MXP_GAP();
+      MXP_MFMA(11);
+      copy(2);
+      MXP_GAP();
+      MXP_MFMA(12);
+      copy(3);
+      MXP_GAP();
+      MXP_MFMA(13);
+      copy(4);
+      MXP_GAP();
+      MXP_MFMA(14);
+      copy(5);
+      MXP_GAP();
+      MXP_MFMA(15);
+      copy(6);
+    } else {
+      MXP_MFMA(2);
+      na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
+      na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(3);
+      na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
+      na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
+      MXP_GAP();
+      MXP_MFMA(4);
+      nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
+      nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
+      nsa = *reinterpret_cast<const uint32_t*>(st + sa_off);
+      nsb = *reinterpret_cast<const uint32_t*>(st + sb_off) >> sb_shift;
+      MXP_GAP();
+      MXP_MFMA(5);
+      copy(0);
+      copy(1);
+      MXP_GAP();
+      MXP_MFMA(6);
+      copy(2);
+      copy(3);
+      MXP_GAP();
+      MXP_MFMA(7);
+      copy(4);
+      copy(6);
+    }
     next_stage();
     read_off = read_off + C::STAGE_BYTES == S * C::STAGE_BYTES ? 0 : read_off + C::STAGE_BYTES;
     MXP_GAP();
   };
 
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
-  const long long dbg_c0 = clock64(), dbg_r0 = wall_clock64();   // timing experiment: shader clock during the main loop
-#endif
   for (int64_t kt = 0; kt < k_tiles; kt += 2) {   // k_tiles is even (K is padded to 128)
     ktile(a0, b0, sa0, sb0, a1, b1, sa1, sb1);
     ktile(a1, b1, sa1, sb1, a0, b0, sa0, sb0);
   }
-#if defined(MXP_ABLATE) && (MXP_ABLATE & 16)
-  if (tid == 0) {
-    const int wg = blockIdx.y * gridDim.x + blockIdx.x;
-    mxp_dbg[wg * 4 + 0] = clock64() - dbg_c0;
-    mxp_dbg[wg * 4 + 1] = wall_clock64() - dbg_r0;
-    mxp_dbg[wg * 4 + 2] = dbg_r0;
-    mxp_dbg[wg * 4 + 3] = __builtin_amdgcn_s_getreg((6 << 11) | (0 << 6) | 4) /*HW_ID?*/;
-  }
-#endif
 #undef MXP_MFMA
 #undef MXP_GAP
 #undef MXP_COPY16
-  // drain the copies that were issued past the end before the workgroup's LDS is released
+  // the copies issued past the end must have landed before the ring is filled again (or released)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  store_tile<C, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd);
+  store_tile<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd);
+}
+
+// Work list of workgroup c of P: half tiles  {c, c+P, ...} < H  and full tiles {c, c+P, ...} < F.  Workgroups whose
+// bit 3 is clear start with one half tile and do the rest of their half tiles last; the others do all full tiles first.
+template <class C, int S, bool OUT_BF16>
+__global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                              const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                              int64_t k_tiles, int64_t M, int64_t N, void* __restrict__ Dv,
+                                                              int64_t ldd, int gm, int gnf, int nhc) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int c = blockIdx.x, P = gridDim.x;
+  const int F = gm * gnf, H = gm * nhc;
+  const int nf = c < F ? (F - c + P - 1) / P : 0;
+  const int nh = c < H ? (H - c + P - 1) / P : 0;
+  const bool lead_half = ((c >> 3) & 1) == 0 && nh > 0;
+  for (int it = 0; it < nf + nh; ++it) {
+    bool half;
+    int j;
+    if (lead_half) {
+      half = it == 0 || it > nf;
+      j = it == 0 ? 0 : (it <= nf ? it - 1 : it - nf);
+    } else {
+      half = it >= nf;
+      j = half ? it - nf : it;
+    }
+    const int item = c + j * P;
+    if (half) {
+      const int row = item / nhc, col = item - row * nhc;
+      run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)gnf * 8 + col * 4);
+    } else {
+      const int row = item / gnf, col = item - row * gnf;
+      run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)col * 8);
+    }
+  }
 }
 
 template <class C>
@@ -528,13 +541,33 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   return launch_status();
 }
 
+// Tile list for the persistent kernel: gn tile columns of 256, of which the last `hc` are cut into two half columns.
+// With the strided assignment workgroup 0 has the longest list, ceil(F/P) full + ceil(H/P) half tiles; pick the hc with
+// the smallest such makespan and, among equals, the smallest one that gives every workgroup a half tile (H >= P), so
+// that the two phase groups exist; else no half tiles.
 template <class C, int S>
 int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                hipStream_t s) {
   const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
-  const int64_t gm = (M + C::TM * 32 - 1) / (C::TM * 32), gn = (N + C::TN * 32 - 1) / (C::TN * 32);
-  if (gm > 65535 || gn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)gn, (unsigned)gm);
+  const int64_t gm = (M + 255) / 256, gn = (N + 255) / 256;
+  if (gm * gn * 2 > 2000000000LL) return MXP_ERR_UNSUPPORTED;
+  const int64_t total = gm * gn;
+  const int P = (int)(total < kNumCU ? total : kNumCU);
+  int64_t best_hc = 0;
+  double best = 1e300;
+  bool best_phase = false;
+  for (int64_t hc = 0; hc <= gn; ++hc) {
+    const int64_t F = gm * (gn - hc), H = 2 * gm * hc;
+    const double span = (double)((F + P - 1) / P) + 0.5 * (double)((H + P - 1) / P);
+    const bool phase = H >= P && F >= P;
+    if (span < best - 1e-9 || (span < best + 1e-9 && phase && !best_phase)) {
+      best = span;
+      best_hc = hc;
+      best_phase = phase;
+    }
+  }
+  const int gnf = (int)(gn - best_hc), nhc = (int)(2 * best_hc);
+  dim3 grid((unsigned)P);
   constexpr size_t lds = (size_t)S * C::STAGE_BYTES;
   static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KiB of a CDNA4 compute unit");
   if (d_dtype == MXP_BF16) {
@@ -542,13 +575,13 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
     (void)once_b;
     hipLaunchKernelGGL((gemm_kernel_dma<C, S, true>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
-                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd);
+                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);
   } else {
     static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, false>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
     (void)once_f;
     hipLaunchKernelGGL((gemm_kernel_dma<C, S, false>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
-                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd);
+                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);
   }
   return launch_status();
 }
