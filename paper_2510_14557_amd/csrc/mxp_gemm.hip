@@ -131,6 +131,59 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TWM][TWN], int64_t 
   }
 }
 
+// Epilogue through LDS for the large kernel.  Stored straight from the accumulator layout, a store instruction touches
+// 64 different 128-byte lines with 16 bytes each, and the L2 then sees 4096 partial-line writes per wavefront tile.
+// Each 32 x 32 tile is therefore passed through a private 32 x 36-float LDS patch (rows padded by 16 bytes against bank
+// conflicts; LDS operations of one wavefront execute in order, so no wait is needed between the write and the read)
+// and comes back with 8 consecutive lanes holding the 128 contiguous bytes of one row: every store instruction
+// writes 8 full lines.  `patch` is this wavefront's scratch, two patches of kPatchBytes.
+constexpr int kPatchStride = 144;                 // bytes per patch row: 32 floats + 16
+constexpr int kPatchBytes = 32 * kPatchStride;
+
+template <int TWM, int TWN, bool OUT_BF16>
+__device__ __forceinline__ void store_tile_lds(const v16f (&acc)[TWM][TWN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
+                                               int64_t N, void* __restrict__ Dv, int64_t ldd, uint8_t* patch) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
+  const int wr = (lane & 31) * kPatchStride + 16 * (lane >> 5);   // + 32 g
+  const int rd = (lane >> 3) * kPatchStride + (lane & 7) * 16;    // + 8 k rows
+#pragma unroll
+  for (int i = 0; i < TWM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TWN; ++j) {
+      uint8_t* pb = patch + ((i * TWN + j) & 1) * kPatchBytes;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 q = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        *reinterpret_cast<f32x4*>(pb + wr + 32 * g) = q;
+      }
+      const int64_t col = (tile_n + j) * 32 + 4 * (lane & 7);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(pb + rd + 8 * k * kPatchStride);
+        const int64_t row = (tile_m + i) * 32 + 8 * k + (lane >> 3);
+        if (row >= M || col >= N) continue;
+        if (vec_ok && col + 3 < N) {
+          if (OUT_BF16) {
+            u32x2 o = {f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16), f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16)};
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col) = o;
+          } else {
+            *reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col) = v;
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (col + q < N) {
+              if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col + q] = (uint16_t)f32_to_bf16_rne(v[q]);
+              else static_cast<float*>(Dv)[row * ldd + col + q] = v[q];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 // Source address of 16-byte chunk c of a stage (k-tile kt) -- the stage is a concatenation of contiguous image runs.
 template <class C>
 __device__ __forceinline__ const u32x4* stage_src(int c, int64_t kt, int64_t k_tiles, const uint8_t* a_el, const uint8_t* a_sc,
@@ -232,6 +285,14 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
   store_tile<C::WM, C::WN, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
 }
 
+#ifdef MXP_DEBUG_TIMELINE
+__device__ long long mxp_dbg[4 * 8192];   // timing experiment builds only
+extern "C" int mxp_debug_read(void* dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(mxp_dbg), sizeof(mxp_dbg)); }
+#define MXP_DBG_MARK(slot, k) do { if (threadIdx.x == 0) mxp_dbg[(slot) * 4 + (k)] = wall_clock64(); } while (0)
+#else
+#define MXP_DBG_MARK(slot, k) do { } while (0)
+#endif
+
 // ---- pipelined persistent kernel: S-stage LDS ring filled by direct global->LDS loads ---------------------------
 // A stage (one k-tile of the workgroup's A and B tiles plus their scale dwords) is a concatenation of contiguous image
 // runs, so it is copied with global_load_lds_dwordx4: every lane fetches 16 bytes and the wavefront's 1 KiB lands
@@ -263,7 +324,9 @@ __device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
 template <class C, int S, int WN, bool OUT_BF16>
 __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
-                                         int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0) {
+                                         int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0, int dbg_slot) {
+  (void)dbg_slot;
+  MXP_DBG_MARK(dbg_slot, 0);
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
   constexpr int TILE_CH = kTileBytes / 16;
@@ -379,6 +442,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   sb0 = *reinterpret_cast<const uint32_t*>(lds + sb_off) >> sb_shift;
 
   int read_off = C::STAGE_BYTES;    // byte offset of the ring slot of k-tile kt + 1
+  MXP_DBG_MARK(dbg_slot, 1);
 
   // One k-tile: 4 WN MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can
   // issue one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap:
@@ -479,8 +543,11 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 #undef MXP_GAP
 #undef MXP_COPY16
   // the copies issued past the end must have landed before the ring is filled again (or released)
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  store_tile<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd);
+  // (every wavefront's, since the epilogue reuses the ring as scratch)
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  MXP_DBG_MARK(dbg_slot, 2);
+  store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + wave * (2 * kPatchBytes));
+  MXP_DBG_MARK(dbg_slot, 3);
 }
 
 // Work list of workgroup c of P: half tiles  {c, c+P, ...} < H  and full tiles {c, c+P, ...} < F.  Workgroups whose
@@ -509,10 +576,10 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
     const int item = c + j * P;
     if (half) {
       const int row = item / nhc, col = item - row * nhc;
-      run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)gnf * 8 + col * 4);
+      run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)gnf * 8 + col * 4, c * 8 + it);
     } else {
       const int row = item / gnf, col = item - row * gnf;
-      run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)col * 8);
+      run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)col * 8, c * 8 + it);
     }
   }
 }
