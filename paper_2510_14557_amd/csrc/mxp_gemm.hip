@@ -166,9 +166,9 @@ __device__ __forceinline__ void store_tile_lds(const v16f (&acc)[TWM][TWN], int6
         if (vec_ok && col + 3 < N) {
           if (OUT_BF16) {
             u32x2 o = {f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16), f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16)};
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col) = o;
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col));
           } else {
-            *reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col));
           }
         } else {
 #pragma unroll
@@ -659,7 +659,10 @@ int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, 
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
   if (M <= 32) return launch_cfg<Cfg<1, 2, 1, 4>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (M <= 64) return launch_cfg<Cfg<1, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  return launch_dma<Cfg<4, 4, 2, 2>, 6>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+#ifndef MXP_RING
+#define MXP_RING 6   // ring depth; 6 x 25.6 KB = 153.6 KB of the 160 KB LDS
+#endif
+  return launch_dma<Cfg<4, 4, 2, 2>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
 int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {

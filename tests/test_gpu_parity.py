@@ -278,3 +278,32 @@ def test_gemm_full_size_prefill_attn_sampled():
 
 def test_gemm_full_size_prefill_mlp_sampled():
     _sampled_check("prefill_mlp")
+
+
+def test_gemm_full_size_70b_shaped_sampled():
+    _sampled_check("large70b", n_samples=2048)
+
+
+def test_gemm_half_tile_schedule_sampled():
+    """384 tile columns on 256 compute units: the launcher cuts 128 of them into half tiles (two phase groups)."""
+    M, N, K = 200, 98304 - 100, 128
+    a = synth.activations(M, K, config_id=1, tensor_id=5)
+    w = synth.weights(N, K, config_id=1, tensor_id=6)
+    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4P), mxp.quantize(to_dev(w), mxp.MXFP4P)
+    D = mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P)
+    torch.cuda.synchronize()
+    qh, qwh = q_host(qa), q_host(qw)
+    assert all((g == o).all() for g, o in zip(qh, oracle.quantize(a, oracle.MXFP4P)))
+    rng = np.random.default_rng(4)
+    n_s = 20000
+    rm = rng.integers(0, M, n_s)
+    rn = rng.integers(0, N, n_s)
+    rn[:6] = [0, N - 1, 65535, 65536, 65536 + 127, 65536 + 128]      # around the first half-tile column
+    ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, oracle.MXFP4P, rm, rn)
+    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
+    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+    # every column block is written: no stale values left from the fill
+    D2 = torch.full((M, N), float("nan"), device="cuda")
+    mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P, out=D2)
+    assert not torch.isnan(D2).any() and torch.equal(D, D2)
