@@ -31,6 +31,18 @@ WORKLOADS = {
 }
 
 
+def traffic_from_profiles(workload, out_dtype):
+    """HBM-side bytes per GEMM launch, from the committed rocprofv3 --pmc summary (None if there is no matching line)."""
+    path = os.path.join(ROOT, "profiles", "gemm_kernel_dma_%s.md" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH") and ("out=" + out_dtype) in line:
+                return float(line.split("=")[-1].strip())
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(a_bits, w_bits, budget_s=15.0):
     """The CPU oracle on a bounded sample of the same workload: quantize + fp64 GEMM of a row subset."""
     import numpy as np
@@ -46,8 +58,9 @@ def cpu_baseline(a_bits, w_bits, budget_s=15.0):
     oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
     dt = max(time.perf_counter() - t, 1e-4)
     rate = m0 * n0 * K / dt
-    n = min(w_bits.shape[0], 4096)
-    m = int(max(8, min(a_bits.shape[0], budget_s * rate / (n * K))))
+    macs = budget_s * rate
+    n = int(min(w_bits.shape[0], max(2048, macs / (a_bits.shape[0] * K))))
+    m = int(max(8, min(a_bits.shape[0], macs / (n * K))))
     t = time.perf_counter()
     qa = oracle.quantize(a_bits[:m], oracle.MXFP4P)
     qw = oracle.quantize(w_bits[:n], oracle.MXFP4P)
@@ -124,7 +137,7 @@ def main():
         else:
             mxp.dequantize(qa, mxp.MXFP4P, out=back)
 
-    def step(ev=None):
+    def step(ev=None, gemm_ev=None):
         # the same kernels, in the same order, that mxp_quantize + mxp_gemm + mxp_dequantize enqueue
         if ev is not None:
             ev[0].record()
@@ -137,7 +150,11 @@ def main():
         mxp.prepack(qw, mxp.MXFP4P, out=img_w)
         if ev is not None:
             ev[3].record()
+        if gemm_ev is not None:
+            gemm_ev[0].record()
         mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D)
+        if gemm_ev is not None:
+            gemm_ev[1].record()
         if ev is not None:
             ev[4].record()
         mxp.dequantize(qa, mxp.MXFP4P, out=back)
@@ -155,20 +172,41 @@ def main():
         print(json.dumps({"only": args.only, "ms_per_call": (time.perf_counter() - t0) * 1e3 / args.steps,
                           "note": "profiling aid, not a benchmark line"}))
         return
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    # Timed region: K steps; the only instrumentation inside it is one HIP event pair around the GEMM kernel, recorded
+    # on the stream the kernels are launched on (torch's current stream).
+    gemm_events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        step(events[s])
+        step(gemm_ev=gemm_events[s])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    stage_ms = {n: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
+    gemm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in gemm_events]))
+    # Per-stage breakdown from a second, fully instrumented pass (not part of `value`: the extra events add ~15 us/step).
+    n_prof = min(args.steps, 20)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_prof)]
+    for s in range(n_prof):
+        step(ev=events[s])
+    torch.cuda.synchronize()
+    stage_ms = {n: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(n_prof)]))
                 for i, n in enumerate(stages)}
+    # Quantize on a tensor that cannot sit in the 256 MB Infinity Cache: the weight matrix, two copies alternating.
+    Wb = [to_dev(w_bits), to_dev(w_bits)]
+    qbig = mxp.quantize(Wb[0], mxp.MXFP4P)
+    torch.cuda.synchronize()
+    qe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    qe[0].record()
+    for i in range(10):
+        mxp.quantize_into(Wb[i & 1], mxp.MXFP4P, *qbig)
+    qe[1].record()
+    torch.cuda.synchronize()
+    q_large_ms = qe[0].elapsed_time(qe[1]) / 10
+    del Wb, qbig
 
     flops = 2.0 * M * N * K
     value = flops / (ms_per_step * 1e-3) / 1e12
-    gemm_tflops = flops / (stage_ms["gemm"] * 1e-3) / 1e12
+    gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     q_bytes = M * K * 2.5625                                  # bf16 in + nibbles + scale + index
     dq_bytes = M * K * (0.5625 + 2.0)
     pp_bytes = lambda r: r * K * (0.5625 + 0.78125)
@@ -190,11 +228,16 @@ def main():
                    "out_dtype": args.out_dtype,
                    "step": "quantize(A) -> image(A), image(W) -> scaled-MFMA GEMM -> dequantize(A)"},
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_FP4_TFLOPS, "traffic": None, "kernel": "gemm_kernel",
-                     "kernel_ms": stage_ms["gemm"]},
+                     "frac": gemm_tflops / PEAK_FP4_TFLOPS, "traffic": traffic_from_profiles(args.workload, args.out_dtype),
+                     "kernel": "gemm_kernel_dma", "kernel_ms": gemm_ms,
+                     "note": "kernel_ms = HIP event pair around the launch inside the timed steps (includes the dispatch "
+                             "gap); traffic = FETCH_SIZE*2.0 + WRITE_SIZE bytes per launch from profiles/"},
         "stages_ms": stage_ms,
         "quantize_GBps": q_bytes / (stage_ms["quantize"] * 1e-3) / 1e9,
         "quantize_frac_hbm": q_bytes / (stage_ms["quantize"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "quantize_large_GBps": N * K * 2.5625 / (q_large_ms * 1e-3) / 1e9,
+        "quantize_large_frac_hbm": N * K * 2.5625 / (q_large_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "quantize_large_tensor": "W bf16 [%d x %d], two copies alternating, 10 launches" % (N, K),
         "dequantize_GBps": dq_bytes / (stage_ms["dequantize"] * 1e-3) / 1e9,
         "prepack_w_GBps": pp_bytes(N) / (stage_ms["prepack_w"] * 1e-3) / 1e9,
         "gemm_only_TFLOPs": gemm_tflops,
