@@ -9,6 +9,7 @@
 // of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is element
 // [8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of (first operand) x (second operand)^T.
 #include "mxp_common.h"
+#include <type_traits>
 
 namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
@@ -318,62 +319,48 @@ __device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
   return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
 }
 
-// One output tile: rows [32 tm0, 32 tm0 + 256), columns [32 tn0, 32 tn0 + 64 WN).  WN = 4: full tile (each wavefront
-// 4 x 4 MFMA tiles); WN = 2: half tile (4 x 2).  The ring slot layout is the same for both: A tiles at 0, B tiles at
-// A_BYTES (8 or 4 of them), scale groups of A then of B behind.
-template <class C, int S, int WN, bool OUT_BF16>
-__device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
-                                         const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
-                                         int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0, int dbg_slot) {
-  (void)dbg_slot;
-  MXP_DBG_MARK(dbg_slot, 0);
-  static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
-  static_assert(WN == 4 || WN == 2, "full or half tile");
-  constexpr int TILE_CH = kTileBytes / 16;
-  constexpr int UA = C::A_BYTES / 16 / C::THREADS;                  // 3 whole rounds of 256 lanes x 16 B
-  static_assert(UA == 3 && C::A_BYTES == C::B_BYTES && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
-  constexpr int PER_STAGE = WN == 4 ? 7 : 6;                        // copies per wavefront and stage
-  constexpr int NMFMA = 4 * WN;
+// Copy engine state of one wavefront for one output tile: rows [32 tm0, +256), columns [32 tn0, +64 WN).  WN = 4: full
+// tile (each wavefront 4 x 4 MFMA tiles, 8 B tiles per stage); WN = 2: half tile (4 x 2, 4 B tiles per stage).  The
+// ring slot layout is the same for both: A tiles at 0, B tiles at A_BYTES, scale groups of A then of B behind.
+// Everything except the per-lane offsets is wavefront-uniform and lives in SGPRs.  pA/pB/pS point at the runs of the
+// next stage to copy and advance by one tile (one scale group) per k-tile; wslot is the LDS address of this
+// wavefront's first copy in the next slot: copy u of a stage lands at wslot + 4096 u (element runs, 256 lanes x 16 B
+// per round) and the scale dwords at wslot + sdelta.
+template <class C, int S, int WN>
+struct Copier {
+  static constexpr int PER_STAGE = WN == 4 ? 7 : 6;   // copies per wavefront and stage
+  uint32_t offE[3], offH, offS;
+  const uint8_t *pA, *pB, *pS;
+  uint32_t wslot, wslot_end, sdelta, hdelta;
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
-
-  // Copy sources.  Element runs: scalar base (advanced by one tile per k-tile) + a per-lane 32-bit offset.
-  uint32_t offE[UA];   // chunk tid + 256 u of an 8-tile run (the same for A and B)
+  __device__ __forceinline__ void init(uint32_t lds_base, const uint8_t* a_el, const uint8_t* a_sc, const uint8_t* b_el,
+                                       const uint8_t* b_sc, int64_t k_tiles, int64_t tm0, int64_t tn0, int tid, int wave) {
+    constexpr int TILE_CH = kTileBytes / 16;
 #pragma unroll
-  for (int u = 0; u < UA; ++u) {
-    const int c = tid + u * C::THREADS;
-    offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+    for (int u = 0; u < 3; ++u) {   // chunk tid + 256 u of an 8-tile run (the same for A and B)
+      const int c = tid + u * C::THREADS;
+      offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+    }
+    // half tile: the B run has 4 tiles = 384 chunks; its second round is chunks 256..383, fetched by wavefronts 0-1
+    // and fetched again (same source, same destination) by wavefronts 2-3 so that every wavefront issues the same
+    // number of copies per stage.
+    const int ch = 256 + (tid & 127);
+    offH = (uint32_t)((ch / TILE_CH) * k_tiles * kTileBytes + (ch % TILE_CH) * 16);
+    offS = (uint32_t)(tid & 63) * 4u;
+    pA = a_el + tm0 * k_tiles * kTileBytes;
+    pB = b_el + tn0 * k_tiles * kTileBytes;
+    // Scale dwords: 256 bytes (64 lanes x 1 dword) per group of 4 row tiles and k-tile.  Wavefronts 0,1 copy A's two
+    // groups, wavefronts 2,3 B's two groups (half tile: both copy B's only group; the second lands in an unused place).
+    pS = wave < 2 ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256 : b_sc + ((tn0 / 4 + (WN == 4 ? wave - 2 : 0)) * k_tiles) * 256;
+    wslot = lds_base + (uint32_t)wave * 1024u;
+    wslot_end = wslot + (uint32_t)S * C::STAGE_BYTES;
+    sdelta = (uint32_t)(C::A_BYTES + C::B_BYTES) + (uint32_t)wave * 256u - (uint32_t)wave * 1024u;
+    hdelta = (uint32_t)C::A_BYTES + 4096u - (uint32_t)(wave >> 1) * 2048u;
   }
-  // half tile: the B run has 4 tiles = 384 chunks; its second round is chunks 256..383, fetched by wavefronts 0-1 and
-  // fetched again (same source, same destination) by wavefronts 2-3 so that every wavefront issues the same number of
-  // copies per stage.
-  const int ch = 256 + (tid & 127);
-  const uint32_t offH = (uint32_t)((ch / TILE_CH) * k_tiles * kTileBytes + (ch % TILE_CH) * 16);
-  const uint8_t* pA = a_el + tm0 * k_tiles * kTileBytes;
-  const uint8_t* pB = b_el + tn0 * k_tiles * kTileBytes;
-  // Scale dwords: 256 bytes (64 lanes x 1 dword) per group of 4 row tiles and k-tile.  Wavefronts 0,1 copy A's two
-  // groups, wavefronts 2,3 B's two groups (half tile: both copy B's only group; the second copy lands in an unused place).
-  const uint8_t* pS = wave < 2 ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256
-                               : b_sc + ((tn0 / 4 + (WN == 4 ? wave - 2 : 0)) * k_tiles) * 256;
-  const uint32_t offS = (uint32_t)lane * 4u;
-
-  // Running copy state; everything here is wavefront-uniform and lives in SGPRs.  pA/pB/pS point at the runs of the
-  // next stage to copy and advance by one tile (one scale group) per k-tile until the last k-tile is reached; past
-  // the end the last stage is fetched again into a slot that is never read, which keeps the number of copies in
-  // flight the same in every iteration.  wslot is the LDS address of this wavefront's first copy in the next slot:
-  // copy u of a stage lands at wslot + 4096 u (element runs, 256 lanes x 16 B per round) and the scale dwords at
-  // wslot + sdelta.
-  int left = (int)k_tiles - 1;
-  uint32_t wslot = lds_base + (uint32_t)wave * 1024u;
-  const uint32_t wslot_end = wslot + (uint32_t)S * C::STAGE_BYTES;
-  const uint32_t sdelta = (uint32_t)(C::A_BYTES + C::B_BYTES) + (uint32_t)wave * 256u - (uint32_t)wave * 1024u;
-  const uint32_t hdelta = (uint32_t)C::A_BYTES + 4096u - (uint32_t)(wave >> 1) * 2048u;
 #define MXP_COPY16(voff, sptr, imm) \
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "n"(imm), "v"(voff), "s"(sptr) : "memory", "scc")
-  auto copy = [&](int u) {
+  // copy number u of the next stage; u = 6 is always the scale copy
+  __device__ __forceinline__ void copy(int u) const {
     if (u == 0) MXP_COPY16(offE[0], pA, 0);
     else if (u == 1) MXP_COPY16(offE[1], pA, 4096);
     else if (u == 2) MXP_COPY16(offE[2], pA, 8192);
@@ -382,18 +369,67 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
     else if (u == 5 && WN == 4) MXP_COPY16(offE[2], pB, 20480);
     else if (u == 4 && WN == 2)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "s"(hdelta), "v"(offH), "s"(pB) : "memory", "scc");
-    else
+    else if (u == 6)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(wslot), "s"(sdelta), "v"(offS), "s"(pS) : "memory", "scc");
-  };
-  auto next_stage = [&]() {
-    const bool more = left > 0;
-    pA += more ? kTileBytes : 0;
-    pB += more ? kTileBytes : 0;
-    pS += more ? 256 : 0;
-    --left;
+  }
+#undef MXP_COPY16
+  __device__ __forceinline__ void next_stage() {
+    pA += kTileBytes;
+    pB += kTileBytes;
+    pS += 256;
     wslot += C::STAGE_BYTES;
     if (wslot == wslot_end) wslot -= (uint32_t)S * C::STAGE_BYTES;
-  };
+  }
+  __device__ __forceinline__ void issue_stage() {
+#pragma unroll
+    for (int u = 0; u < 7; ++u)
+      if (u != 5 || WN == 4) copy(u);
+    next_stage();
+  }
+  // same state change as `n` issue_stage() calls, without the copies (they were issued ahead of time)
+  __device__ __forceinline__ void skip_stages(int n) {
+    pA += (int64_t)n * kTileBytes;
+    pB += (int64_t)n * kTileBytes;
+    pS += (int64_t)n * 256;
+    wslot += (uint32_t)n * C::STAGE_BYTES;   // n < S and the ring starts at slot 0 for every tile
+  }
+};
+
+// Stages 0 .. S-2 of a tile (its prologue), issued either at kernel start or while the previous tile is being stored.
+template <class C, int S, int WN>
+__device__ __forceinline__ void issue_prologue(uint8_t* lds, const uint8_t* a_el, const uint8_t* a_sc, const uint8_t* b_el,
+                                               const uint8_t* b_sc, int64_t k_tiles, int64_t tm0, int64_t tn0) {
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  Copier<C, S, WN> cp;
+  cp.init((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0, tid, wave);
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s) cp.issue_stage();
+}
+
+// One output tile whose prologue copies are already in flight.  Requires k_tiles >= S + 2 (and even).  `next_kind`
+// (0 none, 2 half, 4 full) and its coordinates: the prologue of the following tile is issued before this tile's
+// epilogue, so that those copies land while the output is being stored.
+template <class C, int S, int WN, bool OUT_BF16>
+__device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                         const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
+                                         int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0,
+                                         int next_kind, int64_t ntm0, int64_t ntn0, int dbg_slot) {
+  (void)dbg_slot;
+  MXP_DBG_MARK(dbg_slot, 0);
+  static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
+  static_assert(WN == 4 || WN == 2, "full or half tile");
+  static_assert(S == 4, "the peeled tail below is written for a 4-slot ring");
+  static_assert(C::A_BYTES == 3 * C::THREADS * 16 && C::A_BYTES == C::B_BYTES && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
+  using CP = Copier<C, S, WN>;
+  constexpr int PER_STAGE = CP::PER_STAGE;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  CP cp;
+  cp.init((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0, tid, wave);
+  cp.skip_stages(S - 1);
 
   v16f acc[4][WN];
 #pragma unroll
@@ -414,25 +450,17 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   v8i a0[4], b0[WN], a1[4], b1[WN];
   uint32_t sa0, sb0, sa1, sb1;
 
-  // Copy accounting (the copies of one wavefront complete in order, PER_STAGE of them per stage).  The prologue issues
-  // stages 0 .. S-2 and needs stage 0: S-2 newer stages may stay in flight.  Iteration kt waits BEFORE it issues stage
-  // kt+S-1, so stages up to kt+S-2 are issued and it needs stage kt+1: S-3 newer stages may stay in flight.  Stage
-  // kt+S-1 goes to the slot of stage kt-1, whose LDS reads (issued in iteration kt-2) every wavefront has completed
-  // before the barrier of iteration kt-1.  Stores of an earlier tile that are still in flight also count in vmcnt;
-  // they can only make a wait longer, never shorter than needed.
+  // Copy accounting.  The copies of one wavefront complete in order, PER_STAGE of them per stage; stores of the
+  // previous tile that are still in flight also count in vmcnt, but loads complete in order among themselves, so
+  // "at most n operations outstanding" always implies "at most n copies outstanding": a wait can only be longer than
+  // needed, never shorter.  The prologue issued stages 0 .. S-2 and stage 0 is needed: S-2 newer stages may stay in
+  // flight.  Iteration kt waits BEFORE it issues stage kt+S-1, so stages up to kt+S-2 are issued and it needs stage
+  // kt+1: S-3 newer stages may stay in flight.  Stage kt+S-1 goes to the slot of stage kt-1, whose LDS reads (issued
+  // in iteration kt-2) every wavefront has completed before the barrier of iteration kt-1.  The last S-1 iterations
+  // issue nothing and wait for correspondingly fewer stages.
   constexpr int KEEP_PROLOGUE = (S - 2) * PER_STAGE;
   constexpr int KEEP = (S - 3) * PER_STAGE;
-  static_assert(KEEP_PROLOGUE <= 63, "vmcnt is a 6-bit counter");
 
-  // every wavefront is done with the ring contents of the previous tile
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  // prologue: stages 0 .. S-2 in flight, stage 0 landed, fragments of k-tile 0 in registers
-#pragma unroll
-  for (int s = 0; s < S - 1; ++s) {
-#pragma unroll
-    for (int u = 0; u < PER_STAGE; ++u) copy(u == PER_STAGE - 1 ? 6 : u);
-    next_stage();
-  }
   wait_dma_and_barrier<KEEP_PROLOGUE>();
 #pragma unroll
   for (int i = 0; i < 4; ++i) a0[i] = read_operand(lds + a_tiles_off + i * kTileBytes, lane);
@@ -447,106 +475,126 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // One k-tile: 4 WN MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can
   // issue one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap:
   // the barrier after MFMA 1, then the LDS reads of the next k-tile, then the copies of stage kt + S - 1.
+  // COPY: this iteration issues a stage.  KEEPN: copies that may stay in flight at its wait.  NEXT: there is a next
+  // k-tile to wait for and read.
 #define MXP_MFMA(m)                                                                                                          \
   acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
   __builtin_amdgcn_sched_barrier(0)
 #define MXP_GAP() __builtin_amdgcn_sched_barrier(0)
-  auto ktile = [&](const v8i (&ca)[4], const v8i (&cb)[WN], const uint32_t csa, const uint32_t csb, v8i (&na)[4],
-                   v8i (&nb)[WN], uint32_t& nsa, uint32_t& nsb) {
+#define MXP_READ(stmt) do { if (NEXT) { stmt; } } while (0)
+#define MXP_CP(u) do { if (COPY) cp.copy(u); } while (0)
+  auto ktile = [&](auto copy_tag, auto keep_tag, auto next_tag, const v8i (&ca)[4], const v8i (&cb)[WN], const uint32_t csa,
+                   const uint32_t csb, v8i (&na)[4], v8i (&nb)[WN], uint32_t& nsa, uint32_t& nsb) {
+    constexpr bool COPY = decltype(copy_tag)::value;
+    constexpr int KEEPN = decltype(keep_tag)::value;
+    constexpr bool NEXT = decltype(next_tag)::value;
     MXP_MFMA(0);
     MXP_MFMA(1);
-    wait_dma_and_barrier<KEEP>();                     // stage kt + 1 is complete in LDS for every wavefront
+    if (NEXT) wait_dma_and_barrier<KEEPN>();           // stage kt + 1 is complete in LDS for every wavefront
     const uint8_t* st = lds + read_off;
     MXP_GAP();
     if constexpr (WN == 4) {
       MXP_MFMA(2);
-      na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
+      MXP_READ(na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(3);
-      na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
+      MXP_READ(na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(4);
-      na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
+      MXP_READ(na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(5);
-      na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
+      MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(6);
-      nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
+      MXP_READ(nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(7);
-      nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
+      MXP_READ(nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(8);
-      nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane);
-      nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane);
-      nsa = *reinterpret_cast<const uint32_t*>(st + sa_off);
-      nsb = *reinterpret_cast<const uint32_t*>(st + sb_off);
+      MXP_READ(nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane));
+      MXP_READ(nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane));
+      MXP_READ(nsa = *reinterpret_cast<const uint32_t*>(st + sa_off));
+      MXP_READ(nsb = *reinterpret_cast<const uint32_t*>(st + sb_off));
       MXP_GAP();
       MXP_MFMA(9);
-      copy(0);
+      MXP_CP(0);
       MXP_GAP();
       MXP_MFMA(10);
-      copy(1);
+      MXP_CP(1);
       MXP_GAP();
       MXP_MFMA(11);
-      copy(2);
+      MXP_CP(2);
       MXP_GAP();
       MXP_MFMA(12);
-      copy(3);
+      MXP_CP(3);
       MXP_GAP();
       MXP_MFMA(13);
-      copy(4);
+      MXP_CP(4);
       MXP_GAP();
       MXP_MFMA(14);
-      copy(5);
+      MXP_CP(5);
       MXP_GAP();
       MXP_MFMA(15);
-      copy(6);
+      MXP_CP(6);
     } else {
       MXP_MFMA(2);
-      na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane);
-      na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane);
+      MXP_READ(na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane));
+      MXP_READ(na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(3);
-      na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane);
-      na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane);
+      MXP_READ(na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane));
+      MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(4);
-      nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane);
-      nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane);
-      nsa = *reinterpret_cast<const uint32_t*>(st + sa_off);
-      nsb = *reinterpret_cast<const uint32_t*>(st + sb_off) >> sb_shift;
+      MXP_READ(nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane));
+      MXP_READ(nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane));
+      MXP_READ(nsa = *reinterpret_cast<const uint32_t*>(st + sa_off));
+      MXP_READ(nsb = *reinterpret_cast<const uint32_t*>(st + sb_off) >> sb_shift);
       MXP_GAP();
       MXP_MFMA(5);
-      copy(0);
-      copy(1);
+      MXP_CP(0);
+      MXP_CP(1);
       MXP_GAP();
       MXP_MFMA(6);
-      copy(2);
-      copy(3);
+      MXP_CP(2);
+      MXP_CP(3);
       MXP_GAP();
       MXP_MFMA(7);
-      copy(4);
-      copy(6);
+      MXP_CP(4);
+      MXP_CP(6);
     }
-    next_stage();
+    if (COPY) cp.next_stage();
     read_off = read_off + C::STAGE_BYTES == S * C::STAGE_BYTES ? 0 : read_off + C::STAGE_BYTES;
     MXP_GAP();
   };
+  using T = std::true_type;
+  using F = std::false_type;
+  using K1 = std::integral_constant<int, KEEP>;
+  using K0 = std::integral_constant<int, 0>;
 
-  for (int64_t kt = 0; kt < k_tiles; kt += 2) {   // k_tiles is even (K is padded to 128)
-    ktile(a0, b0, sa0, sb0, a1, b1, sa1, sb1);
-    ktile(a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+  // steady state: iterations 0 .. k_tiles-5 (an even number of them)
+  for (int64_t kt = 0; kt < k_tiles - S; kt += 2) {
+    ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+    ktile(T{}, K1{}, T{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
   }
+  // tail (S = 4): k_tiles-4 issues the last stage; k_tiles-3 and k_tiles-2 issue nothing and may leave 1 and 0 stages
+  // in flight; k_tiles-1 has no successor
+  ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+  ktile(F{}, K1{}, T{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+  ktile(F{}, K0{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+  ktile(F{}, K0{}, F{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
 #undef MXP_MFMA
 #undef MXP_GAP
-#undef MXP_COPY16
-  // the copies issued past the end must have landed before the ring is filled again (or released)
-  // (every wavefront's, since the epilogue reuses the ring as scratch)
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#undef MXP_READ
+#undef MXP_CP
+  // every wavefront has read its last fragments: the ring may be refilled
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   MXP_DBG_MARK(dbg_slot, 2);
-  store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + wave * (2 * kPatchBytes));
+  store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + S * C::STAGE_BYTES + wave * (2 * kPatchBytes));
+  if (next_kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
+  else if (next_kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
   MXP_DBG_MARK(dbg_slot, 3);
 }
 
@@ -563,7 +611,9 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   const int nf = c < F ? (F - c + P - 1) / P : 0;
   const int nh = c < H ? (H - c + P - 1) / P : 0;
   const bool lead_half = ((c >> 3) & 1) == 0 && nh > 0;
-  for (int it = 0; it < nf + nh; ++it) {
+  // item `it` of this workgroup: kind (2 half, 4 full) and tile origin in units of 32 rows / columns
+  auto item = [&](int it, int& kind, int64_t& tm0, int64_t& tn0) {
+    if (it >= nf + nh) { kind = 0; tm0 = tn0 = 0; return; }
     bool half;
     int j;
     if (lead_half) {
@@ -573,14 +623,25 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
       half = it >= nf;
       j = half ? it - nf : it;
     }
-    const int item = c + j * P;
+    const int idx = c + j * P;
     if (half) {
-      const int row = item / nhc, col = item - row * nhc;
-      run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)gnf * 8 + col * 4, c * 8 + it);
+      const int row = idx / nhc, col = idx - row * nhc;
+      kind = 2; tm0 = (int64_t)row * 8; tn0 = (int64_t)gnf * 8 + col * 4;
     } else {
-      const int row = item / gnf, col = item - row * gnf;
-      run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, (int64_t)row * 8, (int64_t)col * 8, c * 8 + it);
+      const int row = idx / gnf, col = idx - row * gnf;
+      kind = 4; tm0 = (int64_t)row * 8; tn0 = (int64_t)col * 8;
     }
+  };
+  int kind, nkind;
+  int64_t tm0, tn0, ntm0, ntn0;
+  item(0, kind, tm0, tn0);
+  if (kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
+  else if (kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
+  for (int it = 0; kind != 0; ++it) {
+    item(it + 1, nkind, ntm0, ntn0);
+    if (kind == 2) run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0, c * 8 + it);
+    else run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0, c * 8 + it);
+    kind = nkind; tm0 = ntm0; tn0 = ntn0;
   }
 }
 
@@ -635,7 +696,7 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   }
   const int gnf = (int)(gn - best_hc), nhc = (int)(2 * best_hc);
   dim3 grid((unsigned)P);
-  constexpr size_t lds = (size_t)S * C::STAGE_BYTES;
+  constexpr size_t lds = (size_t)S * C::STAGE_BYTES + 4 * 2 * kPatchBytes;   // ring + one pair of epilogue patches per wavefront
   static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KiB of a CDNA4 compute unit");
   if (d_dtype == MXP_BF16) {
     static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, true>),
@@ -660,8 +721,10 @@ int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, 
   if (M <= 32) return launch_cfg<Cfg<1, 2, 1, 4>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (M <= 64) return launch_cfg<Cfg<1, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 #ifndef MXP_RING
-#define MXP_RING 6   // ring depth; 6 x 25.6 KB = 153.6 KB of the 160 KB LDS
+#define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
 #endif
+  // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail)
+  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return launch_dma<Cfg<4, 4, 2, 2>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 

@@ -286,7 +286,7 @@ def test_gemm_full_size_70b_shaped_sampled():
 
 def test_gemm_half_tile_schedule_sampled():
     """384 tile columns on 256 compute units: the launcher cuts 128 of them into half tiles (two phase groups)."""
-    M, N, K = 200, 98304 - 100, 128
+    M, N, K = 200, 98304 - 100, 256
     a = synth.activations(M, K, config_id=1, tensor_id=5)
     w = synth.weights(N, K, config_id=1, tensor_id=6)
     qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4P), mxp.quantize(to_dev(w), mxp.MXFP4P)
