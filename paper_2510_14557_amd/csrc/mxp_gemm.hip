@@ -680,7 +680,7 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   const int64_t gm = (M + 255) / 256, gn = (N + 255) / 256;
   if (gm * gn * 2 > 2000000000LL) return MXP_ERR_UNSUPPORTED;
   const int64_t total = gm * gn;
-  const int P = (int)(total < kNumCU ? total : kNumCU);
+  const int P = (int)(2 * total < kNumCU ? 2 * total : kNumCU);   // workgroups: one per CU, fewer only if even half tiles run out
   int64_t best_hc = 0;
   double best = 1e300;
   bool best_phase = false;
@@ -714,12 +714,101 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   return launch_status();
 }
 
+// ---- skinny-M kernel (decode: M <= 64) --------------------------------------------------------------------------
+// With a handful of activation rows the product is bound by reading the weight image once (Sec. 7.2: the decode stage
+// is memory-bound), so the aim is to have every byte of it requested at once.  A workgroup owns one 32-column tile
+// of B and splits K over its 8 wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
+// operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the one or two row tiles
+// of A likewise (A is tiny and stays in cache), runs the MFMAs, and the 8 partial tiles are summed through LDS.
+template <int TMR, bool OUT_BF16>
+__global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                          int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  constexpr int WAVES = 8, CHUNK = 4;                       // k-tiles whose loads are in flight together per wavefront
+  __shared__ __attribute__((aligned(16))) float part[WAVES][TMR][16][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t ct = blockIdx.x;                            // column tile of B (32 columns)
+  const uint8_t* bt = b_el + ct * (int64_t)k_tiles * kTileBytes;
+  const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
+  const int b_shift = (int)(ct & 3) * 8;
+  v16f acc[TMR];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+
+  for (int k0 = wave * CHUNK; k0 < k_tiles; k0 += WAVES * CHUNK) {
+    v8i b[CHUNK], a[CHUNK][TMR];
+    uint32_t sb[CHUNK], sa[CHUNK];
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      const int kt = k0 + c < k_tiles ? k0 + c : k_tiles - 1;     // clamped: the surplus is not used
+      const uint8_t* t = bt + (int64_t)kt * kTileBytes;
+      const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + lane * 16));
+      const u32x2 hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
+      b[c] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      sb[c] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
+      sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
+#pragma unroll
+      for (int i = 0; i < TMR; ++i) {
+        const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * kTileBytes;
+        const u32x4 alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
+        const u32x2 ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      if (k0 + c < k_tiles) {
+        acc[0] = mfma<0, 0>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
+        if (TMR > 1) acc[TMR - 1] = mfma<1, 0>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][i][r][lane] = acc[i][r];
+  __syncthreads();
+  // 8 wavefronts x 64 lanes sum the TMR x 16 x 64 accumulator slots; slot (i, r, l) is D[32 i + (l % 32)][32 ct + 8 (r / 4) + 4 (l / 32) + r % 4]
+  for (int e = tid; e < TMR * 16 * 64; e += 512) {
+    const int l = e & 63, r = (e >> 6) & 15, i = e >> 10;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += part[w][i][r][l];
+    const int64_t row = 32 * i + (l & 31);
+    const int64_t col = 32 * ct + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    if (row < M && col < N) {
+      if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne(v);
+      else static_cast<float*>(Dv)[row * ldd + col] = v;
+    }
+  }
+}
+
+int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                  hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const int64_t ct = (N + 31) / 32;
+  if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)ct);
+  const int kt = (int)ga.k_tiles;
+  const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
+  if (M <= 32) {
+    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<1, true>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<1, false>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+  } else {
+    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<2, true>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, false>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+  }
+  return launch_status();
+}
+
 int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                 hipStream_t s) {
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
-  if (M <= 32) return launch_cfg<Cfg<1, 2, 1, 4>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  if (M <= 64) return launch_cfg<Cfg<1, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (M <= 64) return launch_skinny(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 #ifndef MXP_RING
 #define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
 #endif

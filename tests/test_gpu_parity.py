@@ -203,7 +203,8 @@ def test_gemm_single_block_hand_cases():
 
 
 @pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (16, 256, 256), (33, 100, 96), (100, 200, 416), (257, 300, 1024),
-                                   (300, 520, 2048)])
+                                   (300, 520, 2048), (1, 33, 64), (32, 64, 1088), (50, 130, 2368), (64, 1000, 4160),
+                                   (65, 40, 2368), (512, 1100, 640)])
 def test_gemm_shapes(M, N, K):
     a = synth.activations(M, K, config_id=1, tensor_id=0)
     w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
