@@ -598,8 +598,24 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   MXP_DBG_MARK(dbg_slot, 3);
 }
 
-// Work list of workgroup c of P: half tiles  {c, c+P, ...} < H  and full tiles {c, c+P, ...} < F.  Workgroups whose
-// bit 3 is clear start with one half tile and do the rest of their half tiles last; the others do all full tiles first.
+// Work lists.  The hardware deals workgroups round-robin to the 8 XCDs (workgroup c runs on XCD c % 8), each with its
+// own L2.  Full tiles and half tiles are each put in band order (bands of kBand tile columns, row-major inside a band)
+// and cut into one contiguous run per XCD, sized by the XCD's share of the workgroups; local workgroup j = c / 8 of an
+// XCD with Px workgroups takes positions jj, jj + Px, ... of the run.  Workgroups with even j start with one half tile
+// and do their other half tiles last; those with odd j do all their full tiles first: two phase groups whose output
+// bursts do not coincide.  With 32 workgroups per XCD, jj = j / 2 + 16 (j % 2), so that each phase group of an XCD
+// works on 16 consecutive positions = a 4 x 4 block of tiles sharing 4 A panels and 4 B panels through the XCD's L2.
+constexpr int kBand = 4;
+
+__device__ __forceinline__ void band_decode(int p, int rows, int cols, int& r, int& c) {
+  const int per_band = kBand * rows;
+  const int band = p / per_band, q = p - band * per_band;
+  const int c0 = band * kBand;
+  const int w = cols - c0 < kBand ? cols - c0 : kBand;
+  r = q / w;
+  c = c0 + (q - r * w);
+}
+
 template <class C, int S, bool OUT_BF16>
 __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                               const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
@@ -608,27 +624,34 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int c = blockIdx.x, P = gridDim.x;
   const int F = gm * gnf, H = gm * nhc;
-  const int nf = c < F ? (F - c + P - 1) / P : 0;
-  const int nh = c < H ? (H - c + P - 1) / P : 0;
-  const bool lead_half = ((c >> 3) & 1) == 0 && nh > 0;
+  const int x = c & 7, j = c >> 3;
+  const int base = P >> 3, rem = P & 7;
+  const int Px = base + (x < rem ? 1 : 0);                        // workgroups on this XCD
+  const int cum0 = x * base + (x < rem ? x : rem), cum1 = cum0 + Px;
+  const int f_begin = (int)((int64_t)F * cum0 / P), f_count = (int)((int64_t)F * cum1 / P) - f_begin;
+  const int h_begin = (int)((int64_t)H * cum0 / P), h_count = (int)((int64_t)H * cum1 / P) - h_begin;
+  const int jj = Px == 32 ? (j >> 1) + 16 * (j & 1) : j;
+  const int nf = jj < f_count ? (f_count - jj + Px - 1) / Px : 0;
+  const int nh = jj < h_count ? (h_count - jj + Px - 1) / Px : 0;
+  const bool lead_half = (j & 1) == 0 && nh > 0;
   // item `it` of this workgroup: kind (2 half, 4 full) and tile origin in units of 32 rows / columns
   auto item = [&](int it, int& kind, int64_t& tm0, int64_t& tn0) {
     if (it >= nf + nh) { kind = 0; tm0 = tn0 = 0; return; }
     bool half;
-    int j;
+    int t;
     if (lead_half) {
       half = it == 0 || it > nf;
-      j = it == 0 ? 0 : (it <= nf ? it - 1 : it - nf);
+      t = it == 0 ? 0 : (it <= nf ? it - 1 : it - nf);
     } else {
       half = it >= nf;
-      j = half ? it - nf : it;
+      t = half ? it - nf : it;
     }
-    const int idx = c + j * P;
+    int row, col;
     if (half) {
-      const int row = idx / nhc, col = idx - row * nhc;
+      band_decode(h_begin + jj + t * Px, gm, nhc, row, col);
       kind = 2; tm0 = (int64_t)row * 8; tn0 = (int64_t)gnf * 8 + col * 4;
     } else {
-      const int row = idx / gnf, col = idx - row * gnf;
+      band_decode(f_begin + jj + t * Px, gm, gnf, row, col);
       kind = 4; tm0 = (int64_t)row * 8; tn0 = (int64_t)col * 8;
     }
   };
@@ -670,7 +693,7 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 }
 
 // Tile list for the persistent kernel: gn tile columns of 256, of which the last `hc` are cut into two half columns.
-// With the strided assignment workgroup 0 has the longest list, ceil(F/P) full + ceil(H/P) half tiles; pick the hc with
+// The longest per-workgroup list has ceil(F/P) full + ceil(H/P) half tiles; pick the hc with
 // the smallest such makespan and, among equals, the smallest one that gives every workgroup a half tile (H >= P), so
 // that the two phase groups exist; else no half tiles.
 template <class C, int S>
