@@ -80,6 +80,13 @@ size_t mxp_image_bytes(int64_t rows, int64_t K);
 int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt,
                 int64_t rows, int64_t K, void* image, size_t image_bytes, void* stream);
 
+/* Conversion (Sec. 4.1, 4.2) written directly as an image: same source arguments and the same encoding as
+ * mxp_quantize, but the result goes to `image` (mxp_image_bytes(rows, K) bytes, bit-identical to mxp_prepack of the
+ * canonical result) without a pass over the canonical bytes.  If elems / scales / bm_idx are given (all of them, bm_idx
+ * only for MXFP4+) the canonical arrays are written as well; pass three null pointers to skip them. */
+int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                       uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes, void* stream);
+
 /* D[M][N] = A[M][K] x B^T, B given as [N][K] (K-contiguous, the way a linear layer stores W); both operands in
  * canonical storage, formats chosen per operand (Sec. 5: activations MXFP4+ with weights MXFP4 or MXFP4+).
  * The result is the matrix product of the de-converted operands accumulated in fp32 (Sec. 5.1).

@@ -14,8 +14,8 @@
 namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream);
-int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
-                    uint8_t* scales, uint8_t* bm_idx, hipStream_t stream);
+int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream);
 }  // namespace mxp
 
 namespace {
@@ -911,8 +911,7 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
 
 extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
   if (M < 0 || K < 0) return 0;
-  const size_t nb = (size_t)(M * (K / mxp::kBlock));
-  return align_up((size_t)mxp::image_geom(M, K).total()) + align_up(nb * 16) + 2 * align_up(nb);
+  return align_up((size_t)mxp::image_geom(M, K).total());
 }
 
 extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
@@ -930,14 +929,8 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   if (!aligned16(A) || !aligned16(B_image) || !aligned16(workspace) || (lda * (a_dtype == MXP_BF16 ? 2 : 4)) % 16 != 0)
     return MXP_ERR_ALIGN;
   if (workspace_bytes < mxp_gemm_bf16a_workspace_bytes(M, K)) return MXP_ERR_WORKSPACE;
-  const size_t nb = (size_t)(M * (K / kBlock));
   uint8_t* img = static_cast<uint8_t*>(workspace);
-  uint8_t* el = img + align_up((size_t)image_geom(M, K).total());
-  uint8_t* sc = el + align_up(nb * 16);
-  uint8_t* ix = sc + align_up(nb);
-  rc = quantize_launch(A, a_dtype, M, K, lda, fmtA, el, sc, ix, s);
-  if (rc != MXP_OK) return rc;
-  rc = prepack_launch(el, sc, ix, fmtA, M, K, img, s);
+  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
   if (rc != MXP_OK) return rc;
   return gemm_images(img, B_image, M, N, K, D, d_dtype, ldd, s);
 }

@@ -186,6 +186,82 @@ __global__ void __launch_bounds__(256) quantize_kernel(const void* __restrict__ 
   }
 }
 
+// Dense source (row stride = K): the tensor is one run of nq 8-element groups.  A workgroup walks chunks of 256 * U
+// groups (U x 4 KiB of bf16, contiguous); lane t of the workgroup takes groups u * 256 + t of the chunk, so every
+// load, every element store and every scale / index dword store of a wavefront is one contiguous run.  Whole chunks
+// run without per-lane bounds tests; the last, partial chunk takes the checked path.
+template <bool BF16, bool PLUS, int U>
+__global__ void __launch_bounds__(256) quantize_dense_kernel(const void* __restrict__ src, int64_t nq, uint32_t* __restrict__ elems,
+                                                             uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx) {
+  const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
+  constexpr int64_t kChunk = 256 * U;
+  const int64_t n_chunks = (nq + kChunk - 1) / kChunk;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t q_base = c * kChunk;                               // uniform
+    const bool whole = q_base + kChunk <= nq;
+    uint32_t w[U][8];
+    if (BF16) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(src) + q_base;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        u32x4 v = {0, 0, 0, 0};
+        if (whole || q_base + u * 256 + t < nq) v = __builtin_nontemporal_load(p + u * 256 + t);
+        w[u][0] = v.x; w[u][1] = v.y; w[u][2] = v.z; w[u][3] = v.w;
+        w[u][4] = w[u][5] = w[u][6] = w[u][7] = 0;
+      }
+    } else {
+      const u32x4* p = reinterpret_cast<const u32x4*>(src) + 2 * q_base;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        u32x4 v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+        if (whole || q_base + u * 256 + t < nq) {
+          v0 = __builtin_nontemporal_load(p + 2 * (u * 256 + t));
+          v1 = __builtin_nontemporal_load(p + 2 * (u * 256 + t) + 1);
+        }
+        w[u][0] = v0.x; w[u][1] = v0.y; w[u][2] = v0.z; w[u][3] = v0.w;
+        w[u][4] = v1.x; w[u][5] = v1.y; w[u][6] = v1.z; w[u][7] = v1.w;
+      }
+    }
+    uint32_t* e_out = elems + q_base;
+    uint8_t* s_out = scales + (q_base >> 2);
+    uint8_t* i_out = bm_idx + (q_base >> 2);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      uint32_t sbyte, idx;
+      const uint32_t packed = encode_group<BF16, PLUS>(w[u], (int)part, sbyte, idx);
+      // gather the four blocks of this 16-lane row into its lane 12
+      uint32_t sv = (part == 0) ? (sbyte << (8 * quad_in_row)) : 0u;
+      sv |= dpp_mov<kRowShr8>(sv);
+      sv |= dpp_mov<kRowShr4>(sv);
+      uint32_t iv = 0;
+      if (PLUS) {
+        iv = (part == 0) ? (idx << (8 * quad_in_row)) : 0u;
+        iv |= dpp_mov<kRowShr8>(iv);
+        iv |= dpp_mov<kRowShr4>(iv);
+      }
+      const uint32_t ql = u * 256 + t;                               // group within the chunk
+      if (whole) {
+        __builtin_nontemporal_store(packed, e_out + ql);
+        if ((t & 15u) == 12u) {
+          *reinterpret_cast<uint32_t*>(s_out + (ql >> 2) - 3) = sv;
+          if (PLUS) *reinterpret_cast<uint32_t*>(i_out + (ql >> 2) - 3) = iv;
+        }
+      } else if (q_base + ql < nq) {
+        __builtin_nontemporal_store(packed, e_out + ql);
+        if (q_base + (ql | 15u) < nq) {                              // the row's four blocks all exist
+          if ((t & 15u) == 12u) {
+            *reinterpret_cast<uint32_t*>(s_out + (ql >> 2) - 3) = sv;
+            if (PLUS) *reinterpret_cast<uint32_t*>(i_out + (ql >> 2) - 3) = iv;
+          }
+        } else if (part == 0) {
+          s_out[ql >> 2] = (uint8_t)sbyte;
+          if (PLUS) i_out[ql >> 2] = (uint8_t)idx;
+        }
+      }
+    }
+  }
+}
+
 // ---- K-strided source: one thread per block, 32 strided loads that are coalesced across the rows of a wavefront.
 template <bool BF16, bool PLUS>
 __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
@@ -239,6 +315,120 @@ __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict_
   if (PLUS) bm_idx[b] = (uint8_t)idx;
 }
 
+// ---- quantize straight into the MFMA-ready image (optionally also the canonical arrays) -------------------------
+// The GEMM consumes E2M3 tiles, so for an operand that is only multiplied (activations, Sec. 7.2) the canonical
+// bytes need not make a round trip through HBM.  A workgroup takes 32 rows x 4 k-tiles (8 blocks per row): in each of
+// its 4 passes a wavefront reads two 512-byte row segments, encodes them exactly as quantize_kernel does, widens the
+// eight 4-bit codes of a lane to 48 bits of E2M3 (code << 2; the BM becomes sign | 11 | mmm, Sec. 4.2), and drops
+// them at the block's slot of its tile in LDS.  The four finished tiles are contiguous in the image (6 KiB) and leave
+// with full-width stores.  Padding rows / blocks are zero elements with a unit scale, as the prepack kernel writes.
+__device__ __forceinline__ uint32_t widen4(uint32_t h) {   // 4 nibbles -> 4 six-bit codes, code = nibble << 2
+  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
+  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
+}
+
+template <bool BF16, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                             int64_t k_tiles, uint32_t* __restrict__ elems,
+                                                             uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
+                                                             uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
+  const int64_t rt = blockIdx.y, kt0 = (int64_t)blockIdx.x * 4;
+  const bool canon = elems != nullptr;
+  // pass u covers rows 8u .. 8u+7 of the row tile; this lane: row 8u + r0, K-block kb_in (the same in every pass)
+  const uint32_t r0 = t >> 5, kb_in = (t >> 2) & 7u;
+  const int64_t row0 = rt * kTileRows + r0, kb = kt0 * 2 + kb_in;
+  const bool whole = rt * kTileRows + kTileRows <= rows && kt0 * 2 + 8 <= nbk;   // uniform: no lane of the workgroup is padding
+  const bool kb_ok = kb < nbk;
+  const int64_t off0 = row0 * ld + kb * 32 + part * 8, off_step = 8 * ld;         // source element offsets
+  uint32_t w[4][8];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    if (whole || (kb_ok && row0 + 8 * u < rows)) {
+      const int64_t off = off0 + u * off_step;
+      if (BF16) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off));
+        w[u][0] = v.x; w[u][1] = v.y; w[u][2] = v.z; w[u][3] = v.w;
+        w[u][4] = w[u][5] = w[u][6] = w[u][7] = 0;
+      } else {
+        const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+        const u32x4 v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+        w[u][0] = v0.x; w[u][1] = v0.y; w[u][2] = v0.z; w[u][3] = v0.w;
+        w[u][4] = v1.x; w[u][5] = v1.y; w[u][6] = v1.z; w[u][7] = v1.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[u][i] = 0;
+    }
+  }
+  // LDS destinations.  Bytes [6 part, 6 part + 6) of the block's 24: the first 16 bytes of a block sit in the low run
+  // of its tile (16 B per slot), the last 8 in the high run (8 B per slot); slot = 32 (K-block % 2) + row.
+  const uint32_t slot0 = (kb_in & 1u) * 32u + r0;
+  const uint32_t lo0 = (kb_in >> 1) * kTileBytes + slot0 * 16u, hi0 = (kb_in >> 1) * kTileBytes + 1024u + slot0 * 8u;
+  const uint32_t a32 = part == 0 ? lo0 : part == 1 ? lo0 + 8u : part == 2 ? lo0 + 12u : hi0 + 4u;
+  const uint32_t a16 = part == 0 ? lo0 + 4u : part == 1 ? lo0 + 6u : part == 2 ? hi0 : hi0 + 2u;
+  const uint32_t s32 = part == 3 ? 64u : 128u, s16 = part >= 2 ? 64u : 128u;      // 8 slots further per pass
+  const bool odd = (part & 1u) != 0;
+  const int64_t g0 = row0 * nbk + kb, g_step = 8 * nbk;
+  const bool dword_meta = (nbk & 3) == 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const bool valid = whole || (kb_ok && row0 + 8 * u < rows);
+    uint32_t sbyte, idx;
+    const uint32_t packed = encode_group<BF16, PLUS>(w[u], (int)part, sbyte, idx);
+    if (canon) {
+      const int64_t g = g0 + u * g_step;
+      if (valid) __builtin_nontemporal_store(packed, elems + g * 4 + part);
+      if (dword_meta) {
+        // the four blocks of a 16-lane row are consecutive blocks of one matrix row: one dword of scales, one of indices
+        uint32_t sv = (part == 0) ? (sbyte << (8 * quad_in_row)) : 0u;
+        sv |= dpp_mov<kRowShr8>(sv);
+        sv |= dpp_mov<kRowShr4>(sv);
+        uint32_t iv = 0;
+        if (PLUS) {
+          iv = (part == 0) ? (idx << (8 * quad_in_row)) : 0u;
+          iv |= dpp_mov<kRowShr8>(iv);
+          iv |= dpp_mov<kRowShr4>(iv);
+        }
+        if (valid && (t & 15u) == 12u) {
+          *reinterpret_cast<uint32_t*>(scales + g - 3) = sv;
+          if (PLUS) *reinterpret_cast<uint32_t*>(bm_idx + g - 3) = iv;
+        }
+      } else if (valid && part == 0) {
+        scales[g] = (uint8_t)sbyte;
+        if (PLUS) bm_idx[g] = (uint8_t)idx;
+      }
+    }
+    // 48 bits of E2M3 codes for this lane's eight elements
+    uint32_t c0 = widen4(packed & 0xFFFFu), c1 = widen4(packed >> 16);           // 24 bits each
+    if (PLUS) {
+      const uint32_t pos = idx & 7u;
+      const uint32_t nib = (packed >> (4u * pos)) & 15u;
+      const uint32_t code = ((nib & 8u) << 2) | 0x18u | (nib & 7u);
+      const bool mine = sbyte != 0u && sbyte != 255u && (idx >> 3) == part;
+      const uint32_t sh = 6u * (pos & 3u);
+      const uint32_t patched0 = (c0 & ~(0x3Fu << sh)) | (code << sh), patched1 = (c1 & ~(0x3Fu << sh)) | (code << sh);
+      c0 = (mine && pos < 4u) ? patched0 : c0;
+      c1 = (mine && pos >= 4u) ? patched1 : c1;
+    }
+    const uint32_t low32 = c0 | (c1 << 24), high16 = c1 >> 8;                     // bits [0,32) and [32,48)
+    const uint32_t v32 = odd ? (low32 >> 16) | (high16 << 16) : low32;
+    const uint32_t v16 = odd ? low32 & 0xFFFFu : high16;
+    *reinterpret_cast<uint32_t*>(tiles + a32 + u * s32) = v32;
+    *reinterpret_cast<uint16_t*>(tiles + a16 + u * s16) = (uint16_t)v16;
+    if (part == 0) tile_scales[(kb_in >> 1) * 64u + slot0 + 8u * u] = valid ? (uint8_t)sbyte : (uint8_t)127;
+  }
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;          // tiles of this workgroup that exist
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
+  const uint32_t nbytes = (uint32_t)nt * kTileBytes;
+  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
 int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fmt, const uint8_t* elems,
                  const uint8_t* scales, const uint8_t* bm_idx) {
   if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
@@ -261,6 +451,13 @@ static void quantize_dispatch(const void* src, int src_dtype, int64_t nbk, int64
   const int grid = (int)(want < cap ? want : cap);
   uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
   const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
+  if (dense) {
+    if (bf && plus) hipLaunchKernelGGL((quantize_dense_kernel<true, true, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
+    else if (bf) hipLaunchKernelGGL((quantize_dense_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
+    else if (plus) hipLaunchKernelGGL((quantize_dense_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
+    else hipLaunchKernelGGL((quantize_dense_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
+    return;
+  }
   if (bf && plus) hipLaunchKernelGGL((quantize_kernel<true, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
   else if (bf) hipLaunchKernelGGL((quantize_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
   else if (plus) hipLaunchKernelGGL((quantize_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
@@ -282,7 +479,45 @@ int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int
   return launch_status();
 }
 
+// Also used by the GEMM entry point that takes unquantized activations.  Canonical pointers may all be null.
+int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream) {
+  const ImageGeom g = image_geom(rows, K);
+  if (g.row_tiles > 65535) return MXP_ERR_UNSUPPORTED;
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  dim3 grid((unsigned)((g.k_tiles + 3) / 4), (unsigned)g.row_tiles);
+  uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
+  const int64_t nbk = K / kBlock;
+  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
+  if (bf && plus) hipLaunchKernelGGL((quantize_image_kernel<true, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+  else if (bf) hipLaunchKernelGGL((quantize_image_kernel<true, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+  else if (plus) hipLaunchKernelGGL((quantize_image_kernel<false, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+  else hipLaunchKernelGGL((quantize_image_kernel<false, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+  return launch_status();
+}
+
 }  // namespace mxp
+
+extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
+                                  uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes,
+                                  void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!src || !image) return MXP_ERR_NULL;
+  const bool canon = elems || scales || bm_idx;
+  if (canon && (!elems || !scales || (fmt == MXP_FMT_MXFP4P && !bm_idx))) return MXP_ERR_NULL;
+  if (ld_src < K) return MXP_ERR_SHAPE;
+  const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
+  if (!aligned16(src) || !aligned16(image) || (ld_src * esz) % 16 != 0) return MXP_ERR_ALIGN;
+  if (canon && (!aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx)))) return MXP_ERR_ALIGN;
+  if (image_bytes < (size_t)image_geom(rows, K).total()) return MXP_ERR_WORKSPACE;
+  return quantize_image_launch(src, src_dtype, rows, K, ld_src, fmt, canon ? elems : nullptr, scales, bm_idx, image,
+                               static_cast<hipStream_t>(stream));
+}
 
 extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                             uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream) {

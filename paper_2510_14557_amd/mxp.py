@@ -17,7 +17,7 @@ MXFP4, MXFP4P = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
-EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack",
+EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
            "mxp_gemm_bf16a", "mxp_status_string", "mxp_version")
 
@@ -44,6 +44,7 @@ def lib():
     L.mxp_image_bytes.argtypes = [i64, i64]
     L.mxp_image_bytes.restype = sz
     L.mxp_prepack.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
+    L.mxp_quantize_image.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp, sz, vp]
     L.mxp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     L.mxp_gemm_workspace_bytes.restype = sz
     L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
@@ -54,7 +55,7 @@ def lib():
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
-    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_gemm", "mxp_gemm_prepacked",
+    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_gemm", "mxp_gemm_prepacked",
               "mxp_gemm_bf16a"):
         getattr(L, n).restype = i32
     _lib = L
@@ -153,6 +154,25 @@ def prepack(q, fmt: int = MXFP4P, out: torch.Tensor | None = None):
         out = torch.empty(n, dtype=torch.uint8, device=elems.device)
     _check(lib().mxp_prepack(_p(elems), _p(scales), _p(idx), fmt, rows, K, _p(out), out.numel(), _stream()), "mxp_prepack")
     return out
+
+
+def quantize_image(x: torch.Tensor, fmt: int = MXFP4P, canonical: bool = False, out=None, q_out=None):
+    """x [rows, K] fp32/bf16 -> MFMA-ready image; with canonical=True also (elems, scales, bm_idx), from the same pass."""
+    _dev2d(x)
+    rows, K = x.shape
+    ld = x.stride(0) if rows > 1 else max(K, 1)
+    if out is None:
+        out = torch.empty(image_bytes(rows, K), dtype=torch.uint8, device=x.device)
+    q = (None, None, None)
+    if q_out is not None:
+        q = q_out
+    elif canonical:
+        q = (torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device),
+             torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device),
+             torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device))
+    _check(lib().mxp_quantize_image(_p(x), _dt(x), rows, K, ld, fmt, _p(q[0]), _p(q[1]), _p(q[2]), _p(out), out.numel(),
+                                    _stream()), "mxp_quantize_image")
+    return (out, q) if (canonical or q_out is not None) else out
 
 
 def gemm_workspace_bytes(M: int, N: int, K: int) -> int:

@@ -107,6 +107,34 @@ def test_quantize_strided_rows_and_empty():
     assert e.numel() == 0
 
 
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_image_matches_quantize_then_prepack(fmt, bf16):
+    """The one-pass conversion writes the canonical bytes the oracle gives and the image the two-pass route gives."""
+    cases = [special_tensor(bf16=bf16), special_tensor(rows=70, K=224, seed=5, bf16=bf16),
+             synth.activations(300, 4096, config_id=2, tensor_id=3, dtype="bf16" if bf16 else "f32"),
+             synth.activations(40, 4096 + 64, config_id=2, tensor_id=5, dtype="bf16" if bf16 else "f32"),
+             synth.activations(1, 32, config_id=2, tensor_id=4, dtype="bf16" if bf16 else "f32")]
+    for x in cases:
+        d = to_dev(x)
+        img, q = mxp.quantize_image(d, FMT[fmt][0], canonical=True)
+        assert_q_equal(q, oracle.quantize(x, FMT[fmt][1]), fmt, "one-pass canonical %s" % (x.shape,))
+        want = mxp.prepack(q_dev(oracle.quantize(x, FMT[fmt][1])), FMT[fmt][0])
+        assert torch.equal(img, want), "image differs for %s" % (x.shape,)
+        only = torch.full_like(img, 0xA5)
+        mxp.quantize_image(d, FMT[fmt][0], out=only)                      # no canonical outputs
+        assert torch.equal(only, want)
+
+
+def test_quantize_image_strided_rows():
+    x = special_tensor(rows=19, K=192, bf16=True)
+    big = torch.zeros((19, 256), dtype=torch.bfloat16, device="cuda")
+    big[:, :192] = to_dev(x)
+    img, q = mxp.quantize_image(big[:, :192], mxp.MXFP4P, canonical=True)
+    assert_q_equal(q, oracle.quantize(x, oracle.MXFP4P), "mxfp4p", "strided one-pass")
+    assert torch.equal(img, mxp.prepack(q, mxp.MXFP4P))
+
+
 def test_quantize_exhaustive_bf16_patterns():
     pats = np.arange(1 << 16, dtype=np.uint16)
     # every pattern as an ordinary element next to a fixed BM, for several scales, and as the BM of its own block
