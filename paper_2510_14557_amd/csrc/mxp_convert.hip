@@ -121,22 +121,24 @@ __device__ __forceinline__ uint32_t widen4(uint32_t h) {
   return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
 }
 
-// One thread widens one 32-element block into its 24-byte E2M3 operand and stores it at its lane slot of the tile.
-// A 256-thread group covers 32 rows x 8 consecutive K-blocks (4 k-tiles): thread t takes row t / 8, block t % 8, so the
-// eight lanes of a row read 128 contiguous bytes, and the eight rows of a wavefront that share a tile slot range write
-// 128-byte (low part) and 64-byte (high part) runs.
+// One thread widens one 32-element block into its 24-byte E2M3 operand.  A 256-thread group covers 32 rows x 8
+// consecutive K-blocks (4 k-tiles): thread t takes row t / 8, block t % 8, so the eight lanes of a row read 128
+// contiguous bytes.  The finished blocks are dropped at their lane slots of the four tiles in LDS; the tiles are
+// neighbours in the image (6 KiB), which then leaves the workgroup in full 16-byte-per-lane stores.
 template <bool PLUS>
 __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                       const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
                                                       int64_t k_tiles, uint8_t* __restrict__ img_elems,
                                                       uint8_t* __restrict__ img_scales) {
-  const int r_in = threadIdx.x >> 3, kb_in = threadIdx.x & 7;
-  const int64_t kt = (int64_t)blockIdx.x * 4 + (kb_in >> 1);
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const int64_t kt0 = (int64_t)blockIdx.x * 4;
   const int64_t rt = blockIdx.y;
-  if (kt >= k_tiles) return;
-  const int lane = (kb_in & 1) * 32 + r_in;            // slot of this block in its tile: row % 32, K-block % 2
+  const uint32_t slot = (kb_in & 1u) * 32u + r_in;     // slot of this block in its tile: row % 32, K-block % 2
   const int64_t row = rt * kTileRows + r_in;
-  const int64_t kb = (int64_t)blockIdx.x * 8 + kb_in;
+  const int64_t kb = kt0 * 2 + kb_in;
   uint32_t n[4] = {0, 0, 0, 0};
   uint32_t sbyte = 127u, bm = 64u;
   if (row < rows && kb < nbk) {
@@ -147,25 +149,23 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
     if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
     if (sbyte == 0u) n[0] = n[1] = n[2] = n[3] = 0u;          // flushed block: zero whatever the nibbles say
   }
-  uint32_t bm_code = 0;
-  if (PLUS && bm < 32u) {
-    // take the BM nibble out of the stream; its code is sign | 11 | mmm  (E2M3 at exponent e_max, Sec. 4.2)
-    const uint32_t sh = (bm & 7u) * 4u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if ((bm >> 3) == (uint32_t)j) {
-        const uint32_t nib = (n[j] >> sh) & 15u;
-        bm_code = ((nib & 8u) << 2) | 0x18u | (nib & 7u);
-        n[j] &= ~(0xFu << sh);
-      }
-    }
-  }
   // 8 pieces of 24 bits -> 6 dwords
   uint32_t r[8];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     r[2 * j] = widen4(n[j] & 0xFFFFu);
     r[2 * j + 1] = widen4(n[j] >> 16);
+  }
+  if (PLUS && bm < 32u) {
+    // the BM's code is sign | 11 | mmm  (E2M3 at exponent e_max, Sec. 4.2) instead of nibble << 2
+    const uint32_t piece = bm >> 2, sh = (bm & 3u) * 6u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t c = (r[j] >> sh) & 0x3Fu;                 // s mmm 00
+      const uint32_t code = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);
+      const uint32_t patched = (r[j] & ~(0x3Fu << sh)) | (code << sh);
+      r[j] = piece == (uint32_t)j ? patched : r[j];
+    }
   }
   uint32_t d[6];
   d[0] = r[0] | (r[1] << 24);
@@ -174,23 +174,19 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
   d[3] = r[4] | (r[5] << 24);
   d[4] = (r[5] >> 8) | (r[6] << 16);
   d[5] = (r[6] >> 16) | (r[7] << 8);
-  if (PLUS && bm < 32u) {
-    const uint32_t pos = bm * 6u;
-    const uint32_t w = pos >> 5, off = pos & 31u;
-    const uint64_t v = (uint64_t)bm_code << off;
-    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-#pragma unroll
-    for (int j = 0; j < 6; ++j) {
-      if (w == (uint32_t)j) d[j] |= lo;
-      if (w + 1u == (uint32_t)j) d[j] |= hi;
-    }
-  }
-  uint8_t* tile = img_elems + (rt * k_tiles + kt) * (int64_t)kTileBytes;
+  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytes;
   u32x4 lo4 = {d[0], d[1], d[2], d[3]};
   u32x2 hi2 = {d[4], d[5]};
-  *reinterpret_cast<u32x4*>(tile + lane * 16) = lo4;
-  *reinterpret_cast<u32x2*>(tile + 1024 + lane * 8) = hi2;
-  img_scales[(((rt >> 2) * k_tiles + kt) * 64 + lane) * 4 + (rt & 3)] = (uint8_t)sbyte;
+  *reinterpret_cast<u32x4*>(tile + slot * 16u) = lo4;
+  *reinterpret_cast<u32x2*>(tile + 1024u + slot * 8u) = hi2;
+  tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sbyte;
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;          // tiles of this workgroup that exist
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
+  const uint32_t nbytes = (uint32_t)nt * kTileBytes;
+  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
 }
 
 }  // namespace
