@@ -47,4 +47,27 @@ __host__ __device__ inline ImageGeom image_geom(int64_t rows, int64_t K) {
   return g;
 }
 
+// Workgroup -> (row tile, group of 4 k-tiles) for the kernels that write an image.  The hardware deals workgroups
+// round-robin to the 8 XCDs (each with its own L2), so workgroup c runs on XCD c % 8.  All patches of four consecutive
+// row tiles (128 rows: the rows whose scale bytes share the image's scale dwords, and whose canonical scale / index
+// bytes share cache lines along K) go to one XCD, close together in launch order, so that those partially written or
+// partially read lines are merged in one L2 instead of being moved once per XCD.
+struct PatchMap {
+  int64_t rt, kg;
+  bool valid;
+};
+__device__ inline PatchMap patch_of_workgroup(uint32_t c, uint32_t k_groups, uint32_t row_tile_groups) {
+  const uint32_t x = c & 7u, j = c >> 3;
+  const uint32_t per = 4u * k_groups;
+  const uint32_t gi = (j / per) * 8u + x, rem = j % per;
+  PatchMap m;
+  m.rt = (int64_t)gi * 4 + rem / k_groups;
+  m.kg = rem % k_groups;
+  m.valid = gi < row_tile_groups;
+  return m;
+}
+inline int64_t patch_grid(int64_t k_groups, int64_t row_tile_groups) {
+  return 8 * 4 * k_groups * ((row_tile_groups + 7) / 8);
+}
+
 }  // namespace mxp

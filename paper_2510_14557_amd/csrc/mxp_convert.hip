@@ -134,8 +134,10 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
   __shared__ uint8_t tile_scales[4 * 64];
   const uint32_t t = threadIdx.x;
   const uint32_t r_in = t >> 3, kb_in = t & 7u;
-  const int64_t kt0 = (int64_t)blockIdx.x * 4;
-  const int64_t rt = blockIdx.y;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4;
+  const int64_t rt = pm.rt;
   const uint32_t slot = (kb_in & 1u) * 32u + r_in;     // slot of this block in its tile: row % 32, K-block % 2
   const int64_t row = rt * kTileRows + r_in;
   const int64_t kb = kt0 * 2 + kb_in;
@@ -198,8 +200,9 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
   const ImageGeom g = image_geom(rows, K);
   uint8_t* ie = static_cast<uint8_t*>(image);
   uint8_t* is = ie + g.elem_bytes;
-  if (g.row_tiles > 65535) return MXP_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)((g.k_tiles + 3) / 4), (unsigned)g.row_tiles);
+  const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_wg);
   const u32x4* e = reinterpret_cast<const u32x4*>(elems);
   if (fmt == MXP_FMT_MXFP4P)
     hipLaunchKernelGGL((prepack_kernel<true>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);

@@ -335,7 +335,9 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
   __shared__ uint8_t tile_scales[4 * 64];
   const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
-  const int64_t rt = blockIdx.y, kt0 = (int64_t)blockIdx.x * 4;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t rt = pm.rt, kt0 = pm.kg * 4;
   const bool canon = elems != nullptr;
   // pass u covers rows 8u .. 8u+7 of the row tile; this lane: row 8u + r0, K-block kb_in (the same in every pass)
   const uint32_t r0 = t >> 5, kb_in = (t >> 2) & 7u;
@@ -483,10 +485,11 @@ int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
                           uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream) {
   const ImageGeom g = image_geom(rows, K);
-  if (g.row_tiles > 65535) return MXP_ERR_UNSUPPORTED;
+  const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   uint8_t* ie = static_cast<uint8_t*>(image);
   uint8_t* is = ie + g.elem_bytes;
-  dim3 grid((unsigned)((g.k_tiles + 3) / 4), (unsigned)g.row_tiles);
+  dim3 grid((unsigned)n_wg);
   uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
   const int64_t nbk = K / kBlock;
   const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
