@@ -30,9 +30,81 @@ typedef float v2f __attribute__((ext_vector_type(2)));
 // instruction with X = 2^shared_exp as the scale (exact: at most 2 significant bits times a power of two), and the lane
 // that holds the BM overwrites that one element with 2^e_max * 1.mmm * X (Eq. 2, first case).  Blocks whose results
 // can be subnormal or special (scale byte 0, 1, 255) take the integer path, which does not depend on the float mode.
+// out: fp32 patterns, or (OUT_BF16) 4 packed pairs in out[0..3].
+template <bool PLUS, bool OUT_BF16>
+__device__ __forceinline__ void decode_group(uint32_t dw, uint32_t sbyte, uint32_t bm, uint32_t part, uint32_t (&out)[8]) {
+  const bool mine = PLUS && (bm >> 3) == part;       // this lane holds the BM
+  const uint32_t pos = bm & 7u;
+  if (sbyte >= 2u && sbyte != 255u) {
+    const float X = __uint_as_float(sbyte << 23);
+    const uint32_t nib = (dw >> (4u * pos)) & 15u;
+    const float bmv = __uint_as_float(((nib & 8u) << 28) | __float_as_uint((float)(8u + (nib & 7u)) * (X * 0.5f)));
+    if (OUT_BF16) {
+      union { v2bf v; uint32_t u; } c0, c1, c2, c3;
+      c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 0);
+      c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 1);
+      c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 2);
+      c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 3);
+      out[0] = c0.u; out[1] = c1.u; out[2] = c2.u; out[3] = c3.u;
+      if (mine) {
+        const uint32_t h = __float_as_uint(bmv) >> 16;               // exact: 4 significant bits
+        const uint32_t sh = (pos & 1u) * 16u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if ((pos >> 1) == (uint32_t)j) out[j] = (out[j] & ~(0xFFFFu << sh)) | (h << sh);
+      }
+    } else {
+      const v2f f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 0), f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 1);
+      const v2f f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 2), f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 3);
+      out[0] = __float_as_uint(f0[0]); out[1] = __float_as_uint(f0[1]); out[2] = __float_as_uint(f1[0]); out[3] = __float_as_uint(f1[1]);
+      out[4] = __float_as_uint(f2[0]); out[5] = __float_as_uint(f2[1]); out[6] = __float_as_uint(f3[0]); out[7] = __float_as_uint(f3[1]);
+      if (mine) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (pos == (uint32_t)i) out[i] = __float_as_uint(bmv);
+      }
+    }
+  } else {
+    uint32_t f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t nib = (dw >> (4 * i)) & 15u;
+      const uint32_t code = nib & 7u;
+      uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;           // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
+      if (mine && pos == (uint32_t)i) M = 8u + code;               // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
+      uint32_t bits = (nib >> 3) << 31;
+      if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
+      if (sbyte == 0u) bits = 0u;                                  // reserved all-zero code, tested before anything else
+      if (sbyte == 255u) bits = 0x7FC00000u;
+      f[i] = bits;
+    }
+    if (OUT_BF16) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) out[j] = (f[2 * j] >> 16) | (f[2 * j + 1] & 0xFFFF0000u);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] = f[i];
+    }
+  }
+}
+
+template <bool OUT_BF16>
+__device__ __forceinline__ void store_group(void* __restrict__ dst, int64_t off, const uint32_t (&out)[8]) {
+  if (OUT_BF16) {
+    u32x4 v = {out[0], out[1], out[2], out[3]};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off));
+  } else {
+    u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
+    u32x4 v0 = {out[0], out[1], out[2], out[3]}, v1 = {out[4], out[5], out[6], out[7]};
+    __builtin_nontemporal_store(v0, p);
+    __builtin_nontemporal_store(v1, p + 1);
+  }
+}
+
+// General destination (row stride ld): one group per lane and grid step.
 template <bool PLUS, bool OUT_BF16>
 __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
-                                                         const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld, int dense,
+                                                         const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld,
                                                          int64_t nq, void* __restrict__ dst) {
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += stride) {
@@ -41,75 +113,45 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restr
     const uint32_t part = (uint32_t)(q & 3);
     const uint32_t sbyte = scales[g];
     const uint32_t bm = PLUS ? (uint32_t)(bm_idx[g] & 31u) : 64u;
-    const bool mine = PLUS && (bm >> 3) == part;       // this lane holds the BM
-    const uint32_t pos = bm & 7u;
-    uint32_t out[8];                                   // fp32 patterns, or (OUT_BF16) 4 packed pairs in out[0..3]
-    if (sbyte >= 2u && sbyte != 255u) {
-      const float X = __uint_as_float(sbyte << 23);
-      const uint32_t nib = (dw >> (4u * pos)) & 15u;
-      const float bmv = __uint_as_float(((nib & 8u) << 28) | __float_as_uint((float)(8u + (nib & 7u)) * (X * 0.5f)));
-      if (OUT_BF16) {
-        union { v2bf v; uint32_t u; } c0, c1, c2, c3;
-        c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 0);
-        c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 1);
-        c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 2);
-        c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 3);
-        out[0] = c0.u; out[1] = c1.u; out[2] = c2.u; out[3] = c3.u;
-        if (mine) {
-          const uint32_t h = __float_as_uint(bmv) >> 16;               // exact: 4 significant bits
-          const uint32_t sh = (pos & 1u) * 16u;
+    uint32_t out[8];
+    decode_group<PLUS, OUT_BF16>(dw, sbyte, bm, part, out);
+    const int64_t row = g / nbk;
+    store_group<OUT_BF16>(dst, row * ld + (g - row * nbk) * 32 + part * 8, out);
+  }
+}
+
+// Dense destination (row stride = K): the tensor is one run of nq groups.  A workgroup walks chunks of 256 * U groups;
+// all loads of a chunk are issued before the first decode, and whole chunks run without bounds tests.
+template <bool PLUS, bool OUT_BF16, int U>
+__global__ void __launch_bounds__(256) dequantize_dense_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                               const uint8_t* __restrict__ bm_idx, int64_t nq,
+                                                               void* __restrict__ dst) {
+  const uint32_t t = threadIdx.x, part = t & 3u;
+  constexpr int64_t kChunk = 256 * U;
+  const int64_t n_chunks = (nq + kChunk - 1) / kChunk;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t q_base = c * kChunk;
+    const bool whole = q_base + kChunk <= nq;
+    const uint32_t* e_in = elems + q_base;
+    const uint8_t* s_in = scales + (q_base >> 2);
+    const uint8_t* i_in = bm_idx + (q_base >> 2);
+    uint32_t dw[U], sb[U], bm[U];
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if ((pos >> 1) == (uint32_t)j) out[j] = (out[j] & ~(0xFFFFu << sh)) | (h << sh);
-        }
-      } else {
-        const v2f f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 0), f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 1);
-        const v2f f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 2), f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(dw, X, 3);
-        out[0] = __float_as_uint(f0[0]); out[1] = __float_as_uint(f0[1]); out[2] = __float_as_uint(f1[0]); out[3] = __float_as_uint(f1[1]);
-        out[4] = __float_as_uint(f2[0]); out[5] = __float_as_uint(f2[1]); out[6] = __float_as_uint(f3[0]); out[7] = __float_as_uint(f3[1]);
-        if (mine) {
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            if (pos == (uint32_t)i) out[i] = __float_as_uint(bmv);
-        }
-      }
-    } else {
-      uint32_t f[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t nib = (dw >> (4 * i)) & 15u;
-        const uint32_t code = nib & 7u;
-        uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;           // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
-        if (mine && pos == (uint32_t)i) M = 8u + code;               // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
-        uint32_t bits = (nib >> 3) << 31;
-        if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
-        if (sbyte == 0u) bits = 0u;                                  // reserved all-zero code, tested before anything else
-        if (sbyte == 255u) bits = 0x7FC00000u;
-        f[i] = bits;
-      }
-      if (OUT_BF16) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = (f[2 * j] >> 16) | (f[2 * j + 1] & 0xFFFF0000u);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = f[i];
+    for (int u = 0; u < U; ++u) {
+      const uint32_t ql = u * 256 + t;
+      dw[u] = 0; sb[u] = 0; bm[u] = 64u;
+      if (whole || q_base + ql < nq) {
+        dw[u] = __builtin_nontemporal_load(e_in + ql);
+        sb[u] = s_in[ql >> 2];
+        if (PLUS) bm[u] = i_in[ql >> 2] & 31u;
       }
     }
-    int64_t off;
-    if (dense) {
-      off = q * 8;
-    } else {
-      const int64_t row = g / nbk;
-      off = row * ld + (g - row * nbk) * 32 + part * 8;
-    }
-    if (OUT_BF16) {
-      u32x4 v = {out[0], out[1], out[2], out[3]};
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off));
-    } else {
-      u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
-      u32x4 v0 = {out[0], out[1], out[2], out[3]}, v1 = {out[4], out[5], out[6], out[7]};
-      __builtin_nontemporal_store(v0, p);
-      __builtin_nontemporal_store(v1, p + 1);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t ql = u * 256 + t;
+      uint32_t out[8];
+      decode_group<PLUS, OUT_BF16>(dw[u], sb[u], bm[u], part, out);
+      if (whole || q_base + ql < nq) store_group<OUT_BF16>(dst, (q_base + ql) * 8, out);
     }
   }
 }
@@ -226,17 +268,25 @@ extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (bm_idx && !aligned16(bm_idx)) || (ld_dst * esz) % 16 != 0)
     return MXP_ERR_ALIGN;
   const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
-  const int dense = ld_dst == K ? 1 : 0;
-  int64_t want = (nq + 255) / 256;
-  const int64_t cap = (int64_t)kNumCU * 16;
-  const int grid = (int)(want < cap ? want : cap);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const uint32_t* e32 = reinterpret_cast<const uint32_t*>(elems);
   const bool plus = fmt == MXP_FMT_MXFP4P, bf = dst_dtype == MXP_BF16;
-  if (plus && bf) hipLaunchKernelGGL((dequantize_kernel<true, true>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
-  else if (plus) hipLaunchKernelGGL((dequantize_kernel<true, false>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
-  else if (bf) hipLaunchKernelGGL((dequantize_kernel<false, true>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
-  else hipLaunchKernelGGL((dequantize_kernel<false, false>), dim3(grid), dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, dense, nq, dst);
+  if (ld_dst == K) {
+    constexpr int U = 4;
+    const int64_t want = (nq + 256 * U - 1) / (256 * U), cap = (int64_t)kNumCU * 16;
+    const dim3 grid((unsigned)(want < cap ? want : cap));
+    if (plus && bf) hipLaunchKernelGGL((dequantize_dense_kernel<true, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    else if (plus) hipLaunchKernelGGL((dequantize_dense_kernel<true, false, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    else if (bf) hipLaunchKernelGGL((dequantize_dense_kernel<false, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    else hipLaunchKernelGGL((dequantize_dense_kernel<false, false, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    return launch_status();
+  }
+  const int64_t want = (nq + 255) / 256, cap = (int64_t)kNumCU * 16;
+  const dim3 grid((unsigned)(want < cap ? want : cap));
+  if (plus && bf) hipLaunchKernelGGL((dequantize_kernel<true, true>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
+  else if (plus) hipLaunchKernelGGL((dequantize_kernel<true, false>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
+  else if (bf) hipLaunchKernelGGL((dequantize_kernel<false, true>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
+  else hipLaunchKernelGGL((dequantize_kernel<false, false>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
   return launch_status();
 }
 
