@@ -80,6 +80,16 @@ size_t mxp_image_bytes(int64_t rows, int64_t K);
 int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt,
                 int64_t rows, int64_t K, void* image, size_t image_bytes, void* stream);
 
+/* Image kinds.  MXP_IMAGE_E2M3 is what mxp_prepack and mxp_quantize_image write (any format).  A plain MXFP4 operand
+ * has no BM to widen, so as the B operand (the weights of Sec. 7.1's "MXFP4+ activations x MXFP4 weights" setting) it
+ * may stay in its 4-bit codes: MXP_IMAGE_E2M1, two thirds of the bytes, written by mxp_prepack_e2m1 from canonical
+ * MXFP4 storage (elems and scales only).  The A operand of the products below is always an E2M3 image. */
+#define MXP_IMAGE_E2M3 0
+#define MXP_IMAGE_E2M1 1
+size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K);
+int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K,
+                     void* image, size_t image_bytes, void* stream);
+
 /* Conversion (Sec. 4.1, 4.2) written directly as an image: same source arguments and the same encoding as
  * mxp_quantize, but the result goes to `image` (mxp_image_bytes(rows, K) bytes, bit-identical to mxp_prepack of the
  * canonical result) without a pass over the canonical bytes.  If elems / scales / bm_idx are given (all of them, bm_idx
@@ -99,7 +109,7 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
              void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Same product from images built earlier with mxp_prepack (weights are packed once, when they are loaded). */
-int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image,
+int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, int b_kind,
                        void* D, int d_dtype, int64_t ldd, void* stream);
 
 /* Activations given un-quantized (A[M][K], MXP_F32 or MXP_BF16, row stride lda): quantized on the fly to fmtA on
@@ -107,7 +117,7 @@ int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, con
  * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes. */
 size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K);
 int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
-                   const void* B_image, void* D, int d_dtype, int64_t ldd,
+                   const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 const char* mxp_status_string(int status);

@@ -25,6 +25,9 @@ inline int launch_status() {
 constexpr int kTileRows = 32;
 constexpr int kTileK = 64;
 constexpr int kTileBytes = 1536;
+// A plain MXFP4 operand (no BM) can stay in 4-bit codes: the MFMA takes E2M1 for one operand and E2M3 for the other at
+// the same rate.  Its tile is the 64 lanes' 16-byte canonical blocks, [64 x 16 B] = 1024 B; everything else is the same.
+constexpr int kTileBytesE2M1 = 1024;
 constexpr int kRowPad = 256;
 constexpr int kKPad = 128;
 
@@ -36,13 +39,13 @@ struct ImageGeom {
   __host__ __device__ int64_t total() const { return elem_bytes + scale_bytes; }
 };
 
-__host__ __device__ inline ImageGeom image_geom(int64_t rows, int64_t K) {
+__host__ __device__ inline ImageGeom image_geom(int64_t rows, int64_t K, int tile_bytes = kTileBytes) {
   ImageGeom g;
   g.rows_p = (rows + kRowPad - 1) / kRowPad * kRowPad;
   g.K_p = (K + kKPad - 1) / kKPad * kKPad;
   g.row_tiles = g.rows_p / kTileRows;
   g.k_tiles = g.K_p / kTileK;
-  g.elem_bytes = g.row_tiles * g.k_tiles * (int64_t)kTileBytes;
+  g.elem_bytes = g.row_tiles * g.k_tiles * (int64_t)tile_bytes;
   g.scale_bytes = (g.row_tiles / 4) * g.k_tiles * 256;
   return g;
 }

@@ -233,6 +233,38 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
   if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
 }
 
+// Plain MXFP4 operand -> E2M1 image: the canonical 16-byte blocks moved to their lane slots, scales to the scale
+// dwords (same patch walk as above; flushed blocks are zeroed, padding is zero elements with a unit scale).
+__global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                           int64_t rows, int64_t nbk, int64_t k_tiles,
+                                                           uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE2M1];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const uint32_t slot = (kb_in & 1u) * 32u + r_in;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  u32x4 v = {0, 0, 0, 0};
+  uint32_t sbyte = 127u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    v = __builtin_nontemporal_load(elems + b);
+    sbyte = scales[b];
+    if (sbyte == 0u) v = (u32x4){0, 0, 0, 0};
+  }
+  *reinterpret_cast<u32x4*>(tiles + (kb_in >> 1) * kTileBytesE2M1 + slot * 16u) = v;
+  tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sbyte;
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytesE2M1;
+  if (t * 16u < (uint32_t)nt * kTileBytesE2M1)
+    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(tiles + t * 16u), reinterpret_cast<u32x4*>(out + t * 16u));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
 }  // namespace
 
 namespace mxp {
@@ -250,6 +282,17 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
     hipLaunchKernelGGL((prepack_kernel<true>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
   else
     hipLaunchKernelGGL((prepack_kernel<false>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  return launch_status();
+}
+
+int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream) {
+  const ImageGeom g = image_geom(rows, K, kTileBytesE2M1);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(prepack_e2m1_kernel, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems), scales,
+                     rows, K / kBlock, g.k_tiles, ie, is);
   return launch_status();
 }
 
@@ -293,6 +336,22 @@ extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const
 extern "C" size_t mxp_image_bytes(int64_t rows, int64_t K) {
   if (rows < 0 || K < 0) return 0;
   return (size_t)mxp::image_geom(rows, K).total();
+}
+
+extern "C" size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K) {
+  if (rows < 0 || K < 0) return 0;
+  return (size_t)mxp::image_geom(rows, K, mxp::kTileBytesE2M1).total();
+}
+
+extern "C" int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image,
+                                size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image)) return MXP_ERR_ALIGN;
+  if (image_bytes < (size_t)image_geom(rows, K, kTileBytesE2M1).total()) return MXP_ERR_WORKSPACE;
+  return prepack_e2m1_launch(elems, scales, rows, K, image, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,

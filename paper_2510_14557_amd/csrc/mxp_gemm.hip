@@ -14,6 +14,7 @@
 namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream);
+int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
                           uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream);
 }  // namespace mxp
@@ -27,27 +28,32 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kFmtE2M3 = 2;  // cbsz / blgp code of the f8f6f4 MFMA for FP6 E2M3 operands
+constexpr int kFmtE2M1 = 4;  // ... for FP4 E2M1 operands (16 bytes per lane: registers 4..7 of the operand are ignored)
 
 // The B tile goes in as the MFMA's first operand and the A tile as its second, i.e. the instruction forms the
 // transposed 32x32 tile: accumulator register r of lane l is then D[m = l % 32][n = 8 * (r / 4) + 4 * (l / 32) + r % 4],
 // four consecutive columns per register quad, which the epilogue stores as one 16-byte piece.
-template <int OA, int OB>
+// FB = element format of the B operand: E2M3, or E2M1 for a plain MXFP4 operand kept in 4-bit codes.
+template <int OA, int OB, int FB = kFmtE2M3>
 __device__ __forceinline__ v16f mfma(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, c, kFmtE2M3, kFmtE2M3, OB, sb, OA, sa);
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, c, FB, kFmtE2M3, OB, sb, OA, sa);
 }
 
-template <int I, int J>
+template <int I, int J, int FB>
 __device__ __forceinline__ v16f mfma_sel(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
-  return mfma<(I & 3), (J & 3)>(a, b, c, sa, sb);
+  return mfma<(I & 3), (J & 3), FB>(a, b, c, sa, sb);
 }
 
 // Tile configuration: a workgroup of WAVES_M x WAVES_N wavefronts, each computing WM x WN MFMA tiles of 32 x 32.
-template <int WM_, int WN_, int WAVES_M_, int WAVES_N_>
+template <int WM_, int WN_, int WAVES_M_, int WAVES_N_, int BT_ = kTileBytes>
 struct Cfg {
   static constexpr int WM = WM_, WN = WN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int BT = BT_;                                 // bytes of a B tile: 1536 (E2M3) or 1024 (E2M1)
+  static constexpr int FB = BT_ == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  static_assert(BT_ == kTileBytes || BT_ == kTileBytesE2M1, "B tile kind");
   static constexpr int TM = WM * WAVES_M, TN = WN * WAVES_N;   // 32-row tiles per workgroup
   static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
-  static constexpr int A_BYTES = TM * kTileBytes, B_BYTES = TN * kTileBytes;
+  static constexpr int A_BYTES = TM * kTileBytes, B_BYTES = TN * BT;
   static constexpr int SA_BYTES = ((TM + 3) / 4) * 256, SB_BYTES = ((TN + 3) / 4) * 256;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
   static_assert(WM == 1 || WM == 2 || WM == 4 || WM == 8, "WM"); static_assert(WN == 1 || WN == 2 || WN == 4 || WN == 8, "WN");
@@ -65,22 +71,22 @@ __device__ __forceinline__ void mma_all(v16f (&acc)[C::WM][C::WN], const v8i (&a
     for (int j = 0; j < C::WN; ++j) {
         const int sai = (int)sa[i >> 2], sbj = (int)sb[j >> 2];
         switch ((i & 3) * 4 + (j & 3)) {
-          case 0: acc[i][j] = mfma<0, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 1: acc[i][j] = mfma<0, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 2: acc[i][j] = mfma<0, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 3: acc[i][j] = mfma<0, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 4: acc[i][j] = mfma<1, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 5: acc[i][j] = mfma<1, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 6: acc[i][j] = mfma<1, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 7: acc[i][j] = mfma<1, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 8: acc[i][j] = mfma<2, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 9: acc[i][j] = mfma<2, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 10: acc[i][j] = mfma<2, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 11: acc[i][j] = mfma<2, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 12: acc[i][j] = mfma<3, 0>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 13: acc[i][j] = mfma<3, 1>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 14: acc[i][j] = mfma<3, 2>(a[i], b[j], acc[i][j], sai, sbj); break;
-          default: acc[i][j] = mfma<3, 3>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 0: acc[i][j] = mfma<0, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 1: acc[i][j] = mfma<0, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 2: acc[i][j] = mfma<0, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 3: acc[i][j] = mfma<0, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 4: acc[i][j] = mfma<1, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 5: acc[i][j] = mfma<1, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 6: acc[i][j] = mfma<1, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 7: acc[i][j] = mfma<1, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 8: acc[i][j] = mfma<2, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 9: acc[i][j] = mfma<2, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 10: acc[i][j] = mfma<2, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 11: acc[i][j] = mfma<2, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 12: acc[i][j] = mfma<3, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 13: acc[i][j] = mfma<3, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 14: acc[i][j] = mfma<3, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          default: acc[i][j] = mfma<3, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
         }
       }
 }
@@ -196,8 +202,8 @@ __device__ __forceinline__ const u32x4* stage_src(int c, int64_t kt, int64_t k_t
     p = a_el + ((tm0 + t) * k_tiles + kt) * (int64_t)kTileBytes + w * 16;
   } else if (c < A_CH + B_CH) {
     const int cc = c - A_CH;
-    const int t = cc / (kTileBytes / 16), w = cc % (kTileBytes / 16);
-    p = b_el + ((tn0 + t) * k_tiles + kt) * (int64_t)kTileBytes + w * 16;
+    const int t = cc / (C::BT / 16), w = cc % (C::BT / 16);
+    p = b_el + ((tn0 + t) * k_tiles + kt) * (int64_t)C::BT + w * 16;
   } else if (c < A_CH + B_CH + SA_CH) {
     const int cc = c - A_CH - B_CH;
     const int g = cc / 16, w = cc % 16;
@@ -261,9 +267,10 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
     }
 #pragma unroll
     for (int j = 0; j < C::WN; ++j) {
-      const uint8_t* t = st + C::A_BYTES + (wn * C::WN + j) * kTileBytes;
+      const uint8_t* t = st + C::A_BYTES + (wn * C::WN + j) * C::BT;
       const u32x4 lo = *reinterpret_cast<const u32x4*>(t + lane * 16);
-      const u32x2 hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
+      u32x2 hi = {0, 0};
+      if (C::BT == kTileBytes) hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
       b[j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
     }
     // scale dwords: byte q of group g = row tile 4g + q.  The tiles of one wavefront lie in one group when WM <= 4
@@ -318,6 +325,14 @@ __device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
   const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
   return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
 }
+__device__ __forceinline__ v8i read_operand_e2m1(const uint8_t* tile, int lane) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
+}
+template <int BT>
+__device__ __forceinline__ v8i read_b(const uint8_t* tile, int lane) {
+  return BT == kTileBytes ? read_operand(tile, lane) : read_operand_e2m1(tile, lane);
+}
 
 // Copy engine state of one wavefront for one output tile: rows [32 tm0, +256), columns [32 tn0, +64 WN).  WN = 4: full
 // tile (each wavefront 4 x 4 MFMA tiles, 8 B tiles per stage); WN = 2: half tile (4 x 2, 4 B tiles per stage).  The
@@ -328,18 +343,22 @@ __device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
 // per round) and the scale dwords at wslot + sdelta.
 template <class C, int S, int WN>
 struct Copier {
-  static constexpr int PER_STAGE = WN == 4 ? 7 : 6;   // copies per wavefront and stage
-  uint32_t offE[3], offH, offS;
+  static constexpr bool B6 = C::BT == kTileBytes;
+  // copies per wavefront and stage: 3 rounds of A, the rounds of B (E2M3: 3 or 2, E2M1: 2 or 1), one of scales
+  static constexpr int PER_STAGE = 3 + (B6 ? (WN == 4 ? 3 : 2) : (WN == 4 ? 2 : 1)) + 1;
+  uint32_t offE[3], offB[3], offH, offS;
   const uint8_t *pA, *pB, *pS;
   uint32_t wslot, wslot_end, sdelta, hdelta;
 
   __device__ __forceinline__ void init(uint32_t lds_base, const uint8_t* a_el, const uint8_t* a_sc, const uint8_t* b_el,
                                        const uint8_t* b_sc, int64_t k_tiles, int64_t tm0, int64_t tn0, int tid, int wave) {
     constexpr int TILE_CH = kTileBytes / 16;
+    constexpr int TILE_CH_B = C::BT / 16;
 #pragma unroll
-    for (int u = 0; u < 3; ++u) {   // chunk tid + 256 u of an 8-tile run (the same for A and B)
+    for (int u = 0; u < 3; ++u) {   // chunk tid + 256 u of an 8-tile run
       const int c = tid + u * C::THREADS;
       offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+      offB[u] = (uint32_t)((c / TILE_CH_B) * k_tiles * C::BT + (c % TILE_CH_B) * 16);
     }
     // half tile: the B run has 4 tiles = 384 chunks; its second round is chunks 256..383, fetched by wavefronts 0-1
     // and fetched again (same source, same destination) by wavefronts 2-3 so that every wavefront issues the same
@@ -348,7 +367,7 @@ struct Copier {
     offH = (uint32_t)((ch / TILE_CH) * k_tiles * kTileBytes + (ch % TILE_CH) * 16);
     offS = (uint32_t)(tid & 63) * 4u;
     pA = a_el + tm0 * k_tiles * kTileBytes;
-    pB = b_el + tn0 * k_tiles * kTileBytes;
+    pB = b_el + tn0 * k_tiles * C::BT;
     // Scale dwords: 256 bytes (64 lanes x 1 dword) per group of 4 row tiles and k-tile.  Wavefronts 0,1 copy A's two
     // groups, wavefronts 2,3 B's two groups (half tile: both copy B's only group; the second lands in an unused place).
     pS = wave < 2 ? a_sc + ((tm0 / 4 + wave) * k_tiles) * 256 : b_sc + ((tn0 / 4 + (WN == 4 ? wave - 2 : 0)) * k_tiles) * 256;
@@ -364,10 +383,10 @@ struct Copier {
     if (u == 0) MXP_COPY16(offE[0], pA, 0);
     else if (u == 1) MXP_COPY16(offE[1], pA, 4096);
     else if (u == 2) MXP_COPY16(offE[2], pA, 8192);
-    else if (u == 3) MXP_COPY16(offE[0], pB, 12288);
-    else if (u == 4 && WN == 4) MXP_COPY16(offE[1], pB, 16384);
-    else if (u == 5 && WN == 4) MXP_COPY16(offE[2], pB, 20480);
-    else if (u == 4 && WN == 2)
+    else if (u == 3) MXP_COPY16(offB[0], pB, 12288);
+    else if (u == 4 && WN == 4) MXP_COPY16(offB[1], pB, 16384);
+    else if (u == 5 && WN == 4 && B6) MXP_COPY16(offB[2], pB, 20480);
+    else if (u == 4 && WN == 2 && B6)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "s"(hdelta), "v"(offH), "s"(pB) : "memory", "scc");
     else if (u == 6)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3" ::"s"(wslot), "s"(sdelta), "v"(offS), "s"(pS) : "memory", "scc");
@@ -375,21 +394,20 @@ struct Copier {
 #undef MXP_COPY16
   __device__ __forceinline__ void next_stage() {
     pA += kTileBytes;
-    pB += kTileBytes;
+    pB += C::BT;
     pS += 256;
     wslot += C::STAGE_BYTES;
     if (wslot == wslot_end) wslot -= (uint32_t)S * C::STAGE_BYTES;
   }
   __device__ __forceinline__ void issue_stage() {
 #pragma unroll
-    for (int u = 0; u < 7; ++u)
-      if (u != 5 || WN == 4) copy(u);
+    for (int u = 0; u < 7; ++u) copy(u);   // rounds that do not exist for this tile kind are no-ops
     next_stage();
   }
   // same state change as `n` issue_stage() calls, without the copies (they were issued ahead of time)
   __device__ __forceinline__ void skip_stages(int n) {
     pA += (int64_t)n * kTileBytes;
-    pB += (int64_t)n * kTileBytes;
+    pB += (int64_t)n * C::BT;
     pS += (int64_t)n * 256;
     wslot += (uint32_t)n * C::STAGE_BYTES;   // n < S and the ring starts at slot 0 for every tile
   }
@@ -420,7 +438,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
   static_assert(S == 4, "the peeled tail below is written for a 4-slot ring");
-  static_assert(C::A_BYTES == 3 * C::THREADS * 16 && C::A_BYTES == C::B_BYTES && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
+  static_assert(C::A_BYTES == 3 * C::THREADS * 16 && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
   using CP = Copier<C, S, WN>;
   constexpr int PER_STAGE = CP::PER_STAGE;
 
@@ -441,7 +459,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 
   const int64_t ta = tm0 + wm * 4, tb = tn0 + wn * WN;
   const int a_tiles_off = wm * 4 * kTileBytes;
-  const int b_tiles_off = C::A_BYTES + wn * WN * kTileBytes;
+  const int b_tiles_off = C::A_BYTES + wn * WN * C::BT;
   const int sa_off = C::A_BYTES + C::B_BYTES + wm * 256 + lane * 4;
   // full tile: group wn of B, bytes 0..3 = the wavefront's 4 column tiles; half tile: group 0, bytes 2 wn, 2 wn + 1
   const int sb_off = C::A_BYTES + C::B_BYTES + C::SA_BYTES + (WN == 4 ? wn * 256 : 0) + lane * 4;
@@ -465,7 +483,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 #pragma unroll
   for (int i = 0; i < 4; ++i) a0[i] = read_operand(lds + a_tiles_off + i * kTileBytes, lane);
 #pragma unroll
-  for (int j = 0; j < WN; ++j) b0[j] = read_operand(lds + b_tiles_off + j * kTileBytes, lane);
+  for (int j = 0; j < WN; ++j) b0[j] = read_b<C::BT>(lds + b_tiles_off + j * C::BT, lane);
   sa0 = *reinterpret_cast<const uint32_t*>(lds + sa_off);
   sb0 = *reinterpret_cast<const uint32_t*>(lds + sb_off) >> sb_shift;
 
@@ -478,7 +496,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // COPY: this iteration issues a stage.  KEEPN: copies that may stay in flight at its wait.  NEXT: there is a next
   // k-tile to wait for and read.
 #define MXP_MFMA(m)                                                                                                          \
-  acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
+  acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN, C::FB>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
   __builtin_amdgcn_sched_barrier(0)
 #define MXP_GAP() __builtin_amdgcn_sched_barrier(0)
 #define MXP_READ(stmt) do { if (NEXT) { stmt; } } while (0)
@@ -507,14 +525,14 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(6);
-      MXP_READ(nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane));
+      MXP_READ(nb[0] = read_b<C::BT>(st + b_tiles_off + 0 * C::BT, lane));
       MXP_GAP();
       MXP_MFMA(7);
-      MXP_READ(nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane));
+      MXP_READ(nb[1] = read_b<C::BT>(st + b_tiles_off + 1 * C::BT, lane));
       MXP_GAP();
       MXP_MFMA(8);
-      MXP_READ(nb[2] = read_operand(st + b_tiles_off + 2 * kTileBytes, lane));
-      MXP_READ(nb[3] = read_operand(st + b_tiles_off + 3 * kTileBytes, lane));
+      MXP_READ(nb[2] = read_b<C::BT>(st + b_tiles_off + 2 * C::BT, lane));
+      MXP_READ(nb[3] = read_b<C::BT>(st + b_tiles_off + 3 * C::BT, lane));
       MXP_READ(nsa = *reinterpret_cast<const uint32_t*>(st + sa_off));
       MXP_READ(nsb = *reinterpret_cast<const uint32_t*>(st + sb_off));
       MXP_GAP();
@@ -548,8 +566,8 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
       MXP_GAP();
       MXP_MFMA(4);
-      MXP_READ(nb[0] = read_operand(st + b_tiles_off + 0 * kTileBytes, lane));
-      MXP_READ(nb[1] = read_operand(st + b_tiles_off + 1 * kTileBytes, lane));
+      MXP_READ(nb[0] = read_b<C::BT>(st + b_tiles_off + 0 * C::BT, lane));
+      MXP_READ(nb[1] = read_b<C::BT>(st + b_tiles_off + 1 * C::BT, lane));
       MXP_READ(nsa = *reinterpret_cast<const uint32_t*>(st + sa_off));
       MXP_READ(nsb = *reinterpret_cast<const uint32_t*>(st + sb_off) >> sb_shift);
       MXP_GAP();
@@ -671,7 +689,7 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
 template <class C>
 int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, C::BT);
   const int64_t gm = (M + C::TM * 32 - 1) / (C::TM * 32), gn = (N + C::TN * 32 - 1) / (C::TN * 32);
   if (gm > 65535 || gn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)gn, (unsigned)gm);
@@ -699,7 +717,7 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 template <class C, int S>
 int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, C::BT);
   const int64_t gm = (M + 255) / 256, gn = (N + 255) / 256;
   if (gm * gn * 2 > 2000000000LL) return MXP_ERR_UNSUPPORTED;
   const int64_t total = gm * gn;
@@ -743,7 +761,7 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 // of B and splits K over its 8 wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
 // operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the one or two row tiles
 // of A likewise (A is tiny and stays in cache), runs the MFMAs, and the 8 partial tiles are summed through LDS.
-template <int TMR, bool OUT_BF16>
+template <int TMR, bool OUT_BF16, int BT>
 __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                           const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                           int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
@@ -752,7 +770,8 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ct = blockIdx.x;                            // column tile of B (32 columns)
-  const uint8_t* bt = b_el + ct * (int64_t)k_tiles * kTileBytes;
+  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
   const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
   const int b_shift = (int)(ct & 3) * 8;
   v16f acc[TMR];
@@ -767,9 +786,10 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       const int kt = k0 + c < k_tiles ? k0 + c : k_tiles - 1;     // clamped: the surplus is not used
-      const uint8_t* t = bt + (int64_t)kt * kTileBytes;
+      const uint8_t* t = bt + (int64_t)kt * BT;
       const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + lane * 16));
-      const u32x2 hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
+      u32x2 hi = {0, 0};
+      if (BT == kTileBytes) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
       b[c] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
       sb[c] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
       sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
@@ -784,8 +804,8 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
-        acc[0] = mfma<0, 0>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
-        if (TMR > 1) acc[TMR - 1] = mfma<1, 0>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
+        acc[0] = mfma<0, 0, FB>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
+        if (TMR > 1) acc[TMR - 1] = mfma<1, 0, FB>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
       }
     }
   }
@@ -809,35 +829,44 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
   }
 }
 
+template <int BT>
 int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                   hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K);
+  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, BT);
   const int64_t ct = (N + 31) / 32;
   if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)ct);
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
   if (M <= 32) {
-    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<1, true>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<1, false>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<1, true, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<1, false, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else {
-    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<2, true>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, false>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<2, true, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else hipLaunchKernelGGL((gemm_skinny_kernel<2, false, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
   }
   return launch_status();
 }
 
-int gemm_images(const void* A_image, const void* B_image, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
-                hipStream_t s) {
-  const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
-  const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
-  if (M <= 64) return launch_skinny(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 #ifndef MXP_RING
 #define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
 #endif
+template <int BT>
+int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                     hipStream_t s) {
+  if (M <= 64) return launch_skinny<BT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail)
-  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  return launch_dma<Cfg<4, 4, 2, 2>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2, BT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return launch_dma<Cfg<4, 4, 2, 2, BT>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+}
+
+// A image: always E2M3.  B image: E2M3, or E2M1 for a plain MXFP4 operand (b_kind = MXP_IMAGE_E2M1).
+int gemm_images(const void* A_image, const void* B_image, int b_kind, int64_t M, int64_t N, int64_t K, void* D, int d_dtype,
+                int64_t ldd, hipStream_t s) {
+  const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
+  const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
+  if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images_kind<kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
 int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {
@@ -874,15 +903,16 @@ extern "C" size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   return align_up((size_t)mxp::image_geom(M, K).total()) + align_up((size_t)mxp::image_geom(N, K).total());
 }
 
-extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, void* D,
-                                  int d_dtype, int64_t ldd, void* stream) {
+extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, int b_kind,
+                                  void* D, int d_dtype, int64_t ldd, void* stream) {
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
   if (!A_image || !B_image) return MXP_ERR_NULL;
   if (!mxp::aligned16(A_image) || !mxp::aligned16(B_image)) return MXP_ERR_ALIGN;
-  return gemm_images(A_image, B_image, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(A_image, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx,
@@ -904,9 +934,11 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());
   rc = prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
   if (rc != MXP_OK) return rc;
-  rc = prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
+  // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product)
+  const bool b4 = fmtB == MXP_FMT_MXFP4;
+  rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, N, K, wb, s) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
   if (rc != MXP_OK) return rc;
-  return gemm_images(wa, wb, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(wa, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
@@ -915,10 +947,11 @@ extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
 }
 
 extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
-                              const void* B_image, void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd, void* workspace,
+                              size_t workspace_bytes, void* stream) {
   using namespace mxp;
   if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
@@ -932,7 +965,7 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   uint8_t* img = static_cast<uint8_t*>(workspace);
   rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
   if (rc != MXP_OK) return rc;
-  return gemm_images(img, B_image, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(img, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" const char* mxp_status_string(int status) {

@@ -13,12 +13,13 @@ import torch
 
 F32, BF16 = 0, 1
 MXFP4, MXFP4P = 0, 1
+IMAGE_E2M3, IMAGE_E2M1 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
            "mxp_gemm_bf16a", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -48,14 +49,17 @@ def lib():
     L.mxp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     L.mxp_gemm_workspace_bytes.restype = sz
     L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
-    L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, vp, vp, i32, i64, vp]
+    L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32, i64, vp]
+    L.mxp_image_bytes_e2m1.argtypes = [i64, i64]
+    L.mxp_image_bytes_e2m1.restype = sz
+    L.mxp_prepack_e2m1.argtypes = [vp, vp, i64, i64, vp, sz, vp]
     L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
     L.mxp_gemm_bf16a_workspace_bytes.restype = sz
-    L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, vp, i32, i64, vp, sz, vp]
+    L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
-    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_gemm", "mxp_gemm_prepacked",
+    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_prepack_e2m1", "mxp_gemm", "mxp_gemm_prepacked",
               "mxp_gemm_bf16a"):
         getattr(L, n).restype = i32
     _lib = L
@@ -175,6 +179,20 @@ def quantize_image(x: torch.Tensor, fmt: int = MXFP4P, canonical: bool = False, 
     return (out, q) if (canonical or q_out is not None) else out
 
 
+def image_bytes_e2m1(rows: int, K: int) -> int:
+    return int(lib().mxp_image_bytes_e2m1(rows, K))
+
+
+def prepack_e2m1(q, out: torch.Tensor | None = None):
+    """Plain MXFP4 operand (elems, scales[, ignored]) -> E2M1 image for the B side of the product."""
+    elems, scales = q[0], q[1]
+    rows, K = elems.shape[0], elems.shape[1] * 2
+    if out is None:
+        out = torch.empty(image_bytes_e2m1(rows, K), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_e2m1(_p(elems), _p(scales), rows, K, _p(out), out.numel(), _stream()), "mxp_prepack_e2m1")
+    return out
+
+
 def gemm_workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().mxp_gemm_workspace_bytes(M, N, K))
 
@@ -198,11 +216,12 @@ def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torc
     return out
 
 
-def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
+def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None,
+                   b_kind: int = IMAGE_E2M3):
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=a_image.device)
     ldd = out.stride(0) if M > 1 else max(N, 1)
-    _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), _p(b_image), _p(out), _dt(out), ldd, _stream()),
+    _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), _p(b_image), b_kind, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_prepacked")
     return out
 
@@ -212,7 +231,7 @@ def gemm_bf16a_workspace_bytes(M: int, K: int) -> int:
 
 
 def gemm_bf16a(a: torch.Tensor, fmt_a, b_image, N: int, out_dtype: torch.dtype = torch.float32,
-               out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+               out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, b_kind: int = IMAGE_E2M3):
     """Activations quantized on the fly, weights given as a prepacked image."""
     _dev2d(a)
     M, K = a.shape
@@ -222,6 +241,6 @@ def gemm_bf16a(a: torch.Tensor, fmt_a, b_image, N: int, out_dtype: torch.dtype =
         workspace = torch.empty(max(gemm_bf16a_workspace_bytes(M, K), 16), dtype=torch.uint8, device=a.device)
     lda = a.stride(0) if M > 1 else max(K, 1)
     ldd = out.stride(0) if M > 1 else max(N, 1)
-    _check(lib().mxp_gemm_bf16a(M, N, K, _p(a), _dt(a), lda, fmt_a, _p(b_image), _p(out), _dt(out), ldd,
+    _check(lib().mxp_gemm_bf16a(M, N, K, _p(a), _dt(a), lda, fmt_a, _p(b_image), b_kind, _p(out), _dt(out), ldd,
                                 _p(workspace), workspace.numel(), _stream()), "mxp_gemm_bf16a")
     return out

@@ -252,6 +252,29 @@ def test_gemm_shapes(M, N, K):
     assert torch.equal(Db, D.to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (33, 100, 96), (64, 1000, 4160), (100, 200, 416), (257, 300, 1024),
+                                   (300, 520, 2048), (512, 1100, 640)])
+def test_gemm_plain_mxfp4_weights_as_e2m1_image(M, N, K):
+    """Activations MXFP4+, weights plain MXFP4 kept in 4-bit codes on the B side (Sec. 7.1's setting)."""
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = oracle.quantize(a, oracle.MXFP4P), oracle.quantize(w, oracle.MXFP4)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qb, oracle.MXFP4)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4)                 # picks the E2M1 image for B
+    check_gemm(D, ref, S, "w4 %dx%dx%d" % (M, N, K))
+    img4 = mxp.prepack_e2m1(q_dev(qb))
+    assert img4.numel() == mxp.image_bytes_e2m1(N, K) < mxp.image_bytes(N, K)
+    D2 = mxp.gemm_prepacked(M, N, K, mxp.prepack(q_dev(qa), mxp.MXFP4P), img4, b_kind=mxp.IMAGE_E2M1)
+    assert torch.equal(D, D2)
+    D3 = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, img4, N, b_kind=mxp.IMAGE_E2M1)
+    assert torch.equal(D, D3)
+    # the same weights widened to E2M3 give the same products
+    D4 = mxp.gemm_prepacked(M, N, K, mxp.prepack(q_dev(qa), mxp.MXFP4P), mxp.prepack(q_dev(qb), mxp.MXFP4))
+    check_gemm(D4, ref, S, "w4 widened")
+    Db = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4, out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
 def test_gemm_strided_output_and_k0():
     a = synth.activations(40, 128, config_id=1, tensor_id=0)
     w = synth.weights(72, 128, config_id=1, tensor_id=1)
@@ -266,14 +289,14 @@ def test_gemm_strided_output_and_k0():
     assert D.shape == (4, 8) and not D.any()
 
 
-def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0):
+def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0, w_fmt="mxfp4p"):
     """Full-size GEMM on the GPU in the launch configuration the benchmark times; sampled outputs from the oracle."""
     a, ws = synth.make(name, M=M, N=N)
     wname = wname or next(iter(ws))
     w = ws[wname]
     da, dw = to_dev(a), to_dev(w)
-    qa, qw = mxp.quantize(da, mxp.MXFP4P), mxp.quantize(dw, mxp.MXFP4P)
-    D = mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P)
+    qa, qw = mxp.quantize(da, mxp.MXFP4P), mxp.quantize(dw, FMT[w_fmt][0])
+    D = mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0])
     torch.cuda.synchronize()
     rng = np.random.default_rng(seed)
     Mv, Nv = a.shape[0], w.shape[0]
@@ -287,10 +310,12 @@ def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0):
     qh = q_host(qa)
     assert all((g[rows] == o).all() for g, o in zip(qh, qo))
     rows = np.unique(np.concatenate([np.arange(min(64, Nv)), rn[:256]]))
-    qo = oracle.quantize(w[rows], oracle.MXFP4P)
+    qo = oracle.quantize(w[rows], FMT[w_fmt][1])
     qwh = q_host(qw)
-    assert all((g[rows] == o).all() for g, o in zip(qwh, qo))
-    ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, oracle.MXFP4P, rm, rn)
+    assert all((g[rows] == o).all() for g, o in zip(qwh[:2], qo[:2]))
+    if w_fmt == "mxfp4p":
+        assert (qwh[2][rows] == qo[2]).all()
+    ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, FMT[w_fmt][1], rm, rn)
     got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
     assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
     assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
@@ -307,6 +332,12 @@ def test_gemm_full_size_prefill_attn_sampled():
 
 def test_gemm_full_size_prefill_mlp_sampled():
     _sampled_check("prefill_mlp")
+
+
+def test_gemm_full_size_plain_mxfp4_weights_sampled():
+    _sampled_check("prefill_mlp", w_fmt="mxfp4")
+    _sampled_check("decode", w_fmt="mxfp4")
+    _sampled_check("prefill_attn", wname="wkv", w_fmt="mxfp4")
 
 
 def test_gemm_full_size_70b_shaped_sampled():
