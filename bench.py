@@ -211,6 +211,37 @@ def main():
     gemm_w4_ms = timed_gemm(img_w4, mxp.IMAGE_E2M1)
     del img_w4
 
+    # Decode configuration (8 x 4096 activations, 4096 x 4096 weights): activations quantized on the fly, prepacked
+    # weights, 20 calls back to back.  Bound by reading the weight image once; at this size launch latency dominates.
+    def timed_decode():
+        a_d, ws_d = synth.make("decode")
+        Ad, Wd = to_dev(a_d), to_dev(next(iter(ws_d.values())))
+        Md, Kd = Ad.shape
+        Nd = Wd.shape[0]
+        out = {}
+        for name, fmt_w in (("mxfp4p_weights", mxp.MXFP4P), ("mxfp4_weights", mxp.MXFP4)):
+            qwd = mxp.quantize(Wd, fmt_w)
+            kind = mxp.IMAGE_E2M1 if fmt_w == mxp.MXFP4 else mxp.IMAGE_E2M3
+            img = mxp.prepack_e2m1(qwd) if fmt_w == mxp.MXFP4 else mxp.prepack(qwd, fmt_w)
+            Dd = torch.empty((Md, Nd), dtype=torch.float32, device=dev)
+            wsd = torch.empty(max(mxp.gemm_bf16a_workspace_bytes(Md, Kd), 16), dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                mxp.gemm_bf16a(Ad, mxp.MXFP4P, img, Nd, out=Dd, workspace=wsd, b_kind=kind)
+            torch.cuda.synchronize()
+            ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev2[0].record()
+            for _ in range(20):
+                mxp.gemm_bf16a(Ad, mxp.MXFP4P, img, Nd, out=Dd, workspace=wsd, b_kind=kind)
+            ev2[1].record()
+            torch.cuda.synchronize()
+            us = ev2[0].elapsed_time(ev2[1]) / 20 * 1e3
+            out[name] = {"us_per_call": us, "weight_image_GBps": img.numel() / us / 1e3,
+                         "frac_hbm": img.numel() / us / 1e3 / PEAK_HBM_GBPS}
+        out["shape"] = "A bf16 [%d x %d] quantized on the fly (one kernel) + split-K GEMM with W [%d x %d]" % (Md, Kd, Nd, Kd)
+        return out
+
+    decode = timed_decode()
+
     # Standalone quantize (canonical outputs only), launches queued back to back over rotating source copies whose
     # total exceeds the 256 MB Infinity Cache: the activation tensor (12 copies) and the weight matrix (3 copies).
     def timed_quantize(src_bits, copies, launches):
@@ -266,6 +297,7 @@ def main():
         "quantize_a_with_image_GBps": M * K * (2.5625 + 0.78125) / (stage_ms["quantize_a"] * 1e-3) / 1e9,
         "dequantize_GBps": dq_bytes / (stage_ms["dequantize"] * 1e-3) / 1e9,
         "prepack_w_GBps": pp_bytes(N) / (stage_ms["prepack_w"] * 1e-3) / 1e9,
+        "decode": decode,
         "gemm_only_TFLOPs": gemm_tflops,
         "gemm_back_to_back_TFLOPs": flops / (gemm_pp_ms * 1e-3) / 1e12,
         "gemm_a_mxfp4p_w_mxfp4_back_to_back_TFLOPs": flops / (gemm_w4_ms * 1e-3) / 1e12,

@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
   const uint32_t nbytes = (uint32_t)nt * kTileBytes;
   for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
-    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+    MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
   if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
 }
 
