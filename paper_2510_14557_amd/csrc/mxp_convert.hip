@@ -156,6 +156,41 @@ __global__ void __launch_bounds__(256) dequantize_dense_kernel(const uint32_t* _
   }
 }
 
+// Dense fp32 destination: a lane takes 4 elements (2 bytes of codes -> one 16-byte store), so that every store
+// instruction of a wavefront writes 1 KiB contiguously; with 8 elements per lane its two 16-byte stores would each
+// cover every other 16 bytes of the wavefront's 2 KiB.  The decode is the 8-element one applied to the lane's half.
+template <bool PLUS, int U>
+__global__ void __launch_bounds__(256) dequantize_dense_f32_kernel(const uint16_t* __restrict__ elems16, const uint8_t* __restrict__ scales,
+                                                                   const uint8_t* __restrict__ bm_idx, int64_t nh,
+                                                                   float* __restrict__ dst) {
+  const uint32_t t = threadIdx.x, half = t & 1u, part = (t >> 1) & 3u;     // 8 lanes per block
+  constexpr int64_t kChunk = 256 * U;
+  const int64_t n_chunks = (nh + kChunk - 1) / kChunk;
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+    const int64_t h_base = c * kChunk;
+    const bool whole = h_base + kChunk <= nh;
+    uint32_t dw[U], sb[U], bm[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t h = h_base + u * 256 + t;
+      dw[u] = 0; sb[u] = 0; bm[u] = 64u;
+      if (whole || h < nh) {
+        dw[u] = (uint32_t)elems16[h] << (16u * half);
+        sb[u] = scales[h >> 3];
+        if (PLUS) bm[u] = bm_idx[h >> 3] & 31u;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t h = h_base + u * 256 + t;
+      uint32_t out[8];
+      decode_group<PLUS, false>(dw[u], sb[u], bm[u], part, out);
+      u32x4 v = {half ? out[4] : out[0], half ? out[5] : out[1], half ? out[6] : out[2], half ? out[7] : out[3]};
+      if (whole || h < nh) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + h * 4));
+    }
+  }
+}
+
 // 4 nibbles (16 bit) -> 4 six-bit codes (24 bit), code = nibble << 2.  Two multiplies spread the even and the odd
 // nibbles to their positions: bit offsets 4i -> 6i + 2.
 __device__ __forceinline__ uint32_t widen4(uint32_t h) {
@@ -318,10 +353,16 @@ extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const
     constexpr int U = 4;
     const int64_t want = (nq + 256 * U - 1) / (256 * U), cap = (int64_t)kNumCU * 16;
     const dim3 grid((unsigned)(want < cap ? want : cap));
-    if (plus && bf) hipLaunchKernelGGL((dequantize_dense_kernel<true, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
-    else if (plus) hipLaunchKernelGGL((dequantize_dense_kernel<true, false, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
-    else if (bf) hipLaunchKernelGGL((dequantize_dense_kernel<false, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
-    else hipLaunchKernelGGL((dequantize_dense_kernel<false, false, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    if (!bf) {
+      const int64_t nh = nq * 2, want4 = (nh + 256 * U - 1) / (256 * U);
+      const dim3 grid4((unsigned)(want4 < cap ? want4 : cap));
+      const uint16_t* e16 = reinterpret_cast<const uint16_t*>(elems);
+      if (plus) hipLaunchKernelGGL((dequantize_dense_f32_kernel<true, U>), grid4, dim3(256), 0, s, e16, scales, bm_idx, nh, static_cast<float*>(dst));
+      else hipLaunchKernelGGL((dequantize_dense_f32_kernel<false, U>), grid4, dim3(256), 0, s, e16, scales, bm_idx, nh, static_cast<float*>(dst));
+      return launch_status();
+    }
+    if (plus) hipLaunchKernelGGL((dequantize_dense_kernel<true, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    else hipLaunchKernelGGL((dequantize_dense_kernel<false, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
     return launch_status();
   }
   const int64_t want = (nq + 255) / 256, cap = (int64_t)kNumCU * 16;

@@ -186,6 +186,14 @@ def test_dequantize_bit_exact(fmt):
         assert (np.isnan(got) == nan).all()
         assert (got[~nan] == want[~nan]).all()
         assert (np.signbit(got[~nan]) == np.signbit(want[~nan])).all()
+    # sizes that end inside a chunk of the dense kernels, and more than one chunk per workgroup
+    for xs in (special_tensor(rows=37, K=160, seed=8), synth.activations(131, 4096 + 64, config_id=2, tensor_id=7, dtype="f32")):
+        qq = oracle.quantize(xs, FMT[fmt][1])
+        wq = oracle.dequantize(qq, FMT[fmt][1])
+        for dt in (torch.float32, torch.bfloat16):
+            got = mxp.dequantize(q_dev(qq), FMT[fmt][0], dt).float().cpu().numpy().astype(np.float64)
+            nan = np.isnan(wq)
+            assert (np.isnan(got) == nan).all() and (got[~nan] == wq[~nan]).all()
     # strided destination
     out = torch.full((64, 320), 9.0, device="cuda")
     mxp.dequantize(q_dev((e, s, i)), FMT[fmt][0], out=out[:, :256])
