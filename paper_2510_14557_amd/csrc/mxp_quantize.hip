@@ -466,18 +466,15 @@ static void quantize_dispatch(const void* src, int src_dtype, int64_t nbk, int64
   else hipLaunchKernelGGL((quantize_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
 }
 
-// Shared with the on-the-fly GEMM entry point.  Launch shape from measurement: tensors of a few tens of MB finish
-// fastest with 4 independent loads per lane on 8 workgroups per CU; large tensors stream best with 2 loads per lane
-// on 32 workgroups per CU (5.6 TB/s on 470 MB of bf16).
+// Launch shape from a sweep over loads per lane (2, 4, 8) and resident workgroups per CU (4 .. 32): 4 independent
+// 16-byte loads per lane on up to 32 workgroups per CU is the best or within 1 % of it for every size tried
+// (bf16: 6.0-6.2 TB/s on 128-235 MB tensors, 10 us for 32 MiB; fp32: 5.4 TB/s).
 int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
                     uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
   const int64_t nbk = K / kBlock;
   const int64_t nq = rows * nbk * 4;
   const int dense = (ld_src == K) ? 1 : 0;
-  if (nq >= (int64_t)4 << 20)
-    quantize_dispatch<2>(src, src_dtype, nbk, ld_src, dense, nq, fmt, (int64_t)kNumCU * 32, elems, scales, bm_idx, stream);
-  else
-    quantize_dispatch<4>(src, src_dtype, nbk, ld_src, dense, nq, fmt, (int64_t)kNumCU * 8, elems, scales, bm_idx, stream);
+  quantize_dispatch<4>(src, src_dtype, nbk, ld_src, dense, nq, fmt, (int64_t)kNumCU * 32, elems, scales, bm_idx, stream);
   return launch_status();
 }
 
