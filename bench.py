@@ -75,8 +75,10 @@ def cpu_baseline(a_bits, w_bits, budget_s=40.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # The chip needs about 40 ms of sustained load before its clocks settle (step time falls from ~220 us over the first
+    # 20 steps to a steady ~180 us after ~200): the defaults time steady state.  500 steps are about 0.1 s of GPU work.
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
