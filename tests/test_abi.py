@@ -59,6 +59,22 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_prepack(p, p, p, 1, 64, 64, p, 16, None) == -6
     assert L.mxp_gemm(64, 64, 48, p, p, p, 1, p, p, p, 1, p, mxp.F32, 64, p, need, None) == -2
     assert L.mxp_gemm(64, 64, 64, p, p, p, 1, p, p, p, 1, p, mxp.F32, 32, p, need, None) == -2
+    # the one-pass conversion: image required, canonical arrays all or none, image buffer size checked
+    big = mxp.image_bytes(4, 64)
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4P, None, None, None, None, big, None) == -1
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4P, p, None, None, p, big, None) == -1
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4P, p, p, None, p, big, None) == -1
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4P, None, None, None, p, big - 1, None) == -6
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 48, 48, mxp.MXFP4P, None, None, None, p, big, None) == -2
+    assert L.mxp_quantize_image(p, 3, 4, 64, 64, mxp.MXFP4P, None, None, None, p, big, None) == -4
+    assert L.mxp_quantize_image(odd, mxp.BF16, 4, 64, 64, mxp.MXFP4P, None, None, None, p, big, None) == -3
+    # image kinds
+    assert L.mxp_prepack_e2m1(p, p, 64, 64, p, 16, None) == -6
+    assert L.mxp_prepack_e2m1(p, None, 64, 64, p, 1 << 20, None) == -1
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, p, 2, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, None, mxp.IMAGE_E2M1, p, mxp.F32, 64, None) == -1
+    assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 5, p, mxp.F32, 64, p, 1 << 20, None) == -5
+    assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 0, p, mxp.F32, 64, p, 16, None) == -6
     # empty problems are fine and launch nothing
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
     assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0
@@ -70,3 +86,7 @@ def test_image_geometry():
     assert mxp.image_bytes(1, 32) == mxp.image_bytes(256, 128)
     assert mxp.image_bytes(4096, 4096) == 4096 * 128 * 25
     assert mxp.gemm_workspace_bytes(4096, 4096, 4096) == 2 * 4096 * 128 * 25
+    # a plain MXFP4 operand kept in 4-bit codes: 16 bytes per block + 1 scale byte
+    assert mxp.image_bytes_e2m1(256, 128) == 256 * 4 * 16 + 256 * 4
+    assert mxp.image_bytes_e2m1(4096, 4096) == 4096 * 128 * 17
+    assert mxp.gemm_bf16a_workspace_bytes(4096, 4096) == 4096 * 128 * 25
