@@ -26,6 +26,16 @@
  *   - nibble order: element 2j in the low nibble, 2j+1 in the high nibble of byte j
  *   - BM nibble = sign | m2 m1 m0 (m2 m1 sit in the former exponent bits)
  *
+ * MX++ (Sec. 4.3): the NBMs get their own, smaller-or-equal shared exponent
+ *     e = max2 floor(log2|x|) - e_max + 1,   shared_exp_new = CLIP(e, {shared_exp - 7, shared_exp}),
+ * and delta = shared_exp - shared_exp_new goes into the 3 reserved bits of the index byte.  Readings:
+ *   - max2 ("second-largest exponent") = the largest exponent among the NBMs, i.e. all elements but the BM index;
+ *     it equals the BM's exponent when another element shares it, which is the case the upper clip bound is for
+ *   - NBMs all zero or below the fp32 normal range: no exponent to take, the lower clip bound applies
+ *   - delta is also limited to (scale byte - 1), so that the NBM scale stays an E8M0 number >= 2^-126
+ *   - NBM rounding and saturation as in MXFP4 (saturation can only happen when delta = 0)
+ *   - index byte = index | delta << 5; BM, flush and NaN rules as for MXFP4+
+ *
  * All arithmetic that decides a code is done on exact values (scaling by a power of two is exact in
  * double), so no rounding happens before the one rounding step that defines the format.
  */
@@ -38,6 +48,7 @@
 #define MXO_EMAX 2          /* E2M1: exponent field 11b, bias 1  (Sec. 2) */
 #define MXO_FMT_MXFP4 0
 #define MXO_FMT_MXFP4P 1
+#define MXO_FMT_MXFP4PP 2
 
 static float bf16_to_f32(uint16_t h) {
   uint32_t u = (uint32_t)h << 16;
@@ -111,16 +122,30 @@ void mxo_encode_block(const float *x, int fmt, uint8_t *elems, uint8_t *scale, u
   if (e <= -127 + MXO_EMAX) { *scale = 0; return; }
   int shared_exp = e - MXO_EMAX;                        /* Eq. 1 */
   *scale = (uint8_t)(shared_exp + 127);                 /* E8M0, bias 127 */
+  int delta = 0;
+  if (fmt == MXO_FMT_MXFP4PP) {                         /* Sec. 4.3: shared exponent of the NBMs */
+    double a2 = 0.0;                                    /* largest NBM magnitude */
+    for (int i = 0; i < MXO_BLOCK; ++i)
+      if (i != idx && fabs((double)x[i]) > a2) a2 = fabs((double)x[i]);
+    int lo = shared_exp - 7, enew = lo;
+    if (a2 > 0.0 && floor_log2(a2) >= -126) {
+      enew = floor_log2(a2) - MXO_EMAX + 1;
+      if (enew < lo) enew = lo;
+      if (enew > shared_exp) enew = shared_exp;
+    }
+    delta = shared_exp - enew;
+    if (delta > (int)*scale - 1) delta = (int)*scale - 1;
+  }
+  const int plus = (fmt == MXO_FMT_MXFP4P || fmt == MXO_FMT_MXFP4PP);
   for (int i = 0; i < MXO_BLOCK; ++i) {
-    double v = ldexp((double)x[i], -shared_exp);        /* x / X, exact */
     unsigned s = signbit(x[i]) ? 8u : 0u;
     unsigned code;
-    if (fmt == MXO_FMT_MXFP4P && i == idx) code = bm_code(fabs(v));
-    else code = e2m1_code(fabs(v));
+    if (plus && i == idx) code = bm_code(fabs(ldexp((double)x[i], -shared_exp)));          /* BM / X, exact */
+    else code = e2m1_code(fabs(ldexp((double)x[i], -(shared_exp - delta))));               /* NBM / X_new */
     unsigned nib = s | code;
     elems[i >> 1] |= (uint8_t)((i & 1) ? (nib << 4) : nib);
   }
-  if (fmt == MXO_FMT_MXFP4P) *bmidx = (uint8_t)idx;     /* bits [4:0]; reserved bits [7:5] = 0 */
+  if (plus) *bmidx = (uint8_t)(idx | (delta << 5));     /* bits [4:0] index; bits [7:5] delta (0 for MXFP4+) */
 }
 
 /* Decode one block to doubles (Eq. 2). */
@@ -134,7 +159,8 @@ void mxo_decode_block(const uint8_t *elems, uint8_t scale, uint8_t bmidx, int fm
     return;
   }
   int shared_exp = (int)scale - 127;
-  int bm = (fmt == MXO_FMT_MXFP4P) ? (bmidx & 31) : -1;
+  int bm = (fmt == MXO_FMT_MXFP4P || fmt == MXO_FMT_MXFP4PP) ? (bmidx & 31) : -1;
+  int delta = (fmt == MXO_FMT_MXFP4PP) ? (bmidx >> 5) : 0;        /* MXFP4+ ignores the reserved bits */
   for (int i = 0; i < MXO_BLOCK; ++i) {
     unsigned nib = (i & 1) ? (elems[i >> 1] >> 4) : (elems[i >> 1] & 15u);
     double sgn = (nib & 8u) ? -1.0 : 1.0;
@@ -147,7 +173,7 @@ void mxo_decode_block(const uint8_t *elems, uint8_t scale, uint8_t bmidx, int fm
       if (ee == 0) E = 0.5 * (double)m;                               /* subnormal */
       else E = ldexp(1.0, (int)ee - 1) * (1.0 + (double)m / 2.0);     /* 2^(e_i - b) * m_i, b = 1 */
     }
-    out[i] = sgn * ldexp(E, shared_exp);
+    out[i] = sgn * ldexp(E, i == bm ? shared_exp : shared_exp - delta);
   }
 }
 

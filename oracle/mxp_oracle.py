@@ -8,6 +8,7 @@ from . import build as _build
 
 MXFP4 = 0
 MXFP4P = 1
+MXFP4PP = 2
 
 _lib = None
 

@@ -443,3 +443,125 @@ def test_gemm_transposed_operand_mistake_would_show():
     for m in range(3):
         for n in range(5):
             assert D[m, n] == pytest.approx(float(np.dot(da[m], db[n])), rel=1e-13)
+
+
+# ------------------------------------------------------------------ MX++ (Sec. 4.3): own shared exponent for the NBMs
+from oracle import MXFP4PP  # noqa: E402
+
+
+def test_mxpp_paper_example():
+    """The worked example of Sec. 4.3: BM scale 2^1, largest NBM 0.99 -> e = -2; -0.39 -> -1.56 -> -1.5; 0.99 -> 3.96."""
+    g = golden()
+    x = block({5: 9.0, 6: g["nbm_example"], 7: 0.99})
+    e, s, i = oracle.encode_block(x, MXFP4PP)
+    assert s - 127 == g["nbm_example_shared_exp"]                       # the BM's scale is that of MXFP4+
+    delta = i >> 5
+    assert (i & 31) == 5 and delta < 2 ** g["mxpp_delta_bits"]
+    assert (s - 127) - delta == g["mxpp_example_e"] == g["nbm_example_shared_exp_new"]
+    d = oracle.decode_block(e, s, i, MXFP4PP)
+    xnew = 2.0 ** g["mxpp_example_e"]
+    assert d[6] / xnew == g["nbm_example_code_value_new"]               # -1.5
+    assert abs(0.99 / xnew - g["scaled_0p99_with_offset"]) < 1e-9 and d[7] / xnew == 4.0   # 3.96 stays in range -> 4
+    assert d[5] == 9.0
+    # without the +1 offset the scale would be 2^-3 and 0.99 would saturate (7.92 -> 6): the encoder must not do that
+    assert d[7] != g["saturated_to"] * 2.0 ** g["shared_exp_for_bm_0p99"]
+    # the same block in MXFP4+ loses -0.39 entirely
+    e1, s1, i1 = oracle.encode_block(x, MXFP4P)
+    assert oracle.decode_block(e1, s1, i1, MXFP4P)[6] == g["nbm_example_decoded"]
+
+
+def mxpp_delta_by_definition(x):
+    """delta from the stated purpose of the rule: the finest NBM scale, at most 7 steps below the BM's, that keeps the
+    largest NBM below twice the top binade start (scaled value < 4, so rounding cannot saturate)."""
+    a = np.abs(np.asarray(x, np.float64))
+    idx = int(np.argmax(a))
+    se = int(np.floor(np.log2(a[idx]))) - 2
+    a2 = np.delete(a, idx).max()
+    best = 0
+    for d in range(0, 8):
+        if a2 * 2.0 ** (d - se) < 4.0 and se + 127 - d >= 1 and a2 >= 2.0 ** -126:
+            best = d
+    if a2 < 2.0 ** -126:                                # nothing to scale: the lower clip bound (limited by the E8M0 range)
+        best = min(7, se + 127 - 1)
+    return idx, se, best
+
+
+def test_mxpp_matches_definition_by_search_and_keeps_the_bm_of_mxfp4p():
+    rng = np.random.default_rng(77)
+    for trial in range(600):
+        kind = trial % 5
+        x = rng.standard_normal(32).astype(np.float32)
+        if kind == 1:
+            x[rng.integers(32)] *= np.float32(2.0 ** rng.integers(1, 12))          # one outlier of any size
+        elif kind == 2:
+            x = (rng.integers(-32, 33, 32) / 8.0).astype(np.float32)               # ties everywhere
+        elif kind == 3:
+            x = np.zeros(32, np.float32)
+            x[rng.integers(32)] = rng.standard_normal() * 100                      # lone BM, NBMs all zero
+        elif kind == 4:
+            x *= np.float32(2.0 ** rng.integers(-125, -110))                       # near the bottom of the E8M0 range
+        if np.abs(x).max() == 0 or np.floor(np.log2(np.abs(x).max())) <= -125:
+            continue
+        e, s, i = oracle.encode_block(x, MXFP4PP)
+        e1, s1, i1 = oracle.encode_block(x, MXFP4P)
+        idx, se, delta = mxpp_delta_by_definition(x)
+        assert s == s1 == se + 127 and (i & 31) == i1 == idx
+        assert (i >> 5) == delta, (trial, x, i >> 5, delta)
+        nb, nb1 = nibbles(e), nibbles(e1)
+        assert nb[idx] == nb1[idx]                                                 # BM code untouched (Sec. 4.3)
+        for k in range(32):                                                        # NBMs: nearest point of the finer grid
+            if k == idx:
+                continue
+            want = nearest_code(abs(float(x[k])) / 2.0 ** (se - delta), E2M1_GRID)
+            assert (nb[k] & 7) == want and (nb[k] >> 3) == int(np.signbit(x[k])), (trial, k)
+        if delta > 0:
+            assert (np.delete(nb, idx) & 7).max() <= 6                             # no NBM saturates (code 6 = 4.0)
+        if delta == 0:
+            assert (nb == nb1).all()                                               # then it IS the MXFP4+ block
+        # every element at least as close as in MXFP4+
+        d2, d1 = oracle.decode_block(e, s, i, MXFP4PP), oracle.decode_block(e1, s1, i1, MXFP4P)
+        assert (np.abs(d2 - x.astype(np.float64)) <= np.abs(d1 - x.astype(np.float64)) + 0.0).all(), (trial, x)
+
+
+def test_mxpp_clip_bounds_equivariance_and_decode():
+    # second-largest element in the BM's binade: e exceeds shared_exp, clipped to it (delta = 0)
+    e, s, i = oracle.encode_block(block({0: 7.0, 1: 4.5, 2: 0.3}), MXFP4PP)
+    assert i >> 5 == 0
+    # NBMs 2^9 or more below the BM: clipped at shared_exp - 7
+    e, s, i = oracle.encode_block(block({3: 1024.0, 9: 0.75}), MXFP4PP)
+    assert i >> 5 == 7 and (i & 31) == 3
+    assert oracle.decode_block(e, s, i, MXFP4PP)[9] == 1.0                        # 0.75 / 2^(8-7) = 0.375 -> code 0.5 -> 1.0
+    e1, s1, i1 = oracle.encode_block(block({3: 1024.0, 9: 0.75}), MXFP4P)
+    assert oracle.decode_block(e1, s1, i1, MXFP4P)[9] == 0.0                      # 0.75 / 2^8 is lost without MX++
+    # scale byte 1 leaves no room below: delta limited by the E8M0 range
+    e, s, i = oracle.encode_block(block({0: 1.5 * 2.0 ** -124, 1: 2.0 ** -126}), MXFP4PP)
+    assert s == 1 and i >> 5 == 0
+    # power-of-two equivariance and sign symmetry carry over
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(32).astype(np.float32)
+    x[11] *= 300
+    e, s, i = oracle.encode_block(x, MXFP4PP)
+    e2, s2, i2 = oracle.encode_block(x * np.float32(2.0 ** 9), MXFP4PP)
+    assert (e == e2).all() and s2 == s + 9 and i2 == i
+    e3, s3, i3 = oracle.encode_block(-x, MXFP4PP)
+    assert (nibbles(e3) == (nibbles(e) ^ 8)).all() and s3 == s and i3 == i
+    # decoded values are fixed points of the encoder
+    d = oracle.decode_block(e, s, i, MXFP4PP).astype(np.float32)
+    e4, s4, i4 = oracle.encode_block(d, MXFP4PP)
+    assert (oracle.decode_block(e4, s4, i4, MXFP4PP) == d).all()
+    # MXFP4+ ignores the reserved bits, MXFP4++ applies them to the NBMs only
+    d_plus = oracle.decode_block(e, s, i, MXFP4P)
+    k = i & 31
+    assert d_plus[k] == d[k] and np.allclose(np.delete(d_plus, k), np.delete(d, k) * 2.0 ** (i >> 5))
+
+
+def test_mxpp_tensor_entry_points_and_mse():
+    a = synth.activations(64, 512, config_id=2, tensor_id=0, dtype="f32")
+    q1, q2 = oracle.quantize(a, MXFP4P), oracle.quantize(a, MXFP4PP)
+    assert (q1[1] == q2[1]).all() and ((q2[2] & 31) == q1[2]).all()
+    d1, d2 = oracle.dequantize(q1, MXFP4P), oracle.dequantize(q2, MXFP4PP)
+    err1, err2 = ((d1 - a) ** 2).mean(), ((d2 - a) ** 2).mean()
+    assert err2 < err1                                                          # Sec. 4.3 / Sec. 8: finer NBM grid
+    qb = oracle.quantize(synth.f32_to_bf16_bits(a), MXFP4PP)
+    a_b = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(a))
+    assert all((x == y).all() for x, y in zip(qb, oracle.quantize(a_b, MXFP4PP)))
