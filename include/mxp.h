@@ -39,6 +39,9 @@ extern "C" {
 /* block formats */
 #define MXP_FMT_MXFP4 0  /* plain OCP MXFP4 (Sec. 2) */
 #define MXP_FMT_MXFP4P 1 /* MXFP4+ (Sec. 4)          */
+#define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion and de-conversion only; the image and product entry points
+                           * return MXP_ERR_UNSUPPORTED for it (its BM and NBMs have different scales, which one
+                           * block-scaled MFMA operand cannot carry) */
 
 /* status codes */
 #define MXP_OK 0
@@ -57,6 +60,10 @@ extern "C" {
  * x / 2^shared_exp rounded to E2M1 (nearest, ties to even, saturating at 6); for MXFP4+ the BM keeps three mantissa
  * bits, m = RNE(2|x|/2^shared_exp - 8) saturating at 7 (the shared scale is never altered).  A block holding a
  * NaN or Inf gets scale byte 255, nibbles 0, index 0.
+ * MXFP4++ (Sec. 4.3) keeps the BM, scale and index of MXFP4+ and scales the other elements by 2^(shared_exp - delta)
+ * instead: shared_exp - delta = CLIP(e, {shared_exp - 7, shared_exp}) with e = (largest exponent among the
+ * non-BM elements) - 2 + 1; no non-BM element (all zero or below 2^-126) means the lower bound; delta is also kept
+ * <= scale byte - 1 so that the finer scale stays >= 2^-126.  delta is stored in bits 7:5 of the index byte.
  * elems/scales/bm_idx are dense canonical arrays (see top).  bm_idx may be NULL for MXP_FMT_MXFP4. */
 int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                  uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream);
@@ -68,7 +75,9 @@ int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int64_t K, int6
 
 /* De-conversion (Eq. 2): dst[r][k] = (-1)^s * 2^shared_exp * E, with E = 2^e_max * 1.mmm for the BM position of an
  * MXFP4+ block and the E2M1 value otherwise.  Scale byte 0 gives zeros (tested before the BM branch), 255 gives NaN.
- * Every result is exact in both output dtypes.  dst is [rows][K] with row stride ld_dst. */
+ * For MXFP4++ the non-BM elements use 2^(shared_exp - delta), delta = index byte bits 7:5 (MXFP4+ ignores those bits).
+ * Every result is exact in both output dtypes (for MXFP4++ bytes with scale byte - delta < 1, which no quantizer
+ * writes, only the fp32 output is exact).  dst is [rows][K] with row stride ld_dst. */
 int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt,
                    int64_t rows, int64_t K, void* dst, int dst_dtype, int64_t ld_dst, void* stream);
 

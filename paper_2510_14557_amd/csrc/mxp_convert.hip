@@ -12,14 +12,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // Magnitude of an E2M1 code in units of X/2: {0, .5, 1, 1.5, 2, 3, 4, 6} * 2  -> one nibble each.
 constexpr uint32_t kE2M1TimesTwo = 0xC8643210u;
 
-// fp32 bit pattern of  (-1)^sign * M * 2^(sbyte - 128)  for 1 <= M <= 15, 1 <= sbyte <= 254, built from integer
-// fields so that the one subnormal result (M = 1, sbyte = 1 -> 2^-127) does not depend on the float mode.
-__device__ __forceinline__ uint32_t make_f32(uint32_t sign, uint32_t M, uint32_t sbyte) {
-  const uint32_t p = 31u - (uint32_t)__builtin_clz(M);
-  const uint32_t biased = sbyte - 1u + p;
-  const uint32_t frac = (M << (23u - p)) & 0x7FFFFFu;
-  uint32_t bits = biased == 0u ? 0x00400000u : ((biased << 23) | frac);
-  if (biased >= 255u) bits = 0x7F800000u;                // only reachable with scale bytes a quantizer never writes
+// fp32 bit pattern of  (-1)^sign * M * 2^(sbyte - 128)  for 1 <= M <= 15, -6 <= sbyte <= 254, built from integer
+// fields so that subnormal results (M = 1, sbyte = 1 -> 2^-127; lower still for MXFP4++ bytes no quantizer writes) do
+// not depend on the float mode: below the normal range the pattern is the value in units of 2^-149.
+__device__ __forceinline__ uint32_t make_f32(uint32_t sign, uint32_t M, int sbyte) {
+  const int p = 31 - __builtin_clz(M);
+  const int biased = sbyte - 1 + p;
+  const uint32_t frac = (M << (23 - p)) & 0x7FFFFFu;
+  uint32_t bits = biased <= 0 ? (M << (sbyte + 21)) : (((uint32_t)biased << 23) | frac);
+  if (biased >= 255) bits = 0x7F800000u;                 // only reachable with scale bytes a quantizer never writes
   return (sign << 31) | bits;
 }
 
@@ -31,14 +32,18 @@ typedef float v2f __attribute__((ext_vector_type(2)));
 // that holds the BM overwrites that one element with 2^e_max * 1.mmm * X (Eq. 2, first case).  Blocks whose results
 // can be subnormal or special (scale byte 0, 1, 255) take the integer path, which does not depend on the float mode.
 // out: fp32 patterns, or (OUT_BF16) 4 packed pairs in out[0..3].
+// `bm` = index byte & 31 (64 for plain MXFP4); `delta` = bits 7:5 of the index byte for MXFP4++ (Sec. 4.3: the NBMs
+// are scaled by 2^(shared_exp - delta), the BM by 2^shared_exp), else 0.
 template <bool PLUS, bool OUT_BF16>
-__device__ __forceinline__ void decode_group(uint32_t dw, uint32_t sbyte, uint32_t bm, uint32_t part, uint32_t (&out)[8]) {
+__device__ __forceinline__ void decode_group(uint32_t dw, uint32_t sbyte, uint32_t bm, uint32_t part, uint32_t (&out)[8],
+                                             uint32_t delta = 0) {
   const bool mine = PLUS && (bm >> 3) == part;       // this lane holds the BM
   const uint32_t pos = bm & 7u;
-  if (sbyte >= 2u && sbyte != 255u) {
-    const float X = __uint_as_float(sbyte << 23);
+  if (sbyte >= 2u + delta && sbyte != 255u) {
+    const float X = __uint_as_float((sbyte - delta) << 23);          // NBM scale
+    const float XB = __uint_as_float(sbyte << 23);                   // BM scale
     const uint32_t nib = (dw >> (4u * pos)) & 15u;
-    const float bmv = __uint_as_float(((nib & 8u) << 28) | __float_as_uint((float)(8u + (nib & 7u)) * (X * 0.5f)));
+    const float bmv = __uint_as_float(((nib & 8u) << 28) | __float_as_uint((float)(8u + (nib & 7u)) * (XB * 0.5f)));
     if (OUT_BF16) {
       union { v2bf v; uint32_t u; } c0, c1, c2, c3;
       c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw, X, 0);
@@ -71,9 +76,10 @@ __device__ __forceinline__ void decode_group(uint32_t dw, uint32_t sbyte, uint32
       const uint32_t nib = (dw >> (4 * i)) & 15u;
       const uint32_t code = nib & 7u;
       uint32_t M = (kE2M1TimesTwo >> (4u * code)) & 15u;           // ordinary element: 2^(e-b) * m   (Eq. 2, second case)
-      if (mine && pos == (uint32_t)i) M = 8u + code;               // BM: 2^e_max * 1.mmm           (Eq. 2, first case)
+      int sb = (int)sbyte - (int)delta;
+      if (mine && pos == (uint32_t)i) { M = 8u + code; sb = (int)sbyte; }   // BM: 2^e_max * 1.mmm   (Eq. 2, first case)
       uint32_t bits = (nib >> 3) << 31;
-      if (M != 0u) bits = make_f32(nib >> 3, M, sbyte);
+      if (M != 0u) bits = make_f32(nib >> 3, M, sb);
       if (sbyte == 0u) bits = 0u;                                  // reserved all-zero code, tested before anything else
       if (sbyte == 255u) bits = 0x7FC00000u;
       f[i] = bits;
@@ -102,7 +108,7 @@ __device__ __forceinline__ void store_group(void* __restrict__ dst, int64_t off,
 }
 
 // General destination (row stride ld): one group per lane and grid step.
-template <bool PLUS, bool OUT_BF16>
+template <int MODE, bool OUT_BF16>
 __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                          const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld,
                                                          int64_t nq, void* __restrict__ dst) {
@@ -112,9 +118,9 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restr
     const int64_t g = q >> 2;
     const uint32_t part = (uint32_t)(q & 3);
     const uint32_t sbyte = scales[g];
-    const uint32_t bm = PLUS ? (uint32_t)(bm_idx[g] & 31u) : 64u;
+    const uint32_t ib = MODE >= 1 ? (uint32_t)bm_idx[g] : 64u;
     uint32_t out[8];
-    decode_group<PLUS, OUT_BF16>(dw, sbyte, bm, part, out);
+    decode_group<(MODE >= 1), OUT_BF16>(dw, sbyte, MODE >= 1 ? ib & 31u : 64u, part, out, MODE == 2 ? ib >> 5 : 0u);
     const int64_t row = g / nbk;
     store_group<OUT_BF16>(dst, row * ld + (g - row * nbk) * 32 + part * 8, out);
   }
@@ -122,7 +128,7 @@ __global__ void __launch_bounds__(256) dequantize_kernel(const uint32_t* __restr
 
 // Dense destination (row stride = K): the tensor is one run of nq groups.  A workgroup walks chunks of 256 * U groups;
 // all loads of a chunk are issued before the first decode, and whole chunks run without bounds tests.
-template <bool PLUS, bool OUT_BF16, int U>
+template <int MODE, bool OUT_BF16, int U>
 __global__ void __launch_bounds__(256) dequantize_dense_kernel(const uint32_t* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                                const uint8_t* __restrict__ bm_idx, int64_t nq,
                                                                void* __restrict__ dst) {
@@ -143,14 +149,14 @@ __global__ void __launch_bounds__(256) dequantize_dense_kernel(const uint32_t* _
       if (whole || q_base + ql < nq) {
         dw[u] = __builtin_nontemporal_load(e_in + ql);
         sb[u] = s_in[ql >> 2];
-        if (PLUS) bm[u] = i_in[ql >> 2] & 31u;
+        if (MODE >= 1) bm[u] = i_in[ql >> 2];
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t ql = u * 256 + t;
       uint32_t out[8];
-      decode_group<PLUS, OUT_BF16>(dw[u], sb[u], bm[u], part, out);
+      decode_group<(MODE >= 1), OUT_BF16>(dw[u], sb[u], MODE >= 1 ? bm[u] & 31u : 64u, part, out, MODE == 2 ? bm[u] >> 5 : 0u);
       if (whole || q_base + ql < nq) store_group<OUT_BF16>(dst, (q_base + ql) * 8, out);
     }
   }
@@ -159,7 +165,7 @@ __global__ void __launch_bounds__(256) dequantize_dense_kernel(const uint32_t* _
 // Dense fp32 destination: a lane takes 4 elements (2 bytes of codes -> one 16-byte store), so that every store
 // instruction of a wavefront writes 1 KiB contiguously; with 8 elements per lane its two 16-byte stores would each
 // cover every other 16 bytes of the wavefront's 2 KiB.  The decode is the 8-element one applied to the lane's half.
-template <bool PLUS, int U>
+template <int MODE, int U>
 __global__ void __launch_bounds__(256) dequantize_dense_f32_kernel(const uint16_t* __restrict__ elems16, const uint8_t* __restrict__ scales,
                                                                    const uint8_t* __restrict__ bm_idx, int64_t nh,
                                                                    float* __restrict__ dst) {
@@ -177,14 +183,14 @@ __global__ void __launch_bounds__(256) dequantize_dense_f32_kernel(const uint16_
       if (whole || h < nh) {
         dw[u] = (uint32_t)elems16[h] << (16u * half);
         sb[u] = scales[h >> 3];
-        if (PLUS) bm[u] = bm_idx[h >> 3] & 31u;
+        if (MODE >= 1) bm[u] = bm_idx[h >> 3];
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t h = h_base + u * 256 + t;
       uint32_t out[8];
-      decode_group<PLUS, false>(dw[u], sb[u], bm[u], part, out);
+      decode_group<(MODE >= 1), false>(dw[u], sb[u], MODE >= 1 ? bm[u] & 31u : 64u, part, out, MODE == 2 ? bm[u] >> 5 : 0u);
       u32x4 v = {half ? out[4] : out[0], half ? out[5] : out[1], half ? out[6] : out[2], half ? out[7] : out[3]};
       if (whole || h < nh) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + h * 4));
     }
@@ -333,45 +339,54 @@ int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t row
 
 }  // namespace mxp
 
+namespace {
+template <int MODE>
+int dequantize_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, int64_t nbk,
+                      int64_t nq, void* dst, bool bf, int64_t ld_dst, hipStream_t s) {
+  using namespace mxp;
+  (void)rows;
+  const uint32_t* e32 = reinterpret_cast<const uint32_t*>(elems);
+  const int64_t cap = (int64_t)kNumCU * 16;
+  if (ld_dst == K) {
+    constexpr int U = 4;
+    if (!bf) {
+      const int64_t nh = nq * 2, want4 = (nh + 256 * U - 1) / (256 * U);
+      const dim3 grid4((unsigned)(want4 < cap ? want4 : cap));
+      hipLaunchKernelGGL((dequantize_dense_f32_kernel<MODE, U>), grid4, dim3(256), 0, s, reinterpret_cast<const uint16_t*>(elems), scales,
+                         bm_idx, nh, static_cast<float*>(dst));
+      return launch_status();
+    }
+    const int64_t want = (nq + 256 * U - 1) / (256 * U);
+    const dim3 grid((unsigned)(want < cap ? want : cap));
+    hipLaunchKernelGGL((dequantize_dense_kernel<MODE, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
+    return launch_status();
+  }
+  const int64_t want = (nq + 255) / 256;
+  const dim3 grid((unsigned)(want < cap ? want : cap));
+  if (bf) hipLaunchKernelGGL((dequantize_kernel<MODE, true>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
+  else hipLaunchKernelGGL((dequantize_kernel<MODE, false>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
+  return launch_status();
+}
+}  // namespace
+
 extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
                               int64_t K, void* dst, int dst_dtype, int64_t ld_dst, void* stream) {
   using namespace mxp;
-  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
   if (dst_dtype != MXP_F32 && dst_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
   if (rows == 0 || K == 0) return MXP_OK;
-  if (!elems || !scales || !dst || (fmt == MXP_FMT_MXFP4P && !bm_idx)) return MXP_ERR_NULL;
+  if (!elems || !scales || !dst || (fmt != MXP_FMT_MXFP4 && !bm_idx)) return MXP_ERR_NULL;
   if (ld_dst < K) return MXP_ERR_SHAPE;
   const int64_t esz = dst_dtype == MXP_BF16 ? 2 : 4;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (bm_idx && !aligned16(bm_idx)) || (ld_dst * esz) % 16 != 0)
     return MXP_ERR_ALIGN;
   const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const uint32_t* e32 = reinterpret_cast<const uint32_t*>(elems);
-  const bool plus = fmt == MXP_FMT_MXFP4P, bf = dst_dtype == MXP_BF16;
-  if (ld_dst == K) {
-    constexpr int U = 4;
-    const int64_t want = (nq + 256 * U - 1) / (256 * U), cap = (int64_t)kNumCU * 16;
-    const dim3 grid((unsigned)(want < cap ? want : cap));
-    if (!bf) {
-      const int64_t nh = nq * 2, want4 = (nh + 256 * U - 1) / (256 * U);
-      const dim3 grid4((unsigned)(want4 < cap ? want4 : cap));
-      const uint16_t* e16 = reinterpret_cast<const uint16_t*>(elems);
-      if (plus) hipLaunchKernelGGL((dequantize_dense_f32_kernel<true, U>), grid4, dim3(256), 0, s, e16, scales, bm_idx, nh, static_cast<float*>(dst));
-      else hipLaunchKernelGGL((dequantize_dense_f32_kernel<false, U>), grid4, dim3(256), 0, s, e16, scales, bm_idx, nh, static_cast<float*>(dst));
-      return launch_status();
-    }
-    if (plus) hipLaunchKernelGGL((dequantize_dense_kernel<true, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
-    else hipLaunchKernelGGL((dequantize_dense_kernel<false, true, U>), grid, dim3(256), 0, s, e32, scales, bm_idx, nq, dst);
-    return launch_status();
-  }
-  const int64_t want = (nq + 255) / 256, cap = (int64_t)kNumCU * 16;
-  const dim3 grid((unsigned)(want < cap ? want : cap));
-  if (plus && bf) hipLaunchKernelGGL((dequantize_kernel<true, true>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
-  else if (plus) hipLaunchKernelGGL((dequantize_kernel<true, false>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
-  else if (bf) hipLaunchKernelGGL((dequantize_kernel<false, true>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
-  else hipLaunchKernelGGL((dequantize_kernel<false, false>), grid, dim3(256), 0, s, e32, scales, bm_idx, nbk, ld_dst, nq, dst);
-  return launch_status();
+  const bool bf = dst_dtype == MXP_BF16;
+  if (fmt == MXP_FMT_MXFP4PP) return dequantize_launch<2>(elems, scales, bm_idx, rows, K, nbk, nq, dst, bf, ld_dst, s);
+  if (fmt == MXP_FMT_MXFP4P) return dequantize_launch<1>(elems, scales, bm_idx, rows, K, nbk, nq, dst, bf, ld_dst, s);
+  return dequantize_launch<0>(elems, scales, bm_idx, rows, K, nbk, nq, dst, bf, ld_dst, s);
 }
 
 extern "C" size_t mxp_image_bytes(int64_t rows, int64_t K) {
@@ -398,6 +413,7 @@ extern "C" int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
                            int64_t K, void* image, size_t image_bytes, void* stream) {
   using namespace mxp;
+  if (fmt == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
   if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
   if (rows == 0 || K == 0) return MXP_OK;

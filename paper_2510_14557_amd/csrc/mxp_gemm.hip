@@ -919,6 +919,7 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
                         int fmtA, const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB, void* D,
                         int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace mxp;
+  if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
   if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) || (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P)) return MXP_ERR_FORMAT;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
@@ -950,6 +951,7 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
                               const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd, void* workspace,
                               size_t workspace_bytes, void* stream) {
   using namespace mxp;
+  if (fmtA == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
   if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;

@@ -36,9 +36,14 @@ __device__ __forceinline__ uint32_t bm_mantissa(uint32_t frac23) {
 
 // One group = 8 consecutive elements of one block, held by one lane.  `part` = which quarter of the block.
 // Returns the packed dword of 8 nibbles; scale byte and index byte are returned in all four lanes of the quad.
-template <bool BF16, bool PLUS>
+// MODE: 0 = MXFP4, 1 = MXFP4+, 2 = MXFP4++ (Sec. 4.3: the NBMs are scaled by 2^(shared_exp - delta), where
+// shared_exp - delta = CLIP(largest NBM exponent - e_max + 1, {shared_exp - 7, shared_exp}), and delta goes into bits
+// 7:5 of the index byte; delta is also kept <= scale byte - 1 so that the NBM scale stays an E8M0 number).
+template <bool BF16, int MODE>
 __device__ __forceinline__ uint32_t encode_group(const uint32_t (&w)[8], int part, uint32_t& sbyte, uint32_t& idx) {
+  constexpr bool PLUS = MODE >= 1, PP = MODE == 2;
   uint32_t amax32;  // magnitude bits of the block maximum, as an fp32 pattern
+  uint32_t a2 = 0;  // (PP) magnitude bits of the largest element other than the BM
   if (BF16) {
     // key = magnitude(15 bit) << 16 | (31 - position): one unsigned max gives the maximum and, among equal
     // magnitudes, the lowest position.
@@ -55,6 +60,22 @@ __device__ __forceinline__ uint32_t encode_group(const uint32_t (&w)[8], int par
     k = umax(k, dpp_mov<kQuadSwap2>(k));
     amax32 = k & 0xFFFF0000u;
     idx = 31u - (k & 31u);
+    if (PP) {
+      // keys are unique (the position is part of them): the lane whose best key won leaves that element out
+      uint32_t k2 = 0;
+      const uint32_t off = (uint32_t)(3 - part) * 8u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t m = w[j] & 0x7FFF7FFFu;
+        const uint32_t klo = ((m << 16) | (uint32_t)(7 - 2 * j)) + off;
+        const uint32_t khi = ((m & 0xFFFF0000u) | (uint32_t)(6 - 2 * j)) + off;
+        k2 = umax(k2, klo == k ? 0u : klo);
+        k2 = umax(k2, khi == k ? 0u : khi);
+      }
+      k2 = umax(k2, dpp_mov<kQuadSwap1>(k2));
+      k2 = umax(k2, dpp_mov<kQuadSwap2>(k2));
+      a2 = k2 & 0xFFFF0000u;
+    }
   } else {
     uint32_t a[8];
 #pragma unroll
@@ -71,11 +92,28 @@ __device__ __forceinline__ uint32_t encode_group(const uint32_t (&w)[8], int par
     p = umin(p, dpp_mov<kQuadSwap2>(p));
     amax32 = mx;
     idx = p;
+    if (PP) {
+      uint32_t m2 = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) m2 = umax(m2, (uint32_t)(part * 8 + i) == p ? 0u : a[i]);
+      m2 = umax(m2, dpp_mov<kQuadSwap1>(m2));
+      m2 = umax(m2, dpp_mov<kQuadSwap2>(m2));
+      a2 = m2;
+    }
   }
   const uint32_t E = amax32 >> 23;                     // biased exponent of the BM = floor(log2) + 127
   const bool flush = E <= 2u;                          // floor(log2 BM) <= -127 + e_max      (Sec. 4.1)
   const bool nonfinite = E == 255u;
-  const float scale = __uint_as_float((E - 2u) << 23); // X = 2^shared_exp, shared_exp = floor(log2 BM) - e_max (Eq. 1)
+  uint32_t delta = 0;
+  if (PP) {
+    const uint32_t sb = E - 2u, E2 = a2 >> 23;                       // biased: BM scale; exponent of the largest NBM
+    const uint32_t lo = sb > 7u ? sb - 7u : 0u;                      // (flushed blocks are reset below)
+    uint32_t nb = E2 == 0u ? lo : umin(umax(E2 - 1u, lo), sb);       // biased shared_exp_new = E2 - 127 - e_max + 1 + 127
+    nb = umax(nb, 1u);
+    delta = sb - nb;
+  }
+  // X = 2^shared_exp, shared_exp = floor(log2 BM) - e_max (Eq. 1); the NBMs of MXFP4++ use 2^(shared_exp - delta)
+  const float scale = __uint_as_float((E - 2u - delta) << 23);
   uint32_t packed = 0;
   if (BF16) {
 #pragma unroll
@@ -102,6 +140,7 @@ __device__ __forceinline__ uint32_t encode_group(const uint32_t (&w)[8], int par
     packed = ((idx >> 3) == (uint32_t)part) ? repl : packed;
   }
   sbyte = E - 2u;
+  if (PP) idx |= delta << 5;
   if (flush || nonfinite) {
     packed = 0;
     idx = 0;
@@ -135,10 +174,11 @@ __device__ __forceinline__ void load_group(const void* __restrict__ src, int64_t
 
 // nq = number of 8-element groups (= 4 * blocks).  The loop is uniform per 16-lane row, so DPP exchanges never
 // read a lane that left the loop; lanes past the end compute on zeros and store nothing.
-template <bool BF16, bool PLUS, int U>
+template <bool BF16, int MODE, int U>
 __global__ void __launch_bounds__(256) quantize_kernel(const void* __restrict__ src, int64_t nbk, int64_t ld, int dense,
                                                        int64_t nq, uint32_t* __restrict__ elems,
                                                        uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
   const int part = threadIdx.x & 3;
   const int quad_in_row = (threadIdx.x & 15) >> 2;
   const int64_t stride = (int64_t)gridDim.x * 256;
@@ -160,7 +200,7 @@ __global__ void __launch_bounds__(256) quantize_kernel(const void* __restrict__ 
       const int64_t q = q0 + u * stride;
       if ((q & ~(int64_t)15) >= nq) break;
       uint32_t sbyte, idx;
-      const uint32_t packed = encode_group<BF16, PLUS>(w[u], part, sbyte, idx);
+      const uint32_t packed = encode_group<BF16, MODE>(w[u], part, sbyte, idx);
       if (q < nq) __builtin_nontemporal_store(packed, elems + q);
       // gather the four blocks of this 16-lane row into its lane 12
       uint32_t sv = (part == 0) ? (sbyte << (8 * quad_in_row)) : 0u;
@@ -190,9 +230,10 @@ __global__ void __launch_bounds__(256) quantize_kernel(const void* __restrict__ 
 // groups (U x 4 KiB of bf16, contiguous); lane t of the workgroup takes groups u * 256 + t of the chunk, so every
 // load, every element store and every scale / index dword store of a wavefront is one contiguous run.  Whole chunks
 // run without per-lane bounds tests; the last, partial chunk takes the checked path.
-template <bool BF16, bool PLUS, int U>
+template <bool BF16, int MODE, int U>
 __global__ void __launch_bounds__(256) quantize_dense_kernel(const void* __restrict__ src, int64_t nq, uint32_t* __restrict__ elems,
                                                              uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
   const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
   constexpr int64_t kChunk = 256 * U;
   const int64_t n_chunks = (nq + kChunk - 1) / kChunk;
@@ -228,7 +269,7 @@ __global__ void __launch_bounds__(256) quantize_dense_kernel(const void* __restr
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       uint32_t sbyte, idx;
-      const uint32_t packed = encode_group<BF16, PLUS>(w[u], (int)part, sbyte, idx);
+      const uint32_t packed = encode_group<BF16, MODE>(w[u], (int)part, sbyte, idx);
       // gather the four blocks of this 16-lane row into its lane 12
       uint32_t sv = (part == 0) ? (sbyte << (8 * quad_in_row)) : 0u;
       sv |= dpp_mov<kRowShr8>(sv);
@@ -263,10 +304,11 @@ __global__ void __launch_bounds__(256) quantize_dense_kernel(const void* __restr
 }
 
 // ---- K-strided source: one thread per block, 32 strided loads that are coalesced across the rows of a wavefront.
-template <bool BF16, bool PLUS>
+template <bool BF16, int MODE>
 __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
                                                          uint4* __restrict__ elems, uint8_t* __restrict__ scales,
                                                          uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1, PP = MODE == 2;
   const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t kb = blockIdx.y;
   if (r >= rows) return;
@@ -282,7 +324,18 @@ __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict_
 #pragma unroll
   for (int i = 31; i >= 0; --i) idx = ((x[i] & 0x7FFFFFFFu) == mx) ? (uint32_t)i : idx;
   const uint32_t E = mx >> 23;
-  const float scale = __uint_as_float((E - 2u) << 23);
+  uint32_t delta = 0;
+  if (PP) {                                                         // Sec. 4.3: finer scale for the NBMs
+    uint32_t m2 = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) m2 = umax(m2, (uint32_t)i == idx ? 0u : (x[i] & 0x7FFFFFFFu));
+    const uint32_t sb = E - 2u, E2 = m2 >> 23;
+    const uint32_t lo = sb > 7u ? sb - 7u : 0u;
+    uint32_t nb = E2 == 0u ? lo : umin(umax(E2 - 1u, lo), sb);
+    nb = umax(nb, 1u);
+    delta = sb - nb;
+  }
+  const float scale = __uint_as_float((E - 2u - delta) << 23);
   uint32_t out[4] = {0, 0, 0, 0};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -304,6 +357,7 @@ __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict_
     }
   }
   uint32_t sbyte = E - 2u;
+  if (PP) idx |= delta << 5;
   if (E <= 2u || E == 255u) {
     out[0] = out[1] = out[2] = out[3] = 0;
     idx = 0;
@@ -433,11 +487,11 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
 
 int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fmt, const uint8_t* elems,
                  const uint8_t* scales, const uint8_t* bm_idx) {
-  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
   if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
   if (rows == 0 || K == 0) return MXP_OK;
-  if (!src || !elems || !scales || (fmt == MXP_FMT_MXFP4P && !bm_idx)) return MXP_ERR_NULL;
+  if (!src || !elems || !scales || (fmt != MXP_FMT_MXFP4 && !bm_idx)) return MXP_ERR_NULL;
   if (!aligned16(src) || !aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
   return MXP_OK;
 }
@@ -446,24 +500,30 @@ int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fm
 
 namespace mxp {
 
+template <bool BF16, int MODE, int U>
+static void quantize_dispatch_mode(const void* src, int64_t nbk, int64_t ld_src, int dense, int64_t nq, int grid, uint32_t* e32,
+                                   uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
+  if (dense) hipLaunchKernelGGL((quantize_dense_kernel<BF16, MODE, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
+  else hipLaunchKernelGGL((quantize_kernel<BF16, MODE, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
+}
+
 template <int U>
 static void quantize_dispatch(const void* src, int src_dtype, int64_t nbk, int64_t ld_src, int dense, int64_t nq, int fmt,
                               int64_t cap, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, hipStream_t stream) {
   const int64_t want = (nq + 256 * U - 1) / (256 * U);
   const int grid = (int)(want < cap ? want : cap);
   uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
-  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
-  if (dense) {
-    if (bf && plus) hipLaunchKernelGGL((quantize_dense_kernel<true, true, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
-    else if (bf) hipLaunchKernelGGL((quantize_dense_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
-    else if (plus) hipLaunchKernelGGL((quantize_dense_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
-    else hipLaunchKernelGGL((quantize_dense_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nq, e32, scales, bm_idx);
-    return;
+  const bool bf = src_dtype == MXP_BF16;
+  if (fmt == MXP_FMT_MXFP4PP) {
+    if (bf) quantize_dispatch_mode<true, 2, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
+    else quantize_dispatch_mode<false, 2, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
+  } else if (fmt == MXP_FMT_MXFP4P) {
+    if (bf) quantize_dispatch_mode<true, 1, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
+    else quantize_dispatch_mode<false, 1, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
+  } else {
+    if (bf) quantize_dispatch_mode<true, 0, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
+    else quantize_dispatch_mode<false, 0, U>(src, nbk, ld_src, dense, nq, grid, e32, scales, bm_idx, stream);
   }
-  if (bf && plus) hipLaunchKernelGGL((quantize_kernel<true, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
-  else if (bf) hipLaunchKernelGGL((quantize_kernel<true, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
-  else if (plus) hipLaunchKernelGGL((quantize_kernel<false, true, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
-  else hipLaunchKernelGGL((quantize_kernel<false, false, U>), dim3(grid), dim3(256), 0, stream, src, nbk, ld_src, dense, nq, e32, scales, bm_idx);
 }
 
 // Launch shape from a sweep over loads per lane (2, 4, 8) and resident workgroups per CU (4 .. 32): 4 independent
@@ -503,6 +563,7 @@ extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, 
                                   uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes,
                                   void* stream) {
   using namespace mxp;
+  if (fmt == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
   if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
   if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
@@ -541,10 +602,16 @@ extern "C" int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int6
   dim3 grid((unsigned)((rows + 255) / 256), (unsigned)nbk);
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint4* e = reinterpret_cast<uint4*>(elems);
-  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
-  if (bf && plus) hipLaunchKernelGGL((quantize_t_kernel<true, true>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
-  else if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, false>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
-  else if (plus) hipLaunchKernelGGL((quantize_t_kernel<false, true>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
-  else hipLaunchKernelGGL((quantize_t_kernel<false, false>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  const bool bf = src_dtype == MXP_BF16;
+  if (fmt == MXP_FMT_MXFP4PP) {
+    if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, 2>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+    else hipLaunchKernelGGL((quantize_t_kernel<false, 2>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  } else if (fmt == MXP_FMT_MXFP4P) {
+    if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, 1>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+    else hipLaunchKernelGGL((quantize_t_kernel<false, 1>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  } else {
+    if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, 0>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+    else hipLaunchKernelGGL((quantize_t_kernel<false, 0>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
+  }
   return launch_status();
 }

@@ -12,7 +12,7 @@ import os
 import torch
 
 F32, BF16 = 0, 1
-MXFP4, MXFP4P = 0, 1
+MXFP4, MXFP4P, MXFP4PP = 0, 1, 2
 IMAGE_E2M3, IMAGE_E2M1 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -12,7 +12,7 @@ from paper_2510_14557_amd import mxp, synth
 
 pytestmark = pytest.mark.gpu
 
-FMT = {"mxfp4": (mxp.MXFP4, oracle.MXFP4), "mxfp4p": (mxp.MXFP4P, oracle.MXFP4P)}
+FMT = {"mxfp4": (mxp.MXFP4, oracle.MXFP4), "mxfp4p": (mxp.MXFP4P, oracle.MXFP4P), "mxfp4pp": (mxp.MXFP4PP, oracle.MXFP4PP)}
 
 
 def to_dev(x: np.ndarray) -> torch.Tensor:
@@ -35,7 +35,7 @@ def assert_q_equal(got, want, fmt_name, what=""):
     we, ws, wi = want
     assert (gs == ws).all(), "%s: %d scale bytes differ" % (what, (gs != ws).sum())
     assert (ge == we).all(), "%s: %d element bytes differ" % (what, (ge != we).sum())
-    if fmt_name == "mxfp4p":
+    if fmt_name != "mxfp4":
         assert (gi == wi).all(), "%s: %d index bytes differ" % (what, (gi != wi).sum())
 
 
@@ -64,7 +64,7 @@ def special_tensor(rows=37, K=160, seed=3, bf16=False):
     return x
 
 
-@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_quantize_special_cases(fmt, bf16):
     x = special_tensor(bf16=bf16)
@@ -87,6 +87,67 @@ def test_quantize_shapes_ragged_and_full(rows, K, bf16):
     x = synth.activations(rows, K, config_id=2, tensor_id=0, dtype="bf16" if bf16 else "f32")
     got = mxp.quantize(to_dev(x), mxp.MXFP4P)
     assert_q_equal(got, oracle.quantize(x, oracle.MXFP4P), "mxfp4p", "%dx%d" % (rows, K))
+
+
+def mxpp_tensor(rows=96, K=512, seed=31, bf16=False):
+    """Blocks that exercise every delta: outliers 2^1 .. 2^12 above the rest, lone BMs, BM-sized pairs, tiny scales."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, K)).astype(np.float32)
+    nb = K // 32
+    for r in range(rows):
+        for b in range(nb):
+            kind = (r * nb + b) % 8
+            blk = x[r, 32 * b:32 * b + 32]
+            if kind < 5:
+                blk[rng.integers(32)] *= np.float32(2.0 ** rng.integers(1, 13))
+            elif kind == 5:
+                blk[:] = 0
+                blk[rng.integers(32)] = rng.standard_normal() * 37
+            elif kind == 6:
+                blk *= np.float32(2.0 ** rng.integers(-126, -112))
+    x[0, 0:32] = (rng.integers(-32, 33, 32) / 8.0)
+    x[1, 0:32] = 0.0
+    x[2, 3] = np.inf
+    return synth.f32_to_bf16_bits(x) if bf16 else x
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_mxfp4pp_every_delta(bf16):
+    x = mxpp_tensor(bf16=bf16)
+    want = oracle.quantize(x, oracle.MXFP4PP)
+    assert len(np.unique(want[2] >> 5)) == 8                       # all eight shifts occur
+    got = mxp.quantize(to_dev(x), mxp.MXFP4PP)
+    assert_q_equal(got, want, "mxfp4pp", "mxfp4++ dense")
+    # K-strided source and strided rows take the other kernels
+    xt = np.ascontiguousarray((synth.bf16_bits_to_f32(x) if bf16 else x).T)
+    got_t = mxp.quantize_t(to_dev(synth.f32_to_bf16_bits(xt) if bf16 else xt), mxp.MXFP4PP)
+    assert_q_equal(got_t, want, "mxfp4pp", "mxfp4++ K-strided")
+    d = to_dev(x)
+    wide = torch.zeros((x.shape[0], x.shape[1] + 64), dtype=d.dtype, device="cuda")
+    wide[:, :x.shape[1]] = d
+    assert_q_equal(mxp.quantize(wide[:, :x.shape[1]], mxp.MXFP4PP), want, "mxfp4pp", "mxfp4++ strided rows")
+    # de-conversion, both output types, dense and strided destination
+    ref = oracle.dequantize(want, oracle.MXFP4PP)
+    nan = np.isnan(ref)
+    for dt in (torch.float32, torch.bfloat16):
+        back = mxp.dequantize(q_dev(want), mxp.MXFP4PP, dt).float().cpu().numpy().astype(np.float64)
+        assert (np.isnan(back) == nan).all() and (back[~nan] == ref[~nan]).all()
+    out = torch.full((x.shape[0], x.shape[1] + 32), 5.0, device="cuda")
+    mxp.dequantize(q_dev(want), mxp.MXFP4PP, out=out[:, :x.shape[1]])
+    back = out.cpu().numpy()
+    assert (back[:, x.shape[1]:] == 5.0).all() and (back[:, :x.shape[1]][~nan] == ref[~nan]).all()
+    # the image and product entry points refuse the format
+    with pytest.raises(mxp.MxpError):
+        mxp.prepack(q_dev(want), mxp.MXFP4PP)
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm(q_dev(want), mxp.MXFP4PP, q_dev(want), mxp.MXFP4P)
+
+
+def test_quantize_mxfp4pp_activation_shapes():
+    for rows, K in ((131, 4096 + 64), (2048, 4096)):
+        x = synth.activations(rows, K, config_id=2, tensor_id=0, dtype="bf16")
+        got = mxp.quantize(to_dev(x), mxp.MXFP4PP)
+        assert_q_equal(got, oracle.quantize(x, oracle.MXFP4PP), "mxfp4pp", "mxfp4++ %dx%d" % (rows, K))
 
 
 def test_quantize_weights_with_heavy_tails():
