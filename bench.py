@@ -26,7 +26,9 @@ PEAK_HBM_GBPS = 8000.0
 WORKLOADS = {
     # name: (synth config, weight name)
     "prefill_mlp": ("prefill_mlp", "wgate"),
+    "prefill_mlp_down": ("prefill_mlp_down", "wdown"),
     "prefill_attn": ("prefill_attn", "wqo"),
+    "large70b": ("large70b", "w"),
     "decode": ("decode", "w"),
 }
 
@@ -281,12 +283,13 @@ def main():
         "dtype": "mxfp4+ (E2M1 elements, E2M3 block max, E8M0 scales), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "A": "bf16 N(0,1) + outlier channels x50",
-                   "W": "bf16 N(0,0.02) + 0.1% Student-t(3)" if args.workload == "prefill_mlp" else "bf16 N(0,0.02)",
+                   "W": {"prefill_mlp": "bf16 N(0,0.02) + 0.1% Student-t(3)", "prefill_mlp_down": "bf16 N(0,0.02) + 0.1% Student-t(3)",
+                         "large70b": "bf16 N(0,0.015)"}.get(args.workload, "bf16 N(0,0.02)"),
                    "out_dtype": args.out_dtype,
                    "step": "quantize(A) -> canonical + image in one pass, image(W) -> scaled-MFMA GEMM -> dequantize(A)"},
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_FP4_TFLOPS, "traffic": traffic_from_profiles(args.workload, args.out_dtype),
-                     "kernel": "gemm_kernel_dma", "kernel_ms": gemm_ms,
+                     "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms,
                      "note": "kernel_ms = HIP event pair around the launch on every 5th timed step (includes the dispatch "
                              "gap); traffic = FETCH_SIZE*2.0 + WRITE_SIZE bytes per launch from profiles/"},
         "stages_ms": stage_ms,
@@ -305,6 +308,11 @@ def main():
         "gemm_a_mxfp4p_w_mxfp4_back_to_back_TFLOPs": flops / (gemm_w4_ms * 1e-3) / 1e12,
         "gemm_with_prepacked_weights_TFLOPs": flops / ((stage_ms["gemm"] + stage_ms["quantize_a"]) * 1e-3) / 1e12,
     }
+    if M <= 64:
+        # skinny-M product: bound by reading the weight image once
+        wbytes = float(img_w.numel())
+        out_line["roofline"].update({"bound": "hbm", "achieved": wbytes / (gemm_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS,
+                                     "unit": "GB/s", "frac": wbytes / (gemm_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS})
     if not args.no_cpu_baseline:
         out_line["cpu_baseline"] = cpu_baseline(a_bits, w_bits)
     print(json.dumps(out_line))
