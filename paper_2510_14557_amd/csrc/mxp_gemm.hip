@@ -761,12 +761,13 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 // of B and splits K over its 8 wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
 // operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the one or two row tiles
 // of A likewise (A is tiny and stays in cache), runs the MFMAs, and the 8 partial tiles are summed through LDS.
-template <int TMR, bool OUT_BF16, int BT>
-__global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
-                                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
-                                                          int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
-  constexpr int WAVES = 8, CHUNK = 4;                       // k-tiles whose loads are in flight together per wavefront
-  __shared__ __attribute__((aligned(16))) float part[WAVES][TMR][16][64];
+template <int TMR, bool OUT_BF16, int BT, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                                 const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                                 int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  constexpr int CHUNK = 4;                                  // k-tiles whose loads are in flight together per wavefront
+  extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
+  float (*part)[TMR][16][64] = reinterpret_cast<float (*)[TMR][16][64]>(skinny_lds);   // [WAVES][TMR][16][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ct = blockIdx.x;                            // column tile of B (32 columns)
@@ -814,8 +815,8 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
 #pragma unroll
     for (int r = 0; r < 16; ++r) part[wave][i][r][lane] = acc[i][r];
   __syncthreads();
-  // 8 wavefronts x 64 lanes sum the TMR x 16 x 64 accumulator slots; slot (i, r, l) is D[32 i + (l % 32)][32 ct + 8 (r / 4) + 4 (l / 32) + r % 4]
-  for (int e = tid; e < TMR * 16 * 64; e += 512) {
+  // all lanes of the workgroup sum the TMR x 16 x 64 accumulator slots over the wavefronts; slot (i, r, l) is D[32 i + (l % 32)][32 ct + 8 (r / 4) + 4 (l / 32) + r % 4]
+  for (int e = tid; e < TMR * 16 * 64; e += 64 * WAVES) {
     const int l = e & 63, r = (e >> 6) & 15, i = e >> 10;
     float v = 0.0f;
 #pragma unroll
@@ -829,6 +830,18 @@ __global__ void __launch_bounds__(512) gemm_skinny_kernel(const uint8_t* __restr
   }
 }
 
+template <int TMR, bool OUT_BF16, int BT, int WAVES>
+void launch_skinny_cfg(dim3 grid, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be, const uint8_t* bs, int kt,
+                       int64_t M, int64_t N, void* D, int64_t ldd) {
+  constexpr int lds = WAVES * TMR * 16 * 64 * 4;
+  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, OUT_BF16, BT, WAVES>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+  (void)once;
+  hipLaunchKernelGGL((gemm_skinny_kernel<TMR, OUT_BF16, BT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
+}
+
+// 16 wavefronts per column tile when K is long enough to give each at least one chunk of 4 k-tiles (K >= 4096): the
+// whole K range of a column tile is then requested at once; 8 otherwise.
 template <int BT>
 int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                   hipStream_t s) {
@@ -838,12 +851,23 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   dim3 grid((unsigned)ct);
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
+  const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   if (M <= 32) {
-    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<1, true, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<1, false, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    if (wide) {
+      if (bf) launch_skinny_cfg<1, true, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<1, false, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    } else {
+      if (bf) launch_skinny_cfg<1, true, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<1, false, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    }
   } else {
-    if (d_dtype == MXP_BF16) hipLaunchKernelGGL((gemm_skinny_kernel<2, true, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else hipLaunchKernelGGL((gemm_skinny_kernel<2, false, BT>), grid, dim3(512), 0, s, ae, as, be, bs, kt, M, N, D, ldd);
+    if (wide) {
+      if (bf) launch_skinny_cfg<2, true, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<2, false, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    } else {
+      if (bf) launch_skinny_cfg<2, true, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<2, false, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    }
   }
   return launch_status();
 }

@@ -397,6 +397,15 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   const uint32_t r0 = t >> 5, kb_in = (t >> 2) & 7u;
   const int64_t row0 = rt * kTileRows + r0, kb = kt0 * 2 + kb_in;
   const bool whole = rt * kTileRows + kTileRows <= rows && kt0 * 2 + 8 <= nbk;   // uniform: no lane of the workgroup is padding
+  if (rt * kTileRows >= rows) {
+    // a row tile of pure padding (rows are padded to 256): zero elements, unit scales, nothing to encode
+    const int64_t nt0 = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
+    uint8_t* out0 = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
+    const u32x4 z = {0, 0, 0, 0};
+    for (uint32_t o = t * 16u; o < (uint32_t)nt0 * kTileBytes; o += 256u * 16u) MXP_IMAGE_STORE(z, reinterpret_cast<u32x4*>(out0 + o));
+    if ((int64_t)(t >> 6) < nt0) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = 127;
+    return;
+  }
   const bool kb_ok = kb < nbk;
   const int64_t off0 = row0 * ld + kb * 32 + part * 8, off_step = 8 * ld;         // source element offsets
   uint32_t w[4][8];
