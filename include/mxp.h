@@ -92,7 +92,8 @@ int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_i
 /* Image kinds.  MXP_IMAGE_E2M3 is what mxp_prepack and mxp_quantize_image write (any format).  A plain MXFP4 operand
  * has no BM to widen, so as the B operand (the weights of Sec. 7.1's "MXFP4+ activations x MXFP4 weights" setting) it
  * may stay in its 4-bit codes: MXP_IMAGE_E2M1, two thirds of the bytes, written by mxp_prepack_e2m1 from canonical
- * MXFP4 storage (elems and scales only).  The A operand of the products below is always an E2M3 image. */
+ * MXFP4 storage (elems and scales only).  The A operand may be an E2M1 image only next to an E2M1 B image (the plain
+ * MXFP4 x MXFP4 product, the baseline MX+ is compared with); E2M1 A with E2M3 B returns MXP_ERR_UNSUPPORTED. */
 #define MXP_IMAGE_E2M3 0
 #define MXP_IMAGE_E2M1 1
 size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K);
@@ -118,7 +119,7 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
              void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Same product from images built earlier with mxp_prepack (weights are packed once, when they are loaded). */
-int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, int b_kind,
+int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image, int b_kind,
                        void* D, int d_dtype, int64_t ldd, void* stream);
 
 /* Activations given un-quantized (A[M][K], MXP_F32 or MXP_BF16, row stride lda): quantized on the fly to fmtA on

@@ -33,27 +33,30 @@ constexpr int kFmtE2M1 = 4;  // ... for FP4 E2M1 operands (16 bytes per lane: re
 // The B tile goes in as the MFMA's first operand and the A tile as its second, i.e. the instruction forms the
 // transposed 32x32 tile: accumulator register r of lane l is then D[m = l % 32][n = 8 * (r / 4) + 4 * (l / 32) + r % 4],
 // four consecutive columns per register quad, which the epilogue stores as one 16-byte piece.
-// FB = element format of the B operand: E2M3, or E2M1 for a plain MXFP4 operand kept in 4-bit codes.
-template <int OA, int OB, int FB = kFmtE2M3>
+// FB / FA = element format of the B / A operand: E2M3, or E2M1 for a plain MXFP4 operand kept in 4-bit codes.
+template <int OA, int OB, int FB = kFmtE2M3, int FA = kFmtE2M3>
 __device__ __forceinline__ v16f mfma(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, c, FB, kFmtE2M3, OB, sb, OA, sa);
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, c, FB, FA, OB, sb, OA, sa);
 }
 
-template <int I, int J, int FB>
+template <int I, int J, int FB, int FA>
 __device__ __forceinline__ v16f mfma_sel(const v8i& a, const v8i& b, const v16f& c, int sa, int sb) {
-  return mfma<(I & 3), (J & 3), FB>(a, b, c, sa, sb);
+  return mfma<(I & 3), (J & 3), FB, FA>(a, b, c, sa, sb);
 }
 
 // Tile configuration: a workgroup of WAVES_M x WAVES_N wavefronts, each computing WM x WN MFMA tiles of 32 x 32.
-template <int WM_, int WN_, int WAVES_M_, int WAVES_N_, int BT_ = kTileBytes>
+template <int WM_, int WN_, int WAVES_M_, int WAVES_N_, int BT_ = kTileBytes, int AT_ = kTileBytes>
 struct Cfg {
   static constexpr int WM = WM_, WN = WN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int BT = BT_;                                 // bytes of a B tile: 1536 (E2M3) or 1024 (E2M1)
   static constexpr int FB = BT_ == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  static constexpr int AT = AT_;                                 // bytes of an A tile, likewise
+  static constexpr int FA = AT_ == kTileBytes ? kFmtE2M3 : kFmtE2M1;
   static_assert(BT_ == kTileBytes || BT_ == kTileBytesE2M1, "B tile kind");
+  static_assert(AT_ == kTileBytes || AT_ == kTileBytesE2M1, "A tile kind");
   static constexpr int TM = WM * WAVES_M, TN = WN * WAVES_N;   // 32-row tiles per workgroup
   static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
-  static constexpr int A_BYTES = TM * kTileBytes, B_BYTES = TN * BT;
+  static constexpr int A_BYTES = TM * AT, B_BYTES = TN * BT;
   static constexpr int SA_BYTES = ((TM + 3) / 4) * 256, SB_BYTES = ((TN + 3) / 4) * 256;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES + SA_BYTES + SB_BYTES;
   static_assert(WM == 1 || WM == 2 || WM == 4 || WM == 8, "WM"); static_assert(WN == 1 || WN == 2 || WN == 4 || WN == 8, "WN");
@@ -71,22 +74,22 @@ __device__ __forceinline__ void mma_all(v16f (&acc)[C::WM][C::WN], const v8i (&a
     for (int j = 0; j < C::WN; ++j) {
         const int sai = (int)sa[i >> 2], sbj = (int)sb[j >> 2];
         switch ((i & 3) * 4 + (j & 3)) {
-          case 0: acc[i][j] = mfma<0, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 1: acc[i][j] = mfma<0, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 2: acc[i][j] = mfma<0, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 3: acc[i][j] = mfma<0, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 4: acc[i][j] = mfma<1, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 5: acc[i][j] = mfma<1, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 6: acc[i][j] = mfma<1, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 7: acc[i][j] = mfma<1, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 8: acc[i][j] = mfma<2, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 9: acc[i][j] = mfma<2, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 10: acc[i][j] = mfma<2, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 11: acc[i][j] = mfma<2, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 12: acc[i][j] = mfma<3, 0, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 13: acc[i][j] = mfma<3, 1, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          case 14: acc[i][j] = mfma<3, 2, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
-          default: acc[i][j] = mfma<3, 3, C::FB>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 0: acc[i][j] = mfma<0, 0, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 1: acc[i][j] = mfma<0, 1, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 2: acc[i][j] = mfma<0, 2, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 3: acc[i][j] = mfma<0, 3, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 4: acc[i][j] = mfma<1, 0, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 5: acc[i][j] = mfma<1, 1, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 6: acc[i][j] = mfma<1, 2, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 7: acc[i][j] = mfma<1, 3, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 8: acc[i][j] = mfma<2, 0, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 9: acc[i][j] = mfma<2, 1, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 10: acc[i][j] = mfma<2, 2, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 11: acc[i][j] = mfma<2, 3, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 12: acc[i][j] = mfma<3, 0, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 13: acc[i][j] = mfma<3, 1, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          case 14: acc[i][j] = mfma<3, 2, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
+          default: acc[i][j] = mfma<3, 3, C::FB, C::FA>(a[i], b[j], acc[i][j], sai, sbj); break;
         }
       }
 }
@@ -191,6 +194,21 @@ __device__ __forceinline__ void store_tile_lds(const v16f (&acc)[TWM][TWN], int6
   }
 }
 
+// One lane's operand of a tile held in LDS: 24 bytes (E2M3: low 16 + high 8) or 16 bytes (E2M1).
+__device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+}
+__device__ __forceinline__ v8i read_operand_e2m1(const uint8_t* tile, int lane) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
+}
+template <int TILE_BYTES>
+__device__ __forceinline__ v8i read_b(const uint8_t* tile, int lane) {
+  return TILE_BYTES == kTileBytes ? read_operand(tile, lane) : read_operand_e2m1(tile, lane);
+}
+
 // Source address of 16-byte chunk c of a stage (k-tile kt) -- the stage is a concatenation of contiguous image runs.
 template <class C>
 __device__ __forceinline__ const u32x4* stage_src(int c, int64_t kt, int64_t k_tiles, const uint8_t* a_el, const uint8_t* a_sc,
@@ -198,8 +216,8 @@ __device__ __forceinline__ const u32x4* stage_src(int c, int64_t kt, int64_t k_t
   constexpr int A_CH = C::A_BYTES / 16, B_CH = C::B_BYTES / 16, SA_CH = C::SA_BYTES / 16;
   const uint8_t* p;
   if (c < A_CH) {
-    const int t = c / (kTileBytes / 16), w = c % (kTileBytes / 16);
-    p = a_el + ((tm0 + t) * k_tiles + kt) * (int64_t)kTileBytes + w * 16;
+    const int t = c / (C::AT / 16), w = c % (C::AT / 16);
+    p = a_el + ((tm0 + t) * k_tiles + kt) * (int64_t)C::AT + w * 16;
   } else if (c < A_CH + B_CH) {
     const int cc = c - A_CH;
     const int t = cc / (C::BT / 16), w = cc % (C::BT / 16);
@@ -260,10 +278,7 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
     v8i a[C::WM], b[C::WN];
 #pragma unroll
     for (int i = 0; i < C::WM; ++i) {
-      const uint8_t* t = st + (wm * C::WM + i) * kTileBytes;
-      const u32x4 lo = *reinterpret_cast<const u32x4*>(t + lane * 16);
-      const u32x2 hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
-      a[i] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      a[i] = read_b<C::AT>(st + (wm * C::WM + i) * C::AT, lane);
     }
 #pragma unroll
     for (int j = 0; j < C::WN; ++j) {
@@ -320,20 +335,6 @@ __device__ __forceinline__ void wait_dma_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-__device__ __forceinline__ v8i read_operand(const uint8_t* tile, int lane) {
-  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
-  const u32x2 hi = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
-  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
-}
-__device__ __forceinline__ v8i read_operand_e2m1(const uint8_t* tile, int lane) {
-  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
-  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
-}
-template <int BT>
-__device__ __forceinline__ v8i read_b(const uint8_t* tile, int lane) {
-  return BT == kTileBytes ? read_operand(tile, lane) : read_operand_e2m1(tile, lane);
-}
-
 // Copy engine state of one wavefront for one output tile: rows [32 tm0, +256), columns [32 tn0, +64 WN).  WN = 4: full
 // tile (each wavefront 4 x 4 MFMA tiles, 8 B tiles per stage); WN = 2: half tile (4 x 2, 4 B tiles per stage).  The
 // ring slot layout is the same for both: A tiles at 0, B tiles at A_BYTES, scale groups of A then of B behind.
@@ -343,30 +344,30 @@ __device__ __forceinline__ v8i read_b(const uint8_t* tile, int lane) {
 // per round) and the scale dwords at wslot + sdelta.
 template <class C, int S, int WN>
 struct Copier {
-  static constexpr bool B6 = C::BT == kTileBytes;
-  // copies per wavefront and stage: 3 rounds of A, the rounds of B (E2M3: 3 or 2, E2M1: 2 or 1), one of scales
-  static constexpr int PER_STAGE = 3 + (B6 ? (WN == 4 ? 3 : 2) : (WN == 4 ? 2 : 1)) + 1;
+  static constexpr bool B6 = C::BT == kTileBytes, A6 = C::AT == kTileBytes;
+  // copies per wavefront and stage: the rounds of A (E2M3: 3, E2M1: 2), of B (E2M3: 3 or 2, E2M1: 2 or 1), one of scales
+  static constexpr int PER_STAGE = (A6 ? 3 : 2) + (B6 ? (WN == 4 ? 3 : 2) : (WN == 4 ? 2 : 1)) + 1;
   uint32_t offE[3], offB[3], offH, offS;
   const uint8_t *pA, *pB, *pS;
   uint32_t wslot, wslot_end, sdelta, hdelta;
 
   __device__ __forceinline__ void init(uint32_t lds_base, const uint8_t* a_el, const uint8_t* a_sc, const uint8_t* b_el,
                                        const uint8_t* b_sc, int64_t k_tiles, int64_t tm0, int64_t tn0, int tid, int wave) {
-    constexpr int TILE_CH = kTileBytes / 16;
+    constexpr int TILE_CH = C::AT / 16;
     constexpr int TILE_CH_B = C::BT / 16;
 #pragma unroll
     for (int u = 0; u < 3; ++u) {   // chunk tid + 256 u of an 8-tile run
       const int c = tid + u * C::THREADS;
-      offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * kTileBytes + (c % TILE_CH) * 16);
+      offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * C::AT + (c % TILE_CH) * 16);
       offB[u] = (uint32_t)((c / TILE_CH_B) * k_tiles * C::BT + (c % TILE_CH_B) * 16);
     }
     // half tile: the B run has 4 tiles = 384 chunks; its second round is chunks 256..383, fetched by wavefronts 0-1
     // and fetched again (same source, same destination) by wavefronts 2-3 so that every wavefront issues the same
     // number of copies per stage.
     const int ch = 256 + (tid & 127);
-    offH = (uint32_t)((ch / TILE_CH) * k_tiles * kTileBytes + (ch % TILE_CH) * 16);
+    offH = (uint32_t)((ch / TILE_CH_B) * k_tiles * C::BT + (ch % TILE_CH_B) * 16);
     offS = (uint32_t)(tid & 63) * 4u;
-    pA = a_el + tm0 * k_tiles * kTileBytes;
+    pA = a_el + tm0 * k_tiles * C::AT;
     pB = b_el + tn0 * k_tiles * C::BT;
     // Scale dwords: 256 bytes (64 lanes x 1 dword) per group of 4 row tiles and k-tile.  Wavefronts 0,1 copy A's two
     // groups, wavefronts 2,3 B's two groups (half tile: both copy B's only group; the second lands in an unused place).
@@ -382,10 +383,10 @@ struct Copier {
   __device__ __forceinline__ void copy(int u) const {
     if (u == 0) MXP_COPY16(offE[0], pA, 0);
     else if (u == 1) MXP_COPY16(offE[1], pA, 4096);
-    else if (u == 2) MXP_COPY16(offE[2], pA, 8192);
-    else if (u == 3) MXP_COPY16(offB[0], pB, 12288);
-    else if (u == 4 && WN == 4) MXP_COPY16(offB[1], pB, 16384);
-    else if (u == 5 && WN == 4 && B6) MXP_COPY16(offB[2], pB, 20480);
+    else if (u == 2 && A6) MXP_COPY16(offE[2], pA, 8192);
+    else if (u == 3) MXP_COPY16(offB[0], pB, C::A_BYTES);
+    else if (u == 4 && WN == 4) MXP_COPY16(offB[1], pB, C::A_BYTES + 4096);
+    else if (u == 5 && WN == 4 && B6) MXP_COPY16(offB[2], pB, C::A_BYTES + 8192);
     else if (u == 4 && WN == 2 && B6)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "s"(hdelta), "v"(offH), "s"(pB) : "memory", "scc");
     else if (u == 6)
@@ -393,7 +394,7 @@ struct Copier {
   }
 #undef MXP_COPY16
   __device__ __forceinline__ void next_stage() {
-    pA += kTileBytes;
+    pA += C::AT;
     pB += C::BT;
     pS += 256;
     wslot += C::STAGE_BYTES;
@@ -406,7 +407,7 @@ struct Copier {
   }
   // same state change as `n` issue_stage() calls, without the copies (they were issued ahead of time)
   __device__ __forceinline__ void skip_stages(int n) {
-    pA += (int64_t)n * kTileBytes;
+    pA += (int64_t)n * C::AT;
     pB += (int64_t)n * C::BT;
     pS += (int64_t)n * 256;
     wslot += (uint32_t)n * C::STAGE_BYTES;   // n < S and the ring starts at slot 0 for every tile
@@ -438,7 +439,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
   static_assert(S == 4, "the peeled tail below is written for a 4-slot ring");
-  static_assert(C::A_BYTES == 3 * C::THREADS * 16 && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
+  static_assert(C::A_BYTES == 8 * C::AT && C::THREADS == 256 && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
   using CP = Copier<C, S, WN>;
   constexpr int PER_STAGE = CP::PER_STAGE;
 
@@ -458,7 +459,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int64_t ta = tm0 + wm * 4, tb = tn0 + wn * WN;
-  const int a_tiles_off = wm * 4 * kTileBytes;
+  const int a_tiles_off = wm * 4 * C::AT;
   const int b_tiles_off = C::A_BYTES + wn * WN * C::BT;
   const int sa_off = C::A_BYTES + C::B_BYTES + wm * 256 + lane * 4;
   // full tile: group wn of B, bytes 0..3 = the wavefront's 4 column tiles; half tile: group 0, bytes 2 wn, 2 wn + 1
@@ -481,7 +482,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 
   wait_dma_and_barrier<KEEP_PROLOGUE>();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a0[i] = read_operand(lds + a_tiles_off + i * kTileBytes, lane);
+  for (int i = 0; i < 4; ++i) a0[i] = read_b<C::AT>(lds + a_tiles_off + i * C::AT, lane);
 #pragma unroll
   for (int j = 0; j < WN; ++j) b0[j] = read_b<C::BT>(lds + b_tiles_off + j * C::BT, lane);
   sa0 = *reinterpret_cast<const uint32_t*>(lds + sa_off);
@@ -496,7 +497,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // COPY: this iteration issues a stage.  KEEPN: copies that may stay in flight at its wait.  NEXT: there is a next
   // k-tile to wait for and read.
 #define MXP_MFMA(m)                                                                                                          \
-  acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN, C::FB>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
+  acc[(m) / WN][(m) % WN] = mfma_sel<(m) / WN, (m) % WN, C::FB, C::FA>(ca[(m) / WN], cb[(m) % WN], acc[(m) / WN][(m) % WN], (int)csa, (int)csb); \
   __builtin_amdgcn_sched_barrier(0)
 #define MXP_GAP() __builtin_amdgcn_sched_barrier(0)
 #define MXP_READ(stmt) do { if (NEXT) { stmt; } } while (0)
@@ -513,16 +514,16 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
     MXP_GAP();
     if constexpr (WN == 4) {
       MXP_MFMA(2);
-      MXP_READ(na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane));
+      MXP_READ(na[0] = read_b<C::AT>(st + a_tiles_off + 0 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(3);
-      MXP_READ(na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane));
+      MXP_READ(na[1] = read_b<C::AT>(st + a_tiles_off + 1 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(4);
-      MXP_READ(na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane));
+      MXP_READ(na[2] = read_b<C::AT>(st + a_tiles_off + 2 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(5);
-      MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
+      MXP_READ(na[3] = read_b<C::AT>(st + a_tiles_off + 3 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(6);
       MXP_READ(nb[0] = read_b<C::BT>(st + b_tiles_off + 0 * C::BT, lane));
@@ -558,12 +559,12 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_CP(6);
     } else {
       MXP_MFMA(2);
-      MXP_READ(na[0] = read_operand(st + a_tiles_off + 0 * kTileBytes, lane));
-      MXP_READ(na[1] = read_operand(st + a_tiles_off + 1 * kTileBytes, lane));
+      MXP_READ(na[0] = read_b<C::AT>(st + a_tiles_off + 0 * C::AT, lane));
+      MXP_READ(na[1] = read_b<C::AT>(st + a_tiles_off + 1 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(3);
-      MXP_READ(na[2] = read_operand(st + a_tiles_off + 2 * kTileBytes, lane));
-      MXP_READ(na[3] = read_operand(st + a_tiles_off + 3 * kTileBytes, lane));
+      MXP_READ(na[2] = read_b<C::AT>(st + a_tiles_off + 2 * C::AT, lane));
+      MXP_READ(na[3] = read_b<C::AT>(st + a_tiles_off + 3 * C::AT, lane));
       MXP_GAP();
       MXP_MFMA(4);
       MXP_READ(nb[0] = read_b<C::BT>(st + b_tiles_off + 0 * C::BT, lane));
@@ -689,7 +690,7 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
 template <class C>
 int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, C::BT);
+  const ImageGeom ga = image_geom(M, K, C::AT), gb = image_geom(N, K, C::BT);
   const int64_t gm = (M + C::TM * 32 - 1) / (C::TM * 32), gn = (N + C::TN * 32 - 1) / (C::TN * 32);
   if (gm > 65535 || gn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)gn, (unsigned)gm);
@@ -717,7 +718,7 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 template <class C, int S>
 int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, C::BT);
+  const ImageGeom ga = image_geom(M, K, C::AT), gb = image_geom(N, K, C::BT);
   const int64_t gm = (M + 255) / 256, gn = (N + 255) / 256;
   if (gm * gn * 2 > 2000000000LL) return MXP_ERR_UNSUPPORTED;
   const int64_t total = gm * gn;
@@ -761,7 +762,7 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 // of B and splits K over its 8 wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
 // operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the one or two row tiles
 // of A likewise (A is tiny and stays in cache), runs the MFMAs, and the 8 partial tiles are summed through LDS.
-template <int TMR, bool OUT_BF16, int BT, int WAVES>
+template <int TMR, bool OUT_BF16, int BT, int AT, int WAVES>
 __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                                  const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                                  int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
@@ -771,7 +772,7 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ct = blockIdx.x;                            // column tile of B (32 columns)
-  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
   const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
   const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
   const int b_shift = (int)(ct & 3) * 8;
@@ -796,17 +797,18 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
       sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
 #pragma unroll
       for (int i = 0; i < TMR; ++i) {
-        const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * kTileBytes;
+        const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
         const u32x4 alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
-        const u32x2 ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        u32x2 ahi = {0, 0};
+        if (AT == kTileBytes) ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
         a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
       }
     }
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
-        acc[0] = mfma<0, 0, FB>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
-        if (TMR > 1) acc[TMR - 1] = mfma<1, 0, FB>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
+        acc[0] = mfma<0, 0, FB, FA>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
+        if (TMR > 1) acc[TMR - 1] = mfma<1, 0, FB, FA>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
       }
     }
   }
@@ -830,22 +832,22 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
   }
 }
 
-template <int TMR, bool OUT_BF16, int BT, int WAVES>
+template <int TMR, bool OUT_BF16, int BT, int AT, int WAVES>
 void launch_skinny_cfg(dim3 grid, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be, const uint8_t* bs, int kt,
                        int64_t M, int64_t N, void* D, int64_t ldd) {
   constexpr int lds = WAVES * TMR * 16 * 64 * 4;
-  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, OUT_BF16, BT, WAVES>),
+  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, OUT_BF16, BT, AT, WAVES>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
   (void)once;
-  hipLaunchKernelGGL((gemm_skinny_kernel<TMR, OUT_BF16, BT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
+  hipLaunchKernelGGL((gemm_skinny_kernel<TMR, OUT_BF16, BT, AT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
 }
 
 // 16 wavefronts per column tile when K is long enough to give each at least one chunk of 4 k-tiles (K >= 4096): the
 // whole K range of a column tile is then requested at once; 8 otherwise.
-template <int BT>
+template <int BT, int AT>
 int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                   hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K), gb = image_geom(N, K, BT);
+  const ImageGeom ga = image_geom(M, K, AT), gb = image_geom(N, K, BT);
   const int64_t ct = (N + 31) / 32;
   if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   dim3 grid((unsigned)ct);
@@ -854,19 +856,19 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   if (M <= 32) {
     if (wide) {
-      if (bf) launch_skinny_cfg<1, true, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<1, false, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      if (bf) launch_skinny_cfg<1, true, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<1, false, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
     } else {
-      if (bf) launch_skinny_cfg<1, true, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<1, false, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      if (bf) launch_skinny_cfg<1, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<1, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
     }
   } else {
     if (wide) {
-      if (bf) launch_skinny_cfg<2, true, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<2, false, BT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      if (bf) launch_skinny_cfg<2, true, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<2, false, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
     } else {
-      if (bf) launch_skinny_cfg<2, true, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<2, false, BT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      if (bf) launch_skinny_cfg<2, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+      else launch_skinny_cfg<2, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
     }
   }
   return launch_status();
@@ -875,22 +877,24 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
 #ifndef MXP_RING
 #define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
 #endif
-template <int BT>
+template <int BT, int AT>
 int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                      hipStream_t s) {
-  if (M <= 64) return launch_skinny<BT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (M <= 64) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail)
-  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2, BT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  return launch_dma<Cfg<4, 4, 2, 2, BT>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2, BT, AT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return launch_dma<Cfg<4, 4, 2, 2, BT, AT>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
-// A image: always E2M3.  B image: E2M3, or E2M1 for a plain MXFP4 operand (b_kind = MXP_IMAGE_E2M1).
-int gemm_images(const void* A_image, const void* B_image, int b_kind, int64_t M, int64_t N, int64_t K, void* D, int d_dtype,
-                int64_t ldd, hipStream_t s) {
+// Image kinds per operand: E2M3, or E2M1 for a plain MXFP4 operand.  E2M1 A with E2M3 B is not instantiated (a plain
+// MXFP4 A next to MXFP4+ weights is simply widened); the entry points reject that combination.
+int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind, int64_t M, int64_t N, int64_t K, void* D,
+                int d_dtype, int64_t ldd, hipStream_t s) {
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
-  if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  return gemm_images_kind<kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
 int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {
@@ -927,16 +931,18 @@ extern "C" size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   return align_up((size_t)mxp::image_geom(M, K).total()) + align_up((size_t)mxp::image_geom(N, K).total());
 }
 
-extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, const void* B_image, int b_kind,
-                                  void* D, int d_dtype, int64_t ldd, void* stream) {
+extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
+                                  int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
+  if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
+  if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
   if (!A_image || !B_image) return MXP_ERR_NULL;
   if (!mxp::aligned16(A_image) || !mxp::aligned16(B_image)) return MXP_ERR_ALIGN;
-  return gemm_images(A_image, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(A_image, a_kind, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx,
@@ -957,13 +963,14 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;
   uint8_t* wa = static_cast<uint8_t*>(workspace);
   uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());
-  rc = prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+  // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product); so does A
+  // when both operands are plain MXFP4
+  const bool b4 = fmtB == MXP_FMT_MXFP4, a4 = b4 && fmtA == MXP_FMT_MXFP4;
+  rc = a4 ? prepack_e2m1_launch(A_elems, A_scales, M, K, wa, s) : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
   if (rc != MXP_OK) return rc;
-  // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product)
-  const bool b4 = fmtB == MXP_FMT_MXFP4;
   rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, N, K, wb, s) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
   if (rc != MXP_OK) return rc;
-  return gemm_images(wa, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(wa, a4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
@@ -991,7 +998,7 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   uint8_t* img = static_cast<uint8_t*>(workspace);
   rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
   if (rc != MXP_OK) return rc;
-  return gemm_images(img, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(img, MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
 extern "C" const char* mxp_status_string(int status) {

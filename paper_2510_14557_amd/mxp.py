@@ -49,7 +49,7 @@ def lib():
     L.mxp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     L.mxp_gemm_workspace_bytes.restype = sz
     L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
-    L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32, i64, vp]
+    L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, i32, vp, i32, vp, i32, i64, vp]
     L.mxp_image_bytes_e2m1.argtypes = [i64, i64]
     L.mxp_image_bytes_e2m1.restype = sz
     L.mxp_prepack_e2m1.argtypes = [vp, vp, i64, i64, vp, sz, vp]
@@ -217,11 +217,11 @@ def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torc
 
 
 def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None,
-                   b_kind: int = IMAGE_E2M3):
+                   b_kind: int = IMAGE_E2M3, a_kind: int = IMAGE_E2M3):
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=a_image.device)
     ldd = out.stride(0) if M > 1 else max(N, 1)
-    _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), _p(b_image), b_kind, _p(out), _dt(out), ldd, _stream()),
+    _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), a_kind, _p(b_image), b_kind, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_prepacked")
     return out
 

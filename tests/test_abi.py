@@ -71,8 +71,10 @@ def test_argument_errors_are_reported_not_launched():
     # image kinds
     assert L.mxp_prepack_e2m1(p, p, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_e2m1(p, None, 64, 64, p, 1 << 20, None) == -1
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, p, 2, p, mxp.F32, 64, None) == -5
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, None, mxp.IMAGE_E2M1, p, mxp.F32, 64, None) == -1
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 2, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 3, p, 0, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, mxp.IMAGE_E2M1, p, mxp.IMAGE_E2M3, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, None, mxp.IMAGE_E2M1, p, mxp.F32, 64, None) == -1
     assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 5, p, mxp.F32, 64, p, 1 << 20, None) == -5
     assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 0, p, mxp.F32, 64, p, 16, None) == -6
     # empty problems are fine and launch nothing

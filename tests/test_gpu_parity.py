@@ -342,6 +342,13 @@ def test_gemm_plain_mxfp4_weights_as_e2m1_image(M, N, K):
     check_gemm(D4, ref, S, "w4 widened")
     Db = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4, out_dtype=torch.bfloat16)
     assert torch.equal(Db, D.to(torch.bfloat16))
+    # plain MXFP4 on both sides: both images stay 4-bit (the baseline the paper compares MX+ with)
+    qa4 = oracle.quantize(a, oracle.MXFP4)
+    ref4, S4 = oracle.gemm(qa4, oracle.MXFP4, qb, oracle.MXFP4)
+    D5 = mxp.gemm(q_dev(qa4), mxp.MXFP4, q_dev(qb), mxp.MXFP4)
+    check_gemm(D5, ref4, S4, "a4 w4 %dx%dx%d" % (M, N, K))
+    D6 = mxp.gemm_prepacked(M, N, K, mxp.prepack_e2m1(q_dev(qa4)), img4, a_kind=mxp.IMAGE_E2M1, b_kind=mxp.IMAGE_E2M1)
+    assert torch.equal(D5, D6)
 
 
 def test_gemm_strided_output_and_k0():
