@@ -130,6 +130,16 @@ int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, 
                    const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Conversion-based product (Sec. 5: where the 4-bit type is not multiplied directly, or only the weights are
+ * quantized, blocks are de-converted to a wider type inside the kernel): D[M][N] = A[M][K] x deq(W)^T with A left as
+ * it is (MXP_BF16, row stride lda; MXP_F32 returns MXP_ERR_UNSUPPORTED) and W[N][K] in canonical MXFP4, MXFP4+ or
+ * MXFP4++ storage, de-converted by Eq. 2 to bf16 (exact) and multiplied on the bf16 MFMA with fp32 accumulation.
+ * Built for few activation rows, where reading the 4-bit weights once is the whole cost: M <= 64; larger M returns
+ * MXP_ERR_UNSUPPORTED.  D is MXP_F32 or MXP_BF16 with row stride ldd.  No workspace. */
+int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
+                   const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW,
+                   void* D, int d_dtype, int64_t ldd, void* stream);
+
 const char* mxp_status_string(int status);
 int mxp_version(void);
 

@@ -4,5 +4,5 @@ Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import 
 It never imports the product package and the product package never imports it.
 """
 from .mxp_oracle import (  # noqa: F401
-    MXFP4, MXFP4P, MXFP4PP, quantize, quantize_t, dequantize, gemm, gemm_sampled, encode_block, decode_block, num_threads,
+    MXFP4, MXFP4P, MXFP4PP, quantize, quantize_t, dequantize, gemm, gemm_w4a16, gemm_sampled, encode_block, decode_block, num_threads,
 )

@@ -119,6 +119,19 @@ def gemm(qa, fmt_a, qb, fmt_b):
     return D, S
 
 
+def gemm_w4a16(a, qw, fmt_w):
+    """Conversion-based product (Sec. 5: blocks de-converted to a wider type and multiplied there): the activations are
+    taken as they are (bf16 bit patterns as uint16, or float32), the weights are de-converted by Eq. 2, and the product
+    is the plain float64 matrix product.  Returns D[M,N] = a @ deq(W)^T and S = |a| @ |deq(W)|^T."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        a = (a.astype(np.uint32) << 16).view(np.float32)
+    a64 = a.astype(np.float64)
+    w64 = dequantize(qw, fmt_w)
+    assert a64.shape[1] == w64.shape[1]
+    return a64 @ w64.T, np.abs(a64) @ np.abs(w64).T
+
+
 def gemm_sampled(qa, fmt_a, qb, fmt_b, rows_m, rows_n):
     """D[t] = <A[rows_m[t]], B[rows_n[t]]> and S[t], for sampled output positions."""
     ae, as_, ai = _q3(qa)

@@ -1,0 +1,275 @@
+// mxp_gemm_w4a16 : D[M][N] = A[M][K] (bf16, not quantized) x deq(W)[N][K]^T, W in canonical MXFP4 / MXFP4+ / MXFP4++.
+//
+// The conversion-based use of the formats (Sec. 5: on hardware that lacks low-precision units, or for weight-only
+// quantization, the blocks are de-converted to a wider type the hardware multiplies, Eq. 2 inside the kernel; the BM
+// needs one extra select per block).  Here the wider type is bf16 and the multiplier is the bf16 MFMA; the weights are
+// read in their canonical 4.25 / 4.5-bit form, so for few activation rows the product is bound by 0.53-0.56 bytes per
+// weight element.
+#include "mxp_common.h"
+#include "mxp_decode.h"
+
+namespace {
+
+using namespace mxp;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne_bits(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ v8bf as_v8bf(const uint32_t (&d)[4]) {
+  union { u32x4 u; v8bf b; } c;
+  c.u = (u32x4){d[0], d[1], d[2], d[3]};
+  return c.b;
+}
+
+// ---- few activation rows (M <= 64): one workgroup per 32 weight rows, K split over its wavefronts ------------------
+// A 32x32x16 bf16 MFMA operand lane l holds row l % 32 and eight k-slots 8 (l / 32) .. +7.  The sum over k does not care
+// which k sits in which slot as long as both operands agree, so the two lane halves take two different MX blocks: in
+// "super-step" t (64 elements of K) lane (n, h) de-converts block 2t + h of weight row n and feeds its 32 values to four
+// MFMAs, eight at a time; the activation lane (m, h) loads the same eight k per MFMA.  The W operand goes first, so
+// accumulator register r of lane l is D[m = l % 32][n = 8 (r / 4) + 4 (l / 32) + r % 4].
+// A wavefront takes groups of 8 blocks (256 elements of K) of the 32 rows: it reads them the way they lie in memory
+// (8 lanes per row: 128 contiguous bytes), passes them through a private LDS patch, and picks them up in operand order.
+constexpr int kW4RowStride = 144;                            // 8 blocks x 16 B + 16 B padding against bank conflicts
+constexpr int kW4PatchBytes = 32 * kW4RowStride + 256 + 256; // elements, scale bytes [32][8], index bytes [32][8]
+
+// 32 codes -> 32 bf16 (16 dwords of pairs), Eq. 2.  The unpack-convert instruction runs over the whole block with the
+// NBM scale, the BM is overwritten once, and the reserved scale codes are a select (0: zeros, 255: NaN).  Only when some
+// lane of the wavefront holds a block whose values reach below the bf16 normal range (scale byte - delta < 2) does the
+// wavefront take the general de-conversion, which builds those patterns from integer fields.
+template <int MODE>
+__device__ __forceinline__ void decode_block_bf16(const u32x4 q, uint32_t sbyte, uint32_t ib, uint32_t (&w)[16]) {
+  const uint32_t dw[4] = {q.x, q.y, q.z, q.w};
+  const uint32_t delta = MODE == 2 ? ib >> 5 : 0u;
+  const bool tiny = sbyte != 0u && sbyte < 2u + delta;
+  if (__builtin_amdgcn_ballot_w64(tiny) != 0) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      uint32_t out[8];
+      decode_group<(MODE >= 1), true>(dw[s], sbyte, MODE >= 1 ? ib & 31u : 64u, (uint32_t)s, out, delta);
+      w[4 * s] = out[0]; w[4 * s + 1] = out[1]; w[4 * s + 2] = out[2]; w[4 * s + 3] = out[3];
+    }
+    return;
+  }
+  const float X = __uint_as_float((sbyte - delta) << 23);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    union { v2bf v; uint32_t u; } c0, c1, c2, c3;
+    c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw[j], X, 0);
+    c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw[j], X, 1);
+    c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw[j], X, 2);
+    c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(dw[j], X, 3);
+    w[4 * j] = c0.u; w[4 * j + 1] = c1.u; w[4 * j + 2] = c2.u; w[4 * j + 3] = c3.u;
+  }
+  if (MODE >= 1) {
+    const uint32_t idx = ib & 31u;
+    const uint32_t qd = idx < 8u ? dw[0] : idx < 16u ? dw[1] : idx < 24u ? dw[2] : dw[3];
+    const uint32_t nib = (qd >> (4u * (idx & 7u))) & 15u;
+    const float XB = __uint_as_float(sbyte << 23);
+    const uint32_t bm = ((nib & 8u) << 12) | (__float_as_uint((float)(8u + (nib & 7u)) * (XB * 0.5f)) >> 16);   // exact: 4 bits
+    const uint32_t sh = (idx & 1u) * 16u;
+    const uint32_t keep = ~(0xFFFFu << sh), put = bm << sh;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = (idx >> 1) == (uint32_t)j ? (w[j] & keep) | put : w[j];
+  }
+  if (sbyte == 0u || sbyte == 255u) {                       // reserved codes: an all-zero block, a block that held NaN / Inf
+    const uint32_t v = sbyte == 0u ? 0u : 0x7FC07FC0u;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = v;
+  }
+}
+
+template <int MODE, int TMR, bool OUT_BF16, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) w4a16_skinny_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                  const u32x4* __restrict__ w_el, const uint8_t* __restrict__ w_sc,
+                                                                  const uint8_t* __restrict__ w_ix, int64_t nbk, int64_t M, int64_t N,
+                                                                  void* __restrict__ Dv, int64_t ldd) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint8_t* patch = lds_raw + wave * kW4PatchBytes;          // private to this wavefront (LDS operations of a wavefront run in order)
+  uint8_t* p_sc = patch + 32 * kW4RowStride;
+  uint8_t* p_ix = p_sc + 256;
+  const int h = lane >> 5, nl = lane & 31;
+  const int64_t n0 = (int64_t)blockIdx.x * 32;
+  const int64_t groups = (nbk + 7) / 8;
+  const bool meta_dwords = (nbk & 3) == 0;                  // scale / index bytes of 4 blocks can be read as one dword
+  v16f acc[TMR];
+  const uint16_t* a_row[TMR];
+  bool a_ok[TMR];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    a_ok[i] = 32 * i + nl < M;
+    a_row[i] = A + (a_ok[i] ? (int64_t)(32 * i + nl) * lda : 0) + h * 32;
+  }
+
+  // loads of one group in memory order: elements, 8 lanes per row; scale and index bytes, 2 lanes per row
+  u32x4 q[4];
+  uint32_t sc4, ix4;
+  auto load_group = [&](int64_t g) {
+    const int64_t kb0 = 8 * g;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t n = n0 + 8 * i + (lane >> 3), kb = kb0 + (lane & 7);
+      q[i] = (u32x4){0, 0, 0, 0};
+      if (n < N && kb < nbk) q[i] = __builtin_nontemporal_load(w_el + n * nbk + kb);
+    }
+    sc4 = 0;
+    ix4 = 0;
+    const int64_t n = n0 + (lane >> 1), kb = kb0 + 4 * (lane & 1);
+    if (n < N && kb < nbk) {
+      const int64_t b = n * nbk + kb;
+      if (meta_dwords) {
+        sc4 = *reinterpret_cast<const uint32_t*>(w_sc + b);
+        if (MODE >= 1) ix4 = *reinterpret_cast<const uint32_t*>(w_ix + b);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (kb + j < nbk) {
+            sc4 |= (uint32_t)w_sc[b + j] << (8 * j);
+            if (MODE >= 1) ix4 |= (uint32_t)w_ix[b + j] << (8 * j);
+          }
+        }
+      }
+    }
+  };
+  if (wave < groups) load_group(wave);
+  for (int64_t g = wave; g < groups; g += WAVES) {
+    const int64_t kb0 = 8 * g;
+    // ---- through the patch into operand order
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<u32x4*>(patch + (8 * i + (lane >> 3)) * kW4RowStride + (lane & 7) * 16) = q[i];
+    *reinterpret_cast<uint32_t*>(p_sc + (lane >> 1) * 8 + 4 * (lane & 1)) = sc4;
+    if (MODE >= 1) *reinterpret_cast<uint32_t*>(p_ix + (lane >> 1) * 8 + 4 * (lane & 1)) = ix4;
+    if (g + WAVES < groups) load_group(g + WAVES);          // the next group's loads fly while this one is multiplied
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int bl = 2 * t + h;                             // block of the group this lane de-converts
+      // activations: lane (m, h) needs, for MFMA s, eight k of the same block (they stay in cache: A is small)
+      u32x4 a[TMR][4];
+#pragma unroll
+      for (int i = 0; i < TMR; ++i) {
+        const uint16_t* ap = a_row[i] + kb0 * 32 + t * 64;   // a_row already points at this lane's row and block half
+        const bool ok = a_ok[i] && kb0 + bl < nbk;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          a[i][s] = (u32x4){0, 0, 0, 0};
+          if (ok) a[i][s] = *reinterpret_cast<const u32x4*>(ap + 8 * s);
+        }
+      }
+      const u32x4 qq = *reinterpret_cast<const u32x4*>(patch + nl * kW4RowStride + bl * 16);
+      const uint32_t sb = p_sc[nl * 8 + bl];
+      const uint32_t ib = MODE >= 1 ? (uint32_t)p_ix[nl * 8 + bl] : 0u;
+      uint32_t w[16];
+      decode_block_bf16<MODE>(qq, sb, ib, w);               // blocks past K or N were loaded as zeros with scale byte 0
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t w4[4] = {w[4 * s], w[4 * s + 1], w[4 * s + 2], w[4 * s + 3]};
+        const v8bf wv = as_v8bf(w4);
+#pragma unroll
+        for (int i = 0; i < TMR; ++i) {
+          const uint32_t a4[4] = {a[i][s].x, a[i][s].y, a[i][s].z, a[i][s].w};
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, as_v8bf(a4), acc[i], 0, 0, 0);
+        }
+      }
+    }
+  }
+  __syncthreads();                                          // the patches are dead: the same LDS now collects the partial tiles
+  float (*part)[TMR][16][64] = reinterpret_cast<float (*)[TMR][16][64]>(lds_raw);
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][i][r][lane] = acc[i][r];
+  __syncthreads();
+  for (int e = tid; e < TMR * 16 * 64; e += 64 * WAVES) {
+    const int l = e & 63, r = (e >> 6) & 15, i = e >> 10;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += part[w][i][r][l];
+    const int64_t row = 32 * i + (l & 31);
+    const int64_t col = n0 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    if (row < M && col < N) {
+      if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne_bits(v);
+      else static_cast<float*>(Dv)[row * ldd + col] = v;
+    }
+  }
+}
+
+template <int MODE, int TMR, bool OUT_BF16>
+void launch_skinny(dim3 grid, hipStream_t s, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws, const uint8_t* wi,
+                   int64_t nbk, int64_t M, int64_t N, void* D, int64_t ldd) {
+  constexpr int WAVES = 16;
+  constexpr int lds_part = WAVES * TMR * 16 * 64 * 4, lds_patch = WAVES * kW4PatchBytes;
+  constexpr int lds = lds_part > lds_patch ? lds_part : lds_patch;
+  static_assert(lds <= 160 * 1024, "LDS");
+  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_skinny_kernel<MODE, TMR, OUT_BF16, WAVES>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+  (void)once;
+  hipLaunchKernelGGL((w4a16_skinny_kernel<MODE, TMR, OUT_BF16, WAVES>), grid, dim3(64 * WAVES), lds, s,
+                     static_cast<const uint16_t*>(A), lda, reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd);
+}
+
+template <int MODE>
+int dispatch_skinny(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws,
+                    const uint8_t* wi, void* D, int d_dtype, int64_t ldd, hipStream_t s) {
+  const int64_t ct = (N + 31) / 32;
+  if (ct > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)ct);
+  const int64_t nbk = K / kBlock;
+  const bool bf = d_dtype == MXP_BF16;
+  if (M <= 32) {
+    if (bf) launch_skinny<MODE, 1, true>(grid, s, A, lda, we, ws, wi, nbk, M, N, D, ldd);
+    else launch_skinny<MODE, 1, false>(grid, s, A, lda, we, ws, wi, nbk, M, N, D, ldd);
+  } else {
+    if (bf) launch_skinny<MODE, 2, true>(grid, s, A, lda, we, ws, wi, nbk, M, N, D, ldd);
+    else launch_skinny<MODE, 2, false>(grid, s, A, lda, we, ws, wi, nbk, M, N, D, ldd);
+  }
+  return launch_status();
+}
+
+template <bool BF16>
+__global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * N) return;
+  const int64_t r = i / N, c = i - r * N;
+  if (BF16) static_cast<uint16_t*>(D)[r * ldd + c] = 0;
+  else static_cast<float*>(D)[r * ldd + c] = 0.0f;
+}
+
+}  // namespace
+
+extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
+                              const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, void* D,
+                              int d_dtype, int64_t ldd, void* stream) {
+  using namespace mxp;
+  if (fmtW != MXP_FMT_MXFP4 && fmtW != MXP_FMT_MXFP4P && fmtW != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  if (a_dtype != MXP_BF16 && a_dtype != MXP_F32) return MXP_ERR_DTYPE;
+  if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
+  if (M == 0 || N == 0) return MXP_OK;
+  if (!D) return MXP_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) {
+    const unsigned grid = (unsigned)((M * N + 255) / 256);
+    if (d_dtype == MXP_BF16) hipLaunchKernelGGL(zero_kernel<true>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+    else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+    return launch_status();
+  }
+  if (!A || !W_elems || !W_scales || (fmtW != MXP_FMT_MXFP4 && !W_idx)) return MXP_ERR_NULL;
+  if (lda < K) return MXP_ERR_SHAPE;
+  if (a_dtype != MXP_BF16) return MXP_ERR_UNSUPPORTED;      // the activations are multiplied as bf16
+  if (!aligned16(A) || !aligned16(W_elems) || !aligned16(W_scales) || (W_idx && !aligned16(W_idx)) || (lda * 2) % 16 != 0)
+    return MXP_ERR_ALIGN;
+  if (M > 64) return MXP_ERR_UNSUPPORTED;
+  if (fmtW == MXP_FMT_MXFP4PP) return dispatch_skinny<2>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+  if (fmtW == MXP_FMT_MXFP4P) return dispatch_skinny<1>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+  return dispatch_skinny<0>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+}

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
-           "mxp_gemm_bf16a", "mxp_status_string", "mxp_version")
+           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_status_string", "mxp_version")
 
 _lib = None
 
@@ -56,6 +56,8 @@ def lib():
     L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
     L.mxp_gemm_bf16a_workspace_bytes.restype = sz
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
+    L.mxp_gemm_w4a16.argtypes = [i64, i64, i64, vp, i32, i64, vp, vp, vp, i32, vp, i32, i64, vp]
+    L.mxp_gemm_w4a16.restype = i32
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
@@ -223,6 +225,23 @@ def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.flo
     ldd = out.stride(0) if M > 1 else max(N, 1)
     _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), a_kind, _p(b_image), b_kind, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_prepacked")
+    return out
+
+
+def gemm_w4a16(a: torch.Tensor, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
+    """Un-quantized bf16 activations x canonical 4-bit weights, de-converted inside the kernel (M <= 64)."""
+    _dev2d(a)
+    we, ws, wi = qw
+    M, K = a.shape
+    N = we.shape[0]
+    if we.shape[1] * 2 != K:
+        raise MxpError("K mismatch between operands")
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a.device)
+    lda = a.stride(0) if M > 1 else max(K, 1)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_w4a16(M, N, K, _p(a), _dt(a), lda, _p(we), _p(ws), _p(wi), fmt_w, _p(out), _dt(out), ldd, _stream()),
+           "mxp_gemm_w4a16")
     return out
 
 

@@ -351,6 +351,31 @@ def test_gemm_plain_mxfp4_weights_as_e2m1_image(M, N, K):
     assert torch.equal(D5, D6)
 
 
+@pytest.mark.parametrize("w_fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (8, 4096, 4096), (32, 100, 96), (33, 1000, 2368), (64, 520, 4160)])
+def test_gemm_w4a16_few_rows(M, N, K, w_fmt):
+    """bf16 activations as they are x 4-bit weights de-converted in the kernel (Sec. 5), against the float64 product of
+    the same numbers.  Products of two bf16 values are exact in fp32; the error is fp32 accumulation only."""
+    a = synth.activations(M, K, config_id=1, tensor_id=60)               # bf16 bit patterns
+    w = synth.weights(N, K, config_id=1, tensor_id=61, t3_frac=0.001)
+    qw = oracle.quantize(w, FMT[w_fmt][1])
+    ref, S = oracle.gemm_w4a16(a, qw, FMT[w_fmt][1])
+    D = mxp.gemm_w4a16(to_dev(a), q_dev(qw), FMT[w_fmt][0])
+    check_gemm(D, ref, S, "w4a16 %s %dx%dx%d" % (w_fmt, M, N, K))
+    Db = mxp.gemm_w4a16(to_dev(a), q_dev(qw), FMT[w_fmt][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+    # strided activations and output
+    wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = to_dev(a)
+    out = torch.full((M, N + 8), -3.0, device="cuda")
+    mxp.gemm_w4a16(wide[:, :K], q_dev(qw), FMT[w_fmt][0], out=out[:, :N])
+    if M > 1:
+        assert torch.equal(out[:, :N], D) and (out[:, N:] == -3.0).all()
+    if M == 8:
+        with pytest.raises(mxp.MxpError):
+            mxp.gemm_w4a16(torch.zeros((65, K), dtype=torch.bfloat16, device="cuda"), q_dev(qw), FMT[w_fmt][0])
+
+
 def test_gemm_strided_output_and_k0():
     a = synth.activations(40, 128, config_id=1, tensor_id=0)
     w = synth.weights(72, 128, config_id=1, tensor_id=1)

@@ -565,3 +565,30 @@ def test_mxpp_tensor_entry_points_and_mse():
     qb = oracle.quantize(synth.f32_to_bf16_bits(a), MXFP4PP)
     a_b = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(a))
     assert all((x == y).all() for x, y in zip(qb, oracle.quantize(a_b, MXFP4PP)))
+
+
+def test_gemm_w4a16_agrees_with_the_quantized_product_when_the_activations_are_representable():
+    """If the activations happen to be exactly MXFP4+ values, the conversion-based product and the W4A4 product are the
+    same sums; and a hand case in closed form."""
+    rng = np.random.default_rng(8)
+    a = rng.standard_normal((5, 128)).astype(np.float32)
+    a[:, 7] *= 40
+    w = (rng.standard_normal((9, 128)) * 0.02).astype(np.float32)
+    qa, qw = oracle.quantize(a, MXFP4P), oracle.quantize(w, MXFP4P)
+    a_rep = oracle.dequantize(qa, MXFP4P).astype(np.float32)            # exact: at most 4 significant bits each
+    D1, S1 = oracle.gemm(qa, MXFP4P, qw, MXFP4P)
+    D2, S2 = oracle.gemm_w4a16(a_rep, qw, MXFP4P)
+    assert np.allclose(D1, D2, rtol=1e-13, atol=0) and np.allclose(S1, S2, rtol=1e-13, atol=0)
+    # bf16 bit patterns and float32 inputs are the same numbers
+    D3, _ = oracle.gemm_w4a16(synth.f32_to_bf16_bits(a_rep), qw, MXFP4P)
+    assert (D3 == D2).all()
+    # one block by hand: a = (3, -2.5) at positions 4 and 20, W row = 7 (BM, exact as 1.75 * 4) and 0.5
+    x = block({4: 7.0, 20: 0.5})
+    qw1 = oracle.quantize(x[None, :], MXFP4P)
+    arow = np.zeros((1, 32), np.float32)
+    arow[0, 4], arow[0, 20] = 3.0, -2.5
+    D, S = oracle.gemm_w4a16(arow, qw1, MXFP4P)
+    assert D[0, 0] == 3.0 * 7.0 - 2.5 * 0.5 and S[0, 0] == 3.0 * 7.0 + 2.5 * 0.5
+    # plain MXFP4 loses the BM's extra bits: 7 -> 6
+    D4, _ = oracle.gemm_w4a16(arow, oracle.quantize(x[None, :], MXFP4), MXFP4)
+    assert D4[0, 0] == 3.0 * 6.0 - 2.5 * 0.5
