@@ -245,6 +245,21 @@ def main():
             us = ev2[0].elapsed_time(ev2[1]) / 20 * 1e3
             out[name] = {"us_per_call": us, "weight_image_GBps": img.numel() / us / 1e3,
                          "frac_hbm": img.numel() / us / 1e3 / PEAK_HBM_GBPS}
+        # the conversion-based route: bf16 activations as they are, canonical 4-bit weights de-converted in the kernel
+        qwd = mxp.quantize(Wd, mxp.MXFP4P)
+        Dd = torch.empty((Md, Nd), dtype=torch.float32, device=dev)
+        for _ in range(3):
+            mxp.gemm_w4a16(Ad, qwd, mxp.MXFP4P, out=Dd)
+        torch.cuda.synchronize()
+        ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev2[0].record()
+        for _ in range(20):
+            mxp.gemm_w4a16(Ad, qwd, mxp.MXFP4P, out=Dd)
+        ev2[1].record()
+        torch.cuda.synchronize()
+        us = ev2[0].elapsed_time(ev2[1]) / 20 * 1e3
+        wbytes = Nd * Kd * 0.5625
+        out["w4a16_mxfp4p_weights"] = {"us_per_call": us, "weight_GBps": wbytes / us / 1e3, "frac_hbm": wbytes / us / 1e3 / PEAK_HBM_GBPS}
         out["shape"] = "A bf16 [%d x %d] quantized on the fly (one kernel) + split-K GEMM with W [%d x %d]" % (Md, Kd, Nd, Kd)
         return out
 
