@@ -73,6 +73,14 @@ int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_
 int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                    uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream);
 
+/* Conversion of a channel-reordered source (Sec. 9, channel reordering: outlier channels are dealt one per block so
+ * that more of them become a BM): element k of output row r is src[r][perm[k]], perm a device array of K int32 channel
+ * numbers in [0, n_src) (out-of-range entries are clamped into the row; both operands of a product must use the same
+ * table).  The source row has n_src channels and row stride ld_src (any stride >= n_src: elements are read one by
+ * one); src, perm and the outputs are 16-byte aligned.  Otherwise as mxp_quantize. */
+int mxp_quantize_gather(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t n_src, int64_t ld_src,
+                        const int32_t* perm, int fmt, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream);
+
 /* De-conversion (Eq. 2): dst[r][k] = (-1)^s * 2^shared_exp * E, with E = 2^e_max * 1.mmm for the BM position of an
  * MXFP4+ block and the E2M1 value otherwise.  Scale byte 0 gives zeros (tested before the BM branch), 255 gives NaN.
  * For MXFP4++ the non-BM elements use 2^(shared_exp - delta), delta = index byte bits 7:5 (MXFP4+ ignores those bits).

@@ -303,6 +303,125 @@ __global__ void __launch_bounds__(256) quantize_dense_kernel(const void* __restr
   }
 }
 
+// ---- channel-reordered source (Sec. 9, "Scattering Outliers with Channel Reordering"): block element k of a row is
+// source channel perm[k], so that outlier channels can be dealt one per block.  The reordering costs no extra pass: the
+// lane gathers its eight elements through the permutation (entries are clamped to the row, so a bad table cannot
+// read outside it) and the encoding and the stores are those of the ordinary kernel.
+template <bool BF16, int MODE>
+__global__ void __launch_bounds__(256) quantize_gather_kernel(const void* __restrict__ src, int64_t nbk, int64_t ld,
+                                                              const int32_t* __restrict__ perm, int64_t n_src, int64_t nq,
+                                                              uint32_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                              uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
+  const int part = threadIdx.x & 3;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; (q & ~(int64_t)3) < nq; q += stride) {
+    uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const bool ok = q < nq;                                  // nq is a multiple of 4: a quad is in or out as a whole
+    if (ok) {
+      const int64_t g = q >> 2, row = g / nbk, kb = g - row * nbk;
+      const int32_t* pp = perm + kb * 32 + part * 8;
+      uint32_t v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        int64_t c = pp[i];
+        c = c < 0 ? 0 : (c >= n_src ? n_src - 1 : c);
+        v[i] = BF16 ? (uint32_t) static_cast<const uint16_t*>(src)[row * ld + c] : static_cast<const uint32_t*>(src)[row * ld + c];
+      }
+      if (BF16) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = v[2 * j] | (v[2 * j + 1] << 16);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = v[i];
+      }
+    }
+    uint32_t sbyte, idx;
+    const uint32_t packed = encode_group<BF16, MODE>(w, part, sbyte, idx);
+    if (ok) {
+      __builtin_nontemporal_store(packed, elems + q);
+      if (part == 0) {
+        scales[q >> 2] = (uint8_t)sbyte;
+        if (PLUS) bm_idx[q >> 2] = (uint8_t)idx;
+      }
+    }
+  }
+}
+
+// Same, for rows that fit in LDS (the usual case: a few thousand channels).  A workgroup walks rows; a row is read the
+// way it lies in memory (16 bytes per lane) into LDS and the lanes gather their elements from there, so HBM sees only
+// full-width loads.  Lane t encodes groups t, t + 256, ... of every row it meets, hence its part of the permutation is
+// read once, up front, and kept in registers (as byte offsets into the LDS row).
+template <bool BF16, int MODE, int GP>
+__global__ void __launch_bounds__(256) quantize_gather_lds_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                                  const int32_t* __restrict__ perm, int64_t n_src,
+                                                                  uint32_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                                  uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
+  constexpr int ESZ = BF16 ? 2 : 4;
+  extern __shared__ __attribute__((aligned(16))) uint8_t row_lds[];
+  const int t = threadIdx.x, part = t & 3;
+  const int64_t groups = nbk * 4;                            // 8-element groups per output row (a multiple of 4)
+  uint32_t off[GP][8];
+#pragma unroll
+  for (int u = 0; u < GP; ++u) {
+    const int64_t g = t + 256 * u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int64_t c = g < groups ? perm[g * 8 + i] : 0;
+      c = c < 0 ? 0 : (c >= n_src ? n_src - 1 : c);
+      off[u][i] = (uint32_t)c * ESZ;
+    }
+  }
+  const int64_t row_bytes = n_src * ESZ;
+  const bool vec_ok = (ld * ESZ) % 16 == 0;                  // rows start 16-byte aligned (src is)
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+    const uint8_t* rp = static_cast<const uint8_t*>(src) + row * ld * ESZ;
+    __syncthreads();                                         // everyone is done with the previous row
+    if (vec_ok) {
+      for (int64_t o = (int64_t)t * 16; o < row_bytes; o += 256 * 16) {
+        if (o + 16 <= row_bytes) {
+          *reinterpret_cast<u32x4*>(row_lds + o) = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rp + o));
+        } else {
+          for (int64_t b = o; b < row_bytes; b += ESZ) {
+            if (BF16) *reinterpret_cast<uint16_t*>(row_lds + b) = *reinterpret_cast<const uint16_t*>(rp + b);
+            else *reinterpret_cast<uint32_t*>(row_lds + b) = *reinterpret_cast<const uint32_t*>(rp + b);
+          }
+        }
+      }
+    } else {
+      for (int64_t b = (int64_t)t * ESZ; b < row_bytes; b += 256 * ESZ) {
+        if (BF16) *reinterpret_cast<uint16_t*>(row_lds + b) = *reinterpret_cast<const uint16_t*>(rp + b);
+        else *reinterpret_cast<uint32_t*>(row_lds + b) = *reinterpret_cast<const uint32_t*>(rp + b);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < GP; ++u) {
+      const int64_t g = t + 256 * u;
+      if ((g & ~(int64_t)3) >= groups) break;                // whole quads leave together (DPP exchanges inside the encode)
+      uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (BF16) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          w[j] = (uint32_t)*reinterpret_cast<const uint16_t*>(row_lds + off[u][2 * j]) |
+                 ((uint32_t)*reinterpret_cast<const uint16_t*>(row_lds + off[u][2 * j + 1]) << 16);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = *reinterpret_cast<const uint32_t*>(row_lds + off[u][i]);
+      }
+      uint32_t sbyte, idx;
+      const uint32_t packed = encode_group<BF16, MODE>(w, part, sbyte, idx);
+      const int64_t q = row * groups + g;
+      __builtin_nontemporal_store(packed, elems + q);
+      if (part == 0) {
+        scales[q >> 2] = (uint8_t)sbyte;
+        if (PLUS) bm_idx[q >> 2] = (uint8_t)idx;
+      }
+    }
+  }
+}
+
 // ---- K-strided source: one thread per block, 32 strided loads that are coalesced across the rows of a wavefront.
 template <bool BF16, int MODE>
 __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
@@ -598,6 +717,42 @@ extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_
   const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
   if ((ld_src * esz) % 16 != 0) return MXP_ERR_ALIGN;
   return quantize_launch(src, src_dtype, rows, K, ld_src, fmt, elems, scales, bm_idx, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mxp_quantize_gather(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t n_src, int64_t ld_src,
+                                   const int32_t* perm, int fmt, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream) {
+  using namespace mxp;
+  int rc = check_common(src, src_dtype, rows, K, fmt, elems, scales, bm_idx);
+  if (rc != MXP_OK || rows == 0 || K == 0) return rc;
+  if (!perm) return MXP_ERR_NULL;
+  if (n_src <= 0 || ld_src < n_src) return MXP_ERR_SHAPE;
+  if (!aligned16(perm)) return MXP_ERR_ALIGN;
+  const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
+  const int64_t want = (nq + 255) / 256, cap = (int64_t)kNumCU * 32;
+  const dim3 grid((unsigned)(want < cap ? want : cap));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
+  const bool bf = src_dtype == MXP_BF16;
+  // rows that fit in LDS (64 KiB) with at most 8 groups per lane (K <= 16384) go through the LDS kernel
+  const int64_t row_bytes = n_src * (bf ? 2 : 4), gp = (nbk * 4 + 255) / 256;
+  if (row_bytes <= 64 * 1024 && gp <= 8) {
+    const size_t lds = (size_t)((row_bytes + 15) & ~(int64_t)15);
+    const dim3 grid_r((unsigned)(rows < (int64_t)kNumCU * 4 ? rows : (int64_t)kNumCU * 4));
+#define MXP_LAUNCH_GL3(B, MD, G) hipLaunchKernelGGL((quantize_gather_lds_kernel<B, MD, G>), grid_r, dim3(256), lds, s, src, rows, nbk, ld_src, perm, n_src, e32, scales, bm_idx)
+#define MXP_LAUNCH_GL2(B, MD) do { if (gp <= 1) MXP_LAUNCH_GL3(B, MD, 1); else if (gp <= 2) MXP_LAUNCH_GL3(B, MD, 2); else if (gp <= 4) MXP_LAUNCH_GL3(B, MD, 4); else MXP_LAUNCH_GL3(B, MD, 8); } while (0)
+    if (fmt == MXP_FMT_MXFP4PP) { if (bf) MXP_LAUNCH_GL2(true, 2); else MXP_LAUNCH_GL2(false, 2); }
+    else if (fmt == MXP_FMT_MXFP4P) { if (bf) MXP_LAUNCH_GL2(true, 1); else MXP_LAUNCH_GL2(false, 1); }
+    else { if (bf) MXP_LAUNCH_GL2(true, 0); else MXP_LAUNCH_GL2(false, 0); }
+#undef MXP_LAUNCH_GL2
+#undef MXP_LAUNCH_GL3
+    return launch_status();
+  }
+#define MXP_LAUNCH_GATHER(B, MD) hipLaunchKernelGGL((quantize_gather_kernel<B, MD>), grid, dim3(256), 0, s, src, nbk, ld_src, perm, n_src, nq, e32, scales, bm_idx)
+  if (fmt == MXP_FMT_MXFP4PP) { if (bf) MXP_LAUNCH_GATHER(true, 2); else MXP_LAUNCH_GATHER(false, 2); }
+  else if (fmt == MXP_FMT_MXFP4P) { if (bf) MXP_LAUNCH_GATHER(true, 1); else MXP_LAUNCH_GATHER(false, 1); }
+  else { if (bf) MXP_LAUNCH_GATHER(true, 0); else MXP_LAUNCH_GATHER(false, 0); }
+#undef MXP_LAUNCH_GATHER
+  return launch_status();
 }
 
 extern "C" int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,

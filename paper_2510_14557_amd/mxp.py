@@ -18,7 +18,7 @@ IMAGE_E2M3, IMAGE_E2M1 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
-EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
+EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_status_string", "mxp_version")
 
@@ -41,6 +41,8 @@ def lib():
     vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
     L.mxp_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
     L.mxp_quantize_t.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp]
+    L.mxp_quantize_gather.argtypes = [vp, i32, i64, i64, i64, i64, vp, i32, vp, vp, vp, vp]
+    L.mxp_quantize_gather.restype = i32
     L.mxp_dequantize.argtypes = [vp, vp, vp, i32, i64, i64, vp, i32, i64, vp]
     L.mxp_image_bytes.argtypes = [i64, i64]
     L.mxp_image_bytes.restype = sz
@@ -122,6 +124,22 @@ def quantize_into(x, fmt, elems, scales, idx):
     rows, K = x.shape
     ld = x.stride(0) if rows > 1 else max(K, 1)
     _check(lib().mxp_quantize(_p(x), _dt(x), rows, K, ld, fmt, _p(elems), _p(scales), _p(idx), _stream()), "mxp_quantize")
+
+
+def quantize_gather(x: torch.Tensor, perm: torch.Tensor, fmt: int = MXFP4P):
+    """Rows of x with their channels reordered: output element k is x[:, perm[k]] (perm int32 on the GPU, length K)."""
+    _dev2d(x)
+    if perm.dtype != torch.int32 or not perm.is_cuda or perm.dim() != 1 or not perm.is_contiguous():
+        raise MxpError("perm must be a contiguous 1-D int32 tensor on the GPU")
+    rows, n_src = x.shape
+    K = perm.numel()
+    ld = x.stride(0) if rows > 1 else max(n_src, 1)
+    elems = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    idx = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    _check(lib().mxp_quantize_gather(_p(x), _dt(x), rows, K, n_src, ld, _p(perm), fmt, _p(elems), _p(scales), _p(idx), _stream()),
+           "mxp_quantize_gather")
+    return elems, scales, idx
 
 
 def quantize_t(xt: torch.Tensor, fmt: int = MXFP4P):

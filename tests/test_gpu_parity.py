@@ -150,6 +150,71 @@ def test_quantize_mxfp4pp_activation_shapes():
         assert_q_equal(got, oracle.quantize(x, oracle.MXFP4PP), "mxfp4pp", "mxfp4++ %dx%d" % (rows, K))
 
 
+def scatter_permutation(outlier_score, block=32):
+    """Channel order of Sec. 9: channels sorted by outlier count; the worst ones are dealt one to every block, the rest
+    fill the remaining places, lower half first, each in descending order."""
+    K = len(outlier_score)
+    order = np.argsort(-outlier_score, kind="stable")
+    nb = K // block
+    heads, rest = order[:nb], order[nb:]
+    half = len(rest) // 2
+    rest = np.concatenate([rest[half:], rest[:half]])
+    perm = np.empty(K, np.int32)
+    perm[0::block] = heads
+    mask = np.ones(K, bool)
+    mask[0::block] = False
+    perm[mask] = rest
+    return perm
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_gather_channel_reordering(fmt, bf16):
+    rows, K = 67, 4096
+    x = synth.activations(rows, K, config_id=2, tensor_id=9, dtype="bf16" if bf16 else "f32")
+    xf = synth.bf16_bits_to_f32(x) if bf16 else x
+    score = (np.abs(xf) > 6 * np.abs(xf).std()).sum(axis=0).astype(np.float64)
+    rng = np.random.default_rng(12)
+    for perm in (scatter_permutation(score), rng.permutation(K).astype(np.int32), np.arange(K, dtype=np.int32)[::-1].copy()):
+        want = oracle.quantize(np.ascontiguousarray(x[:, perm]), FMT[fmt][1])
+        got = mxp.quantize_gather(to_dev(x), torch.from_numpy(perm).cuda(), FMT[fmt][0])
+        assert_q_equal(got, want, fmt, "gather")
+    # a table that selects a subset (K smaller than the source width), a strided source, and out-of-range entries (clamped)
+    sub = rng.integers(0, K, 96).astype(np.int32)
+    wide = torch.zeros((rows, K + 40), dtype=to_dev(x).dtype, device="cuda")
+    wide[:, :K] = to_dev(x)
+    got = mxp.quantize_gather(wide[:, :K], torch.from_numpy(sub).cuda(), FMT[fmt][0])
+    assert_q_equal(got, oracle.quantize(np.ascontiguousarray(x[:, sub]), FMT[fmt][1]), fmt, "gather subset")
+    if not bf16 and fmt == "mxfp4p":
+        # a row too long for the LDS route takes the direct gather
+        big = synth.activations(5, 20000 - 32, config_id=2, tensor_id=10, dtype="f32")
+        pbig = rng.permutation(big.shape[1]).astype(np.int32)
+        got = mxp.quantize_gather(to_dev(big), torch.from_numpy(pbig).cuda(), FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize(np.ascontiguousarray(big[:, pbig]), FMT[fmt][1]), fmt, "gather long rows")
+    bad = sub.copy()
+    bad[3], bad[50] = -7, K + 1000
+    got = mxp.quantize_gather(to_dev(x), torch.from_numpy(bad).cuda(), FMT[fmt][0])
+    assert_q_equal(got, oracle.quantize(np.ascontiguousarray(x[:, np.clip(bad, 0, K - 1)]), FMT[fmt][1]), fmt, "gather clamped")
+
+
+def test_channel_reordering_separates_outliers():
+    """With the synthetic activations two outlier channels share a block; after the reordering every outlier channel
+    leads a block of its own and the MXFP4+ error drops (Sec. 9)."""
+    x = synth.activations(256, 4096, config_id=2, tensor_id=9, dtype="f32")
+    score = (np.abs(x) > 6 * np.abs(x).std()).sum(axis=0).astype(np.float64)
+    perm = scatter_permutation(score)
+    hot = np.flatnonzero(score > 0.5 * x.shape[0])
+    assert len(hot) >= 2 and len(set(hot // 32)) < len(hot)                  # some block holds two outlier channels
+    where = np.flatnonzero(np.isin(perm, hot))
+    assert len(set(where // 32)) == len(hot)                                 # none does after the reordering
+    d = to_dev(x)
+    q0 = mxp.quantize(d, mxp.MXFP4P)
+    q1 = mxp.quantize_gather(d, torch.from_numpy(perm).cuda(), mxp.MXFP4P)
+    e0 = ((mxp.dequantize(q0, mxp.MXFP4P).cpu().numpy() - x) ** 2).mean()
+    e1 = ((mxp.dequantize(q1, mxp.MXFP4P).cpu().numpy() - x[:, perm]) ** 2).mean()
+    assert e1 < e0
+
+
 def test_quantize_weights_with_heavy_tails():
     w = synth.weights(512, 4096, config_id=3, tensor_id=1, t3_frac=0.001)
     for fmt in ("mxfp4", "mxfp4p"):
