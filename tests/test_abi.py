@@ -77,6 +77,22 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, None, mxp.IMAGE_E2M1, p, mxp.F32, 64, None) == -1
     assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 5, p, mxp.F32, 64, p, 1 << 20, None) == -5
     assert L.mxp_gemm_bf16a(64, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, 0, p, mxp.F32, 64, p, 16, None) == -6
+    # channel-reordered conversion and the conversion-based product
+    assert L.mxp_quantize_gather(p, mxp.BF16, 4, 64, 64, 64, None, mxp.MXFP4P, p, p, p, None) == -1
+    assert L.mxp_quantize_gather(p, mxp.BF16, 4, 64, 0, 64, p, mxp.MXFP4P, p, p, p, None) == -2
+    assert L.mxp_quantize_gather(p, mxp.BF16, 4, 64, 128, 64, p, mxp.MXFP4P, p, p, p, None) == -2
+    assert L.mxp_quantize_gather(p, mxp.BF16, 4, 64, 64, 64, odd, mxp.MXFP4P, p, p, p, None) == -3
+    assert L.mxp_quantize_gather(p, mxp.BF16, 4, 40, 64, 64, p, mxp.MXFP4P, p, p, p, None) == -2
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, p, 7, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.F32, 64, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_w4a16(65, 64, 64, p, mxp.BF16, 64, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, mxp.MXFP4PP, p, mxp.F32, 64, None) == -1
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 32, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, None) == -2
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, p, mxp.MXFP4P, p, mxp.F32, 32, None) == -2
+    # MXFP4++ is a codec: no image, no W4A4 product
+    assert L.mxp_prepack(p, p, p, mxp.MXFP4PP, 64, 64, p, 1 << 20, None) == -8
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, 1 << 20, None) == -8
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4PP, None, None, None, p, 1 << 20, None) == -8
     # empty problems are fine and launch nothing
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
     assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0
