@@ -807,8 +807,15 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
-        acc[0] = mfma<0, 0, FB, FA>(a[c][0], b[c], acc[0], (int)sa[c], (int)sb[c]);
-        if (TMR > 1) acc[TMR - 1] = mfma<1, 0, FB, FA>(a[c][TMR - 1], b[c], acc[TMR - 1], (int)sa[c], (int)sb[c]);
+#pragma unroll
+        for (int i = 0; i < TMR; ++i) {                       // row tile i: byte i of the lane's A scale dword
+          switch (i) {
+            case 0: acc[i] = mfma<0, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
+            case 1: acc[i] = mfma<1, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
+            case 2: acc[i] = mfma<2, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
+            default: acc[i] = mfma<3, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
+          }
+        }
       }
     }
   }
@@ -854,6 +861,11 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
+  if (M > 64) {                                             // 65 .. 128 rows: four row tiles, 8 wavefronts (128 KiB of partial tiles)
+    if (bf) launch_skinny_cfg<4, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else launch_skinny_cfg<4, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
+    return launch_status();
+  }
   if (M <= 32) {
     if (wide) {
       if (bf) launch_skinny_cfg<1, true, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
@@ -880,7 +892,9 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
 template <int BT, int AT>
 int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                      hipStream_t s) {
-  if (M <= 64) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  // few rows: bound by reading the weights once.  Up to 128 rows when the tiled kernel would get fewer than 64 tile columns
+  // (it then leaves most of the chip idle).
+  if (M <= 64 || (M <= 128 && (N + 255) / 256 < 64)) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail)
   if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2, BT, AT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return launch_dma<Cfg<4, 4, 2, 2, BT, AT>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
