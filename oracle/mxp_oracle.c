@@ -16,7 +16,7 @@
  *   - BM = BM_H + BM_L split into two E2M1 numbers                             (Eq. 3)
  *   - D = A x B with K-blocked operands, BM x BM products kept at full width   (Sec. 5.1, Sec. 6.2 BCU)
  *
- * Readings where the paper is silent (each is repeated in the design doc):
+ * Readings where the paper is silent:
  *   - element rounding: round to nearest, ties to the even code; |v| > 6 saturates to 6 (Sec. 4.3 shows
  *     7.92 saturating to 6.0)
  *   - BM mantissa carry (scaled BM >= 7.75): saturates to 7.5 because the shared scale is never altered
