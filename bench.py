@@ -265,6 +265,38 @@ def main():
 
     decode = timed_decode()
 
+    # Measured ceilings: MFMAs alone on register-resident random operands (what the power limit leaves of the nominal
+    # rate), and a plain 256 MiB device copy.
+    def timed_probe(a_kind, b_kind):
+        sink = torch.empty(65536, dtype=torch.float32, device=dev)
+        iters = 4000                                           # ~0.1 ms per launch
+        for _ in range(300):
+            mxp.probe_mfma(iters, a_kind, b_kind, sink=sink)
+        torch.cuda.synchronize()
+        ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev2[0].record()
+        for _ in range(100):
+            mxp.probe_mfma(iters, a_kind, b_kind, sink=sink)
+        ev2[1].record()
+        torch.cuda.synchronize()
+        return mxp.PROBE_FLOP_PER_ITER * iters / (ev2[0].elapsed_time(ev2[1]) / 100 * 1e-3) / 1e12
+
+    mfma_peak_e2m3 = timed_probe(mxp.IMAGE_E2M3, mxp.IMAGE_E2M3)
+    mfma_peak_e2m1 = timed_probe(mxp.IMAGE_E2M1, mxp.IMAGE_E2M1)
+    cp_src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    for _ in range(3):
+        cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev2[0].record()
+    for _ in range(10):
+        cp_dst.copy_(cp_src)
+    ev2[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * (256 << 20) * 10 / (ev2[0].elapsed_time(ev2[1]) * 1e-3) / 1e9
+    del cp_src, cp_dst
+
     # Standalone quantize (canonical outputs only), launches queued back to back over rotating source copies whose
     # total exceeds the 256 MB Infinity Cache: the activation tensor (12 copies) and the weight matrix (3 copies).
     def timed_quantize(src_bits, copies, launches):
@@ -311,6 +343,11 @@ def main():
                      "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms,
                      "note": "kernel_ms = HIP event pair around the launch on every 5th timed step (includes the dispatch "
                              "gap); traffic = FETCH_SIZE*2.0 + WRITE_SIZE bytes per launch from profiles/"},
+        "measured_ceilings": {"mfma_only_e2m3_x_e2m3_TFLOPs": mfma_peak_e2m3, "mfma_only_e2m1_x_e2m1_TFLOPs": mfma_peak_e2m1,
+                              "device_copy_256MiB_GBps": copy_gbps,
+                              "gemm_frac_of_mfma_only": gemm_tflops / mfma_peak_e2m3,
+                              "note": "MFMAs alone on register-resident pseudo-random operands, 1024 wavefronts: the rate the "
+                                      "chip sustains at its power limit; copy = read + written bytes"},
         "stages_ms": stage_ms,
         "quantize_GBps": q_bytes / (q_act_ms * 1e-3) / 1e9,
         "quantize_frac_hbm": q_bytes / (q_act_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,

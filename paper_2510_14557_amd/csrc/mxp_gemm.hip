@@ -1015,6 +1015,59 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   return gemm_images(img, MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
+// ---- measurement aid: the matrix pipes alone ------------------------------------------------------------------
+// One workgroup per compute unit, one wavefront per SIMD, 16 independent accumulator tiles per wavefront (as in the
+// GEMM), operands pseudo-random bit patterns that never leave the registers.  What this reaches is what the chip's
+// power limit leaves of the nominal MFMA rate for these operand formats.
+namespace {
+template <int FA, int FB>
+__global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ sink, int iters, uint32_t seed) {
+  v8i a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[j][i] = (int)((threadIdx.x * 2654435761u + (8 * j + i) * 40503u + blockIdx.x) * seed);
+      b[j][i] = (int)((threadIdx.x * 2246822519u + (8 * j + i) * 3266489917u + blockIdx.x) * seed);
+    }
+  v16f acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  const int sc = 0x7F7F7F7F;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, sc, 0, sc);
+  }
+  float x = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x += acc[i][j][r];
+  sink[blockIdx.x * 256 + threadIdx.x] = x;
+}
+}  // namespace
+
+extern "C" int mxp_probe_mfma(int a_kind, int b_kind, int iters, uint32_t seed, float* sink, void* stream) {
+  if ((a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) || (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1)) return MXP_ERR_FORMAT;
+  if (iters < 0 || iters > (1 << 24)) return MXP_ERR_SHAPE;
+  if (!sink) return MXP_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(mxp::kNumCU), block(256);
+  if (a_kind == MXP_IMAGE_E2M3 && b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
+  else if (a_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
+  else if (b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
+  else hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
+  return mxp::launch_status();
+}
+
 extern "C" const char* mxp_status_string(int status) {
   switch (status) {
     case MXP_OK: return "ok";

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
-           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_status_string", "mxp_version")
+           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
 
@@ -60,6 +60,8 @@ def lib():
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_w4a16.argtypes = [i64, i64, i64, vp, i32, i64, vp, vp, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_w4a16.restype = i32
+    L.mxp_probe_mfma.argtypes = [i32, i32, i32, C.c_uint32, vp, vp]
+    L.mxp_probe_mfma.restype = i32
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
@@ -261,6 +263,17 @@ def gemm_w4a16(a: torch.Tensor, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype 
     _check(lib().mxp_gemm_w4a16(M, N, K, _p(a), _dt(a), lda, _p(we), _p(ws), _p(wi), fmt_w, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_w4a16")
     return out
+
+
+PROBE_FLOP_PER_ITER = 256 * 4 * 16 * 2 * 32 * 32 * 64
+
+
+def probe_mfma(iters: int, a_kind: int = IMAGE_E2M3, b_kind: int = IMAGE_E2M3, seed: int = 1, sink: torch.Tensor | None = None):
+    """Measurement aid: MFMAs only, on register-resident operands (PROBE_FLOP_PER_ITER flop per iteration)."""
+    if sink is None:
+        sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    _check(lib().mxp_probe_mfma(a_kind, b_kind, iters, seed, _p(sink), _stream()), "mxp_probe_mfma")
+    return sink
 
 
 def gemm_bf16a_workspace_bytes(M: int, K: int) -> int:
