@@ -1,6 +1,7 @@
 // mxp_gemm : D[M][N] = A[M][K] x B[N][K]^T on MXFP4 / MXFP4+ operands (Sec. 5.1), fp32 accumulation.
 //
-// Both operands are consumed as E2M3 images (mxp_prepack): every E2M1 element is exactly an E2M3 value and the BM of
+// Operands are consumed as E2M3 images (mxp_prepack; a plain MXFP4 operand may stay an E2M1 image: the MFMA takes the
+// two formats side by side at the same rate): every E2M1 element is exactly an E2M3 value and the BM of
 // an MX+ block is an E2M3 number at exponent e_max (Sec. 4.2), so ONE block-scaled MFMA per block pair yields the
 // exact products A_BM x B_NBM, B_BM x A_NBM and A_BM x B_BM that the paper obtains with a BM_H/BM_L split and an
 // extra MMA (Sec. 5.2, Alg. 1) or with its BM Compute Unit (Sec. 6.2).  The shared E8M0 scales go to the MFMA as is.
