@@ -7,6 +7,7 @@
 // nibble with the 3-bit extended mantissa, and each lane stores one dword of nibbles.  Scale and index bytes of
 // four neighbouring blocks are gathered into one lane and stored as dwords.
 #include "mxp_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -14,6 +15,7 @@ using namespace mxp;
 
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
@@ -422,24 +424,17 @@ __global__ void __launch_bounds__(256) quantize_gather_lds_kernel(const void* __
   }
 }
 
-// ---- K-strided source: one thread per block, 32 strided loads that are coalesced across the rows of a wavefront.
-template <bool BF16, int MODE>
-__global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
-                                                         uint4* __restrict__ elems, uint8_t* __restrict__ scales,
-                                                         uint8_t* __restrict__ bm_idx) {
+// ---- K-strided source -------------------------------------------------------------------------------------------
+// One lane encodes a whole block held in registers as 32 fp32 patterns (same decisions as encode_group: Eq. 1,
+// Sec. 4.1-4.3, lowest-position maximum).
+template <int MODE>
+__device__ __forceinline__ void encode_block_serial(const uint32_t (&x)[32], uint32_t (&out)[4], uint32_t& sbyte,
+                                                    uint32_t& idx) {
   constexpr bool PLUS = MODE >= 1, PP = MODE == 2;
-  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t kb = blockIdx.y;
-  if (r >= rows) return;
-  uint32_t x[32];
   uint32_t mx = 0;
 #pragma unroll
-  for (int i = 0; i < 32; ++i) {
-    const int64_t off = (kb * 32 + i) * ld + r;
-    x[i] = BF16 ? ((uint32_t) static_cast<const uint16_t*>(src)[off]) << 16 : static_cast<const uint32_t*>(src)[off];
-    mx = umax(mx, x[i] & 0x7FFFFFFFu);
-  }
-  uint32_t idx = 32;
+  for (int i = 0; i < 32; ++i) mx = umax(mx, x[i] & 0x7FFFFFFFu);
+  idx = 32;
 #pragma unroll
   for (int i = 31; i >= 0; --i) idx = ((x[i] & 0x7FFFFFFFu) == mx) ? (uint32_t)i : idx;
   const uint32_t E = mx >> 23;
@@ -455,7 +450,6 @@ __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict_
     delta = sb - nb;
   }
   const float scale = __uint_as_float((E - 2u - delta) << 23);
-  uint32_t out[4] = {0, 0, 0, 0};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     uint32_t p = 0;
@@ -475,17 +469,242 @@ __global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict_
       out[j] = ((idx >> 3) == (uint32_t)j) ? repl : out[j];
     }
   }
-  uint32_t sbyte = E - 2u;
+  sbyte = E - 2u;
   if (PP) idx |= delta << 5;
   if (E <= 2u || E == 255u) {
     out[0] = out[1] = out[2] = out[3] = 0;
     idx = 0;
     sbyte = (E == 255u) ? 255u : 0u;
   }
+}
+
+// The same for a block held as 16 words of two bf16 values each (value 2j in the low half of word j).  As in
+// encode_group the position rides in the low bits of an unsigned key, so one maximum yields the BM and its position,
+// and the hardware conversion takes the bf16 pairs as they are.
+template <int MODE>
+__device__ __forceinline__ void encode_block_serial_bf16(const uint32_t (&w)[16], uint32_t (&out)[4], uint32_t& sbyte,
+                                                         uint32_t& idx) {
+  constexpr bool PLUS = MODE >= 1, PP = MODE == 2;
+  uint32_t key[32];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    key[2 * j] = ((w[j] << 16) & 0x7FFF0000u) | (uint32_t)(31 - 2 * j);
+    key[2 * j + 1] = (w[j] & 0x7FFF0000u) | (uint32_t)(30 - 2 * j);
+  }
+  uint32_t k = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) k = umax(k, key[i]);
+  const uint32_t mx = k & 0xFFFF0000u;
+  idx = 31u - (k & 31u);
+  const uint32_t E = mx >> 23;
+  uint32_t delta = 0;
+  if (PP) {                                                         // Sec. 4.3: finer scale for the NBMs
+    uint32_t k2 = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) k2 = umax(k2, key[i] == k ? 0u : key[i]);   // keys are unique
+    const uint32_t sb = E - 2u, E2 = k2 >> 23;
+    const uint32_t lo = sb > 7u ? sb - 7u : 0u;
+    uint32_t nb = E2 == 0u ? lo : umin(umax(E2 - 1u, lo), sb);
+    nb = umax(nb, 1u);
+    delta = sb - nb;
+  }
+  const float scale = __uint_as_float((E - 2u - delta) << 23);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t p = 0;
+    union { uint32_t u; v2bf v; } c0, c1, c2, c3;
+    c0.u = w[4 * j]; c1.u = w[4 * j + 1]; c2.u = w[4 * j + 2]; c3.u = w[4 * j + 3];
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(p, c0.v, scale, 0);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(p, c1.v, scale, 1);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(p, c2.v, scale, 2);
+    p = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(p, c3.v, scale, 3);
+    out[j] = p;
+  }
+  if (PLUS) {
+    const uint32_t m3 = bm_mantissa(mx & 0x7FFFFFu);
+    const uint32_t sh = (idx & 7u) * 4u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t nib = ((out[j] >> sh) & 8u) | m3;
+      const uint32_t repl = (out[j] & ~(0xFu << sh)) | (nib << sh);
+      out[j] = ((idx >> 3) == (uint32_t)j) ? repl : out[j];
+    }
+  }
+  sbyte = E - 2u;
+  if (PP) idx |= delta << 5;
+  if (E <= 2u || E == 255u) {
+    out[0] = out[1] = out[2] = out[3] = 0;
+    idx = 0;
+    sbyte = (E == 255u) ? 255u : 0u;
+  }
+}
+
+// General form (any row stride, any alignment): one thread per block, 32 strided loads that are coalesced across the
+// rows of a wavefront; each lane stores its 16 element bytes and its scale / index byte on its own.
+template <bool BF16, int MODE>
+__global__ void __launch_bounds__(256) quantize_t_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                         uint4* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                         uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t kb = blockIdx.y;
+  if (r >= rows) return;
+  uint32_t x[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const int64_t off = (kb * 32 + i) * ld + r;
+    x[i] = BF16 ? ((uint32_t) static_cast<const uint16_t*>(src)[off]) << 16 : static_cast<const uint32_t*>(src)[off];
+  }
+  uint32_t out[4], sbyte, idx;
+  encode_block_serial<MODE>(x, out, sbyte, idx);
   const int64_t b = r * nbk + kb;
   elems[b] = make_uint4(out[0], out[1], out[2], out[3]);
   scales[b] = (uint8_t)sbyte;
   if (PLUS) bm_idx[b] = (uint8_t)idx;
+}
+
+// Tiled form (even row stride, source aligned to two elements).  A workgroup owns kTRows = 128 rows x kTRun blocks
+// of K and walks them 4 blocks at a time.  Wavefront kb of the workgroup takes block kb of the pass; its lane rp loads
+// the row pair 2rp, 2rp+1, one 4- or 8-byte load per value of K, so each load instruction of a wavefront reads one
+// full 256- (bf16) or 512-byte (fp32) run of a source line; the loads of the next pass are in flight while this one
+// is encoded.  The lane encodes its two blocks and drops them into LDS at [row][kb].  After ACC passes the tile
+// leaves row by row: ACC x 64 contiguous element bytes and ACC x 4 scale and index bytes per row (short runs per
+// row are what the write side of HBM likes least: ACC = 1 costs 40 % more time than ACC = 8).
+constexpr int kBufferFlags = 0x00020000;                             // raw buffer descriptor, dword 3: 32-bit data
+constexpr int kTRows = 128, kTRun = 32, kTAcc = 8;
+
+template <bool BF16, int MODE, int ACC>
+__global__ void __launch_bounds__(256) quantize_t_tiled_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk,
+                                                               int64_t ld, uint4* __restrict__ elems,
+                                                               uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx) {
+  constexpr bool PLUS = MODE >= 1;
+  constexpr int R = kTRows, B = 4, C = ACC * B;                      // C = blocks of K per row in the LDS tile
+  static_assert(kTRun % C == 0, "a run of K is a whole number of LDS tiles");
+  __shared__ u32x4 e_lds[R][C + 1];                                  // + 1: rows land on different banks
+  __shared__ __attribute__((aligned(4))) uint8_t s_lds[R][C];
+  __shared__ __attribute__((aligned(4))) uint8_t i_lds[R][C];
+  const uint32_t t = threadIdx.x, rp = t & 63u;
+  // 64 row pairs: a wavefront shares its block of K, so the K part of every address is wave-uniform
+  const uint32_t kbl = (uint32_t)__builtin_amdgcn_readfirstlane((int)(t >> 6));
+  const int64_t row0 = (int64_t)blockIdx.x * R;
+  const int64_t r = row0 + 2 * rp;                                   // this lane's row pair
+  const int64_t kb_first = (int64_t)blockIdx.y * kTRun;
+  const int64_t kb_end = kb_first + kTRun < nbk ? kb_first + kTRun : nbk;
+  // 4-byte scale / index stores stay aligned
+  const bool wide_meta = ((nbk | (int64_t)reinterpret_cast<uintptr_t>(scales) | (int64_t)reinterpret_cast<uintptr_t>(bm_idx)) & 3) == 0;
+  // Source line k of a block starts at tile_src + k * step.  Buffer loads keep that wave-uniform part in scalar
+  // registers (descriptor base + scalar offset) and the lane part in one 32-bit vector offset.  raw[k] = the lane's
+  // row pair at line k of the block (one row, zero-extended, for the last row of an odd row count; zeros outside).
+  constexpr int64_t kEsize = BF16 ? 2 : 4;
+  using Raw = typename std::conditional<BF16, uint32_t, u32x2>::type;
+  const int32_t step = (int32_t)(ld * kEsize);                       // the launcher keeps 32 * step below 2^31
+  const int32_t lane_off = (int32_t)(rp * 2 * kEsize);
+  auto load_block = [&](int64_t kb, Raw (&raw)[32]) {
+    const uint8_t* tile_src = static_cast<const uint8_t*>(src) + (kb * 32 * ld + row0) * kEsize;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(tile_src), 0, 0x7FFFFFFF, kBufferFlags);
+    if (kb < nbk && row0 + R <= rows) {                              // wave-uniform: all 64 row pairs exist
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if constexpr (BF16) raw[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off, i * step, 0);
+        else raw[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, i * step, 0);
+      }
+    } else if (kb < nbk && r + 1 < rows) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if constexpr (BF16) raw[i] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off, i * step, 0);
+        else raw[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane_off, i * step, 0);
+      }
+    } else if (kb < nbk && r < rows) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if constexpr (BF16) raw[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, lane_off, i * step, 0) & 0xFFFFu;
+        else raw[i] = u32x2{(uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_off, i * step, 0), 0u};
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        if constexpr (BF16) raw[i] = 0u;
+        else raw[i] = u32x2{0u, 0u};
+      }
+    }
+  };
+  // two blocks per lane: as 32 fp32 patterns each, or (bf16) as 16 words of two consecutive values of K each
+  constexpr int NW = BF16 ? 16 : 32;
+  uint32_t xa[NW], xb[NW];
+  auto unpack = [&](const Raw (&raw)[32]) {
+    if constexpr (BF16) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {                                 // regroup into (k, k+1) pairs per row
+        xa[j] = __builtin_amdgcn_perm(raw[2 * j + 1], raw[2 * j], 0x05040100u);
+        xb[j] = __builtin_amdgcn_perm(raw[2 * j + 1], raw[2 * j], 0x07060302u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        xa[i] = raw[i].x;
+        xb[i] = raw[i].y;
+      }
+    }
+  };
+  {
+    Raw raw[32];
+    load_block(kb_first + kbl, raw);
+    unpack(raw);
+  }
+  uint32_t col0 = 0;                                                 // column of this pass in the LDS tile
+  for (int64_t kb0 = kb_first; kb0 < kb_end; kb0 += B) {
+    // the next pass's lines are requested before this pass is encoded and taken over once it has been
+    Raw raw[32];
+    const bool more = kb0 + B < kb_end;
+    if (more) load_block(kb0 + B + kbl, raw);
+    __builtin_amdgcn_sched_barrier(0);                               // (keep the loads above the encode)
+    uint32_t out[4], sbyte, idx;
+    const uint32_t col = col0 + kbl;
+    if constexpr (BF16) encode_block_serial_bf16<MODE>(xa, out, sbyte, idx);
+    else encode_block_serial<MODE>(xa, out, sbyte, idx);
+    e_lds[2 * rp][col] = u32x4{out[0], out[1], out[2], out[3]};
+    s_lds[2 * rp][col] = (uint8_t)sbyte;
+    if (PLUS) i_lds[2 * rp][col] = (uint8_t)idx;
+    if constexpr (BF16) encode_block_serial_bf16<MODE>(xb, out, sbyte, idx);
+    else encode_block_serial<MODE>(xb, out, sbyte, idx);
+    e_lds[2 * rp + 1][col] = u32x4{out[0], out[1], out[2], out[3]};
+    s_lds[2 * rp + 1][col] = (uint8_t)sbyte;
+    if (PLUS) i_lds[2 * rp + 1][col] = (uint8_t)idx;
+    col0 += B;
+    if (col0 < (uint32_t)C && more) {                                // uniform: the tile takes another pass
+      unpack(raw);
+      continue;
+    }
+    // ---- the tile is full (or the run ends): blocks kbf0 .. kbf0 + valid of rows row0 .. row0 + R leave
+    const int64_t kbf0 = kb0 + B - col0;
+    const uint32_t valid = (uint32_t)(kb_end - kbf0 < (int64_t)col0 ? kb_end - kbf0 : (int64_t)col0);
+    __syncthreads();
+    for (uint32_t m = t; m < (uint32_t)(R * C); m += 256u) {
+      const uint32_t lr = m / C, piece = m % C;
+      const int64_t gr = row0 + lr;
+      if (gr < rows && piece < valid)
+        __builtin_nontemporal_store(e_lds[lr][piece], reinterpret_cast<u32x4*>(elems) + gr * nbk + kbf0 + piece);
+    }
+    constexpr uint32_t kWords = C / 4;                               // 4-byte words of scale (index) bytes per row
+    for (uint32_t m = t; m < (PLUS ? 2u : 1u) * R * kWords; m += 256u) {
+      const bool is_scale = m < (uint32_t)R * kWords;
+      const uint32_t mm = is_scale ? m : m - R * kWords;
+      const uint32_t lr = mm / kWords, word = mm % kWords;
+      const int64_t gr = row0 + lr;
+      const uint8_t* from = (is_scale ? s_lds[lr] : i_lds[lr]) + 4 * word;
+      uint8_t* to = (is_scale ? scales : bm_idx) + gr * nbk + kbf0 + 4 * word;
+      if (gr < rows && 4 * word < valid) {
+        if (wide_meta) {                                             // then valid is a multiple of 4 as well
+          *reinterpret_cast<uint32_t*>(to) = *reinterpret_cast<const uint32_t*>(from);
+        } else {
+          for (uint32_t j = 0; j < 4 && 4 * word + j < valid; ++j) to[j] = from[j];
+        }
+      }
+    }
+    __syncthreads();
+    col0 = 0;
+    if (more) unpack(raw);
+  }
 }
 
 // ---- quantize straight into the MFMA-ready image (optionally also the canonical arrays) -------------------------
@@ -763,10 +982,23 @@ extern "C" int mxp_quantize_t(const void* src, int src_dtype, int64_t rows, int6
   if (ld_src < rows) return MXP_ERR_SHAPE;
   const int64_t nbk = K / kBlock;
   if (nbk > 65535) return MXP_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)((rows + 255) / 256), (unsigned)nbk);
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint4* e = reinterpret_cast<uint4*>(elems);
   const bool bf = src_dtype == MXP_BF16;
+  // the tiled kernel loads row pairs: every pair must start on a 4-byte (bf16) / 8-byte (fp32) boundary
+  // and addresses a block's 32 source lines with 32-bit offsets
+  const bool pairs_ok = (ld_src & 1) == 0 && (reinterpret_cast<uintptr_t>(src) & (bf ? 3u : 7u)) == 0 &&
+                        ld_src * (bf ? 2 : 4) * 32 < (int64_t)0x7FFFFFFF;
+  if (pairs_ok) {
+    dim3 grid((unsigned)((rows + kTRows - 1) / kTRows), (unsigned)((nbk + kTRun - 1) / kTRun));
+#define MXP_LAUNCH_QT(B, MD) hipLaunchKernelGGL((quantize_t_tiled_kernel<B, MD, kTAcc>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx)
+    if (fmt == MXP_FMT_MXFP4PP) { if (bf) MXP_LAUNCH_QT(true, 2); else MXP_LAUNCH_QT(false, 2); }
+    else if (fmt == MXP_FMT_MXFP4P) { if (bf) MXP_LAUNCH_QT(true, 1); else MXP_LAUNCH_QT(false, 1); }
+    else { if (bf) MXP_LAUNCH_QT(true, 0); else MXP_LAUNCH_QT(false, 0); }
+#undef MXP_LAUNCH_QT
+    return launch_status();
+  }
+  dim3 grid((unsigned)((rows + 255) / 256), (unsigned)nbk);
   if (fmt == MXP_FMT_MXFP4PP) {
     if (bf) hipLaunchKernelGGL((quantize_t_kernel<true, 2>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);
     else hipLaunchKernelGGL((quantize_t_kernel<false, 2>), grid, dim3(256), 0, s, src, rows, nbk, ld_src, e, scales, bm_idx);

@@ -291,6 +291,21 @@ def test_quantize_t(bf16):
         assert_q_equal(got, oracle.quantize_t(xt, FMT[fmt][1]), fmt, "quantize_t")
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("rows,K,pad", [(301, 160, 0), (301, 160, 1), (64, 256, 0), (130, 2048 + 96, 2), (1, 32, 0),
+                                        (2, 1024 + 256, 0), (257, 1056, 5)])
+def test_quantize_t_shapes(rows, K, pad, bf16):
+    """K-strided source: odd and even row counts and row strides (both kernels), whole and ragged 8-block tiles,
+    more than one 32-block run of K."""
+    x = synth.activations(rows, K, config_id=2, tensor_id=11, dtype="bf16" if bf16 else "f32")
+    xt = np.ascontiguousarray(x.T)                                     # [K][rows]
+    buf = torch.zeros((K, rows + pad), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    buf[:, :rows] = to_dev(xt)
+    for fmt in ("mxfp4", "mxfp4p", "mxfp4pp"):
+        got = mxp.quantize_t(buf[:, :rows], FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize(x, FMT[fmt][1]), fmt, "quantize_t %dx%d ld %d" % (rows, K, rows + pad))
+
+
 @pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p"])
 def test_dequantize_bit_exact(fmt):
     x = special_tensor(rows=64, K=256, seed=21)
