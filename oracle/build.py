@@ -7,15 +7,15 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "mxp_oracle.c")
+SRCS = [os.path.join(HERE, "mxp_oracle.c"), os.path.join(HERE, "mxw_oracle.c")]
 LIB = os.path.join(HERE, "libmxp_oracle.so")
 
 
 def build(force: bool = False) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-           "-Wall", "-Wextra", "-o", LIB, SRC, "-lm"]
+           "-Wall", "-Wextra", "-o", LIB] + SRCS + ["-lm"]
     subprocess.check_call(cmd)
     return LIB
 
