@@ -42,6 +42,23 @@ extern "C" {
 #define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion and de-conversion only; the image and product entry points
                            * return MXP_ERR_UNSUPPORTED for it (its BM and NBMs have different scales, which one
                            * block-scaled MFMA operand cannot carry) */
+/* Six- and eight-bit MX and MX+ formats (Sec. 4.2, data layout): conversion and de-conversion only (mxp_quantize,
+ * mxp_dequantize; every other entry point returns MXP_ERR_FORMAT or MXP_ERR_UNSUPPORTED for them).
+ *   MXFP6 / MXFP6+: elements E2M3 (sign | ee | mmm, bias 1, subnormals m/8, largest 7.5), e_max = 2; the BM of MXFP6+ is
+ *                   sign | mmmmm = 2^2 * 1.mmmmm (an E2M5 number).  elems [rows][K*3/4]: a block is 24 bytes, element i in
+ *                   bits [6i, 6i+6) of the block read as a little-endian bit string.
+ *   MXFP8 / MXFP8+: elements OCP E4M3 (sign | eeee | mmm, bias 7, subnormals m/8 * 2^-6, largest 448; S.1111.111, the NaN
+ *                   code, is never written and de-converts as the number its fields spell), e_max = 8; the BM of MXFP8+ is
+ *                   sign | mmmmmmm = 2^8 * 1.mmmmmmm (an E4M7 number).  elems [rows][K], one code per byte.
+ * Block rule as for MXFP4(+) with that e_max: scale byte = floor(log2|BM|) - e_max + 127, flush when floor(log2|BM|) <=
+ * -127 + e_max, byte 255 for NaN/Inf; elements round to nearest, ties to the even code, and saturate (an E4M3 element can
+ * reach 2^9 X > 448 X); the BM mantissa is rounded the same way and a carry saturates.  scales and bm_idx as above; the
+ * plain forms take no bm_idx.  De-conversion is exact in fp32; bf16 output is the fp32 result rounded to nearest even
+ * (only results below 2^-126 are affected). */
+#define MXP_FMT_MXFP6 3
+#define MXP_FMT_MXFP6P 4
+#define MXP_FMT_MXFP8 5
+#define MXP_FMT_MXFP8P 6
 
 /* status codes */
 #define MXP_OK 0

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmxp.so")
-SOURCES = ["mxp_quantize.hip", "mxp_convert.hip", "mxp_gemm.hip", "mxp_w4a16.hip"]
+SOURCES = ["mxp_quantize.hip", "mxp_convert.hip", "mxp_gemm.hip", "mxp_w4a16.hip", "mxp_wide.hip"]
 HEADERS = [os.path.join(CSRC, "mxp_common.h"), os.path.join(CSRC, "mxp_decode.h"), os.path.join(ROOT, "include", "mxp.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -13,6 +13,14 @@ constexpr int kNumCU = 256;   // MI355X compute units
 // and measured 10 % faster behind image kernels that store this way.
 #define MXP_IMAGE_STORE(v, p) (*(p) = (v))
 
+// six- and eight-bit formats (mxp_wide.hip)
+bool is_wide_format(int fmt);
+inline bool plain_wide_format(int fmt) { return fmt == MXP_FMT_MXFP6 || fmt == MXP_FMT_MXFP8; }   // no index byte
+int wide_quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                         uint8_t* scales, uint8_t* bm_idx, hipStream_t stream);
+int wide_dequantize_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                           int64_t K, void* dst, int dst_dtype, int64_t ld_dst, hipStream_t stream);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int launch_status() {

@@ -288,17 +288,19 @@ int dequantize_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t
 extern "C" int mxp_dequantize(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
                               int64_t K, void* dst, int dst_dtype, int64_t ld_dst, void* stream) {
   using namespace mxp;
-  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  const bool wide = is_wide_format(fmt);
+  if (!wide && fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
   if (dst_dtype != MXP_F32 && dst_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
   if (rows == 0 || K == 0) return MXP_OK;
-  if (!elems || !scales || !dst || (fmt != MXP_FMT_MXFP4 && !bm_idx)) return MXP_ERR_NULL;
+  if (!elems || !scales || !dst || (fmt != MXP_FMT_MXFP4 && !plain_wide_format(fmt) && !bm_idx)) return MXP_ERR_NULL;
   if (ld_dst < K) return MXP_ERR_SHAPE;
   const int64_t esz = dst_dtype == MXP_BF16 ? 2 : 4;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (bm_idx && !aligned16(bm_idx)) || (ld_dst * esz) % 16 != 0)
     return MXP_ERR_ALIGN;
   const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (wide) return wide_dequantize_launch(elems, scales, bm_idx, fmt, rows, K, dst, dst_dtype, ld_dst, s);
   const bool bf = dst_dtype == MXP_BF16;
   if (fmt == MXP_FMT_MXFP4PP) return dequantize_launch<2>(elems, scales, bm_idx, rows, K, nbk, nq, dst, bf, ld_dst, s);
   if (fmt == MXP_FMT_MXFP4P) return dequantize_launch<1>(elems, scales, bm_idx, rows, K, nbk, nq, dst, bf, ld_dst, s);

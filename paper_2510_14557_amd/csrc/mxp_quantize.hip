@@ -930,11 +930,15 @@ extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, 
 extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                             uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* stream) {
   using namespace mxp;
-  int rc = check_common(src, src_dtype, rows, K, fmt, elems, scales, bm_idx);
+  const bool wide = is_wide_format(fmt);
+  // the six- and eight-bit formats share every argument rule; their plain forms, like MXFP4, take no index array
+  int rc = check_common(src, src_dtype, rows, K, wide ? (plain_wide_format(fmt) ? MXP_FMT_MXFP4 : MXP_FMT_MXFP4P) : fmt,
+                        elems, scales, bm_idx);
   if (rc != MXP_OK || rows == 0 || K == 0) return rc;
   if (ld_src < K) return MXP_ERR_SHAPE;
   const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
   if ((ld_src * esz) % 16 != 0) return MXP_ERR_ALIGN;
+  if (wide) return wide_quantize_launch(src, src_dtype, rows, K, ld_src, fmt, elems, scales, bm_idx, static_cast<hipStream_t>(stream));
   return quantize_launch(src, src_dtype, rows, K, ld_src, fmt, elems, scales, bm_idx, static_cast<hipStream_t>(stream));
 }
 

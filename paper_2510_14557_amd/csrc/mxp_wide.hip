@@ -1,0 +1,298 @@
+// Six- and eight-bit MX / MX+ formats (Sec. 4.2, data layout): MXFP6 (E2M3), MXFP6+, MXFP8 (E4M3), MXFP8+.
+// Conversion and de-conversion only; the kernels behind mxp_quantize / mxp_dequantize for these format codes.
+//
+// Block rule as for MXFP4+ (Eq. 1, Sec. 4.1) with e_max = 2 (E2M3) or 8 (E4M3): scale byte = exponent field of the BM
+// - e_max, flush when that field is <= e_max, byte 255 for a block with NaN/Inf.  An ordinary element is x / X rounded
+// to the element type (nearest, ties to the even code, saturating at 7.5 / 448); the BM of a + format keeps e_max as
+// its exponent and spends all non-sign bits on mantissa (E0M5 / E0M7 in the slot; RNE, a carry saturates).
+//
+// Storage: eight-bit codes one per byte; six-bit codes as a little-endian bit string, element i of a block in bits
+// [6i, 6i+6) of its 24 bytes.  Four lanes share a block, a lane holds 8 consecutive elements (48 or 64 code bits).
+// All rounding is done on integer fields of the fp32 pattern, so nothing depends on the float mode.
+#include "mxp_common.h"
+
+namespace {
+
+using namespace mxp;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int kQuadSwap1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kQuadFromEven = 0xA0;  // quad_perm [0,0,2,2]: odd lanes read their left neighbour
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+template <int BITS>
+struct Elem;
+template <>
+struct Elem<6> {   // E2M3
+  static constexpr int MB = 3, BIAS = 1, EMAX = 2;
+  static constexpr uint32_t MAXCODE = 0x1Fu;   // 7.5
+};
+template <>
+struct Elem<8> {   // E4M3 (OCP): S.1111.111 is NaN, the largest number is S.1111.110 = 448
+  static constexpr int MB = 3, BIAS = 7, EMAX = 8;
+  static constexpr uint32_t MAXCODE = 0x7Eu;
+};
+
+// Round-to-nearest-even of sig >> shift, 1 <= shift <= 31.
+__device__ __forceinline__ uint32_t rne_shift(uint32_t sig, uint32_t shift) {
+  const uint32_t t = sig >> shift, rem = sig & ((1u << shift) - 1u), half = 1u << (shift - 1u);
+  return t + ((rem > half || (rem == half && (t & 1u))) ? 1u : 0u);
+}
+
+// Magnitude code of an ordinary element: a = fp32 magnitude bits of x, the block scale is 2^(sbyte - 127).
+// exponent/mantissa fields are produced as one integer, so a mantissa carry moves into the exponent by itself and
+// the subnormal range (field 0) needs no case of its own beyond its larger shift.
+template <int BITS>
+__device__ __forceinline__ uint32_t elem_code(uint32_t a, int sbyte) {
+  using F = Elem<BITS>;
+  if (a == 0u) return 0u;
+  int ea = (int)(a >> 23);
+  uint32_t sig = a & 0x7FFFFFu;
+  if (ea == 0) {                       // fp32 subnormal input: normalise so that bit 23 is the leading one
+    const int lz = __builtin_clz(sig) - 8;
+    sig <<= lz;
+    ea = 1 - lz;
+  } else {
+    sig |= 0x800000u;
+  }
+  const int t = ea - sbyte + F::BIAS;  // exponent field the scaled value would have as a normal number
+  const int eff = t > 1 ? t : 1;
+  int shift = (23 - F::MB) + (eff - t);
+  shift = shift > 31 ? 31 : shift;     // sig < 2^24: everything beyond 25 rounds to zero anyway
+  const uint32_t code = ((uint32_t)(eff - 1) << F::MB) + rne_shift(sig, (uint32_t)shift);
+  return umin(code, F::MAXCODE);
+}
+
+// BM mantissa of a + format: FB = BITS - 1 fraction bits at exponent e_max; a carry out of the field saturates (the
+// shared scale is never altered, Sec. 4.1).  The BM of a block that is not flushed is a normal fp32 number.
+template <int BITS>
+__device__ __forceinline__ uint32_t bm_code(uint32_t a) {
+  constexpr int FB = BITS - 1;
+  return umin(rne_shift(a & 0x7FFFFFu, 23 - FB), (1u << FB) - 1u);
+}
+
+// fp32 pattern of (-1)^sign * M * 2^p for M < 2^24, built from integer fields (exact whenever p >= -149; results
+// below the normal range are the value in units of 2^-149).
+__device__ __forceinline__ uint32_t make_f32(uint32_t sign, uint32_t M, int p) {
+  if (M == 0u) return sign << 31;
+  const int h = 31 - __builtin_clz(M);
+  const int biased = p + h + 127;
+  uint32_t bits;
+  if (biased >= 255) bits = 0x7F800000u;
+  else if (biased >= 1) bits = ((uint32_t)biased << 23) | ((M << (23 - h)) & 0x7FFFFFu);
+  else {
+    const int sh = p + 149;            // value = M * 2^(p + 149) units of 2^-149
+    bits = sh >= 0 ? (M << sh) : (M >> (-sh > 31 ? 31 : -sh));
+  }
+  return (sign << 31) | bits;
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(uint32_t bits) {
+  return (bits + 0x7FFFu + ((bits >> 16) & 1u)) >> 16;
+}
+
+// ---- quantize -------------------------------------------------------------------------------------------------
+// nq = number of 8-element groups (4 per block); a quad of lanes is one block, so a quad is inside or outside as a whole.
+template <bool BF16, int BITS, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_wide_kernel(const void* __restrict__ src, int64_t nbk, int64_t ld, int64_t nq,
+                                                            uint8_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                            uint8_t* __restrict__ bm_idx) {
+  using F = Elem<BITS>;
+  const uint32_t part = threadIdx.x & 3u;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; (q & ~(int64_t)3) < nq; q += stride) {
+    const int64_t g = q >> 2;                       // block
+    const int64_t row = g / nbk;
+    const int64_t off = row * ld + (g - row * nbk) * 32 + part * 8;
+    uint32_t a[8], sg[8];
+    if (BF16) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        a[2 * j] = (w[j] << 16) & 0x7FFF0000u;
+        sg[2 * j] = (w[j] >> 15) & 1u;
+        a[2 * j + 1] = w[j] & 0x7FFF0000u;
+        sg[2 * j + 1] = w[j] >> 31;
+      }
+    } else {
+      const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+      const u32x4 v0 = p[0], v1 = p[1];
+      const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        a[i] = w[i] & 0x7FFFFFFFu;
+        sg[i] = w[i] >> 31;
+      }
+    }
+    uint32_t mx = a[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = umax(mx, a[i]);
+    mx = umax(mx, dpp_mov<kQuadSwap1>(mx));
+    mx = umax(mx, dpp_mov<kQuadSwap2>(mx));
+    uint32_t pos = 32u;                             // lowest position holding the maximum
+#pragma unroll
+    for (int i = 7; i >= 0; --i) pos = (a[i] == mx) ? part * 8u + (uint32_t)i : pos;
+    pos = umin(pos, dpp_mov<kQuadSwap1>(pos));
+    pos = umin(pos, dpp_mov<kQuadSwap2>(pos));
+    const uint32_t E = mx >> 23;
+    const bool flush = E <= (uint32_t)F::EMAX, nonfinite = E == 255u;
+    const int sbyte = (int)E - F::EMAX;             // Eq. 1
+    uint32_t lo = 0, hi = 0;                        // this lane's code bits: 48 (lo, hi[15:0]) or 64
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint32_t c = (PLUS && pos == part * 8u + (uint32_t)i) ? bm_code<BITS>(a[i]) : elem_code<BITS>(a[i], sbyte);
+      c |= sg[i] << (BITS - 1);
+      const int b = i * BITS;                       // bit position inside the lane's string
+      if (b < 32) lo |= c << b;
+      if (b + BITS > 32) hi |= (b >= 32) ? (c << (b - 32)) : (c >> (32 - b));
+    }
+    uint32_t sb = (uint32_t)sbyte, idx = pos;
+    if (flush || nonfinite) {
+      lo = hi = 0;
+      idx = 0;
+      sb = nonfinite ? 255u : 0u;
+    }
+    if (BITS == 8) {
+      if (q < nq) *reinterpret_cast<u32x2*>(elems + g * 32 + part * 8) = u32x2{lo, hi};
+    } else {
+      // 24 bytes = 6 dwords per block: lane 0 -> d0; lane 1 -> d1, d2; lane 2 -> d3; lane 3 -> d4, d5
+      const uint32_t left_hi = dpp_mov<kQuadFromEven>(hi);
+      uint32_t* out = reinterpret_cast<uint32_t*>(elems + g * 24);
+      if (q < nq) {
+        if (part & 1u) {
+          out[part == 1u ? 1 : 4] = (left_hi & 0xFFFFu) | (lo << 16);
+          out[part == 1u ? 2 : 5] = (lo >> 16) | (hi << 16);
+        } else {
+          out[part == 0u ? 0 : 3] = lo;
+        }
+      }
+    }
+    if (part == 0u && q < nq) {
+      scales[g] = (uint8_t)sb;
+      if (PLUS) bm_idx[g] = (uint8_t)idx;
+    }
+  }
+}
+
+// ---- de-conversion (Eq. 2) ------------------------------------------------------------------------------------
+template <int BITS, bool PLUS, bool OUT_BF16>
+__global__ void __launch_bounds__(256) dequantize_wide_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                              const uint8_t* __restrict__ bm_idx, int64_t nbk, int64_t ld,
+                                                              int64_t nq, void* __restrict__ dst) {
+  using F = Elem<BITS>;
+  const uint32_t part = threadIdx.x & 3u;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += stride) {
+    const int64_t g = q >> 2;
+    const int64_t row = g / nbk;
+    const int64_t off = row * ld + (g - row * nbk) * 32 + part * 8;
+    uint32_t lo, hi;
+    if (BITS == 8) {
+      const u32x2 v = *reinterpret_cast<const u32x2*>(elems + g * 32 + part * 8);
+      lo = v.x;
+      hi = v.y;
+    } else {
+      const uint32_t* in = reinterpret_cast<const uint32_t*>(elems + g * 24);
+      const uint32_t first = (part >> 1) * 3u + (part & 1u);       // dwords 0,1 / 1,2 / 3,4 / 4,5
+      const uint32_t w0 = in[first], w1 = in[first + 1];
+      if (part & 1u) {
+        lo = (w0 >> 16) | (w1 << 16);
+        hi = w1 >> 16;
+      } else {
+        lo = w0;
+        hi = w1 & 0xFFFFu;
+      }
+    }
+    const uint32_t sbyte = scales[g];
+    const uint32_t bm = PLUS ? (bm_idx[g] & 31u) : 64u;
+    uint32_t f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int b = i * BITS;
+      uint32_t c = b < 32 ? (lo >> b) : (hi >> (b - 32));
+      if (b < 32 && b + BITS > 32) c |= hi << (32 - b);
+      c &= (1u << BITS) - 1u;
+      const uint32_t sign = c >> (BITS - 1), mag = c & ((1u << (BITS - 1)) - 1u);
+      uint32_t bits;
+      if (PLUS && bm == part * 8u + (uint32_t)i) {
+        // BM: 2^e_max * 1.m with BITS - 1 fraction bits
+        bits = make_f32(sign, (1u << (BITS - 1)) | mag, F::EMAX - (BITS - 1) + (int)sbyte - 127);
+      } else {
+        const uint32_t e = mag >> F::MB, m = mag & ((1u << F::MB) - 1u);
+        const uint32_t M = e ? ((1u << F::MB) | m) : m;            // subnormal: 0.m at the first binade's exponent
+        bits = make_f32(sign, M, (int)(e ? e : 1u) - F::BIAS - F::MB + (int)sbyte - 127);
+      }
+      if (sbyte == 0u) bits = 0u;                                  // reserved all-zero code, tested before anything else
+      if (sbyte == 255u) bits = 0x7FC00000u;
+      f[i] = bits;
+    }
+    if (OUT_BF16) {
+      uint32_t h[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = sbyte == 255u ? 0x7FC0u : f32_to_bf16_rne(f[i]);
+      *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off) =
+          u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    } else {
+      u32x4* o = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
+      o[0] = u32x4{f[0], f[1], f[2], f[3]};
+      o[1] = u32x4{f[4], f[5], f[6], f[7]};
+    }
+  }
+}
+
+dim3 grid_for(int64_t nq) {
+  const int64_t want = (nq + 255) / 256, cap = (int64_t)kNumCU * 32;
+  return dim3((unsigned)(want < cap ? want : cap));
+}
+
+}  // namespace
+
+namespace mxp {
+
+bool is_wide_format(int fmt) { return fmt >= MXP_FMT_MXFP6 && fmt <= MXP_FMT_MXFP8P; }
+
+int wide_quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
+                         uint8_t* scales, uint8_t* bm_idx, hipStream_t s) {
+  const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
+  const dim3 grid = grid_for(nq);
+  const bool bf = src_dtype == MXP_BF16;
+#define MXP_LAUNCH_QW(B, BT, P) hipLaunchKernelGGL((quantize_wide_kernel<B, BT, P>), grid, dim3(256), 0, s, src, nbk, ld_src, nq, elems, scales, bm_idx)
+  switch (fmt) {
+    case MXP_FMT_MXFP6: if (bf) MXP_LAUNCH_QW(true, 6, false); else MXP_LAUNCH_QW(false, 6, false); break;
+    case MXP_FMT_MXFP6P: if (bf) MXP_LAUNCH_QW(true, 6, true); else MXP_LAUNCH_QW(false, 6, true); break;
+    case MXP_FMT_MXFP8: if (bf) MXP_LAUNCH_QW(true, 8, false); else MXP_LAUNCH_QW(false, 8, false); break;
+    case MXP_FMT_MXFP8P: if (bf) MXP_LAUNCH_QW(true, 8, true); else MXP_LAUNCH_QW(false, 8, true); break;
+    default: return MXP_ERR_FORMAT;
+  }
+#undef MXP_LAUNCH_QW
+  return launch_status();
+}
+
+int wide_dequantize_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                           int64_t K, void* dst, int dst_dtype, int64_t ld_dst, hipStream_t s) {
+  const int64_t nbk = K / kBlock, nq = rows * nbk * 4;
+  const dim3 grid = grid_for(nq);
+  const bool bf = dst_dtype == MXP_BF16;
+#define MXP_LAUNCH_DW(BT, P, O) hipLaunchKernelGGL((dequantize_wide_kernel<BT, P, O>), grid, dim3(256), 0, s, elems, scales, bm_idx, nbk, ld_dst, nq, dst)
+  switch (fmt) {
+    case MXP_FMT_MXFP6: if (bf) MXP_LAUNCH_DW(6, false, true); else MXP_LAUNCH_DW(6, false, false); break;
+    case MXP_FMT_MXFP6P: if (bf) MXP_LAUNCH_DW(6, true, true); else MXP_LAUNCH_DW(6, true, false); break;
+    case MXP_FMT_MXFP8: if (bf) MXP_LAUNCH_DW(8, false, true); else MXP_LAUNCH_DW(8, false, false); break;
+    case MXP_FMT_MXFP8P: if (bf) MXP_LAUNCH_DW(8, true, true); else MXP_LAUNCH_DW(8, true, false); break;
+    default: return MXP_ERR_FORMAT;
+  }
+#undef MXP_LAUNCH_DW
+  return launch_status();
+}
+
+}  // namespace mxp

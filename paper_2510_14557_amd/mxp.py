@@ -13,6 +13,8 @@ import torch
 
 F32, BF16 = 0, 1
 MXFP4, MXFP4P, MXFP4PP = 0, 1, 2
+MXFP6, MXFP6P, MXFP8, MXFP8P = 3, 4, 5, 6          # conversion and de-conversion only
+_CODE_BITS = {MXFP4: 4, MXFP4P: 4, MXFP4PP: 4, MXFP6: 6, MXFP6P: 6, MXFP8: 8, MXFP8P: 8}
 IMAGE_E2M3, IMAGE_E2M1 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -110,11 +112,11 @@ def _p(t):
 
 
 def quantize(x: torch.Tensor, fmt: int = MXFP4P):
-    """x [rows, K] fp32/bf16 on the GPU -> (elems [rows,K/2], scales [rows,K/32], bm_idx [rows,K/32]) uint8."""
+    """x [rows, K] fp32/bf16 on the GPU -> (elems [rows, K*bits/8], scales [rows,K/32], bm_idx [rows,K/32]) uint8."""
     _dev2d(x)
     rows, K = x.shape
     ld = x.stride(0) if rows > 1 else max(K, 1)
-    elems = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    elems = torch.empty((rows, K * _CODE_BITS.get(fmt, 4) // 8), dtype=torch.uint8, device=x.device)
     scales = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
     idx = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
     _check(lib().mxp_quantize(_p(x), _dt(x), rows, K, ld, fmt, _p(elems), _p(scales), _p(idx), _stream()), "mxp_quantize")
@@ -159,7 +161,7 @@ def quantize_t(xt: torch.Tensor, fmt: int = MXFP4P):
 
 def dequantize(q, fmt: int = MXFP4P, dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
     elems, scales, idx = q
-    rows, K = elems.shape[0], elems.shape[1] * 2
+    rows, K = elems.shape[0], elems.shape[1] * 8 // _CODE_BITS.get(fmt, 4)
     if out is None:
         out = torch.empty((rows, K), dtype=dtype, device=elems.device)
     ld = out.stride(0) if rows > 1 else max(K, 1)

@@ -52,6 +52,15 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_dequantize(p, p, p, 9, 4, 64, p, mxp.F32, 64, None) == -5
     assert L.mxp_dequantize(p, p, p, mxp.MXFP4P, 4, 64, p, 5, 64, None) == -4
     assert L.mxp_dequantize(p, p, p, mxp.MXFP4P, 4, 40, p, mxp.F32, 64, None) == -2
+    # six- and eight-bit formats: conversion and de-conversion take them (same argument rules; the plain forms need no
+    # index array), every other entry point reports them as a format it does not know
+    assert L.mxp_quantize(p, mxp.BF16, 4, 48, 48, mxp.MXFP8P, p, p, p, None) == -2
+    assert L.mxp_quantize(p, mxp.BF16, 4, 64, 64, mxp.MXFP6P, p, p, None, None) == -1
+    assert L.mxp_quantize(p, mxp.BF16, 0, 64, 64, mxp.MXFP6, None, None, None, None) == 0
+    assert L.mxp_dequantize(p, p, None, mxp.MXFP8P, 4, 64, p, mxp.F32, 64, None) == -1
+    assert L.mxp_dequantize(p, p, None, mxp.MXFP8, 0, 64, p, mxp.F32, 64, None) == 0
+    assert L.mxp_quantize_t(p, mxp.BF16, 4, 64, 64, mxp.MXFP6P, p, p, p, None) == -5
+    assert L.mxp_prepack(p, p, p, mxp.MXFP8P, 64, 64, p, 1 << 20, None) in (-5, -8)
     # workspace too small
     need = mxp.gemm_workspace_bytes(64, 64, 64)
     assert need > 0

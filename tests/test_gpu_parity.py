@@ -575,3 +575,110 @@ def test_gemm_half_tile_schedule_sampled():
     D2 = torch.full((M, N), float("nan"), device="cuda")
     mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P, out=D2)
     assert not torch.isnan(D2).any() and torch.equal(D, D2)
+
+
+# ---- six- and eight-bit MX / MX+ formats (Sec. 4.2 data layout): conversion and de-conversion --------------------
+WIDE = {"mxfp6": (mxp.MXFP6, oracle.wide.MXFP6), "mxfp6p": (mxp.MXFP6P, oracle.wide.MXFP6P),
+        "mxfp8": (mxp.MXFP8, oracle.wide.MXFP8), "mxfp8p": (mxp.MXFP8P, oracle.wide.MXFP8P)}
+
+
+def wide_cases(bf16):
+    """Ordinary activations; blocks over the whole exponent range incl. flushed, subnormal and non-finite inputs; blocks
+    whose ordinary elements sit on rounding midpoints and above the largest element value."""
+    out = [special_tensor(bf16=bf16), special_tensor(rows=70, K=224, seed=5, bf16=bf16),
+           synth.activations(130, 4096 + 64, config_id=2, tensor_id=7, dtype="bf16" if bf16 else "f32"),
+           synth.activations(1, 32, config_id=2, tensor_id=4, dtype="bf16" if bf16 else "f32")]
+    rng = np.random.default_rng(77)
+    x = np.zeros((96, 64), np.float32)
+    for r in range(96):
+        for b in range(2):
+            top = np.float32(2.0 ** rng.integers(-120, 120))
+            v = np.zeros(32, np.float32)
+            kind = (r + b) % 3
+            if kind == 0:      # midpoints of the eight-bit element grid (k + 0.5) * 2^(e-3), BM at 2^8 * X
+                k = rng.integers(8, 16, 31)
+                e = rng.integers(-9, 8, 31)
+                v[1:] = (k + 0.5) * np.exp2(e - 3.0)
+                v[0] = 256.0 * 1.7
+            elif kind == 1:    # the six-bit grid, BM at 2^2 * X
+                k = rng.integers(0, 16, 31)
+                e = rng.integers(0, 3, 31)
+                v[1:] = (k + 0.5) * np.exp2(e - 3.0)
+                v[0] = 4.0 * 1.9
+            else:              # elements just below the BM: above 448 X and 7.5 X
+                v[:] = rng.uniform(0.85, 1.0, 32)
+                v[5] = 1.0
+            x[r, 32 * b:32 * b + 32] = v * top * rng.choice([-1.0, 1.0], 32)
+    out.append(synth.f32_to_bf16_bits(x) if bf16 else x)
+    return out
+
+
+@pytest.mark.parametrize("fmt", list(WIDE))
+@pytest.mark.parametrize("bf16", [False, True])
+def test_wide_quantize_bit_exact(fmt, bf16):
+    for x in wide_cases(bf16):
+        want = oracle.wide.quantize(x, WIDE[fmt][1])
+        got = mxp.quantize(to_dev(x), WIDE[fmt][0])
+        torch.cuda.synchronize()
+        names = ("elems", "scales") + (("idx",) if fmt.endswith("p") else ())
+        for name, g, w in zip(names, got, want):
+            g = g.cpu().numpy()
+            assert g.shape == w.shape, (fmt, name, g.shape, w.shape)
+            bad = np.argwhere(g != w)
+            assert len(bad) == 0, "%s %s %s: %d differ, first at %s: got %d want %d" % (
+                fmt, x.shape, name, len(bad), bad[0], g[tuple(bad[0])], w[tuple(bad[0])])
+    # strided rows
+    x = wide_cases(bf16)[1]
+    d = to_dev(x)
+    wide = torch.zeros((x.shape[0], x.shape[1] + 64), dtype=d.dtype, device="cuda")
+    wide[:, :x.shape[1]] = d
+    got = mxp.quantize(wide[:, :x.shape[1]], WIDE[fmt][0])
+    want = oracle.wide.quantize(x, WIDE[fmt][1])
+    assert all((g.cpu().numpy() == w).all() for g, w in zip(got[:2], want[:2]))
+
+
+@pytest.mark.parametrize("fmt", list(WIDE))
+def test_wide_dequantize(fmt):
+    """Every code at every position, every scale byte that matters, junk index bits; fp32 exact, bf16 = RNE of it."""
+    bits = 6 if "6" in fmt else 8
+    rng = np.random.default_rng(31)
+    rows, nb = 96, 4
+    codes = rng.integers(0, 1 << bits, size=(rows, nb, 32), dtype=np.uint8)
+    codes[:8, 0] = (np.arange(8)[:, None] * 32 + np.arange(32)[None, :]) % (1 << bits)      # all codes
+    scales = rng.integers(1, 247, size=(rows, nb), dtype=np.uint8)
+    scales[:16, 1] = np.arange(16, dtype=np.uint8)                                          # tiny scales: subnormal results
+    scales[16:20, 2] = [0, 255, 246, 1]
+    idx = rng.integers(0, 256, size=(rows, nb), dtype=np.uint8)
+    bitstr = ((codes[..., None] >> np.arange(bits)) & 1).astype(np.uint8).reshape(rows, nb, 32 * bits)
+    elems = np.packbits(bitstr, axis=2, bitorder="little").reshape(rows, nb * 4 * bits)
+    q = (elems, scales, idx)
+    ref = oracle.wide.dequantize(q, WIDE[fmt][1])
+    nan = np.isnan(ref)
+    dq = tuple(torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in q)
+    got32 = mxp.dequantize(dq, WIDE[fmt][0], torch.float32).cpu().numpy().astype(np.float64)
+    assert (np.isnan(got32) == nan).all()
+    fin = ~nan & np.isfinite(ref) & (np.abs(ref) < 3.4e38)
+    assert (got32[fin] == ref[fin]).all() and (np.signbit(got32[fin]) == np.signbit(ref[fin])).all()
+    got16 = mxp.dequantize(dq, WIDE[fmt][0], torch.bfloat16).float().cpu().numpy().astype(np.float64)
+    want16 = torch.from_numpy(ref.astype(np.float32)).to(torch.bfloat16).float().numpy().astype(np.float64)
+    assert (np.isnan(got16) == nan).all() and (got16[fin] == want16[fin]).all()
+    # strided destination keeps the padding
+    out = torch.full((rows, nb * 32 + 32), 5.0, device="cuda")
+    mxp.dequantize(dq, WIDE[fmt][0], torch.float32, out=out[:, :nb * 32])
+    o = out.cpu().numpy()
+    assert (o[:, nb * 32:] == 5.0).all() and (o[:, :nb * 32][fin] == ref[fin]).all()
+
+
+@pytest.mark.parametrize("fmt", list(WIDE))
+def test_wide_round_trip_full_size(fmt):
+    """The benchmark's activation tensor: conversion then de-conversion against the oracle on sampled rows."""
+    x = synth.activations(4096, 4096, config_id=4, tensor_id=0, dtype="bf16")
+    d = to_dev(x)
+    q = mxp.quantize(d, WIDE[fmt][0])
+    back = mxp.dequantize(q, WIDE[fmt][0], torch.bfloat16)
+    rows = np.array([0, 1, 31, 32, 255, 256, 1023, 2048, 4000, 4095])
+    want = oracle.wide.quantize(x[rows], WIDE[fmt][1])
+    for g, w in list(zip(q, want))[: 3 if fmt.endswith("p") else 2]:       # the plain forms write no index bytes
+        assert (g[torch.from_numpy(rows).cuda()].cpu().numpy() == w).all()
+    ref = oracle.wide.dequantize(want, WIDE[fmt][1])
+    assert (back[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64) == ref).all()
