@@ -39,9 +39,10 @@ extern "C" {
 /* block formats */
 #define MXP_FMT_MXFP4 0  /* plain OCP MXFP4 (Sec. 2) */
 #define MXP_FMT_MXFP4P 1 /* MXFP4+ (Sec. 4)          */
-#define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion and de-conversion only; the image and product entry points
+#define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion, de-conversion, and the product through E4M3 images
+                           * (mxp_prepack_e4m3 + mxp_gemm_prepacked); the other image and product entry points
                            * return MXP_ERR_UNSUPPORTED for it (its BM and NBMs have different scales, which one
-                           * block-scaled MFMA operand cannot carry) */
+                           * E2M3 operand cannot carry) */
 /* Six- and eight-bit MX and MX+ formats (Sec. 4.2, data layout): conversion and de-conversion only (mxp_quantize,
  * mxp_dequantize; every other entry point returns MXP_ERR_FORMAT or MXP_ERR_UNSUPPORTED for them).
  *   MXFP6 / MXFP6+: elements E2M3 (sign | ee | mmm, bias 1, subnormals m/8, largest 7.5), e_max = 2; the BM of MXFP6+ is
@@ -123,6 +124,18 @@ int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_i
 #define MXP_IMAGE_E2M1 1
 size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K);
 int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K,
+                     void* image, size_t image_bytes, void* stream);
+
+/* MXP_IMAGE_E4M3: the image kind for MXFP4++ operands (Sec. 4.3; it takes MXFP4 and MXFP4+ operands too).  The ordinary
+ * elements of an MXFP4++ block are scaled by 2^(shared_exp - delta) and its BM by 2^shared_exp, which one E2M3 code per
+ * element cannot express; with the block's scale byte set to (scale byte - delta + 2) every element is an FP8 E4M3
+ * number (ordinary: E2M1 value / 4; BM: 1.mmm * 2^delta), so this image carries the block exactly and the product is
+ * formed as for the other kinds -- at half the MFMA rate, which is the price of MXFP4++ on this hardware.  Both
+ * operands of a product must then be E4M3 images (anything else returns MXP_ERR_UNSUPPORTED).  Index bytes with
+ * delta > scale byte - 1 and scale bytes 253, 254, none of which a conversion writes, are outside its domain. */
+#define MXP_IMAGE_E4M3 2
+size_t mxp_image_bytes_e4m3(int64_t rows, int64_t K);
+int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                      void* image, size_t image_bytes, void* stream);
 
 /* Conversion (Sec. 4.1, 4.2) written directly as an image: same source arguments and the same encoding as

@@ -40,6 +40,10 @@ constexpr int kTileBytes = 1536;
 // A plain MXFP4 operand (no BM) can stay in 4-bit codes: the MFMA takes E2M1 for one operand and E2M3 for the other at
 // the same rate.  Its tile is the 64 lanes' 16-byte canonical blocks, [64 x 16 B] = 1024 B; everything else is the same.
 constexpr int kTileBytesE2M1 = 1024;
+// An MXFP4++ operand (Sec. 4.3) has two scales per block, 2^delta apart.  In units of 2^(shared_exp - delta + 2) every
+// one of its elements is an FP8 E4M3 number (ordinary elements 0.125 ... 1.5, the BM up to 1.875 * 2^7), so an image of
+// E4M3 codes, 32 bytes per lane = [64 x 16 B][64 x 16 B] = 2048 B per tile, carries the block exactly.
+constexpr int kTileBytesE4M3 = 2048;
 constexpr int kRowPad = 256;
 constexpr int kKPad = 128;
 

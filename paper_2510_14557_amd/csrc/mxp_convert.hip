@@ -222,9 +222,107 @@ __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restri
   if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
 }
 
+// MXFP4 / MXFP4+ / MXFP4++ operand -> E4M3 image (the one image kind that can hold the two scales of an MXFP4++
+// block, Sec. 4.3).  With the block scale byte raised to scale byte - delta + 2, an ordinary element (E2M1 value v,
+// true value v * 2^(shared_exp - delta)) becomes v / 4, i.e. 0, 0.125, 0.25 ... 1.5: sign | LUT[magnitude]; the BM
+// (2^2 * 1.mmm * 2^shared_exp) becomes 1.mmm * 2^delta: sign | (delta + 7) << 3 | mmm.  Same patch walk and LDS
+// staging as above.
+constexpr uint64_t kE2M1QuarterAsE4M3 = 0x3C3834302C282000ull;   // byte m = E4M3 code of (E2M1 magnitude m) / 4
+
+__device__ __forceinline__ uint32_t nibbles4_to_e4m3(uint32_t h) {   // low 16 bits: 4 nibbles -> 4 bytes
+  uint32_t out = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t n = (h >> (4 * i)) & 15u;
+    const uint32_t code = (uint32_t)(kE2M1QuarterAsE4M3 >> (8u * (n & 7u))) & 0xFFu;
+    out |= (code | ((n & 8u) << 4)) << (8 * i);
+  }
+  return out;
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(256) prepack_e4m3_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                           const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                           int64_t k_tiles, uint8_t* __restrict__ img_elems,
+                                                           uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE4M3];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const uint32_t slot = (kb_in & 1u) * 32u + r_in;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  uint32_t n[4] = {0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u, delta = 0u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x4 v = __builtin_nontemporal_load(elems + b);
+    n[0] = v.x; n[1] = v.y; n[2] = v.z; n[3] = v.w;
+    sbyte = scales[b];
+    if (MODE >= 1 && sbyte != 0u && sbyte != 255u) {
+      const uint32_t ib = bm_idx[b];
+      bm = ib & 31u;
+      if (MODE == 2) delta = ib >> 5;
+    }
+    if (sbyte == 0u) n[0] = n[1] = n[2] = n[3] = 0u;          // flushed block: zero whatever the nibbles say
+  }
+  uint32_t d[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    d[2 * j] = nibbles4_to_e4m3(n[j] & 0xFFFFu);
+    d[2 * j + 1] = nibbles4_to_e4m3(n[j] >> 16);
+  }
+  if (MODE >= 1 && bm < 32u) {
+    const uint32_t nib = (n[bm >> 3] >> (4u * (bm & 7u))) & 15u;
+    const uint32_t code = ((nib & 8u) << 4) | ((delta + 7u) << 3) | (nib & 7u);
+    const uint32_t sh = (bm & 3u) * 8u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if ((bm >> 2) == (uint32_t)j) d[j] = (d[j] & ~(0xFFu << sh)) | (code << sh);
+  }
+  // scale byte of the image: flushed and padding blocks are zeros with a unit scale, NaN stays NaN
+  uint32_t sb = sbyte == 255u ? 255u : (sbyte == 0u ? 127u : sbyte - delta + 2u);
+  if (row >= rows || kb >= nbk) sb = 127u;
+  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytesE4M3;
+  // FP8 operand registers: the first four hold k = 16 (lane / 32) + 0..15, the last four the same + 32, while the
+  // scale of lanes 0..31 covers k 0..31 and that of lanes 32..63 k 32..63.  Block (kb_in & 1) of the tile therefore
+  // fills register half (kb_in & 1) of both lanes of its row: its codes 0..15 in lane r, 16..31 in lane r + 32.
+  const uint32_t half = (kb_in & 1u) * 1024u;
+  *reinterpret_cast<u32x4*>(tile + half + r_in * 16u) = u32x4{d[0], d[1], d[2], d[3]};
+  *reinterpret_cast<u32x4*>(tile + half + (32u + r_in) * 16u) = u32x4{d[4], d[5], d[6], d[7]};
+  tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sb;
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytesE4M3;
+  const uint32_t nbytes = (uint32_t)nt * kTileBytesE4M3;
+  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+    MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
 }  // namespace
 
 namespace mxp {
+
+int prepack_e4m3_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                        void* image, hipStream_t stream) {
+  const ImageGeom g = image_geom(rows, K, kTileBytesE4M3);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_wg);
+  const u32x4* e = reinterpret_cast<const u32x4*>(elems);
+  if (fmt == MXP_FMT_MXFP4PP)
+    hipLaunchKernelGGL((prepack_e4m3_kernel<2>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  else if (fmt == MXP_FMT_MXFP4P)
+    hipLaunchKernelGGL((prepack_e4m3_kernel<1>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  else
+    hipLaunchKernelGGL((prepack_e4m3_kernel<0>), grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is);
+  return launch_status();
+}
 
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream) {
@@ -315,6 +413,23 @@ extern "C" size_t mxp_image_bytes(int64_t rows, int64_t K) {
 extern "C" size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K) {
   if (rows < 0 || K < 0) return 0;
   return (size_t)mxp::image_geom(rows, K, mxp::kTileBytesE2M1).total();
+}
+
+extern "C" size_t mxp_image_bytes_e4m3(int64_t rows, int64_t K) {
+  if (rows < 0 || K < 0) return 0;
+  return (size_t)mxp::image_geom(rows, K, mxp::kTileBytesE4M3).total();
+}
+
+extern "C" int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                                int64_t K, void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image || (fmt != MXP_FMT_MXFP4 && !bm_idx)) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
+  if (image_bytes < (size_t)image_geom(rows, K, kTileBytesE4M3).total()) return MXP_ERR_WORKSPACE;
+  return prepack_e4m3_launch(elems, scales, bm_idx, fmt, rows, K, image, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image,

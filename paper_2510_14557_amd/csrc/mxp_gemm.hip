@@ -16,6 +16,8 @@ namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream);
 int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
+int prepack_e4m3_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                        void* image, hipStream_t stream);
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
                           uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream);
 }  // namespace mxp
@@ -29,6 +31,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kFmtE2M3 = 2;  // cbsz / blgp code of the f8f6f4 MFMA for FP6 E2M3 operands
+constexpr int kFmtE4M3 = 0;  // ... for FP8 E4M3 operands (32 bytes per lane; the instruction then runs at half rate)
 constexpr int kFmtE2M1 = 4;  // ... for FP4 E2M1 operands (16 bytes per lane: registers 4..7 of the operand are ignored)
 
 // The B tile goes in as the MFMA's first operand and the A tile as its second, i.e. the instruction forms the
@@ -49,12 +52,12 @@ __device__ __forceinline__ v16f mfma_sel(const v8i& a, const v8i& b, const v16f&
 template <int WM_, int WN_, int WAVES_M_, int WAVES_N_, int BT_ = kTileBytes, int AT_ = kTileBytes>
 struct Cfg {
   static constexpr int WM = WM_, WN = WN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-  static constexpr int BT = BT_;                                 // bytes of a B tile: 1536 (E2M3) or 1024 (E2M1)
-  static constexpr int FB = BT_ == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  static constexpr int BT = BT_;                                 // bytes of a B tile: 1536 (E2M3), 1024 (E2M1) or 2048 (E4M3)
+  static constexpr int FB = BT_ == kTileBytes ? kFmtE2M3 : (BT_ == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
   static constexpr int AT = AT_;                                 // bytes of an A tile, likewise
-  static constexpr int FA = AT_ == kTileBytes ? kFmtE2M3 : kFmtE2M1;
-  static_assert(BT_ == kTileBytes || BT_ == kTileBytesE2M1, "B tile kind");
-  static_assert(AT_ == kTileBytes || AT_ == kTileBytesE2M1, "A tile kind");
+  static constexpr int FA = AT_ == kTileBytes ? kFmtE2M3 : (AT_ == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
+  static_assert(BT_ == kTileBytes || BT_ == kTileBytesE2M1 || BT_ == kTileBytesE4M3, "B tile kind");
+  static_assert(AT_ == kTileBytes || AT_ == kTileBytesE2M1 || AT_ == kTileBytesE4M3, "A tile kind");
   static constexpr int TM = WM * WAVES_M, TN = WN * WAVES_N;   // 32-row tiles per workgroup
   static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
   static constexpr int A_BYTES = TM * AT, B_BYTES = TN * BT;
@@ -205,8 +208,14 @@ __device__ __forceinline__ v8i read_operand_e2m1(const uint8_t* tile, int lane) 
   const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
   return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
 }
+__device__ __forceinline__ v8i read_operand_e4m3(const uint8_t* tile, int lane) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  const u32x4 hi = *reinterpret_cast<const u32x4*>(tile + 1024 + lane * 16);
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+}
 template <int TILE_BYTES>
 __device__ __forceinline__ v8i read_b(const uint8_t* tile, int lane) {
+  if (TILE_BYTES == kTileBytesE4M3) return read_operand_e4m3(tile, lane);
   return TILE_BYTES == kTileBytes ? read_operand(tile, lane) : read_operand_e2m1(tile, lane);
 }
 
@@ -283,11 +292,7 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
     }
 #pragma unroll
     for (int j = 0; j < C::WN; ++j) {
-      const uint8_t* t = st + C::A_BYTES + (wn * C::WN + j) * C::BT;
-      const u32x4 lo = *reinterpret_cast<const u32x4*>(t + lane * 16);
-      u32x2 hi = {0, 0};
-      if (C::BT == kTileBytes) hi = *reinterpret_cast<const u32x2*>(t + 1024 + lane * 8);
-      b[j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      b[j] = read_b<C::BT>(st + C::A_BYTES + (wn * C::WN + j) * C::BT, lane);
     }
     // scale dwords: byte q of group g = row tile 4g + q.  The tiles of one wavefront lie in one group when WM <= 4
     // (WM in {1, 2, 4} and workgroup tile origins are multiples of the workgroup tile); shift so that op_sel = i & 3
@@ -907,6 +912,8 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
                 int d_dtype, int64_t ldd, hipStream_t s) {
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
+  // E4M3 images (the MXFP4++ product, Sec. 4.3) run on the two-stage kernel: half the MFMA rate leaves it the time
+  if (a_kind == MXP_IMAGE_E4M3) return launch_cfg<Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
@@ -948,9 +955,10 @@ extern "C" size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
 
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
                                   int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
-  if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
+  if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1 && a_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
   if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
+  if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);

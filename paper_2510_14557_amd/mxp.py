@@ -15,13 +15,13 @@ F32, BF16 = 0, 1
 MXFP4, MXFP4P, MXFP4PP = 0, 1, 2
 MXFP6, MXFP6P, MXFP8, MXFP8P = 3, 4, 5, 6          # conversion and de-conversion only
 _CODE_BITS = {MXFP4: 4, MXFP4P: 4, MXFP4PP: 4, MXFP6: 6, MXFP6P: 6, MXFP8: 8, MXFP8P: 8}
-IMAGE_E2M3, IMAGE_E2M1 = 0, 1
+IMAGE_E2M3, IMAGE_E2M1, IMAGE_E4M3 = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -57,6 +57,9 @@ def lib():
     L.mxp_image_bytes_e2m1.argtypes = [i64, i64]
     L.mxp_image_bytes_e2m1.restype = sz
     L.mxp_prepack_e2m1.argtypes = [vp, vp, i64, i64, vp, sz, vp]
+    L.mxp_image_bytes_e4m3.argtypes = [i64, i64]
+    L.mxp_image_bytes_e4m3.restype = sz
+    L.mxp_prepack_e4m3.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
     L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
     L.mxp_gemm_bf16a_workspace_bytes.restype = sz
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
@@ -67,7 +70,7 @@ def lib():
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
-    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_prepack_e2m1", "mxp_gemm", "mxp_gemm_prepacked",
+    for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_prepack_e2m1", "mxp_prepack_e4m3", "mxp_gemm", "mxp_gemm_prepacked",
               "mxp_gemm_bf16a"):
         getattr(L, n).restype = i32
     _lib = L
@@ -205,6 +208,20 @@ def quantize_image(x: torch.Tensor, fmt: int = MXFP4P, canonical: bool = False, 
 
 def image_bytes_e2m1(rows: int, K: int) -> int:
     return int(lib().mxp_image_bytes_e2m1(rows, K))
+
+
+def image_bytes_e4m3(rows: int, K: int) -> int:
+    return int(lib().mxp_image_bytes_e4m3(rows, K))
+
+
+def prepack_e4m3(q, fmt: int = MXFP4PP, out: torch.Tensor | None = None):
+    """Canonical MXFP4 / MXFP4+ / MXFP4++ -> E4M3 image (the kind that carries MXFP4++ operands)."""
+    elems, scales, idx = q
+    rows, K = elems.shape[0], elems.shape[1] * 2
+    if out is None:
+        out = torch.empty(image_bytes_e4m3(rows, K), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_e4m3(_p(elems), _p(scales), _p(idx), fmt, rows, K, _p(out), out.numel(), _stream()), "mxp_prepack_e4m3")
+    return out
 
 
 def prepack_e2m1(q, out: torch.Tensor | None = None):

@@ -80,7 +80,13 @@ def test_argument_errors_are_reported_not_launched():
     # image kinds
     assert L.mxp_prepack_e2m1(p, p, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_e2m1(p, None, 64, 64, p, 1 << 20, None) == -1
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 2, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 3, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 2, p, mxp.F32, 64, None) == -8      # E4M3 images only in pairs
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 2, p, 1, p, mxp.F32, 64, None) == -8
+    assert L.mxp_prepack_e4m3(p, p, p, mxp.MXFP4PP, 64, 64, p, 16, None) == -6
+    assert L.mxp_prepack_e4m3(p, p, None, mxp.MXFP4PP, 64, 64, p, 1 << 20, None) == -1
+    assert L.mxp_prepack_e4m3(p, p, p, mxp.MXFP6P, 64, 64, p, 1 << 20, None) == -5
+    assert mxp.image_bytes_e4m3(256, 128) == 8 * 2 * 2048 + 2 * 2 * 256
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 3, p, 0, p, mxp.F32, 64, None) == -5
     assert L.mxp_gemm_prepacked(64, 64, 64, p, mxp.IMAGE_E2M1, p, mxp.IMAGE_E2M3, p, mxp.F32, 64, None) == -8
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, None, mxp.IMAGE_E2M1, p, mxp.F32, 64, None) == -1

@@ -682,3 +682,97 @@ def test_wide_round_trip_full_size(fmt):
         assert (g[torch.from_numpy(rows).cuda()].cpu().numpy() == w).all()
     ref = oracle.wide.dequantize(want, WIDE[fmt][1])
     assert (back[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64) == ref).all()
+
+
+# ---- the MXFP4++ product (Sec. 4.3) through E4M3 images ------------------------------------------------------------
+# In an E4M3 image the codes of a block span 0.125 ... 240, so the 64 products one MFMA sums span up to 2^22.  The FP8
+# dot product of the instruction aligns them to the largest one and keeps about 13 bits below it (measured: errors up
+# to 2^-12.7 of the largest product of a k-tile, only in k-tiles where both operands have a large delta; every other
+# output is exact), where the E2M3 / E2M1 products (12 bits of range) lose nothing.  Hence a wider bound for this
+# path: |err| <= 2^-12 * sum_k |a_k b_k| per element and 1e-4 relative Frobenius.
+def check_gemm_e4m3(D, ref, S, what=""):
+    D = D.double().cpu().numpy()
+    fro = np.linalg.norm(D - ref) / max(np.linalg.norm(ref), 1e-300)
+    assert fro <= 1e-4, "%s: relative Frobenius error %.3e" % (what, fro)
+    worst = (np.abs(D - ref) - 2.0 ** -12 * S).max() if D.size else 0.0
+    assert worst <= 0, "%s: element error exceeds 2^-12 * sum|ab| by %.3e" % (what, worst)
+
+
+def test_gemm_mxfp4pp_hand_case():
+    """One block per operand with a small-valued rest, so that delta > 0 on both sides: closed form."""
+    a = np.zeros((1, 32), np.float32)
+    b = np.zeros((1, 32), np.float32)
+    a[0, 3], a[0, 10], a[0, 11] = 6.5, 0.09375, -0.046875        # BM 6.5 (exact: 4 * 1.625); rest needs delta = 5
+    b[0, 3], b[0, 10], b[0, 20] = -7.0, 0.375, 0.25              # BM -7.0; rest 0.375, 0.25: delta = 3
+    qa, qb = oracle.quantize(a, oracle.MXFP4PP), oracle.quantize(b, oracle.MXFP4PP)
+    assert qa[2][0, 0] >> 5 > 0 and qb[2][0, 0] >> 5 > 0
+    assert (oracle.dequantize(qa, oracle.MXFP4PP) == a).all() and (oracle.dequantize(qb, oracle.MXFP4PP) == b).all()
+    ia, ib = mxp.prepack_e4m3(q_dev(qa)), mxp.prepack_e4m3(q_dev(qb))
+    D = mxp.gemm_prepacked(1, 1, 32, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    assert D.cpu().numpy()[0, 0] == 6.5 * -7.0 + 0.09375 * 0.375
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (100, 200, 416), (257, 300, 1024), (300, 520, 2048),
+                                   (64, 1000, 4160), (512, 1100, 640)])
+def test_gemm_mxfp4pp_shapes(M, N, K):
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = oracle.quantize(a, oracle.MXFP4PP), oracle.quantize(w, oracle.MXFP4PP)
+    assert M * K < 4096 or len(np.unique(qa[2] >> 5)) >= 3              # several shifts occur
+    ref, S = oracle.gemm(qa, oracle.MXFP4PP, qb, oracle.MXFP4PP)
+    ia, ib = mxp.prepack_e4m3(q_dev(qa)), mxp.prepack_e4m3(q_dev(qb))
+    assert ia.numel() == mxp.image_bytes_e4m3(M, K)
+    D = mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    check_gemm_e4m3(D, ref, S, "mxfp4++ %dx%dx%d" % (M, N, K))
+    Db = mxp.gemm_prepacked(M, N, K, ia, ib, out_dtype=torch.bfloat16, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+    # an MXFP4+ operand in an E4M3 image gives the products of its E2M3 image (mixed: A MXFP4++, W MXFP4+)
+    qw = oracle.quantize(w, oracle.MXFP4P)
+    ref2, S2 = oracle.gemm(qa, oracle.MXFP4PP, qw, oracle.MXFP4P)
+    D2 = mxp.gemm_prepacked(M, N, K, ia, mxp.prepack_e4m3(q_dev(qw), mxp.MXFP4P), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    check_gemm_e4m3(D2, ref2, S2, "mxfp4++ x mxfp4+ %dx%dx%d" % (M, N, K))
+    # operands without a delta span 12 bits: their E4M3 product meets the bound of the main path
+    qa1 = oracle.quantize(a, oracle.MXFP4P)
+    ref3, S3 = oracle.gemm(qa1, oracle.MXFP4P, qw, oracle.MXFP4P)
+    D3 = mxp.gemm_prepacked(M, N, K, mxp.prepack_e4m3(q_dev(qa1), mxp.MXFP4P), mxp.prepack_e4m3(q_dev(qw), mxp.MXFP4P),
+                            a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    check_gemm(D3, ref3, S3, "mxfp4+ in e4m3 images %dx%dx%d" % (M, N, K))
+
+
+def test_gemm_mxfp4pp_special_blocks():
+    """Flushed, NaN and extreme-scale blocks, every delta."""
+    x = mxpp_tensor(bf16=False)
+    a, b = x[:40], x[40:100]
+    qa, qb = oracle.quantize(a, oracle.MXFP4PP), oracle.quantize(b, oracle.MXFP4PP)
+    ref, S = oracle.gemm(qa, oracle.MXFP4PP, qb, oracle.MXFP4PP)
+    D = mxp.gemm_prepacked(a.shape[0], b.shape[0], a.shape[1], mxp.prepack_e4m3(q_dev(qa)), mxp.prepack_e4m3(q_dev(qb)),
+                           a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3).double().cpu().numpy()
+    nan = np.isnan(ref)
+    assert (np.isnan(D) == nan).all()
+    ok = ~nan & np.isfinite(ref) & (np.abs(ref) < 1e37) & (S < 1e37)
+    assert (np.abs(D - ref)[ok] <= 2.0 ** -12 * S[ok] + 1.2e-38).all()      # results below the fp32 normal range may flush
+
+
+def test_gemm_mxfp4pp_full_size_sampled():
+    M, N, K = 4096, 14336, 4096
+    a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
+    w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
+    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4PP), mxp.quantize(to_dev(w), mxp.MXFP4PP)
+    D = mxp.gemm_prepacked(M, N, K, mxp.prepack_e4m3(qa), mxp.prepack_e4m3(qw), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    rng = np.random.default_rng(4)
+    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
+    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
+    qa_h = tuple(t.cpu().numpy() for t in qa)
+    qw_h = tuple(t.cpu().numpy() for t in qw)
+    sel_a, inv_a = np.unique(rm, return_inverse=True)
+    sel_w, inv_w = np.unique(rn, return_inverse=True)
+    # the canonical bytes the GPU wrote are the oracle's (checked on the sampled rows), then the product on them
+    for g, o in zip(qa_h, oracle.quantize(a[sel_a], oracle.MXFP4PP)):
+        assert (g[sel_a] == o).all()
+    for g, o in zip(qw_h, oracle.quantize(w[sel_w], oracle.MXFP4PP)):
+        assert (g[sel_w] == o).all()
+    ref, S = oracle.gemm_sampled(tuple(x[sel_a] for x in qa_h), oracle.MXFP4PP, tuple(x[sel_w] for x in qw_h), oracle.MXFP4PP,
+                                 inv_a, inv_w)
+    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4
+    assert (np.abs(got - ref) <= 2.0 ** -12 * S).all()
