@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_image", "prepack", "gemm", "dequantize", "copy"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -114,6 +114,7 @@ def main():
     out_dt = torch.float32 if args.out_dtype == "f32" else torch.bfloat16
     # static weights: quantized once, outside the timed region
     qw = mxp.quantize(W, mxp.MXFP4P)
+    WT = W.t().contiguous() if args.only == "quantize_t" else None     # the weights as stored [K][N]
     del W
     # every buffer the step touches is allocated once
     qa = (torch.empty((M, K // 2), dtype=torch.uint8, device=dev), torch.empty((M, K // 32), dtype=torch.uint8, device=dev),
@@ -131,6 +132,8 @@ def main():
     def step_only():
         if args.only == "quantize":
             mxp.quantize_into(A, mxp.MXFP4P, *qa)
+        elif args.only == "quantize_t":
+            mxp.quantize_t(WT, mxp.MXFP4P)
         elif args.only == "quantize_image":
             mxp.quantize_image(A, mxp.MXFP4P, out=img_a, q_out=qa)
         elif args.only == "prepack":
