@@ -764,49 +764,72 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
 
 // ---- skinny-M kernel (decode: M <= 64) --------------------------------------------------------------------------
 // With a handful of activation rows the product is bound by reading the weight image once (Sec. 7.2: the decode stage
-// is memory-bound), so the aim is to have every byte of it requested at once.  A workgroup owns one 32-column tile
-// of B and splits K over its 8 wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
-// operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the one or two row tiles
-// of A likewise (A is tiny and stays in cache), runs the MFMAs, and the 8 partial tiles are summed through LDS.
-template <int TMR, bool OUT_BF16, int BT, int AT, int WAVES>
+// is memory-bound), so the aim is to have every byte of it requested at once.  A workgroup owns CT adjacent 32-column
+// tiles of B and splits K over its wavefronts; a wavefront loads its k-tiles of B straight from the image into MFMA
+// operand registers (a tile is 1536 contiguous bytes in lane order: no LDS staging needed), the row tiles of A
+// likewise (A is tiny and stays in cache), runs the MFMAs, and the partial tiles are summed through LDS.
+// Every workgroup re-reads all of A (padded to 32 rows per tile: as many bytes as one column tile of B), and the sum
+// of both load streams is what the kernel is limited by (8.5 TB/s combined, measured with E2M3 and with E2M1
+// weights); CT > 1 shares one A operand between CT column tiles, for shapes with enough column tiles to go round.
+template <int TMR, int CT, bool OUT_BF16, int BT, int AT, int WAVES>
 __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                                  const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                                  int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
-  constexpr int CHUNK = 4;                                  // k-tiles whose loads are in flight together per wavefront
+  // k-tiles whose loads are in flight together per wavefront: as many as the register file allows (128 registers per
+  // lane with 16 wavefronts, 256 with 8)
+  constexpr int CHUNK = CT == 4 ? 3 : (CT == 2 && WAVES == 16 ? 2 : 4);
+  static_assert(CT == 1 || CT == 2 || CT == 4, "column tiles of a workgroup share one scale dword");
   extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
-  float (*part)[TMR][16][64] = reinterpret_cast<float (*)[TMR][16][64]>(skinny_lds);   // [WAVES][TMR][16][64]
+  float (*part)[TMR * CT][16][64] = reinterpret_cast<float (*)[TMR * CT][16][64]>(skinny_lds);   // [WAVES][TMR * CT][16][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t ct = blockIdx.x;                            // column tile of B (32 columns)
+  const int64_t ct = (int64_t)blockIdx.x * CT;              // first column tile of B (32 columns each)
   constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
   const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
   const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
-  const int b_shift = (int)(ct & 3) * 8;
-  v16f acc[TMR];
+  const int b_shift = (int)(ct & 3) * 8;                    // byte j of the shifted dword = column tile ct + j
+  v16f acc[TMR][CT];
 #pragma unroll
   for (int i = 0; i < TMR; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  for (int k0 = wave * CHUNK; k0 < k_tiles; k0 += WAVES * CHUNK) {
-    v8i b[CHUNK], a[CHUNK][TMR];
+  // The runs of two workgroups lie a multiple of 4 KiB x k_tiles apart: walking them in step would have every workgroup
+  // on the same memory channels at the same time.  Each workgroup therefore starts its walk over the chunks of K at a
+  // different one (and wraps round).
+  const int n_chunks = (k_tiles + CHUNK - 1) / CHUNK;
+  const int first = (int)((blockIdx.x * 5u) % (uint32_t)n_chunks);
+  for (int ci = wave; ci < n_chunks; ci += WAVES) {
+    const int q = ci + first < n_chunks ? ci + first : ci + first - n_chunks;
+    const int k0 = q * CHUNK;
+    v8i b[CHUNK][CT], a[CHUNK][TMR];
     uint32_t sb[CHUNK], sa[CHUNK];
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       const int kt = k0 + c < k_tiles ? k0 + c : k_tiles - 1;     // clamped: the surplus is not used
-      const uint8_t* t = bt + (int64_t)kt * BT;
-      const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + lane * 16));
-      u32x2 hi = {0, 0};
-      if (BT == kTileBytes) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
-      b[c] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+#pragma unroll
+      for (int j = 0; j < CT; ++j) {
+        const uint8_t* t = bt + ((int64_t)j * k_tiles + kt) * BT;
+        const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + lane * 16));
+        u32x2 hi = {0, 0};
+        if (BT == kTileBytes) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
+        b[c][j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      }
       sb[c] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
       sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
 #pragma unroll
       for (int i = 0; i < TMR; ++i) {
+        // lanes of rows past M would fetch the image's zero padding: leaving them out saves that part of the A stream
+        // (with 8 rows, three quarters of it)
         const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
-        const u32x4 alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
+        u32x4 alo = {0, 0, 0, 0};
         u32x2 ahi = {0, 0};
-        if (AT == kTileBytes) ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        if (32 * i + (lane & 31) < M) {
+          alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
+          if (AT == kTileBytes) ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        }
         a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
       }
     }
@@ -814,30 +837,43 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
 #pragma unroll
-        for (int i = 0; i < TMR; ++i) {                       // row tile i: byte i of the lane's A scale dword
-          switch (i) {
-            case 0: acc[i] = mfma<0, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
-            case 1: acc[i] = mfma<1, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
-            case 2: acc[i] = mfma<2, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
-            default: acc[i] = mfma<3, 0, FB, FA>(a[c][i], b[c], acc[i], (int)sa[c], (int)sb[c]); break;
-          }
-        }
+        for (int i = 0; i < TMR; ++i)                         // row tile i: byte i of the lane's A scale dword
+#pragma unroll
+          for (int j = 0; j < CT; ++j)                        // column tile j: byte j of the shifted B scale dword
+            switch (i * 4 + j) {
+              case 0: acc[i][j] = mfma<0, 0, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 1: acc[i][j] = mfma<0, 1, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 2: acc[i][j] = mfma<0, 2, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 3: acc[i][j] = mfma<0, 3, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 4: acc[i][j] = mfma<1, 0, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 5: acc[i][j] = mfma<1, 1, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 6: acc[i][j] = mfma<1, 2, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 7: acc[i][j] = mfma<1, 3, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 8: acc[i][j] = mfma<2, 0, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 9: acc[i][j] = mfma<2, 1, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 12: acc[i][j] = mfma<3, 0, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+              default: acc[i][j] = mfma<3, 1, FB, FA>(a[c][i], b[c][j], acc[i][j], (int)sa[c], (int)sb[c]); break;
+            }
       }
     }
   }
 #pragma unroll
   for (int i = 0; i < TMR; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) part[wave][i][r][lane] = acc[i][r];
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[wave][i * CT + j][r][lane] = acc[i][j][r];
   __syncthreads();
-  // all lanes of the workgroup sum the TMR x 16 x 64 accumulator slots over the wavefronts; slot (i, r, l) is D[32 i + (l % 32)][32 ct + 8 (r / 4) + 4 (l / 32) + r % 4]
-  for (int e = tid; e < TMR * 16 * 64; e += 64 * WAVES) {
-    const int l = e & 63, r = (e >> 6) & 15, i = e >> 10;
+  // all lanes of the workgroup sum the accumulator slots over the wavefronts; slot (i, j, r, l) is
+  // D[32 i + (l % 32)][32 (ct + j) + 8 (r / 4) + 4 (l / 32) + r % 4]
+  for (int e = tid; e < TMR * CT * 16 * 64; e += 64 * WAVES) {
+    const int l = e & 63, r = (e >> 6) & 15, ij = e >> 10;
+    const int i = ij / CT, j = ij % CT;
     float v = 0.0f;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) v += part[w][i][r][l];
+    for (int w = 0; w < WAVES; ++w) v += part[w][ij][r][l];
     const int64_t row = 32 * i + (l & 31);
-    const int64_t col = 32 * ct + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    const int64_t col = 32 * (ct + j) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
     if (row < M && col < N) {
       if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne(v);
       else static_cast<float*>(Dv)[row * ldd + col] = v;
@@ -845,49 +881,50 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
   }
 }
 
-template <int TMR, bool OUT_BF16, int BT, int AT, int WAVES>
-void launch_skinny_cfg(dim3 grid, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be, const uint8_t* bs, int kt,
+template <int TMR, int CT, bool OUT_BF16, int BT, int AT, int WAVES>
+void launch_skinny_cfg(int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be, const uint8_t* bs, int kt,
                        int64_t M, int64_t N, void* D, int64_t ldd) {
-  constexpr int lds = WAVES * TMR * 16 * 64 * 4;
-  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, OUT_BF16, BT, AT, WAVES>),
+  constexpr int lds = WAVES * TMR * CT * 16 * 64 * 4;
+  static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
+  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, CT, OUT_BF16, BT, AT, WAVES>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
   (void)once;
-  hipLaunchKernelGGL((gemm_skinny_kernel<TMR, OUT_BF16, BT, AT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
+  const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
+  hipLaunchKernelGGL((gemm_skinny_kernel<TMR, CT, OUT_BF16, BT, AT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
 }
 
-// 16 wavefronts per column tile when K is long enough to give each at least one chunk of 4 k-tiles (K >= 4096): the
-// whole K range of a column tile is then requested at once; 8 otherwise.
+template <int TMR, int CT, int BT, int AT, int WAVES>
+void launch_skinny_out(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be, const uint8_t* bs,
+                       int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
+  if (bf) launch_skinny_cfg<TMR, CT, true, BT, AT, WAVES>(n_ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+  else launch_skinny_cfg<TMR, CT, false, BT, AT, WAVES>(n_ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+}
+
+// Wavefronts per workgroup: 16 when K is long enough to give each at least one chunk (K >= 4096) and the partial
+// tiles fit, so that the whole K range of a workgroup is requested at once.  Column tiles per workgroup: as many
+// (4, 2, 1) as still leave about one workgroup per compute unit.
 template <int BT, int AT>
 int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                   hipStream_t s) {
   const ImageGeom ga = image_geom(M, K, AT), gb = image_geom(N, K, BT);
   const int64_t ct = (N + 31) / 32;
   if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)ct);
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
+  constexpr int64_t kEnough = 200;                          // workgroups
   if (M > 64) {                                             // 65 .. 128 rows: four row tiles, 8 wavefronts (128 KiB of partial tiles)
-    if (bf) launch_skinny_cfg<4, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else launch_skinny_cfg<4, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    return launch_status();
-  }
-  if (M <= 32) {
-    if (wide) {
-      if (bf) launch_skinny_cfg<1, true, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<1, false, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    } else {
-      if (bf) launch_skinny_cfg<1, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<1, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    }
+    launch_skinny_out<4, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+  } else if (M <= 32) {
+    if (ct / 4 >= kEnough) launch_skinny_out<1, 4, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (ct / 2 >= kEnough && wide) launch_skinny_out<1, 2, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (ct / 2 >= kEnough) launch_skinny_out<1, 2, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (wide) launch_skinny_out<1, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else launch_skinny_out<1, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else {
-    if (wide) {
-      if (bf) launch_skinny_cfg<2, true, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<2, false, BT, AT, 16>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    } else {
-      if (bf) launch_skinny_cfg<2, true, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-      else launch_skinny_cfg<2, false, BT, AT, 8>(grid, s, ae, as, be, bs, kt, M, N, D, ldd);
-    }
+    if (ct / 2 >= kEnough) launch_skinny_out<2, 2, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (wide) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   }
   return launch_status();
 }

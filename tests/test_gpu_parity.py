@@ -776,3 +776,20 @@ def test_gemm_mxfp4pp_full_size_sampled():
     got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
     assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4
     assert (np.abs(got - ref) <= 2.0 ** -12 * S).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 12840, 256), (8, 25632, 320), (40, 12850, 192), (3, 26000, 4160), (33, 13000, 4096)])
+def test_gemm_few_rows_many_columns(M, N, K):
+    """Few activation rows and enough weight columns that a workgroup takes 2 or 4 column tiles (ragged last group)."""
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    qa, qb = oracle.quantize(a), oracle.quantize(w)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qb, oracle.MXFP4P)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P)
+    check_gemm(D, ref, S, "%dx%dx%d" % (M, N, K))
+    Db = mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P, out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+    # plain MXFP4 weights kept as an E2M1 image
+    qb4 = oracle.quantize(w, oracle.MXFP4)
+    ref4, S4 = oracle.gemm(qa, oracle.MXFP4P, qb4, oracle.MXFP4)
+    check_gemm(mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb4), mxp.MXFP4), ref4, S4, "w4 %dx%dx%d" % (M, N, K))
