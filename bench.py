@@ -264,6 +264,34 @@ def main():
         wbytes = Nd * Kd * 0.5625
         out["w4a16_mxfp4p_weights"] = {"us_per_call": us, "weight_GBps": wbytes / us / 1e3, "frac_hbm": wbytes / us / 1e3 / PEAK_HBM_GBPS}
         out["shape"] = "A bf16 [%d x %d] quantized on the fly (one kernel) + split-K GEMM with W [%d x %d]" % (Md, Kd, Nd, Kd)
+        del Wd, qwd
+        # the same 8 rows against a 70B-sized layer (28672 x 8192, random codes): the product kernel alone, where the
+        # weight image is large enough for the HBM rate to show
+        Nl, Kl = 28672, 8192
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        ql = (torch.randint(0, 256, (Nl, Kl // 2), dtype=torch.uint8, device=dev, generator=gen),
+              torch.randint(120, 134, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen),
+              torch.randint(0, 32, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen))
+        qal = tuple(t[:Md].contiguous() for t in ql)
+        img_al = mxp.prepack(qal, mxp.MXFP4P)
+        Dl = torch.empty((Md, Nl), dtype=torch.float32, device=dev)
+        for name, kind in (("mxfp4p_weights", mxp.IMAGE_E2M3), ("mxfp4_weights", mxp.IMAGE_E2M1)):
+            img = mxp.prepack(ql, mxp.MXFP4P) if kind == mxp.IMAGE_E2M3 else mxp.prepack_e2m1(ql)
+            for _ in range(20):
+                mxp.gemm_prepacked(Md, Nl, Kl, img_al, img, out=Dl, b_kind=kind)
+            torch.cuda.synchronize()
+            ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev2[0].record()
+            for _ in range(50):
+                mxp.gemm_prepacked(Md, Nl, Kl, img_al, img, out=Dl, b_kind=kind)
+            ev2[1].record()
+            torch.cuda.synchronize()
+            us = ev2[0].elapsed_time(ev2[1]) / 50 * 1e3
+            out["large_layer_" + name] = {"shape": "%d x %d x %d" % (Md, Nl, Kl), "us_per_call": us,
+                                          "weight_image_GBps": img.numel() / us / 1e3,
+                                          "frac_hbm": img.numel() / us / 1e3 / PEAK_HBM_GBPS}
+            del img
         return out
 
     decode = timed_decode()
