@@ -168,6 +168,18 @@ int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, 
                    const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* The decode stage (Sec. 7.2: few activation rows, bound by reading the weights): the same product for M <= 64 with
+ * the weights W[N][K] left in canonical MXFP4 or MXFP4+ storage (4.25 / 4.5 bits per element instead of the image's
+ * 4.25 / 6.25) and widened to MFMA operands inside the kernel.  A_image is an E2M3 image of the activations
+ * (mxp_prepack or mxp_quantize_image); mxp_gemm_decode_bf16a takes them un-quantized like mxp_gemm_bf16a, with the same
+ * workspace.  K % 256 == 0; larger M, other K and MXFP4++ weights return MXP_ERR_UNSUPPORTED (use the image path).
+ * Results are those of mxp_gemm_prepacked on the same operands (same products, K split and summed the same way). */
+int mxp_gemm_decode(int64_t M, int64_t N, int64_t K, const void* A_image, const uint8_t* W_elems, const uint8_t* W_scales,
+                    const uint8_t* W_idx, int fmtW, void* D, int d_dtype, int64_t ldd, void* stream);
+int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
+                          const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, void* D,
+                          int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Conversion-based product (Sec. 5: where the 4-bit type is not multiplied directly, or only the weights are
  * quantized, blocks are de-converted to a wider type inside the kernel): D[M][N] = A[M][K] x deq(W)^T with A left as
  * it is (MXP_BF16, row stride lda; MXP_F32 returns MXP_ERR_UNSUPPORTED) and W[N][K] in canonical MXFP4, MXFP4+ or

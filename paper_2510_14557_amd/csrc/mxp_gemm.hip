@@ -929,6 +929,214 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   return launch_status();
 }
 
+// ---- skinny-M kernel on canonical weights -----------------------------------------------------------------------
+// The decode stage is bound by the weight bytes (Sec. 7.2), and an MXFP4+ weight is 4.5 bits per element in canonical
+// storage but 6.25 in the E2M3 image.  This kernel reads the canonical arrays and widens in registers: per chunk of 4
+// k-tiles a wavefront loads, for each of its column tiles, 32 rows x 128 contiguous bytes (8 blocks per row: full
+// lines), passes them through a private LDS patch into operand order (lane l gets the block of row l % 32, half
+// l / 32), widens the 32 nibbles to E2M3 codes with the BM as sign | 11 | mmm (Sec. 4.2) and feeds the MFMA; scale and
+// index bytes come as one 8-byte load per row.  Plain MXFP4 weights are fed as they are (E2M1 operand).  Everything
+// else -- A from its image, K split over the wavefronts, rotated walk, reduction through LDS -- as above.
+__device__ __forceinline__ uint32_t widen4_codes(uint32_t h) {   // 4 nibbles -> 4 six-bit codes, code = nibble << 2
+  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
+  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
+}
+
+// One block of 32 nibbles -> its 24-byte E2M3 operand; bm = BM position or >= 32 for none.
+__device__ __forceinline__ v8i widen_block(const u32x4 n, uint32_t bm) {
+  const uint32_t w[4] = {n.x, n.y, n.z, n.w};
+  uint32_t r[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    r[2 * j] = widen4_codes(w[j] & 0xFFFFu);
+    r[2 * j + 1] = widen4_codes(w[j] >> 16);
+  }
+  if (bm < 32u) {
+    const uint32_t piece = bm >> 2, sh = (bm & 3u) * 6u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t c = (r[j] >> sh) & 0x3Fu;                 // s mmm 00
+      const uint32_t code = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);
+      const uint32_t patched = (r[j] & ~(0x3Fu << sh)) | (code << sh);
+      r[j] = piece == (uint32_t)j ? patched : r[j];
+    }
+  }
+  return (v8i){(int)(r[0] | (r[1] << 24)), (int)((r[1] >> 8) | (r[2] << 16)), (int)((r[2] >> 16) | (r[3] << 8)),
+               (int)(r[4] | (r[5] << 24)), (int)((r[5] >> 8) | (r[6] << 16)), (int)((r[6] >> 16) | (r[7] << 8)), 0, 0};
+}
+
+constexpr int kCanonPatchStride = 144;                        // bytes per patch row: 128 + 16 against bank conflicts
+constexpr int kCanonPatchBytes = 32 * kCanonPatchStride;
+
+template <int TMR, int CT, bool OUT_BF16, bool PLUS, int AT, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) gemm_skinny_canon_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                                       const u32x4* __restrict__ w_el, const uint8_t* __restrict__ w_sc,
+                                                                       const uint8_t* __restrict__ w_ix, int64_t nbk, int k_tiles,
+                                                                       int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  constexpr int CHUNK = 4;                                    // k-tiles per chunk = 8 blocks = 128 bytes of a weight row
+  extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
+  float (*part)[TMR * CT][16][64] = reinterpret_cast<float (*)[TMR * CT][16][64]>(skinny_lds);   // after the K loop
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint8_t* patch = skinny_lds + wave * kCanonPatchBytes;      // during the K loop
+  const int64_t ct = (int64_t)blockIdx.x * CT;
+  constexpr int FB = PLUS ? kFmtE2M3 : kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  const int n_in = lane & 31, h = lane >> 5;                  // operand role of this lane: row of the tile, half of the k-tile
+  const int ld_row = lane >> 3, ld_piece = lane & 7;          // load role: row (+ 8 r) and 16-byte piece of the 128-byte run
+  v16f acc[TMR][CT];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int n_chunks = (k_tiles + CHUNK - 1) / CHUNK;
+  const int first = (int)((blockIdx.x * 5u) % (uint32_t)n_chunks);
+  for (int ci = wave; ci < n_chunks; ci += WAVES) {
+    const int q = ci + first < n_chunks ? ci + first : ci + first - n_chunks;
+    const int64_t kb0 = (int64_t)q * 8;                       // first block of the chunk
+    u32x4 raw[CT][4];
+    u32x2 s8[CT], i8[CT];
+#pragma unroll
+    for (int j = 0; j < CT; ++j) {
+      const int64_t row0 = 32 * (ct + j);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t row = row0 + 8 * r + ld_row;
+        raw[j][r] = (u32x4){0, 0, 0, 0};
+        if (row < N && kb0 + ld_piece < nbk) raw[j][r] = __builtin_nontemporal_load(w_el + row * nbk + kb0 + ld_piece);
+      }
+      const int64_t orow = row0 + n_in;
+      s8[j] = (u32x2){0, 0};
+      i8[j] = (u32x2){0, 0};
+      if (orow < N) {                                         // nbk % 8 == 0: the 8 bytes exist and are aligned
+        s8[j] = *reinterpret_cast<const u32x2*>(w_sc + orow * nbk + kb0);
+        if (PLUS) i8[j] = *reinterpret_cast<const u32x2*>(w_ix + orow * nbk + kb0);
+      }
+    }
+    v8i a[CHUNK][TMR];
+    uint32_t sa[CHUNK];
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      const int kt = q * CHUNK + c < k_tiles ? q * CHUNK + c : k_tiles - 1;
+      sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
+#pragma unroll
+      for (int i = 0; i < TMR; ++i) {
+        const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
+        u32x4 alo = {0, 0, 0, 0};
+        u32x2 ahi = {0, 0};
+        if (32 * i + (lane & 31) < M) {
+          alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
+          if (AT == kTileBytes) ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        }
+        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < CT; ++j) {
+      // memory order -> operand order through the wavefront's patch (LDS operations of one wavefront run in order)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        *reinterpret_cast<u32x4*>(patch + (8 * r + ld_row) * kCanonPatchStride + ld_piece * 16) = raw[j][r];
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c) {
+        const u32x4 nib = *reinterpret_cast<const u32x4*>(patch + n_in * kCanonPatchStride + (2 * c + h) * 16);
+        const uint32_t byte_sh = (uint32_t)((2 * c + h) & 3) * 8u;
+        uint32_t sbyte = ((2 * c + h) < 4 ? s8[j].x : s8[j].y) >> byte_sh & 0xFFu;
+        uint32_t bm = 64u;
+        if (PLUS) bm = (((2 * c + h) < 4 ? i8[j].x : i8[j].y) >> byte_sh) & 31u;
+        v8i b;
+        if (PLUS) b = widen_block(nib, (sbyte == 0u || sbyte == 255u) ? 64u : bm);
+        else b = (v8i){(int)nib.x, (int)nib.y, (int)nib.z, (int)nib.w, 0, 0, 0, 0};
+        if (sbyte == 0u) {                                    // flushed (or absent) block: zeros, whatever the nibbles say
+          b = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
+          sbyte = 127u;
+        }
+        if (q * CHUNK + c < k_tiles) {
+#pragma unroll
+          for (int i = 0; i < TMR; ++i)
+            switch (i) {
+              case 0: acc[i][j] = mfma<0, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
+              case 1: acc[i][j] = mfma<1, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
+              case 2: acc[i][j] = mfma<2, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
+              default: acc[i][j] = mfma<3, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
+            }
+        }
+      }
+    }
+  }
+  __syncthreads();                                            // the patches make room for the partial tiles
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[wave][i * CT + j][r][lane] = acc[i][j][r];
+  __syncthreads();
+  for (int e = tid; e < TMR * CT * 16 * 64; e += 64 * WAVES) {
+    const int l = e & 63, r = (e >> 6) & 15, ij = e >> 10;
+    const int i = ij / CT, j = ij % CT;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += part[w][ij][r][l];
+    const int64_t row = 32 * i + (l & 31);
+    const int64_t col = 32 * (ct + j) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    if (row < M && col < N) {
+      if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne(v);
+      else static_cast<float*>(Dv)[row * ldd + col] = v;
+    }
+  }
+}
+
+template <int TMR, int CT, bool PLUS, int WAVES>
+void launch_canon_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* we, const uint8_t* ws,
+                      const uint8_t* wi, int64_t nbk, int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
+  constexpr int part_bytes = WAVES * TMR * CT * 16 * 64 * 4, patch_bytes = WAVES * kCanonPatchBytes;
+  constexpr int lds = part_bytes > patch_bytes ? part_bytes : patch_bytes;
+  static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
+  const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
+  const u32x4* we4 = reinterpret_cast<const u32x4*>(we);
+  if (bf) {
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_canon_kernel<TMR, CT, true, PLUS, kTileBytes, WAVES>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once_b;
+    hipLaunchKernelGGL((gemm_skinny_canon_kernel<TMR, CT, true, PLUS, kTileBytes, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, we4, ws, wi,
+                       nbk, kt, M, N, D, ldd);
+  } else {
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_canon_kernel<TMR, CT, false, PLUS, kTileBytes, WAVES>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once_f;
+    hipLaunchKernelGGL((gemm_skinny_canon_kernel<TMR, CT, false, PLUS, kTileBytes, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, we4, ws, wi,
+                       nbk, kt, M, N, D, ldd);
+  }
+}
+
+// A: E2M3 image of M <= 64 rows; W: canonical MXFP4 (PLUS = false) or MXFP4+ arrays, K % 256 == 0.
+template <bool PLUS>
+int launch_canon(const uint8_t* Ai, const uint8_t* we, const uint8_t* ws, const uint8_t* wi, int64_t M, int64_t N, int64_t K, void* D,
+                 int d_dtype, int64_t ldd, hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K);
+  const int64_t ct = (N + 31) / 32, nbk = K / kBlock;
+  if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const int kt = (int)ga.k_tiles;
+  const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes;
+  const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
+  constexpr int64_t kEnough = 200;
+  if (M <= 32) {
+    if (ct / 4 >= kEnough) launch_canon_cfg<1, 4, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else if (ct / 2 >= kEnough && wide) launch_canon_cfg<1, 2, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else if (ct / 2 >= kEnough) launch_canon_cfg<1, 2, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else if (wide) launch_canon_cfg<1, 1, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else launch_canon_cfg<1, 1, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+  } else {
+    if (ct / 2 >= kEnough) launch_canon_cfg<2, 2, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else if (wide) launch_canon_cfg<2, 1, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else launch_canon_cfg<2, 1, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+  }
+  return launch_status();
+}
+
 #ifndef MXP_RING
 #define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
 #endif
@@ -1059,6 +1267,49 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
   if (rc != MXP_OK) return rc;
   return gemm_images(img, MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
+}
+
+// Few activation rows against weights in canonical storage (the decode stage, Sec. 7.2).
+extern "C" int mxp_gemm_decode(int64_t M, int64_t N, int64_t K, const void* A_image, const uint8_t* W_elems,
+                               const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, void* D, int d_dtype, int64_t ldd,
+                               void* stream) {
+  using namespace mxp;
+  if (fmtW == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
+  if (fmtW != MXP_FMT_MXFP4 && fmtW != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc != MXP_OK || M == 0 || N == 0) return rc;
+  if (M > 64 || K % 256 != 0) return MXP_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
+  if (!A_image || !W_elems || !W_scales || (fmtW == MXP_FMT_MXFP4P && !W_idx)) return MXP_ERR_NULL;
+  if (!aligned16(A_image) || !aligned16(W_elems) || !aligned16(W_scales) || (W_idx && !aligned16(W_idx))) return MXP_ERR_ALIGN;
+  const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
+  if (fmtW == MXP_FMT_MXFP4P) return launch_canon<true>(Ai, W_elems, W_scales, W_idx, M, N, K, D, d_dtype, ldd, s);
+  return launch_canon<false>(Ai, W_elems, W_scales, W_idx, M, N, K, D, d_dtype, ldd, s);
+}
+
+extern "C" int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
+                                     const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, void* D,
+                                     int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace mxp;
+  if (fmtA == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
+  if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (fmtW == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
+  if (fmtW != MXP_FMT_MXFP4 && fmtW != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc != MXP_OK || M == 0 || N == 0) return rc;
+  if (M > 64 || K % 256 != 0) return MXP_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
+  if (!A || !workspace) return MXP_ERR_NULL;
+  if (lda < K) return MXP_ERR_SHAPE;
+  if (!aligned16(A) || !aligned16(workspace) || (lda * (a_dtype == MXP_BF16 ? 2 : 4)) % 16 != 0) return MXP_ERR_ALIGN;
+  if (workspace_bytes < mxp_gemm_bf16a_workspace_bytes(M, K)) return MXP_ERR_WORKSPACE;
+  uint8_t* img = static_cast<uint8_t*>(workspace);
+  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
+  if (rc != MXP_OK) return rc;
+  return mxp_gemm_decode(M, N, K, img, W_elems, W_scales, W_idx, fmtW, D, d_dtype, ldd, stream);
 }
 
 // ---- measurement aid: the matrix pipes alone ------------------------------------------------------------------

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -54,6 +54,8 @@ def lib():
     L.mxp_gemm_workspace_bytes.restype = sz
     L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, i32, vp, i32, vp, i32, i64, vp]
+    L.mxp_gemm_decode.argtypes = [i64, i64, i64, vp, vp, vp, vp, i32, vp, i32, i64, vp]
+    L.mxp_gemm_decode_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_image_bytes_e2m1.argtypes = [i64, i64]
     L.mxp_image_bytes_e2m1.restype = sz
     L.mxp_prepack_e2m1.argtypes = [vp, vp, i64, i64, vp, sz, vp]
@@ -71,7 +73,7 @@ def lib():
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
     for n in ("mxp_quantize", "mxp_quantize_t", "mxp_dequantize", "mxp_prepack", "mxp_quantize_image", "mxp_prepack_e2m1", "mxp_prepack_e4m3", "mxp_gemm", "mxp_gemm_prepacked",
-              "mxp_gemm_bf16a"):
+              "mxp_gemm_bf16a", "mxp_gemm_decode", "mxp_gemm_decode_bf16a"):
         getattr(L, n).restype = i32
     _lib = L
     return L
@@ -264,6 +266,35 @@ def gemm_prepacked(M, N, K, a_image, b_image, out_dtype: torch.dtype = torch.flo
     ldd = out.stride(0) if M > 1 else max(N, 1)
     _check(lib().mxp_gemm_prepacked(M, N, K, _p(a_image), a_kind, _p(b_image), b_kind, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_prepacked")
+    return out
+
+
+def gemm_decode(M, N, K, a_image, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
+    """Few rows (M <= 64) of prepacked activations x canonical weights, widened inside the kernel."""
+    we, ws, wi = qw
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a_image.device)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_decode(M, N, K, _p(a_image), _p(we), _p(ws), _p(wi), fmt_w, _p(out), _dt(out), ldd, _stream()),
+           "mxp_gemm_decode")
+    return out
+
+
+def gemm_decode_bf16a(a: torch.Tensor, fmt_a: int, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype = torch.float32,
+                      out: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    """Un-quantized activations (M <= 64 rows), quantized on the fly, x canonical weights."""
+    _dev2d(a)
+    we, ws, wi = qw
+    M, K = a.shape
+    N = we.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=a.device)
+    if workspace is None:
+        workspace = torch.empty(max(gemm_bf16a_workspace_bytes(M, K), 16), dtype=torch.uint8, device=a.device)
+    lda = a.stride(0) if M > 1 else max(K, 1)
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_decode_bf16a(M, N, K, _p(a), _dt(a), lda, fmt_a, _p(we), _p(ws), _p(wi), fmt_w, _p(out), _dt(out), ldd,
+                                       _p(workspace), workspace.numel(), _stream()), "mxp_gemm_decode_bf16a")
     return out
 
 

@@ -793,3 +793,41 @@ def test_gemm_few_rows_many_columns(M, N, K):
     qb4 = oracle.quantize(w, oracle.MXFP4)
     ref4, S4 = oracle.gemm(qa, oracle.MXFP4P, qb4, oracle.MXFP4)
     check_gemm(mxp.gemm(q_dev(qa), mxp.MXFP4P, q_dev(qb4), mxp.MXFP4), ref4, S4, "w4 %dx%dx%d" % (M, N, K))
+
+
+# ---- the decode product on canonical weights ------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (1, 33, 256), (33, 100, 512), (64, 1000, 4352), (8, 12840, 256),
+                                   (8, 25632, 512), (40, 12850, 256), (3, 26000, 4352), (17, 300, 1024)])
+@pytest.mark.parametrize("fw", ["mxfp4p", "mxfp4"])
+def test_gemm_decode_on_canonical_weights(M, N, K, fw):
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    if N >= 100:
+        w[7, 32:64] = 0                                                  # flushed weight blocks: zeros, and values
+        w[9, 64:96] = 0x0100                                             # whose exponent field is below the flush limit
+    qa, qw = oracle.quantize(a, oracle.MXFP4P), oracle.quantize(w, FMT[fw][1])
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qw, FMT[fw][1])
+    img_a = mxp.prepack(q_dev(qa), mxp.MXFP4P)
+    D = mxp.gemm_decode(M, N, K, img_a, q_dev(qw), FMT[fw][0])
+    check_gemm(D, ref, S, "decode %s %dx%dx%d" % (fw, M, N, K))
+    # the image route forms the same products and sums them in the same order
+    img_w = mxp.prepack(q_dev(qw), FMT[fw][0]) if fw == "mxfp4p" else mxp.prepack_e2m1(q_dev(qw))
+    D2 = mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M3 if fw == "mxfp4p" else mxp.IMAGE_E2M1)
+    assert torch.equal(D, D2)
+    # un-quantized activations, bf16 output
+    D3 = mxp.gemm_decode_bf16a(to_dev(a), mxp.MXFP4P, q_dev(qw), FMT[fw][0])
+    assert torch.equal(D, D3)
+    Db = mxp.gemm_decode(M, N, K, img_a, q_dev(qw), FMT[fw][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+def test_gemm_decode_rejects_what_it_does_not_cover():
+    q = tuple(torch.zeros(s, dtype=torch.uint8, device="cuda") for s in ((128, 160), (128, 10), (128, 10)))
+    img = torch.zeros(mxp.image_bytes(65, 320), dtype=torch.uint8, device="cuda")
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm_decode(8, 128, 320, img, q)                             # K % 256 != 0
+    q = tuple(torch.zeros(s, dtype=torch.uint8, device="cuda") for s in ((128, 128), (128, 8), (128, 8)))
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm_decode(65, 128, 256, img, q)                            # more than 64 rows
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm_decode(8, 128, 256, img, q, mxp.MXFP4PP)
