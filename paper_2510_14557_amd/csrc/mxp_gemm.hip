@@ -101,11 +101,15 @@ __device__ __forceinline__ void mma_all(v16f (&acc)[C::WM][C::WN], const v8i (&a
 // Epilogue.  Lane l holds row m = l % 32 of the tile; register quad g holds columns 8g + 4(l / 32) .. +3.  With an
 // aligned D each quad is one 16-byte (fp32) or 8-byte (bf16) store: 64 stores per wavefront tile instead of 256, which
 // keeps the whole epilogue inside one window of the 6-bit vmcnt counter.
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) {
-  uint32_t u = __float_as_uint(v);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;       // keep NaN a NaN
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;                          // round to nearest even
+// fp32 -> bf16, round to nearest even, NaN stays NaN: the CDNA4 pack-convert instruction (one per two values).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  union { bf16x2 v; uint32_t u; } c;
+  c.v = __builtin_convertvector((f32x2){lo, hi}, bf16x2);
+  return c.u;
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) { return pack_bf16x2(v, 0.0f) & 0xFFFFu; }
 
 template <int TWM, int TWN, bool OUT_BF16>
 __device__ __forceinline__ void store_tile(const v16f (&acc)[TWM][TWN], int64_t tile_m, int64_t tile_n, int lane, int64_t M,
@@ -123,7 +127,7 @@ __device__ __forceinline__ void store_tile(const v16f (&acc)[TWM][TWN], int64_t 
         const float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1], v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
         if (vec_ok && col + 3 < N) {
           if (OUT_BF16) {
-            u32x2 o = {f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16), f32_to_bf16_rne(v2) | (f32_to_bf16_rne(v3) << 16)};
+            u32x2 o = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
             *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col) = o;
           } else {
             typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -161,6 +165,41 @@ __device__ __forceinline__ void store_tile_lds(const v16f (&acc)[TWM][TWN], int6
   const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
   const int wr = (lane & 31) * kPatchStride + 16 * (lane >> 5);   // + 32 g
   const int rd = (lane >> 3) * kPatchStride + (lane & 7) * 16;    // + 8 k rows
+  if (OUT_BF16 && vec_ok && TWN % 2 == 0) {
+    // bf16: a row of one tile is only 64 bytes.  Two neighbouring tiles go through the two patches together and 16
+    // consecutive lanes then hold the 128 contiguous bytes of one row (64 columns), so every store writes whole lines.
+    const int rd2 = (lane >> 4) * kPatchStride + (lane & 7) * 16;  // + 4 k rows; patch (lane & 15) >> 3
+    const uint8_t* pr = patch + ((lane & 15) >> 3) * kPatchBytes;
+#pragma unroll
+    for (int i = 0; i < TWM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TWN; j += 2) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            f32x4 q = {acc[i][j + t][4 * g], acc[i][j + t][4 * g + 1], acc[i][j + t][4 * g + 2], acc[i][j + t][4 * g + 3]};
+            *reinterpret_cast<f32x4*>(patch + t * kPatchBytes + wr + 32 * g) = q;
+          }
+        const int64_t col = (tile_n + j) * 32 + 4 * (lane & 15);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(pr + rd2 + 4 * k * kPatchStride);
+          const int64_t row = (tile_m + i) * 32 + 4 * k + (lane >> 4);
+          if (row >= M || col >= N) continue;
+          if (col + 3 < N) {
+            u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col));
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (col + q < N) static_cast<uint16_t*>(Dv)[row * ldd + col + q] = (uint16_t)f32_to_bf16_rne(v[q]);
+          }
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TWM; ++i) {
 #pragma unroll
@@ -179,7 +218,7 @@ __device__ __forceinline__ void store_tile_lds(const v16f (&acc)[TWM][TWN], int6
         if (row >= M || col >= N) continue;
         if (vec_ok && col + 3 < N) {
           if (OUT_BF16) {
-            u32x2 o = {f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16), f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16)};
+            u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
             __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col));
           } else {
             __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col));
