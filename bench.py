@@ -201,19 +201,25 @@ def main():
     # The paper's main deployment (Sec. 7.1): MXFP4+ activations x plain MXFP4 weights.  The weights stay in 4-bit codes on
     # the B side (E2M1 image).  All products timed the same way: 250 warm-up launches, then 100 back to back, one event pair.
     # The third product is plain MXFP4 x MXFP4 (both images 4-bit): the baseline the paper normalises MX+ to.
-    def timed_gemm(a_image, a_kind, b_image, b_kind, n=100):
+    def timed_gemm(a_image, a_kind, b_image, b_kind, n=100, out=None):
+        out = D if out is None else out
         for _ in range(250):                                  # the clocks need tens of ms to settle on a new load
-            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=D, a_kind=a_kind, b_kind=b_kind)
+            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
         torch.cuda.synchronize()
         ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         ev2[0].record()
         for _ in range(n):
-            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=D, a_kind=a_kind, b_kind=b_kind)
+            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
         ev2[1].record()
         torch.cuda.synchronize()
         return ev2[0].elapsed_time(ev2[1]) / n
 
     gemm_pp_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, mxp.IMAGE_E2M3)
+    # the same product with the other output type (bf16 = the fp32 result rounded once, half the output bytes)
+    other_dt = torch.bfloat16 if out_dt == torch.float32 else torch.float32
+    D_other = torch.empty((M, N), dtype=other_dt, device=dev)
+    gemm_pp_other_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, mxp.IMAGE_E2M3, out=D_other)
+    del D_other
     W4 = to_dev(w_bits)
     img_w4 = mxp.prepack_e2m1(mxp.quantize(W4, mxp.MXFP4))
     del W4
@@ -392,6 +398,7 @@ def main():
         "decode": decode,
         "gemm_only_TFLOPs": gemm_tflops,
         "gemm_back_to_back_TFLOPs": flops / (gemm_pp_ms * 1e-3) / 1e12,
+        "gemm_back_to_back_%s_out_TFLOPs" % ("bf16" if out_dt == torch.float32 else "f32"): flops / (gemm_pp_other_ms * 1e-3) / 1e12,
         "gemm_a_mxfp4p_w_mxfp4_back_to_back_TFLOPs": flops / (gemm_w4_ms * 1e-3) / 1e12,
         "gemm_plain_mxfp4_back_to_back_TFLOPs": flops / (gemm_a4w4_ms * 1e-3) / 1e12,
         "gemm_time_vs_plain_mxfp4": {"mxfp4p_x_mxfp4p": gemm_pp_ms / gemm_a4w4_ms, "mxfp4p_x_mxfp4": gemm_w4_ms / gemm_a4w4_ms,
