@@ -8,7 +8,8 @@
 //
 // Storage: eight-bit codes one per byte; six-bit codes as a little-endian bit string, element i of a block in bits
 // [6i, 6i+6) of its 24 bytes.  Four lanes share a block, a lane holds 8 consecutive elements (48 or 64 code bits).
-// All rounding is done on integer fields of the fp32 pattern, so nothing depends on the float mode.
+// Rounding is done on integer fields of the fp32 pattern (nothing depends on the float mode), except the E4M3
+// elements, which the hardware pack-convert produces.
 #include "mxp_common.h"
 
 namespace {
@@ -17,6 +18,11 @@ using namespace mxp;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+#ifndef MXP_WIDE_HW_FP8
+#define MXP_WIDE_HW_FP8 1
+#endif
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
@@ -113,10 +119,12 @@ __global__ void __launch_bounds__(256) quantize_wide_kernel(const void* __restri
     const int64_t g = q >> 2;                       // block
     const int64_t row = g / nbk;
     const int64_t off = row * ld + (g - row * nbk) * 32 + part * 8;
-    uint32_t a[8], sg[8];
+    uint32_t a[8], sg[8], raw[8];
     if (BF16) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
+      raw[4] = raw[5] = raw[6] = raw[7] = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         a[2 * j] = (w[j] << 16) & 0x7FFF0000u;
@@ -130,6 +138,7 @@ __global__ void __launch_bounds__(256) quantize_wide_kernel(const void* __restri
       const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
+        raw[i] = w[i];
         a[i] = w[i] & 0x7FFFFFFFu;
         sg[i] = w[i] >> 31;
       }
@@ -148,13 +157,52 @@ __global__ void __launch_bounds__(256) quantize_wide_kernel(const void* __restri
     const bool flush = E <= (uint32_t)F::EMAX, nonfinite = E == 255u;
     const int sbyte = (int)E - F::EMAX;             // Eq. 1
     uint32_t lo = 0, hi = 0;                        // this lane's code bits: 48 (lo, hi[15:0]) or 64
+    if (BITS == 8 && MXP_WIDE_HW_FP8) {
+      // E4M3 elements: the CDNA4 pack-convert (x / X, round to nearest even, sign kept), two per instruction; the BM
+      // byte of a + format is replaced afterwards
+      const float X = __uint_as_float((uint32_t)(sbyte > 0 ? sbyte : 1) << 23);
+      v2s plo = {0, 0}, phi = {0, 0};
+      if (BF16) {
+        union { uint32_t u; v2bf v; } c0, c1, c2, c3;
+        c0.u = raw[0]; c1.u = raw[1]; c2.u = raw[2]; c3.u = raw[3];
+        plo = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(plo, c0.v, X, false);
+        plo = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(plo, c1.v, X, true);
+        phi = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(phi, c2.v, X, false);
+        phi = __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(phi, c3.v, X, true);
+      } else {
+        plo = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(plo, __uint_as_float(raw[0]), __uint_as_float(raw[1]), X, false);
+        plo = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(plo, __uint_as_float(raw[2]), __uint_as_float(raw[3]), X, true);
+        phi = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(phi, __uint_as_float(raw[4]), __uint_as_float(raw[5]), X, false);
+        phi = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(phi, __uint_as_float(raw[6]), __uint_as_float(raw[7]), X, true);
+      }
+      union { v2s v; uint32_t u; } ul, uh;
+      ul.v = plo;
+      uh.v = phi;
+      // the instruction answers magnitudes that round above 448 with the NaN code S.1111.111; the format saturates:
+      // clear bit 0 of every byte whose low seven bits are all ones
+      lo = ul.u & ~((((ul.u & 0x7F7F7F7Fu) + 0x01010101u) & 0x80808080u) >> 7);
+      hi = uh.u & ~((((uh.u & 0x7F7F7F7Fu) + 0x01010101u) & 0x80808080u) >> 7);
+      if (PLUS && (pos >> 3) == part) {
+        const uint32_t i = pos & 7u, sh = (i & 3u) * 8u;
+        uint32_t ai = 0, si = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      uint32_t c = (PLUS && pos == part * 8u + (uint32_t)i) ? bm_code<BITS>(a[i]) : elem_code<BITS>(a[i], sbyte);
-      c |= sg[i] << (BITS - 1);
-      const int b = i * BITS;                       // bit position inside the lane's string
-      if (b < 32) lo |= c << b;
-      if (b + BITS > 32) hi |= (b >= 32) ? (c << (b - 32)) : (c >> (32 - b));
+        for (int k = 0; k < 8; ++k) {
+          ai = i == (uint32_t)k ? a[k] : ai;
+          si = i == (uint32_t)k ? sg[k] : si;
+        }
+        const uint32_t code = bm_code<8>(ai) | (si << 7);
+        if (i < 4u) lo = (lo & ~(0xFFu << sh)) | (code << sh);
+        else hi = (hi & ~(0xFFu << sh)) | (code << sh);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint32_t c = (PLUS && pos == part * 8u + (uint32_t)i) ? bm_code<BITS>(a[i]) : elem_code<BITS>(a[i], sbyte);
+        c |= sg[i] << (BITS - 1);
+        const int b = i * BITS;                     // bit position inside the lane's string
+        if (b < 32) lo |= c << b;
+        if (b + BITS > 32) hi |= (b >= 32) ? (c << (b - 32)) : (c >> (32 - b));
+      }
     }
     uint32_t sb = (uint32_t)sbyte, idx = pos;
     if (flush || nonfinite) {
