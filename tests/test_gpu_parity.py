@@ -831,3 +831,27 @@ def test_gemm_decode_rejects_what_it_does_not_cover():
         mxp.gemm_decode(65, 128, 256, img, q)                            # more than 64 rows
     with pytest.raises(mxp.MxpError):
         mxp.gemm_decode(8, 128, 256, img, q, mxp.MXFP4PP)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,N,K,pad", [(300, 520, 1024, 24), (300, 520, 1024, 3), (260, 250, 512, 6), (513, 1030, 640, 1)])
+def test_gemm_tiled_kernel_strided_and_unaligned_output(M, N, K, pad, dt):
+    """The large-M kernel's epilogue: row stride larger than N, strides that allow vector stores and strides that do
+    not, ragged last tiles, both output types (bf16 stores pair two tiles)."""
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = q_dev(oracle.quantize(a)), q_dev(oracle.quantize(w))
+    dense = mxp.gemm(qa, mxp.MXFP4P, qb, mxp.MXFP4P, out_dtype=dt)
+    ref, S = oracle.gemm(tuple(t.cpu().numpy() for t in qa), oracle.MXFP4P, tuple(t.cpu().numpy() for t in qb), oracle.MXFP4P)
+    if dt == torch.float32:
+        check_gemm(dense, ref, S, "dense %dx%dx%d" % (M, N, K))
+    else:
+        assert torch.equal(dense, mxp.gemm(qa, mxp.MXFP4P, qb, mxp.MXFP4P).to(torch.bfloat16))
+    out = torch.full((M, N + pad), -7.0, dtype=dt, device="cuda")
+    mxp.gemm(qa, mxp.MXFP4P, qb, mxp.MXFP4P, out=out[:, :N])
+    assert torch.equal(out[:, :N], dense) and (out[:, N:] == -7.0).all()
+    # an output that starts off the 16-byte grid
+    flat = torch.full((M * (N + pad) + 8,), -7.0, dtype=dt, device="cuda")
+    view = flat[1:1 + M * (N + pad)].view(M, N + pad)
+    mxp.gemm(qa, mxp.MXFP4P, qb, mxp.MXFP4P, out=view[:, :N])
+    assert torch.equal(view[:, :N], dense) and (view[:, N:] == -7.0).all() and flat[0] == -7.0
