@@ -390,9 +390,13 @@ __device__ __forceinline__ void wait_dma_and_barrier() {
 template <class C, int S, int WN>
 struct Copier {
   static constexpr bool B6 = C::BT == kTileBytes, A6 = C::AT == kTileBytes;
-  // copies per wavefront and stage: the rounds of A (E2M3: 3, E2M1: 2), of B (E2M3: 3 or 2, E2M1: 2 or 1), one of scales
-  static constexpr int PER_STAGE = (A6 ? 3 : 2) + (B6 ? (WN == 4 ? 3 : 2) : (WN == 4 ? 2 : 1)) + 1;
-  uint32_t offE[3], offB[3], offH, offS;
+  static constexpr bool B8 = C::BT == kTileBytesE4M3, A8 = C::AT == kTileBytesE4M3;
+  // copies per wavefront and stage: the 4 KiB rounds of A (E2M1: 2, E2M3: 3, E4M3: 4), of B (full tile: the same; half
+  // tile: 1, 2 -- one and a half, the half one issued by every wavefront --, 2), one of scales
+  static constexpr int A_ROUNDS = A8 ? 4 : (A6 ? 3 : 2);
+  static constexpr int B_ROUNDS = WN == 4 ? (B8 ? 4 : (B6 ? 3 : 2)) : ((B8 || B6) ? 2 : 1);
+  static constexpr int PER_STAGE = A_ROUNDS + B_ROUNDS + 1;
+  uint32_t offE[4], offB[4], offH, offS;
   const uint8_t *pA, *pB, *pS;
   uint32_t wslot, wslot_end, sdelta, hdelta;
 
@@ -401,7 +405,7 @@ struct Copier {
     constexpr int TILE_CH = C::AT / 16;
     constexpr int TILE_CH_B = C::BT / 16;
 #pragma unroll
-    for (int u = 0; u < 3; ++u) {   // chunk tid + 256 u of an 8-tile run
+    for (int u = 0; u < 4; ++u) {   // chunk tid + 256 u of an 8-tile run
       const int c = tid + u * C::THREADS;
       offE[u] = (uint32_t)((c / TILE_CH) * k_tiles * C::AT + (c % TILE_CH) * 16);
       offB[u] = (uint32_t)((c / TILE_CH_B) * k_tiles * C::BT + (c % TILE_CH_B) * 16);
@@ -424,14 +428,16 @@ struct Copier {
   }
 #define MXP_COPY16(voff, sptr, imm) \
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "n"(imm), "v"(voff), "s"(sptr) : "memory", "scc")
-  // copy number u of the next stage; u = 6 is always the scale copy
+  // copy number u of the next stage; u = 6 is always the scale copy; 7 and 8 are the fourth rounds of E4M3 operands
   __device__ __forceinline__ void copy(int u) const {
     if (u == 0) MXP_COPY16(offE[0], pA, 0);
     else if (u == 1) MXP_COPY16(offE[1], pA, 4096);
-    else if (u == 2 && A6) MXP_COPY16(offE[2], pA, 8192);
+    else if (u == 2 && (A6 || A8)) MXP_COPY16(offE[2], pA, 8192);
+    else if (u == 7 && A8) MXP_COPY16(offE[3], pA, 12288);
     else if (u == 3) MXP_COPY16(offB[0], pB, C::A_BYTES);
-    else if (u == 4 && WN == 4) MXP_COPY16(offB[1], pB, C::A_BYTES + 4096);
-    else if (u == 5 && WN == 4 && B6) MXP_COPY16(offB[2], pB, C::A_BYTES + 8192);
+    else if (u == 4 && (WN == 4 || B8)) MXP_COPY16(offB[1], pB, C::A_BYTES + 4096);
+    else if (u == 5 && WN == 4 && (B6 || B8)) MXP_COPY16(offB[2], pB, C::A_BYTES + 8192);
+    else if (u == 8 && WN == 4 && B8) MXP_COPY16(offB[3], pB, C::A_BYTES + 12288);
     else if (u == 4 && WN == 2 && B6)
       asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(wslot), "s"(hdelta), "v"(offH), "s"(pB) : "memory", "scc");
     else if (u == 6)
@@ -447,7 +453,7 @@ struct Copier {
   }
   __device__ __forceinline__ void issue_stage() {
 #pragma unroll
-    for (int u = 0; u < 7; ++u) copy(u);   // rounds that do not exist for this tile kind are no-ops
+    for (int u = 0; u < 9; ++u) copy(u);   // rounds that do not exist for this tile kind are no-ops
     next_stage();
   }
   // same state change as `n` issue_stage() calls, without the copies (they were issued ahead of time)
@@ -458,6 +464,16 @@ struct Copier {
     wslot += (uint32_t)n * C::STAGE_BYTES;   // n < S and the ring starts at slot 0 for every tile
   }
 };
+
+// Where the epilogue patches (4 wavefronts x 2 x kPatchBytes) live.  Behind the ring when both fit in the 160 KiB of LDS.
+// With E4M3 operands they do not; the patches then start at the last ring slot: the ring is idle during an epilogue
+// (every wavefront has passed the barrier after its last fragment reads), the next tile's prologue, which a wavefront
+// issues right after its own stores, only fills slots 0 .. S-2, and the first copy into slot S-1 is issued behind the
+// next tile's first barrier, which no wavefront reaches before it has finished its epilogue.
+template <class C, int S>
+__host__ __device__ constexpr int patch_base() {
+  return S * C::STAGE_BYTES + 4 * 2 * kPatchBytes <= 160 * 1024 ? S * C::STAGE_BYTES : (S - 1) * C::STAGE_BYTES;
+}
 
 // Stages 0 .. S-2 of a tile (its prologue), issued either at kernel start or while the previous tile is being stored.
 template <class C, int S, int WN>
@@ -602,6 +618,8 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_GAP();
       MXP_MFMA(15);
       MXP_CP(6);
+      MXP_CP(7);
+      MXP_CP(8);
     } else {
       MXP_MFMA(2);
       MXP_READ(na[0] = read_b<C::AT>(st + a_tiles_off + 0 * C::AT, lane));
@@ -628,6 +646,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_MFMA(7);
       MXP_CP(4);
       MXP_CP(6);
+      MXP_CP(7);
     }
     if (COPY) cp.next_stage();
     read_off = read_off + C::STAGE_BYTES == S * C::STAGE_BYTES ? 0 : read_off + C::STAGE_BYTES;
@@ -656,7 +675,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // every wavefront has read its last fragments: the ring may be refilled
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   MXP_DBG_MARK(dbg_slot, 2);
-  store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + S * C::STAGE_BYTES + wave * (2 * kPatchBytes));
+  store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + patch_base<C, S>() + wave * (2 * kPatchBytes));
   if (next_kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
   else if (next_kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
   MXP_DBG_MARK(dbg_slot, 3);
@@ -783,7 +802,9 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   }
   const int gnf = (int)(gn - best_hc), nhc = (int)(2 * best_hc);
   dim3 grid((unsigned)P);
-  constexpr size_t lds = (size_t)S * C::STAGE_BYTES + 4 * 2 * kPatchBytes;   // ring + one pair of epilogue patches per wavefront
+  // ring + one pair of epilogue patches per wavefront (which may start inside the last ring slot, see patch_base)
+  constexpr size_t lds_patched = (size_t)patch_base<C, S>() + 4 * 2 * kPatchBytes, lds_ring = (size_t)S * C::STAGE_BYTES;
+  constexpr size_t lds = lds_patched > lds_ring ? lds_patched : lds_ring;
   static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KiB of a CDNA4 compute unit");
   if (d_dtype == MXP_BF16) {
     static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, true>),
@@ -1177,7 +1198,7 @@ int launch_canon(const uint8_t* Ai, const uint8_t* we, const uint8_t* ws, const 
 }
 
 #ifndef MXP_RING
-#define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS
+#define MXP_RING 4   // ring depth; 4 x 25.6 KB + 36 KB of epilogue patches = 136 KB of the 160 KB LDS (E4M3: 4 x 33 KB + 3 KB)
 #endif
 template <int BT, int AT>
 int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
@@ -1196,8 +1217,12 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
                 int d_dtype, int64_t ldd, hipStream_t s) {
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
-  // E4M3 images (the MXFP4++ product, Sec. 4.3) run on the two-stage kernel: half the MFMA rate leaves it the time
-  if (a_kind == MXP_IMAGE_E4M3) return launch_cfg<Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  // E4M3 images (the MXFP4++ product, Sec. 4.3): the pipelined kernel, or the two-stage one for few rows / short K
+  if (a_kind == MXP_IMAGE_E4M3) {
+    using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
+    if (M <= 128 || image_geom(M, K).k_tiles < 4) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  }
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
