@@ -844,7 +844,8 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t ct = (int64_t)blockIdx.x * CT;              // first column tile of B (32 columns each)
-  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : (BT == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
+  constexpr int FA = AT == kTileBytes ? kFmtE2M3 : (AT == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
   const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
   const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
   const int b_shift = (int)(ct & 3) * 8;                    // byte j of the shifted dword = column tile ct + j
@@ -873,9 +874,15 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
       for (int j = 0; j < CT; ++j) {
         const uint8_t* t = bt + ((int64_t)j * k_tiles + kt) * BT;
         const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + lane * 16));
-        u32x2 hi = {0, 0};
-        if (BT == kTileBytes) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
-        b[c][j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+        u32x4 hi = {0, 0, 0, 0};
+        if (BT == kTileBytes) {
+          const u32x2 h2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + 1024 + lane * 8));
+          hi.x = h2.x;
+          hi.y = h2.y;
+        } else if (BT == kTileBytesE4M3) {
+          hi = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t + 1024 + lane * 16));
+        }
+        b[c][j] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
       }
       sb[c] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
       sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
@@ -884,13 +891,18 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_kernel(const uint8_t* 
         // lanes of rows past M would fetch the image's zero padding: leaving them out saves that part of the A stream
         // (with 8 rows, three quarters of it)
         const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
-        u32x4 alo = {0, 0, 0, 0};
-        u32x2 ahi = {0, 0};
+        u32x4 alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
         if (32 * i + (lane & 31) < M) {
           alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
-          if (AT == kTileBytes) ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+          if (AT == kTileBytes) {
+            const u32x2 h2 = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+            ahi.x = h2.x;
+            ahi.y = h2.y;
+          } else if (AT == kTileBytesE4M3) {
+            ahi = *reinterpret_cast<const u32x4*>(ta + 1024 + lane * 16);
+          }
         }
-        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, (int)ahi.z, (int)ahi.w};
       }
     }
 #pragma unroll
@@ -1220,6 +1232,7 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   // E4M3 images (the MXFP4++ product, Sec. 4.3): the pipelined kernel, or the two-stage one for few rows / short K
   if (a_kind == MXP_IMAGE_E4M3) {
     using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
+    if (M <= 64) return launch_skinny<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     if (M <= 128 || image_geom(M, K).k_tiles < 4) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }

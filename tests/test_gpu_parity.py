@@ -713,7 +713,7 @@ def test_gemm_mxfp4pp_hand_case():
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (100, 200, 416), (257, 300, 1024), (300, 520, 2048),
-                                   (64, 1000, 4160), (512, 1100, 640)])
+                                   (64, 1000, 4160), (512, 1100, 640), (8, 12840, 256), (8, 25632, 512), (129, 70, 128)])
 def test_gemm_mxfp4pp_shapes(M, N, K):
     a = synth.activations(M, K, config_id=1, tensor_id=0)
     w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
