@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "dequantize", "copy"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_decode_large", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -129,8 +129,29 @@ def main():
         copy_src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         copy_dst = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
 
+    if args.only == "gemm_e4m3":       # the MXFP4++ product (Sec. 4.3) on the same tensors, E4M3 images
+        img_a8 = mxp.prepack_e4m3(mxp.quantize(A, mxp.MXFP4PP), mxp.MXFP4PP)
+        W8 = to_dev(w_bits)
+        img_w8 = mxp.prepack_e4m3(mxp.quantize(W8, mxp.MXFP4PP), mxp.MXFP4PP)
+        del W8
+    if args.only == "gemm_decode_large":   # 8 rows against a 70B-sized layer, random codes
+        Nl, Kl = 28672, 8192
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        ql = (torch.randint(0, 256, (Nl, Kl // 2), dtype=torch.uint8, device=dev, generator=gen),
+              torch.randint(120, 134, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen),
+              torch.randint(0, 32, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen))
+        img_wl = mxp.prepack(ql, mxp.MXFP4P)
+        img_al = mxp.prepack(tuple(t[:8].contiguous() for t in ql), mxp.MXFP4P)
+        Dl = torch.empty((8, Nl), dtype=torch.float32, device=dev)
+        del ql
+
     def step_only():
-        if args.only == "quantize":
+        if args.only == "gemm_e4m3":
+            mxp.gemm_prepacked(M, N, K, img_a8, img_w8, out=D, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+        elif args.only == "gemm_decode_large":
+            mxp.gemm_prepacked(8, Nl, Kl, img_al, img_wl, out=Dl)
+        elif args.only == "quantize":
             mxp.quantize_into(A, mxp.MXFP4P, *qa)
         elif args.only == "quantize_t":
             mxp.quantize_t(WT, mxp.MXFP4P)
