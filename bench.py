@@ -248,6 +248,13 @@ def main():
     img_a4 = mxp.prepack_e2m1(mxp.quantize(A, mxp.MXFP4))
     gemm_a4w4_ms = timed_gemm(img_a4, mxp.IMAGE_E2M1, img_w4, mxp.IMAGE_E2M1)
     del img_w4, img_a4
+    # MXFP4++ x MXFP4++ (Sec. 4.3): E4M3 images, FP8 MFMAs at half rate
+    W8 = to_dev(w_bits)
+    img_w8 = mxp.prepack_e4m3(mxp.quantize(W8, mxp.MXFP4PP), mxp.MXFP4PP)
+    del W8
+    img_a8 = mxp.prepack_e4m3(mxp.quantize(A, mxp.MXFP4PP), mxp.MXFP4PP)
+    gemm_pp8_ms = timed_gemm(img_a8, mxp.IMAGE_E4M3, img_w8, mxp.IMAGE_E4M3)
+    del img_w8, img_a8
 
     # Decode configuration (8 x 4096 activations, 4096 x 4096 weights): activations quantized on the fly, prepacked
     # weights, 20 calls back to back.  Bound by reading the weight image once; at this size launch latency dominates.
@@ -422,7 +429,9 @@ def main():
         "gemm_back_to_back_%s_out_TFLOPs" % ("bf16" if out_dt == torch.float32 else "f32"): flops / (gemm_pp_other_ms * 1e-3) / 1e12,
         "gemm_a_mxfp4p_w_mxfp4_back_to_back_TFLOPs": flops / (gemm_w4_ms * 1e-3) / 1e12,
         "gemm_plain_mxfp4_back_to_back_TFLOPs": flops / (gemm_a4w4_ms * 1e-3) / 1e12,
+        "gemm_mxfp4pp_back_to_back_TFLOPs": flops / (gemm_pp8_ms * 1e-3) / 1e12,
         "gemm_time_vs_plain_mxfp4": {"mxfp4p_x_mxfp4p": gemm_pp_ms / gemm_a4w4_ms, "mxfp4p_x_mxfp4": gemm_w4_ms / gemm_a4w4_ms,
+                                     "mxfp4pp_x_mxfp4pp": gemm_pp8_ms / gemm_a4w4_ms,
                                      "note": "same kernel, same shape, back to back; the paper's software MX+ GEMM costs 1.54x "
                                              "its MXFP4 GEMM in prefill on its GPU (Sec. 8)"},
         "gemm_with_prepacked_weights_TFLOPs": flops / ((stage_ms["gemm"] + stage_ms["quantize_a"]) * 1e-3) / 1e12,
