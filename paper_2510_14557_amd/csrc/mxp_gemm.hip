@@ -995,8 +995,8 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
     else launch_skinny_out<1, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else {
     if (ct / 2 >= kEnough) launch_skinny_out<2, 2, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else if (wide) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (wide && BT != kTileBytesE4M3) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);   // (E4M3 fragments: 16 wavefronts would spill)
   }
   return launch_status();
 }
@@ -1197,14 +1197,12 @@ int launch_canon(const uint8_t* Ai, const uint8_t* we, const uint8_t* ws, const 
   constexpr int64_t kEnough = 200;
   if (M <= 32) {
     if (ct / 4 >= kEnough) launch_canon_cfg<1, 4, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
-    else if (ct / 2 >= kEnough && wide) launch_canon_cfg<1, 2, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
     else if (ct / 2 >= kEnough) launch_canon_cfg<1, 2, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
     else if (wide) launch_canon_cfg<1, 1, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
     else launch_canon_cfg<1, 1, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
   } else {
     if (ct / 2 >= kEnough) launch_canon_cfg<2, 2, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
-    else if (wide) launch_canon_cfg<2, 1, PLUS, 16>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
-    else launch_canon_cfg<2, 1, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);
+    else launch_canon_cfg<2, 1, PLUS, 8>(bf, ct, s, ae, as, we, ws, wi, nbk, kt, M, N, D, ldd);   // 16 wavefronts would spill
   }
   return launch_status();
 }

@@ -206,7 +206,8 @@ __global__ void __launch_bounds__(64 * WAVES) w4a16_skinny_kernel(const uint16_t
 template <int MODE, int TMR, bool OUT_BF16>
 void launch_skinny(dim3 grid, hipStream_t s, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws, const uint8_t* wi,
                    int64_t nbk, int64_t M, int64_t N, void* D, int64_t ldd) {
-  constexpr int WAVES = 16;
+  // two row tiles need more than the 128 registers a lane gets with 16 wavefronts (the compiler spilled ~90): 8 then
+  constexpr int WAVES = TMR == 1 ? 16 : 8;
   constexpr int lds_part = WAVES * TMR * 16 * 64 * 4, lds_patch = WAVES * kW4PatchBytes;
   constexpr int lds = lds_part > lds_patch ? lds_part : lds_patch;
   static_assert(lds <= 160 * 1024, "LDS");
