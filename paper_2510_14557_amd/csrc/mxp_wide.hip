@@ -8,8 +8,9 @@
 //
 // Storage: eight-bit codes one per byte; six-bit codes as a little-endian bit string, element i of a block in bits
 // [6i, 6i+6) of its 24 bytes.  Four lanes share a block, a lane holds 8 consecutive elements (48 or 64 code bits).
-// Rounding is done on integer fields of the fp32 pattern (nothing depends on the float mode), except the E4M3
-// elements, which the hardware pack-convert produces.
+// Ordinary elements go through the CDNA4 pack-convert / unpack-convert instructions; the BM, and every block whose
+// results could leave the fp32 normal range, through integer code on the fields of the fp32 pattern (nothing there
+// depends on the float mode).
 #include "mxp_common.h"
 
 namespace {
@@ -232,6 +233,128 @@ __global__ void __launch_bounds__(256) quantize_wide_kernel(const void* __restri
   }
 }
 
+// ---- MXFP6 / MXFP6+ through the 32-element pack-convert ---------------------------------------------------------
+// The CDNA4 instruction converts 32 values of ONE lane to 32 E2M3 codes (x / X, round to nearest even, saturating, sign
+// kept; code i in bits [6i, 6i+6) of its six result dwords).  The block maximum is still found by the quad; then every
+// lane of the quad collects the whole block with quad broadcasts, all four convert it, and lanes 0..2 store 8 of the 24
+// bytes each.  The E0M5 BM of MXFP6+ is written over its slot inside each lane's 64-bit share.
+typedef __bf16 v32bf __attribute__((ext_vector_type(32)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t v6u __attribute__((ext_vector_type(6)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v32f __attribute__((ext_vector_type(32)));
+constexpr int kQuadLane0 = 0x00, kQuadLane1 = 0x55, kQuadLane2 = 0xAA, kQuadLane3 = 0xFF;   // quad_perm broadcasts
+
+template <bool BF16, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_fp6_kernel(const void* __restrict__ src, int64_t nbk, int64_t ld, int64_t nq,
+                                                           uint8_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                           uint8_t* __restrict__ bm_idx) {
+  using F = Elem<6>;
+  constexpr int NW = BF16 ? 4 : 8;                  // dwords a lane loads
+  const uint32_t part = threadIdx.x & 3u;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; (q & ~(int64_t)3) < nq; q += stride) {
+    const int64_t g = q >> 2;
+    const int64_t row = g / nbk;
+    const int64_t off = row * ld + (g - row * nbk) * 32 + part * 8;
+    uint32_t w[NW], a[8], sg[8];
+    if (BF16) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off);
+      w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        a[2 * j] = (w[j] << 16) & 0x7FFF0000u;
+        sg[2 * j] = (w[j] >> 15) & 1u;
+        a[2 * j + 1] = w[j] & 0x7FFF0000u;
+        sg[2 * j + 1] = w[j] >> 31;
+      }
+    } else {
+      const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+      const u32x4 v0 = p[0], v1 = p[1];
+      const uint32_t t[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        w[i] = t[i];
+        a[i] = t[i] & 0x7FFFFFFFu;
+        sg[i] = t[i] >> 31;
+      }
+    }
+    uint32_t mx = a[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = umax(mx, a[i]);
+    mx = umax(mx, dpp_mov<kQuadSwap1>(mx));
+    mx = umax(mx, dpp_mov<kQuadSwap2>(mx));
+    uint32_t pos = 32u, bm_sign = 0;
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+      const bool hit = a[i] == mx;
+      pos = hit ? part * 8u + (uint32_t)i : pos;
+      bm_sign = hit ? sg[i] : bm_sign;                // sign at this lane's lowest hit
+    }
+    // lowest position over the quad, and the sign that goes with it
+    uint32_t key = (pos << 1) | bm_sign;
+    key = umin(key, dpp_mov<kQuadSwap1>(key));
+    key = umin(key, dpp_mov<kQuadSwap2>(key));
+    pos = key >> 1;
+    bm_sign = key & 1u;
+    const uint32_t E = mx >> 23;
+    const bool flush = E <= (uint32_t)F::EMAX, nonfinite = E == 255u;
+    const int sbyte = (int)E - F::EMAX;
+    const float X = __uint_as_float((uint32_t)(sbyte > 0 ? sbyte : 1) << 23);
+    // the whole block in every lane of the quad
+    uint32_t all[4 * NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+      all[0 * NW + j] = dpp_mov<kQuadLane0>(w[j]);
+      all[1 * NW + j] = dpp_mov<kQuadLane1>(w[j]);
+      all[2 * NW + j] = dpp_mov<kQuadLane2>(w[j]);
+      all[3 * NW + j] = dpp_mov<kQuadLane3>(w[j]);
+    }
+    v6u r;
+    if (BF16) {
+      union { uint32_t u[16]; v32bf v; } c;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c.u[i] = all[i];
+      r = __builtin_amdgcn_cvt_scalef32_pk32_fp6_bf16(c.v, X);
+    } else {
+      v16f lo16, hi16;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {                   // the two sources are interleaved: code 2i from the first, 2i + 1 from the second
+        lo16[i] = __uint_as_float(all[2 * i]);
+        hi16[i] = __uint_as_float(all[2 * i + 1]);
+      }
+      r = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(lo16, hi16, X);
+    }
+    // this lane's share: dwords 2 part, 2 part + 1 (lane 3 stores nothing)
+    uint32_t s0 = part == 0u ? r[0] : (part == 1u ? r[2] : r[4]);
+    uint32_t s1 = part == 0u ? r[1] : (part == 1u ? r[3] : r[5]);
+    if (PLUS) {
+      // BM code sign | mmmmm at bit 6 pos of the block's string = bit rel of this share (may hang over either edge)
+      const uint32_t code = (bm_sign << 5) | bm_code<6>(mx);
+      const int rel = (int)(6u * pos) - 64 * (int)part;
+      uint64_t share = ((uint64_t)s1 << 32) | s0;
+      if (rel > -6 && rel < 64) {
+        const uint64_t m = rel >= 0 ? ((uint64_t)0x3Fu << rel) : ((uint64_t)0x3Fu >> (-rel));
+        const uint64_t c = rel >= 0 ? ((uint64_t)code << rel) : ((uint64_t)code >> (-rel));
+        share = (share & ~m) | c;
+      }
+      s0 = (uint32_t)share;
+      s1 = (uint32_t)(share >> 32);
+    }
+    uint32_t sb = (uint32_t)sbyte, idx = pos;
+    if (flush || nonfinite) {
+      s0 = s1 = 0;
+      idx = 0;
+      sb = nonfinite ? 255u : 0u;
+    }
+    if (q < nq && part < 3u) *reinterpret_cast<u32x2*>(elems + g * 24 + part * 8) = u32x2{s0, s1};
+    if (part == 0u && q < nq) {
+      scales[g] = (uint8_t)sb;
+      if (PLUS) bm_idx[g] = (uint8_t)idx;
+    }
+  }
+}
+
 // ---- de-conversion (Eq. 2) ------------------------------------------------------------------------------------
 template <int BITS, bool PLUS, bool OUT_BF16>
 __global__ void __launch_bounds__(256) dequantize_wide_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
@@ -244,6 +367,99 @@ __global__ void __launch_bounds__(256) dequantize_wide_kernel(const uint8_t* __r
     const int64_t g = q >> 2;
     const int64_t row = g / nbk;
     const int64_t off = row * ld + (g - row * nbk) * 32 + part * 8;
+    // Common case (no result below the normal range, no overflow, no E4M3 NaN code): the CDNA4 unpack-convert
+    // instructions, value * X exact in both output types; the lane that holds the BM then writes it over its element.
+    {
+      const uint32_t sb = scales[g];
+      if (sb >= 16u && sb <= 240u) {
+        const float X = __uint_as_float(sb << 23);
+        const uint32_t bmq = PLUS ? (bm_idx[g] & 31u) : 64u;
+        const bool mine = PLUS && (bmq >> 3) == part;
+        const uint32_t pi = bmq & 7u;
+        uint32_t f[8], hb[4];
+        bool done = true;
+        if (BITS == 8) {
+          const u32x2 v = *reinterpret_cast<const u32x2*>(elems + g * 32 + part * 8);
+          // bytes whose low seven bits are all ones (S.1111.111) take the general path below
+          const uint32_t nanlike = (((v.x & 0x7F7F7F7Fu) + 0x01010101u) | ((v.y & 0x7F7F7F7Fu) + 0x01010101u)) & 0x80808080u;
+          done = nanlike == 0u;
+          if (done) {
+            const uint32_t code = ((pi < 4u ? v.x : v.y) >> (8u * (pi & 3u))) & 0xFFu;
+            const uint32_t bmbits = make_f32(code >> 7, 128u | (code & 127u), F::EMAX - 7 + (int)sb - 127);
+            if (OUT_BF16) {
+              union { v2bf v; uint32_t u; } c0, c1, c2, c3;
+              c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, X, false);
+              c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, X, true);
+              c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, X, false);
+              c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, X, true);
+              hb[0] = c0.u; hb[1] = c1.u; hb[2] = c2.u; hb[3] = c3.u;
+            } else {
+              const v2f f0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v.x, X, false), f1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v.x, X, true);
+              const v2f f2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v.y, X, false), f3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(v.y, X, true);
+              f[0] = __float_as_uint(f0[0]); f[1] = __float_as_uint(f0[1]); f[2] = __float_as_uint(f1[0]); f[3] = __float_as_uint(f1[1]);
+              f[4] = __float_as_uint(f2[0]); f[5] = __float_as_uint(f2[1]); f[6] = __float_as_uint(f3[0]); f[7] = __float_as_uint(f3[1]);
+            }
+            if (mine) {
+              if (OUT_BF16) {
+                const uint32_t sh = (pi & 1u) * 16u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                  if ((pi >> 1) == (uint32_t)j) hb[j] = (hb[j] & ~(0xFFFFu << sh)) | ((bmbits >> 16) << sh);
+              } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                  if (pi == (uint32_t)i) f[i] = bmbits;
+              }
+            }
+          }
+        } else {
+          const u32x2* in = reinterpret_cast<const u32x2*>(elems + g * 24);
+          const u32x2 d0 = in[0], d1 = in[1], d2 = in[2];
+          const v6u str = {d0.x, d0.y, d1.x, d1.y, d2.x, d2.y};
+          // the BM's code, from this lane's own 48 bits
+          const uint32_t first = (part >> 1) * 3u + (part & 1u);
+          const uint32_t w0 = first == 0u ? d0.x : (first == 1u ? d0.y : (first == 3u ? d1.y : d2.x));
+          const uint32_t w1 = first == 0u ? d0.y : (first == 1u ? d1.x : (first == 3u ? d2.x : d2.y));
+          const uint64_t mine48 = (part & 1u) ? (((uint64_t)w1 << 16) | (w0 >> 16)) : (((uint64_t)(w1 & 0xFFFFu) << 32) | w0);
+          const uint32_t code = (uint32_t)(mine48 >> (6u * pi)) & 0x3Fu;
+          const uint32_t bmbits = make_f32(code >> 5, 32u | (code & 31u), F::EMAX - 5 + (int)sb - 127);
+          if (OUT_BF16) {
+            union { v32bf v; uint32_t u[16]; } c;
+            c.v = __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(str, X);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              hb[j] = part == 0u ? c.u[j] : (part == 1u ? c.u[4 + j] : (part == 2u ? c.u[8 + j] : c.u[12 + j]));
+            if (mine) {
+              const uint32_t sh = (pi & 1u) * 16u;
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                if ((pi >> 1) == (uint32_t)j) hb[j] = (hb[j] & ~(0xFFFFu << sh)) | ((bmbits >> 16) << sh);
+            }
+          } else {
+            union { v32f v; uint32_t u[32]; } c;
+            c.v = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(str, X);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              f[i] = part == 0u ? c.u[i] : (part == 1u ? c.u[8 + i] : (part == 2u ? c.u[16 + i] : c.u[24 + i]));
+            if (mine) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i)
+                if (pi == (uint32_t)i) f[i] = bmbits;
+            }
+          }
+        }
+        if (done) {
+          if (OUT_BF16) {
+            *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + off) = u32x4{hb[0], hb[1], hb[2], hb[3]};
+          } else {
+            u32x4* o = reinterpret_cast<u32x4*>(static_cast<float*>(dst) + off);
+            o[0] = u32x4{f[0], f[1], f[2], f[3]};
+            o[1] = u32x4{f[4], f[5], f[6], f[7]};
+          }
+          continue;
+        }
+      }
+    }
     uint32_t lo, hi;
     if (BITS == 8) {
       const u32x2 v = *reinterpret_cast<const u32x2*>(elems + g * 32 + part * 8);
@@ -316,8 +532,10 @@ int wide_quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K
   const bool bf = src_dtype == MXP_BF16;
 #define MXP_LAUNCH_QW(B, BT, P) hipLaunchKernelGGL((quantize_wide_kernel<B, BT, P>), grid, dim3(256), 0, s, src, nbk, ld_src, nq, elems, scales, bm_idx)
   switch (fmt) {
-    case MXP_FMT_MXFP6: if (bf) MXP_LAUNCH_QW(true, 6, false); else MXP_LAUNCH_QW(false, 6, false); break;
-    case MXP_FMT_MXFP6P: if (bf) MXP_LAUNCH_QW(true, 6, true); else MXP_LAUNCH_QW(false, 6, true); break;
+#define MXP_LAUNCH_Q6(B, P) hipLaunchKernelGGL((quantize_fp6_kernel<B, P>), grid, dim3(256), 0, s, src, nbk, ld_src, nq, elems, scales, bm_idx)
+    case MXP_FMT_MXFP6: if (bf) MXP_LAUNCH_Q6(true, false); else MXP_LAUNCH_Q6(false, false); break;
+    case MXP_FMT_MXFP6P: if (bf) MXP_LAUNCH_Q6(true, true); else MXP_LAUNCH_Q6(false, true); break;
+#undef MXP_LAUNCH_Q6
     case MXP_FMT_MXFP8: if (bf) MXP_LAUNCH_QW(true, 8, false); else MXP_LAUNCH_QW(false, 8, false); break;
     case MXP_FMT_MXFP8P: if (bf) MXP_LAUNCH_QW(true, 8, true); else MXP_LAUNCH_QW(false, 8, true); break;
     default: return MXP_ERR_FORMAT;
