@@ -348,6 +348,7 @@ def main():
 
     mfma_peak_e2m3 = timed_probe(mxp.IMAGE_E2M3, mxp.IMAGE_E2M3)
     mfma_peak_e2m1 = timed_probe(mxp.IMAGE_E2M1, mxp.IMAGE_E2M1)
+    mfma_peak_e4m3 = timed_probe(mxp.IMAGE_E4M3, mxp.IMAGE_E4M3)   # iterations take twice as long: FP8 runs at half rate
     cp_src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
     cp_dst = torch.empty_like(cp_src)
     for _ in range(3):
@@ -408,7 +409,7 @@ def main():
                      "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms,
                      "note": "kernel_ms = HIP event pair around the launch on every 5th timed step (includes the dispatch "
                              "gap); traffic = FETCH_SIZE*2.0 + WRITE_SIZE bytes per launch from profiles/"},
-        "measured_ceilings": {"mfma_only_e2m3_x_e2m3_TFLOPs": mfma_peak_e2m3, "mfma_only_e2m1_x_e2m1_TFLOPs": mfma_peak_e2m1,
+        "measured_ceilings": {"mfma_only_e2m3_x_e2m3_TFLOPs": mfma_peak_e2m3, "mfma_only_e2m1_x_e2m1_TFLOPs": mfma_peak_e2m1, "mfma_only_e4m3_x_e4m3_TFLOPs": mfma_peak_e4m3,
                               "device_copy_256MiB_GBps": copy_gbps,
                               "gemm_frac_of_mfma_only": gemm_tflops / mfma_peak_e2m3,
                               "note": "MFMAs alone on register-resident pseudo-random operands, 1024 wavefronts: the rate the "

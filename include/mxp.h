@@ -191,7 +191,7 @@ int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, 
                    void* D, int d_dtype, int64_t ldd, void* stream);
 
 /* Measurement aid (no paper passage: it serves the roofline): runs nothing but block-scaled MFMAs on register-resident
- * pseudo-random operands of the given image kinds, 256 workgroups x 4 wavefronts x iters x 16 MFMAs of 32x32x64
+ * pseudo-random operands of the given image kinds (E2M3 / E2M1 in any mix, or both E4M3), 256 workgroups x 4 wavefronts x iters x 16 MFMAs of 32x32x64
  * (2 * 65536 flop each); seed 0 gives all-zero operands.  sink receives 65536 floats.  Timing it gives the MFMA rate
  * the chip sustains at its power limit, the measured ceiling next to the nominal 10.1 PFLOP/s. */
 int mxp_probe_mfma(int a_kind, int b_kind, int iters, uint32_t seed, float* sink, void* stream);

@@ -1428,12 +1428,14 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ sin
 }  // namespace
 
 extern "C" int mxp_probe_mfma(int a_kind, int b_kind, int iters, uint32_t seed, float* sink, void* stream) {
-  if ((a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) || (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1)) return MXP_ERR_FORMAT;
+  const bool fp8 = a_kind == MXP_IMAGE_E4M3 && b_kind == MXP_IMAGE_E4M3;
+  if (!fp8 && ((a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) || (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1))) return MXP_ERR_FORMAT;
   if (iters < 0 || iters > (1 << 24)) return MXP_ERR_SHAPE;
   if (!sink) return MXP_ERR_NULL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid(mxp::kNumCU), block(256);
-  if (a_kind == MXP_IMAGE_E2M3 && b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
+  if (fp8) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE4M3, kFmtE4M3>), grid, block, 0, s, sink, iters, seed);
+  else if (a_kind == MXP_IMAGE_E2M3 && b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
   else if (a_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
   else if (b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
   else hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
