@@ -40,7 +40,7 @@ extern "C" {
 #define MXP_FMT_MXFP4 0  /* plain OCP MXFP4 (Sec. 2) */
 #define MXP_FMT_MXFP4P 1 /* MXFP4+ (Sec. 4)          */
 #define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion, de-conversion, and the product through E4M3 images
-                           * (mxp_prepack_e4m3 + mxp_gemm_prepacked); the other image and product entry points
+                           * (mxp_gemm, or mxp_prepack_e4m3 + mxp_gemm_prepacked); the other image and product entry points
                            * return MXP_ERR_UNSUPPORTED for it (its BM and NBMs have different scales, which one
                            * E2M3 operand cannot carry) */
 /* Six- and eight-bit MX and MX+ formats (Sec. 4.2, data layout): conversion and de-conversion only (mxp_quantize,
@@ -149,8 +149,11 @@ int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, 
  * canonical storage, formats chosen per operand (Sec. 5: activations MXFP4+ with weights MXFP4 or MXFP4+).
  * The result is the matrix product of the de-converted operands accumulated in fp32 (Sec. 5.1).
  * D is MXP_F32 or MXP_BF16 with row stride ldd.  workspace must hold mxp_gemm_workspace_bytes(M, N, K) bytes; it is
- * scratch for the two images and may be reused after the call's work on `stream` has finished. */
+ * scratch for the two images and may be reused after the call's work on `stream` has finished.  If either format is
+ * MXFP4++ (Sec. 4.3) both operands go through E4M3 images (see MXP_IMAGE_E4M3 for what that costs and how exact it is)
+ * and the workspace must hold mxp_gemm_workspace_bytes_e4m3(M, N, K) bytes. */
 size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when either format is MXP_FMT_MXFP4PP */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
              const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,

@@ -1273,6 +1273,11 @@ extern "C" size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
   return align_up((size_t)mxp::image_geom(M, K).total()) + align_up((size_t)mxp::image_geom(N, K).total());
 }
 
+extern "C" size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K) {
+  if (M < 0 || N < 0 || K < 0) return 0;
+  return align_up((size_t)mxp::image_geom(M, K, mxp::kTileBytesE4M3).total()) + align_up((size_t)mxp::image_geom(N, K, mxp::kTileBytesE4M3).total());
+}
+
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
                                   int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
@@ -1292,17 +1297,30 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
                         int fmtA, const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB, void* D,
                         int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace mxp;
-  if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
-  if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) || (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P)) return MXP_ERR_FORMAT;
+  const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
+  if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
+      (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP))
+    return MXP_ERR_FORMAT;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
-  if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA == MXP_FMT_MXFP4P && !A_idx) || (fmtB == MXP_FMT_MXFP4P && !B_idx) || !workspace)
+  if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA != MXP_FMT_MXFP4 && !A_idx) || (fmtB != MXP_FMT_MXFP4 && !B_idx) || !workspace)
     return MXP_ERR_NULL;
   if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(workspace) ||
       (A_idx && !aligned16(A_idx)) || (B_idx && !aligned16(B_idx)))
     return MXP_ERR_ALIGN;
+  if (pp) {
+    // an MXFP4++ operand needs the E4M3 image, and then both operands do (Sec. 4.3)
+    if (workspace_bytes < mxp_gemm_workspace_bytes_e4m3(M, N, K)) return MXP_ERR_WORKSPACE;
+    uint8_t* wa8 = static_cast<uint8_t*>(workspace);
+    uint8_t* wb8 = wa8 + align_up((size_t)image_geom(M, K, kTileBytesE4M3).total());
+    rc = prepack_e4m3_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa8, s);
+    if (rc != MXP_OK) return rc;
+    rc = prepack_e4m3_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb8, s);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa8, MXP_IMAGE_E4M3, wb8, MXP_IMAGE_E4M3, M, N, K, D, d_dtype, ldd, s);
+  }
   if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;
   uint8_t* wa = static_cast<uint8_t*>(workspace);
   uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());

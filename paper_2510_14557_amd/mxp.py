@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -52,6 +52,8 @@ def lib():
     L.mxp_quantize_image.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp, sz, vp]
     L.mxp_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     L.mxp_gemm_workspace_bytes.restype = sz
+    L.mxp_gemm_workspace_bytes_e4m3.argtypes = [i64, i64, i64]
+    L.mxp_gemm_workspace_bytes_e4m3.restype = sz
     L.mxp_gemm.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_prepacked.argtypes = [i64, i64, i64, vp, i32, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_decode.argtypes = [i64, i64, i64, vp, vp, vp, vp, i32, vp, i32, i64, vp]
@@ -236,7 +238,9 @@ def prepack_e2m1(q, out: torch.Tensor | None = None):
     return out
 
 
-def gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+def gemm_workspace_bytes(M: int, N: int, K: int, fmt_a: int = MXFP4P, fmt_b: int = MXFP4P) -> int:
+    if MXFP4PP in (fmt_a, fmt_b):
+        return int(lib().mxp_gemm_workspace_bytes_e4m3(M, N, K))
     return int(lib().mxp_gemm_workspace_bytes(M, N, K))
 
 
@@ -252,7 +256,7 @@ def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torc
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=ae.device)
     if workspace is None:
-        workspace = torch.empty(max(gemm_workspace_bytes(M, N, K), 16), dtype=torch.uint8, device=ae.device)
+        workspace = torch.empty(max(gemm_workspace_bytes(M, N, K, fmt_a, fmt_b), 16), dtype=torch.uint8, device=ae.device)
     ldd = out.stride(0) if M > 1 else max(N, 1)
     _check(lib().mxp_gemm(M, N, K, _p(ae), _p(as_), _p(ai), fmt_a, _p(be), _p(bs), _p(bi), fmt_b, _p(out), _dt(out), ldd,
                           _p(workspace), workspace.numel(), _stream()), "mxp_gemm")

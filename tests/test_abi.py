@@ -106,7 +106,10 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, p, mxp.MXFP4P, p, mxp.F32, 32, None) == -2
     # MXFP4++ is a codec: no image, no W4A4 product
     assert L.mxp_prepack(p, p, p, mxp.MXFP4PP, 64, 64, p, 1 << 20, None) == -8
-    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, 1 << 20, None) == -8
+    # an MXFP4++ operand sends both through E4M3 images: a workspace sized for E2M3 images is too small
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4P) > mxp.gemm_workspace_bytes(64, 64, 64)
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, mxp.gemm_workspace_bytes(64, 64, 64), None) == -6
+    assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, 1 << 20, None) == -1
     assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4PP, None, None, None, p, 1 << 20, None) == -8
     # empty problems are fine and launch nothing
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0

@@ -136,11 +136,9 @@ def test_quantize_mxfp4pp_every_delta(bf16):
     mxp.dequantize(q_dev(want), mxp.MXFP4PP, out=out[:, :x.shape[1]])
     back = out.cpu().numpy()
     assert (back[:, x.shape[1]:] == 5.0).all() and (back[:, :x.shape[1]][~nan] == ref[~nan]).all()
-    # the image and product entry points refuse the format
+    # the E2M3 image cannot hold the format (its product goes through E4M3 images)
     with pytest.raises(mxp.MxpError):
         mxp.prepack(q_dev(want), mxp.MXFP4PP)
-    with pytest.raises(mxp.MxpError):
-        mxp.gemm(q_dev(want), mxp.MXFP4PP, q_dev(want), mxp.MXFP4P)
 
 
 def test_quantize_mxfp4pp_activation_shapes():
@@ -724,6 +722,7 @@ def test_gemm_mxfp4pp_shapes(M, N, K):
     assert ia.numel() == mxp.image_bytes_e4m3(M, K)
     D = mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
     check_gemm_e4m3(D, ref, S, "mxfp4++ %dx%dx%d" % (M, N, K))
+    assert torch.equal(D, mxp.gemm(q_dev(qa), mxp.MXFP4PP, q_dev(qb), mxp.MXFP4PP))     # the one-call route
     Db = mxp.gemm_prepacked(M, N, K, ia, ib, out_dtype=torch.bfloat16, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
     assert torch.equal(Db, D.to(torch.bfloat16))
     # an MXFP4+ operand in an E4M3 image gives the products of its E2M3 image (mixed: A MXFP4++, W MXFP4+)
@@ -731,6 +730,7 @@ def test_gemm_mxfp4pp_shapes(M, N, K):
     ref2, S2 = oracle.gemm(qa, oracle.MXFP4PP, qw, oracle.MXFP4P)
     D2 = mxp.gemm_prepacked(M, N, K, ia, mxp.prepack_e4m3(q_dev(qw), mxp.MXFP4P), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
     check_gemm_e4m3(D2, ref2, S2, "mxfp4++ x mxfp4+ %dx%dx%d" % (M, N, K))
+    assert torch.equal(D2, mxp.gemm(q_dev(qa), mxp.MXFP4PP, q_dev(qw), mxp.MXFP4P))
     # operands without a delta span 12 bits: their E4M3 product meets the bound of the main path
     qa1 = oracle.quantize(a, oracle.MXFP4P)
     ref3, S3 = oracle.gemm(qa1, oracle.MXFP4P, qw, oracle.MXFP4P)
