@@ -141,7 +141,9 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
 /* Conversion (Sec. 4.1, 4.2) written directly as an image: same source arguments and the same encoding as
  * mxp_quantize, but the result goes to `image` (mxp_image_bytes(rows, K) bytes, bit-identical to mxp_prepack of the
  * canonical result) without a pass over the canonical bytes.  If elems / scales / bm_idx are given (all of them, bm_idx
- * only for MXFP4+) the canonical arrays are written as well; pass three null pointers to skip them. */
+ * for MXFP4+ and MXFP4++) the canonical arrays are written as well; pass three null pointers to skip them.
+ * fmt = MXP_FMT_MXFP4PP (Sec. 4.3) writes an E4M3 image instead (mxp_image_bytes_e4m3(rows, K) bytes, bit-identical to
+ * mxp_prepack_e4m3 of the canonical result). */
 int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                        uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes, void* stream);
 
@@ -165,7 +167,9 @@ int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int
 
 /* Activations given un-quantized (A[M][K], MXP_F32 or MXP_BF16, row stride lda): quantized on the fly to fmtA on
  * the same stream, then multiplied with the prepacked weight image (Sec. 7.1: activations are converted at run time,
- * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes. */
+ * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes.  fmtA = MXP_FMT_MXFP4PP
+ * needs b_kind = MXP_IMAGE_E4M3 and mxp_image_bytes_e4m3(M, K) bytes of workspace, and an E4M3 weight image is taken
+ * with that fmtA only (other pairings return MXP_ERR_UNSUPPORTED). */
 size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K);
 int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
                    const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,

@@ -89,4 +89,18 @@ inline int64_t patch_grid(int64_t k_groups, int64_t row_tile_groups) {
   return 8 * 4 * k_groups * ((row_tile_groups + 7) / 8);
 }
 
+// E4M3 image codes (Sec. 4.3): an E2M1 magnitude m stands in the image as m / 4, an FP8 E4M3 number.
+constexpr uint64_t kE2M1QuarterAsE4M3 = 0x3C3834302C282000ull;   // byte m = E4M3 code of (E2M1 magnitude m) / 4
+
+__device__ __forceinline__ uint32_t nibbles4_to_e4m3(uint32_t h) {   // low 16 bits: 4 nibbles -> 4 bytes
+  uint32_t out = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t n = (h >> (4 * i)) & 15u;
+    const uint32_t code = (uint32_t)(kE2M1QuarterAsE4M3 >> (8u * (n & 7u))) & 0xFFu;
+    out |= (code | ((n & 8u) << 4)) << (8 * i);
+  }
+  return out;
+}
+
 }  // namespace mxp

@@ -227,19 +227,6 @@ __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restri
 // true value v * 2^(shared_exp - delta)) becomes v / 4, i.e. 0, 0.125, 0.25 ... 1.5: sign | LUT[magnitude]; the BM
 // (2^2 * 1.mmm * 2^shared_exp) becomes 1.mmm * 2^delta: sign | (delta + 7) << 3 | mmm.  Same patch walk and LDS
 // staging as above.
-constexpr uint64_t kE2M1QuarterAsE4M3 = 0x3C3834302C282000ull;   // byte m = E4M3 code of (E2M1 magnitude m) / 4
-
-__device__ __forceinline__ uint32_t nibbles4_to_e4m3(uint32_t h) {   // low 16 bits: 4 nibbles -> 4 bytes
-  uint32_t out = 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t n = (h >> (4 * i)) & 15u;
-    const uint32_t code = (uint32_t)(kE2M1QuarterAsE4M3 >> (8u * (n & 7u))) & 0xFFu;
-    out |= (code | ((n & 8u) << 4)) << (8 * i);
-  }
-  return out;
-}
-
 template <int MODE>
 __global__ void __launch_bounds__(256) prepack_e4m3_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                            const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,

@@ -1343,9 +1343,10 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
                               const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd, void* workspace,
                               size_t workspace_bytes, void* stream) {
   using namespace mxp;
-  if (fmtA == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
-  if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_FORMAT;
+  if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
+  const bool fp8 = fmtA == MXP_FMT_MXFP4PP;
+  if (fp8 != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
@@ -1355,11 +1356,11 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   if (lda < K) return MXP_ERR_SHAPE;
   if (!aligned16(A) || !aligned16(B_image) || !aligned16(workspace) || (lda * (a_dtype == MXP_BF16 ? 2 : 4)) % 16 != 0)
     return MXP_ERR_ALIGN;
-  if (workspace_bytes < mxp_gemm_bf16a_workspace_bytes(M, K)) return MXP_ERR_WORKSPACE;
+  if (workspace_bytes < (fp8 ? mxp_image_bytes_e4m3(M, K) : mxp_gemm_bf16a_workspace_bytes(M, K))) return MXP_ERR_WORKSPACE;
   uint8_t* img = static_cast<uint8_t*>(workspace);
   rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
   if (rc != MXP_OK) return rc;
-  return gemm_images(img, MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
+  return gemm_images(img, fp8 ? MXP_IMAGE_E4M3 : MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
 
 // Few activation rows against weights in canonical storage (the decode stage, Sec. 7.2).

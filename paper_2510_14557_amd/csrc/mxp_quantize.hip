@@ -832,6 +832,87 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
 }
 
+// The same one-pass conversion for MXFP4++ (Sec. 4.3), whose GEMM operand is an E4M3 image: with the image's scale
+// byte set to scale byte - delta + 2 an ordinary element (E2M1 value v) becomes v / 4 and the BM 1.mmm * 2^delta, both
+// FP8 E4M3 numbers.  A lane's eight codes are eight bytes; the FP8 operand registers of a lane hold k = 16 (lane / 32)
+// + 0..15 in their first half and the same + 32 in the second, so block (kb % 2) of a tile fills register half
+// (kb % 2) of the two lanes of its row: codes 0..15 in lane r, 16..31 in lane r + 32.
+template <bool BF16>
+__global__ void __launch_bounds__(256) quantize_image_e4m3_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                                  int64_t k_tiles, uint32_t* __restrict__ elems,
+                                                                  uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
+                                                                  uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE4M3];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x, part = t & 3u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t rt = pm.rt, kt0 = pm.kg * 4;
+  const bool canon = elems != nullptr;
+  const uint32_t r0 = t >> 5, kb_in = (t >> 2) & 7u;
+  const int64_t row0 = rt * kTileRows + r0, kb = kt0 * 2 + kb_in;
+  const bool kb_ok = kb < nbk;
+  const int64_t off0 = row0 * ld + kb * 32 + part * 8, off_step = 8 * ld;
+  uint32_t w[4][8];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[u][i] = 0;
+    if (kb_ok && row0 + 8 * u < rows) {
+      const int64_t off = off0 + u * off_step;
+      if (BF16) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off));
+        w[u][0] = v.x; w[u][1] = v.y; w[u][2] = v.z; w[u][3] = v.w;
+      } else {
+        const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+        const u32x4 v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+        w[u][0] = v0.x; w[u][1] = v0.y; w[u][2] = v0.z; w[u][3] = v0.w;
+        w[u][4] = v1.x; w[u][5] = v1.y; w[u][6] = v1.z; w[u][7] = v1.w;
+      }
+    }
+  }
+  const int64_t g0 = row0 * nbk + kb, g_step = 8 * nbk;
+  // LDS destination of this lane's 8 bytes in pass u: tile kb_in / 2, register half kb_in % 2, lane (part / 2) * 32 + row
+  const uint32_t dst0 = (kb_in >> 1) * kTileBytesE4M3 + (kb_in & 1u) * 1024u + ((part >> 1) * 32u + r0) * 16u + (part & 1u) * 8u;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const bool valid = kb_ok && row0 + 8 * u < rows;
+    uint32_t sbyte, idx;
+    const uint32_t packed = encode_group<BF16, 2>(w[u], (int)part, sbyte, idx);
+    if (canon && valid) {
+      const int64_t g = g0 + u * g_step;
+      __builtin_nontemporal_store(packed, elems + g * 4 + part);
+      if (part == 0) {
+        scales[g] = (uint8_t)sbyte;
+        bm_idx[g] = (uint8_t)idx;
+      }
+    }
+    uint32_t c0 = nibbles4_to_e4m3(packed & 0xFFFFu), c1 = nibbles4_to_e4m3(packed >> 16);
+    if (sbyte == 0u) c0 = c1 = 0u;                                               // flushed block: plain zeros
+    const uint32_t delta = idx >> 5, pos = idx & 31u;
+    const bool live = sbyte != 0u && sbyte != 255u;
+    if (live && (pos >> 3) == part) {
+      const uint32_t pi = pos & 7u, nib = (packed >> (4u * pi)) & 15u;
+      const uint32_t code = ((nib & 8u) << 4) | ((delta + 7u) << 3) | (nib & 7u);
+      const uint32_t sh = (pi & 3u) * 8u;
+      if (pi < 4u) c0 = (c0 & ~(0xFFu << sh)) | (code << sh);
+      else c1 = (c1 & ~(0xFFu << sh)) | (code << sh);
+    }
+    *reinterpret_cast<u32x2*>(tiles + dst0 + u * 128u) = u32x2{c0, c1};          // 8 rows further per pass
+    if (part == 0) {
+      const uint32_t sb = !valid ? 127u : (sbyte == 255u ? 255u : (sbyte == 0u ? 127u : sbyte - delta + 2u));
+      tile_scales[(kb_in >> 1) * 64u + (kb_in & 1u) * 32u + r0 + 8u * u] = (uint8_t)sb;
+    }
+  }
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytesE4M3;
+  const uint32_t nbytes = (uint32_t)nt * kTileBytesE4M3;
+  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+    MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
 int check_common(const void* src, int src_dtype, int64_t rows, int64_t K, int fmt, const uint8_t* elems,
                  const uint8_t* scales, const uint8_t* bm_idx) {
   if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
@@ -888,7 +969,8 @@ int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int
 // Also used by the GEMM entry point that takes unquantized activations.  Canonical pointers may all be null.
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
                           uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream) {
-  const ImageGeom g = image_geom(rows, K);
+  const bool pp = fmt == MXP_FMT_MXFP4PP;
+  const ImageGeom g = image_geom(rows, K, pp ? kTileBytesE4M3 : kTileBytes);
   const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
   if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   uint8_t* ie = static_cast<uint8_t*>(image);
@@ -897,6 +979,11 @@ int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t 
   uint32_t* e32 = reinterpret_cast<uint32_t*>(elems);
   const int64_t nbk = K / kBlock;
   const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
+  if (pp) {
+    if (bf) hipLaunchKernelGGL((quantize_image_e4m3_kernel<true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+    else hipLaunchKernelGGL((quantize_image_e4m3_kernel<false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+    return launch_status();
+  }
   if (bf && plus) hipLaunchKernelGGL((quantize_image_kernel<true, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
   else if (bf) hipLaunchKernelGGL((quantize_image_kernel<true, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
   else if (plus) hipLaunchKernelGGL((quantize_image_kernel<false, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
@@ -910,19 +997,18 @@ extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, 
                                   uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes,
                                   void* stream) {
   using namespace mxp;
-  if (fmt == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
-  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P) return MXP_ERR_FORMAT;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
   if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
   if (rows == 0 || K == 0) return MXP_OK;
   if (!src || !image) return MXP_ERR_NULL;
   const bool canon = elems || scales || bm_idx;
-  if (canon && (!elems || !scales || (fmt == MXP_FMT_MXFP4P && !bm_idx))) return MXP_ERR_NULL;
+  if (canon && (!elems || !scales || (fmt != MXP_FMT_MXFP4 && !bm_idx))) return MXP_ERR_NULL;
   if (ld_src < K) return MXP_ERR_SHAPE;
   const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
   if (!aligned16(src) || !aligned16(image) || (ld_src * esz) % 16 != 0) return MXP_ERR_ALIGN;
   if (canon && (!aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx)))) return MXP_ERR_ALIGN;
-  if (image_bytes < (size_t)image_geom(rows, K).total()) return MXP_ERR_WORKSPACE;
+  if (image_bytes < (size_t)image_geom(rows, K, fmt == MXP_FMT_MXFP4PP ? kTileBytesE4M3 : kTileBytes).total()) return MXP_ERR_WORKSPACE;
   return quantize_image_launch(src, src_dtype, rows, K, ld_src, fmt, canon ? elems : nullptr, scales, bm_idx, image,
                                static_cast<hipStream_t>(stream));
 }

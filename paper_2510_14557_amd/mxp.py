@@ -192,12 +192,14 @@ def prepack(q, fmt: int = MXFP4P, out: torch.Tensor | None = None):
 
 
 def quantize_image(x: torch.Tensor, fmt: int = MXFP4P, canonical: bool = False, out=None, q_out=None):
-    """x [rows, K] fp32/bf16 -> MFMA-ready image; with canonical=True also (elems, scales, bm_idx), from the same pass."""
+    """x [rows, K] fp32/bf16 -> MFMA-ready image (E4M3 for MXFP4PP, else E2M3); with canonical=True also
+    (elems, scales, bm_idx), from the same pass."""
     _dev2d(x)
     rows, K = x.shape
     ld = x.stride(0) if rows > 1 else max(K, 1)
     if out is None:
-        out = torch.empty(image_bytes(rows, K), dtype=torch.uint8, device=x.device)
+        nbytes = image_bytes_e4m3(rows, K) if fmt == MXFP4PP else image_bytes(rows, K)
+        out = torch.empty(nbytes, dtype=torch.uint8, device=x.device)
     q = (None, None, None)
     if q_out is not None:
         q = q_out
@@ -336,13 +338,14 @@ def gemm_bf16a_workspace_bytes(M: int, K: int) -> int:
 
 def gemm_bf16a(a: torch.Tensor, fmt_a, b_image, N: int, out_dtype: torch.dtype = torch.float32,
                out: torch.Tensor | None = None, workspace: torch.Tensor | None = None, b_kind: int = IMAGE_E2M3):
-    """Activations quantized on the fly, weights given as a prepacked image."""
+    """Activations quantized on the fly, weights given as a prepacked image (fmt_a MXFP4PP: b_kind IMAGE_E4M3)."""
     _dev2d(a)
     M, K = a.shape
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=a.device)
     if workspace is None:
-        workspace = torch.empty(max(gemm_bf16a_workspace_bytes(M, K), 16), dtype=torch.uint8, device=a.device)
+        nbytes = image_bytes_e4m3(M, K) if fmt_a == MXFP4PP else gemm_bf16a_workspace_bytes(M, K)
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=a.device)
     lda = a.stride(0) if M > 1 else max(K, 1)
     ldd = out.stride(0) if M > 1 else max(N, 1)
     _check(lib().mxp_gemm_bf16a(M, N, K, _p(a), _dt(a), lda, fmt_a, _p(b_image), b_kind, _p(out), _dt(out), ldd,

@@ -110,7 +110,13 @@ def test_argument_errors_are_reported_not_launched():
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4P) > mxp.gemm_workspace_bytes(64, 64, 64)
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, mxp.gemm_workspace_bytes(64, 64, 64), None) == -6
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP4PP, p, p, p, 1, p, mxp.F32, 64, p, 1 << 20, None) == -1
-    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4PP, None, None, None, p, 1 << 20, None) == -8
+    # MXFP4++ activations become an E4M3 image (larger than the E2M3 one) and pair with E4M3 weight images only
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4PP, None, None, None, p, mxp.image_bytes(4, 64), None) == -6
+    assert L.mxp_quantize_image(p, mxp.BF16, 4, 64, 64, mxp.MXFP4PP, p, p, None, p, 1 << 20, None) == -1
+    assert L.mxp_gemm_bf16a(4, 64, 64, p, mxp.BF16, 64, mxp.MXFP4PP, p, mxp.IMAGE_E2M3, p, mxp.F32, 64, p, 1 << 20, None) == -8
+    assert L.mxp_gemm_bf16a(4, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, mxp.IMAGE_E4M3, p, mxp.F32, 64, p, 1 << 20, None) == -8
+    assert L.mxp_gemm_bf16a(4, 64, 64, p, mxp.BF16, 64, mxp.MXFP4PP, p, mxp.IMAGE_E4M3, p, mxp.F32, 64, p,
+                            mxp.gemm_bf16a_workspace_bytes(4, 64), None) == -6
     # empty problems are fine and launch nothing
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
     assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0

@@ -778,6 +778,49 @@ def test_gemm_mxfp4pp_full_size_sampled():
     assert (np.abs(got - ref) <= 2.0 ** -12 * S).all()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_image_mxfp4pp_one_pass(bf16):
+    """MXFP4++ written directly as an E4M3 image: canonical bytes are the oracle's, the image is the two-pass one."""
+    dt = "bf16" if bf16 else "f32"
+    cases = [mxpp_tensor(bf16=bf16), mxpp_tensor(rows=70, K=224, seed=5, bf16=bf16),
+             synth.activations(300, 4096, config_id=2, tensor_id=3, dtype=dt),
+             synth.activations(40, 4096 + 64, config_id=2, tensor_id=5, dtype=dt),
+             synth.activations(1, 32, config_id=2, tensor_id=4, dtype=dt)]
+    for x in cases:
+        d = to_dev(x)
+        want_q = oracle.quantize(x, oracle.MXFP4PP)
+        img, q = mxp.quantize_image(d, mxp.MXFP4PP, canonical=True)
+        assert img.numel() == mxp.image_bytes_e4m3(*x.shape)
+        assert_q_equal(q, want_q, "mxfp4pp", "one-pass canonical %s" % (x.shape,))
+        want = mxp.prepack_e4m3(q_dev(want_q), mxp.MXFP4PP)
+        assert torch.equal(img, want), "image differs for %s" % (x.shape,)
+        only = torch.full_like(img, 0xA5)
+        mxp.quantize_image(d, mxp.MXFP4PP, out=only)
+        assert torch.equal(only, want)
+    # strided source rows
+    x = mxpp_tensor(rows=19, K=192, bf16=bf16)
+    d = to_dev(x)
+    big = torch.zeros((19, 256), dtype=d.dtype, device="cuda")
+    big[:, :192] = d
+    img = mxp.quantize_image(big[:, :192], mxp.MXFP4PP)
+    assert torch.equal(img, mxp.prepack_e4m3(q_dev(oracle.quantize(x, oracle.MXFP4PP)), mxp.MXFP4PP))
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 70, 64), (130, 300, 1024), (300, 520, 2048)])
+def test_gemm_bf16a_mxfp4pp(M, N, K):
+    """Un-quantized activations x prepacked MXFP4++ weights, activations converted on the fly (Sec. 4.3, 7.1)."""
+    a = synth.activations(M, K, config_id=3, tensor_id=0, dtype="bf16")
+    w = synth.weights(N, K, config_id=3, tensor_id=1, t3_frac=0.001)
+    qa, qw = oracle.quantize(a, oracle.MXFP4PP), oracle.quantize(w, oracle.MXFP4PP)
+    ref, S = oracle.gemm(qa, oracle.MXFP4PP, qw, oracle.MXFP4PP)
+    iw = mxp.prepack_e4m3(q_dev(qw))
+    D = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4PP, iw, N, b_kind=mxp.IMAGE_E4M3)
+    check_gemm_e4m3(D, ref, S, "bf16a mxfp4++ %dx%dx%d" % (M, N, K))
+    assert torch.equal(D, mxp.gemm_prepacked(M, N, K, mxp.prepack_e4m3(q_dev(qa)), iw, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3))
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, iw, N, b_kind=mxp.IMAGE_E4M3)
+
+
 @pytest.mark.parametrize("M,N,K", [(8, 12840, 256), (8, 25632, 320), (40, 12850, 192), (3, 26000, 4160), (33, 13000, 4096)])
 def test_gemm_few_rows_many_columns(M, N, K):
     """Few activation rows and enough weight columns that a workgroup takes 2 or 4 column tiles (ragged last group)."""
