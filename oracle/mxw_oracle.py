@@ -97,3 +97,13 @@ def decode_block(codes32, scale, idx, fmt):
     rc = _L().mxw_decode_block(_p(c, C.c_uint8), int(scale), int(idx), fmt, _p(out, C.c_double))
     assert rc == 0
     return out
+
+
+def gemm(qa, fmt_a, qb, fmt_b):
+    """The product of two six- or eight-bit operands is the matrix product of their de-converted values (Sec. 5.1,
+    with the BM taken at its full precision as Sec. 6.2 defines the result): D = deq(A) deq(B)^T in float64 and
+    S = |deq(A)| |deq(B)|^T.  A: [M, K], B: [N, K]."""
+    a = dequantize(qa, fmt_a)
+    b = dequantize(qb, fmt_b)
+    assert a.shape[1] == b.shape[1]
+    return a @ b.T, np.abs(a) @ np.abs(b).T

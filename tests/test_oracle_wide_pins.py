@@ -232,3 +232,59 @@ def test_ties_take_the_lowest_index_and_signs_survive_zero_codes(name):
     assert d[3] == -5.0 and d[17] == 5.0 and d[20] == 5.0        # 5.0 is exact both as a BM and as an ordinary element
     assert codes[17] == codes[20] and codes[17] != (codes[3] & (sign - 1))
     assert np.signbit(d[1]) and d[1] == 0.0 and np.signbit(d[2])
+
+
+@pytest.mark.parametrize("fa,fb", [("mxfp6p", "mxfp6p"), ("mxfp6p", "mxfp6"), ("mxfp6", "mxfp6"), ("mxfp8", "mxfp8"),
+                                   ("mxfp8p", "mxfp8")])
+def test_product_is_the_exact_sum_of_decoded_products(fa, fb):
+    """Brute force on a tiny case: every decoded element is a dyadic rational, so the sum over K can be formed without
+    any rounding in Python's fractions; the oracle's float64 result and its bound S must equal it."""
+    from fractions import Fraction
+    rng = np.random.default_rng(11)
+    M, N, K = 3, 4, 96
+    a = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-3, 4, (M, K)))).astype(np.float32)
+    b = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    a[1, 5] = 77.0                                              # an outlier: its block's other elements become tiny codes
+    qa, qb = W.quantize(a, FMTS[fa]), W.quantize(b, FMTS[fb])
+    D, S = W.gemm(qa, FMTS[fa], qb, FMTS[fb])
+    bpb_a, bpb_b = W.block_bytes(FMTS[fa]), W.block_bytes(FMTS[fb])
+
+    def rows_of(q, fmt, bpb, bits):
+        e, s, i = q
+        out = []
+        for r in range(e.shape[0]):
+            vals = []
+            for kb in range(K // 32):
+                blk = e[r, kb * bpb:(kb + 1) * bpb]
+                if bits == 6:
+                    codes = np.packbits(np.unpackbits(blk, bitorder="little").reshape(32, 6)[:, ::-1], axis=1,
+                                        bitorder="big")[:, 0] >> 2
+                else:
+                    codes = blk
+                vals += [Fraction(float(v)) for v in W.decode_block(codes, s[r, kb], i[r, kb], fmt)]
+            out.append(vals)
+        return out
+
+    ra, rb = rows_of(qa, FMTS[fa], bpb_a, BITS[fa]), rows_of(qb, FMTS[fb], bpb_b, BITS[fb])
+    for m in range(M):
+        for n in range(N):
+            exact = sum(x * y for x, y in zip(ra[m], rb[n]))
+            bound = sum(abs(x * y) for x, y in zip(ra[m], rb[n]))
+            assert Fraction(float(D[m, n])) == exact or abs(Fraction(float(D[m, n])) - exact) <= abs(exact) * Fraction(1, 2 ** 50)
+            assert abs(Fraction(float(S[m, n])) - bound) <= bound * Fraction(1, 2 ** 50)
+
+
+def test_product_hand_case_with_a_split_bm():
+    """One block per operand.  The MXFP6+ BM 4 + 13/8 = 5.625 is not an E2M3 number (it is 5.5 + 0.125); the product
+    must use all five mantissa bits."""
+    a = np.zeros((1, 32), np.float32)
+    b = np.zeros((1, 32), np.float32)
+    a[0, 7], a[0, 8] = 5.625, 1.25
+    b[0, 7], b[0, 8], b[0, 9] = -4.375, 3.0, 0.875
+    qa, qb = W.quantize(a, W.MXFP6P), W.quantize(b, W.MXFP6P)
+    assert (W.dequantize(qa, W.MXFP6P) == a).all() and (W.dequantize(qb, W.MXFP6P) == b).all()
+    D, S = W.gemm(qa, W.MXFP6P, qb, W.MXFP6P)
+    assert D[0, 0] == 5.625 * -4.375 + 1.25 * 3.0 and S[0, 0] == 5.625 * 4.375 + 3.75
+    # the plain format keeps only three mantissa bits of each BM (5.625 -> 5.5, 4.375 -> 4.5)
+    D6, _ = W.gemm(W.quantize(a, W.MXFP6), W.MXFP6, W.quantize(b, W.MXFP6), W.MXFP6)
+    assert D6[0, 0] == 5.5 * -4.5 + 3.75
