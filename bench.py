@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_decode_large", "dequantize", "copy"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_decode_large", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -134,6 +134,11 @@ def main():
         W8 = to_dev(w_bits)
         img_w8 = mxp.prepack_e4m3(mxp.quantize(W8, mxp.MXFP4PP), mxp.MXFP4PP)
         del W8
+    if args.only == "gemm_fp6p":       # MXFP6+ activations x MXFP6 weights (Sec. 4.2 formats): two K segments, incl. both prepacks
+        W6 = to_dev(w_bits)
+        qa6, qw6 = mxp.quantize(A, mxp.MXFP6P), mxp.quantize(W6, mxp.MXFP6)
+        del W6
+        ws6 = torch.empty(mxp.gemm_workspace_bytes(M, N, K, mxp.MXFP6P, mxp.MXFP6), dtype=torch.uint8, device=dev)
     if args.only == "gemm_decode_large":   # 8 rows against a 70B-sized layer, random codes
         Nl, Kl = 28672, 8192
         gen = torch.Generator(device=dev)
@@ -149,6 +154,8 @@ def main():
     def step_only():
         if args.only == "gemm_e4m3":
             mxp.gemm_prepacked(M, N, K, img_a8, img_w8, out=D, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+        elif args.only == "gemm_fp6p":
+            mxp.gemm(qa6, mxp.MXFP6P, qw6, mxp.MXFP6, out=D, workspace=ws6)
         elif args.only == "gemm_decode_large":
             mxp.gemm_prepacked(8, Nl, Kl, img_al, img_wl, out=Dl)
         elif args.only == "quantize":
@@ -222,15 +229,16 @@ def main():
     # The paper's main deployment (Sec. 7.1): MXFP4+ activations x plain MXFP4 weights.  The weights stay in 4-bit codes on
     # the B side (E2M1 image).  All products timed the same way: 250 warm-up launches, then 100 back to back, one event pair.
     # The third product is plain MXFP4 x MXFP4 (both images 4-bit): the baseline the paper normalises MX+ to.
-    def timed_gemm(a_image, a_kind, b_image, b_kind, n=100, out=None):
+    def timed_gemm(a_image, a_kind, b_image, b_kind, n=100, out=None, k=None):
         out = D if out is None else out
+        k = K if k is None else k
         for _ in range(250):                                  # the clocks need tens of ms to settle on a new load
-            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
+            mxp.gemm_prepacked(M, N, k, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
         torch.cuda.synchronize()
         ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         ev2[0].record()
         for _ in range(n):
-            mxp.gemm_prepacked(M, N, K, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
+            mxp.gemm_prepacked(M, N, k, a_image, b_image, out=out, a_kind=a_kind, b_kind=b_kind)
         ev2[1].record()
         torch.cuda.synchronize()
         return ev2[0].elapsed_time(ev2[1]) / n
@@ -267,6 +275,17 @@ def main():
     qimg_pp8_ms = ev2[0].elapsed_time(ev2[1]) / 100
     qimg_pp8_bytes = A.numel() * A.element_size() + img_a8.numel()
     del img_w8, img_a8
+    # six-bit operands (Sec. 4.2): MXFP6 x MXFP6 is one E2M3 product; the MXFP6+ BM adds K segments (2 one-sided, 4 two-sided)
+    Kp = (K + 127) // 128 * 128
+    W6 = to_dev(w_bits)
+    qa6 = mxp.quantize(A, mxp.MXFP6P)
+    fp6_ms = {}
+    for name, fmt_w, n_seg, ma, mb in (("mxfp6p_x_mxfp6", mxp.MXFP6, 2, 0b10, 0), ("mxfp6p_x_mxfp6p", mxp.MXFP6P, 4, 0b1010, 0b1100)):
+        ia6 = mxp.prepack_fp6(qa6, mxp.MXFP6P, n_seg, ma)
+        iw6 = mxp.prepack_fp6(mxp.quantize(W6, fmt_w), fmt_w, n_seg, mb)
+        fp6_ms[name] = timed_gemm(ia6, mxp.IMAGE_E2M3, iw6, mxp.IMAGE_E2M3, k=n_seg * Kp)
+        del ia6, iw6
+    del qa6, W6
 
     # Decode configuration (8 x 4096 activations, 4096 x 4096 weights): activations quantized on the fly, prepacked
     # weights, 20 calls back to back.  Bound by reading the weight image once; at this size launch latency dominates.
@@ -444,6 +463,8 @@ def main():
         "gemm_plain_mxfp4_back_to_back_TFLOPs": flops / (gemm_a4w4_ms * 1e-3) / 1e12,
         "gemm_mxfp4pp_back_to_back_TFLOPs": flops / (gemm_pp8_ms * 1e-3) / 1e12,
         "quantize_image_mxfp4pp_GBps": qimg_pp8_bytes / (qimg_pp8_ms * 1e-3) / 1e9,
+        "gemm_mxfp6p_x_mxfp6_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6"] * 1e-3) / 1e12,
+        "gemm_mxfp6p_x_mxfp6p_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6p"] * 1e-3) / 1e12,
         "gemm_time_vs_plain_mxfp4": {"mxfp4p_x_mxfp4p": gemm_pp_ms / gemm_a4w4_ms, "mxfp4p_x_mxfp4": gemm_w4_ms / gemm_a4w4_ms,
                                      "mxfp4pp_x_mxfp4pp": gemm_pp8_ms / gemm_a4w4_ms,
                                      "note": "same kernel, same shape, back to back; the paper's software MX+ GEMM costs 1.54x "

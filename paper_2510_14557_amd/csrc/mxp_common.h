@@ -21,6 +21,10 @@ int wide_quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K
 int wide_dequantize_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
                            int64_t K, void* dst, int dst_dtype, int64_t ld_dst, hipStream_t stream);
 
+int prepack_fp6_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                       int n_seg, uint32_t res_mask, void* image, hipStream_t stream);
+int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int launch_status() {

@@ -1278,6 +1278,37 @@ extern "C" size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K)
   return align_up((size_t)mxp::image_geom(M, K, mxp::kTileBytesE4M3).total()) + align_up((size_t)mxp::image_geom(N, K, mxp::kTileBytesE4M3).total());
 }
 
+// Six-bit operands (Sec. 4.2): K segments per image and which of them hold the BM residual.  A+ x B: A = [p | r],
+// B = [p | p];  A x B+: A = [p | p], B = [p | r];  A+ x B+: A = [p | r | p | r], B = [p | p | r | r].
+namespace {
+struct Fp6Plan {
+  int n_seg;
+  uint32_t mask_a, mask_b;
+};
+Fp6Plan fp6_plan(int fmtA, int fmtB) {
+  const bool pa = fmtA == MXP_FMT_MXFP6P, pb = fmtB == MXP_FMT_MXFP6P;
+  if (pa && pb) return {4, 0xAu, 0xCu};
+  if (pa) return {2, 0x2u, 0x0u};
+  if (pb) return {2, 0x0u, 0x2u};
+  return {1, 0u, 0u};
+}
+bool is_fp6(int fmt) { return fmt == MXP_FMT_MXFP6 || fmt == MXP_FMT_MXFP6P; }
+}  // namespace
+
+extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB) {
+  if (M < 0 || N < 0 || K < 0) return 0;
+  if (is_fp6(fmtA) && is_fp6(fmtB)) {
+    const int n = fp6_plan(fmtA, fmtB).n_seg;
+    return align_up(mxp_image_bytes_fp6(M, K, n)) + align_up(mxp_image_bytes_fp6(N, K, n));
+  }
+  if (fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
+  const bool a4 = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P || fmtA == MXP_FMT_MXFP4PP;
+  const bool b4 = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P || fmtB == MXP_FMT_MXFP4PP;
+  if (!a4 || !b4) return 0;
+  if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
+  return mxp_gemm_workspace_bytes(M, N, K);
+}
+
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
                                   int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
@@ -1298,18 +1329,47 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
                         int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace mxp;
   const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
-  if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
-      (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP))
+  const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;
+  if (fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P) return MXP_ERR_UNSUPPORTED;
+  if (six || eight) {
+    if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
+    // both operands six-bit, or both plain MXFP8 (widths are not mixed)
+    if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !(fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8)) return MXP_ERR_UNSUPPORTED;
+  } else if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
+             (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP)) {
     return MXP_ERR_FORMAT;
+  }
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
-  if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA != MXP_FMT_MXFP4 && !A_idx) || (fmtB != MXP_FMT_MXFP4 && !B_idx) || !workspace)
+  const bool idx_a = fmtA != MXP_FMT_MXFP4 && !plain_wide_format(fmtA), idx_b = fmtB != MXP_FMT_MXFP4 && !plain_wide_format(fmtB);
+  if (!A_elems || !A_scales || !B_elems || !B_scales || (idx_a && !A_idx) || (idx_b && !B_idx) || !workspace)
     return MXP_ERR_NULL;
   if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(workspace) ||
       (A_idx && !aligned16(A_idx)) || (B_idx && !aligned16(B_idx)))
     return MXP_ERR_ALIGN;
+  if (six) {
+    const Fp6Plan plan = fp6_plan(fmtA, fmtB);
+    if (workspace_bytes < mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB)) return MXP_ERR_WORKSPACE;
+    uint8_t* wa6 = static_cast<uint8_t*>(workspace);
+    uint8_t* wb6 = wa6 + align_up(mxp_image_bytes_fp6(M, K, plan.n_seg));
+    rc = prepack_fp6_launch(A_elems, A_scales, A_idx, fmtA, M, K, plan.n_seg, plan.mask_a, wa6, s);
+    if (rc != MXP_OK) return rc;
+    rc = prepack_fp6_launch(B_elems, B_scales, B_idx, fmtB, N, K, plan.n_seg, plan.mask_b, wb6, s);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa6, MXP_IMAGE_E2M3, wb6, MXP_IMAGE_E2M3, M, N, image_geom(M, K).K_p * plan.n_seg, D, d_dtype, ldd, s);
+  }
+  if (eight) {
+    if (workspace_bytes < mxp_gemm_workspace_bytes_e4m3(M, N, K)) return MXP_ERR_WORKSPACE;
+    uint8_t* wa8 = static_cast<uint8_t*>(workspace);
+    uint8_t* wb8 = wa8 + align_up((size_t)image_geom(M, K, kTileBytesE4M3).total());
+    rc = prepack_fp8_launch(A_elems, A_scales, M, K, wa8, s);
+    if (rc != MXP_OK) return rc;
+    rc = prepack_fp8_launch(B_elems, B_scales, N, K, wb8, s);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa8, MXP_IMAGE_E4M3, wb8, MXP_IMAGE_E4M3, M, N, K, D, d_dtype, ldd, s);
+  }
   if (pp) {
     // an MXFP4++ operand needs the E4M3 image, and then both operands do (Sec. 4.3)
     if (workspace_bytes < mxp_gemm_workspace_bytes_e4m3(M, N, K)) return MXP_ERR_WORKSPACE;

@@ -519,6 +519,118 @@ dim3 grid_for(int64_t nq) {
   return dim3((unsigned)(want < cap ? want : cap));
 }
 
+// ---- operands of a product (MFMA-ready images) -----------------------------------------------------------------
+// MXFP6 elements are E2M3 numbers and a block's 24 bytes are already the six-bit operand string of one MFMA lane, so a
+// plain MXFP6 operand becomes an E2M3 image by moving bytes.  The BM of MXFP6+, 2^2 * 1.mmmmm = 4 + m/8, has six
+// significant bits; as Eq. 3 does for MXFP4+ it is taken as the sum of two numbers of the element type,
+// BM_H = 2^2 * 1.m4m3m2 (code s 11 m4m3m2) and BM_L = (m1m0) / 8 (the subnormal code s 00 0m1m0).  An operand is then
+// primary + residual, where the primary has BM_H in the BM's place and the residual is BM_L there and zero elsewhere,
+// and the product of two operands is one product over concatenated K segments:
+//   A+ x B  :  [A_p | A_r] x [B | B]^T           A+ x B+ :  [A_p | A_r | A_p | A_r] x [B_p | B_p | B_r | B_r]^T
+// The image written here has n_seg segments of K_p = K rounded up to 128 each; bit s of res_mask says that segment s
+// holds the residual.  A workgroup takes 32 rows x 8 K-blocks (4 k-tiles) like the four-bit prepack kernel, one thread
+// per block, and writes the 4 tiles of every segment in turn.
+template <bool PLUS>
+__global__ void __launch_bounds__(256) prepack_fp6_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                          const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                          int64_t kts, int n_seg, uint32_t res_mask,
+                                                          uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((kts + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const int64_t k_tiles = kts * n_seg;                         // k-tiles of the whole image
+  const uint32_t slot = (kb_in & 1u) * 32u + r_in;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  uint32_t d[6] = {0, 0, 0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x2* src = reinterpret_cast<const u32x2*>(elems + b * 24);
+    const u32x2 v0 = __builtin_nontemporal_load(src), v1 = __builtin_nontemporal_load(src + 1), v2 = __builtin_nontemporal_load(src + 2);
+    sbyte = scales[b];
+    if (sbyte != 0u) { d[0] = v0.x; d[1] = v0.y; d[2] = v1.x; d[3] = v1.y; d[4] = v2.x; d[5] = v2.y; }   // flushed: zeros
+    if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
+  }
+  // the BM's six bits: element i sits in 24-bit piece i / 4 (bytes 3 (i/4) .. +2) at bit 6 (i % 4)
+  uint32_t pr[6] = {d[0], d[1], d[2], d[3], d[4], d[5]}, rs[6] = {0, 0, 0, 0, 0, 0};
+  if (PLUS && bm < 32u) {
+    const uint32_t bit = 6u * bm, w = bit >> 5, sh = bit & 31u;            // first dword and shift; may straddle two
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+      lo = w == (uint32_t)j ? d[j] : lo;
+      hi = w + 1u == (uint32_t)j ? d[j] : hi;
+    }
+    const uint64_t both = ((uint64_t)hi << 32) | lo;
+    const uint32_t c = (uint32_t)(both >> sh) & 0x3Fu;                    // s mmmmm
+    const uint32_t code_h = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);        // s 11 m4m3m2
+    const uint32_t code_l = (c & 0x20u) | (c & 3u);                       // s 00 0m1m0
+    const uint64_t clear = ~((uint64_t)0x3Fu << sh);
+    const uint64_t ph = (both & clear) | ((uint64_t)code_h << sh), rl = (uint64_t)code_l << sh;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+      if (w == (uint32_t)j) { pr[j] = (uint32_t)ph; rs[j] = (uint32_t)rl; }
+      if (w + 1u == (uint32_t)j) { pr[j] = (uint32_t)(ph >> 32); rs[j] = (uint32_t)(rl >> 32); }
+    }
+  }
+  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytes;
+  const int64_t nt = kts - kt0 < 4 ? kts - kt0 : 4;            // tiles of this workgroup that exist (per segment)
+  const uint32_t nbytes = (uint32_t)nt * kTileBytes;
+  for (int sg = 0; sg < n_seg; ++sg) {
+    const bool res = (res_mask >> sg) & 1u;
+    if (sg > 0) __syncthreads();                                // the previous segment has left LDS
+    *reinterpret_cast<u32x4*>(tile + slot * 16u) = res ? u32x4{rs[0], rs[1], rs[2], rs[3]} : u32x4{pr[0], pr[1], pr[2], pr[3]};
+    *reinterpret_cast<u32x2*>(tile + 1024u + slot * 8u) = res ? u32x2{rs[4], rs[5]} : u32x2{pr[4], pr[5]};
+    tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sbyte;
+    __syncthreads();
+    const int64_t kt_img = sg * kts + kt0;
+    uint8_t* out = img_elems + (rt * k_tiles + kt_img) * (int64_t)kTileBytes;
+    for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+      MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+    if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt_img + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+  }
+}
+
+// Plain MXFP8 operand -> E4M3 image: the elements are the FP8 codes the MFMA takes and the scale byte is the block's
+// (e_max only enters the conversion).  Register layout of the FP8 operand: codes 0..15 of block (kb % 2) in register
+// half (kb % 2) of lane r, codes 16..31 in the same half of lane r + 32.
+__global__ void __launch_bounds__(256) prepack_fp8_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                          int64_t rows, int64_t nbk, int64_t k_tiles,
+                                                          uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE4M3];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  u32x4 c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
+  uint32_t sbyte = 127u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x4* src = reinterpret_cast<const u32x4*>(elems + b * 32);
+    sbyte = scales[b];
+    if (sbyte != 0u) { c0 = __builtin_nontemporal_load(src); c1 = __builtin_nontemporal_load(src + 1); }
+    else sbyte = 127u;                                        // flushed: zeros with a unit scale
+  }
+  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytesE4M3 + (kb_in & 1u) * 1024u;
+  *reinterpret_cast<u32x4*>(tile + r_in * 16u) = c0;
+  *reinterpret_cast<u32x4*>(tile + (32u + r_in) * 16u) = c1;
+  tile_scales[(kb_in >> 1) * 64u + (kb_in & 1u) * 32u + r_in] = (uint8_t)sbyte;
+  __syncthreads();
+  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
+  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytesE4M3;
+  const uint32_t nbytes = (uint32_t)nt * kTileBytesE4M3;
+  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+    MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
 }  // namespace
 
 namespace mxp {
@@ -561,4 +673,60 @@ int wide_dequantize_launch(const uint8_t* elems, const uint8_t* scales, const ui
   return launch_status();
 }
 
+int prepack_fp6_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                       int n_seg, uint32_t res_mask, void* image, hipStream_t stream) {
+  const ImageGeom seg = image_geom(rows, K), g = image_geom(rows, seg.K_p * n_seg);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  const int64_t n_wg = patch_grid((seg.k_tiles + 3) / 4, seg.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_wg);
+  if (fmt == MXP_FMT_MXFP6P)
+    hipLaunchKernelGGL((prepack_fp6_kernel<true>), grid, dim3(256), 0, stream, elems, scales, bm_idx, rows, K / kBlock, seg.k_tiles,
+                       n_seg, res_mask, ie, is);
+  else
+    hipLaunchKernelGGL((prepack_fp6_kernel<false>), grid, dim3(256), 0, stream, elems, scales, bm_idx, rows, K / kBlock, seg.k_tiles,
+                       n_seg, 0u, ie, is);
+  return launch_status();
+}
+
+int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream) {
+  const ImageGeom g = image_geom(rows, K, kTileBytesE4M3);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(prepack_fp8_kernel, dim3((unsigned)n_wg), dim3(256), 0, stream, elems, scales, rows, K / kBlock, g.k_tiles, ie,
+                     ie + g.elem_bytes);
+  return launch_status();
+}
+
 }  // namespace mxp
+
+extern "C" size_t mxp_image_bytes_fp6(int64_t rows, int64_t K, int n_seg) {
+  if (rows < 0 || K < 0 || n_seg < 1 || n_seg > 4) return 0;
+  return (size_t)mxp::image_geom(rows, mxp::image_geom(rows, K).K_p * n_seg).total();
+}
+
+extern "C" int mxp_prepack_fp6(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,
+                               int64_t K, int n_seg, unsigned res_mask, void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP6 && fmt != MXP_FMT_MXFP6P) return MXP_ERR_FORMAT;
+  if (rows < 0 || K < 0 || K % kBlock != 0 || n_seg < 1 || n_seg > 4 || (res_mask >> n_seg) != 0u) return MXP_ERR_SHAPE;
+  if (fmt == MXP_FMT_MXFP6 && res_mask != 0u) return MXP_ERR_SHAPE;     // a plain operand has no residual
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image || (fmt == MXP_FMT_MXFP6P && !bm_idx)) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
+  if (image_bytes < mxp_image_bytes_fp6(rows, K, n_seg)) return MXP_ERR_WORKSPACE;
+  return prepack_fp6_launch(elems, scales, bm_idx, fmt, rows, K, n_seg, res_mask, image, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mxp_prepack_fp8(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image,
+                               size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image)) return MXP_ERR_ALIGN;
+  if (image_bytes < (size_t)image_geom(rows, K, kTileBytesE4M3).total()) return MXP_ERR_WORKSPACE;
+  return prepack_fp8_launch(elems, scales, rows, K, image, static_cast<hipStream_t>(stream));
+}

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -64,6 +64,14 @@ def lib():
     L.mxp_image_bytes_e4m3.argtypes = [i64, i64]
     L.mxp_image_bytes_e4m3.restype = sz
     L.mxp_prepack_e4m3.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
+    L.mxp_gemm_workspace_bytes_fmt.argtypes = [i64, i64, i64, i32, i32]
+    L.mxp_gemm_workspace_bytes_fmt.restype = sz
+    L.mxp_image_bytes_fp6.argtypes = [i64, i64, i32]
+    L.mxp_image_bytes_fp6.restype = sz
+    L.mxp_prepack_fp6.argtypes = [vp, vp, vp, i32, i64, i64, i32, C.c_uint, vp, sz, vp]
+    L.mxp_prepack_fp6.restype = i32
+    L.mxp_prepack_fp8.argtypes = [vp, vp, i64, i64, vp, sz, vp]
+    L.mxp_prepack_fp8.restype = i32
     L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
     L.mxp_gemm_bf16a_workspace_bytes.restype = sz
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
@@ -230,6 +238,32 @@ def prepack_e4m3(q, fmt: int = MXFP4PP, out: torch.Tensor | None = None):
     return out
 
 
+def image_bytes_fp6(rows: int, K: int, n_seg: int = 1) -> int:
+    return int(lib().mxp_image_bytes_fp6(rows, K, n_seg))
+
+
+def prepack_fp6(q, fmt: int = MXFP6P, n_seg: int = 1, res_mask: int = 0, out: torch.Tensor | None = None):
+    """Canonical MXFP6 / MXFP6+ -> E2M3 image of n_seg K segments (each K rounded up to 128 wide); bit s of res_mask makes
+    segment s the BM residual instead of the primary operand."""
+    elems, scales, idx = q
+    rows, K = elems.shape[0], scales.shape[1] * 32
+    if out is None:
+        out = torch.empty(image_bytes_fp6(rows, K, n_seg), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_fp6(_p(elems), _p(scales), _p(idx), fmt, rows, K, n_seg, res_mask, _p(out), out.numel(), _stream()),
+           "mxp_prepack_fp6")
+    return out
+
+
+def prepack_fp8(q, out: torch.Tensor | None = None):
+    """Canonical plain MXFP8 -> E4M3 image."""
+    elems, scales = q[0], q[1]
+    rows, K = elems.shape[0], scales.shape[1] * 32
+    if out is None:
+        out = torch.empty(image_bytes_e4m3(rows, K), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_fp8(_p(elems), _p(scales), rows, K, _p(out), out.numel(), _stream()), "mxp_prepack_fp8")
+    return out
+
+
 def prepack_e2m1(q, out: torch.Tensor | None = None):
     """Plain MXFP4 operand (elems, scales[, ignored]) -> E2M1 image for the B side of the product."""
     elems, scales = q[0], q[1]
@@ -241,9 +275,7 @@ def prepack_e2m1(q, out: torch.Tensor | None = None):
 
 
 def gemm_workspace_bytes(M: int, N: int, K: int, fmt_a: int = MXFP4P, fmt_b: int = MXFP4P) -> int:
-    if MXFP4PP in (fmt_a, fmt_b):
-        return int(lib().mxp_gemm_workspace_bytes_e4m3(M, N, K))
-    return int(lib().mxp_gemm_workspace_bytes(M, N, K))
+    return int(lib().mxp_gemm_workspace_bytes_fmt(M, N, K, fmt_a, fmt_b))
 
 
 def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None,
@@ -251,9 +283,9 @@ def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torc
     """D[M,N] = deq(A)[M,K] @ deq(B)[N,K]^T from canonical operands."""
     ae, as_, ai = qa
     be, bs, bi = qb
-    M, K = ae.shape[0], ae.shape[1] * 2
+    M, K = ae.shape[0], as_.shape[1] * 32
     N = be.shape[0]
-    if be.shape[1] * 2 != K:
+    if bs.shape[1] * 32 != K:
         raise MxpError("K mismatch between operands")
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=ae.device)

@@ -117,6 +117,26 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_gemm_bf16a(4, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, mxp.IMAGE_E4M3, p, mxp.F32, 64, p, 1 << 20, None) == -8
     assert L.mxp_gemm_bf16a(4, 64, 64, p, mxp.BF16, 64, mxp.MXFP4PP, p, mxp.IMAGE_E4M3, p, mxp.F32, 64, p,
                             mxp.gemm_bf16a_workspace_bytes(4, 64), None) == -6
+    # six-bit operand images: segments 1..4, a residual only for MXFP6+, sized by the segment count
+    assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP6P, 64, 64, 5, 0, p, 1 << 24, None) == -2
+    assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP6P, 64, 64, 2, 0b100, p, 1 << 24, None) == -2
+    assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP6, 64, 64, 2, 0b10, p, 1 << 24, None) == -2
+    assert L.mxp_prepack_fp6(p, p, None, mxp.MXFP6P, 64, 64, 2, 0b10, p, 1 << 24, None) == -1
+    assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP4P, 64, 64, 1, 0, p, 1 << 24, None) == -5
+    assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP6P, 64, 64, 2, 0b10, p, mxp.image_bytes_fp6(64, 64, 1), None) == -6
+    assert mxp.image_bytes_fp6(64, 64, 2) == mxp.image_bytes(64, 256) and mxp.image_bytes_fp6(64, 64, 0) == 0
+    assert L.mxp_prepack_fp8(p, p, 64, 64, p, 16, None) == -6
+    assert L.mxp_prepack_fp8(p, None, 64, 64, p, 1 << 24, None) == -1
+    # products: MXFP6 / MXFP6+ pair with each other, MXFP8 with MXFP8, MXFP8+ with nothing
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP6P) == 2 * mxp.image_bytes_fp6(64, 64, 4)
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4) == 0
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4)
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, p, 1 << 24, None) == -8
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP8P, p, p, p, mxp.MXFP8, p, mxp.F32, 64, p, 1 << 24, None) == -8
+    assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -1
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1024, None) == -6
+    assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8, p, p, None, mxp.MXFP8, p, mxp.F32, 64, p, 1024, None) == -6
+    assert L.mxp_gemm(64, 64, 64, p, p, p, 7, p, p, p, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -5
     # empty problems are fine and launch nothing
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
     assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0

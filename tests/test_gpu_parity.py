@@ -682,6 +682,115 @@ def test_wide_round_trip_full_size(fmt):
     assert (back[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64) == ref).all()
 
 
+# ---- products of six- and eight-bit operands (Sec. 4.2 formats) -------------------------------------------------------
+# MXFP6(+): E2M3 images; the MXFP6+ BM enters as BM_H + BM_L over K segments, every product is exact in the MFMA, so the
+# bound of the main path applies.  MXFP8: E4M3 images, the FP8 dot product's bound (see check_gemm_e4m3 below).
+FP6_PLAN = {("mxfp6", "mxfp6"): (1, 0, 0), ("mxfp6p", "mxfp6"): (2, 0b10, 0), ("mxfp6", "mxfp6p"): (2, 0, 0b10),
+            ("mxfp6p", "mxfp6p"): (4, 0b1010, 0b1100)}
+
+
+def test_gemm_mxfp6_hand_case():
+    """One block per operand; 5.625 = 5.5 + 0.125 and 4.375 = 4.0 + 0.375 need the BM residuals of both operands."""
+    a = np.zeros((1, 32), np.float32)
+    b = np.zeros((1, 32), np.float32)
+    a[0, 7], a[0, 8] = 5.625, 1.25
+    b[0, 7], b[0, 8], b[0, 9] = -4.375, 3.0, 0.875
+    W = oracle.wide
+    qa, qb = W.quantize(a, W.MXFP6P), W.quantize(b, W.MXFP6P)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP6P, q_dev(qb), mxp.MXFP6P)
+    assert D.cpu().numpy()[0, 0] == 5.625 * -4.375 + 1.25 * 3.0
+    D6 = mxp.gemm(q_dev(W.quantize(a, W.MXFP6)), mxp.MXFP6, q_dev(W.quantize(b, W.MXFP6)), mxp.MXFP6)
+    assert D6.cpu().numpy()[0, 0] == 5.5 * -4.5 + 3.75
+    # BM positions differ: the BM of A meets an ordinary element of B and the other way round
+    b2 = np.zeros((1, 32), np.float32)
+    b2[0, 8], b2[0, 7] = -4.375, 0.875
+    D2 = mxp.gemm(q_dev(qa), mxp.MXFP6P, q_dev(W.quantize(b2, W.MXFP6P)), mxp.MXFP6P)
+    assert D2.cpu().numpy()[0, 0] == 5.625 * 0.875 + 1.25 * -4.375
+
+
+@pytest.mark.parametrize("fa,fb", list(FP6_PLAN))
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (100, 200, 416), (257, 300, 1024), (64, 1000, 2080), (300, 520, 2048)])
+def test_gemm_mxfp6_shapes(fa, fb, M, N, K):
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = W.quantize(a, WIDE[fa][1]), W.quantize(w, WIDE[fb][1])
+    ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
+    D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0])
+    check_gemm(D, ref, S, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
+    # the same through images built ahead of time
+    n_seg, mask_a, mask_b = FP6_PLAN[(fa, fb)]
+    ia = mxp.prepack_fp6(q_dev(qa), WIDE[fa][0], n_seg, mask_a)
+    ib = mxp.prepack_fp6(q_dev(qb), WIDE[fb][0], n_seg, mask_b)
+    assert ia.numel() == mxp.image_bytes_fp6(M, K, n_seg)
+    Kp = (K + 127) // 128 * 128
+    assert torch.equal(D, mxp.gemm_prepacked(M, N, n_seg * Kp, ia, ib))
+    Db = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+def test_gemm_mxfp6_special_blocks():
+    """Flushed, NaN and extreme-scale blocks; every BM mantissa."""
+    W = oracle.wide
+    x = special_tensor(rows=100, K=256, seed=9, bf16=False)
+    x[3, 32:64] = 4.0 + np.arange(32) / 8.0                      # BM 7.875 at the end, the other BM mantissas as elements
+    for r in range(32):
+        x[40 + r, 0:32] = 0.01
+        x[40 + r, r] = -(4.0 + r / 8.0)                          # every BM mantissa at every position
+    a, b = x[:40], x[40:100]
+    for fa, fb in (("mxfp6p", "mxfp6p"), ("mxfp6p", "mxfp6")):
+        qa, qb = W.quantize(a, WIDE[fa][1]), W.quantize(b, WIDE[fb][1])
+        ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
+        D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0]).double().cpu().numpy()
+        nan = np.isnan(ref)
+        assert nan.any() and (np.isnan(D) == nan).all()
+        ok = ~nan & np.isfinite(ref) & (np.abs(ref) < 1e37) & (S < 1e37)
+        assert (np.abs(D - ref)[ok] <= 2.0 ** -16 * S[ok] + 1.2e-38).all()
+
+
+def test_gemm_mxfp6p_full_size_sampled():
+    """Benchmark shape, MXFP6+ activations x MXFP6 weights, operands converted on the GPU."""
+    W = oracle.wide
+    M, N, K = 4096, 14336, 4096
+    a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
+    w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
+    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP6P), mxp.quantize(to_dev(w), mxp.MXFP6)
+    D = mxp.gemm(qa, mxp.MXFP6P, qw, mxp.MXFP6)
+    rng = np.random.default_rng(6)
+    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
+    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
+    sel_a, inv_a = np.unique(rm, return_inverse=True)
+    sel_w, inv_w = np.unique(rn, return_inverse=True)
+    qa_o, qw_o = W.quantize(a[sel_a], W.MXFP6P), W.quantize(w[sel_w], W.MXFP6)
+    for g, o in zip(qa, qa_o):
+        assert (g.cpu().numpy()[sel_a] == o).all()
+    for g, o in list(zip(qw, qw_o))[:2]:
+        assert (g.cpu().numpy()[sel_w] == o).all()
+    da, dw = W.dequantize(qa_o, W.MXFP6P), W.dequantize(qw_o, W.MXFP6)
+    ref = np.einsum("tk,tk->t", da[inv_a], dw[inv_w])
+    S = np.einsum("tk,tk->t", np.abs(da[inv_a]), np.abs(dw[inv_w]))
+    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
+    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (257, 300, 1024), (64, 1000, 2080), (300, 520, 2048)])
+def test_gemm_mxfp8_shapes(M, N, K):
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = W.quantize(a, W.MXFP8), W.quantize(w, W.MXFP8)
+    ref, S = W.gemm(qa, W.MXFP8, qb, W.MXFP8)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(qb), mxp.MXFP8)
+    check_gemm_e4m3(D, ref, S, "mxfp8 %dx%dx%d" % (M, N, K))
+    ia, ib = mxp.prepack_fp8(q_dev(qa)), mxp.prepack_fp8(q_dev(qb))
+    assert torch.equal(D, mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3))
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm(q_dev(W.quantize(a, W.MXFP8P)), mxp.MXFP8P, q_dev(qb), mxp.MXFP8)     # no MXFP8+ product
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(W.quantize(w, W.MXFP6)), mxp.MXFP6)       # widths are not mixed
+
+
 # ---- the MXFP4++ product (Sec. 4.3) through E4M3 images ------------------------------------------------------------
 # In an E4M3 image the codes of a block span 0.125 ... 240, so the 64 products one MFMA sums span up to 2^22.  The FP8
 # dot product of the instruction aligns them to the largest one and keeps about 13 bits below it (measured: errors up
