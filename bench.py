@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_decode_large", "dequantize", "copy"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_w4a16", "gemm_decode_large", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -139,6 +139,10 @@ def main():
         qa6, qw6 = mxp.quantize(A, mxp.MXFP6P), mxp.quantize(W6, mxp.MXFP6)
         del W6
         ws6 = torch.empty(mxp.gemm_workspace_bytes(M, N, K, mxp.MXFP6P, mxp.MXFP6), dtype=torch.uint8, device=dev)
+    if args.only == "gemm_w4a16":      # conversion-based product at the benchmark shape (tiled kernel)
+        W16 = to_dev(w_bits)
+        qw16 = mxp.quantize(W16, mxp.MXFP4P)
+        del W16
     if args.only == "gemm_decode_large":   # 8 rows against a 70B-sized layer, random codes
         Nl, Kl = 28672, 8192
         gen = torch.Generator(device=dev)
@@ -154,6 +158,8 @@ def main():
     def step_only():
         if args.only == "gemm_e4m3":
             mxp.gemm_prepacked(M, N, K, img_a8, img_w8, out=D, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+        elif args.only == "gemm_w4a16":
+            mxp.gemm_w4a16(A, qw16, mxp.MXFP4P, out=D)
         elif args.only == "gemm_fp6p":
             mxp.gemm(qa6, mxp.MXFP6P, qw6, mxp.MXFP6, out=D, workspace=ws6)
         elif args.only == "gemm_decode_large":
@@ -286,6 +292,21 @@ def main():
         fp6_ms[name] = timed_gemm(ia6, mxp.IMAGE_E2M3, iw6, mxp.IMAGE_E2M3, k=n_seg * Kp)
         del ia6, iw6
     del qa6, W6
+    # the conversion-based product at this shape (Sec. 5; weight-only quantization): bf16 A as it is x canonical MXFP4+ W
+    W16 = to_dev(w_bits)
+    qw16 = mxp.quantize(W16, mxp.MXFP4P)
+    del W16
+    for _ in range(20):
+        mxp.gemm_w4a16(A, qw16, mxp.MXFP4P, out=D)
+    torch.cuda.synchronize()
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev2[0].record()
+    for _ in range(20):
+        mxp.gemm_w4a16(A, qw16, mxp.MXFP4P, out=D)
+    ev2[1].record()
+    torch.cuda.synchronize()
+    w4a16_ms = ev2[0].elapsed_time(ev2[1]) / 20
+    del qw16
 
     # Decode configuration (8 x 4096 activations, 4096 x 4096 weights): activations quantized on the fly, prepacked
     # weights, 20 calls back to back.  Bound by reading the weight image once; at this size launch latency dominates.
@@ -463,6 +484,7 @@ def main():
         "gemm_plain_mxfp4_back_to_back_TFLOPs": flops / (gemm_a4w4_ms * 1e-3) / 1e12,
         "gemm_mxfp4pp_back_to_back_TFLOPs": flops / (gemm_pp8_ms * 1e-3) / 1e12,
         "quantize_image_mxfp4pp_GBps": qimg_pp8_bytes / (qimg_pp8_ms * 1e-3) / 1e9,
+        "gemm_w4a16_bf16_x_mxfp4p_TFLOPs": flops / (w4a16_ms * 1e-3) / 1e12,
         "gemm_mxfp6p_x_mxfp6_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6"] * 1e-3) / 1e12,
         "gemm_mxfp6p_x_mxfp6p_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6p"] * 1e-3) / 1e12,
         "gemm_time_vs_plain_mxfp4": {"mxfp4p_x_mxfp4p": gemm_pp_ms / gemm_a4w4_ms, "mxfp4p_x_mxfp4": gemm_w4_ms / gemm_a4w4_ms,

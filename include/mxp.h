@@ -216,8 +216,9 @@ int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_
  * quantized, blocks are de-converted to a wider type inside the kernel): D[M][N] = A[M][K] x deq(W)^T with A left as
  * it is (MXP_BF16, row stride lda; MXP_F32 returns MXP_ERR_UNSUPPORTED) and W[N][K] in canonical MXFP4, MXFP4+ or
  * MXFP4++ storage, de-converted by Eq. 2 to bf16 (exact) and multiplied on the bf16 MFMA with fp32 accumulation.
- * Built for few activation rows, where reading the 4-bit weights once is the whole cost: M <= 64; larger M returns
- * MXP_ERR_UNSUPPORTED.  D is MXP_F32 or MXP_BF16 with row stride ldd.  No workspace. */
+ * M <= 64 (up to 128 in two passes): a kernel bound by reading the 4-bit weights once.  Larger M (prefill with
+ * weight-only quantization): 256 x 256 output tiles, the weights de-converted once per tile and 64-element step of K
+ * on their way into LDS.  D is MXP_F32 or MXP_BF16 with row stride ldd.  No workspace. */
 int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
                    const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW,
                    void* D, int d_dtype, int64_t ldd, void* stream);

@@ -12,6 +12,7 @@ namespace {
 
 using namespace mxp;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
@@ -236,6 +237,216 @@ int dispatch_skinny(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
   return launch_status();
 }
 
+// ---- many activation rows (prefill with weight-only quantization): 256 x 256 output tiles ---------------------------
+// A workgroup of 2 x 4 wavefronts (two per SIMD, so that one's conversions and LDS traffic run under the other's MFMAs)
+// computes 256 rows of A x 256 rows of W; each wavefront 4 x 2 MFMA tiles of 32 x 32.  K is walked in steps of 64 (two
+// MX blocks: the two lane halves of an operand take one each, as above).  Both operands of a step lie in LDS as bf16,
+// 256 rows x 128 bytes each, double-buffered: the activations are copied, the weights are de-converted (Eq. 2) on the
+// way in -- thread (n, b) of the workgroup owns block b of weight row n in every step, one block per thread and step,
+// so each block is converted once per workgroup.  A row's eight 16-byte chunks are stored at chunk ^ ((row / 2) % 8):
+// the 16 lanes that read the same chunk of 16 consecutive rows then hit 16 different 16-byte bank groups.  Global loads run one step
+// (activations) or two (weight codes) ahead of the MFMAs that use them and are written to the other LDS stage behind the
+// MFMAs of the step before; one barrier per step.
+constexpr int kTOperand = 256 * 128;                         // one operand of one step: 256 rows x 64 bf16
+constexpr int kTStage = 2 * kTOperand;                       // activations, then weights
+constexpr int kTiledLds = 2 * kTStage;
+#ifndef MXP_W4A16_NJ
+#define MXP_W4A16_NJ 2
+#endif
+constexpr int kTiledNJ = MXP_W4A16_NJ;                       // column tiles per wavefront: 2 -> 2 x 4 wavefronts, 4 -> 2 x 2
+constexpr int kTiledThreads = 64 * 2 * (8 / kTiledNJ);
+
+template <int MODE, bool OUT_BF16>
+__global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                    const u32x4* __restrict__ w_el, const uint8_t* __restrict__ w_sc,
+                                                                    const uint8_t* __restrict__ w_ix, int64_t nbk, int64_t M, int64_t N,
+                                                                    void* __restrict__ Dv, int64_t ldd, int tiles_n) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int NJ = kTiledNJ, WAVES_N = 8 / NJ, PA = 2048 / kTiledThreads, PW = 512 / kTiledThreads;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N, h = lane >> 5, nl = lane & 31;
+  const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * 256, n0 = (int64_t)(blockIdx.x % tiles_n) * 256;
+  const int64_t nks = (nbk + 1) / 2;
+
+  v16f acc[4][NJ];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // activations: chunk kc = tid % 8 of rows tid / 8 + 64 u; the swizzle term is the same for the four rows
+  const int a_row = tid >> 3, a_kc = tid & 7;
+  const uint32_t a_off = (uint32_t)(a_row * 128 + ((a_kc ^ ((a_row >> 1) & 7)) << 4));
+  constexpr int A_STEP = kTiledThreads / 8;                  // rows between a thread's chunks (a multiple of 16: same swizzle)
+  const uint16_t* a_ptr[PA];
+  bool a_ok[PA];
+#pragma unroll
+  for (int u = 0; u < PA; ++u) {
+    a_ok[u] = m0 + a_row + A_STEP * u < M;
+    a_ptr[u] = A + (a_ok[u] ? (m0 + a_row + A_STEP * u) * lda : 0) + a_kc * 8;
+  }
+  // weights: blocks tid * PW + x of the step's 512 (row = block / 2, b = block % 2), the same in every step
+  bool w_ok[PW];
+  int64_t w_base[PW];
+  int w_bb[PW];
+  uint32_t w_off[PW][4];
+#pragma unroll
+  for (int x = 0; x < PW; ++x) {
+    const int c = tid * PW + x, w_row = c >> 1;
+    w_bb[x] = c & 1;
+    w_ok[x] = n0 + w_row < N;
+    w_base[x] = w_ok[x] ? (n0 + w_row) * nbk + w_bb[x] : 0;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) w_off[x][s4] = (uint32_t)(kTOperand + w_row * 128 + (((4 * w_bb[x] + s4) ^ ((w_row >> 1) & 7)) << 4));
+  }
+
+  struct ABlock {
+    u32x4 v[PA];
+  };
+  auto load_a = [&](int64_t ks) {
+    ABlock r;
+    const bool k_ok = 2 * ks + (a_kc >> 2) < nbk;            // the chunk's block exists (K % 32 == 0: chunks are whole)
+#pragma unroll
+    for (int u = 0; u < PA; ++u) {
+      r.v[u] = (u32x4){0, 0, 0, 0};
+      if (a_ok[u] && k_ok) r.v[u] = *reinterpret_cast<const u32x4*>(a_ptr[u] + ks * 64);
+    }
+    return r;
+  };
+  auto store_a = [&](int buf, const ABlock& r) {
+#pragma unroll
+    for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + a_off + u * (A_STEP * 128)) = r.v[u];
+  };
+  struct WBlock {
+    u32x4 q[PW];
+    uint32_t sb[PW], ib[PW];
+  };
+  auto load_w = [&](int64_t ks) {
+    WBlock r;
+#pragma unroll
+    for (int x = 0; x < PW; ++x) {
+      r.q[x] = (u32x4){0, 0, 0, 0};
+      r.sb[x] = 0;                                           // blocks past N or K: scale byte 0, an all-zero block
+      r.ib[x] = 0;
+      if (w_ok[x] && 2 * ks + w_bb[x] < nbk) {
+        const int64_t b = w_base[x] + 2 * ks;
+        r.q[x] = w_el[b];
+        r.sb[x] = w_sc[b];
+        if (MODE >= 1) r.ib[x] = w_ix[b];
+      }
+    }
+    return r;
+  };
+  auto store_w = [&](int buf, const WBlock& r) {
+#pragma unroll
+    for (int x = 0; x < PW; ++x) {
+      uint32_t w[16];
+      decode_block_bf16<MODE>(r.q[x], r.sb[x], r.ib[x], w);
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+        *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + w_off[x][s4]) = (u32x4){w[4 * s4], w[4 * s4 + 1], w[4 * s4 + 2], w[4 * s4 + 3]};
+    }
+  };
+
+  // operand reads: lane (nl, h) of tile row / column r takes chunk 4 h + s4
+  uint32_t rd_a[4], rd_w[NJ];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = wm * 128 + 32 * i + nl;
+    rd_a[i] = (uint32_t)(row * 128) | (uint32_t)(((row >> 1) & 7) << 4);        // low bits: the row's swizzle term
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int n = wn * (32 * NJ) + 32 * j + nl;
+    rd_w[j] = (uint32_t)(kTOperand + n * 128) | (uint32_t)(((n >> 1) & 7) << 4);
+  }
+
+  ABlock a1 = load_a(0);
+  WBlock w1 = load_w(0);
+  store_a(0, a1);
+  store_w(0, w1);
+  w1 = load_w(1);
+  __syncthreads();
+  for (int64_t ks = 0; ks < nks; ++ks) {
+    const bool more = ks + 1 < nks;
+    const uint8_t* st = lds_raw + (ks & 1) * kTStage;
+    const int nb = (int)((ks + 1) & 1);
+    if (more) a1 = load_a(ks + 1);
+    const WBlock w2 = load_w(ks + 2);
+    // the MFMAs of one eighth of K (k-slots 8 s4 .. 8 s4 + 7 of both blocks)
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const uint32_t kc = (uint32_t)((4 * h + s4) << 4);
+      v8bf wv[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(st + (rd_w[j] ^ kc));
+        const uint32_t v4[4] = {v.x, v.y, v.z, v.w};
+        wv[j] = as_v8bf(v4);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(st + (rd_a[i] ^ kc));
+        const uint32_t v4[4] = {v.x, v.y, v.z, v.w};
+        const v8bf a8 = as_v8bf(v4);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, wv[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    // the next step's operands go into the other stage.  (Measured alternatives that were slower: stores placed between
+    // the MFMA slices -- the branches of the de-conversion cut the MFMA sequence --, activations loaded two steps ahead,
+    // the two wavefronts of a SIMD running half a step out of phase, 2 x 2 wavefronts of 4 x 4 tiles.)
+    if (more) {
+      store_a(nb, a1);
+      store_w(nb, w1);
+    }
+    w1 = w2;
+    __syncthreads();
+  }
+  // accumulator register r of lane l: D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32] of the 32 x 32 tile
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int64_t col = n0 + wn * (32 * NJ) + 32 * j + nl;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = m0 + wm * 128 + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (row < M && col < N) {
+          if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne_bits(acc[i][j][r]);
+          else static_cast<float*>(Dv)[row * ldd + col] = acc[i][j][r];
+        }
+      }
+    }
+}
+
+template <int MODE>
+int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws,
+                   const uint8_t* wi, void* D, int d_dtype, int64_t ldd, hipStream_t s) {
+  const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256;
+  if (tm * tn > 2147483647LL || tn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)(tm * tn));
+  const int64_t nbk = K / kBlock;
+  static_assert(kTiledLds <= 160 * 1024, "LDS");
+  if (d_dtype == MXP_BF16) {
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_tiled_kernel<MODE, true>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
+    (void)once_b;
+    hipLaunchKernelGGL((w4a16_tiled_kernel<MODE, true>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A), lda,
+                       reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd, (int)tn);
+  } else {
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_tiled_kernel<MODE, false>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
+    (void)once_f;
+    hipLaunchKernelGGL((w4a16_tiled_kernel<MODE, false>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A), lda,
+                       reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd, (int)tn);
+  }
+  return launch_status();
+}
+
 template <bool BF16>
 __global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -269,7 +480,25 @@ extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, in
   if (a_dtype != MXP_BF16) return MXP_ERR_UNSUPPORTED;      // the activations are multiplied as bf16
   if (!aligned16(A) || !aligned16(W_elems) || !aligned16(W_scales) || (W_idx && !aligned16(W_idx)) || (lda * 2) % 16 != 0)
     return MXP_ERR_ALIGN;
-  if (M > 64) return MXP_ERR_UNSUPPORTED;
+  if (M > 64 && M <= 128) {
+    // two passes of the few-row kernel read the weights twice and still beat one row of 256 x 256 tiles here
+    const int64_t esz = d_dtype == MXP_BF16 ? 2 : 4;
+    for (int64_t r0 = 0; r0 < M; r0 += 64) {
+      const int64_t mr = M - r0 < 64 ? M - r0 : 64;
+      const void* Ar = static_cast<const uint16_t*>(A) + r0 * lda;
+      void* Dr = static_cast<uint8_t*>(D) + r0 * ldd * esz;
+      const int rc = fmtW == MXP_FMT_MXFP4PP  ? dispatch_skinny<2>(mr, N, K, Ar, lda, W_elems, W_scales, W_idx, Dr, d_dtype, ldd, s)
+                     : fmtW == MXP_FMT_MXFP4P ? dispatch_skinny<1>(mr, N, K, Ar, lda, W_elems, W_scales, W_idx, Dr, d_dtype, ldd, s)
+                                              : dispatch_skinny<0>(mr, N, K, Ar, lda, W_elems, W_scales, W_idx, Dr, d_dtype, ldd, s);
+      if (rc != MXP_OK) return rc;
+    }
+    return MXP_OK;
+  }
+  if (M > 64) {
+    if (fmtW == MXP_FMT_MXFP4PP) return dispatch_tiled<2>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+    if (fmtW == MXP_FMT_MXFP4P) return dispatch_tiled<1>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+    return dispatch_tiled<0>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
+  }
   if (fmtW == MXP_FMT_MXFP4PP) return dispatch_skinny<2>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
   if (fmtW == MXP_FMT_MXFP4P) return dispatch_skinny<1>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
   return dispatch_skinny<0>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);

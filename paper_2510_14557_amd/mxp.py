@@ -337,7 +337,7 @@ def gemm_decode_bf16a(a: torch.Tensor, fmt_a: int, qw, fmt_w: int = MXFP4P, out_
 
 
 def gemm_w4a16(a: torch.Tensor, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
-    """Un-quantized bf16 activations x canonical 4-bit weights, de-converted inside the kernel (M <= 64)."""
+    """Un-quantized bf16 activations x canonical 4-bit weights, de-converted inside the kernel (few-row kernel for M <= 64, 256 x 256 tiles above)."""
     _dev2d(a)
     we, ws, wi = qw
     M, K = a.shape

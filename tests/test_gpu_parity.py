@@ -449,9 +449,67 @@ def test_gemm_w4a16_few_rows(M, N, K, w_fmt):
     mxp.gemm_w4a16(wide[:, :K], q_dev(qw), FMT[w_fmt][0], out=out[:, :N])
     if M > 1:
         assert torch.equal(out[:, :N], D) and (out[:, N:] == -3.0).all()
-    if M == 8:
-        with pytest.raises(mxp.MxpError):
-            mxp.gemm_w4a16(torch.zeros((65, K), dtype=torch.bfloat16, device="cuda"), q_dev(qw), FMT[w_fmt][0])
+
+
+@pytest.mark.parametrize("w_fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
+@pytest.mark.parametrize("M,N,K", [(65, 40, 64), (100, 200, 416), (257, 300, 1024), (300, 520, 2048), (512, 1100, 640),
+                                   (129, 70, 4160)])
+def test_gemm_w4a16_many_rows(M, N, K, w_fmt):
+    """The tiled form of the conversion-based product (more than 64 activation rows): ragged tiles in M and N, K that
+    ends inside a step (odd number of blocks) and inside a group of 8 blocks."""
+    a = synth.activations(M, K, config_id=1, tensor_id=62)
+    w = synth.weights(N, K, config_id=1, tensor_id=63, t3_frac=0.001)
+    qw = oracle.quantize(w, FMT[w_fmt][1])
+    ref, S = oracle.gemm_w4a16(a, qw, FMT[w_fmt][1])
+    D = mxp.gemm_w4a16(to_dev(a), q_dev(qw), FMT[w_fmt][0])
+    check_gemm(D, ref, S, "w4a16 tiled %s %dx%dx%d" % (w_fmt, M, N, K))
+    Db = mxp.gemm_w4a16(to_dev(a), q_dev(qw), FMT[w_fmt][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+    wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = to_dev(a)
+    out = torch.full((M, N + 8), -3.0, device="cuda")
+    mxp.gemm_w4a16(wide[:, :K], q_dev(qw), FMT[w_fmt][0], out=out[:, :N])
+    assert torch.equal(out[:, :N], D) and (out[:, N:] == -3.0).all()
+    # the first 64 rows through the few-row kernel: same operands, another summation order
+    D64 = mxp.gemm_w4a16(to_dev(a)[:64], q_dev(qw), FMT[w_fmt][0])
+    check_gemm(D64, ref[:64], S[:64], "w4a16 few rows of the same")
+
+
+def test_gemm_w4a16_special_blocks():
+    """Flushed, NaN, extreme-scale weight blocks and every delta through the tiled kernel."""
+    w = mxpp_tensor(rows=96, K=512, bf16=False)
+    a = synth.activations(70, 512, config_id=1, tensor_id=64)
+    for w_fmt in ("mxfp4p", "mxfp4pp"):
+        qw = oracle.quantize(w, FMT[w_fmt][1])
+        ref, S = oracle.gemm_w4a16(a, qw, FMT[w_fmt][1])
+        D = mxp.gemm_w4a16(to_dev(a), q_dev(qw), FMT[w_fmt][0]).double().cpu().numpy()
+        nan = np.isnan(ref)
+        assert nan.any() and (np.isnan(D) == nan).all()
+        ok = ~nan & np.isfinite(ref) & (np.abs(ref) < 1e37) & (S < 1e37)
+        assert (np.abs(D - ref)[ok] <= 2.0 ** -16 * S[ok] + 1.2e-38).all()
+
+
+def test_gemm_w4a16_full_size_sampled():
+    """Prefill MLP shape, bf16 activations x MXFP4+ weights de-converted in the kernel; sampled outputs."""
+    M, N, K = 4096, 14336, 4096
+    a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
+    w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
+    qw = mxp.quantize(to_dev(w), mxp.MXFP4P)
+    D = mxp.gemm_w4a16(to_dev(a), qw, mxp.MXFP4P)
+    rng = np.random.default_rng(8)
+    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
+    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
+    sel_w, inv_w = np.unique(rn, return_inverse=True)
+    qw_o = oracle.quantize(w[sel_w], oracle.MXFP4P)
+    for g, o in zip(qw, qw_o):
+        assert (g.cpu().numpy()[sel_w] == o).all()
+    a64 = synth.bf16_bits_to_f32(a[rm]).astype(np.float64)
+    w64 = oracle.dequantize(qw_o, oracle.MXFP4P)[inv_w]
+    ref = np.einsum("tk,tk->t", a64, w64)
+    S = np.einsum("tk,tk->t", np.abs(a64), np.abs(w64))
+    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
+    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
 
 
 def test_gemm_strided_output_and_k0():
