@@ -243,11 +243,13 @@ int dispatch_skinny(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
 // MX blocks: the two lane halves of an operand take one each, as above).  Both operands of a step lie in LDS as bf16,
 // 256 rows x 128 bytes each, double-buffered: the activations are copied, the weights are de-converted (Eq. 2) on the
 // way in -- thread (n, b) of the workgroup owns block b of weight row n in every step, one block per thread and step,
-// so each block is converted once per workgroup.  A row's eight 16-byte chunks are stored at chunk ^ ((row / 2) % 8):
-// the 16 lanes that read the same chunk of 16 consecutive rows then hit 16 different 16-byte bank groups.  Global loads run one step
+// so each block is converted once per workgroup.  Rows are 144 bytes apart in LDS (128 + 16 of padding): the 16 lanes that
+// read the same chunk of 16 consecutive rows then hit 16 different 16-byte bank groups (9 r mod 16), and the chunk is an
+// immediate offset of the read.  Global loads run one step
 // (activations) or two (weight codes) ahead of the MFMAs that use them and are written to the other LDS stage behind the
 // MFMAs of the step before; one barrier per step.
-constexpr int kTOperand = 256 * 128;                         // one operand of one step: 256 rows x 64 bf16
+constexpr int kTRow = 144;                                   // bytes per operand row in LDS: 64 bf16 + 16 B of padding
+constexpr int kTOperand = 256 * kTRow;                       // one operand of one step: 256 rows x 64 bf16
 constexpr int kTStage = 2 * kTOperand;                       // activations, then weights
 constexpr int kTiledLds = 2 * kTStage;
 #ifndef MXP_W4A16_NJ
@@ -279,7 +281,7 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
 
   // activations: chunk kc = tid % 8 of rows tid / 8 + 64 u; the swizzle term is the same for the four rows
   const int a_row = tid >> 3, a_kc = tid & 7;
-  const uint32_t a_off = (uint32_t)(a_row * 128 + ((a_kc ^ ((a_row >> 1) & 7)) << 4));
+  const uint32_t a_off = (uint32_t)(a_row * kTRow + (a_kc << 4));
   constexpr int A_STEP = kTiledThreads / 8;                  // rows between a thread's chunks (a multiple of 16: same swizzle)
   const uint16_t* a_ptr[PA];
   bool a_ok[PA];
@@ -300,7 +302,7 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     w_ok[x] = n0 + w_row < N;
     w_base[x] = w_ok[x] ? (n0 + w_row) * nbk + w_bb[x] : 0;
 #pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) w_off[x][s4] = (uint32_t)(kTOperand + w_row * 128 + (((4 * w_bb[x] + s4) ^ ((w_row >> 1) & 7)) << 4));
+    for (int s4 = 0; s4 < 4; ++s4) w_off[x][s4] = (uint32_t)(kTOperand + w_row * kTRow + ((4 * w_bb[x] + s4) << 4));
   }
 
   struct ABlock {
@@ -318,7 +320,7 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
   };
   auto store_a = [&](int buf, const ABlock& r) {
 #pragma unroll
-    for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + a_off + u * (A_STEP * 128)) = r.v[u];
+    for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + a_off + u * (A_STEP * kTRow)) = r.v[u];
   };
   struct WBlock {
     u32x4 q[PW];
@@ -351,17 +353,17 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     }
   };
 
-  // operand reads: lane (nl, h) of tile row / column r takes chunk 4 h + s4
+  // operand reads: lane (nl, h) of tile row / column r takes chunk 4 h + s4 (an immediate offset from these bases)
   uint32_t rd_a[4], rd_w[NJ];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = wm * 128 + 32 * i + nl;
-    rd_a[i] = (uint32_t)(row * 128) | (uint32_t)(((row >> 1) & 7) << 4);        // low bits: the row's swizzle term
+    rd_a[i] = (uint32_t)(row * kTRow + 64 * h);
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int n = wn * (32 * NJ) + 32 * j + nl;
-    rd_w[j] = (uint32_t)(kTOperand + n * 128) | (uint32_t)(((n >> 1) & 7) << 4);
+    rd_w[j] = (uint32_t)(kTOperand + n * kTRow + 64 * h);
   }
 
   ABlock a1 = load_a(0);
@@ -379,17 +381,16 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     // the MFMAs of one eighth of K (k-slots 8 s4 .. 8 s4 + 7 of both blocks)
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
-      const uint32_t kc = (uint32_t)((4 * h + s4) << 4);
       v8bf wv[NJ];
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(st + (rd_w[j] ^ kc));
+        const u32x4 v = *reinterpret_cast<const u32x4*>(st + rd_w[j] + 16 * s4);
         const uint32_t v4[4] = {v.x, v.y, v.z, v.w};
         wv[j] = as_v8bf(v4);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(st + (rd_a[i] ^ kc));
+        const u32x4 v = *reinterpret_cast<const u32x4*>(st + rd_a[i] + 16 * s4);
         const uint32_t v4[4] = {v.x, v.y, v.z, v.w};
         const v8bf a8 = as_v8bf(v4);
 #pragma unroll
@@ -407,17 +408,28 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     __syncthreads();
   }
   // accumulator register r of lane l: D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32] of the 32 x 32 tile
+  const bool whole = m0 + 256 <= M && n0 + 256 <= N;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int64_t col = n0 + wn * (32 * NJ) + 32 * j + nl;
+      const int64_t row0 = m0 + wm * 128 + 32 * i + 4 * h;
+      if (whole) {                                           // tile inside the matrix (uniform): no per-element tests
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = m0 + wm * 128 + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (row < M && col < N) {
-          if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne_bits(acc[i][j][r]);
-          else static_cast<float*>(Dv)[row * ldd + col] = acc[i][j][r];
+        for (int r = 0; r < 16; ++r) {
+          const int64_t o = (row0 + 8 * (r >> 2) + (r & 3)) * ldd + col;
+          if (OUT_BF16) static_cast<uint16_t*>(Dv)[o] = (uint16_t)f32_to_bf16_rne_bits(acc[i][j][r]);
+          else static_cast<float*>(Dv)[o] = acc[i][j][r];
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t row = row0 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) {
+            if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne_bits(acc[i][j][r]);
+            else static_cast<float*>(Dv)[row * ldd + col] = acc[i][j][r];
+          }
         }
       }
     }
