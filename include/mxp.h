@@ -179,7 +179,9 @@ int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, 
 size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when either format is MXP_FMT_MXFP4PP */
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
- * (see mxp_prepack_fp6 for the cost), MXFP8 x MXFP8; 0 for a pair it does not take */
+ * (see mxp_prepack_fp6 for the cost), plain MXFP6 with MXFP4 or MXFP4+ on the other side (six-bit activations x
+ * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product), MXFP8 x MXFP8; 0 for a pair it does not
+ * take */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,

@@ -1302,6 +1302,10 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
     return align_up(mxp_image_bytes_fp6(M, K, n)) + align_up(mxp_image_bytes_fp6(N, K, n));
   }
   if (fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
+  {
+    const bool fa = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, fb = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
+    if ((fmtA == MXP_FMT_MXFP6 && fb) || (fa && fmtB == MXP_FMT_MXFP6)) return mxp_gemm_workspace_bytes(M, N, K);
+  }
   const bool a4 = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P || fmtA == MXP_FMT_MXFP4PP;
   const bool b4 = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P || fmtB == MXP_FMT_MXFP4PP;
   if (!a4 || !b4) return 0;
@@ -1333,8 +1337,11 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   if (fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P) return MXP_ERR_UNSUPPORTED;
   if (six || eight) {
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
-    // both operands six-bit, or both plain MXFP8 (widths are not mixed)
-    if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !(fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8)) return MXP_ERR_UNSUPPORTED;
+    // both operands six-bit, or both plain MXFP8, or plain MXFP6 with MXFP4 / MXFP4+ (one segment: the same E2M3 / E2M1
+    // images as ever; an MXFP6+ operand would need the four-bit one laid out twice)
+    const bool four_a = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, four_b = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
+    const bool mixed64 = (fmtA == MXP_FMT_MXFP6 && four_b) || (four_a && fmtB == MXP_FMT_MXFP6);
+    if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !(fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) && !mixed64) return MXP_ERR_UNSUPPORTED;
   } else if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
              (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP)) {
     return MXP_ERR_FORMAT;
@@ -1349,6 +1356,21 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(workspace) ||
       (A_idx && !aligned16(A_idx)) || (B_idx && !aligned16(B_idx)))
     return MXP_ERR_ALIGN;
+  if (six && !(is_fp6(fmtA) && is_fp6(fmtB))) {
+    // plain MXFP6 with a four-bit operand: one E2M3 image each (a plain MXFP4 B stays in four-bit codes)
+    if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;
+    uint8_t* wa = static_cast<uint8_t*>(workspace);
+    uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());
+    rc = is_fp6(fmtA) ? prepack_fp6_launch(A_elems, A_scales, nullptr, fmtA, M, K, 1, 0u, wa, s)
+                      : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+    if (rc != MXP_OK) return rc;
+    const bool b4 = fmtB == MXP_FMT_MXFP4;
+    rc = is_fp6(fmtB) ? prepack_fp6_launch(B_elems, B_scales, nullptr, fmtB, N, K, 1, 0u, wb, s)
+         : b4         ? prepack_e2m1_launch(B_elems, B_scales, N, K, wb, s)
+                      : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa, MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
+  }
   if (six) {
     const Fp6Plan plan = fp6_plan(fmtA, fmtB);
     if (workspace_bytes < mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB)) return MXP_ERR_WORKSPACE;

@@ -787,6 +787,29 @@ def test_gemm_mxfp6_shapes(fa, fb, M, N, K):
     assert torch.equal(Db, D.to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("M,N,K", [(33, 100, 96), (257, 300, 1024), (64, 1000, 2080), (300, 520, 2048)])
+def test_gemm_mxfp6_activations_with_four_bit_weights(M, N, K):
+    """Plain MXFP6 on one side, MXFP4 / MXFP4+ on the other: one E2M3 (or E2M1) image each, exact products."""
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa6 = W.quantize(a, W.MXFP6)
+    a64 = W.dequantize(qa6, W.MXFP6)
+    for w_fmt in ("mxfp4p", "mxfp4"):
+        qw = oracle.quantize(w, FMT[w_fmt][1])
+        w64 = oracle.dequantize(qw, FMT[w_fmt][1]).astype(np.float64)
+        ref, S = a64 @ w64.T, np.abs(a64) @ np.abs(w64).T
+        D = mxp.gemm(q_dev(qa6), mxp.MXFP6, q_dev(qw), FMT[w_fmt][0])
+        check_gemm(D, ref, S, "mxfp6 x %s %dx%dx%d" % (w_fmt, M, N, K))
+    # the other way round: four-bit activations, six-bit weights
+    qa4, qw6 = oracle.quantize(a, oracle.MXFP4P), W.quantize(w, W.MXFP6)
+    a4, w6 = oracle.dequantize(qa4, oracle.MXFP4P).astype(np.float64), W.dequantize(qw6, W.MXFP6)
+    D = mxp.gemm(q_dev(qa4), mxp.MXFP4P, q_dev(qw6), mxp.MXFP6)
+    check_gemm(D, a4 @ w6.T, np.abs(a4) @ np.abs(w6).T, "mxfp4+ x mxfp6 %dx%dx%d" % (M, N, K))
+    with pytest.raises(mxp.MxpError):
+        mxp.gemm(q_dev(W.quantize(a, W.MXFP6P)), mxp.MXFP6P, q_dev(oracle.quantize(w, oracle.MXFP4P)), mxp.MXFP4P)
+
+
 def test_gemm_mxfp6_special_blocks():
     """Flushed, NaN and extreme-scale blocks; every BM mantissa."""
     W = oracle.wide
