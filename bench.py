@@ -307,6 +307,22 @@ def main():
     torch.cuda.synchronize()
     w4a16_ms = ev2[0].elapsed_time(ev2[1]) / 20
     del qw16
+    # MXFP8+ x MXFP8+ (Sec. 4.2 formats): no block-scaled MFMA element holds an E4M7 BM; de-converted in the kernel, bf16 MFMA
+    W8p = to_dev(w_bits)
+    qa8p, qw8p = mxp.quantize(A, mxp.MXFP8P), mxp.quantize(W8p, mxp.MXFP8P)
+    del W8p
+    ws8p = torch.empty(16, dtype=torch.uint8, device=dev)
+    for _ in range(5):
+        mxp.gemm(qa8p, mxp.MXFP8P, qw8p, mxp.MXFP8P, out=D, workspace=ws8p)
+    torch.cuda.synchronize()
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev2[0].record()
+    for _ in range(10):
+        mxp.gemm(qa8p, mxp.MXFP8P, qw8p, mxp.MXFP8P, out=D, workspace=ws8p)
+    ev2[1].record()
+    torch.cuda.synchronize()
+    fp8p_ms = ev2[0].elapsed_time(ev2[1]) / 10
+    del qa8p, qw8p
 
     # Decode configuration (8 x 4096 activations, 4096 x 4096 weights): activations quantized on the fly, prepacked
     # weights, 20 calls back to back.  Bound by reading the weight image once; at this size launch latency dominates.
@@ -485,6 +501,7 @@ def main():
         "gemm_mxfp4pp_back_to_back_TFLOPs": flops / (gemm_pp8_ms * 1e-3) / 1e12,
         "quantize_image_mxfp4pp_GBps": qimg_pp8_bytes / (qimg_pp8_ms * 1e-3) / 1e9,
         "gemm_w4a16_bf16_x_mxfp4p_TFLOPs": flops / (w4a16_ms * 1e-3) / 1e12,
+        "gemm_mxfp8p_x_mxfp8p_TFLOPs": flops / (fp8p_ms * 1e-3) / 1e12,
         "gemm_mxfp6p_x_mxfp6_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6"] * 1e-3) / 1e12,
         "gemm_mxfp6p_x_mxfp6p_useful_TFLOPs": flops / (fp6_ms["mxfp6p_x_mxfp6p"] * 1e-3) / 1e12,
         "gemm_time_vs_plain_mxfp4": {"mxfp4p_x_mxfp4p": gemm_pp_ms / gemm_a4w4_ms, "mxfp4p_x_mxfp4": gemm_w4_ms / gemm_a4w4_ms,

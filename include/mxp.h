@@ -152,8 +152,11 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
  * (mxp_gemm_workspace_bytes_fmt).  image: mxp_image_bytes_fp6(rows, K, n_seg) bytes.
  * mxp_prepack_fp8: a plain MXFP8 operand as an MXP_IMAGE_E4M3 image (mxp_image_bytes_e4m3 bytes; the codes are the
  * FP8 numbers the MFMA takes; a NaN code S.1111.111 in the input makes the products it meets NaN).  The FP8 product
- * keeps about 13 bits below the largest product of 64 consecutive k (see MXP_IMAGE_E4M3).  MXFP8+ has no product here:
- * its BM (eight significant bits, up to 1.992 * 2^8 > 448) needs three E4M3 terms per operand. */
+ * keeps about 13 bits below the largest product of 64 consecutive k (see MXP_IMAGE_E4M3).  The BM of MXFP8+ (eight
+ * significant bits, up to 1.992 * 2^8 > 448) would need three E4M3 terms per operand; mxp_gemm forms products with an
+ * MXFP8+ operand (the other one MXFP8 or MXFP8+) on the bf16 MFMA from operands de-converted inside the kernel
+ * instead: every value is a bf16 number, so the products are exact; no image, no workspace, about a quarter of the
+ * FP8 rate.  (Values below the bf16 normal range, scale bytes under 16, are rounded to bf16 first.) */
 size_t mxp_image_bytes_fp6(int64_t rows, int64_t K, int n_seg);
 int mxp_prepack_fp6(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                     int n_seg, unsigned res_mask, void* image, size_t image_bytes, void* stream);
@@ -181,7 +184,7 @@ size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
  * (see mxp_prepack_fp6 for the cost), plain MXFP6 with MXFP4 or MXFP4+ on the other side (six-bit activations x
  * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product), MXFP8 x MXFP8; 0 for a pair it does not
- * take */
+ * take and for pairs with MXFP8+, which need none */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
@@ -220,7 +223,8 @@ int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_
  * MXFP4++ storage, de-converted by Eq. 2 to bf16 (exact) and multiplied on the bf16 MFMA with fp32 accumulation.
  * M <= 64 (up to 128 in two passes): a kernel bound by reading the 4-bit weights once.  Larger M (prefill with
  * weight-only quantization): 256 x 256 output tiles, the weights de-converted once per tile and 64-element step of K
- * on their way into LDS.  D is MXP_F32 or MXP_BF16 with row stride ldd.  No workspace. */
+ * on their way into LDS.  The tiled kernel also takes MXFP6(+) and MXFP8(+) weights (any M).  D is MXP_F32 or MXP_BF16
+ * with row stride ldd.  No workspace. */
 int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
                    const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW,
                    void* D, int d_dtype, int64_t ldd, void* stream);

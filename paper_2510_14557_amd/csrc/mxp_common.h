@@ -25,6 +25,11 @@ int prepack_fp6_launch(const uint8_t* elems, const uint8_t* scales, const uint8_
                        int n_seg, uint32_t res_mask, void* image, hipStream_t stream);
 int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
 
+// both operands eight-bit (MXFP8 / MXFP8+): the bf16-MFMA product of the de-converted operands (mxp_w4a16.hip)
+int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
+                           const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
+                           hipStream_t s);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline int launch_status() {

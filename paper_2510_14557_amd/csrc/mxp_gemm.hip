@@ -1334,7 +1334,24 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   using namespace mxp;
   const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
   const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;
-  if (fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P) return MXP_ERR_UNSUPPORTED;
+  const bool eight_plus = fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P;
+  if (eight_plus) {
+    // an E4M7 BM fits no block-scaled MFMA element: the product of the de-converted operands on the bf16 MFMA (exact
+    // products: every value is a bf16 number), both operands eight-bit; no workspace
+    const bool a8 = fmtA == MXP_FMT_MXFP8 || fmtA == MXP_FMT_MXFP8P, b8 = fmtB == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8P;
+    if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
+    if (!a8 || !b8) return MXP_ERR_UNSUPPORTED;
+    int rc8 = check_gemm(M, N, K, D, d_dtype, ldd);
+    if (rc8 != MXP_OK || M == 0 || N == 0) return rc8;
+    hipStream_t s8 = static_cast<hipStream_t>(stream);
+    if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s8);
+    if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA == MXP_FMT_MXFP8P && !A_idx) || (fmtB == MXP_FMT_MXFP8P && !B_idx))
+      return MXP_ERR_NULL;
+    if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || (A_idx && !aligned16(A_idx)) ||
+        (B_idx && !aligned16(B_idx)))
+      return MXP_ERR_ALIGN;
+    return deconv_gemm_fp8_launch(M, N, K, A_elems, A_scales, A_idx, fmtA, B_elems, B_scales, B_idx, fmtB, D, d_dtype, ldd, s8);
+  }
   if (six || eight) {
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
     // both operands six-bit, or both plain MXFP8, or plain MXFP6 with MXFP4 / MXFP4+ (one segment: the same E2M3 / E2M1

@@ -237,36 +237,89 @@ int dispatch_skinny(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
   return launch_status();
 }
 
-// ---- many activation rows (prefill with weight-only quantization): 256 x 256 output tiles ---------------------------
+// ---- tiled product on de-converted operands: 256 x 256 output tiles ------------------------------------------------
+// Many activation rows (prefill with weight-only quantization), weights of any block format; and the product of two
+// quantized operands whose BM fits no block-scaled MFMA element (MXFP8+): every format's values are bf16 numbers, so
+// the product of the de-converted operands on the bf16 MFMA is the exact product (fp32 accumulation).
 // A workgroup of 2 x 4 wavefronts (two per SIMD, so that one's conversions and LDS traffic run under the other's MFMAs)
 // computes 256 rows of A x 256 rows of W; each wavefront 4 x 2 MFMA tiles of 32 x 32.  K is walked in steps of 64 (two
 // MX blocks: the two lane halves of an operand take one each, as above).  Both operands of a step lie in LDS as bf16,
-// 256 rows x 128 bytes each, double-buffered: the activations are copied, the weights are de-converted (Eq. 2) on the
-// way in -- thread (n, b) of the workgroup owns block b of weight row n in every step, one block per thread and step,
-// so each block is converted once per workgroup.  Rows are 144 bytes apart in LDS (128 + 16 of padding): the 16 lanes that
+// 256 rows each, double-buffered: un-quantized activations are copied, quantized operands are de-converted (Eq. 2) on
+// the way in -- thread (n, b) of the workgroup owns block b of row n in every step, one block per thread and step, so
+// each block is converted once per workgroup.  Rows are 144 bytes apart in LDS (128 + 16 of padding): the 16 lanes that
 // read the same chunk of 16 consecutive rows then hit 16 different 16-byte bank groups (9 r mod 16), and the chunk is an
-// immediate offset of the read.  Global loads run one step
-// (activations) or two (weight codes) ahead of the MFMAs that use them and are written to the other LDS stage behind the
-// MFMAs of the step before; one barrier per step.
+// immediate offset of the read.  Global loads run one step (un-quantized rows) or two (codes) ahead of the MFMAs that
+// use them and are written to the other LDS stage behind the MFMAs of the step before; one barrier per step.
 constexpr int kTRow = 144;                                   // bytes per operand row in LDS: 64 bf16 + 16 B of padding
 constexpr int kTOperand = 256 * kTRow;                       // one operand of one step: 256 rows x 64 bf16
 constexpr int kTStage = 2 * kTOperand;                       // activations, then weights
 constexpr int kTiledLds = 2 * kTStage;
-#ifndef MXP_W4A16_NJ
-#define MXP_W4A16_NJ 2
-#endif
-constexpr int kTiledNJ = MXP_W4A16_NJ;                       // column tiles per wavefront: 2 -> 2 x 4 wavefronts, 4 -> 2 x 2
-constexpr int kTiledThreads = 64 * 2 * (8 / kTiledNJ);
+constexpr int kTiledThreads = 512;
 
-template <int MODE, bool OUT_BF16>
-__global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                                    const u32x4* __restrict__ w_el, const uint8_t* __restrict__ w_sc,
-                                                                    const uint8_t* __restrict__ w_ix, int64_t nbk, int64_t M, int64_t N,
-                                                                    void* __restrict__ Dv, int64_t ldd, int tiles_n) {
+// operand kinds
+constexpr int kRawBf16 = 0, kFp4 = 1 /* + MODE: 1, 2, 3 */, kFp6 = 4, kFp8 = 6;   // six- / eight-bit: plain or + by a flag
+
+struct QBlock {                                              // one block of codes with its scale and index bytes
+  uint32_t raw[8];
+  uint32_t sb, ib;
+};
+
+template <int KIND>
+__device__ __forceinline__ QBlock q_load(bool ok, const uint8_t* el, const uint8_t* sc, const uint8_t* ix, int64_t b, bool has_ix) {
+  QBlock r;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r.raw[j] = 0;
+  r.sb = 0;                                                  // blocks past the matrix: scale byte 0, an all-zero block
+  r.ib = 0;
+  if (ok) {
+    if (KIND == kFp6) {
+      const u32x2* p = reinterpret_cast<const u32x2*>(el + b * 24);
+      const u32x2 d0 = p[0], d1 = p[1], d2 = p[2];
+      r.raw[0] = d0.x; r.raw[1] = d0.y; r.raw[2] = d1.x; r.raw[3] = d1.y; r.raw[4] = d2.x; r.raw[5] = d2.y;
+    } else if (KIND == kFp8) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(el + b * 32);
+      const u32x4 d0 = p[0], d1 = p[1];
+      r.raw[0] = d0.x; r.raw[1] = d0.y; r.raw[2] = d0.z; r.raw[3] = d0.w;
+      r.raw[4] = d1.x; r.raw[5] = d1.y; r.raw[6] = d1.z; r.raw[7] = d1.w;
+    } else {
+      const u32x4 d0 = *reinterpret_cast<const u32x4*>(el + b * 16);
+      r.raw[0] = d0.x; r.raw[1] = d0.y; r.raw[2] = d0.z; r.raw[3] = d0.w;
+    }
+    r.sb = sc[b];
+    if (has_ix) r.ib = ix[b];
+  }
+  return r;
+}
+
+// de-convert the block and store its 64 bytes of bf16 at `dst` (the block's place in its LDS row)
+template <int KIND>
+__device__ __forceinline__ void q_store(const QBlock& r, bool plus, uint8_t* dst) {
+  uint32_t w[16];
+  if (KIND == kFp6 || KIND == kFp8) {
+    constexpr int BITS = KIND == kFp6 ? 6 : 8;
+    const bool general = __builtin_amdgcn_ballot_w64(!wide_block_is_plain<BITS>(r.raw, r.sb, plus ? (r.ib & 31u) : 64u)) != 0;
+    decode_wide_block_bf16<BITS>(r.raw, r.sb, r.ib, plus, general, w);
+  } else {
+    decode_block_bf16<(KIND >= 1 && KIND <= 3 ? KIND - 1 : 0)>((u32x4){r.raw[0], r.raw[1], r.raw[2], r.raw[3]}, r.sb, r.ib, w);
+  }
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4)
+    *reinterpret_cast<u32x4*>(dst + 16 * s4) = (u32x4){w[4 * s4], w[4 * s4 + 1], w[4 * s4 + 2], w[4 * s4 + 3]};
+}
+
+struct QOperand {                                            // a quantized operand: codes, scale bytes, index bytes
+  const uint8_t *el, *sc, *ix;
+  int plus;                                                  // six- / eight-bit kinds: the + form
+};
+
+template <int AK, int WK, bool OUT_BF16>
+__global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint16_t* __restrict__ A, int64_t lda, QOperand qa,
+                                                                     QOperand qw, int64_t nbk, int64_t M, int64_t N,
+                                                                     void* __restrict__ Dv, int64_t ldd, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int NJ = kTiledNJ, WAVES_N = 8 / NJ, PA = 2048 / kTiledThreads, PW = 512 / kTiledThreads;
+  constexpr int NJ = 2, WAVES_N = 4, PA = 2048 / kTiledThreads;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N, h = lane >> 5, nl = lane & 31;
   const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * 256, n0 = (int64_t)(blockIdx.x % tiles_n) * 256;
   const int64_t nks = (nbk + 1) / 2;
@@ -279,31 +332,24 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // activations: chunk kc = tid % 8 of rows tid / 8 + 64 u; the swizzle term is the same for the four rows
+  // un-quantized activations: chunk kc = tid % 8 of rows tid / 8 + 64 u
   const int a_row = tid >> 3, a_kc = tid & 7;
   const uint32_t a_off = (uint32_t)(a_row * kTRow + (a_kc << 4));
-  constexpr int A_STEP = kTiledThreads / 8;                  // rows between a thread's chunks (a multiple of 16: same swizzle)
+  constexpr int A_STEP = kTiledThreads / 8;
   const uint16_t* a_ptr[PA];
   bool a_ok[PA];
 #pragma unroll
   for (int u = 0; u < PA; ++u) {
-    a_ok[u] = m0 + a_row + A_STEP * u < M;
+    a_ok[u] = AK == kRawBf16 && m0 + a_row + A_STEP * u < M;
     a_ptr[u] = A + (a_ok[u] ? (m0 + a_row + A_STEP * u) * lda : 0) + a_kc * 8;
   }
-  // weights: blocks tid * PW + x of the step's 512 (row = block / 2, b = block % 2), the same in every step
-  bool w_ok[PW];
-  int64_t w_base[PW];
-  int w_bb[PW];
-  uint32_t w_off[PW][4];
-#pragma unroll
-  for (int x = 0; x < PW; ++x) {
-    const int c = tid * PW + x, w_row = c >> 1;
-    w_bb[x] = c & 1;
-    w_ok[x] = n0 + w_row < N;
-    w_base[x] = w_ok[x] ? (n0 + w_row) * nbk + w_bb[x] : 0;
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) w_off[x][s4] = (uint32_t)(kTOperand + w_row * kTRow + ((4 * w_bb[x] + s4) << 4));
-  }
+  // quantized operands: block b = tid % 2 of row tid / 2 in every step
+  const int q_row = tid >> 1, q_b = tid & 1;
+  const uint32_t q_off = (uint32_t)(q_row * kTRow + 64 * q_b);
+  const bool qa_ok = AK != kRawBf16 && m0 + q_row < M, qw_ok = n0 + q_row < N;
+  const int64_t qa_base = qa_ok ? (m0 + q_row) * nbk + q_b : 0, qw_base = qw_ok ? (n0 + q_row) * nbk + q_b : 0;
+  const bool a_has_ix = AK == 2 || AK == 3 || ((AK == kFp6 || AK == kFp8) && qa.plus);
+  const bool w_has_ix = WK == 2 || WK == 3 || ((WK == kFp6 || WK == kFp8) && qw.plus);
 
   struct ABlock {
     u32x4 v[PA];
@@ -322,63 +368,41 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
 #pragma unroll
     for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + a_off + u * (A_STEP * kTRow)) = r.v[u];
   };
-  struct WBlock {
-    u32x4 q[PW];
-    uint32_t sb[PW], ib[PW];
-  };
-  auto load_w = [&](int64_t ks) {
-    WBlock r;
-#pragma unroll
-    for (int x = 0; x < PW; ++x) {
-      r.q[x] = (u32x4){0, 0, 0, 0};
-      r.sb[x] = 0;                                           // blocks past N or K: scale byte 0, an all-zero block
-      r.ib[x] = 0;
-      if (w_ok[x] && 2 * ks + w_bb[x] < nbk) {
-        const int64_t b = w_base[x] + 2 * ks;
-        r.q[x] = w_el[b];
-        r.sb[x] = w_sc[b];
-        if (MODE >= 1) r.ib[x] = w_ix[b];
-      }
-    }
-    return r;
-  };
-  auto store_w = [&](int buf, const WBlock& r) {
-#pragma unroll
-    for (int x = 0; x < PW; ++x) {
-      uint32_t w[16];
-      decode_block_bf16<MODE>(r.q[x], r.sb[x], r.ib[x], w);
-#pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
-        *reinterpret_cast<u32x4*>(lds_raw + buf * kTStage + w_off[x][s4]) = (u32x4){w[4 * s4], w[4 * s4 + 1], w[4 * s4 + 2], w[4 * s4 + 3]};
-    }
-  };
+  auto load_qa = [&](int64_t ks) { return q_load<AK>(qa_ok && 2 * ks + q_b < nbk, qa.el, qa.sc, qa.ix, qa_base + 2 * ks, a_has_ix); };
+  auto load_qw = [&](int64_t ks) { return q_load<WK>(qw_ok && 2 * ks + q_b < nbk, qw.el, qw.sc, qw.ix, qw_base + 2 * ks, w_has_ix); };
 
   // operand reads: lane (nl, h) of tile row / column r takes chunk 4 h + s4 (an immediate offset from these bases)
   uint32_t rd_a[4], rd_w[NJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = wm * 128 + 32 * i + nl;
-    rd_a[i] = (uint32_t)(row * kTRow + 64 * h);
-  }
+  for (int i = 0; i < 4; ++i) rd_a[i] = (uint32_t)((wm * 128 + 32 * i + nl) * kTRow + 64 * h);
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int n = wn * (32 * NJ) + 32 * j + nl;
-    rd_w[j] = (uint32_t)(kTOperand + n * kTRow + 64 * h);
-  }
+  for (int j = 0; j < NJ; ++j) rd_w[j] = (uint32_t)(kTOperand + (wn * (32 * NJ) + 32 * j + nl) * kTRow + 64 * h);
 
-  ABlock a1 = load_a(0);
-  WBlock w1 = load_w(0);
-  store_a(0, a1);
-  store_w(0, w1);
-  w1 = load_w(1);
+  ABlock a1;
+  QBlock qa1, qa2, qw1, qw2;
+  if (AK == kRawBf16) {
+    a1 = load_a(0);
+    store_a(0, a1);
+  } else {
+    qa1 = load_qa(0);
+    q_store<AK>(qa1, qa.plus != 0, lds_raw + q_off);
+    qa1 = load_qa(1);
+  }
+  qw1 = load_qw(0);
+  q_store<WK>(qw1, qw.plus != 0, lds_raw + kTOperand + q_off);
+  qw1 = load_qw(1);
   __syncthreads();
   for (int64_t ks = 0; ks < nks; ++ks) {
     const bool more = ks + 1 < nks;
     const uint8_t* st = lds_raw + (ks & 1) * kTStage;
-    const int nb = (int)((ks + 1) & 1);
-    if (more) a1 = load_a(ks + 1);
-    const WBlock w2 = load_w(ks + 2);
-    // the MFMAs of one eighth of K (k-slots 8 s4 .. 8 s4 + 7 of both blocks)
+    uint8_t* nxt = lds_raw + ((ks + 1) & 1) * kTStage;
+    if (AK == kRawBf16) {
+      if (more) a1 = load_a(ks + 1);
+    } else {
+      qa2 = load_qa(ks + 2);
+    }
+    qw2 = load_qw(ks + 2);
+    // the MFMAs of one eighth of K per slice (k-slots 8 s4 .. 8 s4 + 7 of both blocks)
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
       v8bf wv[NJ];
@@ -401,10 +425,12 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     // the MFMA slices -- the branches of the de-conversion cut the MFMA sequence --, activations loaded two steps ahead,
     // the two wavefronts of a SIMD running half a step out of phase, 2 x 2 wavefronts of 4 x 4 tiles.)
     if (more) {
-      store_a(nb, a1);
-      store_w(nb, w1);
+      if (AK == kRawBf16) store_a((int)((ks + 1) & 1), a1);
+      else q_store<AK>(qa1, qa.plus != 0, nxt + q_off);
+      q_store<WK>(qw1, qw.plus != 0, nxt + kTOperand + q_off);
     }
-    w1 = w2;
+    if (AK != kRawBf16) qa1 = qa2;
+    qw1 = qw2;
     __syncthreads();
   }
   // accumulator register r of lane l: D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32] of the 32 x 32 tile
@@ -435,28 +461,53 @@ __global__ void __launch_bounds__(kTiledThreads) w4a16_tiled_kernel(const uint16
     }
 }
 
-template <int MODE>
-int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws,
-                   const uint8_t* wi, void* D, int d_dtype, int64_t ldd, hipStream_t s) {
+template <int AK, int WK>
+int launch_deconv(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const QOperand& qa, const QOperand& qw, void* D,
+                  int d_dtype, int64_t ldd, hipStream_t s) {
   const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256;
   if (tm * tn > 2147483647LL || tn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)(tm * tn));
   const int64_t nbk = K / kBlock;
   static_assert(kTiledLds <= 160 * 1024, "LDS");
   if (d_dtype == MXP_BF16) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_tiled_kernel<MODE, true>),
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, true>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
     (void)once_b;
-    hipLaunchKernelGGL((w4a16_tiled_kernel<MODE, true>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A), lda,
-                       reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd, (int)tn);
+    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, true>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
+                       lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_tiled_kernel<MODE, false>),
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, false>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
     (void)once_f;
-    hipLaunchKernelGGL((w4a16_tiled_kernel<MODE, false>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A), lda,
-                       reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd, (int)tn);
+    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, false>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
+                       lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   }
   return launch_status();
+}
+
+// kind of the tiled kernel's operand loader for a block format, and whether it is the + form
+inline int kind_of(int fmt) {
+  switch (fmt) {
+    case MXP_FMT_MXFP4: return 1;
+    case MXP_FMT_MXFP4P: return 2;
+    case MXP_FMT_MXFP4PP: return 3;
+    case MXP_FMT_MXFP6: case MXP_FMT_MXFP6P: return kFp6;
+    default: return kFp8;
+  }
+}
+inline int plus_of(int fmt) { return fmt == MXP_FMT_MXFP6P || fmt == MXP_FMT_MXFP8P; }
+
+// un-quantized bf16 activations x weights of any block format
+int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws,
+                   const uint8_t* wi, int fmtW, void* D, int d_dtype, int64_t ldd, hipStream_t s) {
+  const QOperand none = {nullptr, nullptr, nullptr, 0}, qw = {we, ws, wi, plus_of(fmtW)};
+  switch (kind_of(fmtW)) {
+    case 1: return launch_deconv<kRawBf16, 1>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+    case 2: return launch_deconv<kRawBf16, 2>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+    case 3: return launch_deconv<kRawBf16, 3>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+    case kFp6: return launch_deconv<kRawBf16, kFp6>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+    default: return launch_deconv<kRawBf16, kFp8>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+  }
 }
 
 template <bool BF16>
@@ -470,11 +521,22 @@ __global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
 
 }  // namespace
 
+namespace mxp {
+// Both operands quantized, eight-bit (MXFP8 / MXFP8+ in any combination): the product of the de-converted operands.
+int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
+                           const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
+                           hipStream_t s) {
+  const QOperand qa = {ae, as, ai, plus_of(fmtA)}, qb = {be, bs, bi, plus_of(fmtB)};
+  return launch_deconv<kFp8, kFp8>(M, N, K, nullptr, 0, qa, qb, D, d_dtype, ldd, s);
+}
+}  // namespace mxp
+
 extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
                               const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, void* D,
                               int d_dtype, int64_t ldd, void* stream) {
   using namespace mxp;
-  if (fmtW != MXP_FMT_MXFP4 && fmtW != MXP_FMT_MXFP4P && fmtW != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  if (fmtW < MXP_FMT_MXFP4 || fmtW > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
+  const bool wide_w = fmtW >= MXP_FMT_MXFP6;
   if (a_dtype != MXP_BF16 && a_dtype != MXP_F32) return MXP_ERR_DTYPE;
   if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
@@ -487,11 +549,13 @@ extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, in
     else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
     return launch_status();
   }
-  if (!A || !W_elems || !W_scales || (fmtW != MXP_FMT_MXFP4 && !W_idx)) return MXP_ERR_NULL;
+  if (!A || !W_elems || !W_scales || (fmtW != MXP_FMT_MXFP4 && !plain_wide_format(fmtW) && !W_idx)) return MXP_ERR_NULL;
   if (lda < K) return MXP_ERR_SHAPE;
   if (a_dtype != MXP_BF16) return MXP_ERR_UNSUPPORTED;      // the activations are multiplied as bf16
   if (!aligned16(A) || !aligned16(W_elems) || !aligned16(W_scales) || (W_idx && !aligned16(W_idx)) || (lda * 2) % 16 != 0)
     return MXP_ERR_ALIGN;
+  // six- and eight-bit weights: the tiled kernel at any number of rows
+  if (wide_w) return dispatch_tiled(M, N, K, A, lda, W_elems, W_scales, W_idx, fmtW, D, d_dtype, ldd, s);
   if (M > 64 && M <= 128) {
     // two passes of the few-row kernel read the weights twice and still beat one row of 256 x 256 tiles here
     const int64_t esz = d_dtype == MXP_BF16 ? 2 : 4;
@@ -506,11 +570,7 @@ extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, in
     }
     return MXP_OK;
   }
-  if (M > 64) {
-    if (fmtW == MXP_FMT_MXFP4PP) return dispatch_tiled<2>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
-    if (fmtW == MXP_FMT_MXFP4P) return dispatch_tiled<1>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
-    return dispatch_tiled<0>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
-  }
+  if (M > 64) return dispatch_tiled(M, N, K, A, lda, W_elems, W_scales, W_idx, fmtW, D, d_dtype, ldd, s);
   if (fmtW == MXP_FMT_MXFP4PP) return dispatch_skinny<2>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
   if (fmtW == MXP_FMT_MXFP4P) return dispatch_skinny<1>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);
   return dispatch_skinny<0>(M, N, K, A, lda, W_elems, W_scales, W_idx, D, d_dtype, ldd, s);

@@ -337,12 +337,13 @@ def gemm_decode_bf16a(a: torch.Tensor, fmt_a: int, qw, fmt_w: int = MXFP4P, out_
 
 
 def gemm_w4a16(a: torch.Tensor, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None):
-    """Un-quantized bf16 activations x canonical 4-bit weights, de-converted inside the kernel (few-row kernel for M <= 64, 256 x 256 tiles above)."""
+    """Un-quantized bf16 activations x canonical weights of any block format, de-converted inside the kernel (4-bit weights:
+    few-row kernel for M <= 64; otherwise 256 x 256 tiles on the bf16 MFMA)."""
     _dev2d(a)
     we, ws, wi = qw
     M, K = a.shape
     N = we.shape[0]
-    if we.shape[1] * 2 != K:
+    if ws.shape[1] * 32 != K:
         raise MxpError("K mismatch between operands")
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=a.device)

@@ -131,7 +131,11 @@ def test_argument_errors_are_reported_not_launched():
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4) == 0
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4)
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, p, 1 << 24, None) == -8
-    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP8P, p, p, p, mxp.MXFP8, p, mxp.F32, 64, p, 1 << 24, None) == -8
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP8P, p, p, p, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -8
+    assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8P, p, p, p, mxp.MXFP8, p, mxp.F32, 64, None, 0, None) == -1
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8P, mxp.MXFP8) == 0
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, mxp.MXFP8P, p, mxp.F32, 64, None) == -1
+    assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, 7, p, mxp.F32, 64, None) == -5
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -1
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1024, None) == -6
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8, p, p, None, mxp.MXFP8, p, mxp.F32, 64, p, 1024, None) == -6

@@ -867,9 +867,66 @@ def test_gemm_mxfp8_shapes(M, N, K):
     ia, ib = mxp.prepack_fp8(q_dev(qa)), mxp.prepack_fp8(q_dev(qb))
     assert torch.equal(D, mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3))
     with pytest.raises(mxp.MxpError):
-        mxp.gemm(q_dev(W.quantize(a, W.MXFP8P)), mxp.MXFP8P, q_dev(qb), mxp.MXFP8)     # no MXFP8+ product
-    with pytest.raises(mxp.MxpError):
         mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(W.quantize(w, W.MXFP6)), mxp.MXFP6)       # widths are not mixed
+
+
+@pytest.mark.parametrize("fa,fb", [("mxfp8p", "mxfp8p"), ("mxfp8p", "mxfp8"), ("mxfp8", "mxfp8p")])
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (257, 300, 1024), (300, 520, 2048), (64, 1000, 2080)])
+def test_gemm_mxfp8p_shapes(fa, fb, M, N, K):
+    """Products with an MXFP8+ operand: de-converted inside the kernel, multiplied as bf16 (exact products), so the
+    bound of the main path applies."""
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    qa, qb = W.quantize(a, WIDE[fa][1]), W.quantize(w, WIDE[fb][1])
+    ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
+    D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0])
+    check_gemm(D, ref, S, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
+    Db = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+def test_gemm_mxfp8p_special_blocks():
+    """Flushed and NaN blocks, every code incl. the E4M3 NaN code (takes the integer path), BMs with all mantissa bits."""
+    W = oracle.wide
+    rng = np.random.default_rng(5)
+    x = special_tensor(rows=100, K=256, seed=11, bf16=False)
+    x[9, 5] = 1.0                                                # (no 3e38: its products overflow fp32)
+    for r in range(20, 40):
+        x[r, 32:64] = rng.standard_normal(32) * 3
+        x[r, 40] = np.float32(256.0 * (1.0 + rng.integers(0, 128) / 128.0)) * rng.choice([-1, 1])
+    a, b = x[:40], x[40:100]
+    qa, qb = W.quantize(a, W.MXFP8P), W.quantize(b, W.MXFP8P)
+    ref, S = W.gemm(qa, W.MXFP8P, qb, W.MXFP8P)
+    D = mxp.gemm(q_dev(qa), mxp.MXFP8P, q_dev(qb), mxp.MXFP8P).double().cpu().numpy()
+    nan = np.isnan(ref)
+    assert nan.any() and (np.isnan(D) == nan).all()
+    ok = ~nan & np.isfinite(ref) & (np.abs(ref) < 1e37) & (S < 1e37)
+    # blocks whose values lie below the bf16 normal range are rounded to bf16 first: leave those rows / columns out
+    tiny_a = ((qa[1] < 10) & (qa[1] > 0)).any(axis=1)                # smallest E4M3 value 2^-9 X >= 2^-126 from scale byte 10 on
+    tiny_b = ((qb[1] < 10) & (qb[1] > 0)).any(axis=1)
+    ok &= ~tiny_a[:, None] & ~tiny_b[None, :]
+    assert ok.sum() > 1000
+    assert (np.abs(D - ref)[ok] <= 2.0 ** -16 * S[ok] + 1.2e-38).all()
+
+
+@pytest.mark.parametrize("w_fmt", ["mxfp6", "mxfp6p", "mxfp8", "mxfp8p"])
+@pytest.mark.parametrize("M,N,K", [(8, 100, 96), (100, 200, 416), (257, 300, 1024), (300, 520, 2048)])
+def test_gemm_w4a16_wide_weights(M, N, K, w_fmt):
+    """Un-quantized bf16 activations x six- / eight-bit weights de-converted in the tiled kernel."""
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=62)
+    w = synth.weights(N, K, config_id=1, tensor_id=63, t3_frac=0.001)
+    qw = W.quantize(w, WIDE[w_fmt][1])
+    a64 = synth.bf16_bits_to_f32(a).astype(np.float64) if a.dtype == np.uint16 else a.astype(np.float64)
+    w64 = W.dequantize(qw, WIDE[w_fmt][1])
+    ref, S = a64 @ w64.T, np.abs(a64) @ np.abs(w64).T
+    ad = to_dev(a) if a.dtype == np.uint16 else torch.from_numpy(a).cuda().to(torch.bfloat16)
+    if a.dtype != np.uint16:
+        a64 = ad.float().cpu().numpy().astype(np.float64)
+        ref, S = a64 @ w64.T, np.abs(a64) @ np.abs(w64).T
+    D = mxp.gemm_w4a16(ad, q_dev(qw), WIDE[w_fmt][0])
+    check_gemm(D, ref, S, "bf16 x %s %dx%dx%d" % (w_fmt, M, N, K))
 
 
 def test_gemm_mxfp8_full_size_sampled():
