@@ -1,4 +1,6 @@
-// mxp_gemm_w4a16 : D[M][N] = A[M][K] (bf16, not quantized) x deq(W)[N][K]^T, W in canonical MXFP4 / MXFP4+ / MXFP4++.
+// mxp_gemm_w4a16 : D[M][N] = A[M][K] (bf16, not quantized) x deq(W)[N][K]^T, W in canonical MXFP4 / MXFP4+ / MXFP4++
+// (few rows: a weight-read-bound kernel; many rows: a tiled kernel, which also takes MXFP6(+) / MXFP8(+) weights and, for
+// the MXFP8+ products of mxp_gemm, quantized eight-bit activations).
 //
 // The conversion-based use of the formats (Sec. 5: on hardware that lacks low-precision units, or for weight-only
 // quantization, the blocks are de-converted to a wider type the hardware multiplies, Eq. 2 inside the kernel; the BM

@@ -1,5 +1,6 @@
 // Six- and eight-bit MX / MX+ formats (Sec. 4.2, data layout): MXFP6 (E2M3), MXFP6+, MXFP8 (E4M3), MXFP8+.
-// Conversion and de-conversion only; the kernels behind mxp_quantize / mxp_dequantize for these format codes.
+// The kernels behind mxp_quantize / mxp_dequantize for these format codes, and the kernels that lay MXFP6(+) and plain
+// MXFP8 operands out as MFMA-ready images (mxp_prepack_fp6, mxp_prepack_fp8).
 //
 // Block rule as for MXFP4+ (Eq. 1, Sec. 4.1) with e_max = 2 (E2M3) or 8 (E4M3): scale byte = exponent field of the BM
 // - e_max, flush when that field is <= e_max, byte 255 for a block with NaN/Inf.  An ordinary element is x / X rounded
