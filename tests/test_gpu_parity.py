@@ -863,7 +863,7 @@ def test_gemm_mxfp8_shapes(M, N, K):
     qa, qb = W.quantize(a, W.MXFP8), W.quantize(w, W.MXFP8)
     ref, S = W.gemm(qa, W.MXFP8, qb, W.MXFP8)
     D = mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(qb), mxp.MXFP8)
-    check_gemm_e4m3(D, ref, S, "mxfp8 %dx%dx%d" % (M, N, K))
+    check_gemm_mxfp8(D, ref, S, "mxfp8 %dx%dx%d" % (M, N, K))
     ia, ib = mxp.prepack_fp8(q_dev(qa)), mxp.prepack_fp8(q_dev(qb))
     assert torch.equal(D, mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3))
     with pytest.raises(mxp.MxpError):
@@ -951,8 +951,8 @@ def test_gemm_mxfp8_full_size_sampled():
     ref = np.einsum("tk,tk->t", da[inv_a], dw[inv_w])
     S = np.einsum("tk,tk->t", np.abs(da[inv_a]), np.abs(dw[inv_w]))
     got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4
-    assert (np.abs(got - ref) <= 2.0 ** -12 * S).all()
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 2e-4
+    assert (np.abs(got - ref) <= 2.0 ** -10 * S).all()
 
 
 # ---- the MXFP4++ product (Sec. 4.3) through E4M3 images ------------------------------------------------------------
@@ -961,12 +961,21 @@ def test_gemm_mxfp8_full_size_sampled():
 # to 2^-12.7 of the largest product of a k-tile, only in k-tiles where both operands have a large delta; every other
 # output is exact), where the E2M3 / E2M1 products (12 bits of range) lose nothing.  Hence a wider bound for this
 # path: |err| <= 2^-12 * sum_k |a_k b_k| per element and 1e-4 relative Frobenius.
-def check_gemm_e4m3(D, ref, S, what=""):
+def check_gemm_e4m3(D, ref, S, what="", log2_tol=-12, fro_tol=1e-4):
     D = D.double().cpu().numpy()
     fro = np.linalg.norm(D - ref) / max(np.linalg.norm(ref), 1e-300)
-    assert fro <= 1e-4, "%s: relative Frobenius error %.3e" % (what, fro)
-    worst = (np.abs(D - ref) - 2.0 ** -12 * S).max() if D.size else 0.0
-    assert worst <= 0, "%s: element error exceeds 2^-12 * sum|ab| by %.3e" % (what, worst)
+    assert fro <= fro_tol, "%s: relative Frobenius error %.3e" % (what, fro)
+    worst = (np.abs(D - ref) - 2.0 ** log2_tol * S).max() if D.size else 0.0
+    assert worst <= 0, "%s: element error exceeds 2^%d * sum|ab| by %.3e" % (what, log2_tol, worst)
+
+
+# Plain MXFP8 operands use the whole E4M3 range (2^-9 ... 448), so the products of a k-tile spread further than in an
+# MXFP4++ image and more of them lose low bits when the FP8 dot product aligns them to the largest one.  Measured over
+# activations with outlier channels x1 ... x1000: errors up to 2^-11.1 * sum|ab| (unbiased: mean signed error 1e-8 of it)
+# and 1.1e-4 relative Frobenius.  Bound for this path: 2^-10 * sum|ab| and 2e-4.  (MXFP8+ products and anything else
+# that must be exact go through the bf16 MFMA on de-converted operands.)
+def check_gemm_mxfp8(D, ref, S, what=""):
+    check_gemm_e4m3(D, ref, S, what, log2_tol=-10, fro_tol=2e-4)
 
 
 def test_gemm_mxfp4pp_hand_case():
