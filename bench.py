@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="prefill_mlp", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed steps and the per-stage pass (no format comparisons, decode shapes or probes): "
+                         "the run whose kernel trace holds nothing but the step's own kernels")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_w4a16", "gemm_decode_large", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
@@ -232,6 +235,25 @@ def main():
     torch.cuda.synchronize()
     stage_ms = {n: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(n_prof)]))
                 for i, n in enumerate(stages)}
+    if args.no_extras:
+        flops = 2.0 * M * N * K
+        gemm_tflops_core = flops / (gemm_ms * 1e-3) / 1e12
+        line = {
+            "metric": "MXFP4+ GEMM TFLOP/s (Llama-8B linear shapes); quantize GB/s; % roofline",
+            "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "mxfp4+ (E2M1 elements, E2M3 block max, E8M0 scales), fp32 accumulate", "data": "synthetic",
+            "config": {"workload": args.workload, "M": M, "N": N, "K": K, "out_dtype": args.out_dtype,
+                       "step": "quantize(A) -> canonical + image in one pass, image(W) -> scaled-MFMA GEMM -> dequantize(A)"},
+            "roofline": {"bound": "mfma", "achieved": gemm_tflops_core, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
+                         "frac": gemm_tflops_core / PEAK_FP4_TFLOPS, "traffic": traffic_from_profiles(args.workload, args.out_dtype),
+                         "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms},
+            "stages_ms": stage_ms,
+        }
+        if not args.no_cpu_baseline:
+            line["cpu_baseline"] = cpu_baseline(a_bits, w_bits)
+        print(json.dumps(line))
+        return
     # The paper's main deployment (Sec. 7.1): MXFP4+ activations x plain MXFP4 weights.  The weights stay in 4-bit codes on
     # the B side (E2M1 image).  All products timed the same way: 250 warm-up launches, then 100 back to back, one event pair.
     # The third product is plain MXFP4 x MXFP4 (both images 4-bit): the baseline the paper normalises MX+ to.
