@@ -3,6 +3,8 @@
 Quantized bytes, scales and BM indices must be bit-exact; de-converted values bit-exact; GEMM outputs within
 rel-Frobenius 1e-5 and |err| <= 2^-16 * sum_k |a_k b_k| per element.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -1180,3 +1182,15 @@ def test_gemm_tiled_kernel_strided_and_unaligned_output(M, N, K, pad, dt):
     view = flat[1:1 + M * (N + pad)].view(M, N + pad)
     mxp.gemm(qa, mxp.MXFP4P, qb, mxp.MXFP4P, out=view[:, :N])
     assert torch.equal(view[:, :N], dense) and (view[:, N:] == -7.0).all() and flat[0] == -7.0
+
+
+def test_readme_example_runs():
+    """The usage block of README.md, as it stands."""
+    import re
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "README.md")).read()
+    block = re.search(r"## Use\n\n```python\n(.*?)```", text, re.S).group(1)
+    env = {}
+    exec(compile(block, "README.md", "exec"), env)
+    torch.cuda.synchronize()
+    assert env["d"].shape == (4096, 14336) and env["d6"].shape == (4096, 14336) and env["dw"].dtype == torch.float32
+    assert torch.isfinite(env["d"]).all() and torch.isfinite(env["dpp"]).all()
