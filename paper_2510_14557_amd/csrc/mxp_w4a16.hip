@@ -314,21 +314,23 @@ struct QOperand {                                            // a quantized oper
   int plus;                                                  // six- / eight-bit kinds: the + form
 };
 
-template <int AK, int WK, bool OUT_BF16>
+template <int AK, int WK, bool OUT_BF16, int WI>
 __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint16_t* __restrict__ A, int64_t lda, QOperand qa,
                                                                      QOperand qw, int64_t nbk, int64_t M, int64_t N,
                                                                      void* __restrict__ Dv, int64_t ldd, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int NJ = 2, WAVES_N = 4, PA = 2048 / kTiledThreads;
+  // WI row tiles per wavefront: 4 -> 256 rows of A per workgroup; 2 -> 128 rows, for launches that would otherwise leave
+  // most compute units without a tile
+  constexpr int NJ = 2, WAVES_N = 4, TROWS = 64 * WI, PA = TROWS * 8 / kTiledThreads;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N, h = lane >> 5, nl = lane & 31;
-  const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * 256, n0 = (int64_t)(blockIdx.x % tiles_n) * 256;
+  const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * TROWS, n0 = (int64_t)(blockIdx.x % tiles_n) * 256;
   const int64_t nks = (nbk + 1) / 2;
 
-  v16f acc[4][NJ];
+  v16f acc[WI][NJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < WI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -348,7 +350,7 @@ __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint1
   // quantized operands: block b = tid % 2 of row tid / 2 in every step
   const int q_row = tid >> 1, q_b = tid & 1;
   const uint32_t q_off = (uint32_t)(q_row * kTRow + 64 * q_b);
-  const bool qa_ok = AK != kRawBf16 && m0 + q_row < M, qw_ok = n0 + q_row < N;
+  const bool qa_ok = AK != kRawBf16 && q_row < TROWS && m0 + q_row < M, qw_ok = n0 + q_row < N;
   const int64_t qa_base = qa_ok ? (m0 + q_row) * nbk + q_b : 0, qw_base = qw_ok ? (n0 + q_row) * nbk + q_b : 0;
   const bool a_has_ix = AK == 2 || AK == 3 || ((AK == kFp6 || AK == kFp8) && qa.plus);
   const bool w_has_ix = WK == 2 || WK == 3 || ((WK == kFp6 || WK == kFp8) && qw.plus);
@@ -374,9 +376,9 @@ __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint1
   auto load_qw = [&](int64_t ks) { return q_load<WK>(qw_ok && 2 * ks + q_b < nbk, qw.el, qw.sc, qw.ix, qw_base + 2 * ks, w_has_ix); };
 
   // operand reads: lane (nl, h) of tile row / column r takes chunk 4 h + s4 (an immediate offset from these bases)
-  uint32_t rd_a[4], rd_w[NJ];
+  uint32_t rd_a[WI], rd_w[NJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) rd_a[i] = (uint32_t)((wm * 128 + 32 * i + nl) * kTRow + 64 * h);
+  for (int i = 0; i < WI; ++i) rd_a[i] = (uint32_t)((wm * (32 * WI) + 32 * i + nl) * kTRow + 64 * h);
 #pragma unroll
   for (int j = 0; j < NJ; ++j) rd_w[j] = (uint32_t)(kTOperand + (wn * (32 * NJ) + 32 * j + nl) * kTRow + 64 * h);
 
@@ -415,7 +417,7 @@ __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint1
         wv[j] = as_v8bf(v4);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < WI; ++i) {
         const u32x4 v = *reinterpret_cast<const u32x4*>(st + rd_a[i] + 16 * s4);
         const uint32_t v4[4] = {v.x, v.y, v.z, v.w};
         const v8bf a8 = as_v8bf(v4);
@@ -436,13 +438,13 @@ __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint1
     __syncthreads();
   }
   // accumulator register r of lane l: D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32] of the 32 x 32 tile
-  const bool whole = m0 + 256 <= M && n0 + 256 <= N;
+  const bool whole = m0 + TROWS <= M && n0 + 256 <= N;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < WI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int64_t col = n0 + wn * (32 * NJ) + 32 * j + nl;
-      const int64_t row0 = m0 + wm * 128 + 32 * i + 4 * h;
+      const int64_t row0 = m0 + wm * (32 * WI) + 32 * i + 4 * h;
       if (whole) {                                           // tile inside the matrix (uniform): no per-element tests
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -463,25 +465,25 @@ __global__ void __launch_bounds__(kTiledThreads) deconv_tiled_kernel(const uint1
     }
 }
 
-template <int AK, int WK>
+template <int AK, int WK, int WI = 4>
 int launch_deconv(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const QOperand& qa, const QOperand& qw, void* D,
                   int d_dtype, int64_t ldd, hipStream_t s) {
-  const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256;
+  const int64_t tm = (M + 64 * WI - 1) / (64 * WI), tn = (N + 255) / 256;
   if (tm * tn > 2147483647LL || tn > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)(tm * tn));
   const int64_t nbk = K / kBlock;
   static_assert(kTiledLds <= 160 * 1024, "LDS");
   if (d_dtype == MXP_BF16) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, true>),
+    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, true, WI>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
     (void)once_b;
-    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, true>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
+    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, true, WI>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
                        lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, false>),
+    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, false, WI>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
     (void)once_f;
-    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, false>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
+    hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, false, WI>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
                        lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   }
   return launch_status();
@@ -503,6 +505,15 @@ inline int plus_of(int fmt) { return fmt == MXP_FMT_MXFP6P || fmt == MXP_FMT_MXF
 int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const uint8_t* we, const uint8_t* ws,
                    const uint8_t* wi, int fmtW, void* D, int d_dtype, int64_t ldd, hipStream_t s) {
   const QOperand none = {nullptr, nullptr, nullptr, 0}, qw = {we, ws, wi, plus_of(fmtW)};
+  // fewer than ~200 tiles of 256 rows: tiles of 128 rows, twice as many workgroups (four-bit weights only)
+  const bool small = ((M + 255) / 256) * ((N + 255) / 256) < 200 && M > 128;
+  if (small && kind_of(fmtW) <= 3) {
+    switch (kind_of(fmtW)) {
+      case 1: return launch_deconv<kRawBf16, 1, 2>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+      case 2: return launch_deconv<kRawBf16, 2, 2>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+      default: return launch_deconv<kRawBf16, 3, 2>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
+    }
+  }
   switch (kind_of(fmtW)) {
     case 1: return launch_deconv<kRawBf16, 1>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
     case 2: return launch_deconv<kRawBf16, 2>(M, N, K, A, lda, none, qw, D, d_dtype, ldd, s);
