@@ -293,9 +293,58 @@ __device__ __forceinline__ QBlock q_load(bool ok, const uint8_t* el, const uint8
   return r;
 }
 
+// Four-bit block -> 64 bytes of bf16 at `dst`.  As decode_block_bf16, except that the rare cases are kept out of the
+// registers: the 32 elements are converted with the NBM scale and stored, then the BM is written over its two bytes
+// with one LDS store, and blocks with a reserved scale byte (all-zero, NaN) are overwritten by the lanes that hold one
+// (LDS operations of a wavefront execute in order).  Wavefronts with a block below the bf16 normal range take the
+// general routine.
+template <int MODE>
+__device__ __forceinline__ void q_store_fp4(const QBlock& r, uint8_t* dst) {
+  const uint32_t delta = MODE == 2 ? r.ib >> 5 : 0u;
+  const bool tiny = r.sb != 0u && r.sb < 2u + delta;
+  if (__builtin_amdgcn_ballot_w64(tiny) != 0) {
+    uint32_t w[16];
+    decode_block_bf16<MODE>((u32x4){r.raw[0], r.raw[1], r.raw[2], r.raw[3]}, r.sb, r.ib, w);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+      *reinterpret_cast<u32x4*>(dst + 16 * s4) = (u32x4){w[4 * s4], w[4 * s4 + 1], w[4 * s4 + 2], w[4 * s4 + 3]};
+    return;
+  }
+  const bool special = r.sb == 0u || r.sb == 255u;
+  const float X = __uint_as_float((special ? 127u : r.sb - delta) << 23);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    union { v2bf v; uint32_t u; } c0, c1, c2, c3;
+    c0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(r.raw[j], X, 0);
+    c1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(r.raw[j], X, 1);
+    c2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(r.raw[j], X, 2);
+    c3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(r.raw[j], X, 3);
+    *reinterpret_cast<u32x4*>(dst + 16 * j) = (u32x4){c0.u, c1.u, c2.u, c3.u};
+  }
+  if (MODE >= 1 && !special) {
+    const uint32_t idx = r.ib & 31u;
+    const uint32_t qd = idx < 8u ? r.raw[0] : idx < 16u ? r.raw[1] : idx < 24u ? r.raw[2] : r.raw[3];
+    const uint32_t nib = (qd >> (4u * (idx & 7u))) & 15u;
+    const float XB = __uint_as_float(r.sb << 23);
+    const uint32_t bm = ((nib & 8u) << 12) | (__float_as_uint((float)(8u + (nib & 7u)) * (XB * 0.5f)) >> 16);   // exact: 4 bits
+    *reinterpret_cast<uint16_t*>(dst + 2u * idx) = (uint16_t)bm;
+  }
+  if (__builtin_amdgcn_ballot_w64(special) != 0) {
+    if (special) {
+      const uint32_t v = r.sb == 0u ? 0u : 0x7FC07FC0u;
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) *reinterpret_cast<u32x4*>(dst + 16 * s4) = (u32x4){v, v, v, v};
+    }
+  }
+}
+
 // de-convert the block and store its 64 bytes of bf16 at `dst` (the block's place in its LDS row)
 template <int KIND>
 __device__ __forceinline__ void q_store(const QBlock& r, bool plus, uint8_t* dst) {
+  if constexpr (KIND >= 1 && KIND <= 3) {
+    q_store_fp4<KIND - 1>(r, dst);
+    return;
+  }
   uint32_t w[16];
   if (KIND == kFp6 || KIND == kFp8) {
     constexpr int BITS = KIND == kFp6 ? 6 : 8;
