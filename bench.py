@@ -250,6 +250,10 @@ def main():
                          "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms},
             "stages_ms": stage_ms,
         }
+        if M <= 64:                                          # few rows: bound by reading the weight image once
+            wbytes = float(img_w.numel())
+            line["roofline"].update({"bound": "hbm", "achieved": wbytes / (gemm_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS,
+                                     "unit": "GB/s", "frac": wbytes / (gemm_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS})
         if not args.no_cpu_baseline:
             line["cpu_baseline"] = cpu_baseline(a_bits, w_bits)
         print(json.dumps(line))
