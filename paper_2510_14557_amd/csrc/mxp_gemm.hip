@@ -19,7 +19,7 @@ int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t row
 int prepack_e4m3_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                         void* image, hipStream_t stream);
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
-                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream);
+                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream, bool skip_padding_tiles);
 }  // namespace mxp
 
 namespace {
@@ -1457,7 +1457,7 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
     return MXP_ERR_ALIGN;
   if (workspace_bytes < (fp8 ? mxp_image_bytes_e4m3(M, K) : mxp_gemm_bf16a_workspace_bytes(M, K))) return MXP_ERR_WORKSPACE;
   uint8_t* img = static_cast<uint8_t*>(workspace);
-  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
+  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s, /*skip_padding_tiles=*/M <= 64);   // (M <= 64: the few-row kernels read only the tiles that hold rows)
   if (rc != MXP_OK) return rc;
   return gemm_images(img, fp8 ? MXP_IMAGE_E4M3 : MXP_IMAGE_E2M3, B_image, b_kind, M, N, K, D, d_dtype, ldd, s);
 }
@@ -1500,7 +1500,7 @@ extern "C" int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void
   if (!aligned16(A) || !aligned16(workspace) || (lda * (a_dtype == MXP_BF16 ? 2 : 4)) % 16 != 0) return MXP_ERR_ALIGN;
   if (workspace_bytes < mxp_gemm_bf16a_workspace_bytes(M, K)) return MXP_ERR_WORKSPACE;
   uint8_t* img = static_cast<uint8_t*>(workspace);
-  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s);
+  rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s, /*skip_padding_tiles=*/M <= 64);   // (M <= 64: the few-row kernels read only the tiles that hold rows)
   if (rc != MXP_OK) return rc;
   return mxp_gemm_decode(M, N, K, img, W_elems, W_scales, W_idx, fmtW, D, d_dtype, ldd, stream);
 }

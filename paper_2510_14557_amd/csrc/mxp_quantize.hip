@@ -723,7 +723,8 @@ template <bool BF16, bool PLUS>
 __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
                                                              int64_t k_tiles, uint32_t* __restrict__ elems,
                                                              uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
-                                                             uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+                                                             uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales,
+                                                             int skip_padding_tiles) {
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
   __shared__ uint8_t tile_scales[4 * 64];
   const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
@@ -736,7 +737,9 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   const int64_t row0 = rt * kTileRows + r0, kb = kt0 * 2 + kb_in;
   const bool whole = rt * kTileRows + kTileRows <= rows && kt0 * 2 + 8 <= nbk;   // uniform: no lane of the workgroup is padding
   if (rt * kTileRows >= rows) {
-    // a row tile of pure padding (rows are padded to 256): zero elements, unit scales, nothing to encode
+    // a row tile of pure padding (rows are padded to 256): zero elements, unit scales, nothing to encode; left
+    // unwritten when the only reader is the few-row product, which touches the tiles that hold rows only
+    if (skip_padding_tiles) return;
     const int64_t nt0 = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
     uint8_t* out0 = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
     const u32x4 z = {0, 0, 0, 0};
@@ -841,13 +844,15 @@ template <bool BF16>
 __global__ void __launch_bounds__(256) quantize_image_e4m3_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
                                                                   int64_t k_tiles, uint32_t* __restrict__ elems,
                                                                   uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
-                                                                  uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+                                                                  uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales,
+                                                                  int skip_padding_tiles) {
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE4M3];
   __shared__ uint8_t tile_scales[4 * 64];
   const uint32_t t = threadIdx.x, part = t & 3u;
   const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
   if (!pm.valid) return;
   const int64_t rt = pm.rt, kt0 = pm.kg * 4;
+  if (skip_padding_tiles && rt * kTileRows >= rows) return;   // (see quantize_image_kernel)
   const bool canon = elems != nullptr;
   const uint32_t r0 = t >> 5, kb_in = (t >> 2) & 7u;
   const int64_t row0 = rt * kTileRows + r0, kb = kt0 * 2 + kb_in;
@@ -968,7 +973,8 @@ int quantize_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int
 
 // Also used by the GEMM entry point that takes unquantized activations.  Canonical pointers may all be null.
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
-                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream) {
+                          uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream, bool skip_padding_tiles) {
+  const int skip = skip_padding_tiles ? 1 : 0;
   const bool pp = fmt == MXP_FMT_MXFP4PP;
   const ImageGeom g = image_geom(rows, K, pp ? kTileBytesE4M3 : kTileBytes);
   const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
@@ -980,14 +986,14 @@ int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t 
   const int64_t nbk = K / kBlock;
   const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP4P;
   if (pp) {
-    if (bf) hipLaunchKernelGGL((quantize_image_e4m3_kernel<true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
-    else hipLaunchKernelGGL((quantize_image_e4m3_kernel<false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+    if (bf) hipLaunchKernelGGL((quantize_image_e4m3_kernel<true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
+    else hipLaunchKernelGGL((quantize_image_e4m3_kernel<false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
     return launch_status();
   }
-  if (bf && plus) hipLaunchKernelGGL((quantize_image_kernel<true, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
-  else if (bf) hipLaunchKernelGGL((quantize_image_kernel<true, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
-  else if (plus) hipLaunchKernelGGL((quantize_image_kernel<false, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
-  else hipLaunchKernelGGL((quantize_image_kernel<false, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is);
+  if (bf && plus) hipLaunchKernelGGL((quantize_image_kernel<true, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
+  else if (bf) hipLaunchKernelGGL((quantize_image_kernel<true, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
+  else if (plus) hipLaunchKernelGGL((quantize_image_kernel<false, true>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
+  else hipLaunchKernelGGL((quantize_image_kernel<false, false>), grid, dim3(256), 0, stream, src, rows, nbk, ld_src, g.k_tiles, e32, scales, bm_idx, ie, is, skip);
   return launch_status();
 }
 
@@ -1010,7 +1016,7 @@ extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, 
   if (canon && (!aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx)))) return MXP_ERR_ALIGN;
   if (image_bytes < (size_t)image_geom(rows, K, fmt == MXP_FMT_MXFP4PP ? kTileBytesE4M3 : kTileBytes).total()) return MXP_ERR_WORKSPACE;
   return quantize_image_launch(src, src_dtype, rows, K, ld_src, fmt, canon ? elems : nullptr, scales, bm_idx, image,
-                               static_cast<hipStream_t>(stream));
+                               static_cast<hipStream_t>(stream), false);
 }
 
 extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
