@@ -1194,3 +1194,46 @@ def test_readme_example_runs():
     torch.cuda.synchronize()
     assert env["d"].shape == (4096, 14336) and env["d6"].shape == (4096, 14336) and env["dw"].dtype == torch.float32
     assert torch.isfinite(env["d"]).all() and torch.isfinite(env["dpp"]).all()
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_shapes_every_product_path(seed):
+    """A seeded sweep over ragged shapes and format pairs: every product entry point against the oracle."""
+    W = oracle.wide
+    rng = np.random.default_rng(seed)
+    pairs_wide = [("mxfp6", "mxfp6"), ("mxfp6p", "mxfp6"), ("mxfp6", "mxfp6p"), ("mxfp6p", "mxfp6p"), ("mxfp8", "mxfp8"),
+                  ("mxfp8p", "mxfp8"), ("mxfp8p", "mxfp8p"), ("mxfp8", "mxfp8p")]
+    for it in range(8):
+        M = int(rng.choice([rng.integers(1, 65), rng.integers(65, 130), rng.integers(130, 600)]))
+        N, K = int(rng.integers(1, 1200)), 32 * int(rng.integers(1, 70))
+        what = "%dx%dx%d" % (M, N, K)
+        a = synth.activations(M, K, config_id=9, tensor_id=100 * seed + 2 * it)
+        w = synth.weights(N, K, config_id=9, tensor_id=100 * seed + 2 * it + 1, t3_frac=0.001)
+        # four-bit formats, any mix
+        fa, fb = rng.choice(list(FMT)), rng.choice(list(FMT))
+        qa, qb = oracle.quantize(a, FMT[fa][1]), oracle.quantize(w, FMT[fb][1])
+        ref, S = oracle.gemm(qa, FMT[fa][1], qb, FMT[fb][1])
+        D = mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qb), FMT[fb][0])
+        if "pp" in fa + fb:
+            check_gemm_e4m3(D, ref, S, "%s x %s %s" % (fa, fb, what))
+        else:
+            check_gemm(D, ref, S, "%s x %s %s" % (fa, fb, what))
+            img = mxp.prepack_e2m1(q_dev(qb)) if fb == "mxfp4" else mxp.prepack(q_dev(qb), FMT[fb][0])
+            D2 = mxp.gemm_bf16a(to_dev(a), FMT[fa][0], img, N, b_kind=mxp.IMAGE_E2M1 if fb == "mxfp4" else mxp.IMAGE_E2M3)
+            check_gemm(D2, ref, S, "bf16a %s x %s %s" % (fa, fb, what))
+        # un-quantized activations x weights of any format
+        fw = rng.choice(list(FMT) + list(WIDE))
+        a64 = synth.bf16_bits_to_f32(a).astype(np.float64)
+        if fw in FMT:
+            qw, fc = oracle.quantize(w, FMT[fw][1]), FMT[fw][0]
+            w64 = oracle.dequantize(qw, FMT[fw][1]).astype(np.float64)
+        else:
+            qw, fc = W.quantize(w, WIDE[fw][1]), WIDE[fw][0]
+            w64 = W.dequantize(qw, WIDE[fw][1])
+        check_gemm(mxp.gemm_w4a16(to_dev(a), q_dev(qw), fc), a64 @ w64.T, np.abs(a64) @ np.abs(w64).T, "bf16 x %s %s" % (fw, what))
+        # six- and eight-bit pairs
+        fa, fb = pairs_wide[int(rng.integers(len(pairs_wide)))]
+        qa, qb = W.quantize(a, WIDE[fa][1]), W.quantize(w, WIDE[fb][1])
+        ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
+        D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0])
+        (check_gemm_mxfp8 if (fa, fb) == ("mxfp8", "mxfp8") else check_gemm)(D, ref, S, "%s x %s %s" % (fa, fb, what))
