@@ -10,6 +10,8 @@
  *   - K is the reduction dimension; MX blocks are 32 consecutive elements ALONG K (paper Sec. 2 and Sec. 5.1:
  *     a row of A and a column of B are sequences of blocks), so K % 32 == 0 is required.
  *   - Return value: MXP_OK or a negative status; nothing is thrown or aborted, and on an error nothing is enqueued.
+ *   - Sizes are 64-bit throughout (tensors and images beyond 4 GiB are fine); the product entry points (mxp_gemm*)
+ *     take K up to 2^21 (mxp_gemm_prepacked: 2^23 for the images' K) and return MXP_ERR_UNSUPPORTED beyond.
  *     Outputs are overwritten, never accumulated into.
  *
  * Canonical MXFP4 / MXFP4+ storage of a [rows][K] operand (what bit-exact parity is defined on)

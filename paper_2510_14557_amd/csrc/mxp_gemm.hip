@@ -785,6 +785,8 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   const ImageGeom ga = image_geom(M, K, C::AT), gb = image_geom(N, K, C::BT);
   const int64_t gm = (M + 255) / 256, gn = (N + 255) / 256;
   if (gm * gn * 2 > 2000000000LL) return MXP_ERR_UNSUPPORTED;
+  // the copies address an 8-tile run of one operand with a 32-bit lane offset: 8 * k_tiles * tile bytes must fit
+  if (ga.k_tiles > (int64_t)(0xFFFFFFFFu / (8u * kTileBytesE4M3))) return MXP_ERR_UNSUPPORTED;
   const int64_t total = gm * gn;
   const int P = (int)(2 * total < kNumCU ? 2 * total : kNumCU);   // workgroups: one per CU, fewer only if even half tiles run out
   int64_t best_hc = 0;
@@ -1239,9 +1241,14 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
-int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd) {
+// Longest reduction the product entry points take: the tiled kernel addresses an 8-tile run of an operand image with a
+// 32-bit lane offset, and a six-bit + product lays up to four K segments side by side.
+constexpr int64_t kMaxGemmK = (int64_t)1 << 21;
+
+int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd, int64_t max_k = kMaxGemmK) {
   if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
+  if (K > max_k) return MXP_ERR_UNSUPPORTED;
   if (M > 0 && N > 0 && !D) return MXP_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(D) % (d_dtype == MXP_BF16 ? 2 : 4) != 0) return MXP_ERR_ALIGN;
   return MXP_OK;
@@ -1319,7 +1326,7 @@ extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A
   if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1 && a_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
   if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
   if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
-  int rc = check_gemm(M, N, K, D, d_dtype, ldd);
+  int rc = check_gemm(M, N, K, D, d_dtype, ldd, 4 * kMaxGemmK);   // K of the images: up to four K segments
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);

@@ -140,7 +140,10 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1024, None) == -6
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8, p, p, None, mxp.MXFP8, p, mxp.F32, 64, p, 1024, None) == -6
     assert L.mxp_gemm(64, 64, 64, p, p, p, 7, p, p, p, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -5
-    # empty problems are fine and launch nothing
+    # the products take K up to 2^21 (prepacked images, which may hold four K segments: 2^23)
+    assert L.mxp_gemm(64, 64, (1 << 21) + 32, p, p, p, 1, p, p, p, 1, p, mxp.F32, 64, p, 1 << 24, None) == -8
+    assert L.mxp_gemm_prepacked(64, 64, (1 << 23) + 128, p, 0, p, 0, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_bf16a(4, 64, (1 << 21) + 32, p, mxp.BF16, 1 << 22, mxp.MXFP4P, p, mxp.IMAGE_E2M3, p, mxp.F32, 64, p, 1 << 20, None) == -8
     assert L.mxp_quantize(None, mxp.BF16, 0, 64, 64, mxp.MXFP4P, None, None, None, None) == 0
     assert L.mxp_gemm(0, 64, 64, None, None, None, 1, None, None, None, 1, None, mxp.F32, 64, None, 0, None) == 0
 

@@ -1237,3 +1237,60 @@ def test_random_shapes_every_product_path(seed):
         ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
         D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0])
         (check_gemm_mxfp8 if (fa, fb) == ("mxfp8", "mxfp8") else check_gemm)(D, ref, S, "%s x %s %s" % (fa, fb, what))
+
+
+def test_tensors_beyond_4_gib_sampled():
+    """Maximum sizes: one operand whose element count passes 2^32 and whose source, code array, de-converted copy and
+    MFMA image each pass 4 GiB, through conversion, de-conversion, both image builders and both product kernels; the
+    oracle checks rows on either side of the 2^31- and 2^32-element offsets, the first and the last (ragged) row."""
+    R, K, N = 90109, 65536, 256
+    if torch.cuda.mem_get_info()[0] < (64 << 30):
+        pytest.skip("needs 64 GiB of free device memory")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(25101455791)
+    x = torch.empty((R, K), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, R, 4096):
+        n = min(4096, R - r0)
+        x[r0:r0 + n] = torch.randn((n, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    x[:, ::509] *= 50.0                                                      # outlier channels
+    rows = np.array([0, 1, 32767, 32768, 50001, 65535, 65536, R - 2, R - 1])
+    rows_d = torch.from_numpy(rows).cuda()
+    xs = x[rows_d].cpu().view(torch.int16).numpy().view(np.uint16)             # the sampled rows' bf16 bits
+    assert x.numel() > 2 ** 32
+
+    # conversion and de-conversion
+    q = mxp.quantize(x, mxp.MXFP4P)
+    q_o = oracle.quantize(xs, oracle.MXFP4P)
+    for name, g, o in zip(("elems", "scales", "idx"), q, q_o):
+        assert (g[rows_d].cpu().numpy() == o).all(), name
+    back = mxp.dequantize(q, mxp.MXFP4P, torch.bfloat16)
+    assert (back[rows_d].float().cpu().numpy().astype(np.float64) == oracle.dequantize(q_o, oracle.MXFP4P)).all()
+    del back
+    # eight-bit codes: the code array itself is 5.5 GiB
+    q8 = mxp.quantize(x, mxp.MXFP8P)
+    assert q8[0].numel() > 2 ** 32
+    for name, g, o in zip(("elems", "scales", "idx"), q8, oracle.wide.quantize(xs, oracle.wide.MXFP8P)):
+        assert (g[rows_d].cpu().numpy() == o).all(), "mxfp8p " + name
+    del q8
+
+    # the image (4.3 GiB): both builders agree byte for byte, and the canonical arrays of the one-pass kernel too
+    img = mxp.prepack(q, mxp.MXFP4P)
+    assert img.numel() > 2 ** 32
+    img1, q1 = mxp.quantize_image(x, mxp.MXFP4P, canonical=True)
+    assert torch.equal(img, img1)
+    assert all(torch.equal(a, b) for a, b in zip(q, q1))
+    del img1, q1
+
+    # products: W4A4 from the image, and bf16 activations x MXFP4+ weights de-converted in the kernel
+    w = synth.weights(N, K, config_id=5, tensor_id=1, dtype="bf16")
+    qw = mxp.quantize(to_dev(w), mxp.MXFP4P)
+    qw_o = oracle.quantize(w, oracle.MXFP4P)
+    D = mxp.gemm_prepacked(R, N, K, img, mxp.prepack(qw, mxp.MXFP4P))
+    ref, S = oracle.gemm(q_o, oracle.MXFP4P, qw_o, oracle.MXFP4P)
+    check_gemm(D[rows_d], ref, S, "image beyond 4 GiB")
+    del img, D
+    D = mxp.gemm_w4a16(x, qw, mxp.MXFP4P)
+    ref, S = oracle.gemm_w4a16(xs, qw_o, oracle.MXFP4P)
+    check_gemm(D[rows_d], ref, S, "activations beyond 4 GiB")
+    del D, x, q
+    torch.cuda.empty_cache()
