@@ -129,6 +129,19 @@ size_t mxp_image_bytes_e2m1(int64_t rows, int64_t K);
 int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K,
                      void* image, size_t image_bytes, void* stream);
 
+/* MXP_IMAGE_E2M1R: MXFP4+ weights kept in 4-bit codes for the few-row (decode) product, which is bound by the weight
+ * bytes (Sec. 7.2): 4.5 bits per element as in canonical storage instead of the 6.25 of the E2M3 image.  The BM is
+ * split as in Eq. 3 (Sec. 5.2): its nibble holds BM_H = 2^2 * 1.m2 as an ordinary E2M1 code, which the FP4 MFMA
+ * multiplies like any other element, and BM_L = +-(m1 + m0/2) goes with the BM position into one residual byte per
+ * block (sign << 7 | m1 m0 << 5 | index) behind the scales; the product kernel adds a[m][32 kb + index] * BM_L * 2^scale
+ * for every weight block from the activation tile it already holds (one multiply-add per block and activation row).
+ * Results are those of the E2M3 route up to fp32 summation order.  B operand only, next to an E2M3 A image, M <= 64
+ * (mxp_gemm_prepacked, mxp_gemm_bf16a); anything else returns MXP_ERR_UNSUPPORTED. */
+#define MXP_IMAGE_E2M1R 3
+size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K);
+int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K,
+                      void* image, size_t image_bytes, void* stream);
+
 /* MXP_IMAGE_E4M3: the image kind for MXFP4++ operands (Sec. 4.3; it takes MXFP4 and MXFP4+ operands too).  The ordinary
  * elements of an MXFP4++ block are scaled by 2^(shared_exp - delta) and its BM by 2^shared_exp, which one E2M3 code per
  * element cannot express; with the block's scale byte set to (scale byte - delta + 2) every element is an FP8 E4M3

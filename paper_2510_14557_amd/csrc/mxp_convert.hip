@@ -192,11 +192,18 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
 
 // Plain MXFP4 operand -> E2M1 image: the canonical 16-byte blocks moved to their lane slots, scales to the scale
 // dwords (same patch walk as above; flushed blocks are zeroed, padding is zero elements with a unit scale).
+// RES: an MXFP4+ operand kept in 4-bit codes for the few-row product.  The BM (2^2 * 1.m2m1m0) is split as in Eq. 3:
+// its nibble becomes the E2M1 code of BM_H = 2^2 * 1.m2 (sign | 11 | m2), and the rest, BM_L = +-(m1 + m0 / 2), goes
+// with the BM position into one residual byte per block, sign << 7 | m1 m0 << 5 | index, stored in the lane order of
+// the tiles ([row tile][k-tile][64]) behind the scale part.
+template <bool RES>
 __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
-                                                           int64_t rows, int64_t nbk, int64_t k_tiles,
-                                                           uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+                                                           const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                           int64_t k_tiles, uint8_t* __restrict__ img_elems,
+                                                           uint8_t* __restrict__ img_scales, uint8_t* __restrict__ img_res) {
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytesE2M1];
   __shared__ uint8_t tile_scales[4 * 64];
+  __shared__ uint8_t tile_res[4 * 64];
   const uint32_t t = threadIdx.x;
   const uint32_t r_in = t >> 3, kb_in = t & 7u;
   const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
@@ -205,21 +212,39 @@ __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restri
   const uint32_t slot = (kb_in & 1u) * 32u + r_in;
   const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
   u32x4 v = {0, 0, 0, 0};
-  uint32_t sbyte = 127u;
+  uint32_t sbyte = 127u, res = 0u;
   if (row < rows && kb < nbk) {
     const int64_t b = row * nbk + kb;
     v = __builtin_nontemporal_load(elems + b);
     sbyte = scales[b];
     if (sbyte == 0u) v = (u32x4){0, 0, 0, 0};
+    if (RES && sbyte != 0u && sbyte != 255u) {
+      const uint32_t bm = bm_idx[b] & 31u, sh = 4u * (bm & 7u);
+      uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t nib = (w[j] >> sh) & 15u;
+        const uint32_t hi = (nib & 8u) | 6u | ((nib >> 2) & 1u);
+        if ((bm >> 3) == (uint32_t)j) {
+          w[j] = (w[j] & ~(15u << sh)) | (hi << sh);
+          res = bm | ((nib & 3u) << 5) | ((nib & 8u) << 4);
+        }
+      }
+      v = (u32x4){w[0], w[1], w[2], w[3]};
+    }
   }
   *reinterpret_cast<u32x4*>(tiles + (kb_in >> 1) * kTileBytesE2M1 + slot * 16u) = v;
   tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sbyte;
+  if (RES) tile_res[(kb_in >> 1) * 64u + slot] = (uint8_t)res;
   __syncthreads();
   const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;
   uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytesE2M1;
   if (t * 16u < (uint32_t)nt * kTileBytesE2M1)
     MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + t * 16u), reinterpret_cast<u32x4*>(out + t * 16u));
-  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+  if ((int64_t)(t >> 6) < nt) {
+    img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+    if (RES) img_res[(rt * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)] = tile_res[t];
+  }
 }
 
 // MXFP4 / MXFP4+ / MXFP4++ operand -> E4M3 image (the one image kind that can hold the two scales of an MXFP4++
@@ -327,14 +352,21 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
   return launch_status();
 }
 
-int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream) {
+// bm_idx == nullptr: plain E2M1 image; else the E2M1 image of an MXFP4+ operand with its residual bytes behind it
+int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
+                        hipStream_t stream) {
   const ImageGeom g = image_geom(rows, K, kTileBytesE2M1);
   uint8_t* ie = static_cast<uint8_t*>(image);
   uint8_t* is = ie + g.elem_bytes;
+  uint8_t* ir = is + g.scale_bytes;
   const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
   if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(prepack_e2m1_kernel, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems), scales,
-                     rows, K / kBlock, g.k_tiles, ie, is);
+  if (bm_idx)
+    hipLaunchKernelGGL(prepack_e2m1_kernel<true>, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems),
+                       scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  else
+    hipLaunchKernelGGL(prepack_e2m1_kernel<false>, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems),
+                       scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
   return launch_status();
 }
 
@@ -427,7 +459,24 @@ extern "C" int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int
   if (!elems || !scales || !image) return MXP_ERR_NULL;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(image)) return MXP_ERR_ALIGN;
   if (image_bytes < (size_t)image_geom(rows, K, kTileBytesE2M1).total()) return MXP_ERR_WORKSPACE;
-  return prepack_e2m1_launch(elems, scales, rows, K, image, static_cast<hipStream_t>(stream));
+  return prepack_e2m1_launch(elems, scales, nullptr, rows, K, image, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K) {
+  if (rows < 0 || K < 0) return 0;
+  const mxp::ImageGeom g = mxp::image_geom(rows, K, mxp::kTileBytesE2M1);
+  return (size_t)(g.total() + g.row_tiles * g.k_tiles * 64);
+}
+
+extern "C" int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K,
+                                 void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !bm_idx || !image) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(bm_idx) || !aligned16(image)) return MXP_ERR_ALIGN;
+  if (image_bytes < mxp_image_bytes_e2m1r(rows, K)) return MXP_ERR_WORKSPACE;
+  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,

@@ -15,7 +15,8 @@
 namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream);
-int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
+int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
+                        hipStream_t stream);
 int prepack_e4m3_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                         void* image, hipStream_t stream);
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
@@ -1003,6 +1004,224 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   return launch_status();
 }
 
+// ---- skinny-M kernel on MXFP4+ weights kept in 4-bit codes (E2M1 image + residual bytes) --------------------------
+// The decode stage is bound by the weight bytes (Sec. 7.2), and the E2M3 image spends 6.25 bits on an element that
+// canonical MXFP4+ stores in 4.5.  Here the weights stay 4-bit: the BM's nibble holds BM_H of Eq. 3 as an ordinary E2M1
+// code, so the FP4 MFMA forms every product except a[k_BM] * BM_L, one per weight block and activation row (Sec. 5.2:
+// the extra sparse product).  That term is added on the vector ALU: in the MFMA operand order a lane holds exactly one
+// weight block of a k-tile (column l % 32, block l / 32) and one activation block (row l % 32, block l / 32).  Each
+// k-tile, the lanes de-convert their activation blocks (one conversion instruction, with the block scale) into a
+// private LDS patch [row][64 k] of fp32 -- exact: four significant bits -- and every lane gathers, for each activation
+// row, the element at its weight block's BM position and accumulates a * (BM_L * 2^scale) in fp32.  RB = activation
+// rows covered (8, 16, 32, 64); the RB partial corrections per lane and column tile join the MFMA accumulators through
+// the same patch before the usual reduction over the wavefronts.  Everything else as in gemm_skinny_kernel.
+typedef int v6i __attribute__((ext_vector_type(6)));
+typedef float v32f __attribute__((ext_vector_type(32)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int RB, int CT, bool OUT_BF16, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                                     const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                                     const uint8_t* __restrict__ b_res, int k_tiles, int64_t M,
+                                                                     int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  constexpr int TMR = RB > 32 ? 2 : 1;
+  constexpr int AT = kTileBytes, BT = kTileBytesE2M1;
+  constexpr int CHUNK = CT == 4 ? 3 : (CT == 2 && WAVES == 16 ? 2 : 4);
+  constexpr int kPart = TMR * CT * 16 * 64 * 4;              // a wavefront's partial accumulators
+  constexpr int kStage = TMR * 32 * 64 * 4;                  // its de-converted activation tiles of one k-tile
+  constexpr int kWave = kPart > kStage ? kPart : kStage;     // bytes of LDS per wavefront (the two uses alternate)
+  static_assert(CT * RB * 256 <= kWave, "the corrections pass through the same patch");
+  extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float* mine = reinterpret_cast<float*>(skinny_lds + wave * kWave);
+  const int half = lane >> 5;
+  const int64_t ct = (int64_t)blockIdx.x * CT;
+  const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
+  const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
+  const uint8_t* br = b_res + ct * (int64_t)k_tiles * 64 + lane;
+  const int b_shift = (int)(ct & 3) * 8;
+  v16f acc[TMR][CT];
+  float corr[CT][RB];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+#pragma unroll
+  for (int j = 0; j < CT; ++j)
+#pragma unroll
+    for (int m = 0; m < RB; ++m) corr[j][m] = 0.0f;
+
+  const int n_chunks = (k_tiles + CHUNK - 1) / CHUNK;
+  const int first = (int)((blockIdx.x * 5u) % (uint32_t)n_chunks);
+  for (int ci = wave; ci < n_chunks; ci += WAVES) {
+    const int q = ci + first < n_chunks ? ci + first : ci + first - n_chunks;
+    const int k0 = q * CHUNK;
+    u32x4 b[CHUNK][CT];
+    v8i a[CHUNK][TMR];
+    uint32_t sb[CHUNK], sa[CHUNK], rs[CHUNK][CT];
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      const int kt = k0 + c < k_tiles ? k0 + c : k_tiles - 1;     // clamped: the surplus is not used
+#pragma unroll
+      for (int j = 0; j < CT; ++j) {
+        b[c][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bt + ((int64_t)j * k_tiles + kt) * BT + lane * 16));
+        rs[c][j] = __builtin_nontemporal_load(br + ((int64_t)j * k_tiles + kt) * 64);
+      }
+      sb[c] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
+      sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + (int64_t)kt * 256 + lane * 4);
+#pragma unroll
+      for (int i = 0; i < TMR; ++i) {
+        const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
+        u32x4 alo = {0, 0, 0, 0};
+        u32x2 ahi = {0, 0};
+        if (32 * i + (lane & 31) < M) {
+          alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
+          ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+        }
+        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      if (k0 + c < k_tiles) {
+#pragma unroll
+        for (int i = 0; i < TMR; ++i)
+#pragma unroll
+          for (int j = 0; j < CT; ++j) {
+            const v8i bv = {(int)b[c][j].x, (int)b[c][j].y, (int)b[c][j].z, (int)b[c][j].w, 0, 0, 0, 0};
+            switch (i * 4 + j) {
+              case 0: acc[i][j] = mfma<0, 0, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 1: acc[i][j] = mfma<0, 1, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 2: acc[i][j] = mfma<0, 2, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
+              case 3: acc[i][j] = mfma<0, 3, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
+              default: acc[i][j] = mfma<1, 0, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
+            }
+          }
+        // the BM_L products of this k-tile.  Activation tile -> fp32 in the patch: row 32 i + l % 32, k = 32 (l / 32) + e
+#pragma unroll
+        for (int i = 0; i < TMR; ++i) {
+          const uint32_t sbyte = (sa[c] >> (8 * i)) & 255u;
+          const v6i codes = {a[c][i][0], a[c][i][1], a[c][i][2], a[c][i][3], a[c][i][4], a[c][i][5]};
+          const v32f av = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(codes, __uint_as_float(sbyte << 23));
+          if (32 * i + (lane & 31) < M) {
+            float* dst = mine + (32 * i + (lane & 31)) * 64 + 32 * half;
+#pragma unroll
+            for (int e = 0; e < 32; e += 4) *reinterpret_cast<f32x4_t*>(dst + e) = (f32x4_t){av[e], av[e + 1], av[e + 2], av[e + 3]};
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < CT; ++j) {
+          const uint32_t r = rs[c][j];
+          const uint32_t sw = (sb[c] >> (8 * j)) & 255u;
+          // BM_L * 2^(scale - 127) = +-(m1 m0) * 2^(scale - 128); zero residual bits for blocks without a BM
+          float lw = __builtin_ldexpf((float)((r >> 5) & 3u), (int)sw - 128);
+          lw = (r & 0x80u) ? -lw : lw;
+          const float* src = mine + 32 * half + (r & 31u);
+#pragma unroll
+          for (int m = 0; m < RB; ++m)
+            if (m < M) corr[j][m] = __builtin_fmaf(src[m * 64], lw, corr[j][m]);
+        }
+      }
+    }
+  }
+  // corrections -> accumulator layout: lane l holds those of column l % 32 for every row; register r of lane l is
+  // row l % 32, column 8 (r / 4) + 4 (l / 32) + r % 4
+#pragma unroll
+  for (int j = 0; j < CT; ++j)
+#pragma unroll
+    for (int m = 0; m < RB; ++m) mine[(j * RB + m) * 64 + lane] = corr[j][m];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i) {
+    const int row = 32 * i + (lane & 31);
+    if (row < RB) {
+#pragma unroll
+      for (int j = 0; j < CT; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float* p = mine + (j * RB + row) * 64 + 8 * g + 4 * half;
+          const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(p), c1 = *reinterpret_cast<const f32x4_t*>(p + 32);
+          acc[i][j][4 * g] += c0.x + c1.x;
+          acc[i][j][4 * g + 1] += c0.y + c1.y;
+          acc[i][j][4 * g + 2] += c0.z + c1.z;
+          acc[i][j][4 * g + 3] += c0.w + c1.w;
+        }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mine[((i * CT + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  __syncthreads();
+  for (int e = tid; e < TMR * CT * 16 * 64; e += 64 * WAVES) {
+    const int l = e & 63, r = (e >> 6) & 15, ij = e >> 10;
+    const int i = ij / CT, j = ij % CT;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += reinterpret_cast<const float*>(skinny_lds + w * kWave)[(ij * 16 + r) * 64 + l];
+    const int64_t row = 32 * i + (l & 31);
+    const int64_t col = 32 * (ct + j) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+    if (row < M && col < N) {
+      if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne(v);
+      else static_cast<float*>(Dv)[row * ldd + col] = v;
+    }
+  }
+}
+
+template <int RB, int CT, int WAVES>
+void launch_skinny_res_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be,
+                           const uint8_t* bs, const uint8_t* br, int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
+  constexpr int TMR = RB > 32 ? 2 : 1;
+  constexpr int part = TMR * CT * 16 * 64 * 4, stage = TMR * 32 * 64 * 4;
+  constexpr int lds = WAVES * (part > stage ? part : stage);
+  static_assert(lds <= 128 * 1024, "per-wavefront patches must fit in LDS");
+  const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
+  if (bf) {
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<RB, CT, true, WAVES>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<RB, CT, true, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+  } else {
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<RB, CT, false, WAVES>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<RB, CT, false, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+  }
+}
+
+// Launch shapes as for gemm_skinny_kernel; fewer column tiles per workgroup as the rows (correction registers) grow.
+int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                      hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K, kTileBytes), gb = image_geom(N, K, kTileBytesE2M1);
+  const int64_t ct = (N + 31) / 32;
+  if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const int kt = (int)ga.k_tiles;
+  const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes, *br = bs + gb.scale_bytes;
+  const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
+  constexpr int64_t kEnough = 200;                          // workgroups
+#define MXP_RES(RB, CT, W) launch_skinny_res_cfg<RB, CT, W>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
+  // (16 wavefronts only where the kernel still fits 128 registers: 8 rows, one column tile)
+  if (M <= 8) {
+    if (ct / 4 >= kEnough) MXP_RES(8, 4, 8);
+    else if (ct / 2 >= kEnough) MXP_RES(8, 2, 8);
+    else if (wide) MXP_RES(8, 1, 16);
+    else MXP_RES(8, 1, 8);
+  } else if (M <= 16) {
+    if (ct / 2 >= kEnough) MXP_RES(16, 2, 8);
+    else MXP_RES(16, 1, 8);
+  } else if (M <= 32) {
+    MXP_RES(32, 1, 8);
+  } else {
+    MXP_RES(64, 1, 8);
+  }
+#undef MXP_RES
+  return launch_status();
+}
+
 // ---- skinny-M kernel on canonical weights -----------------------------------------------------------------------
 // The decode stage is bound by the weight bytes (Sec. 7.2), and an MXFP4+ weight is 4.5 bits per element in canonical
 // storage but 6.25 in the E2M3 image.  This kernel reads the canonical arrays and widens in registers: per chunk of 4
@@ -1236,6 +1455,10 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
     if (M <= 128 || image_geom(M, K).k_tiles < 4) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
+  if (b_kind == MXP_IMAGE_E2M1R) {      // decode-only image: 4-bit MXFP4+ weights with residual bytes
+    if (a_kind != MXP_IMAGE_E2M3 || M > 64) return MXP_ERR_UNSUPPORTED;
+    return launch_skinny_res(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  }
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
@@ -1322,9 +1545,10 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
 
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
                                   int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
   if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1 && a_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
   if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
+  if (b_kind == MXP_IMAGE_E2M1R && (a_kind != MXP_IMAGE_E2M3 || M > 64)) return MXP_ERR_UNSUPPORTED;
   if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd, 4 * kMaxGemmK);   // K of the images: up to four K segments
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
@@ -1390,7 +1614,7 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
     if (rc != MXP_OK) return rc;
     const bool b4 = fmtB == MXP_FMT_MXFP4;
     rc = is_fp6(fmtB) ? prepack_fp6_launch(B_elems, B_scales, nullptr, fmtB, N, K, 1, 0u, wb, s)
-         : b4         ? prepack_e2m1_launch(B_elems, B_scales, N, K, wb, s)
+         : b4         ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s)
                       : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
     if (rc != MXP_OK) return rc;
     return gemm_images(wa, MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
@@ -1433,9 +1657,9 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product); so does A
   // when both operands are plain MXFP4
   const bool b4 = fmtB == MXP_FMT_MXFP4, a4 = b4 && fmtA == MXP_FMT_MXFP4;
-  rc = a4 ? prepack_e2m1_launch(A_elems, A_scales, M, K, wa, s) : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+  rc = a4 ? prepack_e2m1_launch(A_elems, A_scales, nullptr, M, K, wa, s) : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
   if (rc != MXP_OK) return rc;
-  rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, N, K, wb, s) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
+  rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
   if (rc != MXP_OK) return rc;
   return gemm_images(wa, a4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
 }
@@ -1450,9 +1674,10 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
                               size_t workspace_bytes, void* stream) {
   using namespace mxp;
   if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
   const bool fp8 = fmtA == MXP_FMT_MXFP4PP;
   if (fp8 != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
+  if (b_kind == MXP_IMAGE_E2M1R && M > 64) return MXP_ERR_UNSUPPORTED;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;

@@ -80,7 +80,16 @@ def test_argument_errors_are_reported_not_launched():
     # image kinds
     assert L.mxp_prepack_e2m1(p, p, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_e2m1(p, None, 64, 64, p, 1 << 20, None) == -1
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 3, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 4, p, mxp.F32, 64, None) == -5
+    # the 4-bit MXFP4+ weight image with residual bytes: B side of the few-row product only
+    assert L.mxp_gemm_prepacked(65, 64, 64, p, mxp.IMAGE_E2M3, p, mxp.IMAGE_E2M1R, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_prepacked(8, 64, 64, p, mxp.IMAGE_E2M1, p, mxp.IMAGE_E2M1R, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_prepacked(8, 64, 64, p, mxp.IMAGE_E2M1R, p, mxp.IMAGE_E2M3, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_bf16a(65, 64, 64, p, mxp.BF16, 64, mxp.MXFP4P, p, mxp.IMAGE_E2M1R, p, mxp.F32, 64, p, 1 << 20, None) == -8
+    assert L.mxp_prepack_e2m1r(p, p, None, 64, 64, p, 1 << 20, None) == -1
+    assert L.mxp_prepack_e2m1r(p, p, p, 64, 48, p, 1 << 20, None) == -2
+    assert L.mxp_prepack_e2m1r(p, p, p, 64, 64, p, mxp.image_bytes_e2m1(64, 64), None) == -6
+    assert mxp.image_bytes_e2m1r(4096, 4096) == mxp.image_bytes_e2m1(4096, 4096) + 4096 * 128
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 2, p, mxp.F32, 64, None) == -8      # E4M3 images only in pairs
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 2, p, 1, p, mxp.F32, 64, None) == -8
     assert L.mxp_prepack_e4m3(p, p, p, mxp.MXFP4PP, 64, 64, p, 16, None) == -6

@@ -1294,3 +1294,79 @@ def test_tensors_beyond_4_gib_sampled():
     check_gemm(D[rows_d], ref, S, "activations beyond 4 GiB")
     del D, x, q
     torch.cuda.empty_cache()
+
+
+# ---- few-row product on MXFP4+ weights kept in 4-bit codes: BM_H in the FP4 MFMA, BM_L added per block (Eq. 3, Sec. 5.2) --
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (1, 33, 256), (5, 100, 512), (8, 12840, 256), (8, 25632, 512), (3, 26000, 4352),
+                                   (9, 300, 1024), (16, 12850, 256), (13, 1000, 4352), (17, 300, 1024), (32, 6400, 512),
+                                   (33, 100, 512), (40, 12850, 256), (64, 1000, 4352)])
+def test_gemm_few_rows_on_four_bit_mxfp4p_weights(M, N, K):
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    if N >= 100:
+        w[7, 32:64] = 0                                                  # flushed weight blocks: zeros, and values
+        w[9, 64:96] = 0x0100                                             # whose exponent field is below the flush limit
+        w[11, 0:32] = synth.f32_to_bf16_bits(np.full(32, 0.01, np.float32))
+        w[11, 31] = synth.f32_to_bf16_bits(np.array([-7.9], np.float32))[0]   # BM at the last position, all residual bits set
+    qa, qw = oracle.quantize(a, oracle.MXFP4P), oracle.quantize(w, oracle.MXFP4P)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
+    img_a = mxp.prepack(q_dev(qa), mxp.MXFP4P)
+    img_w = mxp.prepack_e2m1r(q_dev(qw))
+    assert img_w.numel() == mxp.image_bytes_e2m1r(N, K)
+    D = mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1R)
+    check_gemm(D, ref, S, "e2m1r %dx%dx%d" % (M, N, K))
+    # un-quantized activations, bf16 output
+    D2 = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, img_w, N, b_kind=mxp.IMAGE_E2M1R)
+    assert torch.equal(D, D2)
+    Db = mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1R, out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+def test_four_bit_mxfp4p_image_bytes_and_special_activations():
+    """The image: BM nibbles hold BM_H, the residual bytes BM_L and the position (checked against the oracle's codes);
+    then the product with activation blocks that are all-zero, flushed, tiny, tied and saturated."""
+    x = special_tensor(rows=37, K=160)
+    x[7, 3] = 1.0                                                        # (no NaN / Inf rows: those are the codec's business)
+    x[8, 40] = 2.0
+    w = synth.weights(96, 160, config_id=2, tensor_id=1, dtype="fp32")
+    qa, qw = oracle.quantize(x, oracle.MXFP4P), oracle.quantize(w, oracle.MXFP4P)
+    N, K = 96, 160
+    img = mxp.prepack_e2m1r(q_dev(qw)).cpu().numpy()
+    e, sc, ix = qw
+    k_tiles = (K + 127) // 128 * 2
+    row_tiles = 256 // 32
+    res = img[row_tiles * k_tiles * 1024 + (row_tiles // 4) * k_tiles * 256:].reshape(row_tiles, k_tiles, 2, 32)
+    codes = img[:row_tiles * k_tiles * 1024].reshape(row_tiles, k_tiles, 2, 32, 16)
+    for n in (0, 31, 32, 95):
+        for kb in range(K // 32):
+            nib = (e[n, kb * 16 + ix[n, kb] // 2] >> (4 * (ix[n, kb] % 2))) & 15
+            got = res[n // 32, kb // 2, kb % 2, n % 32]
+            live = sc[n, kb] not in (0, 255)
+            assert got == ((ix[n, kb] | ((nib & 3) << 5) | ((nib & 8) << 4)) if live else 0)
+            c = codes[n // 32, kb // 2, kb % 2, n % 32]
+            want = e[n, kb * 16:(kb + 1) * 16].copy()
+            if live:
+                hi = (nib & 8) | 6 | ((nib >> 2) & 1)
+                b, sh = ix[n, kb] // 2, 4 * (ix[n, kb] % 2)
+                want[b] = (want[b] & ~(15 << sh) & 255) | (hi << sh)
+            else:
+                want[:] = 0 if sc[n, kb] == 0 else want
+            assert (c == want).all()
+    for M in (8, 16, 37):
+        qa_m = tuple(t[:M] for t in qa)
+        ref, S = oracle.gemm(qa_m, oracle.MXFP4P, qw, oracle.MXFP4P)
+        D = mxp.gemm_prepacked(M, N, K, mxp.prepack(q_dev(qa_m), mxp.MXFP4P), mxp.prepack_e2m1r(q_dev(qw)), b_kind=mxp.IMAGE_E2M1R)
+        check_gemm(D, ref, S, "special activations, %d rows" % M)
+
+
+def test_gemm_full_size_decode_four_bit_mxfp4p_weights():
+    """The decode configuration and a 70B-sized layer through the 4-bit weight image, against the oracle (sampled)."""
+    for M, N, K, cfg in ((8, 4096, 4096, 2), (8, 28672, 8192, 5)):
+        a = synth.activations(M, K, config_id=cfg, tensor_id=0)
+        w = synth.weights(N, K, config_id=cfg, tensor_id=1)
+        qw = mxp.quantize(to_dev(w), mxp.MXFP4P)
+        D = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, mxp.prepack_e2m1r(qw), N, b_kind=mxp.IMAGE_E2M1R)
+        cols = np.unique(np.concatenate([np.random.default_rng(3).integers(0, N, 300), [0, 31, 32, N - 1]]))
+        qa_o, qw_o = oracle.quantize(a, oracle.MXFP4P), oracle.quantize(w[cols], oracle.MXFP4P)
+        ref, S = oracle.gemm(qa_o, oracle.MXFP4P, qw_o, oracle.MXFP4P)
+        check_gemm(D[:, torch.from_numpy(cols).cuda()], ref, S, "decode %dx%dx%d" % (M, N, K))
