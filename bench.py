@@ -388,10 +388,11 @@ def main():
         Md, Kd = Ad.shape
         Nd = Wd.shape[0]
         out = {}
-        for name, fmt_w in (("mxfp4p_weights", mxp.MXFP4P), ("mxfp4_weights", mxp.MXFP4)):
+        for name, fmt_w, kind in (("mxfp4p_weights", mxp.MXFP4P, mxp.IMAGE_E2M3), ("mxfp4_weights", mxp.MXFP4, mxp.IMAGE_E2M1),
+                                  ("mxfp4p_weights_four_bit_image", mxp.MXFP4P, mxp.IMAGE_E2M1R)):
             qwd = mxp.quantize(Wd, fmt_w)
-            kind = mxp.IMAGE_E2M1 if fmt_w == mxp.MXFP4 else mxp.IMAGE_E2M3
-            img = mxp.prepack_e2m1(qwd) if fmt_w == mxp.MXFP4 else mxp.prepack(qwd, fmt_w)
+            img = (mxp.prepack_e2m1(qwd) if kind == mxp.IMAGE_E2M1 else mxp.prepack_e2m1r(qwd) if kind == mxp.IMAGE_E2M1R
+                   else mxp.prepack(qwd, fmt_w))
             Dd = torch.empty((Md, Nd), dtype=torch.float32, device=dev)
             wsd = torch.empty(max(mxp.gemm_bf16a_workspace_bytes(Md, Kd), 16), dtype=torch.uint8, device=dev)
             for _ in range(3):
@@ -443,8 +444,10 @@ def main():
         qal = tuple(t[:Md].contiguous() for t in ql)
         img_al = mxp.prepack(qal, mxp.MXFP4P)
         Dl = torch.empty((Md, Nl), dtype=torch.float32, device=dev)
-        for name, kind in (("mxfp4p_weights", mxp.IMAGE_E2M3), ("mxfp4_weights", mxp.IMAGE_E2M1)):
-            img = mxp.prepack(ql, mxp.MXFP4P) if kind == mxp.IMAGE_E2M3 else mxp.prepack_e2m1(ql)
+        for name, kind in (("mxfp4p_weights", mxp.IMAGE_E2M3), ("mxfp4_weights", mxp.IMAGE_E2M1),
+                           ("mxfp4p_weights_four_bit_image", mxp.IMAGE_E2M1R)):
+            img = (mxp.prepack(ql, mxp.MXFP4P) if kind == mxp.IMAGE_E2M3 else mxp.prepack_e2m1(ql) if kind == mxp.IMAGE_E2M1
+                   else mxp.prepack_e2m1r(ql))
             for _ in range(20):
                 mxp.gemm_prepacked(Md, Nl, Kl, img_al, img, out=Dl, b_kind=kind)
             torch.cuda.synchronize()

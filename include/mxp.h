@@ -133,9 +133,10 @@ int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, 
  * bytes (Sec. 7.2): 4.5 bits per element as in canonical storage instead of the 6.25 of the E2M3 image.  The BM is
  * split as in Eq. 3 (Sec. 5.2): its nibble holds BM_H = 2^2 * 1.m2 as an ordinary E2M1 code, which the FP4 MFMA
  * multiplies like any other element, and BM_L = +-(m1 + m0/2) goes with the BM position into one residual byte per
- * block (sign << 7 | m1 m0 << 5 | index) behind the scales; the product kernel adds a[m][32 kb + index] * BM_L * 2^scale
- * for every weight block from the activation tile it already holds (one multiply-add per block and activation row).
- * Results are those of the E2M3 route up to fp32 summation order.  B operand only, next to an E2M3 A image, M <= 64
+ * block (sign << 7 | m1 m0 << 5 | index) behind the scales; BM_L is an E2M1 number too, so the product kernel adds the
+ * missing a[m][32 kb + index] * BM_L terms with a second MFMA per tile whose weight operand -- zero except for the
+ * BM_L code at the BM position of each block -- it builds in registers from the residual bytes.  Every product is exact;
+ * results equal those of the E2M3 route up to fp32 summation order.  B operand only, next to an E2M3 A image, M <= 64
  * (mxp_gemm_prepacked, mxp_gemm_bf16a); anything else returns MXP_ERR_UNSUPPORTED. */
 #define MXP_IMAGE_E2M1R 3
 size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K);

@@ -1007,52 +1007,36 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
 // ---- skinny-M kernel on MXFP4+ weights kept in 4-bit codes (E2M1 image + residual bytes) --------------------------
 // The decode stage is bound by the weight bytes (Sec. 7.2), and the E2M3 image spends 6.25 bits on an element that
 // canonical MXFP4+ stores in 4.5.  Here the weights stay 4-bit: the BM's nibble holds BM_H of Eq. 3 as an ordinary E2M1
-// code, so the FP4 MFMA forms every product except a[k_BM] * BM_L, one per weight block and activation row (Sec. 5.2:
-// the extra sparse product).  That term is added on the vector ALU: in the MFMA operand order a lane holds exactly one
-// weight block of a k-tile (column l % 32, block l / 32) and one activation block (row l % 32, block l / 32).  Each
-// k-tile, the lanes de-convert their activation blocks (one conversion instruction, with the block scale) into a
-// private LDS patch [row][64 k] of fp32 -- exact: four significant bits -- and every lane gathers, for each activation
-// row, the element at its weight block's BM position and accumulates a * (BM_L * 2^scale) in fp32.  RB = activation
-// rows covered (8, 16, 32, 64); the RB partial corrections per lane and column tile join the MFMA accumulators through
-// the same patch before the usual reduction over the wavefronts.  Everything else as in gemm_skinny_kernel.
-typedef int v6i __attribute__((ext_vector_type(6)));
-typedef float v32f __attribute__((ext_vector_type(32)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-template <int RB, int CT, bool OUT_BF16, int WAVES>
+// code, so the FP4 MFMA forms every product except a[k_BM] * BM_L, one per weight block and activation row -- the extra
+// sparse product of Sec. 5.2.  BM_L = +-(m1 + m0 / 2) is itself an E2M1 number (code sign | 0 m1 m0), so the missing
+// products are a second MFMA of the same activation tile with a weight tile that is zero except for that one nibble
+// per block; in the MFMA operand order a lane holds exactly one weight block, so it builds its 16 bytes of that tile
+// from the block's residual byte in registers (a shift and four selects) and nothing but the residual bytes is read
+// from memory.  The matrix pipe has the time: the kernel waits for weight bytes.  Everything else as in
+// gemm_skinny_kernel, whose launch shapes it shares.
+template <int TMR, int CT, bool OUT_BF16, int WAVES>
 __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                                      const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                                      const uint8_t* __restrict__ b_res, int k_tiles, int64_t M,
                                                                      int64_t N, void* __restrict__ Dv, int64_t ldd) {
-  constexpr int TMR = RB > 32 ? 2 : 1;
   constexpr int AT = kTileBytes, BT = kTileBytesE2M1;
   constexpr int CHUNK = CT == 4 ? 3 : (CT == 2 && WAVES == 16 ? 2 : 4);
-  constexpr int kPart = TMR * CT * 16 * 64 * 4;              // a wavefront's partial accumulators
-  constexpr int kStage = TMR * 32 * 64 * 4;                  // its de-converted activation tiles of one k-tile
-  constexpr int kWave = kPart > kStage ? kPart : kStage;     // bytes of LDS per wavefront (the two uses alternate)
-  static_assert(CT * RB * 256 <= kWave, "the corrections pass through the same patch");
   extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
+  float (*part)[TMR * CT][16][64] = reinterpret_cast<float (*)[TMR * CT][16][64]>(skinny_lds);   // [WAVES][TMR * CT][16][64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float* mine = reinterpret_cast<float*>(skinny_lds + wave * kWave);
-  const int half = lane >> 5;
   const int64_t ct = (int64_t)blockIdx.x * CT;
   const uint8_t* bt = b_el + ct * (int64_t)k_tiles * BT;
   const uint8_t* bs = b_sc + ((ct >> 2) * (int64_t)k_tiles) * 256 + lane * 4;
   const uint8_t* br = b_res + ct * (int64_t)k_tiles * 64 + lane;
   const int b_shift = (int)(ct & 3) * 8;
   v16f acc[TMR][CT];
-  float corr[CT][RB];
 #pragma unroll
   for (int i = 0; i < TMR; ++i)
 #pragma unroll
     for (int j = 0; j < CT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-#pragma unroll
-  for (int j = 0; j < CT; ++j)
-#pragma unroll
-    for (int m = 0; m < RB; ++m) corr[j][m] = 0.0f;
 
   const int n_chunks = (k_tiles + CHUNK - 1) / CHUNK;
   const int first = (int)((blockIdx.x * 5u) % (uint32_t)n_chunks);
@@ -1088,66 +1072,37 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
 #pragma unroll
-        for (int i = 0; i < TMR; ++i)
-#pragma unroll
-          for (int j = 0; j < CT; ++j) {
-            const v8i bv = {(int)b[c][j].x, (int)b[c][j].y, (int)b[c][j].z, (int)b[c][j].w, 0, 0, 0, 0};
-            switch (i * 4 + j) {
-              case 0: acc[i][j] = mfma<0, 0, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
-              case 1: acc[i][j] = mfma<0, 1, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
-              case 2: acc[i][j] = mfma<0, 2, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
-              case 3: acc[i][j] = mfma<0, 3, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
-              default: acc[i][j] = mfma<1, 0, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]); break;
-            }
-          }
-        // the BM_L products of this k-tile.  Activation tile -> fp32 in the patch: row 32 i + l % 32, k = 32 (l / 32) + e
-#pragma unroll
-        for (int i = 0; i < TMR; ++i) {
-          const uint32_t sbyte = (sa[c] >> (8 * i)) & 255u;
-          const v6i codes = {a[c][i][0], a[c][i][1], a[c][i][2], a[c][i][3], a[c][i][4], a[c][i][5]};
-          const v32f av = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(codes, __uint_as_float(sbyte << 23));
-          if (32 * i + (lane & 31) < M) {
-            float* dst = mine + (32 * i + (lane & 31)) * 64 + 32 * half;
-#pragma unroll
-            for (int e = 0; e < 32; e += 4) *reinterpret_cast<f32x4_t*>(dst + e) = (f32x4_t){av[e], av[e + 1], av[e + 2], av[e + 3]};
-          }
-        }
-#pragma unroll
         for (int j = 0; j < CT; ++j) {
+          const v8i bv = {(int)b[c][j].x, (int)b[c][j].y, (int)b[c][j].z, (int)b[c][j].w, 0, 0, 0, 0};
+          // the tile of BM_L codes: sign | 0 m1 m0 at the block's BM position, zeros elsewhere (no BM: residual byte 0)
           const uint32_t r = rs[c][j];
-          const uint32_t sw = (sb[c] >> (8 * j)) & 255u;
-          // BM_L * 2^(scale - 127) = +-(m1 m0) * 2^(scale - 128); zero residual bits for blocks without a BM
-          float lw = __builtin_ldexpf((float)((r >> 5) & 3u), (int)sw - 128);
-          lw = (r & 0x80u) ? -lw : lw;
-          const float* src = mine + 32 * half + (r & 31u);
+          const uint32_t word = (((r >> 5) & 3u) | ((r >> 4) & 8u)) << (4u * (r & 7u));
+          const uint32_t piece = (r >> 3) & 3u;
+          const v8i lv = {(int)(piece == 0u ? word : 0u), (int)(piece == 1u ? word : 0u), (int)(piece == 2u ? word : 0u),
+                          (int)(piece == 3u ? word : 0u), 0, 0, 0, 0};
 #pragma unroll
-          for (int m = 0; m < RB; ++m)
-            if (m < M) corr[j][m] = __builtin_fmaf(src[m * 64], lw, corr[j][m]);
+          for (int i = 0; i < TMR; ++i)
+            switch (i * 4 + j) {
+#define MXP_RES_MFMA(I, J)                                                                                        \
+  acc[i][j] = mfma<I, J, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
+  acc[i][j] = mfma<I, J, kFmtE2M1, kFmtE2M3>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
+  break
+              case 0: MXP_RES_MFMA(0, 0);
+              case 1: MXP_RES_MFMA(0, 1);
+              case 2: MXP_RES_MFMA(0, 2);
+              case 3: MXP_RES_MFMA(0, 3);
+              case 4: MXP_RES_MFMA(1, 0);
+              case 5: MXP_RES_MFMA(1, 1);
+              case 6: MXP_RES_MFMA(1, 2);
+              case 7: MXP_RES_MFMA(1, 3);
+              case 8: MXP_RES_MFMA(2, 0);
+              case 9: MXP_RES_MFMA(2, 1);
+              case 12: MXP_RES_MFMA(3, 0);
+              default: MXP_RES_MFMA(3, 1);
+#undef MXP_RES_MFMA
+            }
         }
       }
-    }
-  }
-  // corrections -> accumulator layout: lane l holds those of column l % 32 for every row; register r of lane l is
-  // row l % 32, column 8 (r / 4) + 4 (l / 32) + r % 4
-#pragma unroll
-  for (int j = 0; j < CT; ++j)
-#pragma unroll
-    for (int m = 0; m < RB; ++m) mine[(j * RB + m) * 64 + lane] = corr[j][m];
-#pragma unroll
-  for (int i = 0; i < TMR; ++i) {
-    const int row = 32 * i + (lane & 31);
-    if (row < RB) {
-#pragma unroll
-      for (int j = 0; j < CT; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float* p = mine + (j * RB + row) * 64 + 8 * g + 4 * half;
-          const f32x4_t c0 = *reinterpret_cast<const f32x4_t*>(p), c1 = *reinterpret_cast<const f32x4_t*>(p + 32);
-          acc[i][j][4 * g] += c0.x + c1.x;
-          acc[i][j][4 * g + 1] += c0.y + c1.y;
-          acc[i][j][4 * g + 2] += c0.z + c1.z;
-          acc[i][j][4 * g + 3] += c0.w + c1.w;
-        }
     }
   }
 #pragma unroll
@@ -1155,14 +1110,14 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
 #pragma unroll
     for (int j = 0; j < CT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mine[((i * CT + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+      for (int r = 0; r < 16; ++r) part[wave][i * CT + j][r][lane] = acc[i][j][r];
   __syncthreads();
   for (int e = tid; e < TMR * CT * 16 * 64; e += 64 * WAVES) {
     const int l = e & 63, r = (e >> 6) & 15, ij = e >> 10;
     const int i = ij / CT, j = ij % CT;
     float v = 0.0f;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) v += reinterpret_cast<const float*>(skinny_lds + w * kWave)[(ij * 16 + r) * 64 + l];
+    for (int w = 0; w < WAVES; ++w) v += part[w][ij][r][l];
     const int64_t row = 32 * i + (l & 31);
     const int64_t col = 32 * (ct + j) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
     if (row < M && col < N) {
@@ -1172,28 +1127,26 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
   }
 }
 
-template <int RB, int CT, int WAVES>
+template <int TMR, int CT, int WAVES>
 void launch_skinny_res_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be,
                            const uint8_t* bs, const uint8_t* br, int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
-  constexpr int TMR = RB > 32 ? 2 : 1;
-  constexpr int part = TMR * CT * 16 * 64 * 4, stage = TMR * 32 * 64 * 4;
-  constexpr int lds = WAVES * (part > stage ? part : stage);
-  static_assert(lds <= 128 * 1024, "per-wavefront patches must fit in LDS");
+  constexpr int lds = WAVES * TMR * CT * 16 * 64 * 4;
+  static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   if (bf) {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<RB, CT, true, WAVES>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<RB, CT, true, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   } else {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<RB, CT, false, WAVES>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<RB, CT, false, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   }
 }
 
-// Launch shapes as for gemm_skinny_kernel; fewer column tiles per workgroup as the rows (correction registers) grow.
+// Launch shapes: those of launch_skinny (the entry points admit up to 64 rows).
 int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                       hipStream_t s) {
   const ImageGeom ga = image_geom(M, K, kTileBytes), gb = image_geom(N, K, kTileBytesE2M1);
@@ -1203,20 +1156,17 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes, *br = bs + gb.scale_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   constexpr int64_t kEnough = 200;                          // workgroups
-#define MXP_RES(RB, CT, W) launch_skinny_res_cfg<RB, CT, W>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
-  // (16 wavefronts only where the kernel still fits 128 registers: 8 rows, one column tile)
-  if (M <= 8) {
-    if (ct / 4 >= kEnough) MXP_RES(8, 4, 8);
-    else if (ct / 2 >= kEnough) MXP_RES(8, 2, 8);
-    else if (wide) MXP_RES(8, 1, 16);
-    else MXP_RES(8, 1, 8);
-  } else if (M <= 16) {
-    if (ct / 2 >= kEnough) MXP_RES(16, 2, 8);
-    else MXP_RES(16, 1, 8);
-  } else if (M <= 32) {
-    MXP_RES(32, 1, 8);
+#define MXP_RES(TMR, CT, W) launch_skinny_res_cfg<TMR, CT, W>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
+  if (M <= 32) {
+    if (ct / 4 >= kEnough) MXP_RES(1, 4, 8);
+    else if (ct / 2 >= kEnough && wide) MXP_RES(1, 2, 16);
+    else if (ct / 2 >= kEnough) MXP_RES(1, 2, 8);
+    else if (wide) MXP_RES(1, 1, 16);
+    else MXP_RES(1, 1, 8);
   } else {
-    MXP_RES(64, 1, 8);
+    if (ct / 2 >= kEnough) MXP_RES(2, 2, 8);
+    else if (wide) MXP_RES(2, 1, 16);
+    else MXP_RES(2, 1, 8);
   }
 #undef MXP_RES
   return launch_status();
