@@ -87,7 +87,7 @@ def main():
                     help="only the timed steps and the per-stage pass (no format comparisons, decode shapes or probes): "
                          "the run whose kernel trace holds nothing but the step's own kernels")
     ap.add_argument("--out-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_w4a16", "gemm_decode_large", "dequantize", "copy"],
+    ap.add_argument("--only", default="all", choices=["all", "quantize", "quantize_t", "quantize_image", "prepack", "gemm", "gemm_e4m3", "gemm_fp6p", "gemm_w4a16", "gemm_decode_large", "gemm_decode_large_four_bit", "dequantize", "copy"],
                     help="profiling aid: run just one stage per step (the JSON line is then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -146,14 +146,14 @@ def main():
         W16 = to_dev(w_bits)
         qw16 = mxp.quantize(W16, mxp.MXFP4P)
         del W16
-    if args.only == "gemm_decode_large":   # 8 rows against a 70B-sized layer, random codes
+    if args.only in ("gemm_decode_large", "gemm_decode_large_four_bit"):   # 8 rows against a 70B-sized layer, random codes
         Nl, Kl = 28672, 8192
         gen = torch.Generator(device=dev)
         gen.manual_seed(7)
         ql = (torch.randint(0, 256, (Nl, Kl // 2), dtype=torch.uint8, device=dev, generator=gen),
               torch.randint(120, 134, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen),
               torch.randint(0, 32, (Nl, Kl // 32), dtype=torch.uint8, device=dev, generator=gen))
-        img_wl = mxp.prepack(ql, mxp.MXFP4P)
+        img_wl = mxp.prepack(ql, mxp.MXFP4P) if args.only == "gemm_decode_large" else mxp.prepack_e2m1r(ql)   # E2M3 image / 4-bit image
         img_al = mxp.prepack(tuple(t[:8].contiguous() for t in ql), mxp.MXFP4P)
         Dl = torch.empty((8, Nl), dtype=torch.float32, device=dev)
         del ql
@@ -167,6 +167,8 @@ def main():
             mxp.gemm(qa6, mxp.MXFP6P, qw6, mxp.MXFP6, out=D, workspace=ws6)
         elif args.only == "gemm_decode_large":
             mxp.gemm_prepacked(8, Nl, Kl, img_al, img_wl, out=Dl)
+        elif args.only == "gemm_decode_large_four_bit":
+            mxp.gemm_prepacked(8, Nl, Kl, img_al, img_wl, out=Dl, b_kind=mxp.IMAGE_E2M1R)
         elif args.only == "quantize":
             mxp.quantize_into(A, mxp.MXFP4P, *qa)
         elif args.only == "quantize_t":

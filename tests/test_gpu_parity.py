@@ -1194,6 +1194,7 @@ def test_readme_example_runs():
     torch.cuda.synchronize()
     assert env["d"].shape == (4096, 14336) and env["d6"].shape == (4096, 14336) and env["dw"].dtype == torch.float32
     assert torch.isfinite(env["d"]).all() and torch.isfinite(env["dpp"]).all()
+    assert env["dd"].shape == (8, 14336) and torch.allclose(env["dd"], env["d"][:8], rtol=1e-4, atol=1e-2)
 
 
 @pytest.mark.parametrize("seed", [21, 22])
