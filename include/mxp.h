@@ -223,11 +223,12 @@ int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, 
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* The decode stage (Sec. 7.2: few activation rows, bound by reading the weights): the same product for M <= 64 with
- * the weights W[N][K] left in canonical MXFP4 or MXFP4+ storage (4.25 / 4.5 bits per element instead of the image's
- * 4.25 / 6.25) and widened to MFMA operands inside the kernel.  A_image is an E2M3 image of the activations
+ * the weights W[N][K] left in canonical MXFP4 or MXFP4+ storage (no prepack step, no second copy of the weights); the
+ * 4-bit codes feed the FP4 MFMA and an MXFP4+ block gets the BM split of MXP_IMAGE_E2M1R inside the kernel (BM_H in
+ * place, BM_L in a second MFMA).  A_image is an E2M3 image of the activations
  * (mxp_prepack or mxp_quantize_image); mxp_gemm_decode_bf16a takes them un-quantized like mxp_gemm_bf16a, with the same
  * workspace.  K % 256 == 0; larger M, other K and MXFP4++ weights return MXP_ERR_UNSUPPORTED (use the image path).
- * Results are those of mxp_gemm_prepacked on the same operands (same products, K split and summed the same way). */
+ * Results are those of mxp_gemm_prepacked on the same operands up to fp32 summation order (every product is exact). */
 int mxp_gemm_decode(int64_t M, int64_t N, int64_t K, const void* A_image, const uint8_t* W_elems, const uint8_t* W_scales,
                     const uint8_t* W_idx, int fmtW, void* D, int d_dtype, int64_t ldd, void* stream);
 int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,

@@ -1173,41 +1173,13 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
 }
 
 // ---- skinny-M kernel on canonical weights -----------------------------------------------------------------------
-// The decode stage is bound by the weight bytes (Sec. 7.2), and an MXFP4+ weight is 4.5 bits per element in canonical
-// storage but 6.25 in the E2M3 image.  This kernel reads the canonical arrays and widens in registers: per chunk of 4
-// k-tiles a wavefront loads, for each of its column tiles, 32 rows x 128 contiguous bytes (8 blocks per row: full
-// lines), passes them through a private LDS patch into operand order (lane l gets the block of row l % 32, half
-// l / 32), widens the 32 nibbles to E2M3 codes with the BM as sign | 11 | mmm (Sec. 4.2) and feeds the MFMA; scale and
-// index bytes come as one 8-byte load per row.  Plain MXFP4 weights are fed as they are (E2M1 operand).  Everything
-// else -- A from its image, K split over the wavefronts, rotated walk, reduction through LDS -- as above.
-__device__ __forceinline__ uint32_t widen4_codes(uint32_t h) {   // 4 nibbles -> 4 six-bit codes, code = nibble << 2
-  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
-  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
-}
-
-// One block of 32 nibbles -> its 24-byte E2M3 operand; bm = BM position or >= 32 for none.
-__device__ __forceinline__ v8i widen_block(const u32x4 n, uint32_t bm) {
-  const uint32_t w[4] = {n.x, n.y, n.z, n.w};
-  uint32_t r[8];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    r[2 * j] = widen4_codes(w[j] & 0xFFFFu);
-    r[2 * j + 1] = widen4_codes(w[j] >> 16);
-  }
-  if (bm < 32u) {
-    const uint32_t piece = bm >> 2, sh = (bm & 3u) * 6u;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t c = (r[j] >> sh) & 0x3Fu;                 // s mmm 00
-      const uint32_t code = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);
-      const uint32_t patched = (r[j] & ~(0x3Fu << sh)) | (code << sh);
-      r[j] = piece == (uint32_t)j ? patched : r[j];
-    }
-  }
-  return (v8i){(int)(r[0] | (r[1] << 24)), (int)((r[1] >> 8) | (r[2] << 16)), (int)((r[2] >> 16) | (r[3] << 8)),
-               (int)(r[4] | (r[5] << 24)), (int)((r[5] >> 8) | (r[6] << 16)), (int)((r[6] >> 16) | (r[7] << 8)), 0, 0};
-}
-
+// The decode stage is bound by the weight bytes (Sec. 7.2).  This kernel reads the canonical arrays as they are: per
+// chunk of 4 k-tiles a wavefront loads, for each of its column tiles, 32 rows x 128 contiguous bytes (8 blocks per row:
+// full lines) and passes them through a private LDS patch into operand order (lane l gets the block of row l % 32,
+// half l / 32); scale and index bytes come as one 8-byte load per row.  The 4-bit codes are the FP4 MFMA's operand;
+// an MXFP4+ block gets the BM split of Eq. 3 in registers (BM_H in place, BM_L in a second MFMA), as in
+// gemm_skinny_res_kernel.  Everything else -- A from its image, K split over the wavefronts, rotated walk, reduction
+// through LDS -- as above.
 constexpr int kCanonPatchStride = 144;                        // bytes per patch row: 128 + 16 against bank conflicts
 constexpr int kCanonPatchBytes = 32 * kCanonPatchStride;
 
@@ -1223,7 +1195,7 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_canon_kernel(const uin
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   uint8_t* patch = skinny_lds + wave * kCanonPatchBytes;      // during the K loop
   const int64_t ct = (int64_t)blockIdx.x * CT;
-  constexpr int FB = PLUS ? kFmtE2M3 : kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  constexpr int FB = kFmtE2M1, FA = AT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
   const int n_in = lane & 31, h = lane >> 5;                  // operand role of this lane: row of the tile, half of the k-tile
   const int ld_row = lane >> 3, ld_piece = lane & 7;          // load role: row (+ 8 r) and 16-byte piece of the 128-byte run
   v16f acc[TMR][CT];
@@ -1289,9 +1261,21 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_canon_kernel(const uin
         uint32_t sbyte = ((2 * c + h) < 4 ? s8[j].x : s8[j].y) >> byte_sh & 0xFFu;
         uint32_t bm = 64u;
         if (PLUS) bm = (((2 * c + h) < 4 ? i8[j].x : i8[j].y) >> byte_sh) & 31u;
-        v8i b;
-        if (PLUS) b = widen_block(nib, (sbyte == 0u || sbyte == 255u) ? 64u : bm);
-        else b = (v8i){(int)nib.x, (int)nib.y, (int)nib.z, (int)nib.w, 0, 0, 0, 0};
+        // MXFP4+: the BM split of Eq. 3 as in gemm_skinny_res_kernel -- the BM's nibble becomes the E2M1 code of BM_H
+        // (sign | 11 | m2) and BM_L (sign | 0 m1 m0, an E2M1 number too) goes into a second operand that is zero elsewhere
+        uint32_t w[4] = {nib.x, nib.y, nib.z, nib.w}, l[4] = {0u, 0u, 0u, 0u};
+        if (PLUS && sbyte != 0u && sbyte != 255u) {
+          const uint32_t sh = 4u * (bm & 7u);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const uint32_t n4 = (w[p] >> sh) & 15u;
+            const bool here = (bm >> 3) == (uint32_t)p;
+            w[p] = here ? (w[p] & ~(15u << sh)) | (((n4 & 8u) | 6u | ((n4 >> 2) & 1u)) << sh) : w[p];
+            l[p] = here ? ((n4 & 8u) | (n4 & 3u)) << sh : 0u;
+          }
+        }
+        v8i b = {(int)w[0], (int)w[1], (int)w[2], (int)w[3], 0, 0, 0, 0};
+        const v8i lv = {(int)l[0], (int)l[1], (int)l[2], (int)l[3], 0, 0, 0, 0};
         if (sbyte == 0u) {                                    // flushed (or absent) block: zeros, whatever the nibbles say
           b = (v8i){0, 0, 0, 0, 0, 0, 0, 0};
           sbyte = 127u;
@@ -1300,10 +1284,15 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_canon_kernel(const uin
 #pragma unroll
           for (int i = 0; i < TMR; ++i)
             switch (i) {
-              case 0: acc[i][j] = mfma<0, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
-              case 1: acc[i][j] = mfma<1, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
-              case 2: acc[i][j] = mfma<2, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
-              default: acc[i][j] = mfma<3, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte); break;
+#define MXP_CANON_MFMA(I)                                                                               \
+  acc[i][j] = mfma<I, 0, FB, FA>(a[c][i], b, acc[i][j], (int)sa[c], (int)sbyte);                         \
+  if (PLUS) acc[i][j] = mfma<I, 0, FB, FA>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sbyte);              \
+  break
+              case 0: MXP_CANON_MFMA(0);
+              case 1: MXP_CANON_MFMA(1);
+              case 2: MXP_CANON_MFMA(2);
+              default: MXP_CANON_MFMA(3);
+#undef MXP_CANON_MFMA
             }
         }
       }
