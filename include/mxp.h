@@ -136,8 +136,10 @@ int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int64_t rows, 
  * block (sign << 7 | m1 m0 << 5 | index) behind the scales; BM_L is an E2M1 number too, so the product kernel adds the
  * missing a[m][32 kb + index] * BM_L terms with a second MFMA per tile whose weight operand -- zero except for the
  * BM_L code at the BM position of each block -- it builds in registers from the residual bytes.  Every product is exact;
- * results equal those of the E2M3 route up to fp32 summation order.  B operand only, next to an E2M3 A image, M <= 64
- * (mxp_gemm_prepacked, mxp_gemm_bf16a); anything else returns MXP_ERR_UNSUPPORTED. */
+ * results equal those of the E2M3 route up to fp32 summation order.  B operand only, M <= 64 (mxp_gemm_prepacked,
+ * mxp_gemm_bf16a), next to an E2M3 A image or, for MXFP4++ activations (Sec. 4.3), an E4M3 A image -- the MFMA takes an
+ * FP8 and an FP4 operand, so MXFP4++ activations meet MXFP4+ (this kind) and plain MXFP4 (MXP_IMAGE_E2M1) weights in
+ * their 4-bit codes when M <= 64, with the error bound of the E4M3 images; anything else returns MXP_ERR_UNSUPPORTED. */
 #define MXP_IMAGE_E2M1R 3
 size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K);
 int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K,

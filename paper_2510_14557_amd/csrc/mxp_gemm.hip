@@ -998,7 +998,7 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
     else launch_skinny_out<1, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else {
     if (ct / 2 >= kEnough) launch_skinny_out<2, 2, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else if (wide && BT != kTileBytesE4M3) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    else if (wide && BT != kTileBytesE4M3 && AT != kTileBytesE4M3) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
     else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);   // (E4M3 fragments: 16 wavefronts would spill)
   }
   return launch_status();
@@ -1014,12 +1014,15 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
 // from the block's residual byte in registers (a shift and four selects) and nothing but the residual bytes is read
 // from memory.  The matrix pipe has the time: the kernel waits for weight bytes.  Everything else as in
 // gemm_skinny_kernel, whose launch shapes it shares.
-template <int TMR, int CT, bool OUT_BF16, int WAVES>
+// AT: the activation image's tile bytes -- E2M3, or E4M3 for MXFP4++ activations (Sec. 4.3; the MFMA takes an FP8 and an FP4 operand).
+template <int TMR, int CT, bool OUT_BF16, int WAVES, int AT>
 __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                                      const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                                      const uint8_t* __restrict__ b_res, int k_tiles, int64_t M,
                                                                      int64_t N, void* __restrict__ Dv, int64_t ldd) {
-  constexpr int AT = kTileBytes, BT = kTileBytesE2M1;
+  constexpr int BT = kTileBytesE2M1;
+  constexpr int FA = AT == kTileBytes ? kFmtE2M3 : kFmtE4M3;
+  static_assert(AT == kTileBytes || AT == kTileBytesE4M3, "activation image: E2M3 or E4M3");
   constexpr int CHUNK = CT == 4 ? 3 : (CT == 2 && WAVES == 16 ? 2 : 4);
   extern __shared__ __attribute__((aligned(16))) uint8_t skinny_lds[];
   float (*part)[TMR * CT][16][64] = reinterpret_cast<float (*)[TMR * CT][16][64]>(skinny_lds);   // [WAVES][TMR * CT][16][64]
@@ -1059,13 +1062,18 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
 #pragma unroll
       for (int i = 0; i < TMR; ++i) {
         const uint8_t* ta = a_el + ((int64_t)i * k_tiles + kt) * AT;
-        u32x4 alo = {0, 0, 0, 0};
-        u32x2 ahi = {0, 0};
+        u32x4 alo = {0, 0, 0, 0}, ahi = {0, 0, 0, 0};
         if (32 * i + (lane & 31) < M) {
           alo = *reinterpret_cast<const u32x4*>(ta + lane * 16);
-          ahi = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+          if (AT == kTileBytes) {
+            const u32x2 h2 = *reinterpret_cast<const u32x2*>(ta + 1024 + lane * 8);
+            ahi.x = h2.x;
+            ahi.y = h2.y;
+          } else {
+            ahi = *reinterpret_cast<const u32x4*>(ta + 1024 + lane * 16);
+          }
         }
-        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+        a[c][i] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, (int)ahi.z, (int)ahi.w};
       }
     }
 #pragma unroll
@@ -1084,8 +1092,8 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
           for (int i = 0; i < TMR; ++i)
             switch (i * 4 + j) {
 #define MXP_RES_MFMA(I, J)                                                                                        \
-  acc[i][j] = mfma<I, J, kFmtE2M1, kFmtE2M3>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
-  acc[i][j] = mfma<I, J, kFmtE2M1, kFmtE2M3>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
+  acc[i][j] = mfma<I, J, kFmtE2M1, FA>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
+  acc[i][j] = mfma<I, J, kFmtE2M1, FA>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
   break
               case 0: MXP_RES_MFMA(0, 0);
               case 1: MXP_RES_MFMA(0, 1);
@@ -1127,36 +1135,37 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
   }
 }
 
-template <int TMR, int CT, int WAVES>
+template <int TMR, int CT, int WAVES, int AT>
 void launch_skinny_res_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be,
                            const uint8_t* bs, const uint8_t* br, int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
   constexpr int lds = WAVES * TMR * CT * 16 * 64 * 4;
   static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   if (bf) {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   } else {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   }
 }
 
 // Launch shapes: those of launch_skinny (the entry points admit up to 64 rows).
+template <int AT>
 int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                       hipStream_t s) {
-  const ImageGeom ga = image_geom(M, K, kTileBytes), gb = image_geom(N, K, kTileBytesE2M1);
+  const ImageGeom ga = image_geom(M, K, AT), gb = image_geom(N, K, kTileBytesE2M1);
   const int64_t ct = (N + 31) / 32;
   if (ct > 2147483647LL || ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes, *br = bs + gb.scale_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   constexpr int64_t kEnough = 200;                          // workgroups
-#define MXP_RES(TMR, CT, W) launch_skinny_res_cfg<TMR, CT, W>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
+#define MXP_RES(TMR, CT, W) launch_skinny_res_cfg<TMR, CT, W, AT>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
   if (M <= 32) {
     if (ct / 4 >= kEnough) MXP_RES(1, 4, 8);
     else if (ct / 2 >= kEnough && wide) MXP_RES(1, 2, 16);
@@ -1165,7 +1174,7 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
     else MXP_RES(1, 1, 8);
   } else {
     if (ct / 2 >= kEnough) MXP_RES(2, 2, 8);
-    else if (wide) MXP_RES(2, 1, 16);
+    else if (wide && AT != kTileBytesE4M3) MXP_RES(2, 1, 16);   // (E4M3 fragments: 16 wavefronts would spill)
     else MXP_RES(2, 1, 8);
   }
 #undef MXP_RES
@@ -1388,15 +1397,20 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
   // E4M3 images (the MXFP4++ product, Sec. 4.3): the pipelined kernel, or the two-stage one for few rows / short K
+  if (b_kind == MXP_IMAGE_E2M1R) {      // decode-only image: 4-bit MXFP4+ weights with residual bytes
+    if (a_kind == MXP_IMAGE_E2M1 || M > 64) return MXP_ERR_UNSUPPORTED;
+    if (a_kind == MXP_IMAGE_E4M3) return launch_skinny_res<kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    return launch_skinny_res<kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  }
+  if (a_kind == MXP_IMAGE_E4M3 && b_kind == MXP_IMAGE_E2M1) {   // MXFP4++ activations x plain MXFP4 weights, few rows
+    if (M > 64) return MXP_ERR_UNSUPPORTED;
+    return launch_skinny<kTileBytesE2M1, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  }
   if (a_kind == MXP_IMAGE_E4M3) {
     using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
     if (M <= 64) return launch_skinny<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     if (M <= 128 || image_geom(M, K).k_tiles < 4) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  }
-  if (b_kind == MXP_IMAGE_E2M1R) {      // decode-only image: 4-bit MXFP4+ weights with residual bytes
-    if (a_kind != MXP_IMAGE_E2M3 || M > 64) return MXP_ERR_UNSUPPORTED;
-    return launch_skinny_res(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
@@ -1487,8 +1501,10 @@ extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
   if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1 && a_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
   if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
-  if (b_kind == MXP_IMAGE_E2M1R && (a_kind != MXP_IMAGE_E2M3 || M > 64)) return MXP_ERR_UNSUPPORTED;
-  if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
+  if (b_kind == MXP_IMAGE_E2M1R && (a_kind == MXP_IMAGE_E2M1 || M > 64)) return MXP_ERR_UNSUPPORTED;
+  // E4M3 images pair with each other; few rows of E4M3 activations (MXFP4++) also with the 4-bit weight images
+  const bool b_four = b_kind == MXP_IMAGE_E2M1 || b_kind == MXP_IMAGE_E2M1R;
+  if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3) && !(a_kind == MXP_IMAGE_E4M3 && b_four && M <= 64)) return MXP_ERR_UNSUPPORTED;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd, 4 * kMaxGemmK);   // K of the images: up to four K segments
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1615,7 +1631,8 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
   if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
   if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
   const bool fp8 = fmtA == MXP_FMT_MXFP4PP;
-  if (fp8 != (b_kind == MXP_IMAGE_E4M3)) return MXP_ERR_UNSUPPORTED;
+  const bool b_four = b_kind == MXP_IMAGE_E2M1 || b_kind == MXP_IMAGE_E2M1R;
+  if (fp8 != (b_kind == MXP_IMAGE_E4M3) && !(fp8 && b_four && M <= 64)) return MXP_ERR_UNSUPPORTED;
   if (b_kind == MXP_IMAGE_E2M1R && M > 64) return MXP_ERR_UNSUPPORTED;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);

@@ -91,7 +91,7 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_prepack_e2m1r(p, p, p, 64, 64, p, mxp.image_bytes_e2m1(64, 64), None) == -6
     assert mxp.image_bytes_e2m1r(4096, 4096) == mxp.image_bytes_e2m1(4096, 4096) + 4096 * 128
     assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 2, p, mxp.F32, 64, None) == -8      # E4M3 images only in pairs
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, 2, p, 1, p, mxp.F32, 64, None) == -8
+    assert L.mxp_gemm_prepacked(65, 64, 64, p, 2, p, 1, p, mxp.F32, 64, None) == -8      # (few rows: E4M3 activations x 4-bit weights run)
     assert L.mxp_prepack_e4m3(p, p, p, mxp.MXFP4PP, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_e4m3(p, p, None, mxp.MXFP4PP, 64, 64, p, 1 << 20, None) == -1
     assert L.mxp_prepack_e4m3(p, p, p, mxp.MXFP6P, 64, 64, p, 1 << 20, None) == -5

@@ -1372,3 +1372,22 @@ def test_gemm_full_size_decode_four_bit_mxfp4p_weights():
         qa_o, qw_o = oracle.quantize(a, oracle.MXFP4P), oracle.quantize(w[cols], oracle.MXFP4P)
         ref, S = oracle.gemm(qa_o, oracle.MXFP4P, qw_o, oracle.MXFP4P)
         check_gemm(D[:, torch.from_numpy(cols).cuda()], ref, S, "decode %dx%dx%d" % (M, N, K))
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (1, 33, 256), (8, 25632, 512), (3, 26000, 4352), (16, 12850, 256),
+                                   (33, 100, 512), (40, 12850, 256), (64, 1000, 4352)])
+def test_gemm_few_rows_mxfp4pp_activations_on_four_bit_weights(M, N, K):
+    """MXFP4++ activations (Sec. 4.3; E4M3 image, converted on the fly) x MXFP4+ or plain MXFP4 weights kept 4-bit."""
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    qa = oracle.quantize(a, oracle.MXFP4PP)
+    for fw, pack, kind in (("mxfp4p", mxp.prepack_e2m1r, mxp.IMAGE_E2M1R), ("mxfp4", mxp.prepack_e2m1, mxp.IMAGE_E2M1)):
+        qw = oracle.quantize(w, FMT[fw][1])
+        ref, S = oracle.gemm(qa, oracle.MXFP4PP, qw, FMT[fw][1])
+        img_w = pack(q_dev(qw))
+        D = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4PP, img_w, N, b_kind=kind)
+        check_gemm_e4m3(D, ref, S, "mxfp4++ x %s %dx%dx%d" % (fw, M, N, K))
+        D2 = mxp.gemm_prepacked(M, N, K, mxp.prepack_e4m3(q_dev(qa), mxp.MXFP4PP), img_w, a_kind=mxp.IMAGE_E4M3, b_kind=kind)
+        assert torch.equal(D, D2)
+    with pytest.raises(mxp.MxpError):                                   # more than 64 rows: E4M3 weight images only
+        mxp.gemm_prepacked(65, N, K, mxp.prepack_e4m3(q_dev(qa), mxp.MXFP4PP), img_w, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E2M1)
