@@ -210,15 +210,19 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,
              void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Same product from images built earlier with mxp_prepack (weights are packed once, when they are loaded). */
+/* Same product from images built earlier (weights are packed once, when they are loaded).  Kinds that go together:
+ *   A E2M3 with B E2M3 or E2M1 (any M), or B E2M1R (M <= 64);   A E2M1 with B E2M1;   A E4M3 with B E4M3 (any M), or
+ *   B E2M1 / E2M1R (M <= 64).  Unknown kinds return MXP_ERR_FORMAT, other pairings MXP_ERR_UNSUPPORTED.  K is the images' K
+ *   (for six-bit images of several K segments: n_seg * K rounded up to 128). */
 int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image, int b_kind,
                        void* D, int d_dtype, int64_t ldd, void* stream);
 
 /* Activations given un-quantized (A[M][K], MXP_F32 or MXP_BF16, row stride lda): quantized on the fly to fmtA on
  * the same stream, then multiplied with the prepacked weight image (Sec. 7.1: activations are converted at run time,
  * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes.  fmtA = MXP_FMT_MXFP4PP
- * needs b_kind = MXP_IMAGE_E4M3 and mxp_image_bytes_e4m3(M, K) bytes of workspace, and an E4M3 weight image is taken
- * with that fmtA only (other pairings return MXP_ERR_UNSUPPORTED). */
+ * makes an E4M3 image of the activations: it needs mxp_image_bytes_e4m3(M, K) bytes of workspace and b_kind =
+ * MXP_IMAGE_E4M3, or, for M <= 64, a 4-bit weight image (MXP_IMAGE_E2M1, MXP_IMAGE_E2M1R); an E4M3 weight image is taken
+ * with that fmtA only, and MXP_IMAGE_E2M1R with M <= 64 only (other pairings return MXP_ERR_UNSUPPORTED). */
 size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K);
 int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
                    const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,
