@@ -1198,7 +1198,7 @@ def test_readme_example_runs():
     assert env["dd"].shape == (8, 14336) and torch.allclose(env["dd"], env["d"][:8], rtol=1e-4, atol=1e-2)
 
 
-@pytest.mark.parametrize("seed", [21, 22])
+@pytest.mark.parametrize("seed", [21, 22, 23, 24])
 def test_random_shapes_every_product_path(seed):
     """A seeded sweep over ragged shapes and format pairs: every product entry point against the oracle."""
     W = oracle.wide
@@ -1223,6 +1223,13 @@ def test_random_shapes_every_product_path(seed):
             img = mxp.prepack_e2m1(q_dev(qb)) if fb == "mxfp4" else mxp.prepack(q_dev(qb), FMT[fb][0])
             D2 = mxp.gemm_bf16a(to_dev(a), FMT[fa][0], img, N, b_kind=mxp.IMAGE_E2M1 if fb == "mxfp4" else mxp.IMAGE_E2M3)
             check_gemm(D2, ref, S, "bf16a %s x %s %s" % (fa, fb, what))
+        # few rows: the weights kept in 4-bit codes (MXFP4+ with residual bytes, plain MXFP4), activations MXFP4+ or MXFP4++
+        if M <= 64 and fb != "mxfp4pp" and fa != "mxfp4":
+            img4 = mxp.prepack_e2m1(q_dev(qb)) if fb == "mxfp4" else mxp.prepack_e2m1r(q_dev(qb))
+            D4 = mxp.gemm_bf16a(to_dev(a), FMT[fa][0], img4, N, b_kind=mxp.IMAGE_E2M1 if fb == "mxfp4" else mxp.IMAGE_E2M1R)
+            (check_gemm_e4m3 if fa == "mxfp4pp" else check_gemm)(D4, ref, S, "4-bit weights %s x %s %s" % (fa, fb, what))
+            if fb == "mxfp4p" and K % 256 == 0 and fa == "mxfp4p":
+                check_gemm(mxp.gemm_decode_bf16a(to_dev(a), mxp.MXFP4P, q_dev(qb), mxp.MXFP4P), ref, S, "canonical weights " + what)
         # un-quantized activations x weights of any format
         fw = rng.choice(list(FMT) + list(WIDE))
         a64 = synth.bf16_bits_to_f32(a).astype(np.float64)
