@@ -123,7 +123,10 @@ def main():
     qa = (torch.empty((M, K // 2), dtype=torch.uint8, device=dev), torch.empty((M, K // 32), dtype=torch.uint8, device=dev),
           torch.empty((M, K // 32), dtype=torch.uint8, device=dev))
     img_a = torch.empty(mxp.image_bytes(M, K), dtype=torch.uint8, device=dev)
-    img_w = torch.empty(mxp.image_bytes(N, K), dtype=torch.uint8, device=dev)
+    # few rows (decode): the MXFP4+ weights stay 4-bit (E2M1 image with residual bytes); otherwise the E2M3 image
+    few_rows = M <= 64 and args.only == "all"
+    img_w = torch.empty(mxp.image_bytes_e2m1r(N, K) if few_rows else mxp.image_bytes(N, K), dtype=torch.uint8, device=dev)
+    w_kind = mxp.IMAGE_E2M1R if few_rows else mxp.IMAGE_E2M3
     D = torch.empty((M, N), dtype=out_dt, device=dev)
     back = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
 
@@ -192,12 +195,15 @@ def main():
         mxp.quantize_image(A, mxp.MXFP4P, out=img_a, q_out=qa)
         if ev is not None:
             ev[1].record()
-        mxp.prepack(qw, mxp.MXFP4P, out=img_w)
+        if few_rows:
+            mxp.prepack_e2m1r(qw, out=img_w)
+        else:
+            mxp.prepack(qw, mxp.MXFP4P, out=img_w)
         if ev is not None:
             ev[2].record()
         if gemm_ev is not None:
             gemm_ev[0].record()
-        mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D)
+        mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D, b_kind=w_kind)
         if gemm_ev is not None:
             gemm_ev[1].record()
         if ev is not None:
@@ -249,7 +255,7 @@ def main():
                        "step": "quantize(A) -> canonical + image in one pass, image(W) -> scaled-MFMA GEMM -> dequantize(A)"},
             "roofline": {"bound": "mfma", "achieved": gemm_tflops_core, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                          "frac": gemm_tflops_core / PEAK_FP4_TFLOPS, "traffic": traffic_from_profiles(args.workload, args.out_dtype),
-                         "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_kernel", "kernel_ms": gemm_ms},
+                         "kernel": "gemm_kernel_dma" if M > 64 else "gemm_skinny_res_kernel", "kernel_ms": gemm_ms},
             "stages_ms": stage_ms,
         }
         if M <= 64:                                          # few rows: bound by reading the weight image once
@@ -277,11 +283,11 @@ def main():
         torch.cuda.synchronize()
         return ev2[0].elapsed_time(ev2[1]) / n
 
-    gemm_pp_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, mxp.IMAGE_E2M3)
+    gemm_pp_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, w_kind)
     # the same product with the other output type (bf16 = the fp32 result rounded once, half the output bytes)
     other_dt = torch.bfloat16 if out_dt == torch.float32 else torch.float32
     D_other = torch.empty((M, N), dtype=other_dt, device=dev)
-    gemm_pp_other_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, mxp.IMAGE_E2M3, out=D_other)
+    gemm_pp_other_ms = timed_gemm(img_a, mxp.IMAGE_E2M3, img_w, w_kind, out=D_other)
     del D_other
     W4 = to_dev(w_bits)
     img_w4 = mxp.prepack_e2m1(mxp.quantize(W4, mxp.MXFP4))
