@@ -145,6 +145,16 @@ size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K);
 int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K,
                       void* image, size_t image_bytes, void* stream);
 
+/* MXP_IMAGE_E2M1X: the same idea for MXFP4++ weights (Sec. 4.3; MXFP4+ weights are the case delta = 0), again 4.5 bits per
+ * element.  The 4-bit codes stay as they are, the BM's nibble included, and the residual byte is the canonical index byte
+ * (position | delta << 5).  The product kernel's first MFMA takes the codes without the BM, scaled by the block's scale
+ * lowered by delta; the second takes the BM alone, as the E2M3 code sign | 11 | mmm (Sec. 4.2), with the block's own
+ * scale.  Same size (mxp_image_bytes_e2m1r), same pairing rules and limits as MXP_IMAGE_E2M1R; fmt is MXP_FMT_MXFP4P or
+ * MXP_FMT_MXFP4PP (plain MXFP4: MXP_ERR_UNSUPPORTED -- use mxp_prepack_e2m1). */
+#define MXP_IMAGE_E2M1X 4
+int mxp_prepack_e2m1x(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                      void* image, size_t image_bytes, void* stream);
+
 /* MXP_IMAGE_E4M3: the image kind for MXFP4++ operands (Sec. 4.3; it takes MXFP4 and MXFP4+ operands too).  The ordinary
  * elements of an MXFP4++ block are scaled by 2^(shared_exp - delta) and its BM by 2^shared_exp, which one E2M3 code per
  * element cannot express; with the block's scale byte set to (scale byte - delta + 2) every element is an FP8 E4M3
@@ -211,8 +221,8 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
              void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Same product from images built earlier (weights are packed once, when they are loaded).  Kinds that go together:
- *   A E2M3 with B E2M3 or E2M1 (any M), or B E2M1R (M <= 64);   A E2M1 with B E2M1;   A E4M3 with B E4M3 (any M), or
- *   B E2M1 / E2M1R (M <= 64).  Unknown kinds return MXP_ERR_FORMAT, other pairings MXP_ERR_UNSUPPORTED.  K is the images' K
+ *   A E2M3 with B E2M3 or E2M1 (any M), or B E2M1R / E2M1X (M <= 64);   A E2M1 with B E2M1;   A E4M3 with B E4M3 (any M),
+ *   or B E2M1 / E2M1R / E2M1X (M <= 64).  Unknown kinds return MXP_ERR_FORMAT, other pairings MXP_ERR_UNSUPPORTED.  K is the images' K
  *   (for six-bit images of several K segments: n_seg * K rounded up to 128). */
 int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image, int b_kind,
                        void* D, int d_dtype, int64_t ldd, void* stream);
@@ -221,8 +231,8 @@ int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int
  * the same stream, then multiplied with the prepacked weight image (Sec. 7.1: activations are converted at run time,
  * weights ahead of time).  workspace must hold mxp_gemm_bf16a_workspace_bytes(M, K) bytes.  fmtA = MXP_FMT_MXFP4PP
  * makes an E4M3 image of the activations: it needs mxp_image_bytes_e4m3(M, K) bytes of workspace and b_kind =
- * MXP_IMAGE_E4M3, or, for M <= 64, a 4-bit weight image (MXP_IMAGE_E2M1, MXP_IMAGE_E2M1R); an E4M3 weight image is taken
- * with that fmtA only, and MXP_IMAGE_E2M1R with M <= 64 only (other pairings return MXP_ERR_UNSUPPORTED). */
+ * MXP_IMAGE_E4M3, or, for M <= 64, a 4-bit weight image (MXP_IMAGE_E2M1, MXP_IMAGE_E2M1R, MXP_IMAGE_E2M1X); an E4M3 weight
+ * image is taken with that fmtA only, and MXP_IMAGE_E2M1R / MXP_IMAGE_E2M1X with M <= 64 only (other pairings return MXP_ERR_UNSUPPORTED). */
 size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K);
 int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda, int fmtA,
                    const void* B_image, int b_kind, void* D, int d_dtype, int64_t ldd,

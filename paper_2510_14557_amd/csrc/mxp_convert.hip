@@ -196,7 +196,10 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
 // its nibble becomes the E2M1 code of BM_H = 2^2 * 1.m2 (sign | 11 | m2), and the rest, BM_L = +-(m1 + m0 / 2), goes
 // with the BM position into one residual byte per block, sign << 7 | m1 m0 << 5 | index, stored in the lane order of
 // the tiles ([row tile][k-tile][64]) behind the scale part.
-template <bool RES>
+// RES == 2: an MXFP4+ or MXFP4++ operand with the BM's nibble left as it is and the residual byte = the canonical index
+// byte (position | delta << 5; 0 for all-zero and NaN blocks): the product kernel takes the BM out of the 4-bit operand
+// and feeds it as an E2M3 code with the block's own scale, the other elements with the scale lowered by delta (Sec. 4.3).
+template <int RES>
 __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                            const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
                                                            int64_t k_tiles, uint8_t* __restrict__ img_elems,
@@ -212,13 +215,14 @@ __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restri
   const uint32_t slot = (kb_in & 1u) * 32u + r_in;
   const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
   u32x4 v = {0, 0, 0, 0};
-  uint32_t sbyte = 127u, res = 0u;
+  uint32_t sbyte = RES == 2 ? 0u : 127u, res = 0u;   // (RES == 2: absent blocks must read as blocks without a BM)
   if (row < rows && kb < nbk) {
     const int64_t b = row * nbk + kb;
     v = __builtin_nontemporal_load(elems + b);
     sbyte = scales[b];
     if (sbyte == 0u) v = (u32x4){0, 0, 0, 0};
-    if (RES && sbyte != 0u && sbyte != 255u) {
+    if (RES == 2 && sbyte != 0u && sbyte != 255u) res = bm_idx[b];
+    if (RES == 1 && sbyte != 0u && sbyte != 255u) {
       const uint32_t bm = bm_idx[b] & 31u, sh = 4u * (bm & 7u);
       uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -352,21 +356,21 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
   return launch_status();
 }
 
-// bm_idx == nullptr: plain E2M1 image; else the E2M1 image of an MXFP4+ operand with its residual bytes behind it
+// mode 0: plain E2M1 image; 1: MXFP4+ operand, BM split, residual bytes behind the scales; 2: MXFP4+ / MXFP4++ operand,
+// BM nibble in place, index bytes behind the scales
 int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
-                        hipStream_t stream) {
+                        hipStream_t stream, int mode) {
   const ImageGeom g = image_geom(rows, K, kTileBytesE2M1);
   uint8_t* ie = static_cast<uint8_t*>(image);
   uint8_t* is = ie + g.elem_bytes;
   uint8_t* ir = is + g.scale_bytes;
   const int64_t n_wg = patch_grid((g.k_tiles + 3) / 4, g.row_tiles / 4);
   if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
-  if (bm_idx)
-    hipLaunchKernelGGL(prepack_e2m1_kernel<true>, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems),
-                       scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
-  else
-    hipLaunchKernelGGL(prepack_e2m1_kernel<false>, dim3((unsigned)n_wg), dim3(256), 0, stream, reinterpret_cast<const u32x4*>(elems),
-                       scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  const dim3 grid((unsigned)n_wg);
+  const u32x4* e = reinterpret_cast<const u32x4*>(elems);
+  if (mode == 2) hipLaunchKernelGGL(prepack_e2m1_kernel<2>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  else if (mode == 1) hipLaunchKernelGGL(prepack_e2m1_kernel<1>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  else hipLaunchKernelGGL(prepack_e2m1_kernel<0>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
   return launch_status();
 }
 
@@ -459,7 +463,7 @@ extern "C" int mxp_prepack_e2m1(const uint8_t* elems, const uint8_t* scales, int
   if (!elems || !scales || !image) return MXP_ERR_NULL;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(image)) return MXP_ERR_ALIGN;
   if (image_bytes < (size_t)image_geom(rows, K, kTileBytesE2M1).total()) return MXP_ERR_WORKSPACE;
-  return prepack_e2m1_launch(elems, scales, nullptr, rows, K, image, static_cast<hipStream_t>(stream));
+  return prepack_e2m1_launch(elems, scales, nullptr, rows, K, image, static_cast<hipStream_t>(stream), 0);
 }
 
 extern "C" size_t mxp_image_bytes_e2m1r(int64_t rows, int64_t K) {
@@ -476,7 +480,19 @@ extern "C" int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, co
   if (!elems || !scales || !bm_idx || !image) return MXP_ERR_NULL;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(bm_idx) || !aligned16(image)) return MXP_ERR_ALIGN;
   if (image_bytes < mxp_image_bytes_e2m1r(rows, K)) return MXP_ERR_WORKSPACE;
-  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream));
+  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream), 1);
+}
+
+extern "C" int mxp_prepack_e2m1x(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                                 void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return fmt == MXP_FMT_MXFP4 ? MXP_ERR_UNSUPPORTED : MXP_ERR_FORMAT;
+  if (rows < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !bm_idx || !image) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(bm_idx) || !aligned16(image)) return MXP_ERR_ALIGN;
+  if (image_bytes < mxp_image_bytes_e2m1r(rows, K)) return MXP_ERR_WORKSPACE;
+  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream), 2);
 }
 
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,

@@ -16,7 +16,7 @@ namespace mxp {
 int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                    void* image, hipStream_t stream);
 int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
-                        hipStream_t stream);
+                        hipStream_t stream, int mode);
 int prepack_e4m3_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                         void* image, hipStream_t stream);
 int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, uint8_t* elems,
@@ -1015,7 +1015,10 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
 // from memory.  The matrix pipe has the time: the kernel waits for weight bytes.  Everything else as in
 // gemm_skinny_kernel, whose launch shapes it shares.
 // AT: the activation image's tile bytes -- E2M3, or E4M3 for MXFP4++ activations (Sec. 4.3; the MFMA takes an FP8 and an FP4 operand).
-template <int TMR, int CT, bool OUT_BF16, int WAVES, int AT>
+// XM: the image keeps the BM's nibble in place and its residual bytes are the canonical index bytes (position | delta << 5):
+// MXFP4+ and MXFP4++ weights (Sec. 4.3).  The first MFMA then takes the 4-bit codes without the BM, scaled by the block's scale
+// lowered by delta; the second takes the BM alone as an E2M3 code (sign | 11 | mmm, Sec. 4.2) with the block's own scale.
+template <int TMR, int CT, bool OUT_BF16, int WAVES, int AT, bool XM>
 __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                                      const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                                      const uint8_t* __restrict__ b_res, int k_tiles, int64_t M,
@@ -1079,21 +1082,47 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) {
       if (k0 + c < k_tiles) {
+        uint32_t sbm = sb[c];                                   // XM: the scale bytes of the first MFMA, each lowered by its delta
+        if (XM) {
+#pragma unroll
+          for (int j = 0; j < CT; ++j) sbm -= (rs[c][j] >> 5) << (8 * j);
+        }
 #pragma unroll
         for (int j = 0; j < CT; ++j) {
-          const v8i bv = {(int)b[c][j].x, (int)b[c][j].y, (int)b[c][j].z, (int)b[c][j].w, 0, 0, 0, 0};
-          // the tile of BM_L codes: sign | 0 m1 m0 at the block's BM position, zeros elsewhere (no BM: residual byte 0)
           const uint32_t r = rs[c][j];
-          const uint32_t word = (((r >> 5) & 3u) | ((r >> 4) & 8u)) << (4u * (r & 7u));
-          const uint32_t piece = (r >> 3) & 3u;
-          const v8i lv = {(int)(piece == 0u ? word : 0u), (int)(piece == 1u ? word : 0u), (int)(piece == 2u ? word : 0u),
-                          (int)(piece == 3u ? word : 0u), 0, 0, 0, 0};
+          v8i bv, lv;
+          if (!XM) {
+            bv = (v8i){(int)b[c][j].x, (int)b[c][j].y, (int)b[c][j].z, (int)b[c][j].w, 0, 0, 0, 0};
+            // the tile of BM_L codes: sign | 0 m1 m0 at the block's BM position, zeros elsewhere (no BM: residual byte 0)
+            const uint32_t word = (((r >> 5) & 3u) | ((r >> 4) & 8u)) << (4u * (r & 7u));
+            const uint32_t piece = (r >> 3) & 3u;
+            lv = (v8i){(int)(piece == 0u ? word : 0u), (int)(piece == 1u ? word : 0u), (int)(piece == 2u ? word : 0u),
+                       (int)(piece == 3u ? word : 0u), 0, 0, 0, 0};
+          } else {
+            const uint32_t sw = (sb[c] >> (8 * j)) & 255u;
+            const bool live = sw != 0u && sw != 255u;             // all-zero, absent and NaN blocks have no BM
+            const uint32_t idx = r & 31u, piece = idx >> 3, sh4 = 4u * (idx & 7u);
+            uint32_t w[4] = {b[c][j].x, b[c][j].y, b[c][j].z, b[c][j].w};
+            const uint32_t nib = ((piece == 0u ? w[0] : piece == 1u ? w[1] : piece == 2u ? w[2] : w[3]) >> sh4) & 15u;
+#pragma unroll
+            for (int p4 = 0; p4 < 4; ++p4) w[p4] = (live && piece == (uint32_t)p4) ? w[p4] & ~(15u << sh4) : w[p4];
+            bv = (v8i){(int)w[0], (int)w[1], (int)w[2], (int)w[3], 0, 0, 0, 0};
+            // the BM as an E2M3 code at element idx of a 32 x 6-bit string
+            const uint32_t code = live ? (((nib & 8u) << 2) | 0x18u | (nib & 7u)) : 0u;
+            const uint32_t o = 6u * idx, d = o >> 5, s6 = o & 31u;
+            const uint32_t lo = code << s6, hi = s6 > 26u ? code >> (32u - s6) : 0u;
+            uint32_t e[6];
+#pragma unroll
+            for (int q6 = 0; q6 < 6; ++q6) e[q6] = (d == (uint32_t)q6 ? lo : 0u) | (d + 1u == (uint32_t)q6 ? hi : 0u);
+            lv = (v8i){(int)e[0], (int)e[1], (int)e[2], (int)e[3], (int)e[4], (int)e[5], 0, 0};
+          }
+          constexpr int FL = XM ? kFmtE2M3 : kFmtE2M1;
 #pragma unroll
           for (int i = 0; i < TMR; ++i)
             switch (i * 4 + j) {
 #define MXP_RES_MFMA(I, J)                                                                                        \
-  acc[i][j] = mfma<I, J, kFmtE2M1, FA>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
-  acc[i][j] = mfma<I, J, kFmtE2M1, FA>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sb[c]);                     \
+  acc[i][j] = mfma<I, J, kFmtE2M1, FA>(a[c][i], bv, acc[i][j], (int)sa[c], (int)sbm);                             \
+  acc[i][j] = mfma<I, J, FL, FA>(a[c][i], lv, acc[i][j], (int)sa[c], (int)sb[c]);                                 \
   break
               case 0: MXP_RES_MFMA(0, 0);
               case 1: MXP_RES_MFMA(0, 1);
@@ -1135,27 +1164,27 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
   }
 }
 
-template <int TMR, int CT, int WAVES, int AT>
+template <int TMR, int CT, int WAVES, int AT, bool XM>
 void launch_skinny_res_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, const uint8_t* as, const uint8_t* be,
                            const uint8_t* bs, const uint8_t* br, int kt, int64_t M, int64_t N, void* D, int64_t ldd) {
   constexpr int lds = WAVES * TMR * CT * 16 * 64 * 4;
   static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   if (bf) {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT, XM>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT, XM>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   } else {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT>),
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT, XM>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
-    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
+    hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT, XM>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   }
 }
 
 // Launch shapes: those of launch_skinny (the entry points admit up to 64 rows).
-template <int AT>
+template <int AT, bool XM>
 int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
                       hipStream_t s) {
   const ImageGeom ga = image_geom(M, K, AT), gb = image_geom(N, K, kTileBytesE2M1);
@@ -1165,7 +1194,7 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes, *br = bs + gb.scale_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   constexpr int64_t kEnough = 200;                          // workgroups
-#define MXP_RES(TMR, CT, W) launch_skinny_res_cfg<TMR, CT, W, AT>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
+#define MXP_RES(TMR, CT, W) launch_skinny_res_cfg<TMR, CT, W, AT, XM>(bf, ct, s, ae, as, be, bs, br, kt, M, N, D, ldd)
   if (M <= 32) {
     if (ct / 4 >= kEnough) MXP_RES(1, 4, 8);
     else if (ct / 2 >= kEnough && wide) MXP_RES(1, 2, 16);
@@ -1397,10 +1426,14 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   const uint8_t* Ai = static_cast<const uint8_t*>(A_image);
   const uint8_t* Bi = static_cast<const uint8_t*>(B_image);
   // E4M3 images (the MXFP4++ product, Sec. 4.3): the pipelined kernel, or the two-stage one for few rows / short K
-  if (b_kind == MXP_IMAGE_E2M1R) {      // decode-only image: 4-bit MXFP4+ weights with residual bytes
+  if (b_kind == MXP_IMAGE_E2M1R || b_kind == MXP_IMAGE_E2M1X) {      // decode-only images: 4-bit MX+ weights with residual bytes
     if (a_kind == MXP_IMAGE_E2M1 || M > 64) return MXP_ERR_UNSUPPORTED;
-    if (a_kind == MXP_IMAGE_E4M3) return launch_skinny_res<kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-    return launch_skinny_res<kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    if (b_kind == MXP_IMAGE_E2M1X) {
+      if (a_kind == MXP_IMAGE_E4M3) return launch_skinny_res<kTileBytesE4M3, true>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+      return launch_skinny_res<kTileBytes, true>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    }
+    if (a_kind == MXP_IMAGE_E4M3) return launch_skinny_res<kTileBytesE4M3, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    return launch_skinny_res<kTileBytes, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
   if (a_kind == MXP_IMAGE_E4M3 && b_kind == MXP_IMAGE_E2M1) {   // MXFP4++ activations x plain MXFP4 weights, few rows
     if (M > 64) return MXP_ERR_UNSUPPORTED;
@@ -1498,12 +1531,13 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
 
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
                                   int b_kind, void* D, int d_dtype, int64_t ldd, void* stream) {
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R && b_kind != MXP_IMAGE_E2M1X) return MXP_ERR_FORMAT;
   if (a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1 && a_kind != MXP_IMAGE_E4M3) return MXP_ERR_FORMAT;
   if (a_kind == MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E2M1) return MXP_ERR_UNSUPPORTED;
-  if (b_kind == MXP_IMAGE_E2M1R && (a_kind == MXP_IMAGE_E2M1 || M > 64)) return MXP_ERR_UNSUPPORTED;
+  const bool b_res = b_kind == MXP_IMAGE_E2M1R || b_kind == MXP_IMAGE_E2M1X;
+  if (b_res && (a_kind == MXP_IMAGE_E2M1 || M > 64)) return MXP_ERR_UNSUPPORTED;
   // E4M3 images pair with each other; few rows of E4M3 activations (MXFP4++) also with the 4-bit weight images
-  const bool b_four = b_kind == MXP_IMAGE_E2M1 || b_kind == MXP_IMAGE_E2M1R;
+  const bool b_four = b_kind == MXP_IMAGE_E2M1 || b_res;
   if ((a_kind == MXP_IMAGE_E4M3) != (b_kind == MXP_IMAGE_E4M3) && !(a_kind == MXP_IMAGE_E4M3 && b_four && M <= 64)) return MXP_ERR_UNSUPPORTED;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd, 4 * kMaxGemmK);   // K of the images: up to four K segments
   if (rc != MXP_OK || M == 0 || N == 0) return rc;
@@ -1569,7 +1603,7 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
     if (rc != MXP_OK) return rc;
     const bool b4 = fmtB == MXP_FMT_MXFP4;
     rc = is_fp6(fmtB) ? prepack_fp6_launch(B_elems, B_scales, nullptr, fmtB, N, K, 1, 0u, wb, s)
-         : b4         ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s)
+         : b4         ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s, 0)
                       : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
     if (rc != MXP_OK) return rc;
     return gemm_images(wa, MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
@@ -1612,9 +1646,9 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product); so does A
   // when both operands are plain MXFP4
   const bool b4 = fmtB == MXP_FMT_MXFP4, a4 = b4 && fmtA == MXP_FMT_MXFP4;
-  rc = a4 ? prepack_e2m1_launch(A_elems, A_scales, nullptr, M, K, wa, s) : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+  rc = a4 ? prepack_e2m1_launch(A_elems, A_scales, nullptr, M, K, wa, s, 0) : prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
   if (rc != MXP_OK) return rc;
-  rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
+  rc = b4 ? prepack_e2m1_launch(B_elems, B_scales, nullptr, N, K, wb, s, 0) : prepack_launch(B_elems, B_scales, B_idx, fmtB, N, K, wb, s);
   if (rc != MXP_OK) return rc;
   return gemm_images(wa, a4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
 }
@@ -1629,11 +1663,11 @@ extern "C" int mxp_gemm_bf16a(int64_t M, int64_t N, int64_t K, const void* A, in
                               size_t workspace_bytes, void* stream) {
   using namespace mxp;
   if (fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
-  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R) return MXP_ERR_FORMAT;
+  if (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1 && b_kind != MXP_IMAGE_E4M3 && b_kind != MXP_IMAGE_E2M1R && b_kind != MXP_IMAGE_E2M1X) return MXP_ERR_FORMAT;
   const bool fp8 = fmtA == MXP_FMT_MXFP4PP;
-  const bool b_four = b_kind == MXP_IMAGE_E2M1 || b_kind == MXP_IMAGE_E2M1R;
+  const bool b_res = b_kind == MXP_IMAGE_E2M1R || b_kind == MXP_IMAGE_E2M1X, b_four = b_kind == MXP_IMAGE_E2M1 || b_res;
   if (fp8 != (b_kind == MXP_IMAGE_E4M3) && !(fp8 && b_four && M <= 64)) return MXP_ERR_UNSUPPORTED;
-  if (b_kind == MXP_IMAGE_E2M1R && M > 64) return MXP_ERR_UNSUPPORTED;
+  if (b_res && M > 64) return MXP_ERR_UNSUPPORTED;
   if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
   int rc = check_gemm(M, N, K, D, d_dtype, ldd);
   if (rc != MXP_OK || M == 0 || N == 0) return rc;

@@ -15,13 +15,13 @@ F32, BF16 = 0, 1
 MXFP4, MXFP4P, MXFP4PP = 0, 1, 2
 MXFP6, MXFP6P, MXFP8, MXFP8P = 3, 4, 5, 6          # conversion and de-conversion only
 _CODE_BITS = {MXFP4: 4, MXFP4P: 4, MXFP4PP: 4, MXFP6: 6, MXFP6P: 6, MXFP8: 8, MXFP8P: 8}
-IMAGE_E2M3, IMAGE_E2M1, IMAGE_E4M3, IMAGE_E2M1R = 0, 1, 2, 3
+IMAGE_E2M3, IMAGE_E2M1, IMAGE_E4M3, IMAGE_E2M1R, IMAGE_E2M1X = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -65,6 +65,8 @@ def lib():
     L.mxp_image_bytes_e2m1r.restype = sz
     L.mxp_prepack_e2m1r.argtypes = [vp, vp, vp, i64, i64, vp, sz, vp]
     L.mxp_prepack_e2m1r.restype = i32
+    L.mxp_prepack_e2m1x.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
+    L.mxp_prepack_e2m1x.restype = i32
     L.mxp_image_bytes_e4m3.argtypes = [i64, i64]
     L.mxp_image_bytes_e4m3.restype = sz
     L.mxp_prepack_e4m3.argtypes = [vp, vp, vp, i32, i64, i64, vp, sz, vp]
@@ -289,6 +291,16 @@ def prepack_e2m1r(q, out: torch.Tensor | None = None):
     if out is None:
         out = torch.empty(image_bytes_e2m1r(rows, K), dtype=torch.uint8, device=elems.device)
     _check(lib().mxp_prepack_e2m1r(_p(elems), _p(scales), _p(idx), rows, K, _p(out), out.numel(), _stream()), "mxp_prepack_e2m1r")
+    return out
+
+
+def prepack_e2m1x(q, fmt: int = MXFP4PP, out: torch.Tensor | None = None):
+    """MXFP4+ / MXFP4++ weights -> 4-bit image with index bytes (IMAGE_E2M1X): the B side of the few-row product."""
+    elems, scales, idx = q
+    rows, K = elems.shape[0], elems.shape[1] * 2
+    if out is None:
+        out = torch.empty(image_bytes_e2m1r(rows, K), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_e2m1x(_p(elems), _p(scales), _p(idx), fmt, rows, K, _p(out), out.numel(), _stream()), "mxp_prepack_e2m1x")
     return out
 
 

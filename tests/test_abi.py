@@ -80,7 +80,12 @@ def test_argument_errors_are_reported_not_launched():
     # image kinds
     assert L.mxp_prepack_e2m1(p, p, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_e2m1(p, None, 64, 64, p, 1 << 20, None) == -1
-    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 4, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(64, 64, 64, p, 0, p, 5, p, mxp.F32, 64, None) == -5
+    assert L.mxp_gemm_prepacked(65, 64, 64, p, mxp.IMAGE_E2M3, p, mxp.IMAGE_E2M1X, p, mxp.F32, 64, None) == -8
+    assert L.mxp_prepack_e2m1x(p, p, p, mxp.MXFP4, 64, 64, p, 1 << 20, None) == -8
+    assert L.mxp_prepack_e2m1x(p, p, p, mxp.MXFP6, 64, 64, p, 1 << 20, None) == -5
+    assert L.mxp_prepack_e2m1x(p, p, None, mxp.MXFP4PP, 64, 64, p, 1 << 20, None) == -1
+    assert L.mxp_prepack_e2m1x(p, p, p, mxp.MXFP4PP, 64, 64, p, 16, None) == -6
     # the 4-bit MXFP4+ weight image with residual bytes: B side of the few-row product only
     assert L.mxp_gemm_prepacked(65, 64, 64, p, mxp.IMAGE_E2M3, p, mxp.IMAGE_E2M1R, p, mxp.F32, 64, None) == -8
     assert L.mxp_gemm_prepacked(8, 64, 64, p, mxp.IMAGE_E2M1, p, mxp.IMAGE_E2M1R, p, mxp.F32, 64, None) == -8

@@ -1398,3 +1398,32 @@ def test_gemm_few_rows_mxfp4pp_activations_on_four_bit_weights(M, N, K):
         assert torch.equal(D, D2)
     with pytest.raises(mxp.MxpError):                                   # more than 64 rows: E4M3 weight images only
         mxp.gemm_prepacked(65, N, K, mxp.prepack_e4m3(q_dev(qa), mxp.MXFP4PP), img_w, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E2M1)
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 512, 4096), (1, 33, 256), (8, 25632, 512), (3, 26000, 4352), (16, 12850, 256),
+                                   (33, 100, 160), (40, 12850, 256), (64, 1000, 4352)])
+@pytest.mark.parametrize("fw", ["mxfp4pp", "mxfp4p"])
+def test_gemm_few_rows_on_four_bit_mxfp4pp_weights(M, N, K, fw):
+    """MXFP4++ (and MXFP4+) weights kept 4-bit with their index bytes (Sec. 4.3): the BM leaves the FP4 operand and enters
+    a second MFMA as an E2M3 code with the block's own scale; MXFP4+ and MXFP4++ activations."""
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    if N >= 100:
+        w[7, 32:64] = 0                                                  # flushed weight blocks
+        w[9, 64:96] = 0x0100
+        w[11, 0:32] = synth.f32_to_bf16_bits(np.full(32, 0.01, np.float32))      # every delta up to 7, BM first and last
+        w[11, 31] = synth.f32_to_bf16_bits(np.array([-7.9], np.float32))[0]
+        w[12, 0:32] = synth.f32_to_bf16_bits(np.full(32, 0.3, np.float32))
+        w[12, 0] = synth.f32_to_bf16_bits(np.array([5.5], np.float32))[0]
+    qw = oracle.quantize(w, FMT[fw][1])
+    img_w = mxp.prepack_e2m1x(q_dev(qw), FMT[fw][0])
+    for fa in ("mxfp4p", "mxfp4pp"):
+        qa = oracle.quantize(a, FMT[fa][1])
+        ref, S = oracle.gemm(qa, FMT[fa][1], qw, FMT[fw][1])
+        D = mxp.gemm_bf16a(to_dev(a), FMT[fa][0], img_w, N, b_kind=mxp.IMAGE_E2M1X)
+        (check_gemm_e4m3 if fa == "mxfp4pp" else check_gemm)(D, ref, S, "e2m1x %s x %s %dx%dx%d" % (fa, fw, M, N, K))
+    img_a = mxp.prepack(q_dev(oracle.quantize(a, oracle.MXFP4P)), mxp.MXFP4P)
+    ref, S = oracle.gemm(oracle.quantize(a, oracle.MXFP4P), oracle.MXFP4P, qw, FMT[fw][1])
+    D32 = mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1X)
+    check_gemm(D32, ref, S, "e2m1x prepacked %s %dx%dx%d" % (fw, M, N, K))
+    assert torch.equal(mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1X, out_dtype=torch.bfloat16), D32.to(torch.bfloat16))
