@@ -1101,19 +1101,21 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_res_kernel(const uint8
           } else {
             const uint32_t sw = (sb[c] >> (8 * j)) & 255u;
             const bool live = sw != 0u && sw != 255u;             // all-zero, absent and NaN blocks have no BM
-            const uint32_t idx = r & 31u, piece = idx >> 3, sh4 = 4u * (idx & 7u);
+            const uint32_t idx = r & 31u, piece = idx >> 3, in8 = idx & 7u, sh4 = 4u * in8;
             uint32_t w[4] = {b[c][j].x, b[c][j].y, b[c][j].z, b[c][j].w};
             const uint32_t nib = ((piece == 0u ? w[0] : piece == 1u ? w[1] : piece == 2u ? w[2] : w[3]) >> sh4) & 15u;
+            const uint32_t out4 = live ? nib << sh4 : 0u;         // xor takes the BM's nibble out of its dword
 #pragma unroll
-            for (int p4 = 0; p4 < 4; ++p4) w[p4] = (live && piece == (uint32_t)p4) ? w[p4] & ~(15u << sh4) : w[p4];
+            for (int p4 = 0; p4 < 4; ++p4) w[p4] ^= piece == (uint32_t)p4 ? out4 : 0u;
             bv = (v8i){(int)w[0], (int)w[1], (int)w[2], (int)w[3], 0, 0, 0, 0};
-            // the BM as an E2M3 code at element idx of a 32 x 6-bit string
+            // the BM as an E2M3 code at element idx of a 32 x 6-bit string: 8 elements are 48 bits, so group `piece` starts at
+            // bit 0 or 16 of dword 3 (piece / 2) and the code, shifted to its place in the group, spans at most two dwords
             const uint32_t code = live ? (((nib & 8u) << 2) | 0x18u | (nib & 7u)) : 0u;
-            const uint32_t o = 6u * idx, d = o >> 5, s6 = o & 31u;
-            const uint32_t lo = code << s6, hi = s6 > 26u ? code >> (32u - s6) : 0u;
-            uint32_t e[6];
-#pragma unroll
-            for (int q6 = 0; q6 < 6; ++q6) e[q6] = (d == (uint32_t)q6 ? lo : 0u) | (d + 1u == (uint32_t)q6 ? hi : 0u);
+            const uint64_t v48 = (uint64_t)code << (6u * in8);
+            const uint32_t lo = (uint32_t)v48, hi = (uint32_t)(v48 >> 32);
+            const bool odd = (piece & 1u) != 0u, upper = piece >= 2u;
+            const uint32_t t0 = odd ? 0u : lo, t1 = odd ? lo << 16 : hi, t2 = odd ? __builtin_amdgcn_alignbit(hi, lo, 16) : 0u;
+            const uint32_t e[6] = {upper ? 0u : t0, upper ? 0u : t1, upper ? 0u : t2, upper ? t0 : 0u, upper ? t1 : 0u, upper ? t2 : 0u};
             lv = (v8i){(int)e[0], (int)e[1], (int)e[2], (int)e[3], (int)e[4], (int)e[5], 0, 0};
           }
           constexpr int FL = XM ? kFmtE2M3 : kFmtE2M1;
