@@ -1304,14 +1304,17 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_skinny_canon_kernel(const uin
         // MXFP4+: the BM split of Eq. 3 as in gemm_skinny_res_kernel -- the BM's nibble becomes the E2M1 code of BM_H
         // (sign | 11 | m2) and BM_L (sign | 0 m1 m0, an E2M1 number too) goes into a second operand that is zero elsewhere
         uint32_t w[4] = {nib.x, nib.y, nib.z, nib.w}, l[4] = {0u, 0u, 0u, 0u};
-        if (PLUS && sbyte != 0u && sbyte != 255u) {
-          const uint32_t sh = 4u * (bm & 7u);
+        if (PLUS) {
+          const bool live = sbyte != 0u && sbyte != 255u;
+          const uint32_t sh = 4u * (bm & 7u), piece = bm >> 3;
+          const uint32_t n4 = ((piece == 0u ? w[0] : piece == 1u ? w[1] : piece == 2u ? w[2] : w[3]) >> sh) & 15u;
+          // s m2 m1 m0 -> s 1 1 m2 by xor; s 0 m1 m0 beside it
+          const uint32_t flip = live ? (n4 ^ ((n4 & 8u) | 6u | ((n4 >> 2) & 1u))) << sh : 0u;
+          const uint32_t low = live ? (n4 & 11u) << sh : 0u;
 #pragma unroll
           for (int p = 0; p < 4; ++p) {
-            const uint32_t n4 = (w[p] >> sh) & 15u;
-            const bool here = (bm >> 3) == (uint32_t)p;
-            w[p] = here ? (w[p] & ~(15u << sh)) | (((n4 & 8u) | 6u | ((n4 >> 2) & 1u)) << sh) : w[p];
-            l[p] = here ? ((n4 & 8u) | (n4 & 3u)) << sh : 0u;
+            w[p] ^= piece == (uint32_t)p ? flip : 0u;
+            l[p] = piece == (uint32_t)p ? low : 0u;
           }
         }
         v8i b = {(int)w[0], (int)w[1], (int)w[2], (int)w[3], 0, 0, 0, 0};
