@@ -215,6 +215,7 @@ size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when
  * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product), MXFP8 x MXFP8; 0 for a pair it does not
  * take and for pairs with MXFP8+, which need none */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);   /* the same function under its short name */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
              const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,
@@ -262,12 +263,6 @@ int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void* A, int a_
 int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, int a_dtype, int64_t lda,
                    const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW,
                    void* D, int d_dtype, int64_t ldd, void* stream);
-
-/* Measurement aid (no paper passage: it serves the roofline): runs nothing but block-scaled MFMAs on register-resident
- * pseudo-random operands of the given image kinds (E2M3 / E2M1 in any mix, or both E4M3), 256 workgroups x 4 wavefronts x iters x 16 MFMAs of 32x32x64
- * (2 * 65536 flop each); seed 0 gives all-zero operands.  sink receives 65536 floats.  Timing it gives the MFMA rate
- * the chip sustains at its power limit, the measured ceiling next to the nominal 10.1 PFLOP/s. */
-int mxp_probe_mfma(int a_kind, int b_kind, int iters, uint32_t seed, float* sink, void* stream);
 
 const char* mxp_status_string(int status);
 int mxp_version(void);

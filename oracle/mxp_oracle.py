@@ -1,4 +1,6 @@
-"""ctypes front-end of oracle/mxp_oracle.c (argument marshalling only; all arithmetic is in the C file)."""
+"""ctypes front-end of oracle/mxp_oracle.c.  Conversion, de-conversion and the MX x MX product are computed in the C
+file; this module marshals arguments, and `gemm_w4a16` additionally forms its float64 matrix product with numpy (the
+plain definition, on operands the C file de-converted)."""
 import ctypes as C
 import os
 

@@ -1,4 +1,6 @@
-"""ctypes front-end of oracle/mxw_oracle.c: the six- and eight-bit MX / MX+ formats (argument marshalling only)."""
+"""ctypes front-end of oracle/mxw_oracle.c: the six- and eight-bit MX / MX+ formats.  Conversion and de-conversion are
+computed in the C file; `gemm` forms the float64 matrix product of the de-converted operands with numpy (the plain
+definition of the product)."""
 import ctypes as C
 
 import numpy as np

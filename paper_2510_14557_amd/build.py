@@ -7,6 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmxp.so")
+PROBE_DIR = os.path.join(HERE, "probe")
+PROBE_LIB = os.path.join(PROBE_DIR, "libmxp_probe.so")      # bench-only measurement aid, not part of the product ABI
 SOURCES = ["mxp_quantize.hip", "mxp_convert.hip", "mxp_gemm.hip", "mxp_w4a16.hip", "mxp_wide.hip"]
 HEADERS = [os.path.join(CSRC, "mxp_common.h"), os.path.join(CSRC, "mxp_decode.h"), os.path.join(ROOT, "include", "mxp.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -25,7 +27,11 @@ def up_to_date():
         return False
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, s) for s in SOURCES] + HEADERS + [os.path.abspath(__file__)]
-    return all(os.path.getmtime(d) <= t for d in deps)
+    if not os.path.exists(PROBE_LIB):
+        return False
+    tp = os.path.getmtime(PROBE_LIB)
+    pdeps = [os.path.join(PROBE_DIR, f) for f in ("mxp_probe.hip", "mxp_probe.h")] + HEADERS
+    return all(os.path.getmtime(d) <= t for d in deps) and all(os.path.getmtime(d) <= tp for d in pdeps)
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -42,6 +48,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose:
             print(" ".join(cmd))
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    pcmd = [_hipcc()] + FLAGS + ["-I" + PROBE_DIR, "-shared", os.path.join(PROBE_DIR, "mxp_probe.hip"), "-o", PROBE_LIB]
+    procs.append(("mxp_probe.hip", subprocess.Popen(pcmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for s, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)

@@ -7,7 +7,17 @@
 namespace mxp {
 
 constexpr int kBlock = 32;    // elements per MX block (Sec. 2)
-constexpr int kNumCU = 256;   // MI355X compute units
+constexpr int kNumCU = 256;   // MI355X compute units (whole device): what the persistent launches are laid out for
+constexpr int kNumXCD = 8;    // ... in 8 XCDs, each with its own L2; the hardware deals workgroups to them round-robin
+
+// Shape of the current device, asked of the runtime once per device: compute units and XCDs.  The XCD-aware work lists of
+// the tiled product are laid out for kNumCU / kNumXCD; on any other shape (a partitioned device) the entry points take
+// the plain, non-persistent kernel instead.  The grid caps of the streaming kernels only use kNumCU as a size hint.
+struct Chip {
+  int cus, xcds;
+  bool whole_mi355x() const { return cus == kNumCU && xcds == kNumXCD; }
+};
+Chip chip();
 
 // Image stores are ordinary (cached) stores, not streaming ones: the GEMM reads the image right after it is written,
 // and measured 10 % faster behind image kernels that store this way.
@@ -29,6 +39,14 @@ int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows
 int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
                            const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
                            hipStream_t s);
+
+// Longest reduction the product entry points take: the tiled kernel addresses an 8-tile run of an operand image with a
+// 32-bit lane offset, and a six-bit + product lays up to four K segments side by side.
+constexpr int64_t kMaxGemmK = (int64_t)1 << 21;
+// Checks shared by every mxp_gemm* entry point: dtype, shape, K limit, D non-null and aligned to its element type.
+int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd, int64_t max_k = kMaxGemmK);
+// D[M][N] = 0 (the product over an empty K).
+int zero_output(void* D, int d_dtype, int64_t M, int64_t N, int64_t ldd, hipStream_t s);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -196,8 +196,8 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
 // its nibble becomes the E2M1 code of BM_H = 2^2 * 1.m2 (sign | 11 | m2), and the rest, BM_L = +-(m1 + m0 / 2), goes
 // with the BM position into one residual byte per block, sign << 7 | m1 m0 << 5 | index, stored in the lane order of
 // the tiles ([row tile][k-tile][64]) behind the scale part.
-// RES == 2: an MXFP4+ or MXFP4++ operand with the BM's nibble left as it is and the residual byte = the canonical index
-// byte (position | delta << 5; 0 for all-zero and NaN blocks): the product kernel takes the BM out of the 4-bit operand
+// RES == 2 (MXFP4++) / 3 (MXFP4+): the BM's nibble left as it is and the residual byte = position | delta << 5 (delta
+// taken as 0 for MXFP4+; 0 for all-zero and NaN blocks): the product kernel takes the BM out of the 4-bit operand
 // and feeds it as an E2M3 code with the block's own scale, the other elements with the scale lowered by delta (Sec. 4.3).
 template <int RES>
 __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
@@ -215,13 +215,18 @@ __global__ void __launch_bounds__(256) prepack_e2m1_kernel(const u32x4* __restri
   const uint32_t slot = (kb_in & 1u) * 32u + r_in;
   const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
   u32x4 v = {0, 0, 0, 0};
-  uint32_t sbyte = RES == 2 ? 0u : 127u, res = 0u;   // (RES == 2: absent blocks must read as blocks without a BM)
+  uint32_t sbyte = RES >= 2 ? 0u : 127u, res = 0u;   // (RES == 2: absent blocks must read as blocks without a BM)
   if (row < rows && kb < nbk) {
     const int64_t b = row * nbk + kb;
     v = __builtin_nontemporal_load(elems + b);
     sbyte = scales[b];
     if (sbyte == 0u) v = (u32x4){0, 0, 0, 0};
-    if (RES == 2 && sbyte != 0u && sbyte != 255u) res = bm_idx[b];
+    if (RES >= 2 && sbyte != 0u && sbyte != 255u) {
+      // MXFP4+ ignores bits 7:5 of the index byte (reserved, Sec. 4.2); an MXFP4++ delta (Sec. 4.3) is kept at most
+      // scale byte - 1, the range the conversion writes, so that lowering the scale byte by it never borrows
+      const uint32_t ib = bm_idx[b], delta = RES == 3 ? 0u : (ib >> 5);
+      res = (ib & 31u) | ((delta < sbyte ? delta : sbyte - 1u) << 5);
+    }
     if (RES == 1 && sbyte != 0u && sbyte != 255u) {
       const uint32_t bm = bm_idx[b] & 31u, sh = 4u * (bm & 7u);
       uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -356,8 +361,8 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
   return launch_status();
 }
 
-// mode 0: plain E2M1 image; 1: MXFP4+ operand, BM split, residual bytes behind the scales; 2: MXFP4+ / MXFP4++ operand,
-// BM nibble in place, index bytes behind the scales
+// mode 0: plain E2M1 image; 1: MXFP4+ operand, BM split, residual bytes behind the scales; 2 / 3: MXFP4++ / MXFP4+
+// operand, BM nibble in place, position | delta << 5 behind the scales (delta = 0 for MXFP4+)
 int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
                         hipStream_t stream, int mode) {
   const ImageGeom g = image_geom(rows, K, kTileBytesE2M1);
@@ -368,7 +373,8 @@ int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8
   if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)n_wg);
   const u32x4* e = reinterpret_cast<const u32x4*>(elems);
-  if (mode == 2) hipLaunchKernelGGL(prepack_e2m1_kernel<2>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  if (mode == 3) hipLaunchKernelGGL(prepack_e2m1_kernel<3>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
+  else if (mode == 2) hipLaunchKernelGGL(prepack_e2m1_kernel<2>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
   else if (mode == 1) hipLaunchKernelGGL(prepack_e2m1_kernel<1>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
   else hipLaunchKernelGGL(prepack_e2m1_kernel<0>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, g.k_tiles, ie, is, ir);
   return launch_status();
@@ -492,7 +498,7 @@ extern "C" int mxp_prepack_e2m1x(const uint8_t* elems, const uint8_t* scales, co
   if (!elems || !scales || !bm_idx || !image) return MXP_ERR_NULL;
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(bm_idx) || !aligned16(image)) return MXP_ERR_ALIGN;
   if (image_bytes < mxp_image_bytes_e2m1r(rows, K)) return MXP_ERR_WORKSPACE;
-  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream), 2);
+  return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream), fmt == MXP_FMT_MXFP4P ? 3 : 2);
 }
 
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,

@@ -23,6 +23,52 @@ int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t 
                           uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream, bool skip_padding_tiles);
 }  // namespace mxp
 
+namespace mxp {
+Chip chip() {
+  constexpr int kMaxDev = 64;
+  static Chip cache[kMaxDev] = {};      // cus == 0: not asked yet (a benign race: every thread writes the same values)
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return Chip{0, 0};
+  if (cache[dev].cus == 0) {
+    int cus = 0, xcds = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = -1;
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) xcds = -1;
+    cache[dev].xcds = xcds;
+    cache[dev].cus = cus == 0 ? -1 : cus;
+  }
+  return cache[dev];
+}
+
+// Argument checks common to every product entry point (declared in mxp_common.h).
+int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd, int64_t max_k) {
+  if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
+  if (K > max_k) return MXP_ERR_UNSUPPORTED;
+  if (M > 0 && N > 0 && !D) return MXP_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(D) % (d_dtype == MXP_BF16 ? 2 : 4) != 0) return MXP_ERR_ALIGN;
+  return MXP_OK;
+}
+
+namespace {
+// K == 0: the product is an empty sum.
+template <bool BF16>
+__global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * N) return;
+  const int64_t r = i / N, c = i - r * N;
+  if (BF16) static_cast<uint16_t*>(D)[r * ldd + c] = 0;
+  else static_cast<float*>(D)[r * ldd + c] = 0.0f;
+}
+}  // namespace
+
+int zero_output(void* D, int d_dtype, int64_t M, int64_t N, int64_t ldd, hipStream_t s) {
+  const unsigned grid = (unsigned)((M * N + 255) / 256);
+  if (d_dtype == MXP_BF16) hipLaunchKernelGGL(zero_kernel<true>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+  else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
+  return launch_status();
+}
+}  // namespace mxp
+
 namespace {
 
 using namespace mxp;
@@ -354,14 +400,6 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel(const uint8_t* __restr
   store_tile<C::WM, C::WN, OUT_BF16>(acc, tm0 + wm * C::WM, tn0 + wn * C::WN, lane, M, N, Dv, ldd);
 }
 
-#ifdef MXP_DEBUG_TIMELINE
-__device__ long long mxp_dbg[4 * 8192];   // timing experiment builds only
-extern "C" int mxp_debug_read(void* dst) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(mxp_dbg), sizeof(mxp_dbg)); }
-#define MXP_DBG_MARK(slot, k) do { if (threadIdx.x == 0) mxp_dbg[(slot) * 4 + (k)] = wall_clock64(); } while (0)
-#else
-#define MXP_DBG_MARK(slot, k) do { } while (0)
-#endif
-
 // ---- pipelined persistent kernel: S-stage LDS ring filled by direct global->LDS loads ---------------------------
 // A stage (one k-tile of the workgroup's A and B tiles plus their scale dwords) is a concatenation of contiguous image
 // runs, so it is copied with global_load_lds_dwordx4: every lane fetches 16 bytes and the wavefront's 1 KiB lands
@@ -495,9 +533,7 @@ template <class C, int S, int WN, bool OUT_BF16>
 __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
                                          int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0,
-                                         int next_kind, int64_t ntm0, int64_t ntn0, int dbg_slot) {
-  (void)dbg_slot;
-  MXP_DBG_MARK(dbg_slot, 0);
+                                         int next_kind, int64_t ntm0, int64_t ntn0) {
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
   static_assert(S == 4, "the peeled tail below is written for a 4-slot ring");
@@ -551,7 +587,6 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   sb0 = *reinterpret_cast<const uint32_t*>(lds + sb_off) >> sb_shift;
 
   int read_off = C::STAGE_BYTES;    // byte offset of the ring slot of k-tile kt + 1
-  MXP_DBG_MARK(dbg_slot, 1);
 
   // One k-tile: 4 WN MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can
   // issue one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap:
@@ -675,11 +710,9 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 #undef MXP_CP
   // every wavefront has read its last fragments: the ring may be refilled
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  MXP_DBG_MARK(dbg_slot, 2);
   store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + patch_base<C, S>() + wave * (2 * kPatchBytes));
   if (next_kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
   else if (next_kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
-  MXP_DBG_MARK(dbg_slot, 3);
 }
 
 // Work lists.  The hardware deals workgroups round-robin to the 8 XCDs (workgroup c runs on XCD c % 8), each with its
@@ -746,8 +779,8 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   else if (kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
   for (int it = 0; kind != 0; ++it) {
     item(it + 1, nkind, ntm0, ntn0);
-    if (kind == 2) run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0, c * 8 + it);
-    else run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0, c * 8 + it);
+    if (kind == 2) run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
+    else run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
     kind = nkind; tm0 = ntm0; tn0 = ntn0;
   }
 }
@@ -1419,8 +1452,9 @@ int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N,
   // few rows: bound by reading the weights once.  Up to 128 rows when the tiled kernel would get fewer than 64 tile columns
   // (it then leaves most of the chip idle).
   if (M <= 64 || (M <= 128 && (N + 255) / 256 < 64)) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-  // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail)
-  if (image_geom(M, K).k_tiles < 4) return launch_cfg<Cfg<4, 4, 2, 2, BT, AT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail) and a whole MI355X (its work
+  // lists are cut for 256 compute units in 8 XCDs)
+  if (image_geom(M, K).k_tiles < 4 || !chip().whole_mi355x()) return launch_cfg<Cfg<4, 4, 2, 2, BT, AT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return launch_dma<Cfg<4, 4, 2, 2, BT, AT>, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
 }
 
@@ -1447,42 +1481,12 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   if (a_kind == MXP_IMAGE_E4M3) {
     using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
     if (M <= 64) return launch_skinny<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-    if (M <= 128 || image_geom(M, K).k_tiles < 4) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    if (M <= 128 || image_geom(M, K).k_tiles < 4 || !chip().whole_mi355x()) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   return gemm_images_kind<kTileBytes, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-}
-
-// Longest reduction the product entry points take: the tiled kernel addresses an 8-tile run of an operand image with a
-// 32-bit lane offset, and a six-bit + product lays up to four K segments side by side.
-constexpr int64_t kMaxGemmK = (int64_t)1 << 21;
-
-int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int64_t ldd, int64_t max_k = kMaxGemmK) {
-  if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
-  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
-  if (K > max_k) return MXP_ERR_UNSUPPORTED;
-  if (M > 0 && N > 0 && !D) return MXP_ERR_NULL;
-  if (reinterpret_cast<uintptr_t>(D) % (d_dtype == MXP_BF16 ? 2 : 4) != 0) return MXP_ERR_ALIGN;
-  return MXP_OK;
-}
-
-// K == 0: the product is an empty sum.
-template <bool BF16>
-__global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= M * N) return;
-  const int64_t r = i / N, c = i - r * N;
-  if (BF16) static_cast<uint16_t*>(D)[r * ldd + c] = 0;
-  else static_cast<float*>(D)[r * ldd + c] = 0.0f;
-}
-
-int zero_output(void* D, int d_dtype, int64_t M, int64_t N, int64_t ldd, hipStream_t s) {
-  const unsigned grid = (unsigned)((M * N + 255) / 256);
-  if (d_dtype == MXP_BF16) hipLaunchKernelGGL(zero_kernel<true>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
-  else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
-  return launch_status();
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -1532,6 +1536,10 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
   if (!a4 || !b4) return 0;
   if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
   return mxp_gemm_workspace_bytes(M, N, K);
+}
+
+extern "C" size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB) {
+  return mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB);
 }
 
 extern "C" int mxp_gemm_prepacked(int64_t M, int64_t N, int64_t K, const void* A_image, int a_kind, const void* B_image,
@@ -1730,61 +1738,6 @@ extern "C" int mxp_gemm_decode_bf16a(int64_t M, int64_t N, int64_t K, const void
   rc = quantize_image_launch(A, a_dtype, M, K, lda, fmtA, nullptr, nullptr, nullptr, img, s, /*skip_padding_tiles=*/M <= 64);   // (M <= 64: the few-row kernels read only the tiles that hold rows)
   if (rc != MXP_OK) return rc;
   return mxp_gemm_decode(M, N, K, img, W_elems, W_scales, W_idx, fmtW, D, d_dtype, ldd, stream);
-}
-
-// ---- measurement aid: the matrix pipes alone ------------------------------------------------------------------
-// One workgroup per compute unit, one wavefront per SIMD, 16 independent accumulator tiles per wavefront (as in the
-// GEMM), operands pseudo-random bit patterns that never leave the registers.  What this reaches is what the chip's
-// power limit leaves of the nominal MFMA rate for these operand formats.
-namespace {
-template <int FA, int FB>
-__global__ void __launch_bounds__(256) mfma_probe_kernel(float* __restrict__ sink, int iters, uint32_t seed) {
-  v8i a[4], b[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      a[j][i] = (int)((threadIdx.x * 2654435761u + (8 * j + i) * 40503u + blockIdx.x) * seed);
-      b[j][i] = (int)((threadIdx.x * 2246822519u + (8 * j + i) * 3266489917u + blockIdx.x) * seed);
-    }
-  v16f acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-  const int sc = 0x7F7F7F7F;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, sc, 0, sc);
-  }
-  float x = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) x += acc[i][j][r];
-  sink[blockIdx.x * 256 + threadIdx.x] = x;
-}
-}  // namespace
-
-extern "C" int mxp_probe_mfma(int a_kind, int b_kind, int iters, uint32_t seed, float* sink, void* stream) {
-  const bool fp8 = a_kind == MXP_IMAGE_E4M3 && b_kind == MXP_IMAGE_E4M3;
-  if (!fp8 && ((a_kind != MXP_IMAGE_E2M3 && a_kind != MXP_IMAGE_E2M1) || (b_kind != MXP_IMAGE_E2M3 && b_kind != MXP_IMAGE_E2M1))) return MXP_ERR_FORMAT;
-  if (iters < 0 || iters > (1 << 24)) return MXP_ERR_SHAPE;
-  if (!sink) return MXP_ERR_NULL;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const dim3 grid(mxp::kNumCU), block(256);
-  if (fp8) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE4M3, kFmtE4M3>), grid, block, 0, s, sink, iters, seed);
-  else if (a_kind == MXP_IMAGE_E2M3 && b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
-  else if (a_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M3, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
-  else if (b_kind == MXP_IMAGE_E2M3) hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M3>), grid, block, 0, s, sink, iters, seed);
-  else hipLaunchKernelGGL((mfma_probe_kernel<kFmtE2M1, kFmtE2M1>), grid, block, 0, s, sink, iters, seed);
-  return mxp::launch_status();
 }
 
 extern "C" const char* mxp_status_string(int status) {

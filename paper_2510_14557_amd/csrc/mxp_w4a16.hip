@@ -572,15 +572,6 @@ int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, 
   }
 }
 
-template <bool BF16>
-__global__ void zero_kernel(void* D, int64_t M, int64_t N, int64_t ldd) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= M * N) return;
-  const int64_t r = i / N, c = i - r * N;
-  if (BF16) static_cast<uint16_t*>(D)[r * ldd + c] = 0;
-  else static_cast<float*>(D)[r * ldd + c] = 0.0f;
-}
-
 }  // namespace
 
 namespace mxp {
@@ -600,17 +591,10 @@ extern "C" int mxp_gemm_w4a16(int64_t M, int64_t N, int64_t K, const void* A, in
   if (fmtW < MXP_FMT_MXFP4 || fmtW > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
   const bool wide_w = fmtW >= MXP_FMT_MXFP6;
   if (a_dtype != MXP_BF16 && a_dtype != MXP_F32) return MXP_ERR_DTYPE;
-  if (d_dtype != MXP_F32 && d_dtype != MXP_BF16) return MXP_ERR_DTYPE;
-  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0 || ldd < N) return MXP_ERR_SHAPE;
-  if (M == 0 || N == 0) return MXP_OK;
-  if (!D) return MXP_ERR_NULL;
+  const int rc0 = check_gemm(M, N, K, D, d_dtype, ldd);
+  if (rc0 != MXP_OK || M == 0 || N == 0) return rc0;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (K == 0) {
-    const unsigned grid = (unsigned)((M * N + 255) / 256);
-    if (d_dtype == MXP_BF16) hipLaunchKernelGGL(zero_kernel<true>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
-    else hipLaunchKernelGGL(zero_kernel<false>, dim3(grid), dim3(256), 0, s, D, M, N, ldd);
-    return launch_status();
-  }
+  if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s);
   if (!A || !W_elems || !W_scales || (fmtW != MXP_FMT_MXFP4 && !plain_wide_format(fmtW) && !W_idx)) return MXP_ERR_NULL;
   if (lda < K) return MXP_ERR_SHAPE;
   if (a_dtype != MXP_BF16) return MXP_ERR_UNSUPPORTED;      // the activations are multiplied as bf16

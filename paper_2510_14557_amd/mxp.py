@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
-           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_probe_mfma", "mxp_status_string", "mxp_version")
+           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_gemm_workspace_size", "mxp_status_string", "mxp_version")
 
 _lib = None
 
@@ -83,8 +83,8 @@ def lib():
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_w4a16.argtypes = [i64, i64, i64, vp, i32, i64, vp, vp, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_w4a16.restype = i32
-    L.mxp_probe_mfma.argtypes = [i32, i32, i32, C.c_uint32, vp, vp]
-    L.mxp_probe_mfma.restype = i32
+    L.mxp_gemm_workspace_size.argtypes = [i64, i64, i64, i32, i32]
+    L.mxp_gemm_workspace_size.restype = sz
     L.mxp_status_string.argtypes = [i32]
     L.mxp_status_string.restype = C.c_char_p
     L.mxp_version.restype = i32
@@ -308,6 +308,10 @@ def gemm_workspace_bytes(M: int, N: int, K: int, fmt_a: int = MXFP4P, fmt_b: int
     return int(lib().mxp_gemm_workspace_bytes_fmt(M, N, K, fmt_a, fmt_b))
 
 
+def gemm_workspace_size(M: int, N: int, K: int, fmt_a: int = MXFP4P, fmt_b: int = MXFP4P) -> int:
+    return int(lib().mxp_gemm_workspace_size(M, N, K, fmt_a, fmt_b))
+
+
 def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torch.Tensor | None = None,
          workspace: torch.Tensor | None = None):
     """D[M,N] = deq(A)[M,K] @ deq(B)[N,K]^T from canonical operands."""
@@ -382,17 +386,6 @@ def gemm_w4a16(a: torch.Tensor, qw, fmt_w: int = MXFP4P, out_dtype: torch.dtype 
     _check(lib().mxp_gemm_w4a16(M, N, K, _p(a), _dt(a), lda, _p(we), _p(ws), _p(wi), fmt_w, _p(out), _dt(out), ldd, _stream()),
            "mxp_gemm_w4a16")
     return out
-
-
-PROBE_FLOP_PER_ITER = 256 * 4 * 16 * 2 * 32 * 32 * 64
-
-
-def probe_mfma(iters: int, a_kind: int = IMAGE_E2M3, b_kind: int = IMAGE_E2M3, seed: int = 1, sink: torch.Tensor | None = None):
-    """Measurement aid: MFMAs only, on register-resident operands (PROBE_FLOP_PER_ITER flop per iteration)."""
-    if sink is None:
-        sink = torch.empty(65536, dtype=torch.float32, device="cuda")
-    _check(lib().mxp_probe_mfma(a_kind, b_kind, iters, seed, _p(sink), _stream()), "mxp_probe_mfma")
-    return sink
 
 
 def gemm_bf16a_workspace_bytes(M: int, K: int) -> int:

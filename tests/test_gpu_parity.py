@@ -1427,3 +1427,30 @@ def test_gemm_few_rows_on_four_bit_mxfp4pp_weights(M, N, K, fw):
     D32 = mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1X)
     check_gemm(D32, ref, S, "e2m1x prepacked %s %dx%dx%d" % (fw, M, N, K))
     assert torch.equal(mxp.gemm_prepacked(M, N, K, img_a, img_w, b_kind=mxp.IMAGE_E2M1X, out_dtype=torch.bfloat16), D32.to(torch.bfloat16))
+
+
+def test_four_bit_image_ignores_reserved_index_bits_of_mxfp4p():
+    """Bits 7:5 of an MXFP4+ index byte are reserved (Sec. 4.2): de-conversion, the E2M3 image and the oracle ignore them,
+    and so must the 4-bit image whose kernel reads those bits as the MXFP4++ offset (Sec. 4.3) -- also where the junk
+    exceeds the block's scale byte (weights near the bottom of the E8M0 range)."""
+    M, N, K = 8, 520, 512
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    w[5] = synth.f32_to_bf16_bits((synth.bf16_bits_to_f32(w[5]) * 2.0 ** -118).astype(np.float32))   # scale bytes 1..8
+    qa = oracle.quantize(a, oracle.MXFP4P)
+    qw = oracle.quantize(w, oracle.MXFP4P)
+    assert qw[1][5].min() < 8 and qw[1][5].max() > 0
+    rng = np.random.default_rng(12)
+    junk = (qw[2] | (rng.integers(0, 8, qw[2].shape) << 5)).astype(np.uint8)
+    ref, S = oracle.gemm(qa, oracle.MXFP4P, qw, oracle.MXFP4P)
+    ref_j, _ = oracle.gemm(qa, oracle.MXFP4P, (qw[0], qw[1], junk), oracle.MXFP4P)
+    assert (ref == ref_j).all()                                        # the oracle ignores the reserved bits
+    img_a = mxp.prepack(q_dev(qa), mxp.MXFP4P)
+    clean = mxp.prepack_e2m1x(q_dev(qw), mxp.MXFP4P)
+    dirty = mxp.prepack_e2m1x(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P)
+    assert torch.equal(clean, dirty)
+    D = mxp.gemm_prepacked(M, N, K, img_a, dirty, b_kind=mxp.IMAGE_E2M1X)
+    check_gemm(D, ref, S, "e2m1x, MXFP4+ weights with junk in the reserved index bits")
+    # the other consumers of the same bytes
+    assert torch.equal(mxp.dequantize(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P), mxp.dequantize(q_dev(qw), mxp.MXFP4P))
+    assert torch.equal(mxp.prepack(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P), mxp.prepack(q_dev(qw), mxp.MXFP4P))
