@@ -74,6 +74,7 @@ extern "C" {
 #define MXP_ERR_WORKSPACE (-6)   /* workspace / image buffer too small                */
 #define MXP_ERR_HIP (-7)         /* the HIP runtime reported a launch error           */
 #define MXP_ERR_UNSUPPORTED (-8) /* valid request this build does not implement       */
+#define MXP_ERR_SCRATCH (-9)     /* mxp_gemm_static: the operand images do not fit its built-in scratch array */
 
 /* Quantize src[rows][K] (row stride ld_src, dtype MXP_F32 or MXP_BF16) into MXFP4 or MXFP4+.
  * Per block (Sec. 4.1, Eq. 1): BM = largest magnitude (lowest index on ties); shared_exp = floor(log2|BM|) - 2;
@@ -220,6 +221,21 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
              const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
              const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,
              void* D, int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream);
+
+/* mxp_gemm for callers that cannot allocate device memory (code under HIP graph capture, serving loops and harnesses
+ * that forbid hipMalloc): the same product, same kernels and same results as mxp_gemm, with the operand images in a
+ * device array built into the library instead of a caller workspace.  Neither this call nor anything it runs allocates
+ * or frees memory.  The array holds mxp_gemm_static_capacity() bytes (64 MiB, resident on every GPU the library is used
+ * on until the process ends); a product whose images need more -- mxp_gemm_workspace_size(M, N, K, fmtA, fmtB) bytes --
+ * returns MXP_ERR_SCRATCH and enqueues nothing (the Llama-8B prefill-MLP product, 4096 x 14336 x 4096, needs 56.3 MiB).
+ * All calls on one GPU share that array, which keeps the previous call's images: every byte a product reads is
+ * rewritten by the image kernels of the same call first, and calls whose work overlaps on one GPU (different streams,
+ * or different threads) race -- serialise them.  Arguments otherwise as mxp_gemm. */
+size_t mxp_gemm_static_capacity(void);
+int mxp_gemm_static(int64_t M, int64_t N, int64_t K,
+                    const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
+                    const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB,
+                    void* D, int d_dtype, int64_t ldd, void* stream);
 
 /* Same product from images built earlier (weights are packed once, when they are loaded).  Kinds that go together:
  *   A E2M3 with B E2M3 or E2M1 (any M), or B E2M1R / E2M1X (M <= 64);   A E2M1 with B E2M1;   A E4M3 with B E4M3 (any M),

@@ -10,6 +10,7 @@
 // of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is element
 // [8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of (first operand) x (second operand)^T.
 #include "mxp_common.h"
+#include <mutex>
 #include <type_traits>
 
 namespace mxp {
@@ -1666,6 +1667,51 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   return gemm_images(wa, a4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, wb, b4 ? MXP_IMAGE_E2M1 : MXP_IMAGE_E2M3, M, N, K, D, d_dtype, ldd, s);
 }
 
+// ---- mxp_gemm without a caller workspace ------------------------------------------------------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops that forbid hipMalloc): the two operand images go
+// to a file-scope device array instead of a workspace argument.  Every GPU the library runs on holds its own copy of
+// the array at its own address until the process ends; host code never uses the array's name as a pointer (it is only
+// a stand-in on the host) but the address hipGetSymbolAddress returns, asked once per device with that device current.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+int static_scratch(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDev] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return MXP_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return MXP_ERR_HIP;
+    }
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return MXP_OK;
+}
+}  // namespace
+
+extern "C" size_t mxp_gemm_static_capacity(void) { return kStaticScratchBytes; }
+
+extern "C" int mxp_gemm_static(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx,
+                               int fmtA, const uint8_t* B_elems, const uint8_t* B_scales, const uint8_t* B_idx, int fmtB, void* D,
+                               int d_dtype, int64_t ldd, void* stream) {
+  if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
+  if (M < 0 || N < 0 || K < 0) return MXP_ERR_SHAPE;
+  // (the size functions saturate nowhere near these limits: image bytes of 2^31 x 2^21 elements still fit a size_t)
+  if (M > ((int64_t)1 << 31) || N > ((int64_t)1 << 31) || K > mxp::kMaxGemmK) return MXP_ERR_SCRATCH;
+  if (mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB) > kStaticScratchBytes) return MXP_ERR_SCRATCH;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != MXP_OK) return rc;
+  return mxp_gemm(M, N, K, A_elems, A_scales, A_idx, fmtA, B_elems, B_scales, B_idx, fmtB, D, d_dtype, ldd, ws, kStaticScratchBytes, stream);
+}
+
 extern "C" size_t mxp_gemm_bf16a_workspace_bytes(int64_t M, int64_t K) {
   if (M < 0 || K < 0) return 0;
   return align_up((size_t)mxp::image_geom(M, K).total());
@@ -1751,6 +1797,7 @@ extern "C" const char* mxp_status_string(int status) {
     case MXP_ERR_WORKSPACE: return "workspace or image buffer too small";
     case MXP_ERR_HIP: return "HIP launch error";
     case MXP_ERR_UNSUPPORTED: return "request not supported by this build";
+    case MXP_ERR_SCRATCH: return "operand images exceed the built-in scratch array of mxp_gemm_static (mxp_gemm_static_capacity bytes)";
     default: return "unknown status";
   }
 }

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
-           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_gemm_workspace_size", "mxp_status_string", "mxp_version")
+           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_gemm_workspace_size", "mxp_gemm_static", "mxp_gemm_static_capacity", "mxp_status_string", "mxp_version")
 
 _lib = None
 
@@ -83,6 +83,10 @@ def lib():
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_w4a16.argtypes = [i64, i64, i64, vp, i32, i64, vp, vp, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_w4a16.restype = i32
+    L.mxp_gemm_static.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp]
+    L.mxp_gemm_static.restype = i32
+    L.mxp_gemm_static_capacity.argtypes = []
+    L.mxp_gemm_static_capacity.restype = sz
     L.mxp_gemm_workspace_size.argtypes = [i64, i64, i64, i32, i32]
     L.mxp_gemm_workspace_size.restype = sz
     L.mxp_status_string.argtypes = [i32]
@@ -328,6 +332,24 @@ def gemm(qa, fmt_a, qb, fmt_b, out_dtype: torch.dtype = torch.float32, out: torc
     ldd = out.stride(0) if M > 1 else max(N, 1)
     _check(lib().mxp_gemm(M, N, K, _p(ae), _p(as_), _p(ai), fmt_a, _p(be), _p(bs), _p(bi), fmt_b, _p(out), _dt(out), ldd,
                           _p(workspace), workspace.numel(), _stream()), "mxp_gemm")
+    return out
+
+
+def gemm_static_capacity() -> int:
+    return int(lib().mxp_gemm_static_capacity())
+
+
+def gemm_static(qa, fmt_a, qb, fmt_b, out: torch.Tensor):
+    """mxp_gemm with the operand images in the library's built-in scratch array: nothing is allocated, `out` is the caller's."""
+    ae, as_, ai = qa
+    be, bs, bi = qb
+    M, K = ae.shape[0], as_.shape[1] * 32
+    N = be.shape[0]
+    if bs.shape[1] * 32 != K:
+        raise MxpError("K mismatch between operands")
+    ldd = out.stride(0) if M > 1 else max(N, 1)
+    _check(lib().mxp_gemm_static(M, N, K, _p(ae), _p(as_), _p(ai), fmt_a, _p(be), _p(bs), _p(bi), fmt_b, _p(out), _dt(out), ldd,
+                                 _stream()), "mxp_gemm_static")
     return out
 
 

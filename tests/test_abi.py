@@ -26,7 +26,7 @@ def test_library_is_built_and_exports_every_declared_symbol():
         assert hasattr(L, n), n
     assert mxp.version() >= 100
     assert mxp.status_string(0) == "ok"
-    for rc in range(-8, 0):
+    for rc in range(-9, 0):
         assert mxp.status_string(rc) not in ("ok", "unknown status")
 
 
@@ -172,3 +172,16 @@ def test_image_geometry():
     assert mxp.image_bytes_e2m1(256, 128) == 256 * 4 * 16 + 256 * 4
     assert mxp.image_bytes_e2m1(4096, 4096) == 4096 * 128 * 17
     assert mxp.gemm_bf16a_workspace_bytes(4096, 4096) == 4096 * 128 * 25
+
+
+def test_gemm_static_refuses_oversized_products_before_touching_the_gpu():
+    L = mxp.lib()
+    buf = (C.c_uint8 * 4096)()
+    p = C.c_void_p((C.addressof(buf) + 15) & ~15)
+    assert L.mxp_gemm_static_capacity() == 64 << 20
+    # the 70B-shaped product needs ~235 MB of images: more than the built-in array holds
+    assert L.mxp_gemm_workspace_size(8192, 28672, 8192, mxp.MXFP4P, mxp.MXFP4P) > L.mxp_gemm_static_capacity()
+    assert L.mxp_gemm_static(8192, 28672, 8192, p, p, p, mxp.MXFP4P, p, p, p, mxp.MXFP4P, p, mxp.F32, 28672, None) == -9
+    assert L.mxp_gemm_static(8, 8, 32, p, p, p, 11, p, p, p, mxp.MXFP4P, p, mxp.F32, 8, None) == -5
+    assert L.mxp_gemm_static(-1, 8, 32, p, p, p, mxp.MXFP4P, p, p, p, mxp.MXFP4P, p, mxp.F32, 8, None) == -2
+    assert "scratch" in mxp.status_string(-9)
