@@ -202,6 +202,16 @@ int mxp_prepack_fp8(const uint8_t* elems, const uint8_t* scales, int64_t rows, i
 int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,
                        uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, size_t image_bytes, void* stream);
 
+/* Both conversions in front of a product with un-quantized activations and weights kept in canonical storage, as ONE
+ * launch (Sec. 7.1: activations are converted at run time; Sec. 5.2: the BM is prepared per operand): A as
+ * mxp_quantize_image (A_elems / A_scales / A_idx all given or all NULL), W[N][K] as mxp_prepack -- same results bit for
+ * bit, same arguments and error rules; the two jobs share one grid, so the second fills the compute units the first
+ * one's tail leaves idle.  fmtA, fmtW: MXP_FMT_MXFP4 or MXP_FMT_MXFP4P (MXFP4++: MXP_ERR_UNSUPPORTED). */
+int mxp_convert_operands(const void* A, int a_dtype, int64_t M, int64_t K, int64_t lda, int fmtA,
+                         uint8_t* A_elems, uint8_t* A_scales, uint8_t* A_idx, void* A_image, size_t a_image_bytes,
+                         const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, int64_t N,
+                         void* W_image, size_t w_image_bytes, void* stream);
+
 /* D[M][N] = A[M][K] x B^T, B given as [N][K] (K-contiguous, the way a linear layer stores W); both operands in
  * canonical storage, formats chosen per operand (Sec. 5: activations MXFP4+ with weights MXFP4 or MXFP4+).
  * The result is the matrix product of the de-converted operands accumulated in fp32 (Sec. 5.1).

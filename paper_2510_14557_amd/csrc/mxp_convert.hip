@@ -2,6 +2,7 @@
 // mxp_prepack    : canonical -> MFMA-ready E2M3 image          (the "BM prepare" step of Sec. 5.2, done once per
 //                  operand instead of once per MMA fragment: on CDNA4 the BM is directly an operand value)
 #include "mxp_common.h"
+#include "mxp_prepack_body.h"
 #include "mxp_decode.h"
 
 namespace {
@@ -113,17 +114,7 @@ __global__ void __launch_bounds__(256) dequantize_dense_f32_kernel(const uint16_
   }
 }
 
-// 4 nibbles (16 bit) -> 4 six-bit codes (24 bit), code = nibble << 2.  Two multiplies spread the even and the odd
-// nibbles to their positions: bit offsets 4i -> 6i + 2.
-__device__ __forceinline__ uint32_t widen4(uint32_t h) {
-  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
-  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
-}
-
-// One thread widens one 32-element block into its 24-byte E2M3 operand.  A 256-thread group covers 32 rows x 8
-// consecutive K-blocks (4 k-tiles): thread t takes row t / 8, block t % 8, so the eight lanes of a row read 128
-// contiguous bytes.  The finished blocks are dropped at their lane slots of the four tiles in LDS; the tiles are
-// neighbours in the image (6 KiB), which then leaves the workgroup in full 16-byte-per-lane stores.
+// canonical block -> 24-byte E2M3 operand, staged through LDS: see prepack_body
 template <bool PLUS>
 __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
                                                       const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
@@ -131,63 +122,7 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
                                                       uint8_t* __restrict__ img_scales) {
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
   __shared__ uint8_t tile_scales[4 * 64];
-  const uint32_t t = threadIdx.x;
-  const uint32_t r_in = t >> 3, kb_in = t & 7u;
-  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
-  if (!pm.valid) return;
-  const int64_t kt0 = pm.kg * 4;
-  const int64_t rt = pm.rt;
-  const uint32_t slot = (kb_in & 1u) * 32u + r_in;     // slot of this block in its tile: row % 32, K-block % 2
-  const int64_t row = rt * kTileRows + r_in;
-  const int64_t kb = kt0 * 2 + kb_in;
-  uint32_t n[4] = {0, 0, 0, 0};
-  uint32_t sbyte = 127u, bm = 64u;
-  if (row < rows && kb < nbk) {
-    const int64_t b = row * nbk + kb;
-    const u32x4 v = __builtin_nontemporal_load(elems + b);
-    n[0] = v.x; n[1] = v.y; n[2] = v.z; n[3] = v.w;
-    sbyte = scales[b];
-    if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
-    if (sbyte == 0u) n[0] = n[1] = n[2] = n[3] = 0u;          // flushed block: zero whatever the nibbles say
-  }
-  // 8 pieces of 24 bits -> 6 dwords
-  uint32_t r[8];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    r[2 * j] = widen4(n[j] & 0xFFFFu);
-    r[2 * j + 1] = widen4(n[j] >> 16);
-  }
-  if (PLUS && bm < 32u) {
-    // the BM's code is sign | 11 | mmm  (E2M3 at exponent e_max, Sec. 4.2) instead of nibble << 2
-    const uint32_t piece = bm >> 2, sh = (bm & 3u) * 6u;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t c = (r[j] >> sh) & 0x3Fu;                 // s mmm 00
-      const uint32_t code = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);
-      const uint32_t patched = (r[j] & ~(0x3Fu << sh)) | (code << sh);
-      r[j] = piece == (uint32_t)j ? patched : r[j];
-    }
-  }
-  uint32_t d[6];
-  d[0] = r[0] | (r[1] << 24);
-  d[1] = (r[1] >> 8) | (r[2] << 16);
-  d[2] = (r[2] >> 16) | (r[3] << 8);
-  d[3] = r[4] | (r[5] << 24);
-  d[4] = (r[5] >> 8) | (r[6] << 16);
-  d[5] = (r[6] >> 16) | (r[7] << 8);
-  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytes;
-  u32x4 lo4 = {d[0], d[1], d[2], d[3]};
-  u32x2 hi2 = {d[4], d[5]};
-  *reinterpret_cast<u32x4*>(tile + slot * 16u) = lo4;
-  *reinterpret_cast<u32x2*>(tile + 1024u + slot * 8u) = hi2;
-  tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)sbyte;
-  __syncthreads();
-  const int64_t nt = k_tiles - kt0 < 4 ? k_tiles - kt0 : 4;          // tiles of this workgroup that exist
-  uint8_t* out = img_elems + (rt * k_tiles + kt0) * (int64_t)kTileBytes;
-  const uint32_t nbytes = (uint32_t)nt * kTileBytes;
-  for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
-    MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
-  if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+  prepack_body<PLUS>(blockIdx.x, tiles, tile_scales, elems, scales, bm_idx, rows, nbk, k_tiles, img_elems, img_scales);
 }
 
 // Plain MXFP4 operand -> E2M1 image: the canonical 16-byte blocks moved to their lane slots, scales to the scale

@@ -7,6 +7,7 @@
 // nibble with the 3-bit extended mantissa, and each lane stores one dword of nibbles.  Scale and index bytes of
 // four neighbouring blocks are gathered into one lane and stored as dwords.
 #include "mxp_common.h"
+#include "mxp_prepack_body.h"
 #include <type_traits>
 
 namespace {
@@ -714,21 +715,16 @@ __global__ void __launch_bounds__(256) quantize_t_tiled_kernel(const void* __res
 // eight 4-bit codes of a lane to 48 bits of E2M3 (code << 2; the BM becomes sign | 11 | mmm, Sec. 4.2), and drops
 // them at the block's slot of its tile in LDS.  The four finished tiles are contiguous in the image (6 KiB) and leave
 // with full-width stores.  Padding rows / blocks are zero elements with a unit scale, as the prepack kernel writes.
-__device__ __forceinline__ uint32_t widen4(uint32_t h) {   // 4 nibbles -> 4 six-bit codes, code = nibble << 2
-  const uint32_t x = h & 0x0F0Fu, y = h & 0xF0F0u;
-  return ((x * 0x44u) & 0x0003C03Cu) | ((y * 0x110u) & 0x00F00F00u);
-}
-
+// `wg`: the workgroup's number in the patch walk; `tiles` (4 * kTileBytes, 16-byte aligned) and `tile_scales` (256 bytes): its
+// LDS staging.
 template <bool BF16, bool PLUS>
-__global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
-                                                             int64_t k_tiles, uint32_t* __restrict__ elems,
-                                                             uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
-                                                             uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales,
-                                                             int skip_padding_tiles) {
-  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
-  __shared__ uint8_t tile_scales[4 * 64];
+__device__ __forceinline__ void quantize_image_body(uint32_t wg, uint8_t* tiles, uint8_t* tile_scales, const void* __restrict__ src,
+                                                    int64_t rows, int64_t nbk, int64_t ld, int64_t k_tiles,
+                                                    uint32_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                    uint8_t* __restrict__ bm_idx, uint8_t* __restrict__ img_elems,
+                                                    uint8_t* __restrict__ img_scales, int skip_padding_tiles) {
   const uint32_t t = threadIdx.x, part = t & 3u, quad_in_row = (t & 15u) >> 2;
-  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  const PatchMap pm = patch_of_workgroup(wg, (uint32_t)((k_tiles + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
   if (!pm.valid) return;
   const int64_t rt = pm.rt, kt0 = pm.kg * 4;
   const bool canon = elems != nullptr;
@@ -833,6 +829,41 @@ __global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restr
   for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
     MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
   if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt0 + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+}
+
+template <bool BF16, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_image_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                             int64_t k_tiles, uint32_t* __restrict__ elems,
+                                                             uint8_t* __restrict__ scales, uint8_t* __restrict__ bm_idx,
+                                                             uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales,
+                                                             int skip_padding_tiles) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  quantize_image_body<BF16, PLUS>(blockIdx.x, tiles, tile_scales, src, rows, nbk, ld, k_tiles, elems, scales, bm_idx, img_elems,
+                                  img_scales, skip_padding_tiles);
+}
+
+// Both conversions of a product with un-quantized activations and canonical weights in ONE launch: the first n_a
+// workgroups walk the activation patches (source -> canonical arrays + E2M3 image), the rest the weight patches
+// (canonical -> E2M3 image).  The two jobs are independent; as separate launches each pays its own ramp-up and tail
+// (10-25 us kernels), as one grid the weight patches fill the compute units the activation job's tail leaves idle.
+struct ConvertPairArgs {
+  const void* src; int64_t rows_a, nbk, ld, k_tiles;
+  uint32_t* a_elems; uint8_t *a_scales, *a_idx, *a_img_elems, *a_img_scales;
+  const img_u32x4* w_elems; const uint8_t *w_scales, *w_idx; int64_t rows_w;
+  uint8_t *w_img_elems, *w_img_scales;
+  uint32_t n_a;
+};
+template <bool BF16, bool PLUS_A, bool PLUS_W>
+__global__ void __launch_bounds__(256) convert_pair_kernel(const ConvertPairArgs p) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  if (blockIdx.x < p.n_a)
+    quantize_image_body<BF16, PLUS_A>(blockIdx.x, tiles, tile_scales, p.src, p.rows_a, p.nbk, p.ld, p.k_tiles, p.a_elems, p.a_scales,
+                                      p.a_idx, p.a_img_elems, p.a_img_scales, 0);
+  else
+    prepack_body<PLUS_W>(blockIdx.x - p.n_a, tiles, tile_scales, p.w_elems, p.w_scales, p.w_idx, p.rows_w, p.nbk, p.k_tiles,
+                         p.w_img_elems, p.w_img_scales);
 }
 
 // The same one-pass conversion for MXFP4++ (Sec. 4.3), whose GEMM operand is an E4M3 image: with the image's scale
@@ -1017,6 +1048,49 @@ extern "C" int mxp_quantize_image(const void* src, int src_dtype, int64_t rows, 
   if (image_bytes < (size_t)image_geom(rows, K, fmt == MXP_FMT_MXFP4PP ? kTileBytesE4M3 : kTileBytes).total()) return MXP_ERR_WORKSPACE;
   return quantize_image_launch(src, src_dtype, rows, K, ld_src, fmt, canon ? elems : nullptr, scales, bm_idx, image,
                                static_cast<hipStream_t>(stream), false);
+}
+
+extern "C" int mxp_convert_operands(const void* A, int a_dtype, int64_t M, int64_t K, int64_t lda, int fmtA, uint8_t* A_elems,
+                                    uint8_t* A_scales, uint8_t* A_idx, void* A_image, size_t a_image_bytes,
+                                    const uint8_t* W_elems, const uint8_t* W_scales, const uint8_t* W_idx, int fmtW, int64_t N,
+                                    void* W_image, size_t w_image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmtA == MXP_FMT_MXFP4PP || fmtW == MXP_FMT_MXFP4PP) return MXP_ERR_UNSUPPORTED;
+  if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P) || (fmtW != MXP_FMT_MXFP4 && fmtW != MXP_FMT_MXFP4P)) return MXP_ERR_FORMAT;
+  if (a_dtype != MXP_F32 && a_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (M < 0 || N < 0 || K < 0 || K % kBlock != 0) return MXP_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // an empty side: the other one alone
+  if (K == 0 || (M == 0 && N == 0)) return MXP_OK;
+  if (M == 0) return mxp_prepack(W_elems, W_scales, W_idx, fmtW, N, K, W_image, w_image_bytes, stream);
+  if (N == 0) return mxp_quantize_image(A, a_dtype, M, K, lda, fmtA, A_elems, A_scales, A_idx, A_image, a_image_bytes, stream);
+  if (!A || !A_image || !W_elems || !W_scales || !W_image || (fmtW == MXP_FMT_MXFP4P && !W_idx)) return MXP_ERR_NULL;
+  const bool canon = A_elems || A_scales || A_idx;
+  if (canon && (!A_elems || !A_scales || (fmtA != MXP_FMT_MXFP4 && !A_idx))) return MXP_ERR_NULL;
+  if (lda < K) return MXP_ERR_SHAPE;
+  const int64_t esz = a_dtype == MXP_BF16 ? 2 : 4;
+  if (!aligned16(A) || !aligned16(A_image) || (lda * esz) % 16 != 0 || !aligned16(W_elems) || !aligned16(W_scales) ||
+      !aligned16(W_image) || (W_idx && !aligned16(W_idx)))
+    return MXP_ERR_ALIGN;
+  if (canon && (!aligned16(A_elems) || !aligned16(A_scales) || (A_idx && !aligned16(A_idx)))) return MXP_ERR_ALIGN;
+  const ImageGeom ga = image_geom(M, K), gw = image_geom(N, K);
+  if (a_image_bytes < (size_t)ga.total() || w_image_bytes < (size_t)gw.total()) return MXP_ERR_WORKSPACE;
+  const int64_t n_a = patch_grid((ga.k_tiles + 3) / 4, ga.row_tiles / 4), n_w = patch_grid((gw.k_tiles + 3) / 4, gw.row_tiles / 4);
+  if (n_a + n_w > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  ConvertPairArgs p;
+  p.src = A; p.rows_a = M; p.nbk = K / kBlock; p.ld = lda; p.k_tiles = ga.k_tiles;
+  p.a_elems = canon ? reinterpret_cast<uint32_t*>(A_elems) : nullptr; p.a_scales = A_scales; p.a_idx = A_idx;
+  p.a_img_elems = static_cast<uint8_t*>(A_image); p.a_img_scales = p.a_img_elems + ga.elem_bytes;
+  p.w_elems = reinterpret_cast<const img_u32x4*>(W_elems); p.w_scales = W_scales; p.w_idx = W_idx; p.rows_w = N;
+  p.w_img_elems = static_cast<uint8_t*>(W_image); p.w_img_scales = p.w_img_elems + gw.elem_bytes;
+  p.n_a = (uint32_t)n_a;
+  const dim3 grid((unsigned)(n_a + n_w)), block(256);
+  const bool bf = a_dtype == MXP_BF16, pa = fmtA == MXP_FMT_MXFP4P, pw = fmtW == MXP_FMT_MXFP4P;
+#define MXP_PAIR(B, PA, PW) hipLaunchKernelGGL((convert_pair_kernel<B, PA, PW>), grid, block, 0, s, p)
+  if (bf) { if (pa) { if (pw) MXP_PAIR(true, true, true); else MXP_PAIR(true, true, false); } else { if (pw) MXP_PAIR(true, false, true); else MXP_PAIR(true, false, false); } }
+  else    { if (pa) { if (pw) MXP_PAIR(false, true, true); else MXP_PAIR(false, true, false); } else { if (pw) MXP_PAIR(false, false, true); else MXP_PAIR(false, false, false); } }
+#undef MXP_PAIR
+  return launch_status();
 }
 
 extern "C" int mxp_quantize(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt,

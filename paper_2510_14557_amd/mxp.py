@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
            "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
-           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_gemm_workspace_size", "mxp_gemm_static", "mxp_gemm_static_capacity", "mxp_status_string", "mxp_version")
+           "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_convert_operands", "mxp_gemm_workspace_size", "mxp_gemm_static", "mxp_gemm_static_capacity", "mxp_status_string", "mxp_version")
 
 _lib = None
 
@@ -83,6 +83,8 @@ def lib():
     L.mxp_gemm_bf16a.argtypes = [i64, i64, i64, vp, i32, i64, i32, vp, i32, vp, i32, i64, vp, sz, vp]
     L.mxp_gemm_w4a16.argtypes = [i64, i64, i64, vp, i32, i64, vp, vp, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_w4a16.restype = i32
+    L.mxp_convert_operands.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, vp, sz, vp, vp, vp, i32, i64, vp, sz, vp]
+    L.mxp_convert_operands.restype = i32
     L.mxp_gemm_static.argtypes = [i64, i64, i64, vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, i64, vp]
     L.mxp_gemm_static.restype = i32
     L.mxp_gemm_static_capacity.argtypes = []
@@ -228,6 +230,20 @@ def quantize_image(x: torch.Tensor, fmt: int = MXFP4P, canonical: bool = False, 
     _check(lib().mxp_quantize_image(_p(x), _dt(x), rows, K, ld, fmt, _p(q[0]), _p(q[1]), _p(q[2]), _p(out), out.numel(),
                                     _stream()), "mxp_quantize_image")
     return (out, q) if (canonical or q_out is not None) else out
+
+
+def convert_operands(a: torch.Tensor, fmt_a: int, q_out, a_image: torch.Tensor, qw, fmt_w: int, w_image: torch.Tensor):
+    """One launch: activations -> (canonical arrays q_out, or None) + E2M3 image; canonical weights qw -> E2M3 image."""
+    _dev2d(a)
+    M, K = a.shape
+    ae, as_, ai = q_out if q_out is not None else (None, None, None)
+    we, ws, wi = qw
+    N = we.shape[0]
+    lda = a.stride(0) if M > 1 else max(K, 1)
+    _check(lib().mxp_convert_operands(_p(a), _dt(a), M, K, lda, fmt_a, _p(ae), _p(as_), _p(ai), _p(a_image), a_image.numel(),
+                                      _p(we), _p(ws), _p(wi), fmt_w, N, _p(w_image), w_image.numel(), _stream()),
+           "mxp_convert_operands")
+    return a_image, w_image
 
 
 def image_bytes_e2m1(rows: int, K: int) -> int:

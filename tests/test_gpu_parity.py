@@ -353,6 +353,41 @@ def check_gemm(D, ref, S, what=""):
     assert worst <= 0, "%s: element error exceeds 2^-16 * sum|ab| by %.3e" % (what, worst)
 
 
+def stratified_positions(M, N, rng, sub=32):
+    """One output position in every sub x sub tile of an M x N result (ragged edge tiles included), drawn at random inside
+    its tile, plus the four corners: no MFMA sub-tile, wavefront quadrant or workgroup tile of a launch goes unsampled."""
+    tm, tn = (M + sub - 1) // sub, (N + sub - 1) // sub
+    r0 = np.repeat(np.arange(tm) * sub, tn)
+    c0 = np.tile(np.arange(tn) * sub, tm)
+    rm = r0 + rng.integers(0, sub, tm * tn) % np.minimum(sub, M - r0)
+    rn = c0 + rng.integers(0, sub, tm * tn) % np.minimum(sub, N - c0)
+    rm = np.concatenate([rm, [0, M - 1, 0, M - 1]]).astype(np.int64)
+    rn = np.concatenate([rn, [0, N - 1, N - 1, 0]]).astype(np.int64)
+    return rm, rn
+
+
+def gather_outputs(D, rm, rn):
+    return D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
+
+
+def dot_rows(da, dw, rm, rn, chunk=8192):
+    """ref[t] = <da[rm[t]], dw[rn[t]]> and S[t] = <|da[rm[t]]|, |dw[rn[t]]|> in float64, in chunks (the gathers are large)."""
+    ref, S = np.empty(rm.size), np.empty(rm.size)
+    for i in range(0, rm.size, chunk):
+        x, y = da[rm[i:i + chunk]].astype(np.float64), dw[rn[i:i + chunk]].astype(np.float64)
+        ref[i:i + chunk] = np.einsum("tk,tk->t", x, y)
+        S[i:i + chunk] = np.einsum("tk,tk->t", np.abs(x), np.abs(y))
+    return ref, S
+
+
+def assert_sampled(got, ref, S, log2_tol=-16, fro_tol=1e-5, what=""):
+    assert np.isfinite(got).all(), what
+    fro = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert fro <= fro_tol, "%s: relative Frobenius error %.3e" % (what, fro)
+    worst = (np.abs(got - ref) - 2.0 ** log2_tol * S).max()
+    assert worst <= 0, "%s: element error exceeds 2^%d * sum|ab| by %.3e" % (what, log2_tol, worst)
+
+
 @pytest.mark.parametrize("fa,fb", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4")])
 def test_gemm_tiny_config(fa, fb):
     a, b = synth.tiny()
@@ -492,26 +527,20 @@ def test_gemm_w4a16_special_blocks():
 
 
 def test_gemm_w4a16_full_size_sampled():
-    """Prefill MLP shape, bf16 activations x MXFP4+ weights de-converted in the kernel; sampled outputs."""
+    """Prefill MLP shape, bf16 activations x MXFP4+ weights de-converted in the kernel; one output per 32 x 32 sub-tile."""
     M, N, K = 4096, 14336, 4096
     a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
     w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
     qw = mxp.quantize(to_dev(w), mxp.MXFP4P)
-    D = mxp.gemm_w4a16(to_dev(a), qw, mxp.MXFP4P)
-    rng = np.random.default_rng(8)
-    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
-    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
-    sel_w, inv_w = np.unique(rn, return_inverse=True)
-    qw_o = oracle.quantize(w[sel_w], oracle.MXFP4P)
+    D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    mxp.gemm_w4a16(to_dev(a), qw, mxp.MXFP4P, out=D)
+    assert torch.isfinite(D).all()
+    rm, rn = stratified_positions(M, N, np.random.default_rng(8))
+    qw_o = oracle.quantize(w, oracle.MXFP4P)
     for g, o in zip(qw, qw_o):
-        assert (g.cpu().numpy()[sel_w] == o).all()
-    a64 = synth.bf16_bits_to_f32(a[rm]).astype(np.float64)
-    w64 = oracle.dequantize(qw_o, oracle.MXFP4P)[inv_w]
-    ref = np.einsum("tk,tk->t", a64, w64)
-    S = np.einsum("tk,tk->t", np.abs(a64), np.abs(w64))
-    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
-    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+        assert (g.cpu().numpy() == o).all()
+    ref, S = dot_rows(synth.bf16_bits_to_f32(a), oracle.dequantize(qw_o, oracle.MXFP4P).astype(np.float32), rm, rn)
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, what="w4a16 full size")
 
 
 def test_gemm_strided_output_and_k0():
@@ -528,36 +557,30 @@ def test_gemm_strided_output_and_k0():
     assert D.shape == (4, 8) and not D.any()
 
 
-def _sampled_check(name, M=None, N=None, wname=None, n_samples=4096, seed=0, w_fmt="mxfp4p"):
-    """Full-size GEMM on the GPU in the launch configuration the benchmark times; sampled outputs from the oracle."""
+def _sampled_check(name, M=None, N=None, wname=None, seed=0, w_fmt="mxfp4p"):
+    """Full-size GEMM on the GPU in the launch configuration the benchmark times, into an output pre-filled with NaN.
+    Compared with the oracle on one output per 32 x 32 MFMA sub-tile of the result (every workgroup tile, wavefront
+    quadrant and sub-tile of the launch is sampled), and every output must have been written with a finite value."""
     a, ws = synth.make(name, M=M, N=N)
     wname = wname or next(iter(ws))
     w = ws[wname]
     da, dw = to_dev(a), to_dev(w)
     qa, qw = mxp.quantize(da, mxp.MXFP4P), mxp.quantize(dw, FMT[w_fmt][0])
-    D = mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0])
-    torch.cuda.synchronize()
-    rng = np.random.default_rng(seed)
     Mv, Nv = a.shape[0], w.shape[0]
-    rm = rng.integers(0, Mv, n_samples)
-    rn = rng.integers(0, Nv, n_samples)
-    rm[:8] = [0, Mv - 1, 0, Mv - 1, Mv // 2, 255 % Mv, 256 % Mv, 31 % Mv]
-    rn[:8] = [0, Nv - 1, Nv - 1, 0, Nv // 2, 255 % Nv, 256 % Nv, 32 % Nv]
-    # quantized operands: compare a band of rows bit-exactly with the oracle, then use the GPU bytes for the product
-    rows = np.unique(np.concatenate([np.arange(min(64, Mv)), rm[:256]]))
-    qo = oracle.quantize(a[rows], oracle.MXFP4P)
-    qh = q_host(qa)
-    assert all((g[rows] == o).all() for g, o in zip(qh, qo))
-    rows = np.unique(np.concatenate([np.arange(min(64, Nv)), rn[:256]]))
-    qo = oracle.quantize(w[rows], FMT[w_fmt][1])
-    qwh = q_host(qw)
-    assert all((g[rows] == o).all() for g, o in zip(qwh[:2], qo[:2]))
+    D = torch.full((Mv, Nv), float("nan"), dtype=torch.float32, device="cuda")
+    mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0], out=D)
+    torch.cuda.synchronize()
+    assert torch.isfinite(D).all(), "%s: outputs left unwritten or not finite" % name
+    rm, rn = stratified_positions(Mv, Nv, np.random.default_rng(seed))
+    # quantized operands: the whole tensors bit-exactly against the oracle, then the product on those bytes
+    qh, qwh = q_host(qa), q_host(qw)
+    assert all((g == o).all() for g, o in zip(qh, oracle.quantize(a, oracle.MXFP4P)))
+    qo = oracle.quantize(w, FMT[w_fmt][1])
+    assert all((g == o).all() for g, o in zip(qwh[:2], qo[:2]))
     if w_fmt == "mxfp4p":
-        assert (qwh[2][rows] == qo[2]).all()
+        assert (qwh[2] == qo[2]).all()
     ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, FMT[w_fmt][1], rm, rn)
-    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
-    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, what="%s %s" % (name, w_fmt))
 
 
 def test_gemm_random_shapes_sampled():
@@ -607,7 +630,7 @@ def test_gemm_full_size_plain_mxfp4_weights_sampled():
 
 
 def test_gemm_full_size_70b_shaped_sampled():
-    _sampled_check("large70b", n_samples=2048)
+    _sampled_check("large70b")
 
 
 def test_gemm_half_tile_schedule_sampled():
@@ -832,29 +855,23 @@ def test_gemm_mxfp6_special_blocks():
 
 
 def test_gemm_mxfp6p_full_size_sampled():
-    """Benchmark shape, MXFP6+ activations x MXFP6 weights, operands converted on the GPU."""
+    """Benchmark shape, MXFP6+ activations x MXFP6 weights, operands converted on the GPU; one output per 32 x 32 sub-tile."""
     W = oracle.wide
     M, N, K = 4096, 14336, 4096
     a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
     w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
     qa, qw = mxp.quantize(to_dev(a), mxp.MXFP6P), mxp.quantize(to_dev(w), mxp.MXFP6)
-    D = mxp.gemm(qa, mxp.MXFP6P, qw, mxp.MXFP6)
-    rng = np.random.default_rng(6)
-    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
-    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
-    sel_a, inv_a = np.unique(rm, return_inverse=True)
-    sel_w, inv_w = np.unique(rn, return_inverse=True)
-    qa_o, qw_o = W.quantize(a[sel_a], W.MXFP6P), W.quantize(w[sel_w], W.MXFP6)
+    D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    mxp.gemm(qa, mxp.MXFP6P, qw, mxp.MXFP6, out=D)
+    assert torch.isfinite(D).all()
+    rm, rn = stratified_positions(M, N, np.random.default_rng(6))
+    qa_o, qw_o = W.quantize(a, W.MXFP6P), W.quantize(w, W.MXFP6)
     for g, o in zip(qa, qa_o):
-        assert (g.cpu().numpy()[sel_a] == o).all()
+        assert (g.cpu().numpy() == o).all()
     for g, o in list(zip(qw, qw_o))[:2]:
-        assert (g.cpu().numpy()[sel_w] == o).all()
-    da, dw = W.dequantize(qa_o, W.MXFP6P), W.dequantize(qw_o, W.MXFP6)
-    ref = np.einsum("tk,tk->t", da[inv_a], dw[inv_w])
-    S = np.einsum("tk,tk->t", np.abs(da[inv_a]), np.abs(dw[inv_w]))
-    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-5
-    assert (np.abs(got - ref) <= 2.0 ** -16 * S).all()
+        assert (g.cpu().numpy() == o).all()
+    ref, S = dot_rows(W.dequantize(qa_o, W.MXFP6P).astype(np.float32), W.dequantize(qw_o, W.MXFP6).astype(np.float32), rm, rn)
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, what="mxfp6+ x mxfp6 full size")
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (257, 300, 1024), (64, 1000, 2080), (300, 520, 2048)])
@@ -1454,3 +1471,30 @@ def test_four_bit_image_ignores_reserved_index_bits_of_mxfp4p():
     # the other consumers of the same bytes
     assert torch.equal(mxp.dequantize(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P), mxp.dequantize(q_dev(qw), mxp.MXFP4P))
     assert torch.equal(mxp.prepack(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P), mxp.prepack(q_dev(qw), mxp.MXFP4P))
+
+
+@pytest.mark.parametrize("fa,fw", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4p")])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_convert_operands_one_launch_matches_the_two_kernels(fa, fw, bf16):
+    """mxp_convert_operands (activations -> canonical + image, canonical weights -> image, one grid) writes the oracle's
+    canonical bytes and, bit for bit, the images of mxp_quantize_image and mxp_prepack; ragged and special shapes."""
+    dt = "bf16" if bf16 else "f32"
+    for (M, N, K), seed in (((37, 70, 160), 0), ((300, 520, 4096 + 64), 1), ((1, 1, 32), 2), ((513, 40, 224), 3), ((40, 1300, 2048), 4)):
+        a = special_tensor(rows=M, K=K, seed=seed, bf16=bf16) if M == 37 else synth.activations(M, K, config_id=2, tensor_id=seed, dtype=dt)
+        w = special_tensor(rows=N, K=K, seed=seed + 9, bf16=True) if N == 70 else synth.weights(N, K, config_id=2, tensor_id=seed + 20, t3_frac=0.001)
+        qw_o = oracle.quantize(w, FMT[fw][1])
+        qw = q_dev(qw_o)
+        da = to_dev(a)
+        qa = tuple(torch.full(s, 0xA5, dtype=torch.uint8, device="cuda") for s in ((M, K // 2), (M, K // 32), (M, K // 32)))
+        ia = torch.full((mxp.image_bytes(M, K),), 0xA5, dtype=torch.uint8, device="cuda")
+        iw = torch.full((mxp.image_bytes(N, K),), 0xA5, dtype=torch.uint8, device="cuda")
+        mxp.convert_operands(da, FMT[fa][0], qa, ia, qw, FMT[fw][0], iw)
+        assert_q_equal(qa, oracle.quantize(a, FMT[fa][1]), fa, "convert_operands canonical %s" % ((M, N, K),))
+        assert torch.equal(ia, mxp.quantize_image(da, FMT[fa][0])), (M, N, K)
+        assert torch.equal(iw, mxp.prepack(qw, FMT[fw][0])), (M, N, K)
+        ia2, iw2 = torch.full_like(ia, 0x5A), torch.full_like(iw, 0x5A)
+        mxp.convert_operands(da, FMT[fa][0], None, ia2, qw, FMT[fw][0], iw2)      # without the canonical outputs
+        assert torch.equal(ia2, ia) and torch.equal(iw2, iw)
+        if M != 37:                                                  # (the special tensors hold NaN blocks and huge values)
+            ref, S = oracle.gemm(oracle.quantize(a, FMT[fa][1]), FMT[fa][1], qw_o, FMT[fw][1])
+            check_gemm(mxp.gemm_prepacked(M, N, K, ia, iw), ref, S, "product of the images of convert_operands")
