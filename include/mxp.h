@@ -41,10 +41,11 @@ extern "C" {
 /* block formats */
 #define MXP_FMT_MXFP4 0  /* plain OCP MXFP4 (Sec. 2) */
 #define MXP_FMT_MXFP4P 1 /* MXFP4+ (Sec. 4)          */
-#define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion, de-conversion, and the product through E4M3 images
-                           * (mxp_gemm, or mxp_prepack_e4m3 + mxp_gemm_prepacked); the other image and product entry points
-                           * return MXP_ERR_UNSUPPORTED for it (its BM and NBMs have different scales, which one
-                           * E2M3 operand cannot carry) */
+#define MXP_FMT_MXFP4PP 2 /* MXFP4++ (Sec. 4.3): conversion, de-conversion, and the product -- exact over two K segments
+                           * when the other operand is MXFP4 / MXFP4+ (mxp_gemm, or mxp_prepack_seg + mxp_gemm_prepacked),
+                           * through E4M3 images when both operands are MXFP4++ (mxp_gemm, or mxp_prepack_e4m3 +
+                           * mxp_gemm_prepacked); the other image and product entry points return MXP_ERR_UNSUPPORTED for
+                           * it (its BM and NBMs have different scales, which one E2M3 operand cannot carry) */
 /* Six- and eight-bit MX and MX+ formats (Sec. 4.2, data layout): conversion and de-conversion (mxp_quantize,
  * mxp_dequantize) and, for MXFP6, MXFP6+ and plain MXFP8, the product (mxp_gemm; mxp_prepack_fp6 / mxp_prepack_fp8 +
  * mxp_gemm_prepacked); every other entry point returns MXP_ERR_FORMAT or MXP_ERR_UNSUPPORTED for them.
@@ -188,6 +189,19 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
  * instead: every value is a bf16 number, so the products are exact; no image, no workspace, about a quarter of the
  * FP8 rate.  (Values below the bf16 normal range, scale bytes under 16, are rounded to bf16 first.) */
 size_t mxp_image_bytes_fp6(int64_t rows, int64_t K, int n_seg);
+
+/* The same K-segment images for four-bit operands: the exact product with ONE MXFP4++ operand (Sec. 4.3; Sec. 7.1 pairs
+ * MX++ activations with MXFP4 / MXFP4+ weights).  An MXFP4++ block has two scales, 2^shared_exp for its BM and
+ * 2^(shared_exp - delta) for the rest, and a block-scaled MFMA operand has one: the operand is laid out as two segments,
+ * role 1 = every element but the BM (its place zero) with the scale byte lowered by delta, role 2 = the BM alone as the
+ * E2M3 code sign | 11 | mmm (Sec. 4.2) with the block's own scale byte; the other operand, MXFP4 or MXFP4+, as its whole
+ * E2M3 image in both segments (role 0).  `roles` holds two bits per segment.  [1 | 2] x [0 | 0]^T over K = 2 * (K rounded
+ * up to 128) through mxp_gemm_prepacked (kinds MXP_IMAGE_E2M3) is the exact product -- twice the MFMA work of an MXFP4+
+ * product, error bound of the main path; mxp_gemm does this by itself when exactly one format is MXP_FMT_MXFP4PP.
+ * fmt MXP_FMT_MXFP4PP takes roles 1 and 2 only, MXP_FMT_MXFP4 role 0 only (else MXP_ERR_UNSUPPORTED); MXFP4+ takes all
+ * three (delta = 0).  image: mxp_image_bytes_fp6(rows, K, n_seg) bytes, n_seg 1..4. */
+int mxp_prepack_seg(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                    int n_seg, unsigned roles, void* image, size_t image_bytes, void* stream);
 int mxp_prepack_fp6(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                     int n_seg, unsigned res_mask, void* image, size_t image_bytes, void* stream);
 int mxp_prepack_fp8(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, size_t image_bytes,
@@ -216,11 +230,12 @@ int mxp_convert_operands(const void* A, int a_dtype, int64_t M, int64_t K, int64
  * canonical storage, formats chosen per operand (Sec. 5: activations MXFP4+ with weights MXFP4 or MXFP4+).
  * The result is the matrix product of the de-converted operands accumulated in fp32 (Sec. 5.1).
  * D is MXP_F32 or MXP_BF16 with row stride ldd.  workspace must hold mxp_gemm_workspace_bytes(M, N, K) bytes; it is
- * scratch for the two images and may be reused after the call's work on `stream` has finished.  If either format is
- * MXFP4++ (Sec. 4.3) both operands go through E4M3 images (see MXP_IMAGE_E4M3 for what that costs and how exact it is)
- * and the workspace must hold mxp_gemm_workspace_bytes_e4m3(M, N, K) bytes. */
+ * scratch for the two images and may be reused after the call's work on `stream` has finished.  With one MXFP4++ operand
+ * (Sec. 4.3) the product is formed exactly over two K segments (see mxp_prepack_seg; workspace:
+ * mxp_gemm_workspace_size(M, N, K, fmtA, fmtB)); with two, both operands go through E4M3 images (see MXP_IMAGE_E4M3 for
+ * what that costs and how exact it is) and the workspace must hold mxp_gemm_workspace_bytes_e4m3(M, N, K) bytes. */
 size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
-size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when either format is MXP_FMT_MXFP4PP */
+size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when both formats are MXP_FMT_MXFP4PP */
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
  * (see mxp_prepack_fp6 for the cost), plain MXFP6 with MXFP4 or MXFP4+ on the other side (six-bit activations x
  * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product), MXFP8 x MXFP8; 0 for a pair it does not

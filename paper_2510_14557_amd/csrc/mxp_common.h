@@ -33,6 +33,8 @@ int wide_dequantize_launch(const uint8_t* elems, const uint8_t* scales, const ui
 
 int prepack_fp6_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                        int n_seg, uint32_t res_mask, void* image, hipStream_t stream);
+int prepack_seg_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K, int n_seg,
+                       uint32_t roles, void* image, hipStream_t stream);
 int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
 
 // both operands eight-bit (MXFP8 / MXFP8+): the bf16-MFMA product of the de-converted operands (mxp_w4a16.hip)

@@ -125,6 +125,87 @@ __global__ void __launch_bounds__(256) prepack_kernel(const u32x4* __restrict__ 
   prepack_body<PLUS>(blockIdx.x, tiles, tile_scales, elems, scales, bm_idx, rows, nbk, k_tiles, img_elems, img_scales);
 }
 
+// ---- images of several K segments for four-bit operands (the exact MXFP4++ product, Sec. 4.3) ----------------------
+// An MXFP4++ block has two scales: its BM is scaled by 2^shared_exp, every other element by 2^(shared_exp - delta).  One
+// block-scaled MFMA operand carries one scale per block, so the operand is laid out as two K segments side by side --
+// N: all elements but the BM (its place zero), scale byte lowered by delta; B: the BM alone as the E2M3 code
+// sign | 11 | mmm (Sec. 4.2), the block's own scale byte -- and the other operand of the product, an MXFP4 / MXFP4+
+// operand, as its whole image twice (role W).  [N | B] x [W | W]^T is then the exact product, formed by the same kernels
+// over a K of two segments: every element is an E2M3 number under its segment's scale.  `roles` holds two bits per
+// segment (0 W, 1 N, 2 B); each segment is K rounded up to 128 wide.  Patch walk and LDS staging as in prepack_body.
+constexpr uint32_t kRoleWhole = 0, kRoleNbm = 1, kRoleBm = 2;
+
+template <int MODE>   // 0 MXFP4, 1 MXFP4+, 2 MXFP4++
+__global__ void __launch_bounds__(256) prepack_seg_kernel(const u32x4* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                          const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                          int64_t kts, int n_seg, uint32_t roles,
+                                                          uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((kts + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const int64_t k_tiles = kts * n_seg;                         // k-tiles of the whole image
+  const uint32_t slot = (kb_in & 1u) * 32u + r_in;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  uint32_t n[4] = {0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u, delta = 0u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x4 v = __builtin_nontemporal_load(elems + b);
+    n[0] = v.x; n[1] = v.y; n[2] = v.z; n[3] = v.w;
+    sbyte = scales[b];
+    if (MODE >= 1 && sbyte != 0u && sbyte != 255u) {
+      const uint32_t ib = bm_idx[b];
+      bm = ib & 31u;
+      // (an MXFP4+ index byte has its upper bits reserved; a delta beyond scale byte - 1 is outside what a conversion writes)
+      if (MODE == 2) delta = (ib >> 5) < sbyte ? (ib >> 5) : sbyte - 1u;
+    }
+    if (sbyte == 0u) n[0] = n[1] = n[2] = n[3] = 0u;          // flushed block: zero whatever the nibbles say
+  }
+  uint32_t r[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    r[2 * j] = widen4(n[j] & 0xFFFFu);
+    r[2 * j + 1] = widen4(n[j] >> 16);
+  }
+  // the three forms of the block: whole (BM patched to sign | 11 | mmm), without the BM, the BM alone
+  uint32_t whole[8], nbm[8], only[8];
+  const uint32_t piece = bm >> 2, sh = (bm & 3u) * 6u;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t c = (r[j] >> sh) & 0x3Fu;                   // s mmm 00
+    const uint32_t code = (c & 0x20u) | 0x18u | ((c >> 2) & 7u);
+    const bool here = bm < 32u && piece == (uint32_t)j;
+    nbm[j] = here ? r[j] & ~(0x3Fu << sh) : r[j];
+    only[j] = here ? code << sh : 0u;
+    whole[j] = nbm[j] | only[j];
+  }
+  uint8_t* tile = tiles + (kb_in >> 1) * kTileBytes;
+  const int64_t nt = kts - kt0 < 4 ? kts - kt0 : 4;            // tiles of this workgroup that exist (per segment)
+  const uint32_t nbytes = (uint32_t)nt * kTileBytes;
+  for (int sg = 0; sg < n_seg; ++sg) {
+    const uint32_t role = (roles >> (2 * sg)) & 3u;
+    if (sg > 0) __syncthreads();                                // the previous segment has left LDS
+    uint32_t q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = role == kRoleNbm ? nbm[j] : role == kRoleBm ? only[j] : whole[j];
+    const u32x4 lo4 = {q[0] | (q[1] << 24), (q[1] >> 8) | (q[2] << 16), (q[2] >> 16) | (q[3] << 8), q[4] | (q[5] << 24)};
+    const u32x2 hi2 = {(q[5] >> 8) | (q[6] << 16), (q[6] >> 16) | (q[7] << 8)};
+    *reinterpret_cast<u32x4*>(tile + slot * 16u) = lo4;
+    *reinterpret_cast<u32x2*>(tile + 1024u + slot * 8u) = hi2;
+    tile_scales[(kb_in >> 1) * 64u + slot] = (uint8_t)(role == kRoleNbm ? sbyte - delta : sbyte);
+    __syncthreads();
+    const int64_t kt_img = sg * kts + kt0;
+    uint8_t* out = img_elems + (rt * k_tiles + kt_img) * (int64_t)kTileBytes;
+    for (uint32_t o = t * 16u; o < nbytes; o += 256u * 16u)
+      MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
+    if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt_img + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
+  }
+}
+
 // Plain MXFP4 operand -> E2M1 image: the canonical 16-byte blocks moved to their lane slots, scales to the scale
 // dwords (same patch walk as above; flushed blocks are zeroed, padding is zero elements with a unit scale).
 // RES: an MXFP4+ operand kept in 4-bit codes for the few-row product.  The BM (2^2 * 1.m2m1m0) is split as in Eq. 3:
@@ -296,6 +377,24 @@ int prepack_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* b
   return launch_status();
 }
 
+int prepack_seg_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K, int n_seg,
+                       uint32_t roles, void* image, hipStream_t stream) {
+  const ImageGeom seg = image_geom(rows, K), g = image_geom(rows, seg.K_p * n_seg);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  const int64_t n_wg = patch_grid((seg.k_tiles + 3) / 4, seg.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)n_wg);
+  const u32x4* e = reinterpret_cast<const u32x4*>(elems);
+  if (fmt == MXP_FMT_MXFP4PP)
+    hipLaunchKernelGGL(prepack_seg_kernel<2>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, seg.k_tiles, n_seg, roles, ie, is);
+  else if (fmt == MXP_FMT_MXFP4P)
+    hipLaunchKernelGGL(prepack_seg_kernel<1>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, seg.k_tiles, n_seg, roles, ie, is);
+  else
+    hipLaunchKernelGGL(prepack_seg_kernel<0>, grid, dim3(256), 0, stream, e, scales, bm_idx, rows, K / kBlock, seg.k_tiles, n_seg, roles, ie, is);
+  return launch_status();
+}
+
 // mode 0: plain E2M1 image; 1: MXFP4+ operand, BM split, residual bytes behind the scales; 2 / 3: MXFP4++ / MXFP4+
 // operand, BM nibble in place, position | delta << 5 behind the scales (delta = 0 for MXFP4+)
 int prepack_e2m1_launch(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int64_t rows, int64_t K, void* image,
@@ -434,6 +533,25 @@ extern "C" int mxp_prepack_e2m1x(const uint8_t* elems, const uint8_t* scales, co
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(bm_idx) || !aligned16(image)) return MXP_ERR_ALIGN;
   if (image_bytes < mxp_image_bytes_e2m1r(rows, K)) return MXP_ERR_WORKSPACE;
   return prepack_e2m1_launch(elems, scales, bm_idx, rows, K, image, static_cast<hipStream_t>(stream), fmt == MXP_FMT_MXFP4P ? 3 : 2);
+}
+
+extern "C" int mxp_prepack_seg(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
+                               int n_seg, unsigned roles, void* image, size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP4 && fmt != MXP_FMT_MXFP4P && fmt != MXP_FMT_MXFP4PP) return MXP_ERR_FORMAT;
+  if (rows < 0 || K < 0 || K % kBlock != 0 || n_seg < 1 || n_seg > 4 || (roles >> (2 * n_seg)) != 0u) return MXP_ERR_SHAPE;
+  for (int sg = 0; sg < n_seg; ++sg) {
+    const unsigned role = (roles >> (2 * sg)) & 3u;
+    if (role == 3u) return MXP_ERR_SHAPE;
+    // an MXFP4++ operand only exists as its two parts; a plain MXFP4 operand has no BM to split off
+    if (fmt == MXP_FMT_MXFP4PP && role == 0u) return MXP_ERR_UNSUPPORTED;
+    if (fmt == MXP_FMT_MXFP4 && role != 0u) return MXP_ERR_UNSUPPORTED;
+  }
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!elems || !scales || !image || (fmt != MXP_FMT_MXFP4 && !bm_idx)) return MXP_ERR_NULL;
+  if (!aligned16(elems) || !aligned16(scales) || !aligned16(image) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
+  if (image_bytes < mxp_image_bytes_fp6(rows, K, n_seg)) return MXP_ERR_WORKSPACE;
+  return prepack_seg_launch(elems, scales, bm_idx, fmt, rows, K, n_seg, roles, image, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int mxp_prepack(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows,

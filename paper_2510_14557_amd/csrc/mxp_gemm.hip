@@ -527,7 +527,7 @@ __device__ __forceinline__ void issue_prologue(uint8_t* lds, const uint8_t* a_el
   for (int s = 0; s < S - 1; ++s) cp.issue_stage();
 }
 
-// One output tile whose prologue copies are already in flight.  Requires k_tiles >= S + 2 (and even).  `next_kind`
+// One output tile whose prologue copies are already in flight.  Requires k_tiles >= S and even.  `next_kind`
 // (0 none, 2 half, 4 full) and its coordinates: the prologue of the following tile is issued before this tile's
 // epilogue, so that those copies land while the output is being stored.
 template <class C, int S, int WN, bool OUT_BF16>
@@ -537,7 +537,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
                                          int next_kind, int64_t ntm0, int64_t ntn0) {
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
-  static_assert(S == 4, "the peeled tail below is written for a 4-slot ring");
+  static_assert(S >= 4, "ring depth: the prologue keeps S - 1 stages in flight");
   static_assert(C::A_BYTES == 8 * C::AT && C::THREADS == 256 && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
   using CP = Copier<C, S, WN>;
   constexpr int PER_STAGE = CP::PER_STAGE;
@@ -692,19 +692,30 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   using T = std::true_type;
   using F = std::false_type;
   using K1 = std::integral_constant<int, KEEP>;
-  using K0 = std::integral_constant<int, 0>;
 
-  // steady state: iterations 0 .. k_tiles-5 (an even number of them)
-  for (int64_t kt = 0; kt < k_tiles - S; kt += 2) {
+  // steady state: iterations 0 .. k_tiles-S-1, in pairs (the operand registers alternate); k_tiles is even, so an odd
+  // ring depth leaves one single iteration
+  for (int64_t kt = 0; kt + 1 < k_tiles - S; kt += 2) {
     ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
     ktile(T{}, K1{}, T{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
   }
-  // tail (S = 4): k_tiles-4 issues the last stage; k_tiles-3 and k_tiles-2 issue nothing and may leave 1 and 0 stages
-  // in flight; k_tiles-1 has no successor
-  ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
-  ktile(F{}, K1{}, T{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
-  ktile(F{}, K0{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
-  ktile(F{}, K0{}, F{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+  if constexpr (S % 2 == 1) ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+  // tail: iteration k_tiles-S issues the last stage; the S-1 after it issue nothing, so at the wait of the j-th of them
+  // (j = 1 .. S-1) all stages are issued, stage k_tiles-S+j+1 is the one needed and S-2-j newer ones may stay in flight;
+  // the last iteration has no successor to wait for
+  auto tail = [&](auto self, auto jc) {
+    constexpr int J = decltype(jc)::value;
+    if constexpr (J < S) {
+      constexpr int KEEPJ = (J == 0 ? S - 3 : (S - 2 - J > 0 ? S - 2 - J : 0)) * PER_STAGE;
+      using KJ = std::integral_constant<int, KEEPJ>;
+      using CJ = std::integral_constant<bool, J == 0>;
+      using NJ = std::integral_constant<bool, (J < S - 1)>;
+      if constexpr ((S + J) % 2 == 0) ktile(CJ{}, KJ{}, NJ{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+      else ktile(CJ{}, KJ{}, NJ{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+      self(self, std::integral_constant<int, J + 1>{});
+    }
+  };
+  tail(tail, std::integral_constant<int, 0>{});
 #undef MXP_MFMA
 #undef MXP_GAP
 #undef MXP_READ
@@ -1246,6 +1257,128 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
   return launch_status();
 }
 
+// ---- few rows against few weight rows: 16-column tiles ----------------------------------------------------------
+// A layer with N = 4096 has only 128 column tiles of 32 -- half the compute units would read weights, and a compute unit
+// draws about 27 GB/s whatever is in flight, so the product would run at half the HBM rate.  With up to 16 activation
+// rows the 16x16x128 form of the block-scaled MFMA gives twice the workgroups from the same images: a workgroup owns 16
+// weight rows (one half of a 32-row image tile), lane l supplies weight row l % 16 and K-block l / 16 of a 128-wide
+// step (= the two K-blocks of two consecutive image k-tiles), and the two halves of a tile read disjoint 256-byte runs
+// of it.  The activations come from rows 0..15 of their image's first row tile the same way.  The B tile goes in as the
+// MFMA's first operand: accumulator register r of lane l is D[m = l % 16][n = 16 c + 4 (l / 16) + r].  K is split over
+// the wavefronts and summed through LDS in a fixed order, as in gemm_skinny_kernel.  RES: 4-bit MXFP4+ weights with
+// residual bytes (image kind E2M1R): BM_H in the FP4 operand, BM_L by a second MFMA (Eq. 3, Sec. 5.2).
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <bool OUT_BF16, int BT, bool RES, int WAVES, int CHUNK>
+__global__ void __launch_bounds__(64 * WAVES) gemm_skinny16_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                                   const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                                   const uint8_t* __restrict__ b_res, int k_tiles, int64_t M,
+                                                                   int64_t N, void* __restrict__ Dv, int64_t ldd) {
+  static_assert(BT == kTileBytes || BT == kTileBytesE2M1, "weight image: E2M3 or E2M1");
+  static_assert(!RES || BT == kTileBytesE2M1, "residual bytes go with 4-bit codes");
+  constexpr int AT = kTileBytes;
+  constexpr int FB = BT == kTileBytes ? kFmtE2M3 : kFmtE2M1;
+  __shared__ float part[WAVES][4][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t c16 = blockIdx.x, T = c16 >> 1;              // 16-column tile, image row tile
+  const int row16 = lane & 15, kq = lane >> 4;               // weight row in the tile, K-block of the 128-wide step
+  const int slot_b = (kq & 1) * 32 + (int)(c16 & 1) * 16 + row16, slot_a = (kq & 1) * 32 + row16;
+  const int kt_in_pair = kq >> 1;
+  const uint8_t* bt = b_el + T * (int64_t)k_tiles * BT + slot_b * 16;
+  const uint8_t* bth = b_el + T * (int64_t)k_tiles * BT + 1024 + slot_b * 8;
+  const uint8_t* bs = b_sc + ((T >> 2) * (int64_t)k_tiles) * 256 + slot_b * 4;
+  const uint8_t* br = RES ? b_res + T * (int64_t)k_tiles * 64 + slot_b : nullptr;
+  const int b_shift = (int)(T & 3) * 8;
+  const bool a_row = row16 < M;
+  v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+
+  const int n_pairs = k_tiles >> 1;                          // images are padded to K % 128 == 0: k_tiles is even
+  const int n_chunks = (n_pairs + CHUNK - 1) / CHUNK;
+  const int first = (int)((blockIdx.x * 5u) % (uint32_t)n_chunks);   // (workgroups start their walk at different chunks)
+  for (int ci = wave; ci < n_chunks; ci += WAVES) {
+    const int q = ci + first < n_chunks ? ci + first : ci + first - n_chunks;
+    const int p0 = q * CHUNK;
+    v8i b[CHUNK], a[CHUNK];
+    uint32_t sb[CHUNK], sa[CHUNK], rs[CHUNK];
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      const int pr = p0 + c < n_pairs ? p0 + c : n_pairs - 1;       // clamped: the surplus is not used
+      const int64_t kt = 2 * pr + kt_in_pair;
+      const u32x4 lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bt + kt * BT));
+      u32x2 hi = {0, 0};
+      if (BT == kTileBytes) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(bth + kt * BT));
+      b[c] = (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      rs[c] = RES ? (uint32_t)__builtin_nontemporal_load(br + kt * 64) : 0u;
+      sb[c] = *reinterpret_cast<const uint32_t*>(bs + kt * 256) >> b_shift;
+      sa[c] = *reinterpret_cast<const uint32_t*>(a_sc + kt * 256 + slot_a * 4);
+      u32x4 alo = {0, 0, 0, 0};
+      u32x2 ahi = {0, 0};
+      if (a_row) {                                             // rows past M are the image's zero padding: not fetched
+        alo = *reinterpret_cast<const u32x4*>(a_el + kt * AT + slot_a * 16);
+        ahi = *reinterpret_cast<const u32x2*>(a_el + kt * AT + 1024 + slot_a * 8);
+      }
+      a[c] = (v8i){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, 0, 0};
+    }
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) {
+      if (p0 + c < n_pairs) {
+        acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[c], a[c], acc, FB, kFmtE2M3, 0, (int)sb[c], 0, (int)sa[c]);
+        if (RES) {
+          // the tile of BM_L codes: sign | 0 m1 m0 at the block's BM position, zeros elsewhere (no BM: residual byte 0)
+          const uint32_t r = rs[c];
+          const uint32_t word = (((r >> 5) & 3u) | ((r >> 4) & 8u)) << (4u * (r & 7u));
+          const uint32_t piece = (r >> 3) & 3u;
+          const v8i lv = (v8i){(int)(piece == 0u ? word : 0u), (int)(piece == 1u ? word : 0u), (int)(piece == 2u ? word : 0u),
+                               (int)(piece == 3u ? word : 0u), 0, 0, 0, 0};
+          acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(lv, a[c], acc, kFmtE2M1, kFmtE2M3, 0, (int)sb[c], 0, (int)sa[c]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) part[wave][r][lane] = acc[r];
+  __syncthreads();
+  if (tid < 256) {
+    const int l = tid & 63, r = tid >> 6;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) v += part[w][r][l];
+    const int64_t row = l & 15, col = 16 * c16 + 4 * (l >> 4) + r;
+    if (row < M && col < N) {
+      if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col] = (uint16_t)f32_to_bf16_rne(v);
+      else static_cast<float*>(Dv)[row * ldd + col] = v;
+    }
+  }
+}
+
+// Takes M <= 16 when the 32-column kernels would launch fewer than one workgroup per compute unit.
+inline bool skinny16_applies(int64_t M, int64_t N) { return M <= 16 && (N + 31) / 32 < kNumCU; }
+
+template <int BT, bool RES>
+int launch_skinny16(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                    hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K, kTileBytes), gb = image_geom(N, K, BT);
+  if (ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const int kt = (int)ga.k_tiles;
+  const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes, *br = bs + gb.scale_bytes;
+  const dim3 grid((unsigned)((N + 15) / 16)), block(64 * 16);
+  const bool bf = d_dtype == MXP_BF16;
+  const int n_pairs = kt / 2;
+#define MXP_S16(CH)                                                                                                               \
+  do {                                                                                                                            \
+    if (bf) hipLaunchKernelGGL((gemm_skinny16_kernel<true, BT, RES, 16, CH>), grid, block, 0, s, ae, as, be, bs, br, kt, M, N, D, ldd); \
+    else hipLaunchKernelGGL((gemm_skinny16_kernel<false, BT, RES, 16, CH>), grid, block, 0, s, ae, as, be, bs, br, kt, M, N, D, ldd);   \
+  } while (0)
+  // k-steps in flight per wavefront: as many as give every one of the 16 wavefronts a chunk, at most 7 (128 registers per lane)
+  if (n_pairs > 64) MXP_S16(7);
+  else if (n_pairs == 64) MXP_S16(4);
+  else if (n_pairs >= 32) MXP_S16(2);
+  else MXP_S16(1);
+#undef MXP_S16
+  return launch_status();
+}
+
 // ---- skinny-M kernel on canonical weights -----------------------------------------------------------------------
 // The decode stage is bound by the weight bytes (Sec. 7.2).  This kernel reads the canonical arrays as they are: per
 // chunk of 4 k-tiles a wavefront loads, for each of its column tiles, 32 rows x 128 contiguous bytes (8 blocks per row:
@@ -1452,6 +1585,9 @@ int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N,
                      hipStream_t s) {
   // few rows: bound by reading the weights once.  Up to 128 rows when the tiled kernel would get fewer than 64 tile columns
   // (it then leaves most of the chip idle).
+  if constexpr (AT == kTileBytes && (BT == kTileBytes || BT == kTileBytesE2M1)) {
+    if (skinny16_applies(M, N)) return launch_skinny16<BT, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  }
   if (M <= 64 || (M <= 128 && (N + 255) / 256 < 64)) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail) and a whole MI355X (its work
   // lists are cut for 256 compute units in 8 XCDs)
@@ -1473,6 +1609,7 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
       return launch_skinny_res<kTileBytes, true>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     }
     if (a_kind == MXP_IMAGE_E4M3) return launch_skinny_res<kTileBytesE4M3, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    if (skinny16_applies(M, N)) return launch_skinny16<kTileBytesE2M1, true>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_skinny_res<kTileBytes, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
   if (a_kind == MXP_IMAGE_E4M3 && b_kind == MXP_IMAGE_E2M1) {   // MXFP4++ activations x plain MXFP4 weights, few rows
@@ -1483,7 +1620,7 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
     using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
     if (M <= 64) return launch_skinny<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     if (M <= 128 || image_geom(M, K).k_tiles < 4 || !chip().whole_mi355x()) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
-    return launch_dma<C8, MXP_RING>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    return launch_dma<C8, 4>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);   // (4 x 33 KiB: a fifth slot does not fit)
   }
   if (a_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytesE2M1>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   if (b_kind == MXP_IMAGE_E2M1) return gemm_images_kind<kTileBytesE2M1, kTileBytes>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
@@ -1527,7 +1664,6 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
     const int n = fp6_plan(fmtA, fmtB).n_seg;
     return align_up(mxp_image_bytes_fp6(M, K, n)) + align_up(mxp_image_bytes_fp6(N, K, n));
   }
-  if (fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
   {
     const bool fa = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, fb = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
     if ((fmtA == MXP_FMT_MXFP6 && fb) || (fa && fmtB == MXP_FMT_MXFP6)) return mxp_gemm_workspace_bytes(M, N, K);
@@ -1535,7 +1671,9 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
   const bool a4 = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P || fmtA == MXP_FMT_MXFP4PP;
   const bool b4 = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P || fmtB == MXP_FMT_MXFP4PP;
   if (!a4 || !b4) return 0;
-  if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
+  if (fmtA == MXP_FMT_MXFP4PP && fmtB == MXP_FMT_MXFP4PP) return mxp_gemm_workspace_bytes_e4m3(M, N, K);
+  if (fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP)      // one-sided MXFP4++: two K segments per image
+    return align_up(mxp_image_bytes_fp6(M, K, 2)) + align_up(mxp_image_bytes_fp6(N, K, 2));
   return mxp_gemm_workspace_bytes(M, N, K);
 }
 
@@ -1567,11 +1705,14 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
                         int d_dtype, int64_t ldd, void* workspace, size_t workspace_bytes, void* stream) {
   using namespace mxp;
   const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
-  const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;
+  const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;   // (eight: mixed with a narrower format)
   const bool eight_plus = fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P;
-  if (eight_plus) {
+  if (eight_plus || (fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8)) {
     // an E4M7 BM fits no block-scaled MFMA element: the product of the de-converted operands on the bf16 MFMA (exact
-    // products: every value is a bf16 number), both operands eight-bit; no workspace
+    // products: every value is a bf16 number), both operands eight-bit; no workspace.  Plain MXFP8 x MXFP8 takes this
+    // route too: the FP8 MFMA aligns the 64 products of a k-tile to the largest and drops what falls below its adder
+    // width, which the stated error bound of this entry point does not admit (that faster route remains available
+    // through mxp_prepack_fp8 + mxp_gemm_prepacked, with its own bound).
     const bool a8 = fmtA == MXP_FMT_MXFP8 || fmtA == MXP_FMT_MXFP8P, b8 = fmtB == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8P;
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
     if (!a8 || !b8) return MXP_ERR_UNSUPPORTED;
@@ -1633,18 +1774,22 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
     if (rc != MXP_OK) return rc;
     return gemm_images(wa6, MXP_IMAGE_E2M3, wb6, MXP_IMAGE_E2M3, M, N, image_geom(M, K).K_p * plan.n_seg, D, d_dtype, ldd, s);
   }
-  if (eight) {
-    if (workspace_bytes < mxp_gemm_workspace_bytes_e4m3(M, N, K)) return MXP_ERR_WORKSPACE;
-    uint8_t* wa8 = static_cast<uint8_t*>(workspace);
-    uint8_t* wb8 = wa8 + align_up((size_t)image_geom(M, K, kTileBytesE4M3).total());
-    rc = prepack_fp8_launch(A_elems, A_scales, M, K, wa8, s);
+  if (pp && (fmtA == MXP_FMT_MXFP4PP) != (fmtB == MXP_FMT_MXFP4PP)) {
+    // one MXFP4++ operand (Sec. 4.3; Sec. 7.1: MX++ activations on MXFP4 / MXFP4+ weights): the exact product over two K
+    // segments -- the MXFP4++ operand as [elements without the BM, scale lowered by delta | the BM alone, own scale], the
+    // other operand as its E2M3 image twice
+    if (workspace_bytes < mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB)) return MXP_ERR_WORKSPACE;
+    constexpr uint32_t kSplit = 1u | (2u << 2), kTwice = 0u;
+    uint8_t* wa2 = static_cast<uint8_t*>(workspace);
+    uint8_t* wb2 = wa2 + align_up(mxp_image_bytes_fp6(M, K, 2));
+    rc = prepack_seg_launch(A_elems, A_scales, A_idx, fmtA, M, K, 2, fmtA == MXP_FMT_MXFP4PP ? kSplit : kTwice, wa2, s);
     if (rc != MXP_OK) return rc;
-    rc = prepack_fp8_launch(B_elems, B_scales, N, K, wb8, s);
+    rc = prepack_seg_launch(B_elems, B_scales, B_idx, fmtB, N, K, 2, fmtB == MXP_FMT_MXFP4PP ? kSplit : kTwice, wb2, s);
     if (rc != MXP_OK) return rc;
-    return gemm_images(wa8, MXP_IMAGE_E4M3, wb8, MXP_IMAGE_E4M3, M, N, K, D, d_dtype, ldd, s);
+    return gemm_images(wa2, MXP_IMAGE_E2M3, wb2, MXP_IMAGE_E2M3, M, N, image_geom(M, K).K_p * 2, D, d_dtype, ldd, s);
   }
   if (pp) {
-    // an MXFP4++ operand needs the E4M3 image, and then both operands do (Sec. 4.3)
+    // both operands MXFP4++: E4M3 images (Sec. 4.3), FP8 MFMAs
     if (workspace_bytes < mxp_gemm_workspace_bytes_e4m3(M, N, K)) return MXP_ERR_WORKSPACE;
     uint8_t* wa8 = static_cast<uint8_t*>(workspace);
     uint8_t* wb8 = wa8 + align_up((size_t)image_geom(M, K, kTileBytesE4M3).total());

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_seg", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_convert_operands", "mxp_gemm_workspace_size", "mxp_gemm_static", "mxp_gemm_static_capacity", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -76,6 +76,8 @@ def lib():
     L.mxp_image_bytes_fp6.restype = sz
     L.mxp_prepack_fp6.argtypes = [vp, vp, vp, i32, i64, i64, i32, C.c_uint, vp, sz, vp]
     L.mxp_prepack_fp6.restype = i32
+    L.mxp_prepack_seg.argtypes = [vp, vp, vp, i32, i64, i64, i32, C.c_uint, vp, sz, vp]
+    L.mxp_prepack_seg.restype = i32
     L.mxp_prepack_fp8.argtypes = [vp, vp, i64, i64, vp, sz, vp]
     L.mxp_prepack_fp8.restype = i32
     L.mxp_gemm_bf16a_workspace_bytes.argtypes = [i64, i64]
@@ -277,6 +279,18 @@ def prepack_fp6(q, fmt: int = MXFP6P, n_seg: int = 1, res_mask: int = 0, out: to
         out = torch.empty(image_bytes_fp6(rows, K, n_seg), dtype=torch.uint8, device=elems.device)
     _check(lib().mxp_prepack_fp6(_p(elems), _p(scales), _p(idx), fmt, rows, K, n_seg, res_mask, _p(out), out.numel(), _stream()),
            "mxp_prepack_fp6")
+    return out
+
+
+def prepack_seg(q, fmt: int, n_seg: int, roles: int, out: torch.Tensor | None = None):
+    """Canonical MXFP4 / MXFP4+ / MXFP4++ -> E2M3 image of n_seg K segments; two bits of `roles` per segment: 0 the whole
+    operand, 1 all elements but the BM (scale lowered by delta), 2 the BM alone."""
+    elems, scales, idx = q
+    rows, K = elems.shape[0], scales.shape[1] * 32
+    if out is None:
+        out = torch.empty(image_bytes_fp6(rows, K, n_seg), dtype=torch.uint8, device=elems.device)
+    _check(lib().mxp_prepack_seg(_p(elems), _p(scales), _p(idx), fmt, rows, K, n_seg, roles, _p(out), out.numel(), _stream()),
+           "mxp_prepack_seg")
     return out
 
 

@@ -143,7 +143,9 @@ def test_argument_errors_are_reported_not_launched():
     # products: MXFP6 / MXFP6+ pair with each other, MXFP8 with MXFP8, MXFP8+ with nothing
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP6P) == 2 * mxp.image_bytes_fp6(64, 64, 4)
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4) == 0
-    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4)
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == 0                      # exact route: no images
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4) == 2 * mxp.image_bytes_fp6(64, 64, 2)
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4PP) == 2 * mxp.image_bytes_e4m3(64, 64)
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, p, mxp.MXFP4P, p, mxp.F32, 64, p, 1 << 24, None) == -8
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP8P, p, p, p, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -8
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8P, p, p, p, mxp.MXFP8, p, mxp.F32, 64, None, 0, None) == -1
@@ -152,7 +154,11 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, 7, p, mxp.F32, 64, None) == -5
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -1
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1024, None) == -6
-    assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8, p, p, None, mxp.MXFP8, p, mxp.F32, 64, p, 1024, None) == -6
+    assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP4PP, p, p, None, mxp.MXFP4, p, mxp.F32, 64, p, 1024, None) == -6
+    assert L.mxp_prepack_seg(p, p, p, mxp.MXFP4PP, 64, 64, 2, 0, p, 1 << 24, None) == -8        # MXFP4++ has no one-scale form
+    assert L.mxp_prepack_seg(p, p, None, mxp.MXFP4, 64, 64, 2, 1, p, 1 << 24, None) == -8       # MXFP4 has no BM to split off
+    assert L.mxp_prepack_seg(p, p, p, mxp.MXFP4P, 64, 64, 2, 3, p, 1 << 24, None) == -2         # unknown role
+    assert L.mxp_prepack_seg(p, p, p, mxp.MXFP4PP, 64, 64, 2, 9, p, 16, None) == -6
     assert L.mxp_gemm(64, 64, 64, p, p, p, 7, p, p, p, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -5
     # the products take K up to 2^21 (prepacked images, which may hold four K segments: 2^23)
     assert L.mxp_gemm(64, 64, (1 << 21) + 32, p, p, p, 1, p, p, p, 1, p, mxp.F32, 64, p, 1 << 24, None) == -8

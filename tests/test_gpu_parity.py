@@ -881,10 +881,12 @@ def test_gemm_mxfp8_shapes(M, N, K):
     w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
     qa, qb = W.quantize(a, W.MXFP8), W.quantize(w, W.MXFP8)
     ref, S = W.gemm(qa, W.MXFP8, qb, W.MXFP8)
+    # mxp_gemm forms the exact products (bf16 MFMA on de-converted operands): the bound of the main path
     D = mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(qb), mxp.MXFP8)
-    check_gemm_mxfp8(D, ref, S, "mxfp8 %dx%dx%d" % (M, N, K))
+    check_gemm(D, ref, S, "mxfp8 %dx%dx%d" % (M, N, K))
+    # the FP8-MFMA route through E4M3 images stays available, with the bound of that instruction's dot product
     ia, ib = mxp.prepack_fp8(q_dev(qa)), mxp.prepack_fp8(q_dev(qb))
-    assert torch.equal(D, mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3))
+    check_gemm_mxfp8(mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3), ref, S, "mxfp8 images %dx%dx%d" % (M, N, K))
     with pytest.raises(mxp.MxpError):
         mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(W.quantize(w, W.MXFP6)), mxp.MXFP6)       # widths are not mixed
 
@@ -949,29 +951,28 @@ def test_gemm_w4a16_wide_weights(M, N, K, w_fmt):
 
 
 def test_gemm_mxfp8_full_size_sampled():
-    """Benchmark shape, both operands plain MXFP8 converted on the GPU; sampled outputs, the FP8 path's bound."""
+    """Benchmark shape, both operands plain MXFP8 converted on the GPU: the exact route of mxp_gemm to the bound of the main
+    path and the FP8-MFMA route through E4M3 images to its own, one output per 32 x 32 sub-tile each."""
     W = oracle.wide
     M, N, K = 4096, 14336, 4096
     a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
     w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
     qa, qw = mxp.quantize(to_dev(a), mxp.MXFP8), mxp.quantize(to_dev(w), mxp.MXFP8)
-    D = mxp.gemm(qa, mxp.MXFP8, qw, mxp.MXFP8)
-    rng = np.random.default_rng(9)
-    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
-    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
-    sel_a, inv_a = np.unique(rm, return_inverse=True)
-    sel_w, inv_w = np.unique(rn, return_inverse=True)
-    qa_o, qw_o = W.quantize(a[sel_a], W.MXFP8), W.quantize(w[sel_w], W.MXFP8)
+    qa_o, qw_o = W.quantize(a, W.MXFP8), W.quantize(w, W.MXFP8)
     for g, o in list(zip(qa, qa_o))[:2]:
-        assert (g.cpu().numpy()[sel_a] == o).all()
+        assert (g.cpu().numpy() == o).all()
     for g, o in list(zip(qw, qw_o))[:2]:
-        assert (g.cpu().numpy()[sel_w] == o).all()
-    da, dw = W.dequantize(qa_o, W.MXFP8), W.dequantize(qw_o, W.MXFP8)
-    ref = np.einsum("tk,tk->t", da[inv_a], dw[inv_w])
-    S = np.einsum("tk,tk->t", np.abs(da[inv_a]), np.abs(dw[inv_w]))
-    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 2e-4
-    assert (np.abs(got - ref) <= 2.0 ** -10 * S).all()
+        assert (g.cpu().numpy() == o).all()
+    rm, rn = stratified_positions(M, N, np.random.default_rng(9))
+    ref, S = dot_rows(W.dequantize(qa_o, W.MXFP8).astype(np.float32), W.dequantize(qw_o, W.MXFP8).astype(np.float32), rm, rn)
+    D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    mxp.gemm(qa, mxp.MXFP8, qw, mxp.MXFP8, out=D)
+    assert torch.isfinite(D).all()
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, what="mxfp8 x mxfp8, exact route")
+    D.fill_(float("nan"))
+    mxp.gemm_prepacked(M, N, K, mxp.prepack_fp8(qa), mxp.prepack_fp8(qw), out=D, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+    assert torch.isfinite(D).all()
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, log2_tol=-10, fro_tol=2e-4, what="mxfp8 x mxfp8, FP8 images")
 
 
 # ---- the MXFP4++ product (Sec. 4.3) through E4M3 images ------------------------------------------------------------
@@ -1031,7 +1032,6 @@ def test_gemm_mxfp4pp_shapes(M, N, K):
     ref2, S2 = oracle.gemm(qa, oracle.MXFP4PP, qw, oracle.MXFP4P)
     D2 = mxp.gemm_prepacked(M, N, K, ia, mxp.prepack_e4m3(q_dev(qw), mxp.MXFP4P), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
     check_gemm_e4m3(D2, ref2, S2, "mxfp4++ x mxfp4+ %dx%dx%d" % (M, N, K))
-    assert torch.equal(D2, mxp.gemm(q_dev(qa), mxp.MXFP4PP, q_dev(qw), mxp.MXFP4P))
     # operands without a delta span 12 bits: their E4M3 product meets the bound of the main path
     qa1 = oracle.quantize(a, oracle.MXFP4P)
     ref3, S3 = oracle.gemm(qa1, oracle.MXFP4P, qw, oracle.MXFP4P)
@@ -1055,28 +1055,58 @@ def test_gemm_mxfp4pp_special_blocks():
 
 
 def test_gemm_mxfp4pp_full_size_sampled():
+    """Benchmark shape; one output per 32 x 32 sub-tile.  Both operands MXFP4++: E4M3 images, the FP8 path's bound.  MXFP4++
+    activations on MXFP4+ and on MXFP4 weights (Sec. 7.1's pairing): the exact route over two K segments, the main bound."""
     M, N, K = 4096, 14336, 4096
     a = synth.activations(M, K, config_id=4, tensor_id=0, dtype="bf16")
     w = synth.weights(N, K, config_id=4, tensor_id=1, dtype="bf16")
-    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4PP), mxp.quantize(to_dev(w), mxp.MXFP4PP)
-    D = mxp.gemm_prepacked(M, N, K, mxp.prepack_e4m3(qa), mxp.prepack_e4m3(qw), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
-    rng = np.random.default_rng(4)
-    rm = np.concatenate([rng.integers(0, M, 500), [0, M - 1, 255, 256]])
-    rn = np.concatenate([rng.integers(0, N, 500), [0, N - 1, 255, 256]])
-    qa_h = tuple(t.cpu().numpy() for t in qa)
-    qw_h = tuple(t.cpu().numpy() for t in qw)
-    sel_a, inv_a = np.unique(rm, return_inverse=True)
-    sel_w, inv_w = np.unique(rn, return_inverse=True)
-    # the canonical bytes the GPU wrote are the oracle's (checked on the sampled rows), then the product on them
-    for g, o in zip(qa_h, oracle.quantize(a[sel_a], oracle.MXFP4PP)):
-        assert (g[sel_a] == o).all()
-    for g, o in zip(qw_h, oracle.quantize(w[sel_w], oracle.MXFP4PP)):
-        assert (g[sel_w] == o).all()
-    ref, S = oracle.gemm_sampled(tuple(x[sel_a] for x in qa_h), oracle.MXFP4PP, tuple(x[sel_w] for x in qw_h), oracle.MXFP4PP,
-                                 inv_a, inv_w)
-    got = D[torch.from_numpy(rm).cuda(), torch.from_numpy(rn).cuda()].double().cpu().numpy()
-    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 1e-4
-    assert (np.abs(got - ref) <= 2.0 ** -12 * S).all()
+    qa = mxp.quantize(to_dev(a), mxp.MXFP4PP)
+    qa_h = q_host(qa)
+    assert all((g == o).all() for g, o in zip(qa_h, oracle.quantize(a, oracle.MXFP4PP)))
+    rm, rn = stratified_positions(M, N, np.random.default_rng(4))
+    D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    for fw in ("mxfp4pp", "mxfp4p", "mxfp4"):
+        qw = mxp.quantize(to_dev(w), FMT[fw][0])
+        qw_h = q_host(qw)
+        qo = oracle.quantize(w, FMT[fw][1])
+        assert all((g == o).all() for g, o in zip(qw_h[:2 if fw == "mxfp4" else 3], qo))
+        ref, S = oracle.gemm_sampled(qa_h, oracle.MXFP4PP, qw_h, FMT[fw][1], rm, rn)
+        D.fill_(float("nan"))
+        mxp.gemm(qa, mxp.MXFP4PP, qw, FMT[fw][0], out=D)
+        assert torch.isfinite(D).all()
+        if fw == "mxfp4pp":
+            assert_sampled(gather_outputs(D, rm, rn), ref, S, log2_tol=-12, fro_tol=1e-4, what="mxfp4++ x mxfp4++")
+        else:
+            assert_sampled(gather_outputs(D, rm, rn), ref, S, what="mxfp4++ x %s, exact" % fw)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (100, 200, 416), (257, 300, 1024), (300, 520, 2048), (64, 1000, 4160),
+                                   (8, 12840, 256), (129, 70, 128), (16, 520, 512)])
+def test_gemm_one_mxfp4pp_operand_exact(M, N, K):
+    """One MXFP4++ operand next to an MXFP4 / MXFP4+ one (either side): exact over two K segments (elements without the BM
+    under the finer scale | the BM alone under the block's scale), to the bound of the main path; special blocks included."""
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    if M >= 33 and K >= 96:
+        x = mxpp_tensor(rows=M, K=96, seed=5, bf16=True)                 # every delta, flushed and extreme-scale blocks
+        keep = np.isfinite(synth.bf16_bits_to_f32(x)).all(axis=1) & (np.abs(synth.bf16_bits_to_f32(x)).max(axis=1) < 1e30)
+        a[keep, :96] = x[keep]
+    for fa, fb in (("mxfp4pp", "mxfp4p"), ("mxfp4pp", "mxfp4"), ("mxfp4p", "mxfp4pp"), ("mxfp4", "mxfp4pp")):
+        qa, qb = oracle.quantize(a, FMT[fa][1]), oracle.quantize(w, FMT[fb][1])
+        ref, S = oracle.gemm(qa, FMT[fa][1], qb, FMT[fb][1])
+        D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qb), FMT[fb][0], out=D)
+        check_gemm(D, ref, S, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
+        assert torch.equal(mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qb), FMT[fb][0], out_dtype=torch.bfloat16), D.to(torch.bfloat16))
+    # the same through the image entry points (weights packed once)
+    qa, qb = oracle.quantize(a, oracle.MXFP4PP), oracle.quantize(w, oracle.MXFP4P)
+    ia = mxp.prepack_seg(q_dev(qa), mxp.MXFP4PP, 2, 1 | (2 << 2))
+    ib = mxp.prepack_seg(q_dev(qb), mxp.MXFP4P, 2, 0)
+    Kp = (K + 127) // 128 * 128
+    ref, S = oracle.gemm(qa, oracle.MXFP4PP, qb, oracle.MXFP4P)
+    check_gemm(mxp.gemm_prepacked(M, N, 2 * Kp, ia, ib), ref, S, "segment images %dx%dx%d" % (M, N, K))
+    with pytest.raises(mxp.MxpError):
+        mxp.prepack_seg(q_dev(qa), mxp.MXFP4PP, 2, 0)                    # an MXFP4++ operand has no one-scale form
 
 
 @pytest.mark.parametrize("bf16", [False, True])
@@ -1233,8 +1263,10 @@ def test_random_shapes_every_product_path(seed):
         qa, qb = oracle.quantize(a, FMT[fa][1]), oracle.quantize(w, FMT[fb][1])
         ref, S = oracle.gemm(qa, FMT[fa][1], qb, FMT[fb][1])
         D = mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qb), FMT[fb][0])
-        if "pp" in fa + fb:
+        if fa == "mxfp4pp" and fb == "mxfp4pp":
             check_gemm_e4m3(D, ref, S, "%s x %s %s" % (fa, fb, what))
+        elif "pp" in fa + fb:
+            check_gemm(D, ref, S, "%s x %s %s" % (fa, fb, what))         # one MXFP4++ operand: exact over two K segments
         else:
             check_gemm(D, ref, S, "%s x %s %s" % (fa, fb, what))
             img = mxp.prepack_e2m1(q_dev(qb)) if fb == "mxfp4" else mxp.prepack(q_dev(qb), FMT[fb][0])
@@ -1262,7 +1294,7 @@ def test_random_shapes_every_product_path(seed):
         qa, qb = W.quantize(a, WIDE[fa][1]), W.quantize(w, WIDE[fb][1])
         ref, S = W.gemm(qa, WIDE[fa][1], qb, WIDE[fb][1])
         D = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0])
-        (check_gemm_mxfp8 if (fa, fb) == ("mxfp8", "mxfp8") else check_gemm)(D, ref, S, "%s x %s %s" % (fa, fb, what))
+        check_gemm(D, ref, S, "%s x %s %s" % (fa, fb, what))
 
 
 def test_tensors_beyond_4_gib_sampled():
@@ -1498,3 +1530,34 @@ def test_convert_operands_one_launch_matches_the_two_kernels(fa, fw, bf16):
         if M != 37:                                                  # (the special tensors hold NaN blocks and huge values)
             ref, S = oracle.gemm(oracle.quantize(a, FMT[fa][1]), FMT[fa][1], qw_o, FMT[fw][1])
             check_gemm(mxp.gemm_prepacked(M, N, K, ia, iw), ref, S, "product of the images of convert_operands")
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 4096, 4096), (1, 33, 64), (16, 100, 96), (5, 520, 512), (8, 4104, 8192), (13, 1000, 14336),
+                                   (16, 8160, 2048 + 128), (3, 17, 160)])
+def test_gemm_few_rows_few_weight_rows_sixteen_column_tiles(M, N, K):
+    """Up to 16 activation rows against layers with fewer than 8192 weight rows run on 16-column tiles (the 16x16x128 MFMA,
+    twice the workgroups): every weight image kind it takes, both output types, ragged N and K, special weight blocks."""
+    a = synth.activations(M, K, config_id=2, tensor_id=0)
+    w = synth.weights(N, K, config_id=2, tensor_id=1, t3_frac=0.001)
+    if N >= 100:
+        w[7, 32:64] = 0                                                  # flushed weight block
+        w[9, 0:32] = 0x0100                                              # tiny values: flushed as well
+        w[17, 0:32] = synth.f32_to_bf16_bits(np.full(32, 0.3, np.float32))
+        w[17, 31] = synth.f32_to_bf16_bits(np.array([-7.9], np.float32))[0]      # BM last, mantissa carry saturates
+        w[33, 0] = synth.f32_to_bf16_bits(np.array([5.5], np.float32))[0]        # BM first
+    qa = oracle.quantize(a, oracle.MXFP4P)
+    img_a = mxp.prepack(q_dev(qa), mxp.MXFP4P)
+    for fw, kinds in (("mxfp4p", (mxp.IMAGE_E2M3, mxp.IMAGE_E2M1R)), ("mxfp4", (mxp.IMAGE_E2M3, mxp.IMAGE_E2M1))):
+        qw = oracle.quantize(w, FMT[fw][1])
+        ref, S = oracle.gemm(qa, oracle.MXFP4P, qw, FMT[fw][1])
+        for kind in kinds:
+            img_w = (mxp.prepack(q_dev(qw), FMT[fw][0]) if kind == mxp.IMAGE_E2M3 else mxp.prepack_e2m1r(q_dev(qw)) if kind == mxp.IMAGE_E2M1R
+                     else mxp.prepack_e2m1(q_dev(qw)))
+            D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            mxp.gemm_prepacked(M, N, K, img_a, img_w, out=D, b_kind=kind)
+            check_gemm(D, ref, S, "16-column tiles %s kind %d %dx%dx%d" % (fw, kind, M, N, K))
+            Db = mxp.gemm_prepacked(M, N, K, img_a, img_w, out_dtype=torch.bfloat16, b_kind=kind)
+            assert torch.equal(Db, D.to(torch.bfloat16))
+            # activations converted on the fly take the same route (their image's padding row tiles are left unwritten)
+            D2 = mxp.gemm_bf16a(to_dev(a), mxp.MXFP4P, img_w, N, b_kind=kind)
+            assert torch.equal(D2, D)
