@@ -157,13 +157,18 @@ int mxp_prepack_e2m1r(const uint8_t* elems, const uint8_t* scales, const uint8_t
 int mxp_prepack_e2m1x(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
                       void* image, size_t image_bytes, void* stream);
 
-/* MXP_IMAGE_E4M3: the image kind for MXFP4++ operands (Sec. 4.3; it takes MXFP4 and MXFP4+ operands too).  The ordinary
- * elements of an MXFP4++ block are scaled by 2^(shared_exp - delta) and its BM by 2^shared_exp, which one E2M3 code per
- * element cannot express; with the block's scale byte set to (scale byte - delta + 2) every element is an FP8 E4M3
- * number (ordinary: E2M1 value / 4; BM: 1.mmm * 2^delta), so this image carries the block exactly and the product is
- * formed as for the other kinds -- at half the MFMA rate, which is the price of MXFP4++ on this hardware.  Both
- * operands of a product must then be E4M3 images (anything else returns MXP_ERR_UNSUPPORTED).  Index bytes with
- * delta > scale byte - 1 and scale bytes 253, 254, none of which a conversion writes, are outside its domain. */
+/* MXP_IMAGE_E4M3: the image kind for products with BOTH operands MXFP4++ (Sec. 4.3; it takes MXFP4 and MXFP4+ operands
+ * too).  The ordinary elements of an MXFP4++ block are scaled by 2^(shared_exp - delta) and its BM by 2^shared_exp, which
+ * one E2M3 code per element cannot express; with the block's scale byte set to (scale byte - delta + 2) every element is
+ * an FP8 E4M3 number (ordinary: E2M1 value / 4; BM: 1.mmm * 2^delta), so this image carries the block exactly and the
+ * product is formed as for the other kinds on the FP8 MFMA, at half the rate.  Both operands of a product must then be E4M3
+ * images (anything else returns MXP_ERR_UNSUPPORTED).  Index bytes with delta > scale byte - 1 and scale bytes 253, 254,
+ * none of which a conversion writes, are outside its domain.
+ * Error bound of every product on E4M3 images: within each group of eight K-consecutive products the FP8 MFMA aligns
+ * the products to the group's largest and truncates each toward zero 13 bits below that product's leading bit (a property
+ * of the instruction, pinned by a test), so an output is within (7 * 2^-13 + 2^-16) * sum_k |a_k b_k| of the exact
+ * product -- about 2^-10.2, where the E2M3 / E2M1 kinds give 2^-16 (they lose nothing inside a group).  With one MXFP4++
+ * operand use the exact route (mxp_prepack_seg). */
 #define MXP_IMAGE_E4M3 2
 size_t mxp_image_bytes_e4m3(int64_t rows, int64_t K);
 int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t* bm_idx, int fmt, int64_t rows, int64_t K,
@@ -181,13 +186,13 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
  * K = n_seg * (K rounded up to 128) and both kinds MXP_IMAGE_E2M3; mxp_gemm does all of this in its workspace
  * (mxp_gemm_workspace_bytes_fmt).  image: mxp_image_bytes_fp6(rows, K, n_seg) bytes.
  * mxp_prepack_fp8: a plain MXFP8 operand as an MXP_IMAGE_E4M3 image (mxp_image_bytes_e4m3 bytes; the codes are the
- * FP8 numbers the MFMA takes; a NaN code S.1111.111 in the input makes the products it meets NaN).  The FP8 dot
- * product keeps about 13 bits below the largest product of 64 consecutive k (see MXP_IMAGE_E4M3); with operands that
- * use the whole E4M3 range the result is within 2^-10 * sum|a b| of the exact one (measured: 2^-11, unbiased).  The BM of MXFP8+ (eight
- * significant bits, up to 1.992 * 2^8 > 448) would need three E4M3 terms per operand; mxp_gemm forms products with an
- * MXFP8+ operand (the other one MXFP8 or MXFP8+) on the bf16 MFMA from operands de-converted inside the kernel
- * instead: every value is a bf16 number, so the products are exact; no image, no workspace, about a quarter of the
- * FP8 rate.  (Values below the bf16 normal range, scale bytes under 16, are rounded to bf16 first.) */
+ * FP8 numbers the MFMA takes; a NaN code S.1111.111 in the input makes the products it meets NaN).  The product of two
+ * such images (mxp_gemm_prepacked) has the error bound stated at MXP_IMAGE_E4M3, (7 * 2^-13 + 2^-16) * sum|a b|; it is the
+ * fast route (FP8 MFMA), not the one mxp_gemm takes.  mxp_gemm forms every product of eight-bit operands -- MXFP8 and
+ * MXFP8+ in any combination; the MXFP8+ BM, eight significant bits up to 1.992 * 2^8 > 448, fits no FP8 code anyway -- on
+ * the bf16 MFMA from operands de-converted inside the kernel: every value is a bf16 number, so the products are exact and
+ * the bound is that of the main path; no image, no workspace, about a quarter of the FP8 rate.  (Values below the bf16
+ * normal range, scale bytes under 16, are rounded to bf16 first.) */
 size_t mxp_image_bytes_fp6(int64_t rows, int64_t K, int n_seg);
 
 /* The same K-segment images for four-bit operands: the exact product with ONE MXFP4++ operand (Sec. 4.3; Sec. 7.1 pairs
@@ -238,8 +243,8 @@ size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when both formats are MXP_FMT_MXFP4PP */
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
  * (see mxp_prepack_fp6 for the cost), plain MXFP6 with MXFP4 or MXFP4+ on the other side (six-bit activations x
- * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product), MXFP8 x MXFP8; 0 for a pair it does not
- * take and for pairs with MXFP8+, which need none */
+ * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product); 0 for a pair it does not take and for
+ * pairs of eight-bit formats, which need none */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);   /* the same function under its short name */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
