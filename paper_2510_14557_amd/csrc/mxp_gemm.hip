@@ -501,7 +501,8 @@ struct Copier {
     pA += (int64_t)n * C::AT;
     pB += (int64_t)n * C::BT;
     pS += (int64_t)n * 256;
-    wslot += (uint32_t)n * C::STAGE_BYTES;   // n < S and the ring starts at slot 0 for every tile
+    wslot += (uint32_t)n * C::STAGE_BYTES;   // n <= S and the ring starts at slot 0 for every tile
+    if (wslot == wslot_end) wslot -= (uint32_t)S * C::STAGE_BYTES;
   }
 };
 
@@ -515,8 +516,20 @@ __host__ __device__ constexpr int patch_base() {
   return S * C::STAGE_BYTES + 4 * 2 * kPatchBytes <= 160 * 1024 ? S * C::STAGE_BYTES : (S - 1) * C::STAGE_BYTES;
 }
 
-// Stages 0 .. S-2 of a tile (its prologue), issued either at kernel start or while the previous tile is being stored.
-template <class C, int S, int WN>
+// How many stages are kept issued ahead of the one being multiplied.  Iteration kt issues stage kt + depth right behind
+// its barrier, into the slot of stage kt: every wavefront has finished reading that slot by then (it waits for its own LDS
+// reads before the barrier).  That is the whole ring, depth = S, when the epilogue patches have LDS of their own; when they
+// share the last slot, that slot must stay empty across an epilogue and the depth is S - 1.
+// DEEP is chosen per launch: with a single tile per workgroup (few tiles: the launch is bound by how fast one workgroup
+// draws its operands) the whole ring measured 5 % faster, with several tiles per workgroup (the chip is busy everywhere)
+// 2 - 3 % slower than S - 1.
+template <class C, int S, bool DEEP>
+__host__ __device__ constexpr int ring_depth() {
+  return DEEP && patch_base<C, S>() == S * C::STAGE_BYTES ? S : S - 1;
+}
+
+// Stages 0 .. depth-1 of a tile (its prologue), issued either at kernel start or while the previous tile is being stored.
+template <class C, int S, bool DEEP, int WN>
 __device__ __forceinline__ void issue_prologue(uint8_t* lds, const uint8_t* a_el, const uint8_t* a_sc, const uint8_t* b_el,
                                                const uint8_t* b_sc, int64_t k_tiles, int64_t tm0, int64_t tn0) {
   const int tid = threadIdx.x;
@@ -524,20 +537,21 @@ __device__ __forceinline__ void issue_prologue(uint8_t* lds, const uint8_t* a_el
   Copier<C, S, WN> cp;
   cp.init((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0, tid, wave);
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s) cp.issue_stage();
+  for (int s = 0; s < ring_depth<C, S, DEEP>(); ++s) cp.issue_stage();
 }
 
-// One output tile whose prologue copies are already in flight.  Requires k_tiles >= S and even.  `next_kind`
+// One output tile whose prologue copies are already in flight.  Requires k_tiles >= ring depth and even.  `next_kind`
 // (0 none, 2 half, 4 full) and its coordinates: the prologue of the following tile is issued before this tile's
 // epilogue, so that those copies land while the output is being stored.
-template <class C, int S, int WN, bool OUT_BF16>
+template <class C, int S, bool DEEP, int WN, bool OUT_BF16>
 __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc, int64_t k_tiles,
                                          int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd, int64_t tm0, int64_t tn0,
                                          int next_kind, int64_t ntm0, int64_t ntn0) {
   static_assert(C::WM == 4 && C::WN == 4 && C::WAVES_M == 2 && C::WAVES_N == 2, "written for 2 x 2 wavefronts of 4 x 4 tiles");
   static_assert(WN == 4 || WN == 2, "full or half tile");
-  static_assert(S >= 4, "ring depth: the prologue keeps S - 1 stages in flight");
+  static_assert(S >= 4, "ring slots");
+  constexpr int DEPTH = ring_depth<C, S, DEEP>();
   static_assert(C::A_BYTES == 8 * C::AT && C::THREADS == 256 && C::SA_BYTES == 512 && C::SB_BYTES == 512, "stage geometry");
   using CP = Copier<C, S, WN>;
   constexpr int PER_STAGE = CP::PER_STAGE;
@@ -547,7 +561,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   const int wm = wave >> 1, wn = wave & 1;
   CP cp;
   cp.init((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0, tid, wave);
-  cp.skip_stages(S - 1);
+  cp.skip_stages(DEPTH);
 
   v16f acc[4][WN];
 #pragma unroll
@@ -571,13 +585,12 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // Copy accounting.  The copies of one wavefront complete in order, PER_STAGE of them per stage; stores of the
   // previous tile that are still in flight also count in vmcnt, but loads complete in order among themselves, so
   // "at most n operations outstanding" always implies "at most n copies outstanding": a wait can only be longer than
-  // needed, never shorter.  The prologue issued stages 0 .. S-2 and stage 0 is needed: S-2 newer stages may stay in
-  // flight.  Iteration kt waits BEFORE it issues stage kt+S-1, so stages up to kt+S-2 are issued and it needs stage
-  // kt+1: S-3 newer stages may stay in flight.  Stage kt+S-1 goes to the slot of stage kt-1, whose LDS reads (issued
-  // in iteration kt-2) every wavefront has completed before the barrier of iteration kt-1.  The last S-1 iterations
-  // issue nothing and wait for correspondingly fewer stages.
-  constexpr int KEEP_PROLOGUE = (S - 2) * PER_STAGE;
-  constexpr int KEEP = (S - 3) * PER_STAGE;
+  // needed, never shorter.  The prologue issued stages 0 .. DEPTH-1 and stage 0 is needed: DEPTH-1 newer stages may stay
+  // in flight.  Iteration kt waits BEFORE it issues stage kt+DEPTH, so stages up to kt+DEPTH-1 are issued and it needs
+  // stage kt+1: DEPTH-2 newer stages may stay in flight.  The last DEPTH iterations issue nothing and wait for
+  // correspondingly fewer stages.
+  constexpr int KEEP_PROLOGUE = (DEPTH - 1) * PER_STAGE;
+  constexpr int KEEP = (DEPTH - 2) * PER_STAGE;
 
   wait_dma_and_barrier<KEEP_PROLOGUE>();
 #pragma unroll
@@ -591,7 +604,7 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 
   // One k-tile: 4 WN MFMAs on (ca, cb).  An MFMA keeps the matrix pipe busy for ~35 clocks while the wavefront can
   // issue one other instruction every 4 clocks, so the work for later k-tiles is dealt out a few instructions per gap:
-  // the barrier after MFMA 1, then the LDS reads of the next k-tile, then the copies of stage kt + S - 1.
+  // the barrier after MFMA 1, then the LDS reads of the next k-tile, then the copies of stage kt + DEPTH.
   // COPY: this iteration issues a stage.  KEEPN: copies that may stay in flight at its wait.  NEXT: there is a next
   // k-tile to wait for and read.
 #define MXP_MFMA(m)                                                                                                          \
@@ -693,25 +706,23 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   using F = std::false_type;
   using K1 = std::integral_constant<int, KEEP>;
 
-  // steady state: iterations 0 .. k_tiles-S-1, in pairs (the operand registers alternate); k_tiles is even, so an odd
-  // ring depth leaves one single iteration
-  for (int64_t kt = 0; kt + 1 < k_tiles - S; kt += 2) {
+  // steady state: iterations 0 .. k_tiles-DEPTH-1, each issuing a stage, in pairs (the operand registers alternate);
+  // k_tiles is even, so an odd depth leaves one single iteration
+  for (int64_t kt = 0; kt + 1 < k_tiles - DEPTH; kt += 2) {
     ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
     ktile(T{}, K1{}, T{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
   }
-  if constexpr (S % 2 == 1) ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
-  // tail: iteration k_tiles-S issues the last stage; the S-1 after it issue nothing, so at the wait of the j-th of them
-  // (j = 1 .. S-1) all stages are issued, stage k_tiles-S+j+1 is the one needed and S-2-j newer ones may stay in flight;
-  // the last iteration has no successor to wait for
+  if constexpr (DEPTH % 2 == 1) ktile(T{}, K1{}, T{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+  // tail: the last DEPTH iterations issue nothing; at the wait of the j-th of them (j = 0 .. DEPTH-1) all stages are issued,
+  // stage k_tiles-DEPTH+j+1 is the one needed and DEPTH-2-j newer ones may stay in flight; the last has no successor
   auto tail = [&](auto self, auto jc) {
     constexpr int J = decltype(jc)::value;
-    if constexpr (J < S) {
-      constexpr int KEEPJ = (J == 0 ? S - 3 : (S - 2 - J > 0 ? S - 2 - J : 0)) * PER_STAGE;
+    if constexpr (J < DEPTH) {
+      constexpr int KEEPJ = (DEPTH - 2 - J > 0 ? DEPTH - 2 - J : 0) * PER_STAGE;
       using KJ = std::integral_constant<int, KEEPJ>;
-      using CJ = std::integral_constant<bool, J == 0>;
-      using NJ = std::integral_constant<bool, (J < S - 1)>;
-      if constexpr ((S + J) % 2 == 0) ktile(CJ{}, KJ{}, NJ{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
-      else ktile(CJ{}, KJ{}, NJ{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
+      using NJ = std::integral_constant<bool, (J < DEPTH - 1)>;
+      if constexpr ((DEPTH + J) % 2 == 0) ktile(F{}, KJ{}, NJ{}, a0, b0, sa0, sb0, a1, b1, sa1, sb1);
+      else ktile(F{}, KJ{}, NJ{}, a1, b1, sa1, sb1, a0, b0, sa0, sb0);
       self(self, std::integral_constant<int, J + 1>{});
     }
   };
@@ -723,17 +734,17 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
   // every wavefront has read its last fragments: the ring may be refilled
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   store_tile_lds<4, WN, OUT_BF16>(acc, ta, tb, lane, M, N, Dv, ldd, lds + patch_base<C, S>() + wave * (2 * kPatchBytes));
-  if (next_kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
-  else if (next_kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
+  if (next_kind == 4) issue_prologue<C, S, DEEP, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
+  else if (next_kind == 2) issue_prologue<C, S, DEEP, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, ntm0, ntn0);
 }
 
 // Work lists.  The hardware deals workgroups round-robin to the 8 XCDs (workgroup c runs on XCD c % 8), each with its
 // own L2.  Full tiles and half tiles are each put in band order (bands of kBand tile columns, row-major inside a band)
 // and cut into one contiguous run per XCD, sized by the XCD's share of the workgroups; local workgroup j = c / 8 of an
-// XCD with Px workgroups takes positions jj, jj + Px, ... of the run.  Workgroups with even j start with one half tile
-// and do their other half tiles last; those with odd j do all their full tiles first: two phase groups whose output
-// bursts do not coincide.  With 32 workgroups per XCD, jj = j / 2 + 16 (j % 2), so that each phase group of an XCD
-// works on 16 consecutive positions = a 4 x 4 block of tiles sharing 4 A panels and 4 B panels through the XCD's L2.
+// XCD with Px workgroups takes positions j, j + Px, ... of the run, so the 32 workgroups of an XCD work on 32 consecutive
+// positions = an 8 x 4 block of tiles sharing 8 A panels and 4 B panels through that XCD's L2.  The workgroups of even
+// XCDs start with one half tile and do their other half tiles last; those of odd XCDs do all their full tiles first: two
+// phase groups whose output bursts do not coincide.
 constexpr int kBand = 4;
 
 __device__ __forceinline__ void band_decode(int p, int rows, int cols, int& r, int& c) {
@@ -745,7 +756,7 @@ __device__ __forceinline__ void band_decode(int p, int rows, int cols, int& r, i
   c = c0 + (q - r * w);
 }
 
-template <class C, int S, bool OUT_BF16>
+template <class C, int S, bool DEEP, bool OUT_BF16>
 __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
                                                               const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                               int64_t k_tiles, int64_t M, int64_t N, void* __restrict__ Dv,
@@ -759,10 +770,10 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   const int cum0 = x * base + (x < rem ? x : rem), cum1 = cum0 + Px;
   const int f_begin = (int)((int64_t)F * cum0 / P), f_count = (int)((int64_t)F * cum1 / P) - f_begin;
   const int h_begin = (int)((int64_t)H * cum0 / P), h_count = (int)((int64_t)H * cum1 / P) - h_begin;
-  const int jj = Px == 32 ? (j >> 1) + 16 * (j & 1) : j;
+  const int jj = j;
   const int nf = jj < f_count ? (f_count - jj + Px - 1) / Px : 0;
   const int nh = jj < h_count ? (h_count - jj + Px - 1) / Px : 0;
-  const bool lead_half = (j & 1) == 0 && nh > 0;
+  const bool lead_half = (x & 1) == 0 && nh > 0;
   // item `it` of this workgroup: kind (2 half, 4 full) and tile origin in units of 32 rows / columns
   auto item = [&](int it, int& kind, int64_t& tm0, int64_t& tn0) {
     if (it >= nf + nh) { kind = 0; tm0 = tn0 = 0; return; }
@@ -787,12 +798,12 @@ __global__ void __launch_bounds__(C::THREADS) gemm_kernel_dma(const uint8_t* __r
   int kind, nkind;
   int64_t tm0, tn0, ntm0, ntn0;
   item(0, kind, tm0, tn0);
-  if (kind == 4) issue_prologue<C, S, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
-  else if (kind == 2) issue_prologue<C, S, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
+  if (kind == 4) issue_prologue<C, S, DEEP, 4>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
+  else if (kind == 2) issue_prologue<C, S, DEEP, 2>(lds, a_el, a_sc, b_el, b_sc, k_tiles, tm0, tn0);
   for (int it = 0; kind != 0; ++it) {
     item(it + 1, nkind, ntm0, ntn0);
-    if (kind == 2) run_tile<C, S, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
-    else run_tile<C, S, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
+    if (kind == 2) run_tile<C, S, DEEP, 2, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
+    else run_tile<C, S, DEEP, 4, OUT_BF16>(lds, a_el, a_sc, b_el, b_sc, k_tiles, M, N, Dv, ldd, tm0, tn0, nkind, ntm0, ntn0);
     kind = nkind; tm0 = ntm0; tn0 = ntn0;
   }
 }
@@ -854,19 +865,25 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   constexpr size_t lds_patched = (size_t)patch_base<C, S>() + 4 * 2 * kPatchBytes, lds_ring = (size_t)S * C::STAGE_BYTES;
   constexpr size_t lds = lds_patched > lds_ring ? lds_patched : lds_ring;
   static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KiB of a CDNA4 compute unit");
+  // one tile per workgroup at most: the whole ring is kept in flight (see ring_depth)
+  const int64_t Fq = gm * gnf, Hq = gm * nhc;
+  const bool deep = (Fq + P - 1) / P + (Hq + P - 1) / P <= 1;
+#define MXP_GO(DEEPV, BFV)                                                                                                         \
+  do {                                                                                                                             \
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, DEEPV, BFV>),               \
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);                    \
+    (void)once;                                                                                                                    \
+    hipLaunchKernelGGL((gemm_kernel_dma<C, S, DEEPV, BFV>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,           \
+                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);                                           \
+  } while (0)
   if (d_dtype == MXP_BF16) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, true>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
-    (void)once_b;
-    hipLaunchKernelGGL((gemm_kernel_dma<C, S, true>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
-                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);
+    if (deep) MXP_GO(true, true);
+    else MXP_GO(false, true);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, false>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
-    (void)once_f;
-    hipLaunchKernelGGL((gemm_kernel_dma<C, S, false>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,
-                       Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);
+    if (deep) MXP_GO(true, false);
+    else MXP_GO(false, false);
   }
+#undef MXP_GO
   return launch_status();
 }
 
@@ -1802,6 +1819,16 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;
   uint8_t* wa = static_cast<uint8_t*>(workspace);
   uint8_t* wb = wa + align_up((size_t)image_geom(M, K).total());
+  if (M <= 64 && fmtB == MXP_FMT_MXFP4P) {
+    // few rows (the decode stage, Sec. 7.2): the product is bound by the weight bytes, so MXFP4+ weights go into the 4-bit
+    // image with residual bytes (BM_H in place, BM_L by a second MFMA: Eq. 3, Sec. 5.2) instead of the wider E2M3 one --
+    // fewer bytes to write here and fewer to read in the product
+    rc = prepack_launch(A_elems, A_scales, A_idx, fmtA, M, K, wa, s);
+    if (rc != MXP_OK) return rc;
+    rc = prepack_e2m1_launch(B_elems, B_scales, B_idx, N, K, wb, s, 1);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa, MXP_IMAGE_E2M3, wb, MXP_IMAGE_E2M1R, M, N, K, D, d_dtype, ldd, s);
+  }
   // a plain MXFP4 B operand stays in 4-bit codes (smaller image, less operand traffic in the product); so does A
   // when both operands are plain MXFP4
   const bool b4 = fmtB == MXP_FMT_MXFP4, a4 = b4 && fmtA == MXP_FMT_MXFP4;

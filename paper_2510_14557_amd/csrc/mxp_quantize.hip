@@ -858,11 +858,13 @@ template <bool BF16, bool PLUS_A, bool PLUS_W>
 __global__ void __launch_bounds__(256) convert_pair_kernel(const ConvertPairArgs p) {
   __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
   __shared__ uint8_t tile_scales[4 * 64];
-  if (blockIdx.x < p.n_a)
-    quantize_image_body<BF16, PLUS_A>(blockIdx.x, tiles, tile_scales, p.src, p.rows_a, p.nbk, p.ld, p.k_tiles, p.a_elems, p.a_scales,
+  const bool is_a = blockIdx.x < p.n_a;
+  const uint32_t wg = is_a ? blockIdx.x : blockIdx.x - p.n_a;
+  if (is_a)
+    quantize_image_body<BF16, PLUS_A>(wg, tiles, tile_scales, p.src, p.rows_a, p.nbk, p.ld, p.k_tiles, p.a_elems, p.a_scales,
                                       p.a_idx, p.a_img_elems, p.a_img_scales, 0);
   else
-    prepack_body<PLUS_W>(blockIdx.x - p.n_a, tiles, tile_scales, p.w_elems, p.w_scales, p.w_idx, p.rows_w, p.nbk, p.k_tiles,
+    prepack_body<PLUS_W>(wg, tiles, tile_scales, p.w_elems, p.w_scales, p.w_idx, p.rows_w, p.nbk, p.k_tiles,
                          p.w_img_elems, p.w_img_scales);
 }
 
