@@ -274,6 +274,11 @@ def run(ctx):
     cp_dst = torch.empty_like(cp_src)
     st = groups(lambda: cp_dst.copy_(cp_src), 5, 4, warm=3)
     ceil["device_copy_256MiB_GBps"] = 2.0 * (256 << 20) / st["mean"] / 1e6
+    # launch floor: the same conversion kernel on one 32 x 32 tile, 20 launches replayed from a HIP graph -- what a launch
+    # costs before it moves any bytes (dispatch, ramp-up, drain); a 10 us kernel cannot reach the rate of a 100 us one
+    tiny = A[:32, :32].contiguous()
+    qt = mxp.quantize(tiny, mxp.MXFP4P)
+    ceil["launch_floor_us_quantize_one_tile_in_hip_graph"] = graph_us(lambda: mxp.quantize_into(tiny, mxp.MXFP4P, *qt))
     ceil["note"] = ("MFMAs alone on register-resident operands, 1024 wavefronts: the rate the chip sustains at its power limit; "
                     "image_bits = operand registers loaded once from the benchmark's own images; copy = read + written bytes")
     res["measured_ceilings"] = ceil
