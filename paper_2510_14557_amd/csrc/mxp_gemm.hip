@@ -747,11 +747,11 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
 // phase groups whose output bursts do not coincide.
 constexpr int kBand = 4;
 
-__device__ __forceinline__ void band_decode(int p, int rows, int cols, int& r, int& c) {
-  const int per_band = kBand * rows;
+__device__ __forceinline__ void band_decode(int p, int rows, int cols, int& r, int& c, int band_cols = kBand) {
+  const int per_band = band_cols * rows;
   const int band = p / per_band, q = p - band * per_band;
-  const int c0 = band * kBand;
-  const int w = cols - c0 < kBand ? cols - c0 : kBand;
+  const int c0 = band * band_cols;
+  const int w = cols - c0 < band_cols ? cols - c0 : band_cols;
   r = q / w;
   c = c0 + (q - r * w);
 }
@@ -1396,6 +1396,189 @@ int launch_skinny16(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, 
   return launch_status();
 }
 
+// ---- block kernel with K split inside the workgroup (shapes with too few 256-wide tiles to fill the chip) ----------
+// A shape like 2048 x 1024 gives the persistent kernel 64 half tiles for 256 compute units, and what one compute unit
+// can draw from the L2 (about 100 GB/s) then sets the time: its 1.2 MB of operand panels.  Here a workgroup owns a
+// 32 TMR x 32 CT block of the output (128 x 64: 256 workgroups for that shape, 0.6 MB of panels each) and its four
+// wavefronts split K in interleaved chunks: every wavefront holds the whole block in its accumulators, loads its k-tiles
+// of both operands straight from the images into MFMA operand registers (a tile is contiguous and in lane order: no
+// LDS staging, no barrier in the loop, no operand fetched twice by a workgroup), two chunks in flight, and the four
+// partial blocks are added through LDS in a fixed order.  The partial blocks lie in LDS as rows of the output (padded
+// by 16 bytes against bank conflicts), so the summing pass reads and stores 16-byte pieces of full 128- or 256-byte rows.
+// Two chunks of two k-tiles per wavefront in flight (147 KB per compute unit) are enough: with three the launch got slower.
+// Workgroups are dealt to the XCDs like the persistent kernel's tiles, in bands of 8 block columns: 32 consecutive positions
+// = 4 x 8 output blocks per XCD, i.e. 4 row panels and 8 (half as large) column panels, which its L2 then fetches once.
+template <int TMR_, int CT_, int BT_, int AT_>
+struct BlockCfg {
+  static constexpr int WM = TMR_, WN = CT_;
+  static constexpr int FB = BT_ == kTileBytes ? kFmtE2M3 : (BT_ == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
+  static constexpr int FA = AT_ == kTileBytes ? kFmtE2M3 : (AT_ == kTileBytesE4M3 ? kFmtE4M3 : kFmtE2M1);
+};
+
+// One lane's operand registers of a tile in global memory: 16 (E2M1), 24 (E2M3) or 32 (E4M3) bytes
+template <int TB>
+__device__ __forceinline__ v8i load_tile_global(const uint8_t* tile, int lane) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(tile + lane * 16);
+  u32x4 hi = {0, 0, 0, 0};
+  if (TB == kTileBytes) {
+    const u32x2 h2 = *reinterpret_cast<const u32x2*>(tile + 1024 + lane * 8);
+    hi.x = h2.x;
+    hi.y = h2.y;
+  } else if (TB == kTileBytesE4M3) {
+    hi = *reinterpret_cast<const u32x4*>(tile + 1024 + lane * 16);
+  }
+  return (v8i){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+}
+
+template <int TMR, int CT, bool OUT_BF16, int BT, int AT>
+__global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restrict__ a_el, const uint8_t* __restrict__ a_sc,
+                                                         const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
+                                                         int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd,
+                                                         int n_rg, int n_cg) {
+  static_assert((TMR == 2 || TMR == 4) && (CT == 2 || CT == 4), "blocks of 64 or 128 rows by 64 or 128 columns");
+  using C = BlockCfg<TMR, CT, BT, AT>;
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  constexpr int WAVES = 4, CHUNK = 2, NBUF = 2;
+  constexpr int ROWS = 32 * TMR, COLS = 32 * CT, STRIDE = COLS + 4;        // floats per row of a partial block
+  extern __shared__ __attribute__((aligned(16))) uint8_t block_lds[];
+  float* part = reinterpret_cast<float*>(block_lds);                        // [WAVES][ROWS][STRIDE]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // this workgroup's block: position in band order, one contiguous run of positions per XCD
+  const int T = n_rg * n_cg, c = blockIdx.x;
+  const int x = c & 7, j = c >> 3, base = T >> 3, rem = T & 7;
+  int rg, cg;
+  band_decode(x * base + (x < rem ? x : rem) + j, n_rg, n_cg, rg, cg, 8);
+  const int64_t rt0 = (int64_t)rg * TMR, ct0 = (int64_t)cg * CT;           // first row tile of A, first column tile of B
+  const uint8_t* at = a_el + rt0 * k_tiles * AT;
+  const uint8_t* bt = b_el + ct0 * k_tiles * BT;
+  const uint8_t* as = a_sc + ((rt0 >> 2) * k_tiles) * 256 + lane * 4;
+  const uint8_t* bs = b_sc + ((ct0 >> 2) * k_tiles) * 256 + lane * 4;
+  const int a_shift = (int)(rt0 & 3) * 8, b_shift = (int)(ct0 & 3) * 8;    // byte i of the shifted dword = tile i of the block
+
+  v16f acc[TMR][CT];
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int jj = 0; jj < CT; ++jj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][jj][r] = 0.0f;
+
+  auto load_chunk = [&](int q, v8i (&a)[CHUNK][TMR], v8i (&b)[CHUNK][CT], uint32_t (&sa)[CHUNK][1], uint32_t (&sb)[CHUNK][1]) {
+#pragma unroll
+    for (int cc = 0; cc < CHUNK; ++cc) {
+      const int kt = q * CHUNK + cc < k_tiles ? q * CHUNK + cc : k_tiles - 1;   // clamped: the surplus is not used
+#pragma unroll
+      for (int i = 0; i < TMR; ++i) a[cc][i] = load_tile_global<AT>(at + ((int64_t)i * k_tiles + kt) * AT, lane);
+#pragma unroll
+      for (int jj = 0; jj < CT; ++jj) b[cc][jj] = load_tile_global<BT>(bt + ((int64_t)jj * k_tiles + kt) * BT, lane);
+      sa[cc][0] = *reinterpret_cast<const uint32_t*>(as + (int64_t)kt * 256) >> a_shift;
+      sb[cc][0] = *reinterpret_cast<const uint32_t*>(bs + (int64_t)kt * 256) >> b_shift;
+    }
+  };
+  auto mma_chunk = [&](int q, const v8i (&a)[CHUNK][TMR], const v8i (&b)[CHUNK][CT], const uint32_t (&sa)[CHUNK][1],
+                       const uint32_t (&sb)[CHUNK][1]) {
+#pragma unroll
+    for (int cc = 0; cc < CHUNK; ++cc)
+      if (q * CHUNK + cc < k_tiles) mma_all<C>(acc, a[cc], b[cc], sa[cc], sb[cc]);
+  };
+  const int n_chunks = (k_tiles + CHUNK - 1) / CHUNK;
+  // NBUF chunks of this wavefront in flight: buffer n % NBUF holds its n-th chunk
+  v8i a[NBUF][CHUNK][TMR], b[NBUF][CHUNK][CT];
+  uint32_t sa[NBUF][CHUNK][1], sb[NBUF][CHUNK][1];
+#pragma unroll
+  for (int n = 0; n < NBUF - 1; ++n)
+    if (wave + n * WAVES < n_chunks) load_chunk(wave + n * WAVES, a[n], b[n], sa[n], sb[n]);
+  for (int q = wave; q < n_chunks; q += NBUF * WAVES) {
+#pragma unroll
+    for (int n = 0; n < NBUF; ++n) {
+      const int qn = q + n * WAVES;                                         // chunk in buffer n
+      if (qn < n_chunks) {
+        constexpr int ahead = NBUF - 1;
+        if (qn + ahead * WAVES < n_chunks) load_chunk(qn + ahead * WAVES, a[(n + ahead) % NBUF], b[(n + ahead) % NBUF], sa[(n + ahead) % NBUF], sb[(n + ahead) % NBUF]);
+        mma_chunk(qn, a[n], b[n], sa[n], sb[n]);
+      }
+    }
+  }
+  // partial blocks to LDS as output rows: accumulator quad g of lane l is row l % 32, columns 8 g + 4 (l / 32) .. + 3 of its tile
+  float* mine = part + (size_t)wave * ROWS * STRIDE;
+#pragma unroll
+  for (int i = 0; i < TMR; ++i)
+#pragma unroll
+    for (int jj = 0; jj < CT; ++jj)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 q4 = {acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]};
+        *reinterpret_cast<f32x4*>(mine + (32 * i + (lane & 31)) * STRIDE + 32 * jj + 8 * g + 4 * (lane >> 5)) = q4;
+      }
+  __syncthreads();
+  const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
+  constexpr int QUADS = COLS / 4;                                           // 16-byte pieces per row
+  for (int e = tid; e < ROWS * QUADS; e += 256) {
+    const int r = e / QUADS, q = e % QUADS;
+    f32x4 v = *reinterpret_cast<const f32x4*>(part + r * STRIDE + 4 * q);
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) v += *reinterpret_cast<const f32x4*>(part + ((size_t)w * ROWS + r) * STRIDE + 4 * q);
+    const int64_t row = rt0 * 32 + r, col = ct0 * 32 + 4 * q;
+    if (row >= M || col >= N) continue;
+    if (vec_ok && col + 3 < N) {
+      if (OUT_BF16) {
+        const u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(Dv) + row * ldd + col));
+      } else {
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(static_cast<float*>(Dv) + row * ldd + col));
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (col + t < N) {
+          if (OUT_BF16) static_cast<uint16_t*>(Dv)[row * ldd + col + t] = (uint16_t)f32_to_bf16_rne(v[t]);
+          else static_cast<float*>(Dv)[row * ldd + col + t] = v[t];
+        }
+    }
+  }
+}
+
+// Which shapes take the block kernel: more rows than the few-row kernels take, and at most half of the compute units busy
+// with the persistent kernel's half tiles.  Blocks of 128 x 64, or 64 x 64 when those would still leave half the chip idle.
+inline bool block_kernel_applies(int64_t M, int64_t N) {
+  const int64_t half_tiles = 2 * ((M + 255) / 256) * ((N + 255) / 256);
+  const int64_t blocks = ((M + 127) / 128) * ((N + 63) / 64);               // one round of workgroups at most
+  return M > 128 && half_tiles <= kNumCU / 2 && blocks <= kNumCU;
+}
+
+template <int BT, int AT>
+int launch_block(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64_t K, void* D, int d_dtype, int64_t ldd,
+                 hipStream_t s) {
+  const ImageGeom ga = image_geom(M, K, AT), gb = image_geom(N, K, BT);
+  if (ga.k_tiles > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const int kt = (int)ga.k_tiles;
+  const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
+  const bool bf = d_dtype == MXP_BF16;
+  const int64_t n_cg = (N + 63) / 64;
+  const bool tall = ((M + 127) / 128) * n_cg >= kNumCU / 2;
+  const int64_t n_rg = tall ? (M + 127) / 128 : (M + 63) / 64;
+#define MXP_BLOCK(TMRV, BFV)                                                                                                      \
+  do {                                                                                                                            \
+    constexpr int lds = 4 * 32 * TMRV * (64 + 4) * 4;                                                                             \
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_block_kernel<TMRV, 2, BFV, BT, AT>),        \
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);                       \
+    (void)once;                                                                                                                   \
+    hipLaunchKernelGGL((gemm_block_kernel<TMRV, 2, BFV, BT, AT>), dim3((unsigned)(n_rg * n_cg)), dim3(256), lds, s, ae, as, be, bs, \
+                       kt, M, N, D, ldd, (int)n_rg, (int)n_cg);                                                                   \
+  } while (0)
+  if (tall) {
+    if (bf) MXP_BLOCK(4, true);
+    else MXP_BLOCK(4, false);
+  } else {
+    if (bf) MXP_BLOCK(2, true);
+    else MXP_BLOCK(2, false);
+  }
+#undef MXP_BLOCK
+  return launch_status();
+}
+
 // ---- skinny-M kernel on canonical weights -----------------------------------------------------------------------
 // The decode stage is bound by the weight bytes (Sec. 7.2).  This kernel reads the canonical arrays as they are: per
 // chunk of 4 k-tiles a wavefront loads, for each of its column tiles, 32 rows x 128 contiguous bytes (8 blocks per row:
@@ -1606,6 +1789,7 @@ int gemm_images_kind(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N,
     if (skinny16_applies(M, N)) return launch_skinny16<BT, false>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   }
   if (M <= 64 || (M <= 128 && (N + 255) / 256 < 64)) return launch_skinny<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+  if (block_kernel_applies(M, N)) return launch_block<BT, AT>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
   // the pipelined kernel needs at least 4 k-tiles (prologue of 3 stages + peeled tail) and a whole MI355X (its work
   // lists are cut for 256 compute units in 8 XCDs)
   if (image_geom(M, K).k_tiles < 4 || !chip().whole_mi355x()) return launch_cfg<Cfg<4, 4, 2, 2, BT, AT>>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);

@@ -612,6 +612,66 @@ def test_gemm_random_shapes_sampled():
             assert torch.isfinite(D).all()
 
 
+def _routes_to_persistent_kernel(M, N):
+    """The launcher's rule, restated: more than 128 rows, and either more than 128 half tiles of 256 x 128 or more than
+    256 blocks of 128 x 64 (otherwise the block kernel with K split inside the workgroup takes the shape)."""
+    half_tiles = 2 * ((M + 255) // 256) * ((N + 255) // 256)
+    blocks = ((M + 127) // 128) * ((N + 63) // 64)
+    return M > 128 and not (half_tiles <= 128 and blocks <= 256)
+
+
+@pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
+@pytest.mark.parametrize("M,N,K,pad", [(1300, 3000, 256, 0), (2100, 2085, 384, 3), (300, 8300, 672, 0), (1025, 3000, 512, 8),
+                                       (385, 6030, 1088, 1)])
+def test_gemm_persistent_kernel_ragged_shapes(M, N, K, pad, w_fmt):
+    """Ragged edges, K of 4 ... 18 k-tiles (even and odd, with and without a padded tail), aligned, strided and unaligned
+    outputs, fp32 and bf16, on shapes large enough for the persistent tiled kernel: one output of every 32 x 32 sub-tile
+    against the oracle, every output written, nothing written outside."""
+    assert _routes_to_persistent_kernel(M, N)
+    a = synth.activations(M, K, config_id=1, tensor_id=60)
+    w = synth.weights(N, K, config_id=1, tensor_id=61, t3_frac=0.001)
+    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4P), mxp.quantize(to_dev(w), FMT[w_fmt][0])
+    qh, qwh = q_host(qa), q_host(qw)
+    rm, rn = stratified_positions(M, N, np.random.default_rng(M + N))
+    ref, S = oracle.gemm_sampled(qh, oracle.MXFP4P, qwh, FMT[w_fmt][1], rm, rn)
+    outs = {}
+    for dt in (torch.float32, torch.bfloat16):
+        buf = torch.full((M, N + pad + 1), float("nan"), dtype=dt, device="cuda")
+        D = buf[:, 1:1 + N] if pad % 2 else buf[:, :N]                    # odd pad: first element off the 16-byte grid
+        mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0], out=D)
+        torch.cuda.synchronize()
+        assert torch.isfinite(D).all()
+        rest = buf[:, :1] if pad % 2 else buf[:, N:]
+        assert torch.isnan(rest).all() and (not pad % 2 or torch.isnan(buf[:, 1 + N:]).all())
+        outs[dt] = D
+    assert_sampled(gather_outputs(outs[torch.float32], rm, rn), ref, S, what="%dx%dx%d %s" % (M, N, K, w_fmt))
+    assert torch.equal(outs[torch.bfloat16], outs[torch.float32].to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
+@pytest.mark.parametrize("M,N,K", [(2048, 1024, 4096), (129, 33, 7168), (130, 1000, 64), (512, 4096, 320), (700, 1500, 1024),
+                                   (1000, 1100, 192), (2049, 300, 2144)])
+def test_gemm_block_kernel_shapes_sampled(M, N, K, w_fmt):
+    """Shapes with too few 256-wide tiles for the persistent kernel: blocks of 128 x 64 or 64 x 64 with K split over the
+    workgroup's wavefronts (1 ... 112 k-tiles: fewer chunks than wavefronts, odd counts, one chunk each, many)."""
+    assert M > 128 and not _routes_to_persistent_kernel(M, N)
+    a = synth.activations(M, K, config_id=3, tensor_id=62)
+    w = synth.weights(N, K, config_id=3, tensor_id=63, t3_frac=0.001)
+    qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4P), mxp.quantize(to_dev(w), FMT[w_fmt][0])
+    D = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0], out=D)
+    torch.cuda.synchronize()
+    assert torch.isfinite(D).all()
+    rm, rn = stratified_positions(M, N, np.random.default_rng(M * N))
+    ref, S = oracle.gemm_sampled(q_host(qa), oracle.MXFP4P, q_host(qw), FMT[w_fmt][1], rm, rn)
+    assert_sampled(gather_outputs(D, rm, rn), ref, S, what="block %dx%dx%d %s" % (M, N, K, w_fmt))
+    Db = mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0], out_dtype=torch.bfloat16)
+    assert torch.equal(Db, D.to(torch.bfloat16))
+    # the same launch twice gives the same bits: the partial blocks are added in a fixed order
+    D2 = mxp.gemm(qa, mxp.MXFP4P, qw, FMT[w_fmt][0])
+    assert torch.equal(D, D2)
+
+
 def test_gemm_full_size_decode_sampled():
     _sampled_check("decode")
 
