@@ -1540,12 +1540,14 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
   }
 }
 
-// Which shapes take the block kernel: more rows than the few-row kernels take, and at most half of the compute units busy
-// with the persistent kernel's half tiles.  Blocks of 128 x 64, or 64 x 64 when those would still leave half the chip idle.
+// Which shapes take the block kernel: more rows than the few-row kernels take, and at most two rounds of 128 x 64 blocks on
+// the chip's compute units.  Measured against the persistent kernel at K = 4096: one round (2048 x 1024, 512 x 4096,
+// 1024 x 2048) 11 - 13 us against 24; two rounds (1024 x 4096, 2048 x 2048, 512 x 8192) 22 - 23 us against 24.5; four rounds
+// (2048 x 4096) 44 us against 29 -- there every compute unit already has a half tile of its own.
+// Blocks are 64 x 64 when 128 x 64 ones would leave more than half of the chip idle.
 inline bool block_kernel_applies(int64_t M, int64_t N) {
-  const int64_t half_tiles = 2 * ((M + 255) / 256) * ((N + 255) / 256);
-  const int64_t blocks = ((M + 127) / 128) * ((N + 63) / 64);               // one round of workgroups at most
-  return M > 128 && half_tiles <= kNumCU / 2 && blocks <= kNumCU;
+  const int64_t blocks = ((M + 127) / 128) * ((N + 63) / 64);
+  return M > 128 && blocks <= 2 * kNumCU;
 }
 
 template <int BT, int AT>
@@ -1820,6 +1822,7 @@ int gemm_images(const void* A_image, int a_kind, const void* B_image, int b_kind
   if (a_kind == MXP_IMAGE_E4M3) {
     using C8 = Cfg<4, 4, 2, 2, kTileBytesE4M3, kTileBytesE4M3>;
     if (M <= 64) return launch_skinny<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
+    if (block_kernel_applies(M, N)) return launch_block<kTileBytesE4M3, kTileBytesE4M3>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     if (M <= 128 || image_geom(M, K).k_tiles < 4 || !chip().whole_mi355x()) return launch_cfg<C8>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);
     return launch_dma<C8, 4>(Ai, Bi, M, N, K, D, d_dtype, ldd, s);   // (4 x 33 KiB: a fifth slot does not fit)
   }

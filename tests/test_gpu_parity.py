@@ -613,16 +613,14 @@ def test_gemm_random_shapes_sampled():
 
 
 def _routes_to_persistent_kernel(M, N):
-    """The launcher's rule, restated: more than 128 rows, and either more than 128 half tiles of 256 x 128 or more than
-    256 blocks of 128 x 64 (otherwise the block kernel with K split inside the workgroup takes the shape)."""
-    half_tiles = 2 * ((M + 255) // 256) * ((N + 255) // 256)
-    blocks = ((M + 127) // 128) * ((N + 63) // 64)
-    return M > 128 and not (half_tiles <= 128 and blocks <= 256)
+    """The launcher's rule, restated: more than 128 rows and more than 512 blocks of 128 x 64 (up to there the block kernel
+    with K split inside the workgroup takes the shape)."""
+    return M > 128 and ((M + 127) // 128) * ((N + 63) // 64) > 512
 
 
 @pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
-@pytest.mark.parametrize("M,N,K,pad", [(1300, 3000, 256, 0), (2100, 2085, 384, 3), (300, 8300, 672, 0), (1025, 3000, 512, 8),
-                                       (385, 6030, 1088, 1)])
+@pytest.mark.parametrize("M,N,K,pad", [(1300, 3000, 256, 0), (2100, 2085, 384, 3), (300, 12000, 672, 0), (1025, 4200, 512, 8),
+                                       (385, 9030, 1088, 1)])
 def test_gemm_persistent_kernel_ragged_shapes(M, N, K, pad, w_fmt):
     """Ragged edges, K of 4 ... 18 k-tiles (even and odd, with and without a padded tail), aligned, strided and unaligned
     outputs, fp32 and bf16, on shapes large enough for the persistent tiled kernel: one output of every 32 x 32 sub-tile
@@ -650,10 +648,11 @@ def test_gemm_persistent_kernel_ragged_shapes(M, N, K, pad, w_fmt):
 
 @pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
 @pytest.mark.parametrize("M,N,K", [(2048, 1024, 4096), (129, 33, 7168), (130, 1000, 64), (512, 4096, 320), (700, 1500, 1024),
-                                   (1000, 1100, 192), (2049, 300, 2144)])
+                                   (1000, 1100, 192), (2049, 300, 2144), (1024, 2100, 320), (1025, 3000, 512)])
 def test_gemm_block_kernel_shapes_sampled(M, N, K, w_fmt):
     """Shapes with too few 256-wide tiles for the persistent kernel: blocks of 128 x 64 or 64 x 64 with K split over the
-    workgroup's wavefronts (1 ... 112 k-tiles: fewer chunks than wavefronts, odd counts, one chunk each, many)."""
+    workgroup's wavefronts (1 ... 112 k-tiles: fewer chunks than wavefronts, odd counts, one chunk each, many), in one
+    round of workgroups and in two."""
     assert M > 128 and not _routes_to_persistent_kernel(M, N)
     a = synth.activations(M, K, config_id=3, tensor_id=62)
     w = synth.weights(N, K, config_id=3, tensor_id=63, t3_frac=0.001)
