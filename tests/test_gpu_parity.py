@@ -1666,3 +1666,36 @@ def test_fp8_mfma_sums_groups_of_eight_products_truncated_13_bits_below_the_larg
     # the exact route of mxp_gemm on the same operands loses nothing but fp32 accumulation
     Dx = mxp.gemm(q_dev((ca, scales, scales)), mxp.MXFP8, q_dev((cb, scales, scales)), mxp.MXFP8).double().cpu().numpy()
     assert (np.abs(Dx - exact) <= 2.0 ** -16 * S).all() and np.abs(Dx - exact).max() < np.abs(D - exact).max()
+
+
+def test_new_entry_points_on_empty_and_degenerate_inputs():
+    """Empty sides of the one-launch conversion fall back to the single conversions; a one-segment image of role 'whole'
+    is the ordinary image; the no-allocation product handles K = 0 (zero-filled result) and M = 0 (nothing written)."""
+    K, N = 256, 96
+    a = to_dev(synth.activations(40, K, config_id=1, tensor_id=70, dtype="bf16"))
+    w = synth.weights(N, K, config_id=1, tensor_id=71)
+    qw = mxp.quantize(to_dev(w), mxp.MXFP4P)
+    img_w_ref = mxp.prepack(qw, mxp.MXFP4P)
+    img_a_ref, qa_ref = mxp.quantize_image(a, mxp.MXFP4P, canonical=True)
+    # M = 0: only the weight image is written
+    img_w = torch.zeros_like(img_w_ref)
+    empty_a = torch.empty((0, K), dtype=torch.bfloat16, device="cuda")
+    mxp.convert_operands(empty_a, mxp.MXFP4P, None, torch.empty(0, dtype=torch.uint8, device="cuda"), qw, mxp.MXFP4P, img_w)
+    assert torch.equal(img_w, img_w_ref)
+    # N = 0: only the activation side
+    img_a = torch.zeros_like(img_a_ref)
+    qa = tuple(torch.zeros_like(t) for t in qa_ref)
+    e = torch.empty((0, K // 2), dtype=torch.uint8, device="cuda")
+    s = torch.empty((0, K // 32), dtype=torch.uint8, device="cuda")
+    mxp.convert_operands(a, mxp.MXFP4P, qa, img_a, (e, s, s), mxp.MXFP4P, torch.empty(0, dtype=torch.uint8, device="cuda"))
+    assert torch.equal(img_a, img_a_ref) and all(torch.equal(x, y) for x, y in zip(qa, qa_ref))
+    # one K segment holding the whole operand = the ordinary image
+    assert torch.equal(mxp.prepack_seg(qw, mxp.MXFP4P, 1, 0), img_w_ref)
+    # no-allocation product: K = 0 and M = 0
+    z8 = lambda r, c: torch.empty((r, c), dtype=torch.uint8, device="cuda")
+    out = torch.full((5, 7), 3.0, device="cuda")
+    mxp.gemm_static((z8(5, 0),) * 3, mxp.MXFP4P, (z8(7, 0),) * 3, mxp.MXFP4P, out)
+    assert not out.any()
+    out0 = torch.empty((0, N), device="cuda")
+    mxp.gemm_static((z8(0, K // 2), z8(0, K // 32), z8(0, K // 32)), mxp.MXFP4P, qw, mxp.MXFP4P, out0)
+    torch.cuda.synchronize()
