@@ -242,9 +242,10 @@ int mxp_convert_operands(const void* A, int a_dtype, int64_t M, int64_t K, int64
 size_t mxp_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when both formats are MXP_FMT_MXFP4PP */
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
- * (see mxp_prepack_fp6 for the cost), plain MXFP6 with MXFP4 or MXFP4+ on the other side (six-bit activations x
- * four-bit weights: one E2M3 image each, at the rate of the MXFP4+ product); 0 for a pair it does not take and for
- * pairs of eight-bit formats, which need none */
+ * (see mxp_prepack_fp6 for the cost), MXFP6 or MXFP6+ with MXFP4 or MXFP4+ on the other side (plain MXFP6: one E2M3
+ * image each, at the rate of the MXFP4+ product; MXFP6+: its two K segments against the four-bit operand's image laid out
+ * twice, twice the work); 0 for a pair it does not take (a six-bit format next to MXFP4++, plain MXFP8 next to a narrower
+ * format) and for pairs of eight-bit formats, which need none */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);   /* the same function under its short name */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,

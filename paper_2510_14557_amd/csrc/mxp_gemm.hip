@@ -1879,6 +1879,8 @@ extern "C" size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, 
   {
     const bool fa = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, fb = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
     if ((fmtA == MXP_FMT_MXFP6 && fb) || (fa && fmtB == MXP_FMT_MXFP6)) return mxp_gemm_workspace_bytes(M, N, K);
+    if ((fmtA == MXP_FMT_MXFP6P && fb) || (fa && fmtB == MXP_FMT_MXFP6P))
+      return align_up(mxp_image_bytes_fp6(M, K, 2)) + align_up(mxp_image_bytes_fp6(N, K, 2));
   }
   const bool a4 = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P || fmtA == MXP_FMT_MXFP4PP;
   const bool b4 = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P || fmtB == MXP_FMT_MXFP4PP;
@@ -1941,10 +1943,11 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   }
   if (six || eight) {
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
-    // both operands six-bit, or both plain MXFP8, or plain MXFP6 with MXFP4 / MXFP4+ (one segment: the same E2M3 / E2M1
-    // images as ever; an MXFP6+ operand would need the four-bit one laid out twice)
+    // both operands six-bit, or both plain MXFP8, or a six-bit operand with MXFP4 / MXFP4+ (plain MXFP6: one segment, the
+    // same E2M3 / E2M1 images as ever; MXFP6+: its two K segments, primary and BM residual, against the four-bit operand's
+    // E2M3 image laid out twice)
     const bool four_a = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, four_b = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
-    const bool mixed64 = (fmtA == MXP_FMT_MXFP6 && four_b) || (four_a && fmtB == MXP_FMT_MXFP6);
+    const bool mixed64 = (is_fp6(fmtA) && four_b) || (four_a && is_fp6(fmtB));
     if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !(fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) && !mixed64) return MXP_ERR_UNSUPPORTED;
   } else if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
              (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP)) {
@@ -1960,6 +1963,19 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(workspace) ||
       (A_idx && !aligned16(A_idx)) || (B_idx && !aligned16(B_idx)))
     return MXP_ERR_ALIGN;
+  if (six && !(is_fp6(fmtA) && is_fp6(fmtB)) && (fmtA == MXP_FMT_MXFP6P || fmtB == MXP_FMT_MXFP6P)) {
+    // MXFP6+ with a four-bit operand (Sec. 5: the approach carries over to MXFP6+): two K segments
+    if (workspace_bytes < mxp_gemm_workspace_bytes_fmt(M, N, K, fmtA, fmtB)) return MXP_ERR_WORKSPACE;
+    uint8_t* wa2 = static_cast<uint8_t*>(workspace);
+    uint8_t* wb2 = wa2 + align_up(mxp_image_bytes_fp6(M, K, 2));
+    rc = is_fp6(fmtA) ? prepack_fp6_launch(A_elems, A_scales, A_idx, fmtA, M, K, 2, 0x2u, wa2, s)
+                      : prepack_seg_launch(A_elems, A_scales, A_idx, fmtA, M, K, 2, 0u, wa2, s);
+    if (rc != MXP_OK) return rc;
+    rc = is_fp6(fmtB) ? prepack_fp6_launch(B_elems, B_scales, B_idx, fmtB, N, K, 2, 0x2u, wb2, s)
+                      : prepack_seg_launch(B_elems, B_scales, B_idx, fmtB, N, K, 2, 0u, wb2, s);
+    if (rc != MXP_OK) return rc;
+    return gemm_images(wa2, MXP_IMAGE_E2M3, wb2, MXP_IMAGE_E2M3, M, N, image_geom(M, K).K_p * 2, D, d_dtype, ldd, s);
+  }
   if (six && !(is_fp6(fmtA) && is_fp6(fmtB))) {
     // plain MXFP6 with a four-bit operand: one E2M3 image each (a plain MXFP4 B stays in four-bit codes)
     if (workspace_bytes < mxp_gemm_workspace_bytes(M, N, K)) return MXP_ERR_WORKSPACE;

@@ -875,7 +875,7 @@ def test_gemm_mxfp6_shapes(fa, fb, M, N, K):
 
 @pytest.mark.parametrize("M,N,K", [(33, 100, 96), (257, 300, 1024), (64, 1000, 2080), (300, 520, 2048)])
 def test_gemm_mxfp6_activations_with_four_bit_weights(M, N, K):
-    """Plain MXFP6 on one side, MXFP4 / MXFP4+ on the other: one E2M3 (or E2M1) image each, exact products."""
+    """MXFP6 or MXFP6+ on one side, MXFP4 / MXFP4+ on the other: exact products."""
     W = oracle.wide
     a = synth.activations(M, K, config_id=1, tensor_id=0)
     w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
@@ -892,8 +892,20 @@ def test_gemm_mxfp6_activations_with_four_bit_weights(M, N, K):
     a4, w6 = oracle.dequantize(qa4, oracle.MXFP4P).astype(np.float64), W.dequantize(qw6, W.MXFP6)
     D = mxp.gemm(q_dev(qa4), mxp.MXFP4P, q_dev(qw6), mxp.MXFP6)
     check_gemm(D, a4 @ w6.T, np.abs(a4) @ np.abs(w6).T, "mxfp4+ x mxfp6 %dx%dx%d" % (M, N, K))
-    with pytest.raises(mxp.MxpError):
-        mxp.gemm(q_dev(W.quantize(a, W.MXFP6P)), mxp.MXFP6P, q_dev(oracle.quantize(w, oracle.MXFP4P)), mxp.MXFP4P)
+    # MXFP6+ next to a four-bit operand, either way round (two K segments: primary and BM residual / the other image twice)
+    qa6p = W.quantize(a, W.MXFP6P)
+    a6p = W.dequantize(qa6p, W.MXFP6P)
+    for w_fmt in ("mxfp4p", "mxfp4"):
+        qw = oracle.quantize(w, FMT[w_fmt][1])
+        w64 = oracle.dequantize(qw, FMT[w_fmt][1]).astype(np.float64)
+        D = mxp.gemm(q_dev(qa6p), mxp.MXFP6P, q_dev(qw), FMT[w_fmt][0])
+        check_gemm(D, a6p @ w64.T, np.abs(a6p) @ np.abs(w64).T, "mxfp6+ x %s %dx%dx%d" % (w_fmt, M, N, K))
+    qw6p = W.quantize(w, W.MXFP6P)
+    w6p = W.dequantize(qw6p, W.MXFP6P)
+    D = mxp.gemm(q_dev(qa4), mxp.MXFP4P, q_dev(qw6p), mxp.MXFP6P)
+    check_gemm(D, a4 @ w6p.T, np.abs(a4) @ np.abs(w6p).T, "mxfp4+ x mxfp6+ %dx%dx%d" % (M, N, K))
+    with pytest.raises(mxp.MxpError):                                      # still refused: six-bit next to MXFP4++
+        mxp.gemm(q_dev(qa6p), mxp.MXFP6P, q_dev(oracle.quantize(w, oracle.MXFP4PP)), mxp.MXFP4PP)
 
 
 def test_gemm_mxfp6_special_blocks():
