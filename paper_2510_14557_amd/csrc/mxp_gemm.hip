@@ -1921,34 +1921,32 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
   const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;   // (eight: mixed with a narrower format)
   const bool eight_plus = fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P;
-  if (eight_plus || (fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8)) {
+  if (eight_plus || eight) {
     // an E4M7 BM fits no block-scaled MFMA element: the product of the de-converted operands on the bf16 MFMA (exact
-    // products: every value is a bf16 number), both operands eight-bit; no workspace.  Plain MXFP8 x MXFP8 takes this
-    // route too: the FP8 MFMA aligns the 64 products of a k-tile to the largest and drops what falls below its adder
-    // width, which the stated error bound of this entry point does not admit (that faster route remains available
-    // through mxp_prepack_fp8 + mxp_gemm_prepacked, with its own bound).
-    const bool a8 = fmtA == MXP_FMT_MXFP8 || fmtA == MXP_FMT_MXFP8P, b8 = fmtB == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8P;
+    // products: every value is a bf16 number), at least one operand eight-bit, the other of any format; no workspace.
+    // Plain MXFP8 x MXFP8 takes this route too: the FP8 MFMA aligns the 64 products of a k-tile to the largest and drops
+    // what falls below its adder width, which the stated error bound of this entry point does not admit (that faster route
+    // remains available through mxp_prepack_fp8 + mxp_gemm_prepacked, with its own bound).
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
-    if (!a8 || !b8) return MXP_ERR_UNSUPPORTED;
     int rc8 = check_gemm(M, N, K, D, d_dtype, ldd);
     if (rc8 != MXP_OK || M == 0 || N == 0) return rc8;
     hipStream_t s8 = static_cast<hipStream_t>(stream);
     if (K == 0) return zero_output(D, d_dtype, M, N, ldd, s8);
-    if (!A_elems || !A_scales || !B_elems || !B_scales || (fmtA == MXP_FMT_MXFP8P && !A_idx) || (fmtB == MXP_FMT_MXFP8P && !B_idx))
-      return MXP_ERR_NULL;
+    const bool ix_a = fmtA != MXP_FMT_MXFP4 && !plain_wide_format(fmtA), ix_b = fmtB != MXP_FMT_MXFP4 && !plain_wide_format(fmtB);
+    if (!A_elems || !A_scales || !B_elems || !B_scales || (ix_a && !A_idx) || (ix_b && !B_idx)) return MXP_ERR_NULL;
     if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || (A_idx && !aligned16(A_idx)) ||
         (B_idx && !aligned16(B_idx)))
       return MXP_ERR_ALIGN;
     return deconv_gemm_fp8_launch(M, N, K, A_elems, A_scales, A_idx, fmtA, B_elems, B_scales, B_idx, fmtB, D, d_dtype, ldd, s8);
   }
-  if (six || eight) {
+  if (six) {
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;
-    // both operands six-bit, or both plain MXFP8, or a six-bit operand with MXFP4 / MXFP4+ (plain MXFP6: one segment, the
+    // both operands six-bit, or a six-bit operand with MXFP4 / MXFP4+ (plain MXFP6: one segment, the
     // same E2M3 / E2M1 images as ever; MXFP6+: its two K segments, primary and BM residual, against the four-bit operand's
     // E2M3 image laid out twice)
     const bool four_a = fmtA == MXP_FMT_MXFP4 || fmtA == MXP_FMT_MXFP4P, four_b = fmtB == MXP_FMT_MXFP4 || fmtB == MXP_FMT_MXFP4P;
     const bool mixed64 = (is_fp6(fmtA) && four_b) || (four_a && is_fp6(fmtB));
-    if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !(fmtA == MXP_FMT_MXFP8 && fmtB == MXP_FMT_MXFP8) && !mixed64) return MXP_ERR_UNSUPPORTED;
+    if (!(is_fp6(fmtA) && is_fp6(fmtB)) && !mixed64) return MXP_ERR_UNSUPPORTED;
   } else if ((fmtA != MXP_FMT_MXFP4 && fmtA != MXP_FMT_MXFP4P && fmtA != MXP_FMT_MXFP4PP) ||
              (fmtB != MXP_FMT_MXFP4 && fmtB != MXP_FMT_MXFP4P && fmtB != MXP_FMT_MXFP4PP)) {
     return MXP_ERR_FORMAT;

@@ -575,12 +575,31 @@ int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, 
 }  // namespace
 
 namespace mxp {
-// Both operands quantized, eight-bit (MXFP8 / MXFP8+ in any combination): the product of the de-converted operands.
+// Both operands quantized, at least one of them eight-bit (MXFP8 / MXFP8+ with each other or with any narrower format):
+// the product of the de-converted operands.
 int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
                            const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
                            hipStream_t s) {
   const QOperand qa = {ae, as, ai, plus_of(fmtA)}, qb = {be, bs, bi, plus_of(fmtB)};
-  return launch_deconv<kFp8, kFp8>(M, N, K, nullptr, 0, qa, qb, D, d_dtype, ldd, s);
+  const int ka = kind_of(fmtA), kb = kind_of(fmtB);
+#define MXP_DECONV(AKV, BKV) return launch_deconv<AKV, BKV>(M, N, K, nullptr, 0, qa, qb, D, d_dtype, ldd, s)
+  if (ka == kFp8) {
+    switch (kb) {
+      case 1: MXP_DECONV(kFp8, 1);
+      case 2: MXP_DECONV(kFp8, 2);
+      case 3: MXP_DECONV(kFp8, 3);
+      case kFp6: MXP_DECONV(kFp8, kFp6);
+      default: MXP_DECONV(kFp8, kFp8);
+    }
+  }
+  if (kb != kFp8) return MXP_ERR_UNSUPPORTED;
+  switch (ka) {
+    case 1: MXP_DECONV(1, kFp8);
+    case 2: MXP_DECONV(2, kFp8);
+    case 3: MXP_DECONV(3, kFp8);
+    default: MXP_DECONV(kFp6, kFp8);
+  }
+#undef MXP_DECONV
 }
 }  // namespace mxp
 

@@ -960,8 +960,6 @@ def test_gemm_mxfp8_shapes(M, N, K):
     # the FP8-MFMA route through E4M3 images stays available, with the bound of that instruction's dot product
     ia, ib = mxp.prepack_fp8(q_dev(qa)), mxp.prepack_fp8(q_dev(qb))
     check_gemm_mxfp8(mxp.gemm_prepacked(M, N, K, ia, ib, a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3), ref, S, "mxfp8 images %dx%dx%d" % (M, N, K))
-    with pytest.raises(mxp.MxpError):
-        mxp.gemm(q_dev(qa), mxp.MXFP8, q_dev(W.quantize(w, W.MXFP6)), mxp.MXFP6)       # widths are not mixed
 
 
 @pytest.mark.parametrize("fa,fb", [("mxfp8p", "mxfp8p"), ("mxfp8p", "mxfp8"), ("mxfp8", "mxfp8p")])
@@ -978,6 +976,30 @@ def test_gemm_mxfp8p_shapes(fa, fb, M, N, K):
     check_gemm(D, ref, S, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
     Db = mxp.gemm(q_dev(qa), WIDE[fa][0], q_dev(qb), WIDE[fb][0], out_dtype=torch.bfloat16)
     assert torch.equal(Db, D.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("M,N,K", [(33, 100, 96), (257, 300, 1024), (64, 1000, 2080)])
+def test_gemm_eight_bit_next_to_narrower_formats(M, N, K):
+    """MXFP8 / MXFP8+ on one side, any four- or six-bit format on the other (either way round): the exact route on
+    de-converted operands, so the main bound applies."""
+    W = oracle.wide
+    a = synth.activations(M, K, config_id=1, tensor_id=0)
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+
+    def quantized(x, name):
+        if name in WIDE:
+            q = W.quantize(x, WIDE[name][1])
+            return q, WIDE[name][0], W.dequantize(q, WIDE[name][1])
+        q = oracle.quantize(x, FMT[name][1])
+        return q, FMT[name][0], oracle.dequantize(q, FMT[name][1]).astype(np.float64)
+
+    narrow = ["mxfp4", "mxfp4p", "mxfp4pp", "mxfp6", "mxfp6p"]
+    pairs = [("mxfp8p", n) for n in narrow] + [(n, "mxfp8p") for n in narrow] + [("mxfp8", "mxfp4p"), ("mxfp6p", "mxfp8"), ("mxfp4pp", "mxfp8")]
+    for fa, fb in pairs:
+        qa, ca, da = quantized(a, fa)
+        qb, cb, db = quantized(w, fb)
+        D = mxp.gemm(q_dev(qa), ca, q_dev(qb), cb)
+        check_gemm(D, da @ db.T, np.abs(da) @ np.abs(db).T, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
 
 
 def test_gemm_mxfp8p_special_blocks():
