@@ -189,7 +189,7 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
  * FP8 numbers the MFMA takes; a NaN code S.1111.111 in the input makes the products it meets NaN).  The product of two
  * such images (mxp_gemm_prepacked) has the error bound stated at MXP_IMAGE_E4M3, (7 * 2^-13 + 2^-16) * sum|a b|; it is the
  * fast route (FP8 MFMA), not the one mxp_gemm takes.  mxp_gemm forms every product with an eight-bit operand -- MXFP8 and
- * MXFP8+ in any combination, and either of them next to any four- or six-bit format; the MXFP8+ BM, eight significant bits
+ * MXFP8+ in any combination, either of them next to any four- or six-bit format (and MXFP6 / MXFP6+ next to MXFP4++); the MXFP8+ BM, eight significant bits
  * up to 1.992 * 2^8 > 448, fits no FP8 code anyway -- on the bf16 MFMA from operands de-converted inside the kernel: every value is a bf16 number, so the products are exact and
  * the bound is that of the main path; no image, no workspace, about a quarter of the FP8 rate.  (Values below the bf16
  * normal range, scale bytes under 16, are rounded to bf16 first.) */
@@ -244,8 +244,8 @@ size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when
 /* for any pair of formats mxp_gemm takes: the four-bit ones in any combination, MXFP6 / MXFP6+ in any combination
  * (see mxp_prepack_fp6 for the cost), MXFP6 or MXFP6+ with MXFP4 or MXFP4+ on the other side (plain MXFP6: one E2M3
  * image each, at the rate of the MXFP4+ product; MXFP6+: its two K segments against the four-bit operand's image laid out
- * twice, twice the work); 0 for a pair it does not take (a six-bit format next to MXFP4++) and for pairs with an
- * eight-bit format, which need none */
+ * twice, twice the work); 0 for pairs with an eight-bit format and for a six-bit format next to MXFP4++, which are
+ * multiplied from operands de-converted inside the kernel and need none, and for unknown formats */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);   /* the same function under its short name */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,

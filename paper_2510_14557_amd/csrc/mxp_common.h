@@ -37,10 +37,11 @@ int prepack_seg_launch(const uint8_t* elems, const uint8_t* scales, const uint8_
                        uint32_t roles, void* image, hipStream_t stream);
 int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream);
 
-// both operands eight-bit (MXFP8 / MXFP8+): the bf16-MFMA product of the de-converted operands (mxp_w4a16.hip)
-int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
-                           const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
-                           hipStream_t s);
+// the bf16-MFMA product of two quantized operands de-converted inside the kernel (mxp_w4a16.hip): pairs with an eight-bit
+// format, and a six-bit format next to MXFP4++
+int deconv_gemm_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
+                       const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
+                       hipStream_t s);
 
 // Longest reduction the product entry points take: the tiled kernel addresses an 8-tile run of an operand image with a
 // 32-bit lane offset, and a six-bit + product lays up to four K segments side by side.

@@ -1921,9 +1921,10 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
   const bool pp = fmtA == MXP_FMT_MXFP4PP || fmtB == MXP_FMT_MXFP4PP;
   const bool six = is_fp6(fmtA) || is_fp6(fmtB), eight = fmtA == MXP_FMT_MXFP8 || fmtB == MXP_FMT_MXFP8;   // (eight: mixed with a narrower format)
   const bool eight_plus = fmtA == MXP_FMT_MXFP8P || fmtB == MXP_FMT_MXFP8P;
-  if (eight_plus || eight) {
+  if (eight_plus || eight || (six && pp)) {
     // an E4M7 BM fits no block-scaled MFMA element: the product of the de-converted operands on the bf16 MFMA (exact
-    // products: every value is a bf16 number), at least one operand eight-bit, the other of any format; no workspace.
+    // products: every value is a bf16 number), at least one operand eight-bit, the other of any format; no workspace.  A
+    // six-bit format next to MXFP4++ goes the same way (two scales per block on one side, a six-bit BM split on the other).
     // Plain MXFP8 x MXFP8 takes this route too: the FP8 MFMA aligns the 64 products of a k-tile to the largest and drops
     // what falls below its adder width, which the stated error bound of this entry point does not admit (that faster route
     // remains available through mxp_prepack_fp8 + mxp_gemm_prepacked, with its own bound).
@@ -1937,7 +1938,7 @@ extern "C" int mxp_gemm(int64_t M, int64_t N, int64_t K, const uint8_t* A_elems,
     if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || (A_idx && !aligned16(A_idx)) ||
         (B_idx && !aligned16(B_idx)))
       return MXP_ERR_ALIGN;
-    return deconv_gemm_fp8_launch(M, N, K, A_elems, A_scales, A_idx, fmtA, B_elems, B_scales, B_idx, fmtB, D, d_dtype, ldd, s8);
+    return deconv_gemm_launch(M, N, K, A_elems, A_scales, A_idx, fmtA, B_elems, B_scales, B_idx, fmtB, D, d_dtype, ldd, s8);
   }
   if (six) {
     if (fmtA < MXP_FMT_MXFP4 || fmtA > MXP_FMT_MXFP8P || fmtB < MXP_FMT_MXFP4 || fmtB > MXP_FMT_MXFP8P) return MXP_ERR_FORMAT;

@@ -575,9 +575,9 @@ int dispatch_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, 
 }  // namespace
 
 namespace mxp {
-// Both operands quantized, at least one of them eight-bit (MXFP8 / MXFP8+ with each other or with any narrower format):
-// the product of the de-converted operands.
-int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
+// Both operands quantized, at least one of them eight-bit (MXFP8 / MXFP8+ with each other or with any narrower format), or
+// a six-bit format next to MXFP4++: the product of the de-converted operands.
+int deconv_gemm_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, const uint8_t* as, const uint8_t* ai, int fmtA,
                            const uint8_t* be, const uint8_t* bs, const uint8_t* bi, int fmtB, void* D, int d_dtype, int64_t ldd,
                            hipStream_t s) {
   const QOperand qa = {ae, as, ai, plus_of(fmtA)}, qb = {be, bs, bi, plus_of(fmtB)};
@@ -592,6 +592,8 @@ int deconv_gemm_fp8_launch(int64_t M, int64_t N, int64_t K, const uint8_t* ae, c
       default: MXP_DECONV(kFp8, kFp8);
     }
   }
+  if (ka == kFp6 && kb == 3) MXP_DECONV(kFp6, 3);              // six-bit next to MXFP4++: no block-scaled image pairing for it
+  if (ka == 3 && kb == kFp6) MXP_DECONV(3, kFp6);
   if (kb != kFp8) return MXP_ERR_UNSUPPORTED;
   switch (ka) {
     case 1: MXP_DECONV(1, kFp8);

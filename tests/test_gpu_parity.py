@@ -904,8 +904,13 @@ def test_gemm_mxfp6_activations_with_four_bit_weights(M, N, K):
     w6p = W.dequantize(qw6p, W.MXFP6P)
     D = mxp.gemm(q_dev(qa4), mxp.MXFP4P, q_dev(qw6p), mxp.MXFP6P)
     check_gemm(D, a4 @ w6p.T, np.abs(a4) @ np.abs(w6p).T, "mxfp4+ x mxfp6+ %dx%dx%d" % (M, N, K))
-    with pytest.raises(mxp.MxpError):                                      # still refused: six-bit next to MXFP4++
-        mxp.gemm(q_dev(qa6p), mxp.MXFP6P, q_dev(oracle.quantize(w, oracle.MXFP4PP)), mxp.MXFP4PP)
+    # six-bit next to MXFP4++: the route on de-converted operands
+    qwpp = oracle.quantize(w, oracle.MXFP4PP)
+    wpp = oracle.dequantize(qwpp, oracle.MXFP4PP).astype(np.float64)
+    check_gemm(mxp.gemm(q_dev(qa6p), mxp.MXFP6P, q_dev(qwpp), mxp.MXFP4PP), a6p @ wpp.T, np.abs(a6p) @ np.abs(wpp).T, "mxfp6+ x mxfp4++")
+    qapp = oracle.quantize(a, oracle.MXFP4PP)
+    app = oracle.dequantize(qapp, oracle.MXFP4PP).astype(np.float64)
+    check_gemm(mxp.gemm(q_dev(qapp), mxp.MXFP4PP, q_dev(qw6), mxp.MXFP6), app @ w6.T, np.abs(app) @ np.abs(w6).T, "mxfp4++ x mxfp6")
 
 
 def test_gemm_mxfp6_special_blocks():
