@@ -677,19 +677,20 @@ __device__ __forceinline__ void run_tile(uint8_t* lds, const uint8_t* __restrict
       MXP_CP(7);
       MXP_CP(8);
     } else {
+      // (in the order the next k-tile's MFMAs want them: only three MFMAs separate the last read from the first use)
       MXP_MFMA(2);
-      MXP_READ(na[0] = read_b<C::AT>(st + a_tiles_off + 0 * C::AT, lane));
-      MXP_READ(na[1] = read_b<C::AT>(st + a_tiles_off + 1 * C::AT, lane));
-      MXP_GAP();
-      MXP_MFMA(3);
-      MXP_READ(na[2] = read_b<C::AT>(st + a_tiles_off + 2 * C::AT, lane));
-      MXP_READ(na[3] = read_b<C::AT>(st + a_tiles_off + 3 * C::AT, lane));
-      MXP_GAP();
-      MXP_MFMA(4);
       MXP_READ(nb[0] = read_b<C::BT>(st + b_tiles_off + 0 * C::BT, lane));
-      MXP_READ(nb[1] = read_b<C::BT>(st + b_tiles_off + 1 * C::BT, lane));
+      MXP_READ(na[0] = read_b<C::AT>(st + a_tiles_off + 0 * C::AT, lane));
       MXP_READ(nsa = *reinterpret_cast<const uint32_t*>(st + sa_off));
       MXP_READ(nsb = *reinterpret_cast<const uint32_t*>(st + sb_off) >> sb_shift);
+      MXP_GAP();
+      MXP_MFMA(3);
+      MXP_READ(na[1] = read_b<C::AT>(st + a_tiles_off + 1 * C::AT, lane));
+      MXP_READ(na[2] = read_b<C::AT>(st + a_tiles_off + 2 * C::AT, lane));
+      MXP_GAP();
+      MXP_MFMA(4);
+      MXP_READ(na[3] = read_b<C::AT>(st + a_tiles_off + 3 * C::AT, lane));
+      MXP_READ(nb[1] = read_b<C::BT>(st + b_tiles_off + 1 * C::BT, lane));
       MXP_GAP();
       MXP_MFMA(5);
       MXP_CP(0);
