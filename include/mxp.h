@@ -211,6 +211,14 @@ int mxp_prepack_fp6(const uint8_t* elems, const uint8_t* scales, const uint8_t* 
                     int n_seg, unsigned res_mask, void* image, size_t image_bytes, void* stream);
 int mxp_prepack_fp8(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, size_t image_bytes,
                     void* stream);
+/* Conversion of un-quantized rows (MXP_BF16 / MXP_F32, row stride ld_src elements) straight into the K-segment image of
+ * mxp_prepack_fp6 -- the activation side of a six-bit product, Sec. 4.2 data layout, Sec. 5 -- in one pass: the image is
+ * bit-identical to mxp_quantize followed by mxp_prepack_fp6 with the same fmt (MXFP6 / MXFP6+), n_seg and res_mask.
+ * elems / scales / bm_idx: all null, or the canonical arrays to write as well (bm_idx only for MXFP6+), with the sizes
+ * and alignment mxp_quantize asks for.  src and image 16-byte aligned, ld_src * element size a multiple of 16. */
+int mxp_quantize_image_fp6(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, int n_seg,
+                           unsigned res_mask, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image,
+                           size_t image_bytes, void* stream);
 
 /* Conversion (Sec. 4.1, 4.2) written directly as an image: same source arguments and the same encoding as
  * mxp_quantize, but the result goes to `image` (mxp_image_bytes(rows, K) bytes, bit-identical to mxp_prepack of the

@@ -531,31 +531,18 @@ dim3 grid_for(int64_t nq) {
 // The image written here has n_seg segments of K_p = K rounded up to 128 each; bit s of res_mask says that segment s
 // holds the residual.  A workgroup takes 32 rows x 8 K-blocks (4 k-tiles) like the four-bit prepack kernel, one thread
 // per block, and writes the 4 tiles of every segment in turn.
+// A block's 24 bytes d[0..5] (zeros for a flushed or padding block), its scale byte and its BM position (64: none) -> the
+// block's place in the four staging tiles, once per K segment: the primary (BM_H in the BM's place) or the residual (BM_L
+// there, zero elsewhere), and out to the image.  Called by all 256 threads of a workgroup that owns row tile rt, k-tiles
+// kt0 .. kt0 + 3 of every segment.
 template <bool PLUS>
-__global__ void __launch_bounds__(256) prepack_fp6_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
-                                                          const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
-                                                          int64_t kts, int n_seg, uint32_t res_mask,
-                                                          uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
-  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
-  __shared__ uint8_t tile_scales[4 * 64];
-  const uint32_t t = threadIdx.x;
-  const uint32_t r_in = t >> 3, kb_in = t & 7u;
-  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((kts + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
-  if (!pm.valid) return;
-  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
-  const int64_t k_tiles = kts * n_seg;                         // k-tiles of the whole image
+__device__ __forceinline__ void fp6_segments_out(const uint32_t (&d)[6], uint32_t sbyte, uint32_t bm, uint8_t* tiles,
+                                                 uint8_t* tile_scales, int64_t rt, int64_t kt0, int64_t kts, int n_seg,
+                                                 uint32_t res_mask, uint8_t* __restrict__ img_elems,
+                                                 uint8_t* __restrict__ img_scales) {
+  const uint32_t t = threadIdx.x, r_in = t >> 3, kb_in = t & 7u;
   const uint32_t slot = (kb_in & 1u) * 32u + r_in;
-  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
-  uint32_t d[6] = {0, 0, 0, 0, 0, 0};
-  uint32_t sbyte = 127u, bm = 64u;
-  if (row < rows && kb < nbk) {
-    const int64_t b = row * nbk + kb;
-    const u32x2* src = reinterpret_cast<const u32x2*>(elems + b * 24);
-    const u32x2 v0 = __builtin_nontemporal_load(src), v1 = __builtin_nontemporal_load(src + 1), v2 = __builtin_nontemporal_load(src + 2);
-    sbyte = scales[b];
-    if (sbyte != 0u) { d[0] = v0.x; d[1] = v0.y; d[2] = v1.x; d[3] = v1.y; d[4] = v2.x; d[5] = v2.y; }   // flushed: zeros
-    if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
-  }
+  const int64_t k_tiles = kts * n_seg;                         // k-tiles of the whole image
   // the BM's six bits: element i sits in 24-bit piece i / 4 (bytes 3 (i/4) .. +2) at bit 6 (i % 4)
   uint32_t pr[6] = {d[0], d[1], d[2], d[3], d[4], d[5]}, rs[6] = {0, 0, 0, 0, 0, 0};
   if (PLUS && bm < 32u) {
@@ -594,6 +581,145 @@ __global__ void __launch_bounds__(256) prepack_fp6_kernel(const uint8_t* __restr
       MXP_IMAGE_STORE(*reinterpret_cast<const u32x4*>(tiles + o), reinterpret_cast<u32x4*>(out + o));
     if ((int64_t)(t >> 6) < nt) img_scales[(((rt >> 2) * k_tiles + kt_img + (t >> 6)) * 64 + (t & 63u)) * 4 + (rt & 3)] = tile_scales[t];
   }
+}
+
+template <bool PLUS>
+__global__ void __launch_bounds__(256) prepack_fp6_kernel(const uint8_t* __restrict__ elems, const uint8_t* __restrict__ scales,
+                                                          const uint8_t* __restrict__ bm_idx, int64_t rows, int64_t nbk,
+                                                          int64_t kts, int n_seg, uint32_t res_mask,
+                                                          uint8_t* __restrict__ img_elems, uint8_t* __restrict__ img_scales) {
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((kts + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  uint32_t d[6] = {0, 0, 0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u;
+  if (row < rows && kb < nbk) {
+    const int64_t b = row * nbk + kb;
+    const u32x2* src = reinterpret_cast<const u32x2*>(elems + b * 24);
+    const u32x2 v0 = __builtin_nontemporal_load(src), v1 = __builtin_nontemporal_load(src + 1), v2 = __builtin_nontemporal_load(src + 2);
+    sbyte = scales[b];
+    if (sbyte != 0u) { d[0] = v0.x; d[1] = v0.y; d[2] = v1.x; d[3] = v1.y; d[4] = v2.x; d[5] = v2.y; }   // flushed: zeros
+    if (PLUS && sbyte != 0u && sbyte != 255u) bm = bm_idx[b] & 31u;
+  }
+  fp6_segments_out<PLUS>(d, sbyte, bm, tiles, tile_scales, rt, kt0, kts, n_seg, res_mask, img_elems, img_scales);
+}
+
+// Conversion straight into such an image (optionally also the canonical arrays): what quantize_fp6_kernel and
+// prepack_fp6_kernel do one after the other, without the canonical bytes making a round trip through memory.  One thread
+// per block: it loads the block's 32 values (the eight threads of a row read 512 or 1024 contiguous bytes), finds the BM
+// (lowest position on ties) and the scale (Eq. 1, flush and NaN rules as in quantize_fp6_kernel), converts the whole block
+// with one hardware conversion, writes the MXFP6+ BM's five-bit mantissa over its slot, and hands the 24 bytes to
+// fp6_segments_out.
+template <bool BF16, bool PLUS>
+__global__ void __launch_bounds__(256) quantize_image_fp6_kernel(const void* __restrict__ src, int64_t rows, int64_t nbk, int64_t ld,
+                                                                 int64_t kts, int n_seg, uint32_t res_mask,
+                                                                 uint8_t* __restrict__ elems, uint8_t* __restrict__ scales,
+                                                                 uint8_t* __restrict__ bm_idx, uint8_t* __restrict__ img_elems,
+                                                                 uint8_t* __restrict__ img_scales) {
+  using F = Elem<6>;
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[4 * kTileBytes];
+  __shared__ uint8_t tile_scales[4 * 64];
+  const uint32_t t = threadIdx.x;
+  const uint32_t r_in = t >> 3, kb_in = t & 7u;
+  const PatchMap pm = patch_of_workgroup(blockIdx.x, (uint32_t)((kts + 3) / 4), (uint32_t)(((rows + kRowPad - 1) / kRowPad) * 2));
+  if (!pm.valid) return;
+  const int64_t kt0 = pm.kg * 4, rt = pm.rt;
+  const int64_t row = rt * kTileRows + r_in, kb = kt0 * 2 + kb_in;
+  uint32_t d[6] = {0, 0, 0, 0, 0, 0};
+  uint32_t sbyte = 127u, bm = 64u;                             // a padding block: zero elements, unit scale
+  if (row < rows && kb < nbk) {
+    const int64_t off = row * ld + kb * 32;
+    constexpr int NW = BF16 ? 16 : 32;
+    uint32_t w[NW];
+    if (BF16) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(src) + off);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const u32x4 v = __builtin_nontemporal_load(p + j);
+        w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+      }
+    } else {
+      const u32x4* p = reinterpret_cast<const u32x4*>(static_cast<const float*>(src) + off);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const u32x4 v = __builtin_nontemporal_load(p + j);
+        w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+      }
+    }
+    // block maximum over the magnitudes (fp32 bit patterns), then the lowest position that holds it and its sign
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const uint32_t a = BF16 ? ((i & 1) ? (w[i >> 1] & 0x7FFF0000u) : ((w[i >> 1] << 16) & 0x7FFF0000u)) : (w[i] & 0x7FFFFFFFu);
+      mx = umax(mx, a);
+    }
+    uint32_t pos = 32u, bm_sign = 0;
+#pragma unroll
+    for (int i = 31; i >= 0; --i) {
+      const uint32_t a = BF16 ? ((i & 1) ? (w[i >> 1] & 0x7FFF0000u) : ((w[i >> 1] << 16) & 0x7FFF0000u)) : (w[i] & 0x7FFFFFFFu);
+      const uint32_t sg = BF16 ? ((i & 1) ? (w[i >> 1] >> 31) : ((w[i >> 1] >> 15) & 1u)) : (w[i] >> 31);
+      const bool hit = a == mx;
+      pos = hit ? (uint32_t)i : pos;                           // ends at the lowest hit
+      bm_sign = hit ? sg : bm_sign;
+    }
+    const uint32_t E = mx >> 23;
+    const bool flush = E <= (uint32_t)F::EMAX, nonfinite = E == 255u;
+    const int sb = (int)E - F::EMAX;
+    const float X = __uint_as_float((uint32_t)(sb > 0 ? sb : 1) << 23);
+    v6u r;
+    if (BF16) {
+      union { uint32_t u[16]; v32bf v; } c;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) c.u[i] = w[i];
+      r = __builtin_amdgcn_cvt_scalef32_pk32_fp6_bf16(c.v, X);
+    } else {
+      v16f lo16, hi16;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {                           // the two sources are interleaved: code 2i from the first, 2i + 1 from the second
+        lo16[i] = __uint_as_float(w[2 * i]);
+        hi16[i] = __uint_as_float(w[2 * i + 1]);
+      }
+      r = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(lo16, hi16, X);
+    }
+    uint32_t c6[6] = {r[0], r[1], r[2], r[3], r[4], r[5]};
+    if (PLUS) {
+      // BM code sign | mmmmm at bit 6 pos of the block's 192-bit string (may straddle two dwords)
+      const uint32_t code = (bm_sign << 5) | bm_code<6>(mx);
+      const uint32_t bit = 6u * pos, wd = bit >> 5, sh = bit & 31u;
+      const uint64_t m = (uint64_t)0x3Fu << sh, cc = (uint64_t)code << sh;
+#pragma unroll
+      for (int j = 0; j < 6; ++j) {
+        if (wd == (uint32_t)j) c6[j] = (c6[j] & ~(uint32_t)m) | (uint32_t)cc;
+        if (wd + 1u == (uint32_t)j) c6[j] = (c6[j] & ~(uint32_t)(m >> 32)) | (uint32_t)(cc >> 32);
+      }
+    }
+    uint32_t idx = pos;
+    sbyte = (uint32_t)sb;
+    if (flush || nonfinite) {
+#pragma unroll
+      for (int j = 0; j < 6; ++j) c6[j] = 0;
+      idx = 0;
+      sbyte = nonfinite ? 255u : 0u;
+    }
+    if (elems) {
+      const int64_t b = row * nbk + kb;
+      u32x2* e = reinterpret_cast<u32x2*>(elems + b * 24);
+      e[0] = u32x2{c6[0], c6[1]};
+      e[1] = u32x2{c6[2], c6[3]};
+      e[2] = u32x2{c6[4], c6[5]};
+      scales[b] = (uint8_t)sbyte;
+      if (PLUS) bm_idx[b] = (uint8_t)idx;
+    }
+#pragma unroll
+    for (int j = 0; j < 6; ++j) d[j] = c6[j];
+    if (PLUS && sbyte != 0u && sbyte != 255u) bm = idx;
+  }
+  fp6_segments_out<PLUS>(d, sbyte, bm, tiles, tile_scales, rt, kt0, kts, n_seg, res_mask, img_elems, img_scales);
 }
 
 // Plain MXFP8 operand -> E4M3 image: the elements are the FP8 codes the MFMA takes and the scale byte is the block's
@@ -691,6 +817,23 @@ int prepack_fp6_launch(const uint8_t* elems, const uint8_t* scales, const uint8_
   return launch_status();
 }
 
+int quantize_image_fp6_launch(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld, int fmt, int n_seg, uint32_t res_mask,
+                              uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image, hipStream_t stream) {
+  const ImageGeom seg = image_geom(rows, K), g = image_geom(rows, seg.K_p * n_seg);
+  uint8_t* ie = static_cast<uint8_t*>(image);
+  uint8_t* is = ie + g.elem_bytes;
+  const int64_t n_wg = patch_grid((seg.k_tiles + 3) / 4, seg.row_tiles / 4);
+  if (n_wg > 2147483647LL) return MXP_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)n_wg);
+  const bool bf = src_dtype == MXP_BF16, plus = fmt == MXP_FMT_MXFP6P;
+#define MXP_QI6(B, P) hipLaunchKernelGGL((quantize_image_fp6_kernel<B, P>), grid, dim3(256), 0, stream, src, rows, K / kBlock, ld, seg.k_tiles, \
+                                         n_seg, plus ? res_mask : 0u, elems, scales, bm_idx, ie, is)
+  if (bf) { if (plus) MXP_QI6(true, true); else MXP_QI6(true, false); }
+  else    { if (plus) MXP_QI6(false, true); else MXP_QI6(false, false); }
+#undef MXP_QI6
+  return launch_status();
+}
+
 int prepack_fp8_launch(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image, hipStream_t stream) {
   const ImageGeom g = image_geom(rows, K, kTileBytesE4M3);
   uint8_t* ie = static_cast<uint8_t*>(image);
@@ -719,6 +862,27 @@ extern "C" int mxp_prepack_fp6(const uint8_t* elems, const uint8_t* scales, cons
   if (!aligned16(elems) || !aligned16(scales) || !aligned16(image) || (bm_idx && !aligned16(bm_idx))) return MXP_ERR_ALIGN;
   if (image_bytes < mxp_image_bytes_fp6(rows, K, n_seg)) return MXP_ERR_WORKSPACE;
   return prepack_fp6_launch(elems, scales, bm_idx, fmt, rows, K, n_seg, res_mask, image, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int mxp_quantize_image_fp6(const void* src, int src_dtype, int64_t rows, int64_t K, int64_t ld_src, int fmt, int n_seg,
+                                      unsigned res_mask, uint8_t* elems, uint8_t* scales, uint8_t* bm_idx, void* image,
+                                      size_t image_bytes, void* stream) {
+  using namespace mxp;
+  if (fmt != MXP_FMT_MXFP6 && fmt != MXP_FMT_MXFP6P) return MXP_ERR_FORMAT;
+  if (src_dtype != MXP_F32 && src_dtype != MXP_BF16) return MXP_ERR_DTYPE;
+  if (rows < 0 || K < 0 || K % kBlock != 0 || n_seg < 1 || n_seg > 4 || (res_mask >> n_seg) != 0u) return MXP_ERR_SHAPE;
+  if (fmt == MXP_FMT_MXFP6 && res_mask != 0u) return MXP_ERR_SHAPE;     // a plain operand has no residual
+  if (rows == 0 || K == 0) return MXP_OK;
+  if (!src || !image) return MXP_ERR_NULL;
+  const bool canon = elems || scales || bm_idx;
+  if (canon && (!elems || !scales || (fmt == MXP_FMT_MXFP6P && !bm_idx))) return MXP_ERR_NULL;
+  if (ld_src < K) return MXP_ERR_SHAPE;
+  const int64_t esz = src_dtype == MXP_BF16 ? 2 : 4;
+  if (!aligned16(src) || (ld_src * esz) % 16 != 0 || !aligned16(image)) return MXP_ERR_ALIGN;
+  if (canon && (!aligned16(elems) || !aligned16(scales) || (bm_idx && !aligned16(bm_idx)))) return MXP_ERR_ALIGN;
+  if (image_bytes < mxp_image_bytes_fp6(rows, K, n_seg)) return MXP_ERR_WORKSPACE;
+  return quantize_image_fp6_launch(src, src_dtype, rows, K, ld_src, fmt, n_seg, res_mask, elems, scales, bm_idx, image,
+                                   static_cast<hipStream_t>(stream));
 }
 
 extern "C" int mxp_prepack_fp8(const uint8_t* elems, const uint8_t* scales, int64_t rows, int64_t K, void* image,

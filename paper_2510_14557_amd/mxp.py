@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxp.so")
 
 EXPORTS = ("mxp_quantize", "mxp_quantize_t", "mxp_quantize_gather", "mxp_dequantize", "mxp_image_bytes", "mxp_prepack", "mxp_quantize_image",
-           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_prepack_seg", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
+           "mxp_image_bytes_e2m1", "mxp_prepack_e2m1", "mxp_image_bytes_e2m1r", "mxp_prepack_e2m1r", "mxp_prepack_e2m1x", "mxp_image_bytes_e4m3", "mxp_prepack_e4m3", "mxp_gemm_workspace_bytes", "mxp_gemm_workspace_bytes_e4m3", "mxp_gemm_workspace_bytes_fmt", "mxp_image_bytes_fp6", "mxp_prepack_fp6", "mxp_quantize_image_fp6", "mxp_prepack_seg", "mxp_prepack_fp8", "mxp_gemm", "mxp_gemm_prepacked", "mxp_gemm_bf16a_workspace_bytes", "mxp_gemm_decode", "mxp_gemm_decode_bf16a",
            "mxp_gemm_bf16a", "mxp_gemm_w4a16", "mxp_convert_operands", "mxp_gemm_workspace_size", "mxp_gemm_static", "mxp_gemm_static_capacity", "mxp_status_string", "mxp_version")
 
 _lib = None
@@ -76,6 +76,8 @@ def lib():
     L.mxp_image_bytes_fp6.restype = sz
     L.mxp_prepack_fp6.argtypes = [vp, vp, vp, i32, i64, i64, i32, C.c_uint, vp, sz, vp]
     L.mxp_prepack_fp6.restype = i32
+    L.mxp_quantize_image_fp6.argtypes = [vp, i32, i64, i64, i64, i32, i32, C.c_uint, vp, vp, vp, vp, sz, vp]
+    L.mxp_quantize_image_fp6.restype = i32
     L.mxp_prepack_seg.argtypes = [vp, vp, vp, i32, i64, i64, i32, C.c_uint, vp, sz, vp]
     L.mxp_prepack_seg.restype = i32
     L.mxp_prepack_fp8.argtypes = [vp, vp, i64, i64, vp, sz, vp]
@@ -280,6 +282,25 @@ def prepack_fp6(q, fmt: int = MXFP6P, n_seg: int = 1, res_mask: int = 0, out: to
     _check(lib().mxp_prepack_fp6(_p(elems), _p(scales), _p(idx), fmt, rows, K, n_seg, res_mask, _p(out), out.numel(), _stream()),
            "mxp_prepack_fp6")
     return out
+
+
+def quantize_image_fp6(x: torch.Tensor, fmt: int = MXFP6P, n_seg: int = 1, res_mask: int = 0, canonical: bool = False,
+                       out: torch.Tensor | None = None):
+    """bf16 / fp32 rows -> the K-segment E2M3 image of prepack_fp6 in one pass; with canonical=True also the canonical
+    (elems, scales, idx) arrays.  Returns image, or (image, q)."""
+    _dev2d(x)
+    rows, K = x.shape
+    if out is None:
+        out = torch.empty(image_bytes_fp6(rows, K, n_seg), dtype=torch.uint8, device=x.device)
+    q = None
+    if canonical:
+        q = (torch.empty((rows, K // 32 * 24), dtype=torch.uint8, device=x.device), torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device),
+             torch.zeros((rows, K // 32), dtype=torch.uint8, device=x.device))
+    e, s_, i = q if q is not None else (None, None, None)
+    ld = x.stride(0) if rows > 1 else max(K, 1)
+    _check(lib().mxp_quantize_image_fp6(_p(x), _dt(x), rows, K, ld, fmt, n_seg, res_mask, _p(e), _p(s_), _p(i if fmt == MXFP6P else None),
+                                        _p(out), out.numel(), _stream()), "mxp_quantize_image_fp6")
+    return (out, q) if canonical else out
 
 
 def prepack_seg(q, fmt: int, n_seg: int, roles: int, out: torch.Tensor | None = None):

@@ -137,6 +137,16 @@ def test_argument_errors_are_reported_not_launched():
     assert L.mxp_prepack_fp6(p, p, None, mxp.MXFP6P, 64, 64, 2, 0b10, p, 1 << 24, None) == -1
     assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP4P, 64, 64, 1, 0, p, 1 << 24, None) == -5
     assert L.mxp_prepack_fp6(p, p, p, mxp.MXFP6P, 64, 64, 2, 0b10, p, mxp.image_bytes_fp6(64, 64, 1), None) == -6
+    # one-pass conversion into the same images
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 64, mxp.MXFP6P, 5, 0, None, None, None, p, 1 << 24, None) == -2
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 64, mxp.MXFP6, 2, 0b10, None, None, None, p, 1 << 24, None) == -2
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 32, mxp.MXFP6P, 1, 0, None, None, None, p, 1 << 24, None) == -2
+    assert L.mxp_quantize_image_fp6(p, 7, 64, 64, 64, mxp.MXFP6P, 1, 0, None, None, None, p, 1 << 24, None) == -4
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 64, mxp.MXFP4P, 1, 0, None, None, None, p, 1 << 24, None) == -5
+    assert L.mxp_quantize_image_fp6(None, mxp.BF16, 64, 64, 64, mxp.MXFP6P, 1, 0, None, None, None, p, 1 << 24, None) == -1
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 64, mxp.MXFP6P, 1, 0, p, p, None, p, 1 << 24, None) == -1
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 64, 64, 64, mxp.MXFP6P, 2, 0b10, None, None, None, p, mxp.image_bytes_fp6(64, 64, 1), None) == -6
+    assert L.mxp_quantize_image_fp6(p, mxp.BF16, 0, 64, 64, mxp.MXFP6P, 1, 0, None, None, None, None, 0, None) == 0
     assert mxp.image_bytes_fp6(64, 64, 2) == mxp.image_bytes(64, 256) and mxp.image_bytes_fp6(64, 64, 0) == 0
     assert L.mxp_prepack_fp8(p, p, 64, 64, p, 16, None) == -6
     assert L.mxp_prepack_fp8(p, None, 64, 64, p, 1 << 24, None) == -1

@@ -913,6 +913,46 @@ def test_gemm_mxfp6_activations_with_four_bit_weights(M, N, K):
     check_gemm(mxp.gemm(q_dev(qapp), mxp.MXFP4PP, q_dev(qw6), mxp.MXFP6), app @ w6.T, np.abs(app) @ np.abs(w6).T, "mxfp4++ x mxfp6")
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("fmt", ["mxfp6", "mxfp6p"])
+def test_quantize_image_fp6_one_pass(fmt, bf16):
+    """Rows straight into the K-segment E2M3 image: the same bytes as conversion followed by mxp_prepack_fp6, for every
+    segment layout the products use, with and without the canonical arrays; special blocks included; and the product of
+    such an image is the oracle's."""
+    W = oracle.wide
+    code, ofmt = WIDE[fmt]
+    layouts = [(1, 0)] if fmt == "mxfp6" else [(1, 0), (2, 0x2), (2, 0x0), (4, 0xA), (4, 0xC)]
+    for x in wide_cases(bf16) + [synth.activations(300, 1024 + 32, config_id=1, tensor_id=3, dtype="bf16" if bf16 else "f32")]:
+        xd = to_dev(x)
+        q_ref = mxp.quantize(xd, code)
+        qo = W.quantize(x, ofmt)
+        n_arr = 3 if fmt == "mxfp6p" else 2
+        assert all((g == o).all() for g, o in zip(q_host(q_ref)[:n_arr], qo[:n_arr]))
+        for n_seg, mask in layouts:
+            want = mxp.prepack_fp6(q_ref, code, n_seg, mask)
+            got = mxp.quantize_image_fp6(xd, code, n_seg, mask)
+            assert torch.equal(got, want), (fmt, bf16, n_seg, mask, tuple(x.shape))
+            got2, q2 = mxp.quantize_image_fp6(xd, code, n_seg, mask, canonical=True)
+            assert torch.equal(got2, want)
+            assert torch.equal(q2[0], q_ref[0]) and torch.equal(q2[1], q_ref[1])
+            if fmt == "mxfp6p":
+                assert torch.equal(q2[2], q_ref[2])
+    # a strided source, and the product from one-pass images
+    M, N, K = 130, 200, 416
+    a = synth.activations(M, K, config_id=1, tensor_id=0, dtype="bf16" if bf16 else "f32")
+    w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
+    big = torch.zeros((M, K + 64), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    big[:, :K] = to_dev(a)
+    n_seg, mask = (1, 0) if fmt == "mxfp6" else (2, 0x2)
+    ia = mxp.quantize_image_fp6(big[:, :K], code, n_seg, mask)
+    assert torch.equal(ia, mxp.prepack_fp6(mxp.quantize(to_dev(a), code), code, n_seg, mask))
+    qw = W.quantize(w, W.MXFP6)
+    iw = mxp.prepack_fp6(q_dev(qw), mxp.MXFP6, n_seg, 0)
+    D = mxp.gemm_prepacked(M, N, mxp.image_bytes_fp6(1, K, 1) and ((K + 127) // 128 * 128) * n_seg, ia, iw)
+    ref, S = W.gemm(W.quantize(a, ofmt), ofmt, qw, W.MXFP6)
+    check_gemm(D, ref, S, "one-pass %s image x mxfp6" % fmt)
+
+
 def test_gemm_mxfp6_special_blocks():
     """Flushed, NaN and extreme-scale blocks; every BM mantissa."""
     W = oracle.wide
