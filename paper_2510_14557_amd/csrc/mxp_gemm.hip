@@ -1415,6 +1415,8 @@ int launch_skinny16(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, 
 // partial blocks are added through LDS in a fixed order.  The partial blocks lie in LDS as rows of the output (padded
 // by 16 bytes against bank conflicts), so the summing pass reads and stores 16-byte pieces of full 128- or 256-byte rows.
 // Two chunks of two k-tiles per wavefront in flight (147 KB per compute unit) are enough: with three the launch got slower.
+// A 128 x 128 block (for shapes that would need a second round of 128 x 64 blocks) fills all 256 AGPRs of a wavefront
+// and keeps two single k-tiles in flight.
 // Workgroups are dealt to the XCDs like the persistent kernel's tiles, in bands of 8 block columns: 32 consecutive positions
 // = 4 x 8 output blocks per XCD, i.e. 4 row panels and 8 (half as large) column panels, which its L2 then fetches once.
 template <int TMR_, int CT_, int BT_, int AT_>
@@ -1444,10 +1446,11 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
                                                          const uint8_t* __restrict__ b_el, const uint8_t* __restrict__ b_sc,
                                                          int k_tiles, int64_t M, int64_t N, void* __restrict__ Dv, int64_t ldd,
                                                          int n_rg, int n_cg) {
-  static_assert((TMR == 2 || TMR == 4) && (CT == 2 || CT == 4), "blocks of 64 or 128 rows by 64 or 128 columns");
+  static_assert((TMR == 2 || TMR == 4) && (CT == 2 || (CT == 4 && TMR == 4)), "blocks of 64 x 64, 128 x 64 or 128 x 128");
   using C = BlockCfg<TMR, CT, BT, AT>;
   typedef float f32x4 __attribute__((ext_vector_type(4)));
-  constexpr int WAVES = 4, CHUNK = 2, NBUF = 2;
+  constexpr bool BIG = TMR * CT == 16;                                      // 128 x 128: the accumulators fill the AGPRs
+  constexpr int WAVES = 4, CHUNK = BIG ? 1 : 2, NBUF = 2;                   // (a third k-tile in flight: 3 - 5 % slower)
   constexpr int ROWS = 32 * TMR, COLS = 32 * CT, STRIDE = COLS + 4;        // floats per row of a partial block
   extern __shared__ __attribute__((aligned(16))) uint8_t block_lds[];
   float* part = reinterpret_cast<float*>(block_lds);                        // [WAVES][ROWS][STRIDE]
@@ -1510,17 +1513,48 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
       }
     }
   }
+  // A 128 x 128 block has four partial blocks of 64 KiB, more than LDS holds: wavefronts 2 and 3 first hand theirs to
+  // wavefronts 0 and 1 in the accumulators' own layout (lane-contiguous 16-byte pieces, no transposition), which add them
+  // to their own; the two sums then go through the row layout like the four partials of the smaller blocks.
+  constexpr int PARTS = BIG ? 2 : WAVES;                                    // partial blocks in the row layout
+  if constexpr (BIG) {
+    f32x4* stage = reinterpret_cast<f32x4*>(block_lds) + (size_t)(wave & 1) * (TMR * CT * 4 * 64) + lane;
+    if (wave >= 2) {
+#pragma unroll
+      for (int i = 0; i < TMR; ++i)
+#pragma unroll
+        for (int jj = 0; jj < CT; ++jj)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            stage[((i * CT + jj) * 4 + g) * 64] = (f32x4){acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]};
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+      for (int i = 0; i < TMR; ++i)
+#pragma unroll
+        for (int jj = 0; jj < CT; ++jj)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 o = stage[((i * CT + jj) * 4 + g) * 64];
+            acc[i][jj][4 * g] += o[0]; acc[i][jj][4 * g + 1] += o[1]; acc[i][jj][4 * g + 2] += o[2]; acc[i][jj][4 * g + 3] += o[3];
+          }
+    }
+    __syncthreads();                                                        // the staging area is read: it becomes the row layout
+  }
   // partial blocks to LDS as output rows: accumulator quad g of lane l is row l % 32, columns 8 g + 4 (l / 32) .. + 3 of its tile
-  float* mine = part + (size_t)wave * ROWS * STRIDE;
+  if (wave < PARTS) {
+    float* mine = part + (size_t)wave * ROWS * STRIDE;
 #pragma unroll
-  for (int i = 0; i < TMR; ++i)
+    for (int i = 0; i < TMR; ++i)
 #pragma unroll
-    for (int jj = 0; jj < CT; ++jj)
+      for (int jj = 0; jj < CT; ++jj)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 q4 = {acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]};
-        *reinterpret_cast<f32x4*>(mine + (32 * i + (lane & 31)) * STRIDE + 32 * jj + 8 * g + 4 * (lane >> 5)) = q4;
-      }
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 q4 = {acc[i][jj][4 * g], acc[i][jj][4 * g + 1], acc[i][jj][4 * g + 2], acc[i][jj][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(mine + (32 * i + (lane & 31)) * STRIDE + 32 * jj + 8 * g + 4 * (lane >> 5)) = q4;
+        }
+  }
   __syncthreads();
   const bool vec_ok = (ldd % 4 == 0) && ((reinterpret_cast<uintptr_t>(Dv) & 15u) == 0);
   constexpr int QUADS = COLS / 4;                                           // 16-byte pieces per row
@@ -1528,7 +1562,7 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
     const int r = e / QUADS, q = e % QUADS;
     f32x4 v = *reinterpret_cast<const f32x4*>(part + r * STRIDE + 4 * q);
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) v += *reinterpret_cast<const f32x4*>(part + ((size_t)w * ROWS + r) * STRIDE + 4 * q);
+    for (int w = 1; w < PARTS; ++w) v += *reinterpret_cast<const f32x4*>(part + ((size_t)w * ROWS + r) * STRIDE + 4 * q);
     const int64_t row = rt0 * 32 + r, col = ct0 * 32 + 4 * q;
     if (row >= M || col >= N) continue;
     if (vec_ok && col + 3 < N) {
@@ -1549,14 +1583,14 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
   }
 }
 
-// Which shapes take the block kernel: more rows than the few-row kernels take, and at most two rounds of 128 x 64 blocks on
-// the chip's compute units.  Measured against the persistent kernel at K = 4096: one round (2048 x 1024, 512 x 4096,
-// 1024 x 2048) 11 - 13 us against 24; two rounds (1024 x 4096, 2048 x 2048, 512 x 8192) 22 - 23 us against 24.5; four rounds
-// (2048 x 4096) 44 us against 29 -- there every compute unit already has a half tile of its own.
-// Blocks are 64 x 64 when 128 x 64 ones would leave more than half of the chip idle.
+// Which shapes take the block kernel: more rows than the few-row kernels take, and one round of workgroups on the chip's
+// compute units with blocks of 128 x 128 at most.  Measured against the persistent kernel at K = 4096: 128 x 64 blocks in
+// one round (2048 x 1024, 512 x 4096, 1024 x 2048) 11 - 13 us against 24; shapes of twice that size (1024 x 4096,
+// 2048 x 2048, 512 x 8192) 22 - 23 us in two rounds of 128 x 64 blocks against 24.5, and in one round of 128 x 128 blocks
+// as launched now; four rounds of 128 x 64 (2048 x 4096) 44 us against 29 -- there every compute unit already has a half
+// tile of its own.  Blocks are 64 x 64 when 128 x 64 ones would leave more than half of the chip idle.
 inline bool block_kernel_applies(int64_t M, int64_t N) {
-  const int64_t blocks = ((M + 127) / 128) * ((N + 63) / 64);
-  return M > 128 && blocks <= 2 * kNumCU;
+  return M > 128 && ((M + 127) / 128) * ((N + 127) / 128) <= kNumCU;
 }
 
 template <int BT, int AT>
@@ -1567,24 +1601,31 @@ int launch_block(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int
   const int kt = (int)ga.k_tiles;
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
   const bool bf = d_dtype == MXP_BF16;
-  const int64_t n_cg = (N + 63) / 64;
-  const bool tall = ((M + 127) / 128) * n_cg >= kNumCU / 2;
-  const int64_t n_rg = tall ? (M + 127) / 128 : (M + 63) / 64;
-#define MXP_BLOCK(TMRV, BFV)                                                                                                      \
+  const int64_t rg128 = (M + 127) / 128, cg64 = (N + 63) / 64;
+  const bool big = rg128 * cg64 > kNumCU;                                    // 128 x 64 blocks would need a second round
+  const bool tall = rg128 * cg64 >= kNumCU / 2;
+  const int64_t n_cg = big ? (N + 127) / 128 : cg64;
+  const int64_t n_rg = (big || tall) ? rg128 : (M + 63) / 64;
+#define MXP_BLOCK(TMRV, CTV, BFV)                                                                                                 \
   do {                                                                                                                            \
-    constexpr int lds = 4 * 32 * TMRV * (64 + 4) * 4;                                                                             \
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_block_kernel<TMRV, 2, BFV, BT, AT>),        \
+    constexpr int rows_l = (CTV == 4 ? 2 : 4) * 32 * TMRV * (32 * CTV + 4) * 4, stage_l = CTV == 4 ? 2 * 16 * 4 * 64 * 16 : 0;    \
+    constexpr int lds = rows_l > stage_l ? rows_l : stage_l;                                                                      \
+    static_assert(lds <= 160 * 1024, "partial blocks must fit in LDS");                                                           \
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_block_kernel<TMRV, CTV, BFV, BT, AT>),      \
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);                       \
     (void)once;                                                                                                                   \
-    hipLaunchKernelGGL((gemm_block_kernel<TMRV, 2, BFV, BT, AT>), dim3((unsigned)(n_rg * n_cg)), dim3(256), lds, s, ae, as, be, bs, \
-                       kt, M, N, D, ldd, (int)n_rg, (int)n_cg);                                                                   \
+    hipLaunchKernelGGL((gemm_block_kernel<TMRV, CTV, BFV, BT, AT>), dim3((unsigned)(n_rg * n_cg)), dim3(256), lds, s, ae, as, be, \
+                       bs, kt, M, N, D, ldd, (int)n_rg, (int)n_cg);                                                               \
   } while (0)
-  if (tall) {
-    if (bf) MXP_BLOCK(4, true);
-    else MXP_BLOCK(4, false);
+  if (big) {
+    if (bf) MXP_BLOCK(4, 4, true);
+    else MXP_BLOCK(4, 4, false);
+  } else if (tall) {
+    if (bf) MXP_BLOCK(4, 2, true);
+    else MXP_BLOCK(4, 2, false);
   } else {
-    if (bf) MXP_BLOCK(2, true);
-    else MXP_BLOCK(2, false);
+    if (bf) MXP_BLOCK(2, 2, true);
+    else MXP_BLOCK(2, 2, false);
   }
 #undef MXP_BLOCK
   return launch_status();

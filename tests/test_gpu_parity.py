@@ -613,9 +613,9 @@ def test_gemm_random_shapes_sampled():
 
 
 def _routes_to_persistent_kernel(M, N):
-    """The launcher's rule, restated: more than 128 rows and more than 512 blocks of 128 x 64 (up to there the block kernel
+    """The launcher's rule, restated: more than 128 rows and more than 256 blocks of 128 x 128 (up to there the block kernel
     with K split inside the workgroup takes the shape)."""
-    return M > 128 and ((M + 127) // 128) * ((N + 63) // 64) > 512
+    return M > 128 and ((M + 127) // 128) * ((N + 127) // 128) > 256
 
 
 @pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
@@ -648,11 +648,12 @@ def test_gemm_persistent_kernel_ragged_shapes(M, N, K, pad, w_fmt):
 
 @pytest.mark.parametrize("w_fmt", ["mxfp4p", "mxfp4"])
 @pytest.mark.parametrize("M,N,K", [(2048, 1024, 4096), (129, 33, 7168), (130, 1000, 64), (512, 4096, 320), (700, 1500, 1024),
-                                   (1000, 1100, 192), (2049, 300, 2144), (1024, 2100, 320), (1025, 3000, 512)])
+                                   (1000, 1100, 192), (2049, 300, 2144), (1024, 2100, 320), (1025, 3000, 512), (2048, 2048, 448),
+                                   (600, 6000, 96), (1500, 2050, 256)])
 def test_gemm_block_kernel_shapes_sampled(M, N, K, w_fmt):
     """Shapes with too few 256-wide tiles for the persistent kernel: blocks of 128 x 64 or 64 x 64 with K split over the
-    workgroup's wavefronts (1 ... 112 k-tiles: fewer chunks than wavefronts, odd counts, one chunk each, many), in one
-    round of workgroups and in two."""
+    workgroup's wavefronts (1 ... 112 k-tiles: fewer chunks than wavefronts, odd counts, one chunk each, many); blocks
+    of 128 x 128 where 128 x 64 ones would need a second round of workgroups."""
     assert M > 128 and not _routes_to_persistent_kernel(M, N)
     a = synth.activations(M, K, config_id=3, tensor_id=62)
     w = synth.weights(N, K, config_id=3, tensor_id=63, t3_frac=0.001)
