@@ -1153,7 +1153,8 @@ def test_gemm_mxfp4pp_hand_case():
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 33, 64), (33, 100, 96), (100, 200, 416), (257, 300, 1024), (300, 520, 2048),
-                                   (64, 1000, 4160), (512, 1100, 640), (8, 12840, 256), (8, 25632, 512), (129, 70, 128)])
+                                   (64, 1000, 4160), (512, 1100, 640), (8, 12840, 256), (8, 25632, 512), (129, 70, 128),
+                                   (1024, 2100, 192)])                 # (the last: 128 x 128 blocks on FP8 images)
 def test_gemm_mxfp4pp_shapes(M, N, K):
     a = synth.activations(M, K, config_id=1, tensor_id=0)
     w = synth.weights(N, K, config_id=1, tensor_id=1, t3_frac=0.001)
