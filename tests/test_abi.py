@@ -153,15 +153,15 @@ def test_argument_errors_are_reported_not_launched():
     # products: MXFP6 / MXFP6+ pair with each other, MXFP8 with MXFP8, MXFP8+ with nothing
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP6P) == 2 * mxp.image_bytes_fp6(64, 64, 4)
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4) == 2 * mxp.image_bytes_fp6(64, 64, 2)
-    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4PP) == 0                   # route without images
-    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP4P) == 0                     # exact route as well
-    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == 0                      # exact route: no images
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP6P, mxp.MXFP4PP) == 64 * 64 * 2         # route without images: A as bf16 (optional)
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP4P) == 64 * 64 * 2           # exact route as well
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8, mxp.MXFP8) == 64 * 64 * 2            # exact route: no images, A as bf16
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4) == 2 * mxp.image_bytes_fp6(64, 64, 2)
     assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP4PP, mxp.MXFP4PP) == 2 * mxp.image_bytes_e4m3(64, 64)
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP6P, p, p, p, mxp.MXFP4PP, p, mxp.F32, 64, None, 0, None) == -1   # taken: arguments checked
     assert L.mxp_gemm(64, 64, 64, p, p, p, mxp.MXFP8P, p, p, None, mxp.MXFP6P, p, mxp.F32, 64, None, 0, None) == -1   # mixed widths: taken, arguments checked
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP8P, p, p, p, mxp.MXFP8, p, mxp.F32, 64, None, 0, None) == -1
-    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8P, mxp.MXFP8) == 0
+    assert mxp.gemm_workspace_bytes(64, 64, 64, mxp.MXFP8P, mxp.MXFP8) == 64 * 64 * 2
     assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, mxp.MXFP8P, p, mxp.F32, 64, None) == -1
     assert L.mxp_gemm_w4a16(8, 64, 64, p, mxp.BF16, 64, p, p, None, 7, p, mxp.F32, 64, None) == -5
     assert L.mxp_gemm(64, 64, 64, p, p, None, mxp.MXFP6P, p, p, None, mxp.MXFP6, p, mxp.F32, 64, p, 1 << 24, None) == -1

@@ -1046,6 +1046,13 @@ def test_gemm_eight_bit_next_to_narrower_formats(M, N, K):
         qb, cb, db = quantized(w, fb)
         D = mxp.gemm(q_dev(qa), ca, q_dev(qb), cb)
         check_gemm(D, da @ db.T, np.abs(da) @ np.abs(db).T, "%s x %s %dx%dx%d" % (fa, fb, M, N, K))
+        # without room for A as bf16 both operands are de-converted inside the tiled kernel: the same products, summed in
+        # that kernel's order (the few-row kernel of the other route splits K over wavefronts)
+        small = torch.empty(16, dtype=torch.uint8, device="cuda")
+        D2 = mxp.gemm(q_dev(qa), ca, q_dev(qb), cb, workspace=small)
+        check_gemm(D2, da @ db.T, np.abs(da) @ np.abs(db).T, "%s x %s %dx%dx%d, no workspace" % (fa, fb, M, N, K))
+        if M > 128:
+            assert torch.equal(D2, D)
 
 
 def test_gemm_mxfp8p_special_blocks():
