@@ -1653,7 +1653,7 @@ def test_four_bit_image_ignores_reserved_index_bits_of_mxfp4p():
     assert torch.equal(mxp.prepack(q_dev((qw[0], qw[1], junk)), mxp.MXFP4P), mxp.prepack(q_dev(qw), mxp.MXFP4P))
 
 
-@pytest.mark.parametrize("fa,fw", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4p")])
+@pytest.mark.parametrize("fa,fw", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4p"), ("mxfp4", "mxfp4")])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_convert_operands_one_launch_matches_the_two_kernels(fa, fw, bf16):
     """mxp_convert_operands (activations -> canonical + image, canonical weights -> image, one grid) writes the oracle's
@@ -1787,3 +1787,171 @@ def test_new_entry_points_on_empty_and_degenerate_inputs():
     out0 = torch.empty((0, N), device="cuda")
     mxp.gemm_static((z8(0, K // 2), z8(0, K // 32), z8(0, K // 32)), mxp.MXFP4P, qw, mxp.MXFP4P, out0)
     torch.cuda.synchronize()
+
+
+# ---- every launch class: the template instances that shape, image kind and output type select ------------------------
+# The few-row kernels are instantiated per (row tiles, column tiles per workgroup, wavefronts, image kinds, output type);
+# which one runs follows from M (<= 32, <= 64, <= 128), the number of 32-column tiles (>= 400, >= 800) and K (>= 4096:
+# sixteen wavefronts).  The shapes below reach each of those classes, ragged in every dimension.
+_IMAGE_PACK = {
+    mxp.IMAGE_E2M3: lambda q, f: mxp.prepack(q, f),
+    mxp.IMAGE_E2M1: lambda q, f: mxp.prepack_e2m1(q),
+    mxp.IMAGE_E4M3: lambda q, f: mxp.prepack_e4m3(q, f),
+    mxp.IMAGE_E2M1R: lambda q, f: mxp.prepack_e2m1r(q),
+    mxp.IMAGE_E2M1X: lambda q, f: mxp.prepack_e2m1x(q, f),
+}
+# (activation format, its image kind, weight format, its image kind, most rows the pairing takes)
+_IMAGE_PAIRS = [
+    ("mxfp4p", mxp.IMAGE_E2M3, "mxfp4p", mxp.IMAGE_E2M3, 128),
+    ("mxfp4p", mxp.IMAGE_E2M3, "mxfp4", mxp.IMAGE_E2M1, 128),
+    ("mxfp4", mxp.IMAGE_E2M1, "mxfp4", mxp.IMAGE_E2M1, 128),
+    ("mxfp4pp", mxp.IMAGE_E4M3, "mxfp4pp", mxp.IMAGE_E4M3, 128),
+    ("mxfp4pp", mxp.IMAGE_E4M3, "mxfp4", mxp.IMAGE_E2M1, 64),
+    ("mxfp4p", mxp.IMAGE_E2M3, "mxfp4p", mxp.IMAGE_E2M1R, 64),
+    ("mxfp4pp", mxp.IMAGE_E4M3, "mxfp4p", mxp.IMAGE_E2M1R, 64),
+    ("mxfp4p", mxp.IMAGE_E2M3, "mxfp4pp", mxp.IMAGE_E2M1X, 64),
+    ("mxfp4pp", mxp.IMAGE_E4M3, "mxfp4pp", mxp.IMAGE_E2M1X, 64),
+    ("mxfp4pp", mxp.IMAGE_E4M3, "mxfp4p", mxp.IMAGE_E2M1X, 64),
+]
+
+
+@pytest.mark.parametrize("M,N,K", [(20, 300, 160), (20, 300, 4000), (20, 12850, 160), (20, 12850, 4000), (20, 25590, 160),
+                                   (48, 300, 160), (48, 300, 4000), (48, 12850, 160), (100, 300, 160), (100, 300, 4000)])
+def test_gemm_few_row_kernels_every_launch_class(M, N, K):
+    a = synth.activations(M, K, config_id=2, tensor_id=80)
+    w = synth.weights(N, K, config_id=2, tensor_id=81, t3_frac=0.001)
+    qa = {f: oracle.quantize(a, FMT[f][1]) for f in FMT}
+    qw = {f: oracle.quantize(w, FMT[f][1]) for f in FMT}
+    for fa, ka, fw, kw, max_rows in _IMAGE_PAIRS:
+        if M > max_rows:
+            continue
+        what = "%s (kind %d) x %s (kind %d) %dx%dx%d" % (fa, ka, fw, kw, M, N, K)
+        ref, S = oracle.gemm(qa[fa], FMT[fa][1], qw[fw], FMT[fw][1])
+        img_a, img_w = _IMAGE_PACK[ka](q_dev(qa[fa]), FMT[fa][0]), _IMAGE_PACK[kw](q_dev(qw[fw]), FMT[fw][0])
+        D = torch.full((M, N + 3), float("nan"), device="cuda")
+        mxp.gemm_prepacked(M, N, K, img_a, img_w, a_kind=ka, b_kind=kw, out=D[:, :N])
+        assert torch.isnan(D[:, N:]).all(), what
+        (check_gemm_e4m3 if ka == mxp.IMAGE_E4M3 else check_gemm)(D[:, :N], ref, S, what)
+        Db = mxp.gemm_prepacked(M, N, K, img_a, img_w, a_kind=ka, b_kind=kw, out_dtype=torch.bfloat16)
+        assert torch.equal(Db, D[:, :N].to(torch.bfloat16)), what
+
+
+# The tiled kernels: blocks of 64 x 64, 128 x 64 and 128 x 128 with K split over the wavefronts (few blocks), the
+# two-stage kernel (fewer than four k-tiles) and the persistent one with one tile per workgroup at most (whole ring in
+# flight) or more -- each per image pairing and output type.
+@pytest.mark.parametrize("fa,fw", [("mxfp4p", "mxfp4p"), ("mxfp4p", "mxfp4"), ("mxfp4", "mxfp4"), ("mxfp4pp", "mxfp4pp")])
+@pytest.mark.parametrize("M,N,K,pad", [(300, 500, 256, 0), (1024, 1030, 160, 1), (1024, 2100, 320, 0), (300, 12000, 96, 3),
+                                       (1300, 3000, 256, 0), (2100, 8200, 192, 5)])
+def test_gemm_tiled_kernels_every_launch_class(M, N, K, pad, fa, fw):
+    a = synth.activations(M, K, config_id=2, tensor_id=82)
+    w = synth.weights(N, K, config_id=2, tensor_id=83, t3_frac=0.001)
+    qa, qw = oracle.quantize(a, FMT[fa][1]), oracle.quantize(w, FMT[fw][1])
+    ref, S = oracle.gemm(qa, FMT[fa][1], qw, FMT[fw][1])
+    what = "%s x %s %dx%dx%d" % (fa, fw, M, N, K)
+    D = torch.full((M, N + pad), float("nan"), device="cuda")
+    mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qw), FMT[fw][0], out=D[:, :N])
+    assert pad == 0 or torch.isnan(D[:, N:]).all(), what
+    (check_gemm_e4m3 if fa == "mxfp4pp" else check_gemm)(D[:, :N], ref, S, what)
+    Db = torch.full((M, N + pad), float("nan"), dtype=torch.bfloat16, device="cuda")
+    mxp.gemm(q_dev(qa), FMT[fa][0], q_dev(qw), FMT[fw][0], out=Db[:, :N])
+    assert pad == 0 or torch.isnan(Db[:, N:]).all(), what
+    assert torch.equal(Db[:, :N], D[:, :N].to(torch.bfloat16)), what
+
+
+def test_gemm_operands_deconverted_in_the_kernel_every_pairing():
+    """The product on de-converted operands (no room for A as bf16): every pairing of operand loaders -- an eight-bit
+    format with any other, a six-bit one with MXFP4++ -- in both output types, on a ragged shape above 128 rows."""
+    W = oracle.wide
+    M, N, K = 257, 300, 256
+    a = synth.activations(M, K, config_id=1, tensor_id=84)
+    w = synth.weights(N, K, config_id=1, tensor_id=85, t3_frac=0.001)
+
+    def quantized(x, name):
+        if name in WIDE:
+            q = W.quantize(x, WIDE[name][1])
+            return q, WIDE[name][0], W.dequantize(q, WIDE[name][1])
+        q = oracle.quantize(x, FMT[name][1])
+        return q, FMT[name][0], oracle.dequantize(q, FMT[name][1]).astype(np.float64)
+
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    for fa, fb in [("mxfp8p", "mxfp4"), ("mxfp8", "mxfp4p"), ("mxfp8p", "mxfp4pp"), ("mxfp8", "mxfp6p"), ("mxfp8p", "mxfp8"),
+                   ("mxfp8", "mxfp8"), ("mxfp4", "mxfp8p"), ("mxfp4p", "mxfp8"), ("mxfp4pp", "mxfp8p"), ("mxfp6", "mxfp8p"),
+                   ("mxfp6p", "mxfp4pp"), ("mxfp4pp", "mxfp6")]:
+        qa, ca, da = quantized(a, fa)
+        qb, cb, db = quantized(w, fb)
+        D = mxp.gemm(q_dev(qa), ca, q_dev(qb), cb, workspace=small)
+        check_gemm(D, da @ db.T, np.abs(da) @ np.abs(db).T, "%s x %s, operands de-converted in the kernel" % (fa, fb))
+        Db = mxp.gemm(q_dev(qa), ca, q_dev(qb), cb, workspace=small, out_dtype=torch.bfloat16)
+        assert torch.equal(Db, D.to(torch.bfloat16)), (fa, fb)
+        assert torch.equal(mxp.gemm(q_dev(qa), ca, q_dev(qb), cb), D), (fa, fb)      # A de-converted once: identical bits
+
+
+@pytest.mark.parametrize("w_fmt", ["mxfp4", "mxfp4p", "mxfp4pp", "mxfp6p"])
+def test_gemm_w4a16_many_tiles_of_256_rows(w_fmt):
+    """Un-quantized activations with 200 or more tiles of 256 x 256: the 256-row form of the tiled kernel, both output types."""
+    M, N, K = 4100, 3100, 64
+    a = synth.activations(M, K, config_id=1, tensor_id=86)
+    w = synth.weights(N, K, config_id=1, tensor_id=87, t3_frac=0.001)
+    if w_fmt in FMT:
+        qw, fc = oracle.quantize(w, FMT[w_fmt][1]), FMT[w_fmt][0]
+        w64 = oracle.dequantize(qw, FMT[w_fmt][1]).astype(np.float64)
+    else:
+        qw, fc = oracle.wide.quantize(w, WIDE[w_fmt][1]), WIDE[w_fmt][0]
+        w64 = oracle.wide.dequantize(qw, WIDE[w_fmt][1])
+    a64 = synth.bf16_bits_to_f32(a).astype(np.float64)
+    D = mxp.gemm_w4a16(to_dev(a), q_dev(qw), fc)
+    check_gemm(D, a64 @ w64.T, np.abs(a64) @ np.abs(w64).T, "bf16 x %s %dx%dx%d" % (w_fmt, M, N, K))
+    assert torch.equal(mxp.gemm_w4a16(to_dev(a), q_dev(qw), fc, out_dtype=torch.bfloat16), D.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_and_dequantize_with_row_strides(fmt, bf16):
+    """Source rows and destination rows further apart than K: the strided forms of the conversion kernels."""
+    rows, K = 45, 224
+    x = special_tensor(rows=rows, K=K, seed=17, bf16=bf16)
+    src = torch.zeros((rows, K + 40), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    src[:, :K] = to_dev(x)
+    want = oracle.quantize(x, FMT[fmt][1])
+    got = mxp.quantize(src[:, :K], FMT[fmt][0])
+    assert_q_equal(got, want, fmt, "strided source")
+    deq = oracle.dequantize(want, FMT[fmt][1])
+    out = torch.full((rows, K + 24), 9.0, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    mxp.dequantize(got, FMT[fmt][0], out=out[:, :K])
+    assert (out[:, K:] == 9.0).all()
+    ref = torch.from_numpy(deq).cuda().to(out.dtype)                       # (bf16: round-to-nearest-even of the exact value)
+    nan = torch.isnan(ref)
+    assert torch.equal(torch.isnan(out[:, :K]), nan)
+    assert torch.equal(out[:, :K][~nan], ref[~nan])
+
+
+@pytest.mark.parametrize("fmt", ["mxfp4", "mxfp4p", "mxfp4pp"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quantize_gather_every_row_length_class(fmt, bf16):
+    """Channel reordering (Sec. 9) on rows of 8192 and 16384 channels (4 and 8 groups per lane of the kernel that stages a
+    row in LDS) and on rows too long for that kernel (gathered straight from memory)."""
+    rng = np.random.default_rng(13)
+    for rows, n_src, K in ((9, 8192, 8192), (5, 16384, 16384), (3, 40000, 20000 - 32)):
+        x = synth.activations(rows, n_src, config_id=2, tensor_id=88, dtype="bf16" if bf16 else "f32")
+        perm = rng.permutation(n_src)[:K].astype(np.int32)
+        got = mxp.quantize_gather(to_dev(x), torch.from_numpy(perm).cuda(), FMT[fmt][0])
+        assert_q_equal(got, oracle.quantize(np.ascontiguousarray(x[:, perm]), FMT[fmt][1]), fmt, "gather %d of %d" % (K, n_src))
+
+
+def test_gemm_mxfp4pp_activations_on_narrower_weights_as_e4m3_images():
+    """Plain MXFP4 and MXFP4+ weights written as E4M3 images (Sec. 4.3: every element of either is an E4M3 number in
+    the image's units) under MXFP4++ activations; K = 0 with a bf16 result."""
+    M, N, K = 70, 200, 416
+    a = synth.activations(M, K, config_id=2, tensor_id=89)
+    w = synth.weights(N, K, config_id=2, tensor_id=90, t3_frac=0.001)
+    qa = oracle.quantize(a, oracle.MXFP4PP)
+    img_a = mxp.prepack_e4m3(q_dev(qa), mxp.MXFP4PP)
+    for fw in ("mxfp4", "mxfp4p"):
+        qw = oracle.quantize(w, FMT[fw][1])
+        ref, S = oracle.gemm(qa, oracle.MXFP4PP, qw, FMT[fw][1])
+        D = mxp.gemm_prepacked(M, N, K, img_a, mxp.prepack_e4m3(q_dev(qw), FMT[fw][0]), a_kind=mxp.IMAGE_E4M3, b_kind=mxp.IMAGE_E4M3)
+        check_gemm_e4m3(D, ref, S, "mxfp4++ x %s as E4M3 images" % fw)
+    z8 = lambda r, c: torch.empty((r, c), dtype=torch.uint8, device="cuda")
+    out = torch.full((5, 7), 3.0, dtype=torch.bfloat16, device="cuda")
+    mxp.gemm((z8(5, 0),) * 3, mxp.MXFP4P, (z8(7, 0),) * 3, mxp.MXFP4P, out=out)
+    assert not out.any()
