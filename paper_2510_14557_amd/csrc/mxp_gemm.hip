@@ -1059,8 +1059,10 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
   const uint8_t *ae = Ai, *as = Ai + ga.elem_bytes, *be = Bi, *bs = Bi + gb.elem_bytes;
   const bool bf = d_dtype == MXP_BF16, wide = kt >= 64;
   constexpr int64_t kEnough = 200;                          // workgroups
+  constexpr bool kFp8Image = BT == kTileBytesE4M3 || AT == kTileBytesE4M3;
   if (M > 64) {                                             // 65 .. 128 rows: four row tiles, 8 wavefronts (128 KiB of partial tiles)
-    launch_skinny_out<4, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    if constexpr (kFp8Image) return MXP_ERR_UNSUPPORTED;    // (callers send E4M3 images here with up to 64 rows only)
+    else launch_skinny_out<4, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else if (M <= 32) {
     if (ct / 4 >= kEnough) launch_skinny_out<1, 4, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
     else if (ct / 2 >= kEnough && wide) launch_skinny_out<1, 2, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
@@ -1069,8 +1071,9 @@ int launch_skinny(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, in
     else launch_skinny_out<1, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   } else {
     if (ct / 2 >= kEnough) launch_skinny_out<2, 2, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else if (wide && BT != kTileBytesE4M3 && AT != kTileBytesE4M3) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
-    else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);   // (E4M3 fragments: 16 wavefronts would spill)
+    else if (wide && !kFp8Image) {                          // (E4M3 fragments: 16 wavefronts would spill)
+      if constexpr (!kFp8Image) launch_skinny_out<2, 1, BT, AT, 16>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
+    } else launch_skinny_out<2, 1, BT, AT, 8>(bf, ct, s, ae, as, be, bs, kt, M, N, D, ldd);
   }
   return launch_status();
 }
@@ -1276,8 +1279,9 @@ int launch_skinny_res(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N
     else MXP_RES(1, 1, 8);
   } else {
     if (ct / 2 >= kEnough) MXP_RES(2, 2, 8);
-    else if (wide && AT != kTileBytesE4M3) MXP_RES(2, 1, 16);   // (E4M3 fragments: 16 wavefronts would spill)
-    else MXP_RES(2, 1, 8);
+    else if (wide && AT != kTileBytesE4M3) {                    // (E4M3 fragments: 16 wavefronts would spill)
+      if constexpr (AT != kTileBytesE4M3) MXP_RES(2, 1, 16);
+    } else MXP_RES(2, 1, 8);
   }
 #undef MXP_RES
   return launch_status();
