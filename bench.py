@@ -48,6 +48,17 @@ def stats(samples):
     return {"mean": float(s.mean()), "median": float(np.median(s)), "min": float(s.min()), "n": int(s.size)}
 
 
+def product_kernel_name(M, N):
+    """The kernel mxp_gemm_prepacked launches for two E2M3 images of this shape (the library's routing, restated for the label)."""
+    if M <= 16 and (N + 31) // 32 < 256:
+        return "gemm_skinny16_kernel"
+    if M <= 64 or (M <= 128 and (N + 255) // 256 < 64):
+        return "gemm_skinny_kernel"
+    if ((M + 127) // 128) * ((N + 127) // 128) <= 256:
+        return "gemm_block_kernel"
+    return "gemm_kernel_dma"
+
+
 def traffic_from_profiles(workload, out_dtype):
     """HBM-side bytes per GEMM launch, from the committed rocprofv3 --pmc summary (None if there is no matching line)."""
     path = os.path.join(ROOT, "profiles", "gemm_kernel_dma_%s.md" % workload)
@@ -286,7 +297,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_FP4_TFLOPS,
                      "traffic": traffic_from_profiles(args.workload, args.out_dtype),
-                     "kernel": "gemm_kernel_dma" if M > 64 else ("gemm_skinny16_kernel" if M <= 16 and N < 6400 else "gemm_skinny_res_kernel"), "kernel_ms": gemm_ms, "kernel_ms_median": gemm_st["median"],
+                     "kernel": product_kernel_name(M, N), "kernel_ms": gemm_ms, "kernel_ms_median": gemm_st["median"],
                      "kernel_ms_min": gemm_st["min"], "kernel_samples": gemm_st["n"],
                      "kernel_ms_back_to_back": gemm_b2b,
                      "frac_back_to_back": flops / (gemm_b2b["mean"] * 1e-3) / 1e12 / PEAK_FP4_TFLOPS,
