@@ -272,7 +272,9 @@ int mxp_gemm(int64_t M, int64_t N, int64_t K,
  * returns MXP_ERR_SCRATCH and enqueues nothing (the Llama-8B prefill-MLP product, 4096 x 14336 x 4096, needs 56.3 MiB).
  * All calls on one GPU share that array, which keeps the previous call's images: every byte a product reads is
  * rewritten by the image kernels of the same call first, and calls whose work overlaps on one GPU (different streams,
- * or different threads) race -- serialise them.  Arguments otherwise as mxp_gemm. */
+ * or different threads) race -- serialise them.  The first call on a device asks the runtime for the array's address on
+ * that device, and the first launch of each kernel sets its launch attributes (as in every entry point): make one call
+ * with the shapes in question before a stream capture begins.  Arguments otherwise as mxp_gemm. */
 size_t mxp_gemm_static_capacity(void);
 int mxp_gemm_static(int64_t M, int64_t N, int64_t K,
                     const uint8_t* A_elems, const uint8_t* A_scales, const uint8_t* A_idx, int fmtA,
