@@ -1955,3 +1955,71 @@ def test_gemm_mxfp4pp_activations_on_narrower_weights_as_e4m3_images():
     out = torch.full((5, 7), 3.0, dtype=torch.bfloat16, device="cuda")
     mxp.gemm((z8(5, 0),) * 3, mxp.MXFP4P, (z8(7, 0),) * 3, mxp.MXFP4P, out=out)
     assert not out.any()
+
+
+def test_products_replayed_from_a_hip_graph():
+    """The entry points enqueue kernels only (no allocation, no synchronisation, no memset), so a captured stream replays
+    them: the whole hot path of a step, the no-allocation product and the decode call are captured once and replayed
+    on inputs rewritten in place, with eager work and synchronisations between the replays; every replay must equal the
+    eager call on the same inputs bit for bit and meet the oracle's bound."""
+    dev = torch.device("cuda")
+    M, N, K = 1300, 3000, 256                       # persistent kernel; the decode call below takes the 16-column tiles
+    Md, Nd, Kd = 8, 4096, 512
+    inputs = []
+    for r in range(3):
+        inputs.append((synth.activations(M, K, config_id=4, tensor_id=10 * r, dtype="bf16"),
+                       synth.weights(N, K, config_id=4, tensor_id=10 * r + 1, t3_frac=0.001),
+                       synth.activations(Md, Kd, config_id=2, tensor_id=10 * r + 2, dtype="bf16"),
+                       synth.weights(Nd, Kd, config_id=2, tensor_id=10 * r + 3)))
+    a, w, ad, wd = (to_dev(x) for x in inputs[0])
+    qw = tuple(torch.empty(s, dtype=torch.uint8, device=dev) for s in ((N, K // 2), (N, K // 32), (N, K // 32)))
+    qa = tuple(torch.empty(s, dtype=torch.uint8, device=dev) for s in ((M, K // 2), (M, K // 32), (M, K // 32)))
+    qwd = tuple(torch.empty(s, dtype=torch.uint8, device=dev) for s in ((Nd, Kd // 2), (Nd, Kd // 32), (Nd, Kd // 32)))
+    ia = torch.empty(mxp.image_bytes(M, K), dtype=torch.uint8, device=dev)
+    iw = torch.empty(mxp.image_bytes(N, K), dtype=torch.uint8, device=dev)
+    iwd = torch.empty(mxp.image_bytes_e2m1r(Nd, Kd), dtype=torch.uint8, device=dev)
+    D = torch.empty((M, N), device=dev)
+    Ds = torch.empty((M, N), device=dev)
+    Dd = torch.empty((Md, Nd), device=dev)
+    back = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(max(mxp.gemm_bf16a_workspace_bytes(Md, Kd), 16), dtype=torch.uint8, device=dev)
+
+    def step():
+        mxp.quantize_into(w, mxp.MXFP4P, *qw)
+        mxp.convert_operands(a, mxp.MXFP4P, qa, ia, qw, mxp.MXFP4P, iw)
+        mxp.gemm_prepacked(M, N, K, ia, iw, out=D)
+        mxp.dequantize(qa, mxp.MXFP4P, out=back)
+        mxp.gemm_static(qa, mxp.MXFP4P, qw, mxp.MXFP4P, Ds)
+        mxp.quantize_into(wd, mxp.MXFP4P, *qwd)
+        mxp.prepack_e2m1r(qwd, out=iwd)
+        mxp.gemm_bf16a(ad, mxp.MXFP4P, iwd, Nd, out=Dd, workspace=ws, b_kind=mxp.IMAGE_E2M1R)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                                      # first calls: kernel attributes, the library array's address
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for r in (1, 2, 0, 1):
+        for dst, src in zip((a, w, ad, wd), inputs[r]):
+            dst.copy_(to_dev(src))                  # eager work between the replays
+        for t in (D, Ds, Dd):
+            t.fill_(float("nan"))
+        back.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (D, Ds, Dd, back)] + [t.clone() for t in qa]
+        step()                                      # the same calls, eagerly, on the same inputs
+        torch.cuda.synchronize()
+        for g, e in zip(got, [D, Ds, Dd, back] + list(qa)):
+            assert torch.equal(g, e), "replay %d differs from the eager call" % r
+        qa_o, qw_o = oracle.quantize(inputs[r][0], oracle.MXFP4P), oracle.quantize(inputs[r][1], oracle.MXFP4P)
+        assert_q_equal(tuple(got[4:7]), qa_o, "mxfp4p", "replayed conversion")
+        ref, S = oracle.gemm(qa_o, oracle.MXFP4P, qw_o, oracle.MXFP4P)
+        check_gemm(got[0], ref, S, "replayed product")
+        check_gemm(got[1], ref, S, "replayed no-allocation product")
+        refd, Sd = oracle.gemm(oracle.quantize(inputs[r][2], oracle.MXFP4P), oracle.MXFP4P, oracle.quantize(inputs[r][3], oracle.MXFP4P), oracle.MXFP4P)
+        check_gemm(got[2], refd, Sd, "replayed decode call")
