@@ -2023,3 +2023,46 @@ def test_products_replayed_from_a_hip_graph():
         check_gemm(got[1], ref, S, "replayed no-allocation product")
         refd, Sd = oracle.gemm(oracle.quantize(inputs[r][2], oracle.MXFP4P), oracle.MXFP4P, oracle.quantize(inputs[r][3], oracle.MXFP4P), oracle.MXFP4P)
         check_gemm(got[2], refd, Sd, "replayed decode call")
+
+
+def test_calls_from_two_threads_on_two_streams():
+    """The library keeps no state between calls (apart from the no-allocation product's array): two host threads, each with
+    a stream of its own, run conversions and products of different shapes at the same time and get what one thread gets."""
+    import threading
+
+    jobs = [(300, 520, 1024, 0), (1300, 3000, 256, 1)]
+    data = [(synth.activations(M, K, config_id=6, tensor_id=2 * t, dtype="bf16"), synth.weights(N, K, config_id=6, tensor_id=2 * t + 1))
+            for M, N, K, t in jobs]
+    want = []
+    for (a, w) in data:
+        qa, qw = mxp.quantize(to_dev(a), mxp.MXFP4P), mxp.quantize(to_dev(w), mxp.MXFP4P)
+        want.append((qa, mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P)))
+    torch.cuda.synchronize()
+    got, errors = [None, None], []
+
+    def worker(i):
+        try:
+            s = torch.cuda.Stream()
+            a, w = to_dev(data[i][0]), to_dev(data[i][1])
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s):
+                for _ in range(20):
+                    qa, qw = mxp.quantize(a, mxp.MXFP4P), mxp.quantize(w, mxp.MXFP4P)
+                    d = mxp.gemm(qa, mxp.MXFP4P, qw, mxp.MXFP4P)
+                s.synchronize()
+            got[i] = (qa, d)
+        except Exception as e:                      # surfaced in the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(2):
+        assert all(torch.equal(x, y) for x, y in zip(got[i][0], want[i][0]))
+        assert torch.equal(got[i][1], want[i][1])
+        qa_o, qw_o = oracle.quantize(data[i][0], oracle.MXFP4P), oracle.quantize(data[i][1], oracle.MXFP4P)
+        ref, S = oracle.gemm(qa_o, oracle.MXFP4P, qw_o, oracle.MXFP4P)
+        check_gemm(got[i][1], ref, S, "thread %d" % i)
