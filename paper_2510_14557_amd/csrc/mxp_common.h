@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "mxp.h"
 
 namespace mxp {
@@ -52,6 +53,20 @@ int check_gemm(int64_t M, int64_t N, int64_t K, const void* D, int d_dtype, int6
 int zero_output(void* D, int d_dtype, int64_t M, int64_t N, int64_t ldd, hipStream_t s);
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// A kernel that takes more than 64 KiB of dynamic LDS has to be told so through its function attribute, on every device it
+// is launched on: done at the first launch per device (one bit per device in a word of the kernel's own; threads that get
+// there together set the same attribute twice).
+template <auto Kernel>
+inline void allow_dynamic_lds(int bytes) {
+  static std::atomic<uint64_t> done{0};
+  int dev = 0;
+  const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64;
+  const uint64_t bit = known ? (uint64_t)1 << dev : 0;
+  if (known && (done.load(std::memory_order_relaxed) & bit)) return;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (known) done.fetch_or(bit, std::memory_order_relaxed);
+}
 
 inline int launch_status() {
   return hipGetLastError() == hipSuccess ? MXP_OK : MXP_ERR_HIP;

@@ -10,6 +10,7 @@
 // of operand row l % 32, K-block l / 32, plus that block's scale byte; accumulator register r of lane l is element
 // [8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of (first operand) x (second operand)^T.
 #include "mxp_common.h"
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 
@@ -27,17 +28,19 @@ int quantize_image_launch(const void* src, int src_dtype, int64_t rows, int64_t 
 namespace mxp {
 Chip chip() {
   constexpr int kMaxDev = 64;
-  static Chip cache[kMaxDev] = {};      // cus == 0: not asked yet (a benign race: every thread writes the same values)
+  // one word per device, (cus << 32) | xcds, 0 = not asked yet: threads that ask at the same time store the same word
+  static std::atomic<uint64_t> cache[kMaxDev] = {};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return Chip{0, 0};
-  if (cache[dev].cus == 0) {
+  uint64_t word = cache[dev].load(std::memory_order_relaxed);
+  if (word == 0) {
     int cus = 0, xcds = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = -1;
-    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) xcds = -1;
-    cache[dev].xcds = xcds;
-    cache[dev].cus = cus == 0 ? -1 : cus;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 0x7FFFFFFF;
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess || xcds < 0) xcds = 0;
+    word = ((uint64_t)(uint32_t)cus << 32) | (uint32_t)xcds;
+    cache[dev].store(word, std::memory_order_relaxed);
   }
-  return cache[dev];
+  return Chip{(int)(word >> 32), (int)(word & 0xFFFFFFFFu)};
 }
 
 // Argument checks common to every product entry point (declared in mxp_common.h).
@@ -826,15 +829,11 @@ int launch_cfg(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   dim3 grid((unsigned)gn, (unsigned)gm);
   const size_t lds = 2 * (size_t)C::STAGE_BYTES;
   if (d_dtype == MXP_BF16) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<C, true>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
-    (void)once_b;
+    allow_dynamic_lds<&gemm_kernel<C, true>>((int)lds);
     hipLaunchKernelGGL((gemm_kernel<C, true>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi, Bi + gb.elem_bytes,
                        ga.k_tiles, M, N, D, ldd);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<C, false>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);
-    (void)once_f;
+    allow_dynamic_lds<&gemm_kernel<C, false>>((int)lds);
     hipLaunchKernelGGL((gemm_kernel<C, false>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi, Bi + gb.elem_bytes,
                        ga.k_tiles, M, N, D, ldd);
   }
@@ -879,9 +878,7 @@ int launch_dma(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int64
   const bool deep = (Fq + P - 1) / P + (Hq + P - 1) / P <= 1;
 #define MXP_GO(DEEPV, BFV)                                                                                                         \
   do {                                                                                                                             \
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel_dma<C, S, DEEPV, BFV>),               \
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds), true);                    \
-    (void)once;                                                                                                                    \
+    allow_dynamic_lds<&gemm_kernel_dma<C, S, DEEPV, BFV>>((int)lds);                                                       \
     hipLaunchKernelGGL((gemm_kernel_dma<C, S, DEEPV, BFV>), grid, dim3(C::THREADS), lds, s, Ai, Ai + ga.elem_bytes, Bi,           \
                        Bi + gb.elem_bytes, ga.k_tiles, M, N, D, ldd, (int)gm, gnf, nhc);                                           \
   } while (0)
@@ -1032,9 +1029,7 @@ void launch_skinny_cfg(int64_t n_ct, hipStream_t s, const uint8_t* ae, const uin
                        int64_t M, int64_t N, void* D, int64_t ldd) {
   constexpr int lds = WAVES * TMR * CT * 16 * 64 * 4;
   static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
-  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_kernel<TMR, CT, OUT_BF16, BT, AT, WAVES>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-  (void)once;
+  allow_dynamic_lds<&gemm_skinny_kernel<TMR, CT, OUT_BF16, BT, AT, WAVES>>((int)lds);
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   hipLaunchKernelGGL((gemm_skinny_kernel<TMR, CT, OUT_BF16, BT, AT, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, kt, M, N, D, ldd);
 }
@@ -1247,14 +1242,10 @@ void launch_skinny_res_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* 
   static_assert(lds <= 128 * 1024, "partial tiles must fit in LDS");
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   if (bf) {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT, XM>),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-    (void)once;
+    allow_dynamic_lds<&gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT, XM>>((int)lds);
     hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, true, WAVES, AT, XM>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   } else {
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT, XM>),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-    (void)once;
+    allow_dynamic_lds<&gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT, XM>>((int)lds);
     hipLaunchKernelGGL((gemm_skinny_res_kernel<TMR, CT, false, WAVES, AT, XM>), grid, dim3(64 * WAVES), lds, s, ae, as, be, bs, br, kt, M, N, D, ldd);
   }
 }
@@ -1615,9 +1606,7 @@ int launch_block(const uint8_t* Ai, const uint8_t* Bi, int64_t M, int64_t N, int
     constexpr int rows_l = (CTV == 4 ? 2 : 4) * 32 * TMRV * (32 * CTV + 4) * 4, stage_l = CTV == 4 ? 2 * 16 * 4 * 64 * 16 : 0;    \
     constexpr int lds = rows_l > stage_l ? rows_l : stage_l;                                                                      \
     static_assert(lds <= 160 * 1024, "partial blocks must fit in LDS");                                                           \
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_block_kernel<TMRV, CTV, BFV, BT, AT>),      \
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);                       \
-    (void)once;                                                                                                                   \
+    allow_dynamic_lds<&gemm_block_kernel<TMRV, CTV, BFV, BT, AT>>((int)lds);                                                    \
     hipLaunchKernelGGL((gemm_block_kernel<TMRV, CTV, BFV, BT, AT>), dim3((unsigned)(n_rg * n_cg)), dim3(256), lds, s, ae, as, be, \
                        bs, kt, M, N, D, ldd, (int)n_rg, (int)n_cg);                                                               \
   } while (0)
@@ -1796,15 +1785,11 @@ void launch_canon_cfg(bool bf, int64_t n_ct, hipStream_t s, const uint8_t* ae, c
   const dim3 grid((unsigned)((n_ct + CT - 1) / CT));
   const u32x4* we4 = reinterpret_cast<const u32x4*>(we);
   if (bf) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_canon_kernel<TMR, CT, true, PLUS, kTileBytes, WAVES>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-    (void)once_b;
+    allow_dynamic_lds<&gemm_skinny_canon_kernel<TMR, CT, true, PLUS, kTileBytes, WAVES>>((int)lds);
     hipLaunchKernelGGL((gemm_skinny_canon_kernel<TMR, CT, true, PLUS, kTileBytes, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, we4, ws, wi,
                        nbk, kt, M, N, D, ldd);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_skinny_canon_kernel<TMR, CT, false, PLUS, kTileBytes, WAVES>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-    (void)once_f;
+    allow_dynamic_lds<&gemm_skinny_canon_kernel<TMR, CT, false, PLUS, kTileBytes, WAVES>>((int)lds);
     hipLaunchKernelGGL((gemm_skinny_canon_kernel<TMR, CT, false, PLUS, kTileBytes, WAVES>), grid, dim3(64 * WAVES), lds, s, ae, as, we4, ws, wi,
                        nbk, kt, M, N, D, ldd);
   }

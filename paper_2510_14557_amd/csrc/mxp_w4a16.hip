@@ -214,9 +214,7 @@ void launch_skinny(dim3 grid, hipStream_t s, const void* A, int64_t lda, const u
   constexpr int lds_part = WAVES * TMR * 16 * 64 * 4, lds_patch = WAVES * kW4PatchBytes;
   constexpr int lds = lds_part > lds_patch ? lds_part : lds_patch;
   static_assert(lds <= 160 * 1024, "LDS");
-  static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&w4a16_skinny_kernel<MODE, TMR, OUT_BF16, WAVES>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
-  (void)once;
+  allow_dynamic_lds<&w4a16_skinny_kernel<MODE, TMR, OUT_BF16, WAVES>>((int)lds);
   hipLaunchKernelGGL((w4a16_skinny_kernel<MODE, TMR, OUT_BF16, WAVES>), grid, dim3(64 * WAVES), lds, s,
                      static_cast<const uint16_t*>(A), lda, reinterpret_cast<const u32x4*>(we), ws, wi, nbk, M, N, D, ldd);
 }
@@ -523,15 +521,11 @@ int launch_deconv(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, c
   const int64_t nbk = K / kBlock;
   static_assert(kTiledLds <= 160 * 1024, "LDS");
   if (d_dtype == MXP_BF16) {
-    static bool once_b = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, true, WI>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
-    (void)once_b;
+    allow_dynamic_lds<&deconv_tiled_kernel<AK, WK, true, WI>>(kTiledLds);
     hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, true, WI>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
                        lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   } else {
-    static bool once_f = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(&deconv_tiled_kernel<AK, WK, false, WI>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds), true);
-    (void)once_f;
+    allow_dynamic_lds<&deconv_tiled_kernel<AK, WK, false, WI>>(kTiledLds);
     hipLaunchKernelGGL((deconv_tiled_kernel<AK, WK, false, WI>), grid, dim3(kTiledThreads), kTiledLds, s, static_cast<const uint16_t*>(A),
                        lda, qa, qw, nbk, M, N, D, ldd, (int)tn);
   }
