@@ -1582,8 +1582,9 @@ __global__ void __launch_bounds__(256) gemm_block_kernel(const uint8_t* __restri
 // compute units with blocks of 128 x 128 at most.  Measured against the persistent kernel at K = 4096: 128 x 64 blocks in
 // one round (2048 x 1024, 512 x 4096, 1024 x 2048) 11 - 13 us against 24; shapes of twice that size (1024 x 4096,
 // 2048 x 2048, 512 x 8192) 22 - 23 us in two rounds of 128 x 64 blocks against 24.5, and in one round of 128 x 128 blocks
-// as launched now; four rounds of 128 x 64 (2048 x 4096) 44 us against 29 -- there every compute unit already has a half
-// tile of its own.  Blocks are 64 x 64 when 128 x 64 ones would leave more than half of the chip idle.
+// as launched now; four rounds of 128 x 64 (2048 x 4096) 44 us and two rounds of 128 x 128 blocks 40 - 41 us against 29 --
+// there every compute unit already has a half tile of its own.  Blocks are 64 x 64 when 128 x 64 ones would leave more
+// than half of the chip idle.
 inline bool block_kernel_applies(int64_t M, int64_t N) {
   return M > 128 && ((M + 127) / 128) * ((N + 127) / 128) <= kNumCU;
 }
