@@ -47,8 +47,10 @@ extern "C" {
                            * mxp_gemm_prepacked); the other image and product entry points return MXP_ERR_UNSUPPORTED for
                            * it (its BM and NBMs have different scales, which one E2M3 operand cannot carry) */
 /* Six- and eight-bit MX and MX+ formats (Sec. 4.2, data layout): conversion and de-conversion (mxp_quantize,
- * mxp_dequantize) and, for MXFP6, MXFP6+ and plain MXFP8, the product (mxp_gemm; mxp_prepack_fp6 / mxp_prepack_fp8 +
- * mxp_gemm_prepacked); every other entry point returns MXP_ERR_FORMAT or MXP_ERR_UNSUPPORTED for them.
+ * mxp_dequantize), the product of any two of the seven formats (mxp_gemm, mxp_gemm_static), weights of any format under
+ * un-quantized activations (mxp_gemm_w4a16) and, for MXFP6, MXFP6+ and plain MXFP8, images of their own (mxp_prepack_fp6,
+ * mxp_quantize_image_fp6, mxp_prepack_fp8 + mxp_gemm_prepacked); every other entry point returns MXP_ERR_FORMAT or
+ * MXP_ERR_UNSUPPORTED for them.
  *   MXFP6 / MXFP6+: elements E2M3 (sign | ee | mmm, bias 1, subnormals m/8, largest 7.5), e_max = 2; the BM of MXFP6+ is
  *                   sign | mmmmm = 2^2 * 1.mmmmm (an E2M5 number).  elems [rows][K*3/4]: a block is 24 bytes, element i in
  *                   bits [6i, 6i+6) of the block read as a little-endian bit string.
@@ -189,9 +191,10 @@ int mxp_prepack_e4m3(const uint8_t* elems, const uint8_t* scales, const uint8_t*
  * FP8 numbers the MFMA takes; a NaN code S.1111.111 in the input makes the products it meets NaN).  The product of two
  * such images (mxp_gemm_prepacked) has the error bound stated at MXP_IMAGE_E4M3, (7 * 2^-13 + 2^-16) * sum|a b|; it is the
  * fast route (FP8 MFMA), not the one mxp_gemm takes.  mxp_gemm forms every product with an eight-bit operand -- MXFP8 and
- * MXFP8+ in any combination, either of them next to any four- or six-bit format (and MXFP6 / MXFP6+ next to MXFP4++); the MXFP8+ BM, eight significant bits
- * up to 1.992 * 2^8 > 448, fits no FP8 code anyway -- on the bf16 MFMA from operands de-converted inside the kernel: every value is a bf16 number, so the products are exact and
- * the bound is that of the main path; no image, no workspace, about a quarter of the FP8 rate.  (Values below the bf16
+ * MXFP8+ in any combination, either of them next to any four- or six-bit format (and MXFP6 / MXFP6+ next to MXFP4++); the
+ * MXFP8+ BM, eight significant bits up to 1.992 * 2^8 > 448, fits no FP8 code anyway -- on the bf16 MFMA from de-converted
+ * operands: every value is a bf16 number, so the products are exact and the bound is that of the main path; no image,
+ * an optional workspace (see mxp_gemm_workspace_bytes_fmt), about a quarter of the FP8 rate.  (Values below the bf16
  * normal range, scale bytes under 16, are rounded to bf16 first.) */
 size_t mxp_image_bytes_fp6(int64_t rows, int64_t K, int n_seg);
 
@@ -255,8 +258,8 @@ size_t mxp_gemm_workspace_bytes_e4m3(int64_t M, int64_t N, int64_t K);   /* when
  * twice, twice the work).  Pairs with an eight-bit format, and a six-bit format next to MXFP4++, are multiplied from
  * de-converted operands: the size returned for them, 2 M K bytes rounded up to 256, is room for A as bf16 and is
  * optional -- with it A is de-converted once ahead of the product (1.3 - 1.65x faster; the same products, and above 128
- * rows the same summation order, i.e. identical bits), with a smaller or
- * no workspace both operands are de-converted inside the kernel.  0 for unknown formats. */
+ * rows the same summation order, i.e. identical bits), with a smaller or no workspace both operands are de-converted
+ * inside the kernel.  0 for unknown formats. */
 size_t mxp_gemm_workspace_bytes_fmt(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 size_t mxp_gemm_workspace_size(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);   /* the same function under its short name */
 int mxp_gemm(int64_t M, int64_t N, int64_t K,
