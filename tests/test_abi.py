@@ -203,3 +203,20 @@ def test_gemm_static_refuses_oversized_products_before_touching_the_gpu():
     assert L.mxp_gemm_static(8, 8, 32, p, p, p, 11, p, p, p, mxp.MXFP4P, p, mxp.F32, 8, None) == -5
     assert L.mxp_gemm_static(-1, 8, 32, p, p, p, mxp.MXFP4P, p, p, p, mxp.MXFP4P, p, mxp.F32, 8, None) == -2
     assert "scratch" in mxp.status_string(-9)
+
+
+def test_bench_refuses_more_than_one_gpu_and_names_its_kernels():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message before anything touches a device; the
+    kernel it names in its roofline entry follows the library's routing of the shape."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+    sys.path.insert(0, root)
+    import bench
+    assert bench.product_kernel_name(4096, 14336) == "gemm_kernel_dma"
+    assert bench.product_kernel_name(2048, 1024) == "gemm_block_kernel"
+    assert bench.product_kernel_name(8, 4096) == "gemm_skinny16_kernel"
+    assert bench.product_kernel_name(8, 28672) == "gemm_skinny_kernel"
