@@ -220,3 +220,23 @@ def test_bench_refuses_more_than_one_gpu_and_names_its_kernels():
     assert bench.product_kernel_name(2048, 1024) == "gemm_block_kernel"
     assert bench.product_kernel_name(8, 4096) == "gemm_skinny16_kernel"
     assert bench.product_kernel_name(8, 28672) == "gemm_skinny_kernel"
+
+
+def test_product_path_and_oracle_share_nothing():
+    """The package never reaches the oracle and the oracle never reaches the package (only the tests, the smoke check and
+    the bench's CPU baseline use the oracle); the only module both sides take inputs from holds no format arithmetic."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg, orc = os.path.join(root, "paper_2510_14557_amd"), os.path.join(root, "oracle")
+    uses_oracle = re.compile(r"^\s*(import\s+oracle\b|from\s+oracle\b)|oracle/|libmxp_oracle", re.M)
+    for dirpath, _, names in os.walk(pkg):
+        for n in names:
+            if n.endswith((".py", ".hip", ".h", ".cpp", ".c")):
+                text = open(os.path.join(dirpath, n)).read()
+                assert not uses_oracle.search(text), "%s refers to the oracle" % n
+    uses_pkg = re.compile(r"paper_2510_14557_amd|libmxp\.so|mxp\.h|csrc")
+    for n in os.listdir(orc):
+        if n.endswith((".py", ".c", ".h")):
+            assert not uses_pkg.search(open(os.path.join(orc, n)).read()), "oracle/%s refers to the HIP path" % n
+    synth = open(os.path.join(pkg, "synth.py")).read()
+    for word in ("quantize", "E2M1", "e2m1", "scale_byte", "shared_exp"):
+        assert word not in synth, "synth.py mentions %s" % word
