@@ -240,3 +240,15 @@ def test_product_path_and_oracle_share_nothing():
     synth = open(os.path.join(pkg, "synth.py")).read()
     for word in ("quantize", "E2M1", "e2m1", "scale_byte", "shared_exp"):
         assert word not in synth, "synth.py mentions %s" % word
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    """Without the built HIP library every call of the binding raises: there is no CPU route behind it."""
+    monkeypatch.setattr(mxp, "_lib", None)
+    monkeypatch.setattr(mxp, "LIB_PATH", os.path.join(os.path.dirname(mxp.LIB_PATH), "no_such_libmxp.so"))
+    with pytest.raises(mxp.MxpError):
+        mxp.lib()
+    with pytest.raises(mxp.MxpError):
+        mxp.version()
+    with pytest.raises(mxp.MxpError):
+        mxp.image_bytes(64, 64)
